@@ -1,0 +1,222 @@
+"""ctypes front end of the C oracle (oracle/trdq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: argument marshalling around the plain C functions,
+plus `acc_exact_blas`, the same integer product evaluated through a float64
+library matmul (every partial sum is an integer below 2^53, hence exact),
+used where the plain loop would take minutes.  The steps follow Eq. 1-2
+(symmetric form), the BlockDiag rotation and Eq. 9/10 of the paper with
+P = I and R^(2) = I.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        i64, i32, p = C.c_int64, C.c_int, C.c_void_p
+        L.trdq_oracle_f64_to_bf16.restype = C.c_uint16
+        L.trdq_oracle_f64_to_bf16.argtypes = [C.c_double]
+        L.trdq_oracle_bf16_to_f64.restype = C.c_double
+        L.trdq_oracle_bf16_to_f64.argtypes = [C.c_uint16]
+        L.trdq_oracle_table_default.argtypes = [i32, i32, p]
+        L.trdq_oracle_hadamard.argtypes = [i32, p]
+        L.trdq_oracle_rotate.argtypes = [p, i64, i32, i64, p, i32, p]
+        L.trdq_oracle_quant_tokens.argtypes = [p, i64, i32, p, p]
+        L.trdq_oracle_rotate_weights.argtypes = [p, i32, i32, p, i32, p]
+        L.trdq_oracle_quant_weights.argtypes = [p, i32, i32, i32, i32, p, p]
+        L.trdq_oracle_pack_int4.argtypes = [p, i32, i32, p]
+        L.trdq_oracle_unpack_int4.argtypes = [p, i32, i32, p]
+        L.trdq_oracle_igemm.argtypes = [p, p, i64, i32, i32, i32, p]
+        L.trdq_oracle_dequant.argtypes = [p, p, p, p, i64, i32, i32, p, p]
+        L.trdq_oracle_linear.argtypes = [p, i64, i32, i64, p, i32, p, p, i32, i32,
+                                         p, p, p, p, p, p]
+        L.trdq_oracle_threads.restype = i32
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _chk(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+
+
+def _c(a, dtype):
+    return None if a is None else np.ascontiguousarray(a, dtype=dtype)
+
+
+def threads():
+    return int(lib().trdq_oracle_threads())
+
+
+def f64_to_bf16(y):
+    y = np.asarray(y, dtype=np.float64)
+    out = np.empty(y.shape, dtype=np.uint16)
+    f = lib().trdq_oracle_f64_to_bf16
+    flat_in, flat_out = y.reshape(-1), out.reshape(-1)
+    for t in range(flat_in.size):
+        flat_out[t] = f(float(flat_in[t]))
+    return out
+
+
+def bf16_to_f64(h):
+    h = np.asarray(h, dtype=np.uint16)
+    return (h.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def table_default(n_steps, n_groups):
+    m = np.empty(n_steps, dtype=np.int32)
+    _chk(lib().trdq_oracle_table_default(n_steps, n_groups, _ptr(m)), "table_default")
+    return m
+
+
+def hadamard(B):
+    H = np.empty((B, B), dtype=np.int8)
+    _chk(lib().trdq_oracle_hadamard(B, _ptr(H)), "hadamard")
+    return H
+
+
+def rotate(X_bf16, d=None, B=128):
+    """V = (X diag(d)) R as float64; X_bf16 is a uint16 [M, K] array of bf16 bit patterns."""
+    X = _c(X_bf16, np.uint16)
+    M, K = X.shape
+    d = _c(d, np.float32)
+    V = np.empty((M, K), dtype=np.float64)
+    _chk(lib().trdq_oracle_rotate(_ptr(X), M, K, K, _ptr(d), B, _ptr(V)), "rotate")
+    return V
+
+
+def quant_tokens(V):
+    V = _c(V, np.float64)
+    M, K = V.shape
+    Xq = np.empty((M, K), dtype=np.int8)
+    sx = np.empty(M, dtype=np.float64)
+    _chk(lib().trdq_oracle_quant_tokens(_ptr(V), M, K, _ptr(Xq), _ptr(sx)), "quant_tokens")
+    return Xq, sx
+
+
+def rotate_quant(X_bf16, d=None, B=128):
+    return quant_tokens(rotate(X_bf16, d, B))
+
+
+def rotate_weights(W, d=None, B=128):
+    W = _c(W, np.float32)
+    K, N = W.shape
+    d = _c(d, np.float32)
+    Wp = np.empty((K, N), dtype=np.float64)
+    _chk(lib().trdq_oracle_rotate_weights(_ptr(W), K, N, _ptr(d), B, _ptr(Wp)), "rotate_weights")
+    return Wp
+
+
+def quant_weights(Wp, wbits=8, group=128):
+    Wp = _c(Wp, np.float64)
+    K, N = Wp.shape
+    ng = 1 if wbits == 8 else K // group
+    Wq = np.empty((K, N), dtype=np.int8)
+    sw = np.empty((ng, N), dtype=np.float64)
+    _chk(lib().trdq_oracle_quant_weights(_ptr(Wp), K, N, wbits, group, _ptr(Wq), _ptr(sw)),
+         "quant_weights")
+    return Wq, (sw[0] if wbits == 8 else sw)
+
+
+def prepare_weights(W, d=None, B=128, wbits=8):
+    return quant_weights(rotate_weights(W, d, B), wbits, B)
+
+
+def pack_int4(Wq):
+    Wq = _c(Wq, np.int8)
+    K, N = Wq.shape
+    out = np.empty((K // 2, N), dtype=np.uint8)
+    _chk(lib().trdq_oracle_pack_int4(_ptr(Wq), K, N, _ptr(out)), "pack_int4")
+    return out
+
+
+def unpack_int4(packed):
+    packed = _c(packed, np.uint8)
+    K2, N = packed.shape
+    out = np.empty((K2 * 2, N), dtype=np.int8)
+    _chk(lib().trdq_oracle_unpack_int4(_ptr(packed), K2 * 2, N, _ptr(out)), "unpack_int4")
+    return out
+
+
+def igemm(Xq, Wq, group=None):
+    """int32 accumulators: [M, N] when group is None/K, else [K/group, M, N]."""
+    Xq, Wq = _c(Xq, np.int8), _c(Wq, np.int8)
+    M, K = Xq.shape
+    K2, N = Wq.shape
+    assert K == K2
+    g = K if group is None else group
+    ng = K // g
+    acc = np.empty((ng, M, N), dtype=np.int32)
+    _chk(lib().trdq_oracle_igemm(_ptr(Xq), _ptr(Wq), M, K, N, g, _ptr(acc)), "igemm")
+    return acc[0] if ng == 1 else acc
+
+
+def acc_exact_blas(Xq, Wq, group=None):
+    """Same integer sums as igemm through a float64 library matmul.
+
+    |partial sums| <= 127*127*K < 2^53, so every float64 operation is exact and the
+    result equals the int32 loop bit for bit (pinned in the tests on small shapes)."""
+    Xq, Wq = np.asarray(Xq), np.asarray(Wq)
+    M, K = Xq.shape
+    g = K if group is None else group
+    ng = K // g
+    Xd, Wd = Xq.astype(np.float64), Wq.astype(np.float64)
+    out = np.empty((ng, M, Wq.shape[1]), dtype=np.int32)
+    for b in range(ng):
+        out[b] = (Xd[:, b * g:(b + 1) * g] @ Wd[b * g:(b + 1) * g]).astype(np.int32)
+    return out[0] if ng == 1 else out
+
+
+def dequant(acc, sx, sw, bias=None, return_f64=False):
+    acc = _c(acc, np.int32)
+    if acc.ndim == 2:
+        ng, (M, N) = 1, acc.shape
+    else:
+        ng, M, N = acc.shape
+    sx = _c(sx, np.float64)
+    sw = _c(sw, np.float64)
+    bias = _c(bias, np.float32)
+    Y = np.empty((M, N), dtype=np.uint16)
+    Yd = np.empty((M, N), dtype=np.float64) if return_f64 else None
+    _chk(lib().trdq_oracle_dequant(_ptr(acc), _ptr(sx), _ptr(sw), _ptr(bias), M, N, ng,
+                                   _ptr(Y), _ptr(Yd)), "dequant")
+    return (Y, Yd) if return_f64 else Y
+
+
+def linear(X_bf16, W, d=None, bias=None, B=128, wbits=8, exact_blas=False):
+    """Whole path; returns a dict with Xq, sx, Wq, sw, acc, Y (bf16 bits) and Yd (float64).
+
+    exact_blas=True replaces only the integer-product step by acc_exact_blas."""
+    Xq, sx = rotate_quant(X_bf16, d, B)
+    Wq, sw = prepare_weights(W, d, B, wbits)
+    group = None if wbits == 8 else B
+    acc = (acc_exact_blas if exact_blas else igemm)(Xq, Wq, group)
+    Y, Yd = dequant(acc, sx, sw, bias, return_f64=True)
+    return dict(Xq=Xq, sx=sx, Wq=Wq, sw=sw, acc=acc, Y=Y, Yd=Yd)
+
+
+def linear_c(X_bf16, W, d=None, bias=None, B=128, wbits=8):
+    """The single C entry point running every step (used for timing the baseline)."""
+    X = _c(X_bf16, np.uint16)
+    W = _c(W, np.float32)
+    M, K = X.shape
+    N = W.shape[1]
+    d = _c(d, np.float32)
+    bias = _c(bias, np.float32)
+    Y = np.empty((M, N), dtype=np.uint16)
+    _chk(lib().trdq_oracle_linear(_ptr(X), M, K, K, _ptr(W), N, _ptr(d), _ptr(bias), B, wbits,
+                                  None, None, None, None, None, _ptr(Y)), "linear")
+    return Y

@@ -1,0 +1,403 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+Each test checks an oracle function against something that is not the oracle:
+integer identities, a library routine (scipy's Sylvester construction, a float64
+BLAS product, torch's float32->bfloat16 cast), closed forms, exact rational
+brute force on tiny inputs, and the computational-invariance identity of
+Eq. 4 / Eq. 9 / Eq. 10.  None needs a GPU.
+"""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.linalg
+
+from paper_2503_06564_amd import workloads as wl
+
+
+# ----------------------------------------------------------------- Hadamard
+
+@pytest.mark.parametrize("B", [2, 8, 128])
+def test_hadamard_orthogonal_integer_exact(oracle, B):
+    # R R^T = I per block (orthogonal rotation, Sec. 3.2): H H^T = B I in integers
+    H = oracle.hadamard(B).astype(np.int64)
+    assert set(np.unique(H)) == {-1, 1}
+    assert np.array_equal(H @ H.T, B * np.eye(B, dtype=np.int64))
+    assert np.array_equal(H, H.T)
+
+
+@pytest.mark.parametrize("B", [8, 128])
+def test_hadamard_is_sylvester(oracle, B):
+    H = oracle.hadamard(B)
+    assert np.array_equal(H, scipy.linalg.hadamard(B).astype(np.int8))
+    h = B // 2
+    assert np.array_equal(H[:h, :h], H[:h, h:])
+    assert np.array_equal(H[:h, :h], H[h:, :h])
+    assert np.array_equal(H[:h, :h], -H[h:, h:])
+
+
+# ----------------------------------------------------------------- rotation
+
+def _bf16(x):
+    return wl.f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+
+
+def test_rotate_unit_vectors_give_hadamard_rows(oracle):
+    B, K = 128, 256
+    X = np.zeros((K, K), dtype=np.float32)
+    X[np.arange(K), np.arange(K)] = 1.0
+    V = oracle.rotate(_bf16(X), None, B)
+    H = scipy.linalg.hadamard(B) / np.sqrt(B)
+    expect = np.zeros((K, K))
+    expect[:B, :B] = H
+    expect[B:, B:] = H                     # block diagonal: no leakage across blocks
+    assert np.allclose(V, expect, rtol=0, atol=1e-15)
+    Xq, sx = oracle.quant_tokens(V)
+    nz = expect != 0
+    assert np.all(np.abs(Xq[nz]) == 127) and np.all(Xq[~nz] == 0)
+    assert np.array_equal(np.sign(Xq[nz]), np.sign(expect[nz]).astype(np.int8))
+    assert np.allclose(sx, 1 / np.sqrt(B) / 127, rtol=1e-15)
+
+
+def test_rotate_constant_block_concentrates(oracle):
+    B = 128
+    X = np.concatenate([np.full((1, B), 0.5), np.full((1, B), -2.0)], axis=1).astype(np.float32)
+    V = oracle.rotate(_bf16(X), None, B)[0]
+    expect = np.zeros(2 * B)
+    expect[0] = 0.5 * np.sqrt(B)
+    expect[B] = -2.0 * np.sqrt(B)
+    assert np.allclose(V, expect, rtol=0, atol=1e-13)
+
+
+def test_rotate_applies_diag_as_multiplier_per_channel(oracle):
+    # (X . Delta) R of Eq. 9/10: channel k is multiplied by d[k] before the rotation
+    B, K = 8, 16
+    r = np.random.default_rng(1)
+    d = r.uniform(0.5, 2.0, K).astype(np.float32)
+    X = np.zeros((K, K), dtype=np.float32)
+    X[np.arange(K), np.arange(K)] = 1.0
+    V = oracle.rotate(_bf16(X), d, B)
+    H = scipy.linalg.hadamard(B) / np.sqrt(B)
+    for k in range(K):
+        b = k // B
+        expect = np.zeros(K)
+        expect[b * B:(b + 1) * B] = float(d[k]) * H[k % B]
+        assert np.allclose(V[k], expect, rtol=1e-15, atol=0)
+
+
+def test_rotate_preserves_row_norm(oracle):
+    cfg = wl.CONFIGS[0]
+    X = wl.make_x(cfg, "proj", M=64)
+    d = wl.make_diag(wl.CONFIGS[1], "proj", 3)
+    V = oracle.rotate(X, d)
+    U = wl.bf16_bits_to_f32(X).astype(np.float64) * d.astype(np.float64)
+    assert np.allclose(np.linalg.norm(V, axis=1), np.linalg.norm(U, axis=1), rtol=1e-12)
+
+
+def test_rotation_narrows_outlier_rows(oracle):
+    # Fig. 1 of the paper: the rotated activations have a much smaller range
+    cfg = wl.CONFIGS[0]
+    X = wl.make_x(cfg, "proj", M=128)
+    V = oracle.rotate(X)
+    before = np.abs(wl.bf16_bits_to_f32(X)).max(axis=1)
+    after = np.abs(V).max(axis=1)
+    assert np.median(before / after) > 3.0
+
+
+@pytest.mark.parametrize("B,K,N,M", [(8, 24, 5, 7), (128, 256, 96, 33)])
+def test_computational_invariance(oracle, B, K, N, M):
+    # (X D R)(R^T D^-1 W) = X W, Eq. 9 / Eq. 10, unquantised, float64, to 1e-9
+    Xb, W, d, _ = wl.small_case(5, M, K, N)
+    V = oracle.rotate(Xb, d, B)
+    Wp = oracle.rotate_weights(W, d, B)
+    exact = wl.bf16_bits_to_f32(Xb).astype(np.float64) @ W.astype(np.float64)
+    err = np.abs(V @ Wp - exact).max() / np.abs(exact).max()
+    assert err < 1e-9
+    # and the weight side really uses 1/d and the transpose: a wrong direction breaks it
+    Wp_bad = oracle.rotate_weights(W, (1.0 / d).astype(np.float32), B)
+    assert np.abs(V @ Wp_bad - exact).max() / np.abs(exact).max() > 1e-3
+
+
+def test_rotate_weights_matches_dense_blockdiag(oracle):
+    B, K, N = 8, 24, 6
+    _, W, d, _ = wl.small_case(6, 4, K, N)
+    R = np.kron(np.eye(K // B), scipy.linalg.hadamard(B) / np.sqrt(B))
+    expect = R.T @ np.diag(1.0 / d.astype(np.float64)) @ W.astype(np.float64)
+    assert np.allclose(oracle.rotate_weights(W, d, B), expect, rtol=1e-13, atol=1e-16)
+
+
+# ---------------------------------------------------------------- quantiser
+
+def test_quant_tokens_properties(oracle):
+    cfg = wl.CONFIGS[0]
+    V = oracle.rotate(wl.make_x(cfg, "proj", M=96))
+    V[5] = 0.0                                            # a dead token
+    Xq, sx = oracle.quant_tokens(V)
+    live = np.ones(len(V), bool); live[5] = False
+    assert np.all(np.abs(Xq[live]).max(axis=1) == 127)    # extreme value maps to +-127
+    assert np.all(np.abs(Xq) <= 127)
+    assert np.allclose(sx[live], np.abs(V[live]).max(axis=1) / 127, rtol=1e-15)
+    assert sx[5] == 0 and np.all(Xq[5] == 0)
+    # nearest rounding: reconstruction error at most half a step (Eq. 1)
+    assert np.all(np.abs(V - sx[:, None] * Xq) <= sx[:, None] * (0.5 + 1e-12))
+    # idempotent on its own grid
+    Xq2, sx2 = oracle.quant_tokens(sx[:, None] * Xq)
+    assert np.array_equal(Xq2, Xq) and np.allclose(sx2, sx, rtol=1e-15)
+
+
+def test_quant_tokens_ties_to_even_and_sign(oracle):
+    # row absmax 127 -> scale exactly 1; halves must go to the even neighbour
+    V = np.array([[127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.49, -126.5, 126.5]])
+    Xq, sx = oracle.quant_tokens(V)
+    assert sx[0] == 1.0
+    assert Xq[0].tolist() == [127, 0, 2, 2, 0, -2, -2, 3, -126, 126]
+
+
+@pytest.mark.parametrize("wbits,qmax", [(8, 127), (4, 7)])
+def test_quant_weights_properties(oracle, wbits, qmax):
+    B, K, N = 128, 384, 40
+    _, W, d, _ = wl.small_case(7, 4, K, N)
+    Wp = oracle.rotate_weights(W, d, B)
+    Wp[:, 3] = 0.0                                        # a dead output channel
+    Wq, sw = oracle.quant_weights(Wp, wbits, B)
+    assert np.abs(Wq).max() == qmax and np.all(np.abs(Wq) <= qmax)
+    if wbits == 8:
+        assert sw.shape == (N,)
+        assert np.allclose(sw, np.abs(Wp).max(axis=0) / 127, rtol=1e-15)   # per output channel
+        s_full = np.broadcast_to(sw, (K, N))
+        assert np.all(np.abs(Wq[:, np.arange(N) != 3]).max(axis=0) == 127)
+    else:
+        assert sw.shape == (K // B, N)
+        expect = np.abs(Wp.reshape(K // B, B, N)).max(axis=1) / 7          # per 128-row group
+        assert np.allclose(sw, expect, rtol=1e-15)
+        s_full = np.repeat(sw, B, axis=0)
+    assert np.all(sw[..., 3] == 0) and np.all(Wq[:, 3] == 0)
+    assert np.all(np.abs(Wp - s_full * Wq) <= s_full * (0.5 + 1e-12))
+
+
+def test_int4_pack_layout_and_roundtrip(oracle):
+    K, N = 6, 3
+    Wq = np.array([[1, -1, 7], [-7, 0, 2], [3, 3, 3], [-3, -4, 5], [0, 0, 0], [-1, 6, -6]], dtype=np.int8)
+    P = oracle.pack_int4(Wq)
+    assert P.shape == (K // 2, N)
+    # low nibble = even k, high nibble = odd k, two's complement
+    assert P[0, 0] == (1 | (0x9 << 4))          # k=0: 1, k=1: -7 -> 0x9
+    assert P[0, 1] == (0xF | (0x0 << 4))        # -1 -> 0xF
+    assert P[2, 2] == (0x0 | (0xA << 4))        # -6 -> 0xA
+    assert np.array_equal(oracle.unpack_int4(P), Wq)
+    r = np.random.default_rng(0).integers(-7, 8, size=(256, 17)).astype(np.int8)
+    assert np.array_equal(oracle.unpack_int4(oracle.pack_int4(r)), r)
+
+
+# ------------------------------------------------------------ integer product
+
+def test_igemm_brute_force_4x8x8(oracle):
+    r = np.random.default_rng(3)
+    Xq = r.integers(-127, 128, size=(4, 8)).astype(np.int8)
+    Wq = r.integers(-127, 128, size=(8, 8)).astype(np.int8)
+    acc = oracle.igemm(Xq, Wq)
+    for i in range(4):
+        for n in range(8):
+            assert acc[i, n] == sum(int(Xq[i, k]) * int(Wq[k, n]) for k in range(8))
+    accg = oracle.igemm(Xq, Wq, group=4)
+    assert accg.shape == (2, 4, 8)
+    for g in range(2):
+        for i in range(4):
+            for n in range(8):
+                assert accg[g, i, n] == sum(int(Xq[i, k]) * int(Wq[k, n]) for k in range(4 * g, 4 * g + 4))
+
+
+def test_igemm_equals_exact_float64_blas(oracle):
+    r = np.random.default_rng(4)
+    M, K, N = 37, 1152, 53                     # non-square: a transposed operand cannot pass
+    Xq = r.integers(-127, 128, size=(M, K)).astype(np.int8)
+    Wq = r.integers(-127, 128, size=(K, N)).astype(np.int8)
+    Xq[0, :] = 127; Wq[:, 0] = 127             # the largest possible accumulator
+    acc = oracle.igemm(Xq, Wq)
+    assert acc[0, 0] == 127 * 127 * K
+    assert np.array_equal(acc, (Xq.astype(np.float64) @ Wq.astype(np.float64)).astype(np.int64))
+    assert np.array_equal(acc, oracle.acc_exact_blas(Xq, Wq))
+    accg = oracle.igemm(Xq, Wq, group=128)
+    assert np.array_equal(accg, oracle.acc_exact_blas(Xq, Wq, group=128))
+    assert np.array_equal(accg.sum(axis=0), acc)
+
+
+# ------------------------------------------------------------------ bf16 cast
+
+def test_f64_to_bf16_matches_torch_on_float32_inputs(oracle):
+    import torch
+    r = np.random.default_rng(8)
+    x = np.concatenate([
+        r.standard_normal(4000).astype(np.float32) * np.float32(10.0) ** r.integers(-30, 30, 4000).astype(np.float32),
+        np.array([0.0, -0.0, 1.0, -1.0, 3.3895314e38, -3.3895314e38, 1e-40, -1e-45, 65504.0], np.float32),
+    ])
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = oracle.f64_to_bf16(x.astype(np.float64))
+    assert np.array_equal(got, want)
+    assert np.array_equal(oracle.bf16_to_f64(got), wl.bf16_bits_to_f32(got).astype(np.float64))
+
+
+def test_f64_to_bf16_rounds_once(oracle):
+    # values where float64 -> float32 -> bf16 would round twice and land elsewhere
+    cases = {
+        1.0 + 2.0 ** -8 + 2.0 ** -30: 0x3F81,      # just above a tie: up
+        1.0 + 2.0 ** -8 - 2.0 ** -30: 0x3F80,      # just below a tie: down
+        1.0 + 2.0 ** -8: 0x3F80,                   # exact tie: to even (down)
+        1.0 + 3 * 2.0 ** -8: 0x3F82,               # exact tie: to even (up)
+        -(1.0 + 2.0 ** -8 + 2.0 ** -30): 0xBF81,
+        3.4e38: 0x7F80,                            # above the largest bf16 + half step: inf
+    }
+    for y, bits in cases.items():
+        assert int(oracle.f64_to_bf16(np.array([y]))[0]) == bits, y
+
+
+# ------------------------------------------------------------------- dequant
+
+def test_dequant_closed_form(oracle):
+    acc = np.array([[100, -200, 0], [1, 2, 3]], dtype=np.int32)
+    sx = np.array([0.5, 2.0]); sw = np.array([0.25, 1.0, 4.0])
+    bias = np.array([1.0, 0.0, -3.0], dtype=np.float32)
+    Y, Yd = oracle.dequant(acc, sx, sw, bias, return_f64=True)
+    expect = np.array([[100 * .5 * .25 + 1, -200 * .5, -3.0], [1 * 2 * .25 + 1, 4.0, 3 * 2 * 4 - 3.0]])
+    assert np.array_equal(Yd, expect)                      # all exactly representable
+    assert np.array_equal(wl.bf16_bits_to_f32(Y), expect.astype(np.float32))
+    # grouped form: s_x * sum_g s_w[g] acc[g] + bias
+    accg = np.stack([acc, 2 * acc]); swg = np.stack([sw, 0.5 * sw])
+    _, Ydg = oracle.dequant(accg, sx, swg, None, return_f64=True)
+    assert np.array_equal(Ydg, 2 * (expect - bias))
+
+
+# ---------------------------------------------------- whole path, tiny + exact
+
+def _round_half_even_fraction(q):
+    f = q.numerator // q.denominator           # floor
+    rem = q - f
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and f % 2):
+        f += 1
+    return f
+
+
+def _brute_force_codes(vals):
+    """codes of one quantisation group from exact rationals: rint(127 v / max|v|)."""
+    a = max(abs(v) for v in vals)
+    return [0 if a == 0 else _round_half_even_fraction(v * 127 / a) for v in vals]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_whole_path_brute_force_4x8x8(oracle, seed):
+    """M=4, K=8, N=8, B=8, W8A8, every step redone in exact rational arithmetic.
+
+    The codes depend only on ratios inside a row/column, so the irrational 1/sqrt(B)
+    cancels and the unnormalised Hadamard sums decide them exactly."""
+    M = K = N = B = 8
+    M = 4
+    Xb, W, d, bias = wl.small_case(seed, M, K, N, n_outliers=1, outlier=20.0)
+    out = oracle.linear(Xb, W, d, bias, B=B, wbits=8)
+    X = [[Fraction(float(v)) for v in row] for row in wl.bf16_bits_to_f32(Xb)]
+    Wf = [[Fraction(float(v)) for v in row] for row in W]
+    df = [Fraction(float(v)) for v in d]
+    sgn = lambda i, j: -1 if bin(i & j).count("1") & 1 else 1
+    Vun = [[sum(X[i][k] * df[k] * sgn(k, j) for k in range(K)) for j in range(K)] for i in range(M)]
+    Wun = [[sum(sgn(k, j) * Wf[k][n] / df[k] for k in range(K)) for n in range(N)] for j in range(K)]
+    Xq = [_brute_force_codes(Vun[i]) for i in range(M)]
+    Wq_cols = [_brute_force_codes([Wun[k][n] for k in range(K)]) for n in range(N)]
+    assert out["Xq"].tolist() == Xq
+    assert out["Wq"].T.tolist() == Wq_cols
+    acc = [[sum(Xq[i][k] * Wq_cols[n][k] for k in range(K)) for n in range(N)] for i in range(M)]
+    assert out["acc"].tolist() == acc
+    rb = 1 / np.sqrt(B)
+    for i in range(M):
+        sx = float(max(abs(v) for v in Vun[i])) * rb / 127
+        assert out["sx"][i] == pytest.approx(sx, rel=1e-14)
+        for n in range(N):
+            sw = float(max(abs(Wun[k][n]) for k in range(K))) * rb / 127
+            y = acc[i][n] * sx * sw + float(bias[n])
+            assert out["Yd"][i, n] == pytest.approx(y, rel=1e-12, abs=1e-15)
+
+
+def test_whole_path_w4_groups_brute_force(oracle):
+    M, K, N, B = 3, 16, 5, 8                   # two groups of 8 input channels
+    Xb, W, d, bias = wl.small_case(11, M, K, N, n_outliers=1, outlier=20.0)
+    out = oracle.linear(Xb, W, d, bias, B=B, wbits=4)
+    Wp = oracle.rotate_weights(W, d, B)
+    assert out["sw"].shape == (2, N) and out["acc"].shape == (2, M, N)
+    for g in range(2):
+        for n in range(N):
+            col = [Fraction(float(v)) for v in Wp[g * B:(g + 1) * B, n]]
+            a = max(abs(v) for v in col)
+            want = [_round_half_even_fraction(v * 7 / a) for v in col]
+            assert out["Wq"][g * B:(g + 1) * B, n].tolist() == want
+    Xq, Wq = out["Xq"].astype(int), out["Wq"].astype(int)
+    for g in range(2):
+        assert np.array_equal(out["acc"][g], Xq[:, g * B:(g + 1) * B] @ Wq[g * B:(g + 1) * B])
+    y = out["sx"][:, None] * sum(out["sw"][g][None, :] * out["acc"][g] for g in range(2)) + bias
+    assert np.allclose(out["Yd"], y, rtol=1e-14)
+
+
+def test_single_c_entry_point_agrees_with_steps(oracle):
+    Xb, W, d, bias = wl.small_case(2, 20, 256, 24)
+    for wbits in (8, 4):
+        a = oracle.linear(Xb, W, d, bias, wbits=wbits)["Y"]
+        assert np.array_equal(a, oracle.linear_c(Xb, W, d, bias, wbits=wbits))
+
+
+# --------------------------------------------------- end-to-end error behaviour
+
+def test_quantised_output_close_to_exact_and_rotation_helps(oracle):
+    """W8A8 on config-0 data: about 1% relative error, inside the analytic bound,
+    and clearly better than the same quantiser without rotation (the paper's claim)."""
+    cfg = wl.CONFIGS[0]
+    Xb = wl.make_x(cfg, "proj", M=256)
+    W = wl.make_w(cfg, "proj")[:, :256].copy()
+    exact = wl.bf16_bits_to_f32(Xb).astype(np.float64) @ W.astype(np.float64)
+    out = oracle.linear(Xb, W, None, None, wbits=8, exact_blas=True)
+    rel = np.linalg.norm(out["Yd"] - exact) / np.linalg.norm(exact)
+    assert rel < 0.02
+    V, Wp = oracle.rotate(Xb), oracle.rotate_weights(W)
+    sx, sw = out["sx"], out["sw"]
+    bound = (0.5 * sx[:, None] * np.abs(Wp).sum(axis=0)[None, :]
+             + 0.5 * sw[None, :] * np.abs(V).sum(axis=1)[:, None]
+             + 0.25 * V.shape[1] * sx[:, None] * sw[None, :])
+    assert np.all(np.abs(out["Yd"] - exact) <= bound * (1 + 1e-9))
+    # no rotation: quantise X and W directly with the same quantisers
+    Xf = wl.bf16_bits_to_f32(Xb).astype(np.float64)
+    Xq0, sx0 = oracle.quant_tokens(Xf)
+    Wq0, sw0 = oracle.quant_weights(W.astype(np.float64), 8, 128)
+    _, Y0 = oracle.dequant(oracle.acc_exact_blas(Xq0, Wq0), sx0, sw0, None, return_f64=True)
+    rel0 = np.linalg.norm(Y0 - exact) / np.linalg.norm(exact)
+    assert rel0 > 2.5 * rel
+
+
+# -------------------------------------------------------------- group table
+
+@pytest.mark.parametrize("n_steps,n_groups", [(20, 5), (50, 10), (10, 10), (7, 3), (1, 1)])
+def test_table_default_partition(oracle, n_steps, n_groups):
+    m = oracle.table_default(n_steps, n_groups)
+    assert m[0] == 0 and m[-1] == n_groups - 1
+    assert np.all(np.diff(m) >= 0) and np.all(np.diff(m) <= 1)       # monotone, contiguous
+    sizes = np.bincount(m, minlength=n_groups)
+    assert sizes.max() - sizes.min() <= 1
+    assert [wl.step_to_group(type("C", (), dict(n_steps=n_steps, n_groups=n_groups)), s)
+            for s in range(n_steps)] == m.tolist()
+
+
+def test_table_default_rejects_bad_arguments(oracle):
+    with pytest.raises(RuntimeError):
+        oracle.table_default(3, 5)
+
+
+# ------------------------------------------------------------ frozen fixtures
+
+@pytest.mark.parametrize("name", ["tiny_w8a8_4x8x8.txt", "tiny_w4a8_3x16x5.txt"])
+def test_oracle_matches_frozen_fixture(oracle, name):
+    import importlib.util
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mg = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mg)
+    out = mg.compute(mg.CASES[name])
+    rows = dict(line.split(" ", 1) for line in open(os.path.join(here, name)) if not line.startswith("#"))
+    for key in ("Xq", "Wq", "acc"):
+        assert out[key].reshape(-1).tolist() == [int(t) for t in rows[key].split()]
+    assert [f"{v:04x}" for v in out["Y"].reshape(-1).tolist()] == rows["Y"].split()
