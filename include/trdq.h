@@ -1,0 +1,189 @@
+/*
+ * trdq.h -- C ABI of libtrdq: the rotated W8A8 / W4A8 linear layer of TR-DQ
+ * (Time-Rotation Diffusion Quantization) on AMD MI355X (gfx950).
+ *
+ * The layer computes, for the linear Y = X . W of a denoiser at sampling
+ * step t (paper Sec. 3.1, Eq. 10):
+ *
+ *     F_t(X_t, W) = G_t(X_t) . H_t(W)
+ *     G_t(X) = (X . Delta_t) . R            (online, per call)
+ *     H_t(W) = R^T . (Delta_t^-1 . W)       (offline, once per time-step group)
+ *
+ * with R block-diagonal, each 128 x 128 block the orthonormal Sylvester
+ * Hadamard matrix (the BlockDiag equation of Sec. 3.2 with 2^n = 128; the
+ * permutation P and the second rotation of Eq. 9 are the identity here).
+ * G_t(X) is quantised per token to int8 with a scale computed online from the
+ * row's largest magnitude; H_t(W) is quantised per output channel to int8 or
+ * per (128-input-channel group, output channel) to int4 (Eq. 1-2 in their
+ * symmetric form: scale = absmax / (2^(b-1) - 1), no zero point, nearest
+ * rounding, ties to even).  The product runs on the int8 matrix cores with
+ * int32 accumulation and is rescaled (and biased) to bf16 in the epilogue.
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses on the current HIP device,
+ *     "host" pointers are ordinary host memory.  The caller owns every buffer
+ *     it passes; the library owns the objects it returns through `** out`
+ *     until the matching *_destroy call.
+ *   - Matrices are row-major.  X is [M, K] (tokens x C_in), W is [K, N]
+ *     (C_in x C_out, as in the paper -- the transpose of a torch Linear
+ *     weight), Y is [M, N].  bf16 values are passed as 16-bit patterns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Online calls (rotate_quant, qgemm, linear_fused, layer_forward) are
+ *     asynchronous on that stream and allocate nothing.  prepare_weights
+ *     allocates device memory; the export calls synchronise.
+ *   - Every call returns a trdq_status.  All argument checks happen before
+ *     the first HIP call, so they can be exercised on a machine with no GPU.
+ *     Nothing is printed and nothing aborts.  M == 0 is a valid no-op, for which the
+ *     data pointers may be NULL (an empty tensor has no storage).
+ *   - NaN / Inf in X or W are not detected; the result is then unspecified.
+ *   - Handles are immutable after creation: concurrent forward calls on
+ *     different streams may share them.
+ */
+#ifndef TRDQ_H
+#define TRDQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum trdq_status {
+    TRDQ_OK = 0,
+    TRDQ_ERR_NULL = 1,        /* a required pointer is NULL */
+    TRDQ_ERR_SHAPE = 2,       /* K % 128 != 0, K/N <= 0, M < 0, leading dimension too small, misaligned pointer */
+    TRDQ_ERR_RANGE = 3,       /* step or group out of range, bad table */
+    TRDQ_ERR_UNSUPPORTED = 4, /* wbits not in {4, 8}, block != 128, shape beyond a kernel's limit */
+    TRDQ_ERR_MISMATCH = 5,    /* handle's K / N / width does not match the call */
+    TRDQ_ERR_ALLOC = 6,       /* host or device allocation failed */
+    TRDQ_ERR_HIP = 7          /* a HIP runtime call or kernel launch failed */
+} trdq_status;
+
+#define TRDQ_BLOCK 128        /* rotation block = int4 scale group, in input channels */
+
+const char *trdq_status_str(trdq_status s);
+
+/* Version of the ABI declared in this header (major * 100 + minor). */
+int trdq_abi_version(void);
+
+/* ------------------------------------------------------------------ table
+ * Time-step -> group table ("activations select R, P and Delta based on the
+ * current time-step", Sec. 3.2 Time-Steps Awareness; t in {1..N}, Eq. 10;
+ * indexed here by sampling-step index 0..n_steps-1).  Host object. */
+typedef struct trdq_table trdq_table;
+
+/* map_host: n_steps entries in [0, n_groups), copied; NULL selects the contiguous
+ * near-equal partition g = floor(step * n_groups / n_steps).
+ * Errors: NULL out -> ERR_NULL; n_steps <= 0, n_groups <= 0, n_groups > n_steps
+ * or a map entry outside [0, n_groups) -> ERR_RANGE. */
+trdq_status trdq_table_create(int n_steps, int n_groups, const int32_t *map_host, trdq_table **out);
+trdq_status trdq_table_lookup(const trdq_table *t, int step, int *group_out);
+trdq_status trdq_table_sizes(const trdq_table *t, int *n_steps_out, int *n_groups_out);
+void trdq_table_destroy(trdq_table *t);
+
+/* ---------------------------------------------------------------- weights
+ * Offline weight transform and quantisation, H_t(W) of Eq. 10 followed by the
+ * per-channel weight quantiser (Sec. 3.1).  One handle per time-step group. */
+typedef struct trdq_weights trdq_weights;
+
+/* W_dev:    float32 [K, N] row-major, device.  Not modified, not retained.
+ * diag_dev: float32 [K], device: this group's Delta (activations are multiplied
+ *           by it, weight rows divided); NULL = all ones.  Entries must be non-zero.
+ * block:    must be 128.   wbits: 8 (scale per output channel, codes in [-127,127])
+ *           or 4 (scale per 128-row group and output channel, codes in [-7,7]).
+ * The call enqueues its kernels on `stream` and synchronises it before returning
+ * (temporary buffers are freed).  *out holds codes and scales in a private,
+ * matrix-core friendly layout.
+ * Errors: NULL W_dev/out -> ERR_NULL; K <= 0, N <= 0, K % 128 != 0, N % 16 != 0
+ * -> ERR_SHAPE; block != 128 or wbits not 4/8 -> ERR_UNSUPPORTED. */
+trdq_status trdq_prepare_weights(const float *W_dev, int K, int N, const float *diag_dev,
+                                 int block, int wbits, void *stream, trdq_weights **out);
+
+trdq_status trdq_weights_info(const trdq_weights *w, int *K_out, int *N_out, int *wbits_out);
+
+/* Canonical copies on the host (synchronises the device):
+ * codes_host  int8 [K, N], one code per byte for both widths (may be NULL);
+ * scales_host float32, [N] for wbits 8, [K/128, N] for wbits 4 (may be NULL). */
+trdq_status trdq_weights_export(const trdq_weights *w, int8_t *codes_host, float *scales_host);
+
+/* wbits 4 only: packed_host uint8 [K/2, N], byte (j, n) = code(2j, n) & 0xF | (code(2j+1, n) & 0xF) << 4
+ * (two's complement nibbles, even k in the low nibble).  wbits 8 -> ERR_MISMATCH. */
+trdq_status trdq_weights_export_packed(const trdq_weights *w, uint8_t *packed_host);
+
+/* Device bytes held by the handle (codes + scales). */
+trdq_status trdq_weights_nbytes(const trdq_weights *w, int64_t *nbytes_out);
+
+void trdq_weights_destroy(trdq_weights *w);
+
+/* ----------------------------------------------------------------- online
+ * G_t(X_t) of Eq. 10 followed by the per-token dynamic quantiser (Sec. 3.1,
+ * Eq. 1-2 symmetric; "quantization parameters computed online", Sec. 3.2):
+ *   V = (X . diag) . R,   s_x[i] = max_k |V[i,k]| / 127,
+ *   Xq[i,k] = rint(V[i,k] / s_x[i]);   an all-zero row gives s_x = 0, codes 0.
+ * X_dev:  bf16 [M, K], row stride ldx elements (ldx >= K, ldx % 8 == 0, 16-byte aligned base).
+ * Xq_dev: int8 [M, K] dense (8-byte aligned).   sx_dev: float32 [M].
+ * Errors: NULL X/Xq/sx -> ERR_NULL; M < 0, K <= 0, K % 128, ldx < K, misalignment
+ * -> ERR_SHAPE; block != 128 -> ERR_UNSUPPORTED. */
+trdq_status trdq_rotate_quant(const void *X_dev, int64_t M, int K, int64_t ldx,
+                              const float *diag_dev, int block,
+                              int8_t *Xq_dev, float *sx_dev, void *stream);
+
+/* The integer product G_t(X_t) . H_t(W) on the codes, with the dequantising epilogue:
+ *   wbits 8: Y[i,n] = bf16( float(acc[i,n]) * s_x[i] * s_w[n] + bias[n] ),  acc = Xq . Wq  (int32, exact)
+ *   wbits 4: Y[i,n] = bf16( s_x[i] * sum_g s_w[g,n] * float(acc_g[i,n]) + bias[n] ),
+ *            acc_g = the partial product over input group g (int32, exact), g ascending.
+ * Xq_dev: int8 [M, K] dense (16-byte aligned);  sx_dev: float32 [M];
+ * bias_dev: float32 [N] or NULL;  Y_dev: bf16 [M, N], row stride ldy elements
+ * (ldy >= N, ldy % 4 == 0, 8-byte aligned base).
+ * acc_debug_dev: NULL, or int32 [M, N] (wbits 8) / [K/128, M, N] (wbits 4) receiving the raw
+ * accumulators (for bit-exactness tests; slows the call).
+ * Errors: NULL w/Xq/sx/Y -> ERR_NULL; M < 0, ldy < N, misalignment -> ERR_SHAPE. */
+trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev, int64_t M,
+                       const float *bias_dev, void *Y_dev, int64_t ldy,
+                       int32_t *acc_debug_dev, void *stream);
+
+/* Fused variant: rotate -> quantise -> integer product -> epilogue in ONE kernel; the int8
+ * activations never travel through HBM.  Same arithmetic and results as
+ * trdq_rotate_quant followed by trdq_qgemm.  K is taken from the handle.
+ * Errors as the two calls above; K beyond the fused kernel's on-chip panel
+ * (K > 6144) -> ERR_UNSUPPORTED. */
+trdq_status trdq_linear_fused(const void *X_dev, int64_t M, int64_t ldx, const float *diag_dev,
+                              const trdq_weights *w, const float *bias_dev,
+                              void *Y_dev, int64_t ldy, void *stream);
+
+/* ------------------------------------------------------------------ layer
+ * Convenience: one linear layer = the step table + one diagonal and one prepared
+ * weight set per group (H_t depends on t, so each group keeps its own weights). */
+typedef struct trdq_layer trdq_layer;
+
+/* The layer copies the table.  Errors as above. */
+trdq_status trdq_layer_create(const trdq_table *t, int K, int N, int wbits, trdq_layer **out);
+
+/* Prepare group g from W_dev [K, N] and diag_dev [K] (or NULL = ones; the diagonal is copied
+ * to a device buffer the layer owns).  Replaces an earlier setting of the same group. */
+trdq_status trdq_layer_set_group(trdq_layer *l, int g, const float *diag_dev, const float *W_dev,
+                                 void *stream);
+
+/* Forward at sampling step `step`: looks up the group, then runs either the fused kernel
+ * (fused != 0) or rotate_quant + qgemm through the caller's workspace:
+ * Xq_ws_dev int8 [M, K] and sx_ws_dev float32 [M] (both may be NULL when fused != 0).
+ * X_dev bf16 [M, K] dense; Y_dev bf16 [M, N] dense.
+ * Errors: step outside the table -> ERR_RANGE; group not set -> ERR_MISMATCH. */
+trdq_status trdq_layer_forward(const trdq_layer *l, int step, const void *X_dev, int64_t M,
+                               const float *bias_dev, void *Y_dev, int fused,
+                               int8_t *Xq_ws_dev, float *sx_ws_dev, void *stream);
+
+trdq_status trdq_layer_weights(const trdq_layer *l, int g, const trdq_weights **w_out);
+void trdq_layer_destroy(trdq_layer *l);
+
+/* --------------------------------------------------------------- selection
+ * Tile-shape override for trdq_qgemm, for tuning and tests: variant < 0 restores the
+ * built-in choice.  Process-wide; not thread-safe against concurrent qgemm calls.
+ * Unknown variant -> ERR_RANGE. */
+trdq_status trdq_qgemm_set_variant(int variant);
+int trdq_qgemm_num_variants(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TRDQ_H */

@@ -152,7 +152,7 @@ def unpack_int4(packed):
 
 
 def igemm(Xq, Wq, group=None):
-    """int32 accumulators: [M, N] when group is None/K, else [K/group, M, N]."""
+    """int32 accumulators: [M, N] when group is None, else [K/group, M, N]."""
     Xq, Wq = _c(Xq, np.int8), _c(Wq, np.int8)
     M, K = Xq.shape
     K2, N = Wq.shape
@@ -161,7 +161,7 @@ def igemm(Xq, Wq, group=None):
     ng = K // g
     acc = np.empty((ng, M, N), dtype=np.int32)
     _chk(lib().trdq_oracle_igemm(_ptr(Xq), _ptr(Wq), M, K, N, g, _ptr(acc)), "igemm")
-    return acc[0] if ng == 1 else acc
+    return acc[0] if group is None else acc
 
 
 def acc_exact_blas(Xq, Wq, group=None):
@@ -177,7 +177,7 @@ def acc_exact_blas(Xq, Wq, group=None):
     out = np.empty((ng, M, Wq.shape[1]), dtype=np.int32)
     for b in range(ng):
         out[b] = (Xd[:, b * g:(b + 1) * g] @ Wd[b * g:(b + 1) * g]).astype(np.int32)
-    return out[0] if ng == 1 else out
+    return out[0] if group is None else out
 
 
 def dequant(acc, sx, sw, bias=None, return_f64=False):

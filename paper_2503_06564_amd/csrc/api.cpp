@@ -1,0 +1,396 @@
+// Host side of libtrdq: argument validation (always before the first HIP call), the
+// time-step table, weight handles, the per-layer convenience object, and the exports.
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "trdq_internal.h"
+
+using trdq::Table;
+using trdq::Weights;
+
+struct trdq_table : Table {};
+struct trdq_weights : Weights {};
+
+struct trdq_layer {
+    Table table;
+    int K = 0, N = 0, wbits = 0;
+    std::vector<trdq_weights *> w;     // one per group (H_t depends on t)
+    std::vector<float *> diag;         // device copies of the groups' diagonals (null = ones)
+    std::vector<char> set;
+};
+
+namespace {
+
+int g_variant = -1;
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline trdq_status hip_status(hipError_t e) { return e == hipSuccess ? TRDQ_OK : TRDQ_ERR_HIP; }
+
+// Data pointers may be NULL when M == 0 (an empty tensor has no storage).
+trdq_status check_rotate_args(const void *X, int64_t M, int K, int64_t ldx, int block)
+{
+    if (block != trdq::kBlock) return TRDQ_ERR_UNSUPPORTED;
+    if (M < 0 || K <= 0 || K % trdq::kBlock != 0 || ldx < K || ldx % 8 != 0) return TRDQ_ERR_SHAPE;
+    if (M > 0 && !X) return TRDQ_ERR_NULL;
+    if (!aligned(X, 16)) return TRDQ_ERR_SHAPE;
+    return TRDQ_OK;
+}
+
+trdq_status check_out_args(const void *Y, int64_t M, int N, int64_t ldy, const float *bias)
+{
+    if (M < 0 || ldy < N || ldy % 4 != 0) return TRDQ_ERR_SHAPE;
+    if (M > 0 && !Y) return TRDQ_ERR_NULL;
+    if (!aligned(Y, 8) || (bias && !aligned(bias, 16))) return TRDQ_ERR_SHAPE;
+    return TRDQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *trdq_status_str(trdq_status s)
+{
+    switch (s) {
+        case TRDQ_OK: return "ok";
+        case TRDQ_ERR_NULL: return "null pointer";
+        case TRDQ_ERR_SHAPE: return "bad shape, stride or alignment";
+        case TRDQ_ERR_RANGE: return "index out of range";
+        case TRDQ_ERR_UNSUPPORTED: return "unsupported configuration";
+        case TRDQ_ERR_MISMATCH: return "handle does not match the call";
+        case TRDQ_ERR_ALLOC: return "allocation failed";
+        case TRDQ_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+int trdq_abi_version(void) { return 100; }
+
+/* ------------------------------------------------------------------ table */
+
+trdq_status trdq_table_create(int n_steps, int n_groups, const int32_t *map_host, trdq_table **out)
+{
+    if (!out) return TRDQ_ERR_NULL;
+    *out = nullptr;
+    if (n_steps <= 0 || n_groups <= 0 || n_groups > n_steps) return TRDQ_ERR_RANGE;
+    if (map_host)
+        for (int s = 0; s < n_steps; ++s)
+            if (map_host[s] < 0 || map_host[s] >= n_groups) return TRDQ_ERR_RANGE;
+    trdq_table *t = new (std::nothrow) trdq_table;
+    if (!t) return TRDQ_ERR_ALLOC;
+    t->map = static_cast<int32_t *>(std::malloc(sizeof(int32_t) * (size_t)n_steps));
+    if (!t->map) { delete t; return TRDQ_ERR_ALLOC; }
+    t->n_steps = n_steps;
+    t->n_groups = n_groups;
+    for (int s = 0; s < n_steps; ++s)
+        t->map[s] = map_host ? map_host[s] : (int32_t)(((int64_t)s * n_groups) / n_steps);
+    *out = t;
+    return TRDQ_OK;
+}
+
+trdq_status trdq_table_lookup(const trdq_table *t, int step, int *group_out)
+{
+    if (!t || !group_out) return TRDQ_ERR_NULL;
+    if (step < 0 || step >= t->n_steps) return TRDQ_ERR_RANGE;
+    *group_out = t->map[step];
+    return TRDQ_OK;
+}
+
+trdq_status trdq_table_sizes(const trdq_table *t, int *n_steps_out, int *n_groups_out)
+{
+    if (!t) return TRDQ_ERR_NULL;
+    if (n_steps_out) *n_steps_out = t->n_steps;
+    if (n_groups_out) *n_groups_out = t->n_groups;
+    return TRDQ_OK;
+}
+
+void trdq_table_destroy(trdq_table *t)
+{
+    if (!t) return;
+    std::free(t->map);
+    delete t;
+}
+
+/* ---------------------------------------------------------------- weights */
+
+trdq_status trdq_prepare_weights(const float *W_dev, int K, int N, const float *diag_dev,
+                                 int block, int wbits, void *stream, trdq_weights **out)
+{
+    if (!out) return TRDQ_ERR_NULL;
+    *out = nullptr;
+    if (!W_dev) return TRDQ_ERR_NULL;
+    if (block != trdq::kBlock || (wbits != 8 && wbits != 4)) return TRDQ_ERR_UNSUPPORTED;
+    if (K <= 0 || N <= 0 || K % trdq::kBlock != 0 || N % 16 != 0) return TRDQ_ERR_SHAPE;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int nb = K / trdq::kBlock;
+    trdq_weights *w = new (std::nothrow) trdq_weights;
+    if (!w) return TRDQ_ERR_ALLOC;
+    w->K = K; w->N = N; w->wbits = wbits;
+    float *Wrot = nullptr, *amax = nullptr;
+    const size_t code_bytes = wbits == 8 ? (size_t)K * N : (size_t)K * N / 2;
+    const size_t scale_count = wbits == 8 ? (size_t)N : (size_t)nb * N;
+    trdq_status rc = TRDQ_OK;
+    if (hipGetDevice(&w->device) != hipSuccess) { rc = TRDQ_ERR_HIP; goto fail; }
+    if (hipMalloc(&w->codes, code_bytes) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&w->scales), scale_count * sizeof(float)) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&Wrot), (size_t)K * N * sizeof(float)) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&amax), (size_t)nb * N * sizeof(float)) != hipSuccess) {
+        rc = TRDQ_ERR_ALLOC;
+        goto fail;
+    }
+    if (trdq::launch_prepare_rotate(W_dev, K, N, diag_dev, Wrot, amax, st) != hipSuccess ||
+        trdq::launch_prepare_quant(Wrot, amax, K, N, wbits, w->codes, w->scales, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) {
+        rc = TRDQ_ERR_HIP;
+        goto fail;
+    }
+    (void)hipFree(Wrot);
+    (void)hipFree(amax);
+    *out = w;
+    return TRDQ_OK;
+fail:
+    (void)hipGetLastError();
+    if (Wrot) (void)hipFree(Wrot);
+    if (amax) (void)hipFree(amax);
+    if (w->codes) (void)hipFree(w->codes);
+    if (w->scales) (void)hipFree(w->scales);
+    delete w;
+    return rc;
+}
+
+trdq_status trdq_weights_info(const trdq_weights *w, int *K_out, int *N_out, int *wbits_out)
+{
+    if (!w) return TRDQ_ERR_NULL;
+    if (K_out) *K_out = w->K;
+    if (N_out) *N_out = w->N;
+    if (wbits_out) *wbits_out = w->wbits;
+    return TRDQ_OK;
+}
+
+trdq_status trdq_weights_nbytes(const trdq_weights *w, int64_t *nbytes_out)
+{
+    if (!w || !nbytes_out) return TRDQ_ERR_NULL;
+    const int64_t codes = w->wbits == 8 ? (int64_t)w->K * w->N : (int64_t)w->K * w->N / 2;
+    const int64_t scales = (w->wbits == 8 ? (int64_t)w->N : (int64_t)(w->K / trdq::kBlock) * w->N) * 4;
+    *nbytes_out = codes + scales;
+    return TRDQ_OK;
+}
+
+trdq_status trdq_weights_export(const trdq_weights *w, int8_t *codes_host, float *scales_host)
+{
+    if (!w) return TRDQ_ERR_NULL;
+    const int K = w->K, N = w->N;
+    if (hipDeviceSynchronize() != hipSuccess) return TRDQ_ERR_HIP;
+    if (scales_host) {
+        const size_t cnt = w->wbits == 8 ? (size_t)N : (size_t)(K / trdq::kBlock) * N;
+        if (hipMemcpy(scales_host, w->scales, cnt * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess)
+            return TRDQ_ERR_HIP;
+    }
+    if (codes_host) {
+        const size_t bytes = w->wbits == 8 ? (size_t)K * N : (size_t)K * N / 2;
+        std::vector<uint8_t> tmp;
+        try { tmp.resize(bytes); } catch (...) { return TRDQ_ERR_ALLOC; }
+        if (hipMemcpy(tmp.data(), w->codes, bytes, hipMemcpyDeviceToHost) != hipSuccess) return TRDQ_ERR_HIP;
+        if (w->wbits == 8) {
+            for (int n = 0; n < N; ++n)
+                for (int k = 0; k < K; ++k)
+                    codes_host[(size_t)k * N + n] = (int8_t)tmp[(size_t)n * K + k];
+        } else {
+            // 4 bytes hold channels k0..k0+7: byte j = code(k0+j) | code(k0+4+j) << 4
+            for (int n = 0; n < N; ++n)
+                for (int k0 = 0; k0 < K; k0 += 8)
+                    for (int j = 0; j < 4; ++j) {
+                        const uint8_t v = tmp[(size_t)n * (K / 2) + k0 / 2 + j];
+                        const int lo = v & 0xF, hi = v >> 4;
+                        codes_host[(size_t)(k0 + j) * N + n] = (int8_t)(lo >= 8 ? lo - 16 : lo);
+                        codes_host[(size_t)(k0 + 4 + j) * N + n] = (int8_t)(hi >= 8 ? hi - 16 : hi);
+                    }
+        }
+    }
+    return TRDQ_OK;
+}
+
+trdq_status trdq_weights_export_packed(const trdq_weights *w, uint8_t *packed_host)
+{
+    if (!w || !packed_host) return TRDQ_ERR_NULL;
+    if (w->wbits != 4) return TRDQ_ERR_MISMATCH;
+    const int K = w->K, N = w->N;
+    std::vector<int8_t> codes;
+    try { codes.resize((size_t)K * N); } catch (...) { return TRDQ_ERR_ALLOC; }
+    trdq_status rc = trdq_weights_export(w, codes.data(), nullptr);
+    if (rc != TRDQ_OK) return rc;
+    for (int j = 0; j < K / 2; ++j)
+        for (int n = 0; n < N; ++n) {
+            const uint8_t lo = (uint8_t)codes[(size_t)(2 * j) * N + n] & 0xF;
+            const uint8_t hi = (uint8_t)codes[(size_t)(2 * j + 1) * N + n] & 0xF;
+            packed_host[(size_t)j * N + n] = (uint8_t)(lo | (hi << 4));
+        }
+    return TRDQ_OK;
+}
+
+void trdq_weights_destroy(trdq_weights *w)
+{
+    if (!w) return;
+    if (w->codes) (void)hipFree(w->codes);
+    if (w->scales) (void)hipFree(w->scales);
+    delete w;
+}
+
+/* ----------------------------------------------------------------- online */
+
+trdq_status trdq_rotate_quant(const void *X_dev, int64_t M, int K, int64_t ldx,
+                              const float *diag_dev, int block,
+                              int8_t *Xq_dev, float *sx_dev, void *stream)
+{
+    trdq_status rc = check_rotate_args(X_dev, M, K, ldx, block);
+    if (rc != TRDQ_OK) return rc;
+    if (M > 0 && (!Xq_dev || !sx_dev)) return TRDQ_ERR_NULL;
+    if (!aligned(Xq_dev, 8) || !aligned(sx_dev, 4) || (diag_dev && !aligned(diag_dev, 16))) return TRDQ_ERR_SHAPE;
+    if (K / trdq::kBlock > 64) return TRDQ_ERR_UNSUPPORTED;
+    if (M == 0) return TRDQ_OK;
+    return hip_status(trdq::launch_rotate_quant(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev,
+                                                Xq_dev, sx_dev, static_cast<hipStream_t>(stream)));
+}
+
+trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev, int64_t M,
+                       const float *bias_dev, void *Y_dev, int64_t ldy,
+                       int32_t *acc_debug_dev, void *stream)
+{
+    if (!w) return TRDQ_ERR_NULL;
+    trdq_status rc = check_out_args(Y_dev, M, w->N, ldy, bias_dev);
+    if (rc != TRDQ_OK) return rc;
+    if (M > 0 && (!Xq_dev || !sx_dev)) return TRDQ_ERR_NULL;
+    if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || (acc_debug_dev && !aligned(acc_debug_dev, 16)))
+        return TRDQ_ERR_SHAPE;
+    if (M == 0) return TRDQ_OK;
+    return hip_status(trdq::launch_qgemm(*w, Xq_dev, sx_dev, M, bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
+                                         acc_debug_dev, g_variant, static_cast<hipStream_t>(stream)));
+}
+
+trdq_status trdq_linear_fused(const void *X_dev, int64_t M, int64_t ldx, const float *diag_dev,
+                              const trdq_weights *w, const float *bias_dev,
+                              void *Y_dev, int64_t ldy, void *stream)
+{
+    if (!w) return TRDQ_ERR_NULL;
+    trdq_status rc = check_rotate_args(X_dev, M, w->K, ldx, trdq::kBlock);
+    if (rc != TRDQ_OK) return rc;
+    rc = check_out_args(Y_dev, M, w->N, ldy, bias_dev);
+    if (rc != TRDQ_OK) return rc;
+    if (diag_dev && !aligned(diag_dev, 16)) return TRDQ_ERR_SHAPE;
+    if (!trdq::fused_supports(w->K)) return TRDQ_ERR_UNSUPPORTED;
+    if (M == 0) return TRDQ_OK;
+    return hip_status(trdq::launch_linear_fused(*w, static_cast<const uint16_t *>(X_dev), M, ldx, diag_dev,
+                                                bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
+                                                static_cast<hipStream_t>(stream)));
+}
+
+/* ------------------------------------------------------------------ layer */
+
+trdq_status trdq_layer_create(const trdq_table *t, int K, int N, int wbits, trdq_layer **out)
+{
+    if (!out) return TRDQ_ERR_NULL;
+    *out = nullptr;
+    if (!t) return TRDQ_ERR_NULL;
+    if (wbits != 8 && wbits != 4) return TRDQ_ERR_UNSUPPORTED;
+    if (K <= 0 || N <= 0 || K % trdq::kBlock != 0 || N % 16 != 0) return TRDQ_ERR_SHAPE;
+    trdq_layer *l = new (std::nothrow) trdq_layer;
+    if (!l) return TRDQ_ERR_ALLOC;
+    l->table.n_steps = t->n_steps;
+    l->table.n_groups = t->n_groups;
+    l->table.map = static_cast<int32_t *>(std::malloc(sizeof(int32_t) * (size_t)t->n_steps));
+    if (!l->table.map) { delete l; return TRDQ_ERR_ALLOC; }
+    std::memcpy(l->table.map, t->map, sizeof(int32_t) * (size_t)t->n_steps);
+    l->K = K; l->N = N; l->wbits = wbits;
+    try {
+        l->w.assign((size_t)t->n_groups, nullptr);
+        l->diag.assign((size_t)t->n_groups, nullptr);
+        l->set.assign((size_t)t->n_groups, 0);
+    } catch (...) {
+        std::free(l->table.map);
+        delete l;
+        return TRDQ_ERR_ALLOC;
+    }
+    *out = l;
+    return TRDQ_OK;
+}
+
+trdq_status trdq_layer_set_group(trdq_layer *l, int g, const float *diag_dev, const float *W_dev, void *stream)
+{
+    if (!l || !W_dev) return TRDQ_ERR_NULL;
+    if (g < 0 || g >= l->table.n_groups) return TRDQ_ERR_RANGE;
+    if (diag_dev && !aligned(diag_dev, 16)) return TRDQ_ERR_SHAPE;
+    trdq_weights *w = nullptr;
+    trdq_status rc = trdq_prepare_weights(W_dev, l->K, l->N, diag_dev, trdq::kBlock, l->wbits, stream, &w);
+    if (rc != TRDQ_OK) return rc;
+    float *d = nullptr;
+    if (diag_dev) {
+        if (hipMalloc(reinterpret_cast<void **>(&d), sizeof(float) * (size_t)l->K) != hipSuccess) {
+            trdq_weights_destroy(w);
+            return TRDQ_ERR_ALLOC;
+        }
+        if (hipMemcpy(d, diag_dev, sizeof(float) * (size_t)l->K, hipMemcpyDeviceToDevice) != hipSuccess) {
+            (void)hipFree(d);
+            trdq_weights_destroy(w);
+            return TRDQ_ERR_HIP;
+        }
+    }
+    if (l->w[(size_t)g]) trdq_weights_destroy(l->w[(size_t)g]);
+    if (l->diag[(size_t)g]) (void)hipFree(l->diag[(size_t)g]);
+    l->w[(size_t)g] = w;
+    l->diag[(size_t)g] = d;
+    l->set[(size_t)g] = 1;
+    return TRDQ_OK;
+}
+
+trdq_status trdq_layer_forward(const trdq_layer *l, int step, const void *X_dev, int64_t M,
+                               const float *bias_dev, void *Y_dev, int fused,
+                               int8_t *Xq_ws_dev, float *sx_ws_dev, void *stream)
+{
+    if (!l) return TRDQ_ERR_NULL;
+    if (step < 0 || step >= l->table.n_steps) return TRDQ_ERR_RANGE;
+    const int g = l->table.map[step];
+    if (!l->set[(size_t)g]) return TRDQ_ERR_MISMATCH;
+    const trdq_weights *w = l->w[(size_t)g];
+    const float *d = l->diag[(size_t)g];
+    if (fused)
+        return trdq_linear_fused(X_dev, M, l->K, d, w, bias_dev, Y_dev, l->N, stream);
+    if (!Xq_ws_dev || !sx_ws_dev) return TRDQ_ERR_NULL;
+    trdq_status rc = trdq_rotate_quant(X_dev, M, l->K, l->K, d, trdq::kBlock, Xq_ws_dev, sx_ws_dev, stream);
+    if (rc != TRDQ_OK) return rc;
+    return trdq_qgemm(w, Xq_ws_dev, sx_ws_dev, M, bias_dev, Y_dev, l->N, nullptr, stream);
+}
+
+trdq_status trdq_layer_weights(const trdq_layer *l, int g, const trdq_weights **w_out)
+{
+    if (!l || !w_out) return TRDQ_ERR_NULL;
+    if (g < 0 || g >= l->table.n_groups) return TRDQ_ERR_RANGE;
+    if (!l->set[(size_t)g]) return TRDQ_ERR_MISMATCH;
+    *w_out = l->w[(size_t)g];
+    return TRDQ_OK;
+}
+
+void trdq_layer_destroy(trdq_layer *l)
+{
+    if (!l) return;
+    for (trdq_weights *w : l->w) trdq_weights_destroy(w);
+    for (float *d : l->diag)
+        if (d) (void)hipFree(d);
+    std::free(l->table.map);
+    delete l;
+}
+
+/* --------------------------------------------------------------- selection */
+
+trdq_status trdq_qgemm_set_variant(int variant)
+{
+    if (variant >= trdq::qgemm_num_variants()) return TRDQ_ERR_RANGE;
+    g_variant = variant < 0 ? -1 : variant;
+    return TRDQ_OK;
+}
+
+int trdq_qgemm_num_variants(void) { return trdq::qgemm_num_variants(); }
+
+}  // extern "C"

@@ -1,0 +1,287 @@
+// linear_fused: rotate -> per-token quantise -> int8 product -> dequantising epilogue in one
+// kernel (Eq. 10 end to end); the int8 activations never leave the chip.
+//
+// A workgroup owns a panel of BM tokens for the WHOLE input width K: the prologue rotates and
+// quantises the panel straight into LDS (int8, BM x K), then the workgroup sweeps its share
+// of the output channels with the same matrix-core loop as qgemm, streaming weight tiles
+// through a double-buffered LDS stage.  The 160 KB of LDS per compute unit bound BM * K; the
+// panel height shrinks as K grows (64 tokens up to K = 1536, 32 up to 3072, 16 up to 6144).
+#include "rotate_core.h"
+
+namespace trdq {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kPad = 16;
+constexpr int kBN = 128;   // output channels per weight tile
+constexpr int kBK = 128;   // input channels per weight tile = one rotation block / scale group
+
+struct FusedArgs {
+    const uint16_t *X;     // bf16 [M, ldx]
+    const float *diag;     // [K] or null
+    const void *Wc;
+    const float *sw;
+    const float *bias;
+    uint16_t *Y;
+    int64_t M, ldx, ldy;
+    int K, N;
+    int tiles_n;           // ceil(N / kBN)
+    int nsplit;            // workgroups sharing one token panel
+};
+
+// BM tokens per panel, S lane-rows per token in the prologue, T blocks per lane-row
+template <int BM, int T, int S, bool W4>
+__global__ __launch_bounds__(kThreads) void linear_fused_kernel(FusedArgs g)
+{
+    constexpr int WM = BM >= 64 ? 32 : BM;           // wave tile (tokens)
+    constexpr int WGM = BM / WM, WGN = 4 / WGM;
+    constexpr int WN = kBN / WGN;
+    constexpr int TM = WM / 16, TN = WN / 16;
+    constexpr int LDW = kBK + kPad;
+    constexpr int CW = W4 ? kBN * (kBK / 32) / kThreads : kBN * (kBK / 16) / kThreads;
+
+    extern __shared__ __align__(16) int8_t smem[];
+    const int K = g.K;
+    const int nb = K / kBlock;
+    const int LDX = K + kPad;
+    int8_t *const Xp = smem;                              // [BM][K + 16]   int8 panel
+    int8_t *const Ws = smem + BM * LDX;                   // [2][kBN][LDW]  weight stages
+    float *const sxs = reinterpret_cast<float *>(Ws + 2 * kBN * LDW);   // [BM]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, lg = lane >> 4;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+
+    // ---- prologue: rotate + quantise the panel into LDS -----------------------------------
+    {
+        const LaneSigns sg(l16);
+        const int s = lg % S;
+        constexpr int kTokPerPass = (kThreads / 64) * (4 / S);
+        for (int r0 = 0; r0 < BM; r0 += kTokPerPass) {
+            const int r = r0 + wave * (4 / S) + lg / S;
+            const int64_t token = m0 + r;
+            const bool ok = r < BM && token < g.M;
+            float v[T][8];
+            float amax;
+            rotate_token<T, S>(g.X + token * g.ldx, ok, nb, s, l16, g.diag, sg, v, amax);
+            const float inv = token_inv_scale(amax);
+            if (r < BM) {
+                if (s == 0 && l16 == 0) sxs[r] = ok ? token_scale(amax) : 0.0f;
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    const int b = t * S + s;
+                    if (b < nb)
+                        *reinterpret_cast<uint2 *>(Xp + r * LDX + b * kBlock + l16 * 8) = quant_pack8(v[t], inv);
+                }
+            }
+        }
+    }
+
+    // ---- weight staging -----------------------------------------------------------------------
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int tiles_per = (g.tiles_n + g.nsplit - 1) / g.nsplit;
+    const int tn_begin = blockIdx.y * tiles_per;
+    const int tn_end = min(tn_begin + tiles_per, g.tiles_n);
+    const int KT = K / kBK;
+    const int iters = (tn_end - tn_begin) * KT;
+
+    uint4 wr[CW];
+    int wrow[CW], wcol[CW], wdst[CW];
+#pragma unroll
+    for (int i = 0; i < CW; ++i) {
+        const int ch = tid + i * kThreads;
+        if constexpr (W4) {
+            wrow[i] = ch / (kBK / 32); wcol[i] = (ch % (kBK / 32)) * 16;
+            wdst[i] = wrow[i] * LDW + (ch % (kBK / 32)) * 32;
+        } else {
+            wrow[i] = ch / (kBK / 16); wcol[i] = (ch % (kBK / 16)) * 16;
+            wdst[i] = wrow[i] * LDW + wcol[i];
+        }
+    }
+    auto load_tile = [&](int it) {
+        const int tn = tn_begin + it / KT, kt = it % KT;
+#pragma unroll
+        for (int i = 0; i < CW; ++i) {
+            int n = tn * kBN + wrow[i];
+            if (n >= g.N) n = g.N - 1;
+            const uint8_t *src = static_cast<const uint8_t *>(g.Wc) +
+                                 (W4 ? (size_t)n * (K / 2) + kt * (kBK / 2) : (size_t)n * K + kt * kBK) + wcol[i];
+            wr[i] = *reinterpret_cast<const uint4 *>(src);
+        }
+    };
+    auto store_tile = [&](int buf) {
+        int8_t *ws = Ws + buf * kBN * LDW;
+#pragma unroll
+        for (int i = 0; i < CW; ++i) {
+            if constexpr (W4) {
+                const uint4 p = wr[i];
+                uint4 a, b;
+                a.x = (p.x << 4) & 0xF0F0F0F0u; a.y = p.x & 0xF0F0F0F0u;
+                a.z = (p.y << 4) & 0xF0F0F0F0u; a.w = p.y & 0xF0F0F0F0u;
+                b.x = (p.z << 4) & 0xF0F0F0F0u; b.y = p.z & 0xF0F0F0F0u;
+                b.z = (p.w << 4) & 0xF0F0F0F0u; b.w = p.w & 0xF0F0F0F0u;
+                *reinterpret_cast<uint4 *>(ws + wdst[i]) = a;
+                *reinterpret_cast<uint4 *>(ws + wdst[i] + 16) = b;
+            } else {
+                *reinterpret_cast<uint4 *>(ws + wdst[i]) = wr[i];
+            }
+        }
+    };
+
+    v4i acc[TN][TM];
+    v4f facc[W4 ? TN : 1][W4 ? TM : 1];
+    auto reset = [&]() {
+#pragma unroll
+        for (int a = 0; a < TN; ++a)
+#pragma unroll
+            for (int b = 0; b < TM; ++b) {
+                acc[a][b] = v4i{0, 0, 0, 0};
+                if constexpr (W4) facc[a][b] = v4f{0.f, 0.f, 0.f, 0.f};
+            }
+    };
+    reset();
+
+    if (iters > 0) { load_tile(0); store_tile(0); }
+    __syncthreads();     // also publishes the panel and the token scales
+
+    const int8_t *xrow = Xp + (wm * WM + l16) * LDX + lg * 16;
+    for (int it = 0; it < iters; ++it) {
+        const int buf = it & 1;
+        const int tn = tn_begin + it / KT, kt = it % KT;
+        if (it + 1 < iters) load_tile(it + 1);
+
+        const int8_t *ws = Ws + buf * kBN * LDW + (wn * WN + l16) * LDW + lg * 16;
+#pragma unroll
+        for (int kk = 0; kk < kBK; kk += 64) {
+            v4i af[TN], bf[TM];
+#pragma unroll
+            for (int a = 0; a < TN; ++a) af[a] = *reinterpret_cast<const v4i *>(ws + a * 16 * LDW + kk);
+#pragma unroll
+            for (int b = 0; b < TM; ++b)
+                bf[b] = *reinterpret_cast<const v4i *>(xrow + b * 16 * LDX + kt * kBK + kk);
+#pragma unroll
+            for (int a = 0; a < TN; ++a)
+#pragma unroll
+                for (int b = 0; b < TM; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[a], bf[b], acc[a][b], 0, 0, 0);
+        }
+
+        const int n_base = tn * kBN + wn * WN + lg * 4;
+        if constexpr (W4) {
+#pragma unroll
+            for (int a = 0; a < TN; ++a) {
+                const int n = n_base + a * 16;
+                float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (n < g.N) s = *reinterpret_cast<const float4 *>(g.sw + (size_t)kt * g.N + n);
+#pragma unroll
+                for (int b = 0; b < TM; ++b) {
+                    facc[a][b][0] += s.x * (float)acc[a][b][0];
+                    facc[a][b][1] += s.y * (float)acc[a][b][1];
+                    facc[a][b][2] += s.z * (float)acc[a][b][2];
+                    facc[a][b][3] += s.w * (float)acc[a][b][3];
+                    acc[a][b] = v4i{0, 0, 0, 0};
+                }
+            }
+        }
+
+        if (kt == KT - 1) {
+            // epilogue of channel tile tn
+#pragma unroll
+            for (int a = 0; a < TN; ++a) {
+                const int n = n_base + a * 16;
+                if (n >= g.N) continue;
+                float4 s = make_float4(1.f, 1.f, 1.f, 1.f), bi = make_float4(0.f, 0.f, 0.f, 0.f);
+                if constexpr (!W4) s = *reinterpret_cast<const float4 *>(g.sw + n);
+                if (g.bias) bi = *reinterpret_cast<const float4 *>(g.bias + n);
+#pragma unroll
+                for (int b = 0; b < TM; ++b) {
+                    const int r = wm * WM + b * 16 + l16;
+                    const int64_t m = m0 + r;
+                    if (m >= g.M) continue;
+                    const float sxm = W4 ? sxs[r] * 0.0625f : sxs[r];
+                    float y0, y1, y2, y3;
+                    if constexpr (W4) {
+                        y0 = sxm * facc[a][b][0] + bi.x;
+                        y1 = sxm * facc[a][b][1] + bi.y;
+                        y2 = sxm * facc[a][b][2] + bi.z;
+                        y3 = sxm * facc[a][b][3] + bi.w;
+                    } else {
+                        y0 = (float)acc[a][b][0] * sxm * s.x + bi.x;
+                        y1 = (float)acc[a][b][1] * sxm * s.y + bi.y;
+                        y2 = (float)acc[a][b][2] * sxm * s.z + bi.z;
+                        y3 = (float)acc[a][b][3] * sxm * s.w + bi.w;
+                    }
+                    uint2 o;
+                    o.x = pack_bf16x2(y0, y1);
+                    o.y = pack_bf16x2(y2, y3);
+                    *reinterpret_cast<uint2 *>(g.Y + m * g.ldy + n) = o;
+                }
+            }
+            reset();
+        }
+
+        if (it + 1 < iters) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+}
+
+template <int BM, int T, int S, bool W4>
+hipError_t launch_one(const FusedArgs &a, hipStream_t st)
+{
+    FusedArgs g = a;
+    const int64_t panels = (g.M + BM - 1) / BM;
+    g.tiles_n = (g.N + kBN - 1) / kBN;
+    // enough workgroups to fill 256 compute units twice; every extra split repeats the prologue
+    int64_t want = (512 + panels - 1) / panels;
+    want = want < 1 ? 1 : (want > g.tiles_n ? g.tiles_n : want);
+    const int tiles_per = (int)((g.tiles_n + want - 1) / want);
+    g.nsplit = (g.tiles_n + tiles_per - 1) / tiles_per;   // no workgroup without a channel tile
+    const size_t smem = (size_t)BM * (g.K + kPad) + 2 * (size_t)kBN * (kBK + kPad) + BM * sizeof(float);
+    auto kern = linear_fused_kernel<BM, T, S, W4>;
+    static size_t attr_smem = 0;
+    if (smem > attr_smem) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_smem = smem;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)panels, (unsigned)g.nsplit), dim3(kThreads), smem, st, g);
+    return hipGetLastError();
+}
+
+template <int BM, int S, bool W4>
+hipError_t launch_t(int T, const FusedArgs &a, hipStream_t st)
+{
+    if (T <= 3) return launch_one<BM, 3, S, W4>(a, st);
+    if (T <= 6) return launch_one<BM, 6, S, W4>(a, st);
+    if (T <= 9) return launch_one<BM, 9, S, W4>(a, st);
+    return launch_one<BM, 12, S, W4>(a, st);
+}
+
+template <bool W4>
+hipError_t launch_w(const FusedArgs &a, hipStream_t st)
+{
+    const int nb = a.K / kBlock;
+    if (nb <= 12) return launch_t<64, 1, W4>(nb, a, st);
+    if (nb <= 24) return launch_t<32, 2, W4>((nb + 1) / 2, a, st);
+    return launch_t<16, 4, W4>((nb + 3) / 4, a, st);
+}
+
+}  // namespace
+
+bool fused_supports(int K) { return K % kBlock == 0 && K / kBlock <= 48; }
+
+hipError_t launch_linear_fused(const Weights &w, const uint16_t *X, int64_t M, int64_t ldx,
+                               const float *diag, const float *bias, uint16_t *Y, int64_t ldy,
+                               hipStream_t st)
+{
+    if (M == 0) return hipSuccess;
+    FusedArgs a;
+    a.X = X; a.diag = diag; a.Wc = w.codes; a.sw = w.scales; a.bias = bias; a.Y = Y;
+    a.M = M; a.ldx = ldx; a.ldy = ldy; a.K = w.K; a.N = w.N; a.tiles_n = 0; a.nsplit = 1;
+    return w.wbits == 4 ? launch_w<true>(a, st) : launch_w<false>(a, st);
+}
+
+}  // namespace trdq

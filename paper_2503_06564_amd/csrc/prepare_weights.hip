@@ -1,0 +1,150 @@
+// prepare_weights: H_t(W) = R^T . (Delta_t^-1 . W) of Eq. 10 and the symmetric weight
+// quantiser (per output channel for int8, per 128-row group and output channel for int4).
+// Offline, once per time-step group; two streaming kernels through a float32 scratch matrix.
+#include "device_utils.h"
+#include "trdq_internal.h"
+
+namespace trdq {
+
+namespace {
+
+constexpr int kCols = 64;          // output channels per workgroup
+constexpr int kPrepThreads = 256;
+
+// Kernel 1: one workgroup rotates one 128-row block of 64 columns.
+//   Wrot[b*128 + j, n] = sum_k H[k][j] * W[b*128 + k, n] / d[b*128 + k]      (unnormalised H)
+//   amax[b, n]         = max_j |Wrot[b*128 + j, n]|
+__global__ __launch_bounds__(kPrepThreads) void prepare_rotate_kernel(
+    const float *__restrict__ W, int K, int N, const float *__restrict__ diag,
+    float *__restrict__ Wrot, float *__restrict__ amax)
+{
+    __shared__ float tile[kBlock][kCols + 1];
+    __shared__ float part[4][kCols];
+    const int b = blockIdx.y;
+    const int n0 = blockIdx.x * kCols;
+    const int c = threadIdx.x % kCols;
+    const int q = threadIdx.x / kCols;     // 0..3
+    const int n = n0 + c;
+    const bool col_ok = n < N;
+
+    for (int k = q; k < kBlock; k += 4) {
+        float w = 0.0f;
+        if (col_ok) {
+            w = W[(size_t)(b * kBlock + k) * N + n];
+            if (diag) w = w / diag[b * kBlock + k];
+        }
+        tile[k][c] = w;
+    }
+    __syncthreads();
+    // 7 butterfly stages down the rows; 64 pairs per column per stage, 16 per thread
+    for (int h = 1; h < kBlock; h <<= 1) {
+        for (int pr = q; pr < kBlock / 2; pr += 4) {
+            const int lo = ((pr / h) * 2 * h) + (pr % h);
+            const float a = tile[lo][c], bb = tile[lo + h][c];
+            tile[lo][c] = a + bb;
+            tile[lo + h][c] = a - bb;
+        }
+        __syncthreads();
+    }
+    float m = 0.0f;
+    for (int k = q; k < kBlock; k += 4) {
+        const float w = tile[k][c];
+        m = fmaxf(m, fabsf(w));
+        if (col_ok) Wrot[(size_t)(b * kBlock + k) * N + n] = w;
+    }
+    part[q][c] = m;
+    __syncthreads();
+    if (q == 0 && col_ok)
+        amax[(size_t)b * N + n] = fmaxf(fmaxf(part[0][c], part[1][c]), fmaxf(part[2][c], part[3][c]));
+}
+
+// Kernel 2: quantise and transpose one 128-row block of 64 columns into the K-contiguous
+// layouts the product kernels read (see Weights in trdq_internal.h).
+//   wbits 8: scale[n]    = max_b amax[b, n] / (sqrt(128) * 127)
+//   wbits 4: scale[b, n] = amax[b, n]       / (sqrt(128) * 7)
+//   code = rint(Wrot * qmax / amax)   (ties to even; amax == 0 -> 0)
+template <int WBITS>
+__global__ __launch_bounds__(kPrepThreads) void prepare_quant_kernel(
+    const float *__restrict__ Wrot, const float *__restrict__ amax, int K, int N,
+    void *__restrict__ codes, float *__restrict__ scales)
+{
+    __shared__ int8_t q8[kCols][kBlock + 16];
+    __shared__ float inv_s[kCols];
+    const int nb = K / kBlock;
+    const int b = blockIdx.y;
+    const int n0 = blockIdx.x * kCols;
+    constexpr float qmax = WBITS == 8 ? 127.0f : 7.0f;
+    constexpr float rsqrtB = 0.08838834764831845f;
+
+    if (threadIdx.x < kCols) {
+        const int n = n0 + threadIdx.x;
+        float a = 0.0f;
+        if (n < N) {
+            if (WBITS == 8) {
+                for (int bb = 0; bb < nb; ++bb) a = fmaxf(a, amax[(size_t)bb * N + n]);
+                if (b == 0) scales[n] = a * (rsqrtB / qmax);
+            } else {
+                a = amax[(size_t)b * N + n];
+                scales[(size_t)b * N + n] = a * (rsqrtB / qmax);
+            }
+        }
+        inv_s[threadIdx.x] = a > 0.0f ? qmax / a : 0.0f;
+    }
+    __syncthreads();
+    const int c = threadIdx.x % kCols;
+    const int q = threadIdx.x / kCols;
+    const int n = n0 + c;
+    for (int k = q; k < kBlock; k += 4) {
+        float w = n < N ? Wrot[(size_t)(b * kBlock + k) * N + n] : 0.0f;
+        q8[c][k] = (int8_t)(quant_bits(w, inv_s[c]) & 0xFF);
+    }
+    __syncthreads();
+    if (WBITS == 8) {
+        // 64 columns x 128 bytes -> 16-byte chunks, K contiguous
+        int8_t *out = static_cast<int8_t *>(codes);
+        for (int ch = threadIdx.x; ch < kCols * (kBlock / 16); ch += kPrepThreads) {
+            const int cc = ch / (kBlock / 16), kk = (ch % (kBlock / 16)) * 16;
+            if (n0 + cc < N)
+                *reinterpret_cast<uint4 *>(out + (size_t)(n0 + cc) * K + b * kBlock + kk) =
+                    *reinterpret_cast<const uint4 *>(&q8[cc][kk]);
+        }
+    } else {
+        // 8 consecutive k -> 4 bytes: byte j = code(k0+j) & 0xF | (code(k0+4+j) & 0xF) << 4
+        uint8_t *out = static_cast<uint8_t *>(codes);
+        for (int u = threadIdx.x; u < kCols * (kBlock / 8); u += kPrepThreads) {
+            const int cc = u / (kBlock / 8), k0 = (u % (kBlock / 8)) * 8;
+            if (n0 + cc < N) {
+                uint32_t word = 0;
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t lo = (uint8_t)q8[cc][k0 + j] & 0xFu;
+                    const uint32_t hi = (uint8_t)q8[cc][k0 + 4 + j] & 0xFu;
+                    word |= (lo | (hi << 4)) << (8 * j);
+                }
+                *reinterpret_cast<uint32_t *>(out + (size_t)(n0 + cc) * (K / 2) + (b * kBlock + k0) / 2) = word;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag, float *Wrot,
+                                 float *amax, hipStream_t st)
+{
+    dim3 grid((N + kCols - 1) / kCols, K / kBlock);
+    hipLaunchKernelGGL(prepare_rotate_kernel, grid, dim3(kPrepThreads), 0, st, W, K, N, diag, Wrot, amax);
+    return hipGetLastError();
+}
+
+hipError_t launch_prepare_quant(const float *Wrot, const float *amax, int K, int N, int wbits,
+                                void *codes, float *scales, hipStream_t st)
+{
+    dim3 grid((N + kCols - 1) / kCols, K / kBlock);
+    if (wbits == 8)
+        hipLaunchKernelGGL(prepare_quant_kernel<8>, grid, dim3(kPrepThreads), 0, st, Wrot, amax, K, N, codes, scales);
+    else
+        hipLaunchKernelGGL(prepare_quant_kernel<4>, grid, dim3(kPrepThreads), 0, st, Wrot, amax, K, N, codes, scales);
+    return hipGetLastError();
+}
+
+}  // namespace trdq

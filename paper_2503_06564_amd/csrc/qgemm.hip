@@ -1,0 +1,310 @@
+// qgemm: the integer product G_t(X_t) . H_t(W) of Eq. 10 on the quantised codes, on the
+// gfx950 int8 matrix cores (v_mfma_i32_16x16x64_i8, int32 accumulation), with the
+// dequantising epilogue (undo the scales of Eq. 1, add the bias, round to bf16).
+//
+// Operand roles.  The matrix instruction computes D[i][j] = sum_k A[i][k] B[k][j] and leaves
+// four consecutive i of one j in each lane.  The weights take the A role (i = output
+// channel n) and the activations the B role (j = token m), so every lane ends up with four
+// consecutive output channels of one token: one 8-byte bf16 store per 16x16 tile.  Both
+// operands are K-contiguous in memory (activations [M, K], prepared weights [N, K]), so both
+// are staged the same way: 16-byte chunks through registers into LDS rows padded by 16 bytes,
+// read back as 16 bytes per lane (row = lane % 16, k-offset = 16 * (lane / 16)).
+//
+// int4 weights are widened to int8 while they are copied into LDS, as 16 * code (the nibble
+// moved to the top of the byte), so the main loop is the same; at every 128-channel group
+// boundary the int32 partial sums are folded into float accumulators with the group's scale.
+#include "device_utils.h"
+#include "trdq_internal.h"
+
+namespace trdq {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kPad = 16;  // bytes of padding per LDS row
+
+struct GemmArgs {
+    const int8_t *Xq;      // [M, K]
+    const void *Wc;        // codes, see Weights
+    const float *sx;       // [M]
+    const float *sw;       // [N] or [K/128, N]
+    const float *bias;     // [N] or null
+    uint16_t *Y;           // [M, ldy]
+    int32_t *acc_debug;    // null, [M, N] or [K/128, M, N]
+    int64_t M, ldy;
+    int K, N;
+    int tiles_m, tiles_n;
+};
+
+// Workgroups are handed to the 8 accelerator dies round-robin by their linear id; give each
+// die a contiguous run of tiles (a few token panels times all channel tiles) so that the
+// panels it re-reads stay in its own L2.
+__device__ __forceinline__ int xcd_remap(int bid, int ntiles)
+{
+    const int q = ntiles >> 3, r = ntiles & 7;
+    const int xcd = bid & 7, idx = bid >> 3;
+    return xcd * q + (xcd < r ? xcd : r) + idx;
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool W4, bool DEBUG>
+__global__ __launch_bounds__(kThreads) void qgemm_kernel(GemmArgs g)
+{
+    static_assert(WGM * WGN == 4, "four waves per workgroup");
+    static_assert(!W4 || BK == kBlock, "int4: one scale group per k-tile");
+    constexpr int WM = BM / WGM, WN = BN / WGN;      // wave tile
+    constexpr int TM = WM / 16, TN = WN / 16;        // 16x16 tiles per wave
+    constexpr int LDR = BK + kPad;                   // LDS row stride in bytes
+    constexpr int CPR = BK / 16;                     // 16-byte chunks per tile row
+    constexpr int CX = BM * CPR / kThreads;          // activation chunks per thread
+    constexpr int CW = W4 ? BN * (BK / 32) / kThreads : BN * CPR / kThreads;  // weight chunks per thread
+    static_assert(CX >= 1 && CW >= 1, "tile too small for 256 threads");
+
+    extern __shared__ __align__(16) int8_t smem[];
+    int8_t *const Xs = smem;                         // [2][BM][LDR]
+    int8_t *const Ws = smem + 2 * BM * LDR;          // [2][BN][LDR]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int l16 = lane & 15, lg = lane >> 4;
+
+    const int tile = xcd_remap(blockIdx.x, g.tiles_m * g.tiles_n);
+    const int tm_idx = tile / g.tiles_n, tn_idx = tile % g.tiles_n;
+    const int64_t m0 = (int64_t)tm_idx * BM;
+    const int n0 = tn_idx * BN;
+    const int K = g.K;
+
+    // ---- global -> register staging --------------------------------------------------
+    uint4 xr[CX], wr[CW];
+    const int8_t *xsrc[CX];
+    const uint8_t *wsrc[CW];
+    int xdst[CX], wdst[CW];
+#pragma unroll
+    for (int i = 0; i < CX; ++i) {
+        const int ch = tid + i * kThreads;
+        const int row = ch / CPR, c16 = ch % CPR;
+        int64_t m = m0 + row;
+        if (m >= g.M) m = g.M - 1;                    // clamp: rows past M are never stored
+        xsrc[i] = g.Xq + m * K + c16 * 16;
+        xdst[i] = row * LDR + c16 * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < CW; ++i) {
+        const int ch = tid + i * kThreads;
+        if constexpr (W4) {
+            constexpr int CPR4 = BK / 32;             // 16 packed bytes = 32 channels
+            const int row = ch / CPR4, c32 = ch % CPR4;
+            int n = n0 + row;
+            if (n >= g.N) n = g.N - 1;
+            wsrc[i] = static_cast<const uint8_t *>(g.Wc) + (size_t)n * (K / 2) + c32 * 16;
+            wdst[i] = row * LDR + c32 * 32;
+        } else {
+            const int row = ch / CPR, c16 = ch % CPR;
+            int n = n0 + row;
+            if (n >= g.N) n = g.N - 1;
+            wsrc[i] = static_cast<const uint8_t *>(g.Wc) + (size_t)n * K + c16 * 16;
+            wdst[i] = row * LDR + c16 * 16;
+        }
+    }
+    auto load_tile = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < CX; ++i) xr[i] = *reinterpret_cast<const uint4 *>(xsrc[i] + kt * BK);
+#pragma unroll
+        for (int i = 0; i < CW; ++i)
+            wr[i] = *reinterpret_cast<const uint4 *>(wsrc[i] + (W4 ? kt * (BK / 2) : kt * BK));
+    };
+    auto store_tile = [&](int buf) {
+        int8_t *xs = Xs + buf * BM * LDR, *ws = Ws + buf * BN * LDR;
+#pragma unroll
+        for (int i = 0; i < CX; ++i) *reinterpret_cast<uint4 *>(xs + xdst[i]) = xr[i];
+#pragma unroll
+        for (int i = 0; i < CW; ++i) {
+            if constexpr (W4) {
+                const uint4 p = wr[i];
+                uint4 a, b;
+                a.x = (p.x << 4) & 0xF0F0F0F0u; a.y = p.x & 0xF0F0F0F0u;
+                a.z = (p.y << 4) & 0xF0F0F0F0u; a.w = p.y & 0xF0F0F0F0u;
+                b.x = (p.z << 4) & 0xF0F0F0F0u; b.y = p.z & 0xF0F0F0F0u;
+                b.z = (p.w << 4) & 0xF0F0F0F0u; b.w = p.w & 0xF0F0F0F0u;
+                *reinterpret_cast<uint4 *>(ws + wdst[i]) = a;
+                *reinterpret_cast<uint4 *>(ws + wdst[i] + 16) = b;
+            } else {
+                *reinterpret_cast<uint4 *>(ws + wdst[i]) = wr[i];
+            }
+        }
+    };
+
+    // ---- accumulators ------------------------------------------------------------------
+    v4i acc[TN][TM];
+    v4f facc[W4 ? TN : 1][W4 ? TM : 1];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b) acc[a][b] = v4i{0, 0, 0, 0};
+    if constexpr (W4) {
+#pragma unroll
+        for (int a = 0; a < TN; ++a)
+#pragma unroll
+            for (int b = 0; b < TM; ++b) facc[a][b] = v4f{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // lane's output coordinates: channels n_lane(a) .. +3, token m_lane(b)
+    auto n_lane = [&](int a) { return n0 + wn * WN + a * 16 + lg * 4; };
+    auto m_lane = [&](int b) { return m0 + wm * WM + b * 16 + l16; };
+
+    const int KT = K / BK;
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (int kt = 0; kt < KT; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < KT) load_tile(kt + 1);
+
+        const int8_t *xs = Xs + buf * BM * LDR + (wm * WM + l16) * LDR + lg * 16;
+        const int8_t *ws = Ws + buf * BN * LDR + (wn * WN + l16) * LDR + lg * 16;
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 64) {
+            v4i af[TN], bf[TM];
+#pragma unroll
+            for (int a = 0; a < TN; ++a) af[a] = *reinterpret_cast<const v4i *>(ws + a * 16 * LDR + kk);
+#pragma unroll
+            for (int b = 0; b < TM; ++b) bf[b] = *reinterpret_cast<const v4i *>(xs + b * 16 * LDR + kk);
+#pragma unroll
+            for (int a = 0; a < TN; ++a)
+#pragma unroll
+                for (int b = 0; b < TM; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[a], bf[b], acc[a][b], 0, 0, 0);
+        }
+
+        if constexpr (W4) {
+            // end of scale group kt: fold 16 * acc_g into the float accumulators
+#pragma unroll
+            for (int a = 0; a < TN; ++a) {
+                const int n = n_lane(a);
+                float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (n < g.N) s = *reinterpret_cast<const float4 *>(g.sw + (size_t)kt * g.N + n);
+#pragma unroll
+                for (int b = 0; b < TM; ++b) {
+                    if constexpr (DEBUG) {
+                        const int64_t m = m_lane(b);
+                        if (m < g.M && n < g.N) {
+                            int4 o = make_int4(acc[a][b][0] >> 4, acc[a][b][1] >> 4,
+                                               acc[a][b][2] >> 4, acc[a][b][3] >> 4);
+                            *reinterpret_cast<int4 *>(g.acc_debug + ((int64_t)kt * g.M + m) * g.N + n) = o;
+                        }
+                    }
+                    facc[a][b][0] += s.x * (float)acc[a][b][0];
+                    facc[a][b][1] += s.y * (float)acc[a][b][1];
+                    facc[a][b][2] += s.z * (float)acc[a][b][2];
+                    facc[a][b][3] += s.w * (float)acc[a][b][3];
+                    acc[a][b] = v4i{0, 0, 0, 0};
+                }
+            }
+        }
+
+        if (kt + 1 < KT) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue ----------------------------------------------------------------------
+    float sxm[TM];
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+        const int64_t m = m_lane(b);
+        sxm[b] = m < g.M ? g.sx[m] : 0.0f;
+        if constexpr (W4) sxm[b] *= 0.0625f;         // the codes were staged as 16 * code
+    }
+#pragma unroll
+    for (int a = 0; a < TN; ++a) {
+        const int n = n_lane(a);
+        if (n >= g.N) continue;
+        float4 s = make_float4(1.f, 1.f, 1.f, 1.f), bi = make_float4(0.f, 0.f, 0.f, 0.f);
+        if constexpr (!W4) s = *reinterpret_cast<const float4 *>(g.sw + n);
+        if (g.bias) bi = *reinterpret_cast<const float4 *>(g.bias + n);
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+            const int64_t m = m_lane(b);
+            if (m >= g.M) continue;
+            float y0, y1, y2, y3;
+            if constexpr (W4) {
+                y0 = sxm[b] * facc[a][b][0] + bi.x;
+                y1 = sxm[b] * facc[a][b][1] + bi.y;
+                y2 = sxm[b] * facc[a][b][2] + bi.z;
+                y3 = sxm[b] * facc[a][b][3] + bi.w;
+            } else {
+                if constexpr (DEBUG) {
+                    int4 o = make_int4(acc[a][b][0], acc[a][b][1], acc[a][b][2], acc[a][b][3]);
+                    *reinterpret_cast<int4 *>(g.acc_debug + m * g.N + n) = o;
+                }
+                y0 = (float)acc[a][b][0] * sxm[b] * s.x + bi.x;
+                y1 = (float)acc[a][b][1] * sxm[b] * s.y + bi.y;
+                y2 = (float)acc[a][b][2] * sxm[b] * s.z + bi.z;
+                y3 = (float)acc[a][b][3] * sxm[b] * s.w + bi.w;
+            }
+            uint2 o;
+            o.x = pack_bf16x2(y0, y1);
+            o.y = pack_bf16x2(y2, y3);
+            *reinterpret_cast<uint2 *>(g.Y + m * g.ldy + n) = o;
+        }
+    }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool W4>
+hipError_t launch_cfg(const GemmArgs &a, bool debug, hipStream_t st)
+{
+    GemmArgs g = a;
+    g.tiles_m = (int)((g.M + BM - 1) / BM);
+    g.tiles_n = (g.N + BN - 1) / BN;
+    const size_t smem = 2 * (size_t)(BM + BN) * (BK + kPad);
+    const dim3 grid((unsigned)(g.tiles_m * g.tiles_n));
+    static bool attr_done[2] = {false, false};
+    auto kern = debug ? qgemm_kernel<BM, BN, BK, WGM, WGN, W4, true>
+                      : qgemm_kernel<BM, BN, BK, WGM, WGN, W4, false>;
+    if (smem > 64 * 1024 && !attr_done[debug]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_done[debug] = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, st, g);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Tile variants: {BM, BN, BK, waves along m, waves along n}
+//   0: 128 x 128 x 64    1: 128 x 128 x 128    2: 256 x 128 x 64    3: 128 x 256 x 64
+//   4: 256 x 128 x 128   5: 64 x 128 x 128
+int qgemm_num_variants() { return 6; }
+
+hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int64_t M,
+                        const float *bias, uint16_t *Y, int64_t ldy, int32_t *acc_debug,
+                        int variant, hipStream_t st)
+{
+    if (M == 0) return hipSuccess;
+    GemmArgs a;
+    a.Xq = Xq; a.Wc = w.codes; a.sx = sx; a.sw = w.scales; a.bias = bias; a.Y = Y;
+    a.acc_debug = acc_debug; a.M = M; a.ldy = ldy; a.K = w.K; a.N = w.N;
+    a.tiles_m = a.tiles_n = 0;
+    const bool dbg = acc_debug != nullptr;
+    if (w.wbits == 4) {
+        // int4 keeps a second (float) accumulator set: smaller tiles, BK = one scale group
+        if (variant < 0) variant = 1;
+        switch (variant) {
+            case 5: return launch_cfg<64, 128, 128, 1, 4, true>(a, dbg, st);
+            default: return launch_cfg<128, 128, 128, 2, 2, true>(a, dbg, st);
+        }
+    }
+    if (variant < 0) variant = (M >= 8192 || w.N >= 2048) ? 2 : 0;
+    switch (variant) {
+        case 1: return launch_cfg<128, 128, 128, 2, 2, false>(a, dbg, st);
+        case 2: return launch_cfg<256, 128, 64, 2, 2, false>(a, dbg, st);
+        case 3: return launch_cfg<128, 256, 64, 2, 2, false>(a, dbg, st);
+        case 4: return launch_cfg<256, 128, 128, 2, 2, false>(a, dbg, st);
+        case 5: return launch_cfg<64, 128, 128, 1, 4, false>(a, dbg, st);
+        default: return launch_cfg<128, 128, 64, 2, 2, false>(a, dbg, st);
+    }
+}
+
+}  // namespace trdq

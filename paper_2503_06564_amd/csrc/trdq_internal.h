@@ -1,0 +1,50 @@
+// Internal declarations shared by the host API and the HIP kernels of libtrdq.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "trdq.h"
+
+namespace trdq {
+
+constexpr int kBlock = TRDQ_BLOCK;  // rotation block = int4 scale group
+
+// Device-side weight set of one time-step group (H_t(W) of Eq. 10, quantised).
+//   wbits 8: codes = int8  [N, K]   (K contiguous: the transposed canonical matrix)
+//   wbits 4: codes = uint8 [N, K/2]; every 4 bytes hold 8 consecutive k of one output
+//            channel: byte j = code(k0+j) & 0xF | (code(k0+4+j) & 0xF) << 4, so that
+//            (v << 4) & 0xF0F0F0F0 and v & 0xF0F0F0F0 give 16*code as packed int8.
+//   scales : float32 [N] (wbits 8) or [K/128, N] (wbits 4), the true s_w.
+struct Weights {
+    int K = 0, N = 0, wbits = 0;
+    void *codes = nullptr;
+    float *scales = nullptr;
+    int device = 0;
+};
+
+struct Table {
+    int n_steps = 0, n_groups = 0;
+    int32_t *map = nullptr;
+};
+
+// Kernel launchers (defined in the .hip files).  All return hipError_t of the launch.
+hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
+                               int8_t *Xq, float *sx, hipStream_t st);
+
+hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag, float *Wrot,
+                                 float *amax, hipStream_t st);
+hipError_t launch_prepare_quant(const float *Wrot, const float *amax, int K, int N, int wbits,
+                                void *codes, float *scales, hipStream_t st);
+
+int qgemm_num_variants();
+hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int64_t M,
+                        const float *bias, uint16_t *Y, int64_t ldy, int32_t *acc_debug,
+                        int variant, hipStream_t st);
+
+bool fused_supports(int K);
+hipError_t launch_linear_fused(const Weights &w, const uint16_t *X, int64_t M, int64_t ldx,
+                               const float *diag, const float *bias, uint16_t *Y, int64_t ldy,
+                               hipStream_t st);
+
+}  // namespace trdq

@@ -1,0 +1,255 @@
+"""ctypes binding of libtrdq.so: same names as the C ABI (include/trdq.h), marshalling only.
+
+Every step of the path runs in the library's HIP kernels; torch appears only as the owner
+of device memory and streams (tensor.data_ptr(), torch.cuda.current_stream()).  The library
+is loaded on first use and a missing build raises: there is no CPU fallback.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtrdq.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_RANGE, ERR_UNSUPPORTED, ERR_MISMATCH, ERR_ALLOC, ERR_HIP = range(8)
+BLOCK = 128
+
+SYMBOLS = [
+    "trdq_status_str", "trdq_abi_version",
+    "trdq_table_create", "trdq_table_lookup", "trdq_table_sizes", "trdq_table_destroy",
+    "trdq_prepare_weights", "trdq_weights_info", "trdq_weights_export",
+    "trdq_weights_export_packed", "trdq_weights_nbytes", "trdq_weights_destroy",
+    "trdq_rotate_quant", "trdq_qgemm", "trdq_linear_fused",
+    "trdq_layer_create", "trdq_layer_set_group", "trdq_layer_forward", "trdq_layer_weights",
+    "trdq_layer_destroy", "trdq_qgemm_set_variant", "trdq_qgemm_num_variants",
+]
+
+_lib = None
+
+
+class TrdqError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_str(status)} (status {status})")
+
+
+def lib():
+    """The loaded library; raises if libtrdq.so has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2503_06564_amd.build` "
+                "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        i32, i64, p = C.c_int, C.c_int64, C.c_void_p
+        L.trdq_status_str.restype = C.c_char_p
+        L.trdq_status_str.argtypes = [i32]
+        L.trdq_abi_version.restype = i32
+        L.trdq_table_create.argtypes = [i32, i32, p, C.POINTER(p)]
+        L.trdq_table_lookup.argtypes = [p, i32, C.POINTER(i32)]
+        L.trdq_table_sizes.argtypes = [p, C.POINTER(i32), C.POINTER(i32)]
+        L.trdq_table_destroy.argtypes = [p]
+        L.trdq_table_destroy.restype = None
+        L.trdq_prepare_weights.argtypes = [p, i32, i32, p, i32, i32, p, C.POINTER(p)]
+        L.trdq_weights_info.argtypes = [p, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+        L.trdq_weights_export.argtypes = [p, p, p]
+        L.trdq_weights_export_packed.argtypes = [p, p]
+        L.trdq_weights_nbytes.argtypes = [p, C.POINTER(i64)]
+        L.trdq_weights_destroy.argtypes = [p]
+        L.trdq_weights_destroy.restype = None
+        L.trdq_rotate_quant.argtypes = [p, i64, i32, i64, p, i32, p, p, p]
+        L.trdq_qgemm.argtypes = [p, p, p, i64, p, p, i64, p, p]
+        L.trdq_linear_fused.argtypes = [p, i64, i64, p, p, p, p, i64, p]
+        L.trdq_layer_create.argtypes = [p, i32, i32, i32, C.POINTER(p)]
+        L.trdq_layer_set_group.argtypes = [p, i32, p, p, p]
+        L.trdq_layer_forward.argtypes = [p, i32, p, i64, p, p, i32, p, p, p]
+        L.trdq_layer_weights.argtypes = [p, i32, C.POINTER(p)]
+        L.trdq_layer_destroy.argtypes = [p]
+        L.trdq_layer_destroy.restype = None
+        L.trdq_qgemm_set_variant.argtypes = [i32]
+        L.trdq_qgemm_num_variants.restype = i32
+        _lib = L
+    return _lib
+
+
+def status_str(status):
+    return lib().trdq_status_str(int(status)).decode()
+
+
+def _check(status, where):
+    if status != OK:
+        raise TrdqError(status, where)
+
+
+def _ptr(t):
+    """Device (or host) address of a torch tensor / numpy array / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if hasattr(t, "data_ptr"):
+        return t.data_ptr()
+    return t.ctypes.data
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+# ------------------------------------------------------------------ table
+
+class Table:
+    def __init__(self, n_steps, n_groups, mapping=None):
+        import numpy as np
+        h = C.c_void_p()
+        m = None if mapping is None else np.ascontiguousarray(mapping, dtype=np.int32)
+        _check(lib().trdq_table_create(n_steps, n_groups, _ptr(m), C.byref(h)), "trdq_table_create")
+        self.handle = h
+
+    def lookup(self, step):
+        g = C.c_int()
+        _check(lib().trdq_table_lookup(self.handle, step, C.byref(g)), "trdq_table_lookup")
+        return g.value
+
+    def sizes(self):
+        a, b = C.c_int(), C.c_int()
+        _check(lib().trdq_table_sizes(self.handle, C.byref(a), C.byref(b)), "trdq_table_sizes")
+        return a.value, b.value
+
+    def close(self):
+        if self.handle:
+            lib().trdq_table_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# ---------------------------------------------------------------- weights
+
+class Weights:
+    """Handle returned by trdq_prepare_weights (or borrowed from a Layer)."""
+
+    def __init__(self, handle, owned=True):
+        self.handle = handle
+        self.owned = owned
+
+    def info(self):
+        k, n, b = C.c_int(), C.c_int(), C.c_int()
+        _check(lib().trdq_weights_info(self.handle, C.byref(k), C.byref(n), C.byref(b)), "trdq_weights_info")
+        return k.value, n.value, b.value
+
+    def nbytes(self):
+        v = C.c_int64()
+        _check(lib().trdq_weights_nbytes(self.handle, C.byref(v)), "trdq_weights_nbytes")
+        return v.value
+
+    def export(self):
+        """(codes int8 [K, N], scales float32 [N] or [K/128, N]) as numpy arrays."""
+        import numpy as np
+        K, N, wbits = self.info()
+        codes = np.empty((K, N), dtype=np.int8)
+        scales = np.empty((N,) if wbits == 8 else (K // BLOCK, N), dtype=np.float32)
+        _check(lib().trdq_weights_export(self.handle, _ptr(codes), _ptr(scales)), "trdq_weights_export")
+        return codes, scales
+
+    def export_packed(self):
+        import numpy as np
+        K, N, _ = self.info()
+        out = np.empty((K // 2, N), dtype=np.uint8)
+        _check(lib().trdq_weights_export_packed(self.handle, _ptr(out)), "trdq_weights_export_packed")
+        return out
+
+    def close(self):
+        if self.handle and self.owned:
+            lib().trdq_weights_destroy(self.handle)
+        self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def prepare_weights(W, diag=None, block=BLOCK, wbits=8, stream=None):
+    """W: float32 device tensor [K, N]; diag: float32 device tensor [K] or None."""
+    K, N = W.shape
+    h = C.c_void_p()
+    _check(lib().trdq_prepare_weights(_ptr(W), K, N, _ptr(diag), block, wbits, _stream(stream), C.byref(h)),
+           "trdq_prepare_weights")
+    return Weights(h)
+
+
+# ----------------------------------------------------------------- online
+
+def rotate_quant(X, diag, Xq, sx, block=BLOCK, stream=None):
+    """X: bf16 [M, K] (row stride X.stride(0)); Xq: int8 [M, K]; sx: float32 [M]."""
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    _check(lib().trdq_rotate_quant(_ptr(X), M, K, ldx, _ptr(diag), block, _ptr(Xq), _ptr(sx), _stream(stream)),
+           "trdq_rotate_quant")
+
+
+def qgemm(w, Xq, sx, Y, bias=None, acc_debug=None, stream=None):
+    M = Xq.shape[0]
+    ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
+    _check(lib().trdq_qgemm(w.handle, _ptr(Xq), _ptr(sx), M, _ptr(bias), _ptr(Y), ldy, _ptr(acc_debug),
+                            _stream(stream)), "trdq_qgemm")
+
+
+def linear_fused(X, diag, w, Y, bias=None, stream=None):
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
+    _check(lib().trdq_linear_fused(_ptr(X), M, ldx, _ptr(diag), w.handle, _ptr(bias), _ptr(Y), ldy,
+                                   _stream(stream)), "trdq_linear_fused")
+
+
+def qgemm_set_variant(variant):
+    _check(lib().trdq_qgemm_set_variant(variant), "trdq_qgemm_set_variant")
+
+
+def qgemm_num_variants():
+    return lib().trdq_qgemm_num_variants()
+
+
+# ------------------------------------------------------------------ layer
+
+class Layer:
+    def __init__(self, table, K, N, wbits=8):
+        h = C.c_void_p()
+        _check(lib().trdq_layer_create(table.handle, K, N, wbits, C.byref(h)), "trdq_layer_create")
+        self.handle = h
+        self.K, self.N, self.wbits = K, N, wbits
+
+    def set_group(self, g, diag, W, stream=None):
+        _check(lib().trdq_layer_set_group(self.handle, g, _ptr(diag), _ptr(W), _stream(stream)),
+               "trdq_layer_set_group")
+
+    def forward(self, step, X, Y, bias=None, fused=False, Xq_ws=None, sx_ws=None, stream=None):
+        _check(lib().trdq_layer_forward(self.handle, step, _ptr(X), X.shape[0], _ptr(bias), _ptr(Y),
+                                        1 if fused else 0, _ptr(Xq_ws), _ptr(sx_ws), _stream(stream)),
+               "trdq_layer_forward")
+
+    def weights(self, g):
+        h = C.c_void_p()
+        _check(lib().trdq_layer_weights(self.handle, g, C.byref(h)), "trdq_layer_weights")
+        return Weights(h, owned=False)
+
+    def close(self):
+        if self.handle:
+            lib().trdq_layer_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,135 @@
+"""C-ABI checks that need no GPU: the library loads, exports every function the header
+declares, and every argument error is reported before any HIP call is made."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2503_06564_amd import trdq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # a non-null, 64 KiB aligned address that is never dereferenced
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "trdq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(trdq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = trdq.lib()
+    names = header_functions()
+    assert len(names) >= 20
+    for name in names:
+        assert hasattr(L, name), name
+    assert sorted(trdq.SYMBOLS) == names          # the binding covers the whole header
+    assert L.trdq_abi_version() == 100
+    assert trdq.status_str(trdq.OK) == "ok"
+    assert "unsupported" in trdq.status_str(trdq.ERR_UNSUPPORTED)
+
+
+def test_table_default_and_explicit():
+    t = trdq.Table(20, 5)
+    assert [t.lookup(s) for s in range(20)] == [s // 4 for s in range(20)]
+    assert t.sizes() == (20, 5)
+    t2 = trdq.Table(50, 10)
+    assert [t2.lookup(s) for s in range(50)] == [s // 5 for s in range(50)]
+    t3 = trdq.Table(7, 3)
+    sizes = np.bincount([t3.lookup(s) for s in range(7)])
+    assert sizes.max() - sizes.min() <= 1
+    t4 = trdq.Table(4, 2, [1, 0, 1, 0])
+    assert [t4.lookup(s) for s in range(4)] == [1, 0, 1, 0]
+
+
+@pytest.mark.parametrize("args", [(0, 1), (5, 0), (3, 5), (-1, 1)])
+def test_table_bad_sizes(args):
+    with pytest.raises(trdq.TrdqError) as e:
+        trdq.Table(*args)
+    assert e.value.status == trdq.ERR_RANGE
+
+
+def test_table_errors():
+    with pytest.raises(trdq.TrdqError) as e:
+        trdq.Table(4, 2, [0, 1, 2, 0])
+    assert e.value.status == trdq.ERR_RANGE
+    t = trdq.Table(4, 2)
+    for step in (-1, 4):
+        with pytest.raises(trdq.TrdqError) as e:
+            t.lookup(step)
+        assert e.value.status == trdq.ERR_RANGE
+    L = trdq.lib()
+    assert L.trdq_table_create(4, 2, None, None) == trdq.ERR_NULL
+    g = C.c_int()
+    assert L.trdq_table_lookup(None, 0, C.byref(g)) == trdq.ERR_NULL
+    L.trdq_table_destroy(None)                     # no-op
+
+
+def test_prepare_weights_argument_errors():
+    L = trdq.lib()
+    h = C.c_void_p()
+    call = lambda W, K, N, block, wbits, out: L.trdq_prepare_weights(W, K, N, None, block, wbits, None, out)
+    assert call(FAKE, 128, 16, 128, 8, None) == trdq.ERR_NULL
+    assert call(None, 128, 16, 128, 8, C.byref(h)) == trdq.ERR_NULL
+    assert call(FAKE, 128, 16, 64, 8, C.byref(h)) == trdq.ERR_UNSUPPORTED
+    assert call(FAKE, 128, 16, 128, 6, C.byref(h)) == trdq.ERR_UNSUPPORTED
+    assert call(FAKE, 100, 16, 128, 8, C.byref(h)) == trdq.ERR_SHAPE
+    assert call(FAKE, 0, 16, 128, 8, C.byref(h)) == trdq.ERR_SHAPE
+    assert call(FAKE, 128, 0, 128, 8, C.byref(h)) == trdq.ERR_SHAPE
+    assert call(FAKE, 128, 24, 128, 4, C.byref(h)) == trdq.ERR_SHAPE
+    assert h.value is None
+
+
+def test_rotate_quant_argument_errors():
+    L = trdq.lib()
+    rq = L.trdq_rotate_quant
+    assert rq(None, 4, 128, 128, None, 128, FAKE, FAKE, None) == trdq.ERR_NULL
+    assert rq(FAKE, 4, 128, 128, None, 128, None, FAKE, None) == trdq.ERR_NULL
+    assert rq(FAKE, 4, 128, 128, None, 128, FAKE, None, None) == trdq.ERR_NULL
+    assert rq(FAKE, 4, 128, 128, None, 64, FAKE, FAKE, None) == trdq.ERR_UNSUPPORTED
+    assert rq(FAKE, -1, 128, 128, None, 128, FAKE, FAKE, None) == trdq.ERR_SHAPE
+    assert rq(FAKE, 4, 120, 128, None, 128, FAKE, FAKE, None) == trdq.ERR_SHAPE
+    assert rq(FAKE, 4, 256, 128, None, 128, FAKE, FAKE, None) == trdq.ERR_SHAPE      # ldx < K
+    assert rq(FAKE, 4, 128, 132, None, 128, FAKE, FAKE, None) == trdq.ERR_SHAPE      # ldx % 8
+    assert rq(FAKE + 2, 4, 128, 128, None, 128, FAKE, FAKE, None) == trdq.ERR_SHAPE  # alignment
+    assert rq(FAKE, 4, 128, 128, FAKE + 4, 128, FAKE, FAKE, None) == trdq.ERR_SHAPE
+    assert rq(FAKE, 4, 128 * 65, 128 * 65, None, 128, FAKE, FAKE, None) == trdq.ERR_UNSUPPORTED
+    assert rq(FAKE, 0, 128, 128, None, 128, FAKE, FAKE, None) == trdq.OK             # empty input
+
+
+def test_qgemm_and_fused_argument_errors():
+    L = trdq.lib()
+    assert L.trdq_qgemm(None, FAKE, FAKE, 4, None, FAKE, 16, None, None) == trdq.ERR_NULL
+    assert L.trdq_linear_fused(FAKE, 4, 128, None, None, None, FAKE, 16, None) == trdq.ERR_NULL
+    assert L.trdq_qgemm_set_variant(10_000) == trdq.ERR_RANGE
+    assert L.trdq_qgemm_set_variant(-1) == trdq.OK
+    assert L.trdq_qgemm_num_variants() >= 1
+    assert L.trdq_weights_info(None, None, None, None) == trdq.ERR_NULL
+    assert L.trdq_weights_export(None, None, None) == trdq.ERR_NULL
+    assert L.trdq_weights_export_packed(None, FAKE) == trdq.ERR_NULL
+    L.trdq_weights_destroy(None)
+
+
+def test_layer_argument_errors():
+    L = trdq.lib()
+    t = trdq.Table(10, 5)
+    h = C.c_void_p()
+    assert L.trdq_layer_create(None, 128, 16, 8, C.byref(h)) == trdq.ERR_NULL
+    assert L.trdq_layer_create(t.handle, 128, 16, 8, None) == trdq.ERR_NULL
+    assert L.trdq_layer_create(t.handle, 128, 16, 5, C.byref(h)) == trdq.ERR_UNSUPPORTED
+    assert L.trdq_layer_create(t.handle, 130, 16, 8, C.byref(h)) == trdq.ERR_SHAPE
+    layer = trdq.Layer(t, 256, 32, 8)
+    assert L.trdq_layer_set_group(layer.handle, 5, None, FAKE, None) == trdq.ERR_RANGE
+    assert L.trdq_layer_set_group(layer.handle, -1, None, FAKE, None) == trdq.ERR_RANGE
+    assert L.trdq_layer_set_group(layer.handle, 0, None, None, None) == trdq.ERR_NULL
+    fwd = L.trdq_layer_forward
+    assert fwd(layer.handle, 10, FAKE, 4, None, FAKE, 0, FAKE, FAKE, None) == trdq.ERR_RANGE
+    assert fwd(layer.handle, -1, FAKE, 4, None, FAKE, 1, None, None, None) == trdq.ERR_RANGE
+    assert fwd(layer.handle, 3, FAKE, 4, None, FAKE, 1, None, None, None) == trdq.ERR_MISMATCH   # group not set
+    w = C.c_void_p()
+    assert L.trdq_layer_weights(layer.handle, 0, C.byref(w)) == trdq.ERR_MISMATCH
+    assert L.trdq_layer_weights(layer.handle, 7, C.byref(w)) == trdq.ERR_RANGE
+    layer.close()
+    L.trdq_layer_destroy(None)

@@ -1,0 +1,255 @@
+"""GPU parity: every kernel of libtrdq against the CPU oracle, element by element, through the
+C ABI, on seeded inputs that span several tiles and ragged tails."""
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2503_06564_amd import trdq, workloads as wl  # noqa: E402
+from tests import gpu_util as gu  # noqa: E402
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need the MI355X; run them with -m gpu on the GPU box")
+    trdq.lib()
+    yield
+    trdq.qgemm_set_variant(-1)
+
+
+# ------------------------------------------------------------ rotate_quant
+
+RQ_SHAPES = [(1, 128), (5, 256), (37, 1152), (130, 4608), (64, 128 * 13), (33, 128 * 25),
+             (19, 128 * 47), (7, 128 * 64), (1000, 1152)]
+
+
+@pytest.mark.parametrize("M,K", RQ_SHAPES)
+@pytest.mark.parametrize("with_diag", [False, True])
+def test_rotate_quant_matches_oracle(oracle, M, K, with_diag):
+    say(f"rotate_quant M={M} K={K} diag={with_diag}")
+    Xb, _, d, _ = wl.small_case(3, M, K, 16, n_outliers=max(1, K // 144))
+    d = d if with_diag else None
+    Xq, sx = gu.gpu_rotate_quant(Xb, d)
+    want_q, want_s = oracle.rotate_quant(Xb, d)
+    gu.assert_codes_close(Xq.cpu().numpy(), want_q, "Xq")
+    gu.assert_scales_close(sx.cpu().numpy(), want_s, "s_x")
+
+
+def test_rotate_quant_strided_rows_zero_rows_and_empty(oracle):
+    say("rotate_quant strided / zero rows / empty")
+    M, K = 70, 1152
+    Xb, _, d, _ = wl.small_case(4, M, K, 16)
+    Xb[3] = 0
+    Xb[69] = 0x8000                       # a row of negative zeros
+    Xq, sx = gu.gpu_rotate_quant(Xb, d, ldx=K + 64)
+    want_q, want_s = oracle.rotate_quant(Xb, d)
+    gu.assert_codes_close(Xq.cpu().numpy(), want_q, "Xq")
+    gu.assert_scales_close(sx.cpu().numpy(), want_s, "s_x")
+    assert sx[3].item() == 0 and sx[69].item() == 0 and int(Xq[3].abs().max()) == 0
+    # M == 0: valid no-op
+    Xq0, sx0 = gu.gpu_rotate_quant(np.zeros((0, K), np.uint16), d)
+    assert Xq0.shape == (0, K) and sx0.shape == (0,)
+
+
+def test_rotate_quant_closed_forms():
+    say("rotate_quant closed forms")
+    K = 256
+    X = np.zeros((K + 1, K), dtype=np.float32)
+    X[np.arange(K), np.arange(K)] = 3.0           # unit vectors: every code of the block +-127
+    X[K, :128] = 0.5                              # constant block: only coefficient 0 survives
+    Xq, sx = gu.gpu_rotate_quant(wl.f32_to_bf16_bits(X), None)
+    Xq = Xq.cpu().numpy().astype(int)
+    for k in (0, 1, 77, 128, 255):
+        b = k // 128
+        blk = Xq[k, b * 128:(b + 1) * 128]
+        signs = np.array([-1 if bin((k % 128) & j).count("1") & 1 else 1 for j in range(128)])
+        assert np.array_equal(blk, 127 * signs)
+        assert np.all(np.delete(Xq[k].reshape(2, 128), b, axis=0) == 0)
+    assert Xq[K, 0] == 127 and np.all(Xq[K, 1:] == 0)
+    assert np.allclose(sx.cpu().numpy()[:K], 3.0 / np.sqrt(128) / 127, rtol=1e-6)
+
+
+# --------------------------------------------------------- prepare_weights
+
+@pytest.mark.parametrize("K,N", [(128, 16), (256, 48), (1152, 1152), (4608, 80), (384, 208)])
+@pytest.mark.parametrize("wbits", [8, 4])
+def test_prepare_weights_matches_oracle(oracle, K, N, wbits):
+    say(f"prepare_weights K={K} N={N} wbits={wbits}")
+    _, W, d, _ = wl.small_case(5, 4, K, N)
+    W[:, N // 2] = 0.0                               # a dead output channel
+    w = trdq.prepare_weights(gu.f32_to_dev(W), gu.f32_to_dev(d), wbits=wbits)
+    assert w.info() == (K, N, wbits)
+    codes, scales = w.export()
+    want_q, want_s = oracle.prepare_weights(W, d, 128, wbits)
+    gu.assert_codes_close(codes, want_q, "Wq")
+    gu.assert_scales_close(scales, want_s, "s_w")
+    assert np.all(codes[:, N // 2] == 0) and np.all(scales[..., N // 2] == 0)
+    assert np.abs(codes).max() == (127 if wbits == 8 else 7)
+    if wbits == 4:
+        assert np.array_equal(w.export_packed(), oracle.pack_int4(codes))
+        assert w.nbytes() == K * N // 2 + (K // 128) * N * 4
+    else:
+        with pytest.raises(trdq.TrdqError) as e:
+            w.export_packed()
+        assert e.value.status == trdq.ERR_MISMATCH
+    w.close()
+
+
+def test_prepare_weights_without_diag(oracle):
+    _, W, _, _ = wl.small_case(6, 4, 256, 32)
+    w = trdq.prepare_weights(gu.f32_to_dev(W), None, wbits=8)
+    codes, scales = w.export()
+    want_q, want_s = oracle.prepare_weights(W, None, 128, 8)
+    gu.assert_codes_close(codes, want_q, "Wq")
+    gu.assert_scales_close(scales, want_s, "s_w")
+
+
+# ------------------------------------------------------------------ qgemm
+
+def _linear_case(oracle, seed, M, K, N, wbits, variant, with_bias=True, ldy=None):
+    """Runs the unfused GPU path and checks every stage against the oracle."""
+    Xb, W, d, bias = wl.small_case(seed, M, K, N, n_outliers=max(1, K // 144))
+    bias = bias if with_bias else None
+    trdq.qgemm_set_variant(variant)
+    w = trdq.prepare_weights(gu.f32_to_dev(W), gu.f32_to_dev(d), wbits=wbits)
+    Xq, sx = gu.gpu_rotate_quant(Xb, d)
+    Y, acc = gu.gpu_qgemm(w, Xq, sx, bias, N, debug=True, ldy=ldy)
+    # (ii) accumulators bit-exact given the GPU's own codes
+    Xq_h, (Wq_h, sw_h) = Xq.cpu().numpy(), w.export()
+    group = None if wbits == 8 else 128
+    want_acc = oracle.acc_exact_blas(Xq_h, Wq_h, group) if M * K * N > 2e8 else oracle.igemm(Xq_h, Wq_h, group)
+    assert np.array_equal(acc.cpu().numpy(), want_acc), "int32 accumulators differ"
+    # epilogue on the same codes and scales
+    y_same = oracle.dequant(want_acc, sx.cpu().numpy(), sw_h, bias)
+    gu.assert_y_close(gu.bf16_to_host(Y), y_same, "Y (same codes)")
+    # (iii) against the oracle's own end-to-end quantised output
+    ref = oracle.linear(Xb, W, d, bias, wbits=wbits, exact_blas=True)
+    worst = gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], "Y (oracle end to end)")
+    # without the debug output the result is the same
+    Y2, _ = gu.gpu_qgemm(w, Xq, sx, bias, N, debug=False, ldy=ldy)
+    assert torch.equal(Y2, Y)
+    w.close()
+    return worst
+
+
+GEMM_SHAPES = [(1, 128, 16), (17, 256, 144), (128, 1152, 128), (257, 1152, 1152), (300, 4608, 272),
+               (513, 384, 400)]
+
+
+@pytest.mark.parametrize("M,K,N", GEMM_SHAPES)
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5])
+def test_qgemm_w8_all_variants(oracle, M, K, N, variant):
+    say(f"qgemm W8 M={M} K={K} N={N} variant={variant}")
+    _linear_case(oracle, 7, M, K, N, 8, variant)
+
+
+@pytest.mark.parametrize("M,K,N", GEMM_SHAPES)
+@pytest.mark.parametrize("variant", [1, 5])
+def test_qgemm_w4_all_variants(oracle, M, K, N, variant):
+    say(f"qgemm W4 M={M} K={K} N={N} variant={variant}")
+    _linear_case(oracle, 8, M, K, N, 4, variant)
+
+
+@pytest.mark.parametrize("wbits", [8, 4])
+def test_qgemm_no_bias_strided_output_and_empty(oracle, wbits):
+    say(f"qgemm no bias / strided Y / empty, wbits={wbits}")
+    _linear_case(oracle, 9, 70, 256, 48, wbits, -1, with_bias=False, ldy=64)
+    _, W, d, _ = wl.small_case(9, 4, 256, 48)
+    w = trdq.prepare_weights(gu.f32_to_dev(W), gu.f32_to_dev(d), wbits=wbits)
+    Xq = torch.zeros((0, 256), dtype=torch.int8, device="cuda")
+    sx = torch.zeros((0,), dtype=torch.float32, device="cuda")
+    Y, _ = gu.gpu_qgemm(w, Xq, sx, None, 48, debug=False)
+    assert Y.shape == (0, 48)
+
+
+def test_qgemm_extreme_accumulators(oracle):
+    """All codes +-127 over K = 4608: the largest accumulator magnitude the path can see."""
+    say("qgemm extreme accumulators")
+    M, K, N = 16, 4608, 16
+    # a column that is sqrt(128) at the head of every block rotates to all ones: codes all +-127
+    W = np.zeros((K, N), dtype=np.float32)
+    W[::128, :] = np.float32(np.sqrt(128.0))
+    W[:, 1::2] *= -1.0
+    w = trdq.prepare_weights(gu.f32_to_dev(W), None, wbits=8)
+    Wq, _ = w.export()
+    assert np.all(np.abs(Wq) == 127)
+    Xq = torch.full((M, K), 127, dtype=torch.int8, device="cuda")
+    Xq[1::2] = -127
+    sx = torch.ones((M,), dtype=torch.float32, device="cuda")
+    Y, acc = gu.gpu_qgemm(w, Xq, sx, None, N, debug=True)
+    want = oracle.igemm(Xq.cpu().numpy(), Wq)
+    assert np.array_equal(acc.cpu().numpy(), want)
+    assert np.abs(want).max() == 127 * 127 * K
+
+
+# ------------------------------------------------------------------ fused
+
+@pytest.mark.parametrize("M,K,N", [(1, 128, 16), (70, 1152, 272), (257, 1152, 1152), (130, 2304, 144),
+                                   (100, 4608, 400), (65, 1536, 128), (33, 128 * 25, 48)])
+@pytest.mark.parametrize("wbits", [8, 4])
+def test_fused_matches_unfused_and_oracle(oracle, M, K, N, wbits):
+    say(f"fused M={M} K={K} N={N} wbits={wbits}")
+    Xb, W, d, bias = wl.small_case(10, M, K, N, n_outliers=max(1, K // 144))
+    trdq.qgemm_set_variant(-1)
+    w = trdq.prepare_weights(gu.f32_to_dev(W), gu.f32_to_dev(d), wbits=wbits)
+    Xq, sx = gu.gpu_rotate_quant(Xb, d)
+    Y_unfused, _ = gu.gpu_qgemm(w, Xq, sx, bias, N, debug=False)
+    X = gu.bf16_to_dev(Xb)
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    trdq.linear_fused(X, gu.f32_to_dev(d), w, Y, bias=gu.f32_to_dev(bias))
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y_unfused), "fused and unfused paths disagree"
+    ref = oracle.linear(Xb, W, d, bias, wbits=wbits, exact_blas=True)
+    gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], "Y fused")
+    w.close()
+
+
+def test_fused_rejects_wide_k():
+    _, W, _, _ = wl.small_case(1, 1, 128 * 49, 16)
+    w = trdq.prepare_weights(gu.f32_to_dev(W), None, wbits=8)
+    X = torch.zeros((4, 128 * 49), dtype=torch.bfloat16, device="cuda")
+    Y = torch.zeros((4, 16), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(trdq.TrdqError) as e:
+        trdq.linear_fused(X, None, w, Y)
+    assert e.value.status == trdq.ERR_UNSUPPORTED
+
+
+# ------------------------------------------------------------------ layer
+
+@pytest.mark.parametrize("wbits,fused", [(8, False), (8, True), (4, False), (4, True)])
+def test_layer_time_step_groups(oracle, wbits, fused):
+    """20 steps -> 5 groups: each step must use its own group's diagonal and weights (Eq. 10)."""
+    say(f"layer wbits={wbits} fused={fused}")
+    M, K, N = 48, 256, 64
+    table = trdq.Table(20, 5)
+    layer = trdq.Layer(table, K, N, wbits)
+    Xb, W, _, bias = wl.small_case(12, M, K, N)
+    diags = [np.random.default_rng(100 + g).lognormal(0, 0.3, K).astype(np.float32) for g in range(5)]
+    for g in (0, 2, 4):
+        layer.set_group(g, gu.f32_to_dev(diags[g]), gu.f32_to_dev(W))
+    X = gu.bf16_to_dev(Xb)
+    Xq_ws = torch.empty((M, K), dtype=torch.int8, device="cuda")
+    sx_ws = torch.empty((M,), dtype=torch.float32, device="cuda")
+    for step in (0, 3, 9, 19):
+        g = table.lookup(step)
+        Y = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+        layer.forward(step, X, Y, bias=gu.f32_to_dev(bias), fused=fused, Xq_ws=Xq_ws, sx_ws=sx_ws)
+        torch.cuda.synchronize()
+        ref = oracle.linear(Xb, W, diags[g], bias, wbits=wbits)
+        gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], f"layer step {step}")
+        codes, _ = layer.weights(g).export()
+        gu.assert_codes_close(codes, ref["Wq"], "layer Wq")
+    with pytest.raises(trdq.TrdqError) as e:       # group 1 was never set
+        layer.forward(5, X, Y, fused=fused, Xq_ws=Xq_ws, sx_ws=sx_ws)
+    assert e.value.status == trdq.ERR_MISMATCH
+    layer.close()
