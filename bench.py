@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Benchmark of the rotated W8A8 linear path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input: for every
+linear of a DiT-XL/2-shaped block (qkv, proj, fc1, fc2) at 4096 tokens, look up the sampling
+step's group, rotate + quantise the bf16 activations (trdq_rotate_quant) and run the int8
+product with the dequantising epilogue (trdq_qgemm) against that group's prepared weights.
+Inputs, diagonals and prepared weights are resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-job int8 TOP/s (2*M*K*N summed over the four linears per step,
+divided by wall time), plus `roofline` for the dominant kernel (qgemm, int8 MFMA bound; its
+launch durations are measured with events on the launch stream inside the timed region) and
+`cpu_baseline` (the CPU oracle timed on a bounded sample of the same workload).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8, published
+HBM_PEAK_GBS = 8000.0             # MI355X HBM3E, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="workload config id (1 = the metric's)")
+    ap.add_argument("--fused", action="store_true", help="use the fused kernel instead of rotate_quant + qgemm")
+    ap.add_argument("--no-events", action="store_true", help="no per-kernel events in the timed region")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU work budget of the oracle's timed sample")
+    ap.add_argument("--variant", type=int, default=-1, help="qgemm tile variant override")
+    ap.add_argument("--groups", type=int, default=0, help="limit the number of groups prepared (0 = all)")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, wl, budget_s):
+    """The oracle, as it stands, on the same workload: whole groups (all tokens of every linear
+    of the block) until about `budget_s` seconds of CPU work are spent."""
+    from oracle import trdq_oracle as o
+    o.lib()
+    group = None if cfg.wbits[0] == 8 else 128
+    ops, tokens, spent, groups = 0, 0, 0.0, 0
+    for g in range(cfg.n_groups):
+        step = next(s for s in range(cfg.n_steps) if wl.step_to_group(cfg, s) == g)
+        prepared = {}
+        for kind in cfg.kinds:                       # untimed: inputs and the offline weight side
+            d = wl.make_diag(cfg, kind, g)
+            prepared[kind] = (wl.make_x(cfg, kind, step), d, wl.make_bias(cfg, kind),
+                              o.prepare_weights(wl.make_w(cfg, kind), d, 128, cfg.wbits[0]))
+        t0 = time.perf_counter()
+        for kind in cfg.kinds:
+            Xb, d, bias, (Wq, sw) = prepared[kind]
+            Xq, sx = o.rotate_quant(Xb, d)
+            acc = o.igemm(Xq, Wq, group)
+            o.dequant(acc, sx, sw, bias)
+            K, N = wl.LAYER_SHAPES[kind]
+            ops += 2 * cfg.M * K * N
+        spent += time.perf_counter() - t0
+        tokens += cfg.M
+        groups += 1
+        if spent >= budget_s:
+            break
+    return {"value": ops / spent / 1e12, "unit": "TOP/s", "cores": o.threads(), "kind": "oracle",
+            "tokens_per_s": tokens / spent,
+            "sample": f"{groups} of {cfg.n_groups} groups x {cfg.M} tokens x {len(cfg.kinds)} linears "
+                      f"(rotate+quantise, int32 product, dequant; weights prepared beforehand, untimed), "
+                      f"{spent:.1f} s of CPU work"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (tokens are independent rows; more GPUs would "
+              "shard them with replicated weights) -- run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2503_06564_amd import trdq, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    trdq.lib()
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.config]
+    wbits = cfg.wbits[0]
+    M = cfg.M
+    n_groups = cfg.n_groups if args.groups <= 0 else min(args.groups, cfg.n_groups)
+    trdq.qgemm_set_variant(args.variant)
+
+    table = trdq.Table(cfg.n_steps, cfg.n_groups)
+    stream = torch.cuda.current_stream()
+
+    # ---- resident state: per kind and group, activations, diagonal, prepared weights ----------
+    X, D, Wh, B, Y, Xq, SX = {}, {}, {}, {}, {}, {}, {}
+    for kind in cfg.kinds:
+        K, N = wl.LAYER_SHAPES[kind]
+        Wd = torch.from_numpy(wl.make_w(cfg, kind)).to(dev)
+        B[kind] = torch.from_numpy(wl.make_bias(cfg, kind)).to(dev)
+        Y[kind] = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        Xq[kind] = torch.empty((M, K), dtype=torch.int8, device=dev)
+        SX[kind] = torch.empty((M,), dtype=torch.float32, device=dev)
+        for g in range(n_groups):
+            step_of_g = next(s for s in range(cfg.n_steps) if wl.step_to_group(cfg, s) == g)
+            xb = wl.make_x(cfg, kind, step_of_g)
+            X[kind, g] = torch.from_numpy(xb.view(np.int16)).to(dev).view(torch.bfloat16)
+            D[kind, g] = torch.from_numpy(wl.make_diag(cfg, kind, g)).to(dev)
+            Wh[kind, g] = trdq.prepare_weights(Wd, D[kind, g], wbits=wbits)
+        del Wd
+    torch.cuda.synchronize()
+
+    ops_step = sum(2 * M * K * N for K, N in (wl.LAYER_SHAPES[k] for k in cfg.kinds))
+    gemm_ops = {k: 2 * M * wl.LAYER_SHAPES[k][0] * wl.LAYER_SHAPES[k][1] for k in cfg.kinds}
+    rq_bytes = {k: M * (3 * wl.LAYER_SHAPES[k][0] + 4) for k in cfg.kinds}
+
+    use_events = not args.no_events
+    ev = []     # (name, kind, start, end)
+
+    def run_step(step, record):
+        g = table.lookup(step % cfg.n_steps) % n_groups
+        for kind in cfg.kinds:
+            if args.fused:
+                if record:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                trdq.linear_fused(X[kind, g], D[kind, g], Wh[kind, g], Y[kind], bias=B[kind], stream=stream)
+                if record:
+                    e1.record(stream)
+                    ev.append(("fused", kind, e0, e1))
+                continue
+            if record:
+                e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+                e0.record(stream)
+            trdq.rotate_quant(X[kind, g], D[kind, g], Xq[kind], SX[kind], stream=stream)
+            if record:
+                e1.record(stream)
+            trdq.qgemm(Wh[kind, g], Xq[kind], SX[kind], Y[kind], bias=B[kind], stream=stream)
+            if record:
+                e2.record(stream)
+                ev.append(("rotate_quant", kind, e0, e1))
+                ev.append(("qgemm", kind, e1, e2))
+
+    for s in range(args.warmup):
+        run_step(s, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        run_step(s, use_events)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms_per_step = dt / args.steps * 1e3
+    value = ops_step * args.steps / dt / 1e12
+    out = {
+        "metric": "int8 TOP/s of the rotated W8A8 linears of one DiT-XL/2-shaped block "
+                  "(rotate_quant + qgemm per linear, 2*M*K*N ops)",
+        "value": value, "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8" if wbits == 8 else "int8xint4", "data": "synthetic",
+        "tokens_per_s": M * args.steps / dt,
+        "config": {"workload": cfg.name, "tokens": M, "layers": list(cfg.kinds), "groups": n_groups,
+                   "path": "fused" if args.fused else "rotate_quant+qgemm", "wbits": wbits},
+    }
+
+    if use_events and ev:
+        per = {}
+        for name, kind, a, b in ev:
+            per.setdefault((name, kind), []).append(a.elapsed_time(b) * 1e-3)
+        kern = {}
+        for (name, kind), ts in per.items():
+            avg = sum(ts) / len(ts)
+            entry = {"avg_us": avg * 1e6, "launches": len(ts)}
+            if name in ("qgemm", "fused"):
+                entry["tops"] = gemm_ops[kind] / avg / 1e12
+                entry["frac_int8_peak"] = entry["tops"] / INT8_MFMA_PEAK_TOPS
+            if name == "rotate_quant":
+                entry["gbs"] = rq_bytes[kind] / avg / 1e9
+                entry["frac_hbm_peak"] = entry["gbs"] / HBM_PEAK_GBS
+            kern[f"{name}:{kind}"] = entry
+        out["kernels"] = kern
+        dom = "fused" if args.fused else "qgemm"
+        tot_t = sum(sum(ts) for (name, _), ts in per.items() if name == dom)
+        n_launch = sum(len(ts) for (name, _), ts in per.items() if name == dom)
+        tot_ops = sum(gemm_ops[kind] * len(ts) for (name, kind), ts in per.items() if name == dom)
+        achieved = tot_ops / tot_t / 1e12
+        out["roofline"] = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS,
+                           "unit": "TOP/s", "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                           "avg_launch_us": tot_t / n_launch * 1e6, "launches": n_launch,
+                           "ops_per_launch": tot_ops / n_launch}
+        if not args.fused:
+            rq_t = sum(sum(ts) for (name, _), ts in per.items() if name == "rotate_quant")
+            rq_b = sum(rq_bytes[kind] * len(ts) for (name, kind), ts in per.items() if name == "rotate_quant")
+            out["roofline_rotate_quant"] = {"bound": "hbm", "achieved": rq_b / rq_t / 1e9, "peak": HBM_PEAK_GBS,
+                                            "unit": "GB/s", "frac": rq_b / rq_t / 1e9 / HBM_PEAK_GBS,
+                                            "traffic": None}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, wl, args.cpu_seconds)
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -10,17 +10,22 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtrdq.so")
 
-SOURCES = ["api.cpp", "rotate_quant.hip", "prepare_weights.hip", "qgemm.hip", "fused.hip"]
+SOURCES = ["api.cpp", "rotate_quant.hip", "prepare_weights.hip", "qgemm.hip", "qgemm_dma.hip", "fused.hip"]
 
 # packed-FP32 instructions are switched off for every device compile
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function", "-I", CSRC, "-I", INCLUDE]
+         "-Wall", "-Wno-unused-function", "-Wno-inline-asm", "-I", CSRC, "-I", INCLUDE]
+
+
+# per-source extra flags: keep the matrix-instruction accumulators of the pipelined product kernel
+# in ordinary VGPRs (no accumulator-register copies around the loop)
+SOURCE_FLAGS = {"qgemm_dma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _compile(src, extra):
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = ["hipcc", *FLAGS, *SOURCE_FLAGS.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     out = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                     if "packed-fp32-ops" not in l and l.strip())

@@ -13,38 +13,15 @@
 // int4 weights are widened to int8 while they are copied into LDS, as 16 * code (the nibble
 // moved to the top of the byte), so the main loop is the same; at every 128-channel group
 // boundary the int32 partial sums are folded into float accumulators with the group's scale.
-#include "device_utils.h"
-#include "trdq_internal.h"
+#include "gemm_common.h"
 
 namespace trdq {
 
+using namespace gemm;
+
 namespace {
 
-constexpr int kThreads = 256;
 constexpr int kPad = 16;  // bytes of padding per LDS row
-
-struct GemmArgs {
-    const int8_t *Xq;      // [M, K]
-    const void *Wc;        // codes, see Weights
-    const float *sx;       // [M]
-    const float *sw;       // [N] or [K/128, N]
-    const float *bias;     // [N] or null
-    uint16_t *Y;           // [M, ldy]
-    int32_t *acc_debug;    // null, [M, N] or [K/128, M, N]
-    int64_t M, ldy;
-    int K, N;
-    int tiles_m, tiles_n;
-};
-
-// Workgroups are handed to the 8 accelerator dies round-robin by their linear id; give each
-// die a contiguous run of tiles (a few token panels times all channel tiles) so that the
-// panels it re-reads stay in its own L2.
-__device__ __forceinline__ int xcd_remap(int bid, int ntiles)
-{
-    const int q = ntiles >> 3, r = ntiles & 7;
-    const int xcd = bid & 7, idx = bid >> 3;
-    return xcd * q + (xcd < r ? xcd : r) + idx;
-}
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool W4, bool DEBUG>
 __global__ __launch_bounds__(kThreads) void qgemm_kernel(GemmArgs g)
@@ -273,10 +250,11 @@ hipError_t launch_cfg(const GemmArgs &a, bool debug, hipStream_t st)
 
 }  // namespace
 
-// Tile variants: {BM, BN, BK, waves along m, waves along n}
-//   0: 128 x 128 x 64    1: 128 x 128 x 128    2: 256 x 128 x 64    3: 128 x 256 x 64
-//   4: 256 x 128 x 128   5: 64 x 128 x 128
-int qgemm_num_variants() { return 6; }
+// Tile variants.  0-5: register-staged double buffer {BM, BN, BK} (also the int4 path):
+//   0: 128x128x64   1: 128x128x128   2: 256x128x64   3: 128x256x64   4: 256x128x128   5: 64x128x128
+// 6 and up: the direct-to-LDS int8 kernels of qgemm_dma.hip (variant - 6 indexes its table).
+constexpr int kRegVariants = 6;
+int qgemm_num_variants() { return kRegVariants + dma_num_variants(); }
 
 hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int64_t M,
                         const float *bias, uint16_t *Y, int64_t ldy, int32_t *acc_debug,
@@ -287,23 +265,26 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int
     a.Xq = Xq; a.Wc = w.codes; a.sx = sx; a.sw = w.scales; a.bias = bias; a.Y = Y;
     a.acc_debug = acc_debug; a.M = M; a.ldy = ldy; a.K = w.K; a.N = w.N;
     a.tiles_m = a.tiles_n = 0;
+    a.remap = 1;
     const bool dbg = acc_debug != nullptr;
     if (w.wbits == 4) {
         // int4 keeps a second (float) accumulator set: smaller tiles, BK = one scale group
-        if (variant < 0) variant = 1;
         switch (variant) {
             case 5: return launch_cfg<64, 128, 128, 1, 4, true>(a, dbg, st);
             default: return launch_cfg<128, 128, 128, 2, 2, true>(a, dbg, st);
         }
     }
-    if (variant < 0) variant = (M >= 8192 || w.N >= 2048) ? 2 : 0;
+    // built-in choice: the software-pipelined 128x128 kernel, two workgroups per compute unit
+    // (it hands ragged shapes to the ring kernel itself)
+    if (variant < 0) variant = kRegVariants + 9;
     switch (variant) {
+        case 0: return launch_cfg<128, 128, 64, 2, 2, false>(a, dbg, st);
         case 1: return launch_cfg<128, 128, 128, 2, 2, false>(a, dbg, st);
         case 2: return launch_cfg<256, 128, 64, 2, 2, false>(a, dbg, st);
         case 3: return launch_cfg<128, 256, 64, 2, 2, false>(a, dbg, st);
         case 4: return launch_cfg<256, 128, 128, 2, 2, false>(a, dbg, st);
         case 5: return launch_cfg<64, 128, 128, 1, 4, false>(a, dbg, st);
-        default: return launch_cfg<128, 128, 64, 2, 2, false>(a, dbg, st);
+        default: return launch_qgemm8_dma(a, dbg, variant - kRegVariants, st);
     }
 }
 

@@ -1,0 +1,422 @@
+// Direct-to-LDS int8 x int8 product kernels for gfx950 (see qgemm.hip for the operand roles).
+//
+// Tiles travel global -> LDS with global_load_lds_dwordx4: a wave-wide copy moves 64 x 16
+// bytes into 1 KB of consecutive LDS, and which global 16-byte chunk a lane fetches is ours
+// to choose, so a tile is stored row-major with the chunk index XOR-swizzled by the row
+// (conflict-free 16-byte fragment reads, no padding).  The copies are issued from inline
+// assembly and tracked by hand: a wave waits with s_waitcnt vmcnt(n) until all but its
+// youngest copies have landed, then the workgroup barrier publishes the tile.
+//
+// Two kernels: `ring` (simple: one barrier per k-tile, fragments read right before use) and
+// `pipe` (fragments double-buffered in registers so LDS reads of the next k-step overlap the
+// matrix instructions of the current one; one workgroup of four waves per compute unit).
+#include <cstdlib>
+
+#include "gemm_common.h"
+
+namespace trdq {
+namespace gemm {
+
+namespace {
+
+// row -> XOR mask of the 16-byte chunk index, a function of (row mod 16) only so that the
+// fragment offsets of different 16-row tiles differ by a constant
+template <int BK>
+__device__ __forceinline__ int chunk_swizzle(int row)
+{
+    const int r = row & 15;
+    if constexpr (BK == 64) return ((r >> 1) ^ (r >> 3)) & 3;
+    else return (r ^ (r >> 3)) & 7;
+}
+
+__device__ __forceinline__ void dma_1k(uint32_t voff, const void *sbase, uint32_t lds_addr)
+{
+    // one wait state between the scalar write of M0 and the copy that reads it
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+// Dequantising epilogue for int8 weights.  The lane holds, for every 16x16 tile (a, b), the
+// accumulators of channels n_lane + 16a .. +3 of token m_lane + 16b:
+//   y = float(acc) * s_x[m] * s_w[n] + bias[n]  -> bf16, one 8-byte store per tile.
+// FULL: the workgroup tile lies entirely inside the matrix (no bounds checks).
+template <int TN, int TM, bool DEBUG, bool FULL>
+__device__ __forceinline__ void epilogue_w8(const v4i (&acc)[TN][TM], const GemmArgs &g,
+                                            int64_t m_lane, int n_lane)
+{
+    float sxm[TM];
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+        const int64_t m = m_lane + b * 16;
+        sxm[b] = (FULL || m < g.M) ? g.sx[m] : 0.0f;
+    }
+    const bool has_bias = g.bias != nullptr;
+#pragma unroll
+    for (int a = 0; a < TN; ++a) {
+        const int n = n_lane + a * 16;
+        const bool n_ok = FULL || n < g.N;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f), bi = s;
+        if (n_ok) {
+            s = *reinterpret_cast<const float4 *>(g.sw + n);
+            if (has_bias) bi = *reinterpret_cast<const float4 *>(g.bias + n);
+        }
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+            const int64_t m = m_lane + b * 16;
+            const float y0 = (float)acc[a][b][0] * sxm[b] * s.x + bi.x;
+            const float y1 = (float)acc[a][b][1] * sxm[b] * s.y + bi.y;
+            const float y2 = (float)acc[a][b][2] * sxm[b] * s.z + bi.z;
+            const float y3 = (float)acc[a][b][3] * sxm[b] * s.w + bi.w;
+            uint2 o;
+            o.x = pack_bf16x2(y0, y1);
+            o.y = pack_bf16x2(y2, y3);
+            if (FULL || (n_ok && m < g.M)) {
+                if constexpr (DEBUG) {
+                    int4 d = make_int4(acc[a][b][0], acc[a][b][1], acc[a][b][2], acc[a][b][3]);
+                    *reinterpret_cast<int4 *>(g.acc_debug + m * g.N + n) = d;
+                }
+                *reinterpret_cast<uint2 *>(g.Y + m * g.ldy + n) = o;
+            }
+        }
+    }
+}
+
+// Conditional forms whose branch lives inside the assembly block, so that the caller's loop
+// body stays one basic block for the compiler (`on` / `steady` are wave-uniform).
+__device__ __forceinline__ void dma_1k_if(int on, uint32_t voff, const void *sbase, uint32_t lds_addr)
+{
+    asm volatile("s_cmp_eq_u32 %3, 0\n\ts_cbranch_scc1 .Lskip%=\n\t"
+                 "s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n"
+                 ".Lskip%=:"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr), "s"(__builtin_amdgcn_readfirstlane(on))
+                 : "memory", "scc");
+}
+
+// waits for vmcnt(N) when `steady` is set, for vmcnt(0) otherwise
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_or_zero(int steady)
+{
+    asm volatile("s_cmp_eq_u32 %0, 0\n\ts_cbranch_scc1 .Lzero%=\n\t"
+                 "s_waitcnt vmcnt(%1)\n\ts_branch .Ldone%=\n"
+                 ".Lzero%=:\n\ts_waitcnt vmcnt(0)\n"
+                 ".Ldone%=:"
+                 :: "s"(__builtin_amdgcn_readfirstlane(steady)), "n"(N) : "memory", "scc");
+}
+
+template <int BM, int BN, int BK, int NS, int WGM, int WGN, bool DEBUG>
+__global__ __launch_bounds__(kThreads) void qgemm8_ring_kernel(GemmArgs g)
+{
+    static_assert(WGM * WGN == 4, "four waves per workgroup");
+    static_assert(BK == 64 || BK == 128, "k-tile of 64 or 128 bytes");
+    static_assert(NS >= 3, "at least three stages");
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int TM = WM / 16, TN = WN / 16;
+    constexpr int CPR = BK / 16;                      // 16-byte chunks per row
+    constexpr int XBYTES = BM * BK, WBYTES = BN * BK, STAGE = XBYTES + WBYTES;
+    constexpr int PX = XBYTES / 4096, PW = WBYTES / 4096;   // 1 KB copies per wave and tile
+    constexpr int P = PX + PW;
+    static_assert(PX >= 1 && PW >= 1 && (NS - 2) * P < 64, "copy count per wave out of range");
+    constexpr int KH = BK / 64;                       // matrix-instruction k-steps per tile
+
+    extern __shared__ __align__(16) int8_t smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t *)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int l16 = lane & 15, lg = lane >> 4;
+
+    const int tile = xcd_remap(blockIdx.x, g.tiles_m * g.tiles_n, g.remap);
+    const int tm_idx = tile / g.tiles_n, tn_idx = tile % g.tiles_n;
+    const int64_t m0 = (int64_t)tm_idx * BM;
+    const int n0 = tn_idx * BN;
+    const int K = g.K;
+
+    // ---- copy plan: this lane's source offsets, relative to the tile's first row --------------
+    uint32_t voffx[PX], voffw[PW];
+#pragma unroll
+    for (int i = 0; i < PX; ++i) {
+        const int slot = (wave * PX + i) * 64 + lane;
+        const int row = slot / CPR, c = (slot % CPR) ^ chunk_swizzle<BK>(row);
+        int64_t m = m0 + row;
+        if (m >= g.M) m = g.M - 1;                    // rows past M are loaded but never stored
+        voffx[i] = (uint32_t)((m - m0) * K + c * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < PW; ++i) {
+        const int slot = (wave * PW + i) * 64 + lane;
+        const int row = slot / CPR, c = (slot % CPR) ^ chunk_swizzle<BK>(row);
+        int n = n0 + row;
+        if (n >= g.N) n = g.N - 1;
+        voffw[i] = (uint32_t)((n - n0) * K + c * 16);
+    }
+    const int8_t *xbase = g.Xq + m0 * K;
+    const int8_t *wbase = static_cast<const int8_t *>(g.Wc) + (size_t)n0 * K;
+
+    auto issue = [&](int kt, int st) {
+        const uint32_t sbase = lds0 + st * STAGE;
+#pragma unroll
+        for (int i = 0; i < PX; ++i) dma_1k(voffx[i], xbase + kt * BK, sbase + (wave * PX + i) * 1024);
+#pragma unroll
+        for (int i = 0; i < PW; ++i) dma_1k(voffw[i], wbase + kt * BK, sbase + XBYTES + (wave * PW + i) * 1024);
+    };
+
+    // ---- fragment read offsets inside a stage ----------------------------------------------------
+    int xoff[KH], woff[KH];
+#pragma unroll
+    for (int h = 0; h < KH; ++h) {
+        const int pc = (4 * h + lg) ^ chunk_swizzle<BK>(l16);
+        xoff[h] = ((wm * WM + l16) * CPR + pc) * 16;
+        woff[h] = XBYTES + ((wn * WN + l16) * CPR + pc) * 16;
+    }
+
+    v4i acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b) acc[a][b] = v4i{0, 0, 0, 0};
+
+    const int KT = K / BK;
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t)
+        if (t < KT) issue(t, t);
+
+    int st = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+        if (kt + NS - 1 <= KT) wait_vmcnt<(NS - 2) * P>();
+        else wait_vmcnt<0>();
+        __syncthreads();
+        if (kt + NS - 1 < KT) issue(kt + NS - 1, st == 0 ? NS - 1 : st - 1);
+
+        const int8_t *stage = smem + st * STAGE;
+#pragma unroll
+        for (int h = 0; h < KH; ++h) {
+            v4i af[TN], bf[TM];
+#pragma unroll
+            for (int a = 0; a < TN; ++a) af[a] = *reinterpret_cast<const v4i *>(stage + woff[h] + a * 16 * BK);
+#pragma unroll
+            for (int b = 0; b < TM; ++b) bf[b] = *reinterpret_cast<const v4i *>(stage + xoff[h] + b * 16 * BK);
+#pragma unroll
+            for (int a = 0; a < TN; ++a)
+#pragma unroll
+                for (int b = 0; b < TM; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[a], bf[b], acc[a][b], 0, 0, 0);
+        }
+        st = (st + 1 == NS) ? 0 : st + 1;
+    }
+
+    epilogue_w8<TN, TM, DEBUG, false>(acc, g, m0 + wm * WM + l16, n0 + wn * WN + lg * 4);
+}
+
+// ---- software-pipelined kernel ---------------------------------------------------------------
+template <int TN, int TM, int BK>
+__device__ __forceinline__ void load_frags(v4i (&af)[TN], v4i (&bf)[TM], const int8_t *stage, int woff, int xoff)
+{
+#pragma unroll
+    for (int a = 0; a < TN; ++a) af[a] = *reinterpret_cast<const v4i *>(stage + woff + a * 16 * BK);
+#pragma unroll
+    for (int b = 0; b < TM; ++b) bf[b] = *reinterpret_cast<const v4i *>(stage + xoff + b * 16 * BK);
+}
+
+template <int TN, int TM>
+__device__ __forceinline__ void mfma_block(v4i (&acc)[TN][TM], const v4i (&af)[TN], const v4i (&bf)[TM])
+{
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+            acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[a], bf[b], acc[a][b], 0, 0, 0);
+}
+
+// Ask the scheduler to spread the NREAD LDS reads of the next step over the NMFMA matrix
+// instructions of the current one (one read, then a few matrix instructions, repeated).
+template <int NREAD, int NMFMA>
+__device__ __forceinline__ void interleave_hint()
+{
+    constexpr int PER = NMFMA / NREAD > 0 ? NMFMA / NREAD : 1;
+#pragma unroll
+    for (int i = 0; i < NREAD; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // one LDS read
+        __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);   // PER matrix instructions
+    }
+    if constexpr (NMFMA - PER * NREAD > 0)
+        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - PER * NREAD, 0);
+}
+
+// BK = 128: two matrix-instruction k-steps per tile.  Fragment set F0 serves step 0 and F1
+// step 1; while one feeds the matrix cores the other is being filled.  At the end of tile kt
+// the workgroup waits for tile kt+1, passes the barrier (which also retires every read of
+// tile kt's stage), refills that stage with tile kt+NS and starts reading tile kt+1.
+template <int BM, int BN, int NS, int WGM, int WGN, bool DEBUG>
+__global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
+{
+    static_assert(WGM * WGN == 4, "four waves per workgroup");
+    static_assert(NS >= 2, "at least two stages");
+    constexpr int BK = 128;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int TM = WM / 16, TN = WN / 16;
+    constexpr int CPR = BK / 16;
+    constexpr int XBYTES = BM * BK, WBYTES = BN * BK, STAGE = XBYTES + WBYTES;
+    constexpr int PX = XBYTES / 4096, PW = WBYTES / 4096;
+    constexpr int P = PX + PW;
+    static_assert(PX >= 1 && PW >= 1 && (NS - 1) * P < 64, "copy count per wave out of range");
+
+    extern __shared__ __align__(16) int8_t smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t *)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int l16 = lane & 15, lg = lane >> 4;
+
+    const int tile = xcd_remap(blockIdx.x, g.tiles_m * g.tiles_n, g.remap);
+    const int tm_idx = tile / g.tiles_n, tn_idx = tile % g.tiles_n;
+    const int64_t m0 = (int64_t)tm_idx * BM;
+    const int n0 = tn_idx * BN;
+    const int K = g.K;
+
+    // Copy plan (tiles are full: M % BM == 0 and N % BN == 0 on this path).  Copy i of a wave
+    // fills LDS rows (wave*PX + i)*8 .. +7, eight 16-byte chunks each; the lane's row inside
+    // the 16-row swizzle period only depends on the parity of i, so two lane offsets per
+    // operand are enough and the rest of the address is scalar.
+    static_assert(PX % 2 == 0 && PW % 2 == 0, "even copy counts");
+    uint32_t voff[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int r = 8 * p + (lane >> 3);
+        voff[p] = (uint32_t)(r * K + (((lane & 7) ^ chunk_swizzle<BK>(r)) * 16));
+    }
+    const int8_t *xbase = g.Xq + (m0 + wave * PX * 8) * K;
+    const int8_t *wbase = static_cast<const int8_t *>(g.Wc) + ((size_t)n0 + wave * PW * 8) * K;
+    const int K16 = 16 * K;
+
+    auto issue = [&](int on, int kt, int st) {
+        const uint32_t sbase = lds0 + st * STAGE;
+        const int8_t *xs = xbase + kt * BK, *ws = wbase + kt * BK;
+#pragma unroll
+        for (int i = 0; i < PX; ++i)
+            dma_1k_if(on, voff[i & 1], xs + (i >> 1) * K16, sbase + (wave * PX + i) * 1024);
+#pragma unroll
+        for (int i = 0; i < PW; ++i)
+            dma_1k_if(on, voff[i & 1], ws + (i >> 1) * K16, sbase + XBYTES + (wave * PW + i) * 1024);
+    };
+
+    int xoff[2], woff[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int pc = (4 * h + lg) ^ chunk_swizzle<BK>(l16);
+        xoff[h] = ((wm * WM + l16) * CPR + pc) * 16;
+        woff[h] = XBYTES + ((wn * WN + l16) * CPR + pc) * 16;
+    }
+
+    v4i acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b) acc[a][b] = v4i{0, 0, 0, 0};
+    v4i af0[TN], bf0[TM], af1[TN], bf1[TM];
+
+    const int KT = K / BK;
+#pragma unroll
+    for (int t = 0; t < NS; ++t) issue(t < KT, t, t);
+    wait_vmcnt_or_zero<(NS - 1) * P>(KT >= NS);
+    __syncthreads();
+    load_frags<TN, TM, BK>(af0, bf0, smem, woff[0], xoff[0]);
+
+    // The loop body is straight-line code (the conditional copy and wait branch inside their
+    // assembly blocks), which keeps the accumulators in place across iterations.
+    int st = 0;
+    for (int kt = 0; kt + 1 < KT; ++kt) {
+        const int nst = (st + 1 == NS) ? 0 : st + 1;
+        const int more = kt + NS < KT;       // tile kt+NS exists and replaces tile kt in its stage
+        load_frags<TN, TM, BK>(af1, bf1, smem + st * STAGE, woff[1], xoff[1]);
+        mfma_block<TN, TM>(acc, af0, bf0);
+        interleave_hint<TN + TM, TN * TM>();
+        wait_vmcnt_or_zero<(NS - 2) * P>(more);   // tile kt+1 has landed (this wave's share)
+        __syncthreads();                          // ... everyone's share; tile kt's stage is retired
+        issue(more, kt + NS, st);
+        load_frags<TN, TM, BK>(af0, bf0, smem + nst * STAGE, woff[0], xoff[0]);
+        mfma_block<TN, TM>(acc, af1, bf1);
+        interleave_hint<TN + TM, TN * TM>();
+        st = nst;
+    }
+    // last tile
+    load_frags<TN, TM, BK>(af1, bf1, smem + st * STAGE, woff[1], xoff[1]);
+    mfma_block<TN, TM>(acc, af0, bf0);
+    interleave_hint<TN + TM, TN * TM>();
+    mfma_block<TN, TM>(acc, af1, bf1);
+
+    epilogue_w8<TN, TM, DEBUG, true>(acc, g, m0 + wm * WM + l16, n0 + wn * WN + lg * 4);
+}
+
+template <typename Kern>
+hipError_t launch_kernel(Kern kern, bool &attr_done, const GemmArgs &a, int BM, int BN, size_t smem, hipStream_t st)
+{
+    GemmArgs g = a;
+    { const char *e = getenv("TRDQ_REMAP"); g.remap = e ? atoi(e) : 1; }
+    g.tiles_m = (int)((g.M + BM - 1) / BM);
+    g.tiles_n = (g.N + BN - 1) / BN;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(kThreads), smem, st, g);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, int BK, int NS, int WGM, int WGN>
+hipError_t launch_ring(const GemmArgs &a, bool debug, hipStream_t st)
+{
+    static bool done[2] = {false, false};
+    const size_t smem = (size_t)NS * (BM + BN) * BK;
+    if (debug) return launch_kernel(qgemm8_ring_kernel<BM, BN, BK, NS, WGM, WGN, true>, done[1], a, BM, BN, smem, st);
+    return launch_kernel(qgemm8_ring_kernel<BM, BN, BK, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st);
+}
+
+template <int BM, int BN, int NS, int WGM, int WGN>
+hipError_t launch_pipe(const GemmArgs &a, bool debug, hipStream_t st)
+{
+    // the pipelined kernel takes full tiles only; ragged shapes go to the ring kernel
+    if (a.M % BM != 0 || a.N % BN != 0) return launch_ring<128, 128, 64, 4, 2, 2>(a, debug, st);
+    static bool done[2] = {false, false};
+    const size_t smem = (size_t)NS * (BM + BN) * 128;
+    if (debug) return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, true>, done[1], a, BM, BN, smem, st);
+    return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st);
+}
+
+}  // namespace
+
+// ring: 0: 128x128x64 NS4   1: 256x128x64 NS4   2: 128x256x64 NS4   3: 128x128x128 NS3   4: 256x128x128 NS3
+// pipe: 5: 256x128 NS3   6: 128x128 NS4   7: 128x256 NS3   8: 256x256 NS2   9: 128x128 NS2
+int dma_num_variants() { return 10; }
+
+hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStream_t st)
+{
+    switch (variant) {
+        case 0: return launch_ring<128, 128, 64, 4, 2, 2>(a, debug, st);
+        case 1: return launch_ring<256, 128, 64, 4, 2, 2>(a, debug, st);
+        case 2: return launch_ring<128, 256, 64, 4, 2, 2>(a, debug, st);
+        case 3: return launch_ring<128, 128, 128, 3, 2, 2>(a, debug, st);
+        case 4: return launch_ring<256, 128, 128, 3, 2, 2>(a, debug, st);
+        case 5: return launch_pipe<256, 128, 3, 2, 2>(a, debug, st);
+        case 6: return launch_pipe<128, 128, 4, 2, 2>(a, debug, st);
+        case 7: return launch_pipe<128, 256, 3, 2, 2>(a, debug, st);
+        case 8: return launch_pipe<256, 256, 2, 2, 2>(a, debug, st);
+        case 9: return launch_pipe<128, 128, 2, 2, 2>(a, debug, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace gemm
+}  // namespace trdq
