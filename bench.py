@@ -34,10 +34,14 @@ def parse():
     ap.add_argument("--config", type=int, default=1, help="workload config id (1 = the metric's)")
     ap.add_argument("--fused", action="store_true", help="use the fused kernel instead of rotate_quant + qgemm")
     ap.add_argument("--no-events", action="store_true", help="no per-kernel events in the timed region")
+    ap.add_argument("--event-every", type=int, default=4,
+                    help="bracket the kernels with events on every n-th timed step (keeps the probe effect small)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU work budget of the oracle's timed sample")
     ap.add_argument("--variant", type=int, default=-1, help="qgemm tile variant override")
     ap.add_argument("--groups", type=int, default=0, help="limit the number of groups prepared (0 = all)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 256 MiB device copy (a kernel of known traffic, to calibrate counters)")
     return ap.parse_args()
 
 
@@ -73,6 +77,21 @@ def cpu_baseline(cfg, wl, budget_s):
             "sample": f"{groups} of {cfg.n_groups} groups x {cfg.M} tokens x {len(cfg.kinds)} linears "
                       f"(rotate+quantise, int32 product, dequant; weights prepared beforehand, untimed), "
                       f"{spent:.1f} s of CPU work"}
+
+
+def committed_traffic(workload):
+    """HBM bytes per qgemm launch from the committed counter summary of this workload, or None.
+
+    The figure comes from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of this same
+    command, scaled by the copy-kernel calibration; the summary file states the commands."""
+    path = os.path.join(ROOT, "profiles", f"qgemm_hbm_traffic_{workload}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -122,31 +141,44 @@ def main():
     rq_bytes = {k: M * (3 * wl.LAYER_SHAPES[k][0] + 4) for k in cfg.kinds}
 
     use_events = not args.no_events
+
+    # one pre-marshalled C call per launch (the binding converts the arguments once)
+    calls = {}
+    for g in range(n_groups):
+        for kind in cfg.kinds:
+            if args.fused:
+                calls[g, kind] = (trdq.bind_linear_fused(X[kind, g], D[kind, g], Wh[kind, g], Y[kind],
+                                                         bias=B[kind], stream=stream),)
+            else:
+                calls[g, kind] = (trdq.bind_rotate_quant(X[kind, g], D[kind, g], Xq[kind], SX[kind], stream=stream),
+                                  trdq.bind_qgemm(Wh[kind, g], Xq[kind], SX[kind], Y[kind], bias=B[kind],
+                                                  stream=stream))
+    n_ev = len(cfg.kinds) * (2 if args.fused else 3)
+    every = max(1, args.event_every)
+    events = {st: [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
+              for st in range(0, args.steps, every)} if use_events else {}
     ev = []     # (name, kind, start, end)
 
     def run_step(step, record):
         g = table.lookup(step % cfg.n_steps) % n_groups
+        evs = events.get(step) if record else None
+        record = evs is not None
+        i = 0
         for kind in cfg.kinds:
-            if args.fused:
+            fns = calls[g, kind]
+            if record:
+                evs[i].record(stream)
+            for j, fn in enumerate(fns):
+                fn()
                 if record:
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record(stream)
-                trdq.linear_fused(X[kind, g], D[kind, g], Wh[kind, g], Y[kind], bias=B[kind], stream=stream)
-                if record:
-                    e1.record(stream)
-                    ev.append(("fused", kind, e0, e1))
-                continue
+                    evs[i + j + 1].record(stream)
             if record:
-                e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-                e0.record(stream)
-            trdq.rotate_quant(X[kind, g], D[kind, g], Xq[kind], SX[kind], stream=stream)
-            if record:
-                e1.record(stream)
-            trdq.qgemm(Wh[kind, g], Xq[kind], SX[kind], Y[kind], bias=B[kind], stream=stream)
-            if record:
-                e2.record(stream)
-                ev.append(("rotate_quant", kind, e0, e1))
-                ev.append(("qgemm", kind, e1, e2))
+                if args.fused:
+                    ev.append(("fused", kind, evs[i], evs[i + 1]))
+                else:
+                    ev.append(("rotate_quant", kind, evs[i], evs[i + 1]))
+                    ev.append(("qgemm", kind, evs[i + 1], evs[i + 2]))
+                i += len(fns) + 1
 
     for s in range(args.warmup):
         run_step(s, False)
@@ -194,6 +226,7 @@ def main():
         out["roofline"] = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS,
                            "unit": "TOP/s", "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None,
                            "avg_launch_us": tot_t / n_launch * 1e6, "launches": n_launch,
+                           "timed_on": f"every {every}th of the {args.steps} timed steps, events on the launch stream",
                            "ops_per_launch": tot_ops / n_launch}
         if not args.fused:
             rq_t = sum(sum(ts) for (name, _), ts in per.items() if name == "rotate_quant")
@@ -201,6 +234,9 @@ def main():
             out["roofline_rotate_quant"] = {"bound": "hbm", "achieved": rq_b / rq_t / 1e9, "peak": HBM_PEAK_GBS,
                                             "unit": "GB/s", "frac": rq_b / rq_t / 1e9 / HBM_PEAK_GBS,
                                             "traffic": None}
+
+    if "roofline" in out:
+        out["roofline"]["traffic"] = committed_traffic(cfg.name)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, wl, args.cpu_seconds)

@@ -20,15 +20,13 @@ struct GemmArgs {
     int64_t M, ldy;
     int K, N;
     int tiles_m, tiles_n;
-    int remap;             // tile order experiment knob
 };
 
 // Workgroups are handed to the 8 accelerator dies round-robin by their linear id; give each
 // die a contiguous run of tiles (a few token panels times all channel tiles) so that the
 // panels it re-reads stay in its own L2.
-__device__ __forceinline__ int xcd_remap(int bid, int ntiles, int mode = 1)
+__device__ __forceinline__ int xcd_remap(int bid, int ntiles)
 {
-    if (mode == 0) return bid;
     const int q = ntiles >> 3, r = ntiles & 7;
     const int xcd = bid & 7, idx = bid >> 3;
     return xcd * q + (xcd < r ? xcd : r) + idx;

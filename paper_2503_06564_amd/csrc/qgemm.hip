@@ -265,7 +265,6 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int
     a.Xq = Xq; a.Wc = w.codes; a.sx = sx; a.sw = w.scales; a.bias = bias; a.Y = Y;
     a.acc_debug = acc_debug; a.M = M; a.ldy = ldy; a.K = w.K; a.N = w.N;
     a.tiles_m = a.tiles_n = 0;
-    a.remap = 1;
     const bool dbg = acc_debug != nullptr;
     if (w.wbits == 4) {
         // int4 keeps a second (float) accumulator set: smaller tiles, BK = one scale group

@@ -10,8 +10,6 @@
 // Two kernels: `ring` (simple: one barrier per k-tile, fragments read right before use) and
 // `pipe` (fragments double-buffered in registers so LDS reads of the next k-step overlap the
 // matrix instructions of the current one; one workgroup of four waves per compute unit).
-#include <cstdlib>
-
 #include "gemm_common.h"
 
 namespace trdq {
@@ -134,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void qgemm8_ring_kernel(GemmArgs g)
     const int wm = wave % WGM, wn = wave / WGM;
     const int l16 = lane & 15, lg = lane >> 4;
 
-    const int tile = xcd_remap(blockIdx.x, g.tiles_m * g.tiles_n, g.remap);
+    const int tile = xcd_remap(blockIdx.x, g.tiles_m * g.tiles_n);
     const int tm_idx = tile / g.tiles_n, tn_idx = tile % g.tiles_n;
     const int64_t m0 = (int64_t)tm_idx * BM;
     const int n0 = tn_idx * BN;
@@ -278,7 +276,7 @@ __global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
     const int wm = wave % WGM, wn = wave / WGM;
     const int l16 = lane & 15, lg = lane >> 4;
 
-    const int tile = xcd_remap(blockIdx.x, g.tiles_m * g.tiles_n, g.remap);
+    const int tile = xcd_remap(blockIdx.x, g.tiles_m * g.tiles_n);
     const int tm_idx = tile / g.tiles_n, tn_idx = tile % g.tiles_n;
     const int64_t m0 = (int64_t)tm_idx * BM;
     const int n0 = tn_idx * BN;
@@ -362,7 +360,6 @@ template <typename Kern>
 hipError_t launch_kernel(Kern kern, bool &attr_done, const GemmArgs &a, int BM, int BN, size_t smem, hipStream_t st)
 {
     GemmArgs g = a;
-    { const char *e = getenv("TRDQ_REMAP"); g.remap = e ? atoi(e) : 1; }
     g.tiles_m = (int)((g.M + BM - 1) / BM);
     g.tiles_n = (g.N + BN - 1) / BN;
     if (!attr_done) {

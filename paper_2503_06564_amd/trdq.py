@@ -212,6 +212,53 @@ def linear_fused(X, diag, w, Y, bias=None, stream=None):
                                    _stream(stream)), "trdq_linear_fused")
 
 
+# ---- pre-marshalled calls ---------------------------------------------------------------------
+# For launch-bound loops: the arguments are converted to ctypes once; calling the returned
+# function performs exactly one C call (same entry points, same semantics).
+
+def bind_rotate_quant(X, diag, Xq, sx, block=BLOCK, stream=None):
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    f = lib().trdq_rotate_quant
+    args = (C.c_void_p(_ptr(X)), C.c_int64(M), C.c_int(K), C.c_int64(ldx), C.c_void_p(_ptr(diag)), C.c_int(block),
+            C.c_void_p(_ptr(Xq)), C.c_void_p(_ptr(sx)), C.c_void_p(_stream(stream)))
+
+    def call():
+        st = f(*args)
+        if st != OK:
+            raise TrdqError(st, "trdq_rotate_quant")
+    return call
+
+
+def bind_qgemm(w, Xq, sx, Y, bias=None, acc_debug=None, stream=None):
+    M = Xq.shape[0]
+    ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
+    f = lib().trdq_qgemm
+    args = (w.handle, C.c_void_p(_ptr(Xq)), C.c_void_p(_ptr(sx)), C.c_int64(M), C.c_void_p(_ptr(bias)),
+            C.c_void_p(_ptr(Y)), C.c_int64(ldy), C.c_void_p(_ptr(acc_debug)), C.c_void_p(_stream(stream)))
+
+    def call():
+        st = f(*args)
+        if st != OK:
+            raise TrdqError(st, "trdq_qgemm")
+    return call
+
+
+def bind_linear_fused(X, diag, w, Y, bias=None, stream=None):
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
+    f = lib().trdq_linear_fused
+    args = (C.c_void_p(_ptr(X)), C.c_int64(M), C.c_int64(ldx), C.c_void_p(_ptr(diag)), w.handle,
+            C.c_void_p(_ptr(bias)), C.c_void_p(_ptr(Y)), C.c_int64(ldy), C.c_void_p(_stream(stream)))
+
+    def call():
+        st = f(*args)
+        if st != OK:
+            raise TrdqError(st, "trdq_linear_fused")
+    return call
+
+
 def qgemm_set_variant(variant):
     _check(lib().trdq_qgemm_set_variant(variant), "trdq_qgemm_set_variant")
 

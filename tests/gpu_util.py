@@ -88,13 +88,25 @@ def assert_scales_close(got, want, what):
         f"{what}: max rel err {np.max(np.abs(got - want) / np.maximum(np.abs(want), 1e-300))}"
 
 
-def assert_y_close(got_bits, want_bits, what):
+def assert_y_close(got_bits, want_bits, what, skip_rows=None, skip_cols=None):
+    """|got - want| <= 1e-2 x row absmax of want, element by element.
+
+    skip_rows / skip_cols: boolean masks of tokens / output channels whose activation / weight
+    codes legitimately differ from the oracle's by one LSB (the <= 0.01 % allowance).  One such
+    step moves the affected outputs by s_x * s_w * |other code|, which for int4 weights can
+    exceed 1e-2 x row absmax, so those entries are judged on identical codes instead (the
+    caller compares them with the oracle's epilogue run on the GPU's own codes)."""
     got, want = bits_to_f64(got_bits), bits_to_f64(want_bits)
     assert got.shape == want.shape, (what, got.shape, want.shape)
     if got.size == 0:
         return 0.0
     row = np.abs(want).max(axis=1, keepdims=True)
     err = np.abs(got - want)
-    worst = float((err / np.maximum(row, 1e-30)).max())
-    assert np.all(err <= Y_TOL * row + 1e-30), f"{what}: max err / row absmax = {worst}"
-    return worst
+    ok = err <= Y_TOL * row + 1e-30
+    if skip_rows is not None:
+        ok = ok | np.asarray(skip_rows, bool)[:, None]
+    if skip_cols is not None:
+        ok = ok | np.asarray(skip_cols, bool)[None, :]
+    worst = float((np.where(ok, 0.0, err) / np.maximum(row, 1e-30)).max())
+    assert np.all(ok), f"{what}: max err / row absmax = {worst}"
+    return float((err / np.maximum(row, 1e-30)).max())

@@ -1,0 +1,146 @@
+"""GPU parity at the full sizes of the five synthetic workloads, in the launch configuration
+bench.py times (built-in tile choice).  The GPU processes every token; the oracle recomputes a
+sample of tokens one by one (first and last tile rows plus random rows), every weight code and
+scale, and properties that hold for all rows are checked on the whole output."""
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2503_06564_amd import trdq, workloads as wl  # noqa: E402
+from tests import gpu_util as gu  # noqa: E402
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need the MI355X; run them with -m gpu on the GPU box")
+    trdq.lib()
+    trdq.qgemm_set_variant(-1)
+
+
+def sample_rows(M, seed, n_random=64, edge=24):
+    r = np.random.default_rng(seed)
+    rows = np.concatenate([np.arange(min(edge, M)), np.arange(max(0, M - edge), M),
+                           r.integers(0, M, size=n_random)])
+    return np.unique(rows)
+
+
+def check_layer(oracle, cfg, kind, step, wbits, block=0, fused_too=True, Xb=None):
+    """One linear of a workload at full M: unfused (and fused) GPU path vs the oracle on sampled rows."""
+    K, N = wl.LAYER_SHAPES[kind]
+    g = wl.step_to_group(cfg, step)
+    Xb = wl.make_x(cfg, kind, step) if Xb is None else Xb
+    M = Xb.shape[0]
+    W, d, bias = wl.make_w(cfg, kind, block), wl.make_diag(cfg, kind, g), wl.make_bias(cfg, kind, block)
+    Wd, dd, bd = gu.f32_to_dev(W), gu.f32_to_dev(d), gu.f32_to_dev(bias)
+    w = trdq.prepare_weights(Wd, dd, wbits=wbits)
+    X = gu.bf16_to_dev(Xb)
+    Xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+    sx = torch.empty((M,), dtype=torch.float32, device="cuda")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    trdq.rotate_quant(X, dd, Xq, sx)
+    trdq.qgemm(w, Xq, sx, Y, bias=bd)
+    torch.cuda.synchronize()
+
+    # properties over ALL tokens: every live token uses the full code range, scales positive
+    amax = Xq.abs().amax(dim=1)
+    live = sx > 0
+    assert bool((amax[live] == 127).all()) and bool((amax[~live] == 0).all())
+    assert bool(torch.isfinite(Y.float()).all())
+
+    rows = sample_rows(M, 1000 * cfg.cfg + step)
+    ref = oracle.linear(Xb[rows], W, d, bias, wbits=wbits, exact_blas=True)
+    idx = torch.from_numpy(rows).cuda()
+    gu.assert_codes_close(Xq[idx].cpu().numpy(), ref["Xq"], f"{kind} Xq")
+    gu.assert_scales_close(sx[idx].cpu().numpy(), ref["sx"], f"{kind} s_x")
+    codes, scales = w.export()
+    gu.assert_codes_close(codes, ref["Wq"], f"{kind} Wq")
+    gu.assert_scales_close(scales, ref["sw"], f"{kind} s_w")
+    # outputs whose codes differ by the allowed LSB are judged on identical codes (below)
+    rows_diff = (Xq[idx].cpu().numpy() != ref["Xq"]).any(axis=1)
+    cols_diff = (codes != ref["Wq"]).any(axis=0)
+    worst = gu.assert_y_close(gu.bf16_to_host(Y[idx]), ref["Y"], f"{kind} Y", rows_diff, cols_diff)
+    # accumulators bit-exact given the GPU's own codes (oracle's exact integer product on them)
+    acc = oracle.acc_exact_blas(Xq[idx].cpu().numpy(), codes, None if wbits == 8 else 128)
+    y_same = oracle.dequant(acc, sx[idx].cpu().numpy(), scales, bias)
+    want = gu.bits_to_f64(y_same)
+    same = gu.bits_to_f64(gu.bf16_to_host(Y[idx])) - want
+    # fp32 epilogue vs float64 epilogue on identical integers: one bf16 step, plus the fp32
+    # rounding of the (up to 36) group terms relative to the row's magnitude where terms cancel
+    row = np.abs(want).max(axis=1, keepdims=True)
+    assert np.all(np.abs(same) <= np.abs(want) * 2.0 ** -7 + row * 1e-5)
+    if fused_too:
+        Yf = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        trdq.linear_fused(X, dd, w, Yf, bias=bd)
+        torch.cuda.synchronize()
+        assert torch.equal(Yf, Y), f"{kind}: fused and unfused outputs differ"
+    w.close()
+    return worst
+
+
+def test_config0_single_layer_every_element(oracle):
+    cfg = wl.CONFIGS[0]
+    say("config 0: 512 x 1152 x 1152, every element")
+    Xb, W = wl.make_x(cfg, "proj"), wl.make_w(cfg, "proj")
+    d, bias = wl.make_diag(cfg, "proj"), wl.make_bias(cfg, "proj")
+    ref = oracle.linear(Xb, W, d, bias, wbits=8)          # the plain int32 loop, all rows
+    w = trdq.prepare_weights(gu.f32_to_dev(W), gu.f32_to_dev(d), wbits=8)
+    Xq, sx = gu.gpu_rotate_quant(Xb, d)
+    Y, acc = gu.gpu_qgemm(w, Xq, sx, bias, 1152, debug=True)
+    gu.assert_codes_close(Xq.cpu().numpy(), ref["Xq"], "Xq")
+    gu.assert_scales_close(sx.cpu().numpy(), ref["sx"], "s_x")
+    codes, scales = w.export()
+    gu.assert_codes_close(codes, ref["Wq"], "Wq")
+    assert np.array_equal(acc.cpu().numpy(), oracle.igemm(Xq.cpu().numpy(), codes))
+    gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], "Y")
+    # the method's own claim on this input: rotated quantisation beats the exact product by ~1 %
+    exact = wl.bf16_bits_to_f32(Xb).astype(np.float64) @ W.astype(np.float64) + bias
+    got = gu.bits_to_f64(gu.bf16_to_host(Y))
+    assert np.linalg.norm(got - exact) / np.linalg.norm(exact) < 0.02
+
+
+@pytest.mark.parametrize("kind", ["qkv", "proj", "fc1", "fc2"])
+@pytest.mark.parametrize("step", [0, 7])
+def test_config1_dit_block_w8a8(oracle, kind, step):
+    say(f"config 1: M=4096 {kind} step {step}")
+    check_layer(oracle, wl.CONFIGS[1], kind, step, 8)
+
+
+@pytest.mark.parametrize("kind", ["qkv", "proj", "fc1", "fc2"])
+def test_config2_w4a8_16384_tokens(oracle, kind):
+    say(f"config 2: M=16384 W4A8 {kind}")
+    check_layer(oracle, wl.CONFIGS[2], kind, 3, 4)
+
+
+@pytest.mark.parametrize("kind", ["qkv", "proj", "fc1", "fc2"])
+@pytest.mark.parametrize("step", [0, 19])
+def test_config3_video_32768_tokens(oracle, kind, step):
+    cfg = wl.CONFIGS[3]
+    say(f"config 3: M=32768 {kind} step {step} (W8A8 and W4A8)")
+    Xb = wl.make_x(cfg, kind, step)
+    check_layer(oracle, cfg, kind, step, 8, Xb=Xb, fused_too=(kind != "fc2"))
+    check_layer(oracle, cfg, kind, step, 4, Xb=Xb, fused_too=False)
+
+
+def test_config3_step_table_maps_20_steps_to_5_groups():
+    t = trdq.Table(20, 5)
+    assert [t.lookup(s) for s in range(20)] == [wl.step_to_group(wl.CONFIGS[3], s) for s in range(20)]
+    t = trdq.Table(50, 10)
+    assert [t.lookup(s) for s in range(50)] == [wl.step_to_group(wl.CONFIGS[4], s) for s in range(50)]
+
+
+@pytest.mark.parametrize("block,step", [(0, 0), (13, 27), (27, 49)])
+@pytest.mark.parametrize("kind", ["qkv", "proj", "fc1", "fc2"])
+def test_config4_denoiser_sweep_layers(oracle, block, step, kind):
+    say(f"config 4: M=8192 block {block} {kind} step {step}")
+    check_layer(oracle, wl.CONFIGS[4], kind, step, 8, block=block, fused_too=False)

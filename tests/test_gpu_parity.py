@@ -134,7 +134,8 @@ def _linear_case(oracle, seed, M, K, N, wbits, variant, with_bias=True, ldy=None
     gu.assert_y_close(gu.bf16_to_host(Y), y_same, "Y (same codes)")
     # (iii) against the oracle's own end-to-end quantised output
     ref = oracle.linear(Xb, W, d, bias, wbits=wbits, exact_blas=True)
-    worst = gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], "Y (oracle end to end)")
+    worst = gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], "Y (oracle end to end)",
+                              (Xq_h != ref["Xq"]).any(axis=1), (Wq_h != ref["Wq"]).any(axis=0))
     # without the debug output the result is the same
     Y2, _ = gu.gpu_qgemm(w, Xq, sx, bias, N, debug=False, ldy=ldy)
     assert torch.equal(Y2, Y)
