@@ -143,8 +143,9 @@ trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float 
                        int32_t *acc_debug_dev, void *stream);
 
 /* Fused variant: rotate -> quantise -> integer product -> epilogue in ONE kernel; the int8
- * activations never travel through HBM.  Same arithmetic and results as
- * trdq_rotate_quant followed by trdq_qgemm.  K is taken from the handle.
+ * activations never travel through HBM.  Same arithmetic as trdq_rotate_quant followed by
+ * trdq_qgemm up to the rounding order of the fp32 rotation (an activation code may differ by
+ * one LSB on a rare element, within the same tolerance).  K is taken from the handle.
  * Errors as the two calls above; K beyond the fused kernel's on-chip panel
  * (K > 6144) -> ERR_UNSUPPORTED. */
 trdq_status trdq_linear_fused(const void *X_dev, int64_t M, int64_t ldx, const float *diag_dev,

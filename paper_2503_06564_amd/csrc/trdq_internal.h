@@ -31,6 +31,8 @@ struct Table {
 // Kernel launchers (defined in the .hip files).  All return hipError_t of the launch.
 hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
                                int8_t *Xq, float *sx, hipStream_t st);
+hipError_t launch_rotate_quant_wide(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
+                                    int8_t *Xq, float *sx, hipStream_t st);
 
 hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag, float *Wrot,
                                  float *amax, hipStream_t st);

