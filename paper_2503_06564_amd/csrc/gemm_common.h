@@ -22,9 +22,8 @@ struct GemmArgs {
     int tiles_m, tiles_n;
 };
 
-// Workgroups are handed to the 8 accelerator dies round-robin by their linear id; give each
-// die a contiguous run of tiles (a few token panels times all channel tiles) so that the
-// panels it re-reads stay in its own L2.
+// Workgroups are handed to the 8 accelerator dies (XCDs) round-robin by their linear id; give
+// each die a contiguous run of tiles so that the panels it re-reads stay in its own L2.
 __device__ __forceinline__ int xcd_remap(int bid, int ntiles)
 {
     const int q = ntiles >> 3, r = ntiles & 7;
@@ -32,6 +31,28 @@ __device__ __forceinline__ int xcd_remap(int bid, int ntiles)
     return xcd * q + (xcd < r ? xcd : r) + idx;
 }
 
+// Work item id -> tile coordinates.  Each die owns a band of token panels; inside the band the
+// tiles are visited in groups of up to 8 token panels, channel tile by channel tile, so the
+// ~64 tiles a die has in flight form an 8 x 8 block: 8 activation panels + 8 weight panels fit
+// its 4 MB L2, instead of every round streaming the whole weight matrix through it.
+// (Needs tiles_m % 8 == 0; otherwise the plain run-per-die order is used.)
+__device__ __forceinline__ void tile_map(int id, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    if ((tiles_m & 7) == 0) {
+        const int per = tiles_m >> 3;                // token panels per die
+        const int xcd = id & 7, i = id >> 3;         // i-th work item of this die
+        const int gm = per < 8 ? per : 8;
+        const int group = i / (gm * tiles_n);
+        const int j = i - group * gm * tiles_n;
+        const int rows = (per - group * gm) < gm ? (per - group * gm) : gm;   // last group may be short
+        tn = j / rows;
+        tm = xcd * per + group * gm + (j - tn * rows);
+    } else {
+        const int t = xcd_remap(id, tiles_m * tiles_n);
+        tm = t / tiles_n;
+        tn = t - tm * tiles_n;
+    }
+}
 
 // Direct-to-LDS int8 kernels (qgemm_dma.hip).  variant indexes the table in that file.
 int dma_num_variants();

@@ -132,8 +132,8 @@ __global__ __launch_bounds__(kThreads) void qgemm8_ring_kernel(GemmArgs g)
     const int wm = wave % WGM, wn = wave / WGM;
     const int l16 = lane & 15, lg = lane >> 4;
 
-    const int tile = xcd_remap(blockIdx.x, g.tiles_m * g.tiles_n);
-    const int tm_idx = tile / g.tiles_n, tn_idx = tile % g.tiles_n;
+    int tm_idx, tn_idx;
+    tile_map(blockIdx.x, g.tiles_m, g.tiles_n, tm_idx, tn_idx);
     const int64_t m0 = (int64_t)tm_idx * BM;
     const int n0 = tn_idx * BN;
     const int K = g.K;
@@ -234,19 +234,20 @@ __device__ __forceinline__ void mfma_block(v4i (&acc)[TN][TM], const v4i (&af)[T
             acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[a], bf[b], acc[a][b], 0, 0, 0);
 }
 
-// Ask the scheduler to spread the NREAD LDS reads of the next step over the NMFMA matrix
-// instructions of the current one (one read, then a few matrix instructions, repeated).
+// Ask the scheduler to issue the NREAD LDS reads of the next step early: one read in front of
+// each of the first matrix instructions of the current step, the remaining matrix instructions
+// after them, so the fragments have the rest of the step to arrive.
 template <int NREAD, int NMFMA>
 __device__ __forceinline__ void interleave_hint()
 {
-    constexpr int PER = NMFMA / NREAD > 0 ? NMFMA / NREAD : 1;
+    constexpr int LEAD = NREAD < NMFMA ? NREAD : NMFMA;
 #pragma unroll
-    for (int i = 0; i < NREAD; ++i) {
+    for (int i = 0; i < LEAD; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // one LDS read
-        __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);   // PER matrix instructions
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one matrix instruction
     }
-    if constexpr (NMFMA - PER * NREAD > 0)
-        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - PER * NREAD, 0);
+    if constexpr (NREAD > LEAD) __builtin_amdgcn_sched_group_barrier(0x100, NREAD - LEAD, 0);
+    if constexpr (NMFMA > LEAD) __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - LEAD, 0);
 }
 
 // BK = 128: two matrix-instruction k-steps per tile.  Fragment set F0 serves step 0 and F1
@@ -276,8 +277,8 @@ __global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
     const int wm = wave % WGM, wn = wave / WGM;
     const int l16 = lane & 15, lg = lane >> 4;
 
-    const int tile = xcd_remap(blockIdx.x, g.tiles_m * g.tiles_n);
-    const int tm_idx = tile / g.tiles_n, tn_idx = tile % g.tiles_n;
+    int tm_idx, tn_idx;
+    tile_map(blockIdx.x, g.tiles_m, g.tiles_n, tm_idx, tn_idx);
     const int64_t m0 = (int64_t)tm_idx * BM;
     const int n0 = tn_idx * BN;
     const int K = g.K;
@@ -356,6 +357,198 @@ __global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
     epilogue_w8<TN, TM, DEBUG, true>(acc, g, m0 + wm * WM + l16, n0 + wn * WN + lg * 4);
 }
 
+// ---- persistent software-pipelined kernel -------------------------------------------------------
+// A workgroup walks a list of output tiles.  The k-tile ring never drains between tiles: while
+// the last k-tiles of tile T are multiplied, the first k-tiles of tile T+1 are already being
+// copied, the epilogue's stores overlap the next tile's main loop, and a second workgroup on
+// the same compute unit fills the matrix cores while this one converts and stores.
+
+// 16-byte load issued from assembly (kept out of the compiler's vmcnt bookkeeping, like the
+// LDS copies): the value is valid once a later hand-placed vmcnt wait has covered it.
+__device__ __forceinline__ float4 asm_load16(const void *p)
+{
+    float4 v;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+__device__ __forceinline__ float asm_load4(const void *p)
+{
+    float v;
+    asm volatile("global_load_dword %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+
+// waits for vmcnt(NBIG) / vmcnt(N) / vmcnt(0) for sel = 2 / 1 / 0 (sel is wave-uniform)
+template <int N, int NBIG>
+__device__ __forceinline__ void wait_vmcnt_select(int sel)
+{
+    asm volatile("s_cmp_eq_u32 %0, 2\n\ts_cbranch_scc0 .Lnotbig%=\n\t"
+                 "s_waitcnt vmcnt(%2)\n\ts_branch .Ldone%=\n"
+                 ".Lnotbig%=:\n\ts_cmp_eq_u32 %0, 1\n\ts_cbranch_scc0 .Lzero%=\n\t"
+                 "s_waitcnt vmcnt(%1)\n\ts_branch .Ldone%=\n"
+                 ".Lzero%=:\n\ts_waitcnt vmcnt(0)\n"
+                 ".Ldone%=:"
+                 :: "s"(__builtin_amdgcn_readfirstlane(sel)), "n"(N), "n"(NBIG) : "memory", "scc");
+}
+
+template <int BM, int BN, int NS, int WGM, int WGN, bool DEBUG>
+__global__ __launch_bounds__(kThreads) void qgemm8_persist_kernel(GemmArgs g)
+{
+    static_assert(WGM * WGN == 4, "four waves per workgroup");
+    static_assert(NS >= 2, "at least two stages");
+    constexpr int BK = 128;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int TM = WM / 16, TN = WN / 16;
+    constexpr int CPR = BK / 16;
+    constexpr int XBYTES = BM * BK, WBYTES = BN * BK, STAGE = XBYTES + WBYTES;
+    constexpr int PX = XBYTES / 4096, PW = WBYTES / 4096;
+    constexpr int P = PX + PW;
+    constexpr int SEP = TN * TM * (DEBUG ? 2 : 1);                    // store instructions of one epilogue
+    constexpr int NWAIT = (NS - 2) * P;
+    constexpr int NBIG = NWAIT + SEP < 63 ? NWAIT + SEP : 63;
+    static_assert(PX % 2 == 0 && PW % 2 == 0 && (NS - 1) * P < 64, "copy counts");
+
+    extern __shared__ __align__(16) int8_t smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t *)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int l16 = lane & 15, lg = lane >> 4;
+    const int K = g.K;
+    const int KT = K / BK;                            // >= NS (checked by the launcher)
+    const int ntiles = g.tiles_m * g.tiles_n;
+
+    uint32_t voff[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int r = 8 * p + (lane >> 3);
+        voff[p] = (uint32_t)(r * K + (((lane & 7) ^ chunk_swizzle<BK>(r)) * 16));
+    }
+    const int K16 = 16 * K;
+    int xoff[2], woff[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int pc = (4 * h + lg) ^ chunk_swizzle<BK>(l16);
+        xoff[h] = ((wm * WM + l16) * CPR + pc) * 16;
+        woff[h] = XBYTES + ((wn * WN + l16) * CPR + pc) * 16;
+    }
+
+    // tile id -> operand bases of this wave's copies
+    auto tile_coords = [&](int L, int64_t &m0, int &n0) {
+        int tm, tn;
+        tile_map(L, g.tiles_m, g.tiles_n, tm, tn);
+        m0 = (int64_t)tm * BM;
+        n0 = tn * BN;
+    };
+    // Copies are unconditional: past the workgroup's last tile they re-read that tile's own
+    // k-tiles into stages nobody reads any more (a few redundant cached reads at the very end)
+    // instead of branching around every copy.
+    auto issue = [&](const int8_t *xs, const int8_t *ws, int st) {
+        const uint32_t sbase = lds0 + st * STAGE;
+#pragma unroll
+        for (int i = 0; i < PX; ++i)
+            dma_1k(voff[i & 1], xs + (i >> 1) * K16, sbase + (wave * PX + i) * 1024);
+#pragma unroll
+        for (int i = 0; i < PW; ++i)
+            dma_1k(voff[i & 1], ws + (i >> 1) * K16, sbase + XBYTES + (wave * PW + i) * 1024);
+    };
+
+    int L = blockIdx.x;                               // this workgroup's tiles: L, L + grid, ...
+    int64_t m0; int n0;
+    tile_coords(L, m0, n0);
+    const int8_t *xcur = g.Xq + (m0 + wave * PX * 8) * K;
+    const int8_t *wcur = static_cast<const int8_t *>(g.Wc) + ((size_t)n0 + wave * PW * 8) * K;
+
+#pragma unroll
+    for (int t = 0; t < NS; ++t) issue(xcur + t * BK, wcur + t * BK, t);
+    wait_vmcnt<(NS - 1) * P>();
+    __syncthreads();
+    v4i af0[TN], bf0[TM], af1[TN], bf1[TM];
+    load_frags<TN, TM, BK>(af0, bf0, smem, woff[0], xoff[0]);
+
+    int st = 0;
+    bool first = true;
+    for (; L < ntiles; L += gridDim.x) {
+        // next tile of this workgroup (its first k-tiles are prefetched during this tile's last ones)
+        const int Ln = L + gridDim.x;
+        const int has_next = Ln < ntiles;
+        int64_t m1 = 0; int n1 = 0;
+        tile_coords(has_next ? Ln : L, m1, n1);
+        const int8_t *xnext = g.Xq + (m1 + wave * PX * 8) * K;
+        const int8_t *wnext = static_cast<const int8_t *>(g.Wc) + ((size_t)n1 + wave * PW * 8) * K;
+
+        // epilogue operands, requested now (older than every copy of this tile, so the first
+        // vmcnt wait of the k-loop covers them) and used after the k-loop
+        const int64_t m_lane = m0 + wm * WM + l16;
+        const int n_lane = n0 + wn * WN + lg * 4;
+        float sxm[TM];
+        float4 swv[TN], biv[TN];
+#pragma unroll
+        for (int b = 0; b < TM; ++b) sxm[b] = asm_load4(g.sx + m_lane + b * 16);
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+            swv[a] = asm_load16(g.sw + n_lane + a * 16);
+            biv[a] = g.bias ? asm_load16(g.bias + n_lane + a * 16) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+
+        v4i acc[TN][TM];
+#pragma unroll
+        for (int a = 0; a < TN; ++a)
+#pragma unroll
+            for (int b = 0; b < TM; ++b) acc[a][b] = v4i{0, 0, 0, 0};
+
+        for (int kt = 0; kt < KT; ++kt) {
+            const int nst = (st + 1 == NS) ? 0 : st + 1;
+            // the copy issued in this step is k-tile kt + NS of this tile, or wraps into the next
+            // tile (after the last tile: into this tile again, unused)
+            const int wrap = kt + NS >= KT;
+            const int ikt = wrap ? kt + NS - KT : kt + NS;
+            const int8_t *xs = (wrap ? xnext : xcur) + ikt * BK;
+            const int8_t *ws = (wrap ? wnext : wcur) + ikt * BK;
+            // younger than the k-tile waited for: (NS-2) k-tiles of copies, plus -- in the first
+            // NS-1 steps after an epilogue -- that epilogue's stores
+            const int sel = (!first && kt < NS - 1) ? 2 : 1;
+
+            load_frags<TN, TM, BK>(af1, bf1, smem + st * STAGE, woff[1], xoff[1]);
+            mfma_block<TN, TM>(acc, af0, bf0);
+            interleave_hint<TN + TM, TN * TM>();
+            wait_vmcnt_select<NWAIT, NBIG>(sel);
+            __syncthreads();
+            issue(xs, ws, st);
+            load_frags<TN, TM, BK>(af0, bf0, smem + nst * STAGE, woff[0], xoff[0]);
+            mfma_block<TN, TM>(acc, af1, bf1);
+            interleave_hint<TN + TM, TN * TM>();
+            st = nst;
+        }
+
+        // epilogue (full tiles only on this path): y = float(acc) * s_x * s_w + bias -> bf16
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+            const int n = n_lane + a * 16;
+#pragma unroll
+            for (int b = 0; b < TM; ++b) {
+                const int64_t m = m_lane + b * 16;
+                if constexpr (DEBUG) {
+                    int4 d = make_int4(acc[a][b][0], acc[a][b][1], acc[a][b][2], acc[a][b][3]);
+                    *reinterpret_cast<int4 *>(g.acc_debug + m * g.N + n) = d;
+                }
+                const float y0 = (float)acc[a][b][0] * sxm[b] * swv[a].x + biv[a].x;
+                const float y1 = (float)acc[a][b][1] * sxm[b] * swv[a].y + biv[a].y;
+                const float y2 = (float)acc[a][b][2] * sxm[b] * swv[a].z + biv[a].z;
+                const float y3 = (float)acc[a][b][3] * sxm[b] * swv[a].w + biv[a].w;
+                uint2 o;
+                o.x = pack_bf16x2(y0, y1);
+                o.y = pack_bf16x2(y2, y3);
+                *reinterpret_cast<uint2 *>(g.Y + m * g.ldy + n) = o;
+            }
+        }
+        m0 = m1; n0 = n1; xcur = xnext; wcur = wnext;
+        first = false;
+    }
+}
+
 template <typename Kern>
 hipError_t launch_kernel(Kern kern, bool &attr_done, const GemmArgs &a, int BM, int BN, size_t smem, hipStream_t st)
 {
@@ -392,11 +585,36 @@ hipError_t launch_pipe(const GemmArgs &a, bool debug, hipStream_t st)
     return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st);
 }
 
+template <int BM, int BN, int NS, int WGM, int WGN, int WGS_PER_CU>
+hipError_t launch_persist(const GemmArgs &a, bool debug, hipStream_t st)
+{
+    // full tiles and at least NS k-tiles; everything else goes to the ring kernel
+    if (a.M % BM != 0 || a.N % BN != 0 || a.K / 128 < NS) return launch_ring<128, 128, 64, 4, 2, 2>(a, debug, st);
+    static bool done[2] = {false, false};
+    GemmArgs g = a;
+    g.tiles_m = (int)(g.M / BM);
+    g.tiles_n = g.N / BN;
+    const size_t smem = (size_t)NS * (BM + BN) * 128;
+    auto kern = debug ? qgemm8_persist_kernel<BM, BN, NS, WGM, WGN, true>
+                      : qgemm8_persist_kernel<BM, BN, NS, WGM, WGN, false>;
+    if (!done[debug]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        done[debug] = true;
+    }
+    int grid = 256 * WGS_PER_CU;
+    if (grid > g.tiles_m * g.tiles_n) grid = g.tiles_m * g.tiles_n;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), smem, st, g);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 // ring: 0: 128x128x64 NS4   1: 256x128x64 NS4   2: 128x256x64 NS4   3: 128x128x128 NS3   4: 256x128x128 NS3
 // pipe: 5: 256x128 NS3   6: 128x128 NS4   7: 128x256 NS3   8: 256x256 NS2   9: 128x128 NS2
-int dma_num_variants() { return 10; }
+// persistent: 10: 128x128 NS2 (2 workgroups per CU)   11: 256x128 NS3   12: 128x256 NS3   13: 128x128 NS4
+int dma_num_variants() { return 14; }
 
 hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStream_t st)
 {
@@ -411,6 +629,10 @@ hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStre
         case 7: return launch_pipe<128, 256, 3, 2, 2>(a, debug, st);
         case 8: return launch_pipe<256, 256, 2, 2, 2>(a, debug, st);
         case 9: return launch_pipe<128, 128, 2, 2, 2>(a, debug, st);
+        case 10: return launch_persist<128, 128, 2, 2, 2, 2>(a, debug, st);
+        case 11: return launch_persist<256, 128, 3, 2, 2, 1>(a, debug, st);
+        case 12: return launch_persist<128, 256, 3, 2, 2, 1>(a, debug, st);
+        case 13: return launch_persist<128, 128, 4, 2, 2, 1>(a, debug, st);
     }
     return hipErrorInvalidValue;
 }
