@@ -254,7 +254,7 @@ hipError_t launch_cfg(const GemmArgs &a, bool debug, hipStream_t st)
 //   0: 128x128x64   1: 128x128x128   2: 256x128x64   3: 128x256x64   4: 256x128x128   5: 64x128x128
 // 6 and up: the direct-to-LDS int8 kernels of qgemm_dma.hip (variant - 6 indexes its table).
 constexpr int kRegVariants = 6;
-int qgemm_num_variants() { return kRegVariants + dma_num_variants(); }
+int qgemm_num_variants() { return kRegVariants + dma_num_variants() + 1; }
 
 hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int64_t M,
                         const float *bias, uint16_t *Y, int64_t ldy, int32_t *acc_debug,
@@ -283,7 +283,12 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int
         case 3: return launch_cfg<128, 256, 64, 2, 2, false>(a, dbg, st);
         case 4: return launch_cfg<256, 128, 128, 2, 2, false>(a, dbg, st);
         case 5: return launch_cfg<64, 128, 128, 1, 4, false>(a, dbg, st);
-        default: return launch_qgemm8_dma(a, dbg, variant - kRegVariants, st);
+        default:
+            // last variant: 256 x 256 tiles, hand-scheduled loop; shapes it does not take go to the
+            // ring kernel
+            if (variant == kRegVariants + dma_num_variants())
+                return wide_supports(a) ? launch_qgemm8_wide(a, dbg, st) : launch_qgemm8_dma(a, dbg, 0, st);
+            return launch_qgemm8_dma(a, dbg, variant - kRegVariants, st);
     }
 }
 

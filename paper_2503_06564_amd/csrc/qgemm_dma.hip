@@ -17,30 +17,6 @@ namespace gemm {
 
 namespace {
 
-// row -> XOR mask of the 16-byte chunk index, a function of (row mod 16) only so that the
-// fragment offsets of different 16-row tiles differ by a constant
-template <int BK>
-__device__ __forceinline__ int chunk_swizzle(int row)
-{
-    const int r = row & 15;
-    if constexpr (BK == 64) return ((r >> 1) ^ (r >> 3)) & 3;
-    else return (r ^ (r >> 3)) & 7;
-}
-
-__device__ __forceinline__ void dma_1k(uint32_t voff, const void *sbase, uint32_t lds_addr)
-{
-    // one wait state between the scalar write of M0 and the copy that reads it
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
-}
-
 // Dequantising epilogue for int8 weights.  The lane holds, for every 16x16 tile (a, b), the
 // accumulators of channels n_lane + 16a .. +3 of token m_lane + 16b:
 //   y = float(acc) * s_x[m] * s_w[n] + bias[n]  -> bf16, one 8-byte store per tile.

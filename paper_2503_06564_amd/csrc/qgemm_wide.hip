@@ -1,0 +1,383 @@
+// W8A8 integer product with a 256 x 256 output tile per workgroup and a hand-scheduled main loop.
+//
+// Why this shape: with int8 matrix instructions at 2048 ops per clock per SIMD the kernel is
+// bound by what the L2 can deliver to the compute units, so the tile is the largest one the
+// register file allows (four waves, each 128 channels x 128 tokens = 256 accumulator registers),
+// which halves the operand bytes per operation of a 128 x 128 tile.  One wave per SIMD means
+// nothing else hides instruction-issue bubbles, so the k-loop is written in assembly: 64 matrix
+// instructions per 64-deep k-step with the 16 LDS fragment reads of the next step and the 16
+// direct-to-LDS copies of a later k-tile placed between them at fixed intervals, accumulators in
+// the accumulation registers a0-a255, fragments double-buffered in v128-v255.
+//
+// Operation: Y = dequant(Xq . Wq^T) of Eq. 10's quantised product, per-token and per-channel
+// scales, optional bias, bf16 output (the same arithmetic as the other int8 kernels).
+#include "gemm_common.h"
+
+#include <type_traits>
+#include <utility>
+
+namespace trdq {
+namespace gemm {
+
+namespace {
+
+constexpr int kWideBM = 256;                 // tokens per tile
+constexpr int kWideBN = 256;                 // output channels per tile
+constexpr int kWideBK = 128;                 // bytes of k per k-tile (two matrix-instruction k-steps)
+constexpr int kWideStage = (kWideBM + kWideBN) * kWideBK;   // 64 KB: [tokens 256 x 128][channels 256 x 128]
+constexpr int kWideLds = 2 * kWideStage;
+
+#define TRDQ_WIDE_CLOBBERS \
+    "v108", "v109", "v110", "v111", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", \
+    "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "v128", "v129", "v130", "v131", \
+    "v132", "v133", "v134", "v135", "v136", "v137", "v138", "v139", "v140", "v141", "v142", "v143", \
+    "v144", "v145", "v146", "v147", "v148", "v149", "v150", "v151", "v152", "v153", "v154", "v155", \
+    "v156", "v157", "v158", "v159", "v160", "v161", "v162", "v163", "v164", "v165", "v166", "v167", \
+    "v168", "v169", "v170", "v171", "v172", "v173", "v174", "v175", "v176", "v177", "v178", "v179", \
+    "v180", "v181", "v182", "v183", "v184", "v185", "v186", "v187", "v188", "v189", "v190", "v191", \
+    "v192", "v193", "v194", "v195", "v196", "v197", "v198", "v199", "v200", "v201", "v202", "v203", \
+    "v204", "v205", "v206", "v207", "v208", "v209", "v210", "v211", "v212", "v213", "v214", "v215", \
+    "v216", "v217", "v218", "v219", "v220", "v221", "v222", "v223", "v224", "v225", "v226", "v227", \
+    "v228", "v229", "v230", "v231", "v232", "v233", "v234", "v235", "v236", "v237", "v238", "v239", \
+    "v240", "v241", "v242", "v243", "v244", "v245", "v246", "v247", "v248", "v249", "v250", "v251", \
+    "v252", "v253", "v254", "v255", "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", \
+    "a10", "a11", "a12", "a13", "a14", "a15", "a16", "a17", "a18", "a19", "a20", "a21", "a22", \
+    "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31", "a32", "a33", "a34", "a35", \
+    "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47", "a48", \
+    "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", \
+    "a62", "a63", "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", \
+    "a75", "a76", "a77", "a78", "a79", "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", \
+    "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95", "a96", "a97", "a98", "a99", "a100", \
+    "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111", "a112", \
+    "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", \
+    "a125", "a126", "a127", "a128", "a129", "a130", "a131", "a132", "a133", "a134", "a135", "a136", \
+    "a137", "a138", "a139", "a140", "a141", "a142", "a143", "a144", "a145", "a146", "a147", "a148", \
+    "a149", "a150", "a151", "a152", "a153", "a154", "a155", "a156", "a157", "a158", "a159", "a160", \
+    "a161", "a162", "a163", "a164", "a165", "a166", "a167", "a168", "a169", "a170", "a171", "a172", \
+    "a173", "a174", "a175", "a176", "a177", "a178", "a179", "a180", "a181", "a182", "a183", "a184", \
+    "a185", "a186", "a187", "a188", "a189", "a190", "a191", "a192", "a193", "a194", "a195", "a196", \
+    "a197", "a198", "a199", "a200", "a201", "a202", "a203", "a204", "a205", "a206", "a207", "a208", \
+    "a209", "a210", "a211", "a212", "a213", "a214", "a215", "a216", "a217", "a218", "a219", "a220", \
+    "a221", "a222", "a223", "a224", "a225", "a226", "a227", "a228", "a229", "a230", "a231", "a232", \
+    "a233", "a234", "a235", "a236", "a237", "a238", "a239", "a240", "a241", "a242", "a243", "a244", \
+    "a245", "a246", "a247", "a248", "a249", "a250", "a251", "a252", "a253", "a254", "a255"
+
+template <int... Is, class F>
+__device__ __forceinline__ void static_for(std::integer_sequence<int, Is...>, F &&f)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+
+template <int IDX>
+__device__ __forceinline__ int acc_read()
+{
+    int v;
+    asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(v) : "n"(IDX));
+    return v;
+}
+
+// LDS layout of a stage: row r of an operand at r * 128, its 16-byte chunk c at ((c ^ swizzle(r)) * 16).
+// A copy instruction moves 8 rows x 128 B: lane -> row lane / 8, chunk lane % 8 (LDS side is linear).
+// Wave w copies rows 64 w .. 64 w + 63 of both operands, 8 instructions each.
+//
+// Pipeline (k-tile q of a tile, h = k-step inside it), two stages:
+//   step A(q): multiply fragments (q,0); read fragments (q,1) from stage q
+//   step B(q): wait for k-tile q+1 (copied during B(q-1)), barrier, multiply fragments (q,1),
+//              read fragments (q+1,0) from the other stage, copy k-tile q+2 into stage q
+// The copy stream runs on into the next tile of the workgroup, so the block ends with that
+// tile's first two k-tiles landed; the block itself ends with vmcnt(0).
+template <bool DEBUG, bool FULL>
+__global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t *)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;          // token half, channel half of the wave
+    const int l16 = lane & 15, lg = lane >> 4;
+    const int K = g.K;
+    const int KT = K / kWideBK;                       // >= 2 (checked by the launcher)
+    const int ntiles = g.tiles_m * g.tiles_n;
+
+    // copies: row of this lane inside the tile (first of the wave's 8 instructions) and chunk
+    // offsets for even / odd instructions (rows 8 apart differ in bit 3, which the swizzle uses)
+    const int lr = lane >> 3;
+    const int rl = wave * 64 + lr;
+    const int c0 = ((lane & 7) ^ chunk_swizzle<128>(lr)) * 16;
+    const int c1 = ((lane & 7) ^ chunk_swizzle<128>(lr + 8)) * 16;
+    // fragment reads: h = 0, 1 -> chunks lg and 4 + lg of row l16 (+16 per fragment)
+    const int sw16 = chunk_swizzle<128>(l16);
+    const uint32_t xo0 = lds0 + ((wm * 128 + l16) * 8 + (lg ^ sw16)) * 16;
+    const uint32_t xo1 = lds0 + ((wm * 128 + l16) * 8 + ((4 + lg) ^ sw16)) * 16;
+    const uint32_t wo0 = xo0 - (wm * 128) * 128 + kWideBM * kWideBK + (wn * 128) * 128;
+    const uint32_t wo1 = xo1 - (wm * 128) * 128 + kWideBM * kWideBK + (wn * 128) * 128;
+    const uint32_t wv = lds0 + wave * 8192;
+
+    auto tile_origin = [&](int L, int64_t &m0, int &n0) {
+        int tm, tn;
+        tile_map(L, g.tiles_m, g.tiles_n, tm, tn);
+        m0 = (int64_t)tm * kWideBM;
+        n0 = tn * kWideBN;
+    };
+    auto last_row_x = [&](int64_t m0) { return (int)((g.M - 1 - m0) < 255 ? (g.M - 1 - m0) : 255); };
+    auto last_row_w = [&](int n0) { return (g.N - 1 - n0) < 255 ? (g.N - 1 - n0) : 255; };
+
+    int L = blockIdx.x;
+    int64_t m0; int n0;
+    tile_origin(L, m0, n0);
+    int mxc = last_row_x(m0), mwc = last_row_w(n0);
+    const int8_t *wbase = static_cast<const int8_t *>(g.Wc);
+    uint64_t xp = (uint64_t)(g.Xq + m0 * K);
+    uint64_t wp = (uint64_t)(wbase + (int64_t)n0 * K);
+
+    // first two k-tiles of the first tile
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int rx = (rl + 8 * i) < mxc ? (rl + 8 * i) : mxc;
+            dma_1k((uint32_t)(rx * K + ((i & 1) ? c1 : c0) + t * kWideBK), (const void *)xp,
+                   lds0 + t * kWideStage + wave * 8192 + i * 1024);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int rw = (rl + 8 * i) < mwc ? (rl + 8 * i) : mwc;
+            dma_1k((uint32_t)(rw * K + ((i & 1) ? c1 : c0) + t * kWideBK), (const void *)wp,
+                   lds0 + t * kWideStage + kWideBM * kWideBK + wave * 8192 + i * 1024);
+        }
+    }
+    wait_vmcnt<0>();
+
+    uint32_t st = 0;                                  // LDS offset of the stage holding k-tile q
+    for (; L < ntiles; L += gridDim.x) {
+        const int Ln = L + gridDim.x;
+        int64_t m1; int n1;
+        tile_origin(Ln < ntiles ? Ln : L, m1, n1);    // after the last tile: re-read it (unused)
+        const int mxn = last_row_x(m1), mwn = last_row_w(n1);
+        const uint64_t xn = (uint64_t)(g.Xq + m1 * K);
+        const uint64_t wnx = (uint64_t)(wbase + (int64_t)n1 * K);
+
+        // epilogue operands, requested before the k-loop
+        const int64_t m_lane = m0 + wm * 128 + l16;
+        const int n_lane = n0 + wn * 128 + lg * 4;
+        float sxm[8];
+        float4 swv[8], biv[8];
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const int64_t m = m_lane + b * 16;
+            sxm[b] = (FULL || m < g.M) ? g.sx[m] : 0.0f;
+        }
+#pragma unroll
+        for (int a = 0; a < 8; ++a) {
+            const int n = n_lane + a * 16;
+            swv[a] = biv[a] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (FULL || n < g.N) {
+                swv[a] = *reinterpret_cast<const float4 *>(g.sw + n);
+                if (g.bias) biv[a] = *reinterpret_cast<const float4 *>(g.bias + n);
+            }
+        }
+
+        uint32_t rem = (uint32_t)__builtin_amdgcn_readfirstlane(KT - 2);   // k-tiles of this tile still to copy
+        const uint32_t ktm = rem;                                           // middle iterations of the k-loop
+        uint32_t t0, cnt;
+        asm volatile(R"(
+  .macro TRDQ_VOFFS maxx, maxw, ce, co
+    .irp i,0,2,4,6
+      v_add_u32 v126, \i*8, %[rl]
+      v_min_u32 v127, \maxx, v126
+      v_min_u32 v126, \maxw, v126
+      v_mad_u32_u24 v[108+\i], v127, %[K], \ce
+      v_mad_u32_u24 v[116+\i], v126, %[K], \ce
+    .endr
+    .irp i,1,3,5,7
+      v_add_u32 v126, \i*8, %[rl]
+      v_min_u32 v127, \maxx, v126
+      v_min_u32 v126, \maxw, v126
+      v_mad_u32_u24 v[108+\i], v127, %[K], \co
+      v_mad_u32_u24 v[116+\i], v126, %[K], \co
+    .endr
+  .endm
+  .macro TRDQ_READ set, r, vax, vaw
+    .if (\r) < 8
+      ds_read_b128 v[128+(\set)*64+(\r)*4:128+(\set)*64+(\r)*4+3], \vaw offset:(\r)*2048
+    .else
+      ds_read_b128 v[160+(\set)*64+((\r)-8)*4:160+(\set)*64+((\r)-8)*4+3], \vax offset:((\r)-8)*2048
+    .endif
+  .endm
+  .macro TRDQ_COPY d
+    .if (\d) < 8
+      global_load_lds_dwordx4 v[108+(\d)], %[xp]
+    .else
+      global_load_lds_dwordx4 v[108+(\d)], %[wp]
+    .endif
+  .endm
+  .macro TRDQ_KSTEP set, first, rd, cp, vax, vaw
+    .set trdq_n, 0
+    .rept 64
+      .if \first
+        v_mfma_i32_16x16x64_i8 a[trdq_n*4:trdq_n*4+3], v[128+\set*64+(trdq_n/8)*4:128+\set*64+(trdq_n/8)*4+3], v[160+\set*64+(trdq_n%%8)*4:160+\set*64+(trdq_n%%8)*4+3], 0
+      .else
+        v_mfma_i32_16x16x64_i8 a[trdq_n*4:trdq_n*4+3], v[128+\set*64+(trdq_n/8)*4:128+\set*64+(trdq_n/8)*4+3], v[160+\set*64+(trdq_n%%8)*4:160+\set*64+(trdq_n%%8)*4+3], a[trdq_n*4:trdq_n*4+3]
+      .endif
+      .if \rd && ((trdq_n %% 2) == 0) && (trdq_n < 32)
+        TRDQ_READ 1-\set, trdq_n/2, \vax, \vaw
+      .endif
+      .if \cp && ((trdq_n %% 4) == 0) && (trdq_n > 0)
+        .if trdq_n == 32
+          s_add_u32 m0, m0, 25600
+        .else
+          s_add_u32 m0, m0, 1024
+        .endif
+      .endif
+      .if \cp && ((trdq_n %% 4) == 1)
+        TRDQ_COPY trdq_n/4
+      .endif
+      .set trdq_n, trdq_n+1
+    .endr
+  .endm
+  .macro TRDQ_ASTEP first
+    v_add_u32 v126, %[st], %[xo1]
+    v_add_u32 v127, %[st], %[wo1]
+    s_waitcnt lgkmcnt(0)
+    TRDQ_KSTEP 0, \first, 1, 0, v126, v127
+  .endm
+  .macro TRDQ_BSTEP wait, rd
+    s_cmp_eq_u32 %[rem], 0
+    s_cbranch_scc0 .Ltrdq_same\@_%=
+    s_mov_b64 %[xp], %[xn]
+    s_mov_b64 %[wp], %[wn]
+    TRDQ_VOFFS %[mxn], %[mwn], %[c0], %[c1]
+.Ltrdq_same\@_%=:
+    s_sub_u32 %[rem], %[rem], 1
+    s_xor_b32 %[t0], %[st], 0x10000
+    v_add_u32 v124, %[t0], %[xo0]
+    v_add_u32 v125, %[t0], %[wo0]
+    .if \wait
+      s_waitcnt vmcnt(0)
+    .endif
+    s_waitcnt lgkmcnt(0)
+    s_barrier
+    s_add_u32 m0, %[st], %[wv]
+    TRDQ_KSTEP 1, 0, \rd, 1, v124, v125
+    .irp i,108,109,110,111,112,113,114,115,116,117,118,119,120,121,122,123
+      v_add_u32 v\i, 0x80, v\i
+    .endr
+    s_mov_b32 %[st], %[t0]
+  .endm
+
+  TRDQ_VOFFS %[mxc], %[mwc], %[c0e], %[c1e]
+  s_barrier
+  v_add_u32 v124, %[st], %[xo0]
+  v_add_u32 v125, %[st], %[wo0]
+  .set trdq_r, 0
+  .rept 16
+    TRDQ_READ 0, trdq_r, v124, v125
+    .set trdq_r, trdq_r+1
+  .endr
+  TRDQ_ASTEP 1
+  TRDQ_BSTEP 0, 1
+  s_cmp_eq_u32 %[ktm], 0
+  s_cbranch_scc1 .Ltrdq_tail_%=
+  s_mov_b32 %[cnt], %[ktm]
+.Ltrdq_loop_%=:
+  TRDQ_ASTEP 0
+  TRDQ_BSTEP 1, 1
+  s_sub_u32 %[cnt], %[cnt], 1
+  s_cmp_lg_u32 %[cnt], 0
+  s_cbranch_scc1 .Ltrdq_loop_%=
+.Ltrdq_tail_%=:
+  TRDQ_ASTEP 0
+  TRDQ_BSTEP 0, 0
+  s_waitcnt vmcnt(0)
+  s_nop 7
+  s_nop 7
+  .purgem TRDQ_VOFFS
+  .purgem TRDQ_READ
+  .purgem TRDQ_COPY
+  .purgem TRDQ_KSTEP
+  .purgem TRDQ_ASTEP
+  .purgem TRDQ_BSTEP
+)"
+                     // every operand the block writes is early-clobber: an input of equal value
+                     // (ktm starts equal to rem) must not share its register
+                     : [xp] "+&s"(xp), [wp] "+&s"(wp), [rem] "+&s"(rem), [st] "+&s"(st), [t0] "=&s"(t0), [cnt] "=&s"(cnt)
+                     : [xn] "s"(xn), [wn] "s"(wnx),
+                       [mxc] "s"(__builtin_amdgcn_readfirstlane(mxc)), [mwc] "s"(__builtin_amdgcn_readfirstlane(mwc)),
+                       [mxn] "s"(__builtin_amdgcn_readfirstlane(mxn)), [mwn] "s"(__builtin_amdgcn_readfirstlane(mwn)),
+                       [K] "s"(__builtin_amdgcn_readfirstlane(K)), [wv] "s"(__builtin_amdgcn_readfirstlane(wv)),
+                       [ktm] "s"(ktm),
+                       [rl] "v"(rl), [c0] "v"(c0), [c1] "v"(c1), [c0e] "v"(c0 + 2 * kWideBK), [c1e] "v"(c1 + 2 * kWideBK),
+                       [xo0] "v"(xo0), [xo1] "v"(xo1), [wo0] "v"(wo0), [wo1] "v"(wo1)
+                     : "memory", "scc", "m0", TRDQ_WIDE_CLOBBERS);
+
+        // epilogue: y = float(acc) * s_x[m] * s_w[n] + bias[n] -> bf16; the lane holds channels
+        // n .. n+3 of token m for each of the 8 x 8 instruction tiles
+        static_for(std::make_integer_sequence<int, 8>{}, [&](auto ai) {
+            constexpr int a = decltype(ai)::value;
+            const int n = n_lane + a * 16;
+            const bool n_ok = FULL || n < g.N;
+            static_for(std::make_integer_sequence<int, 8>{}, [&](auto bi) {
+                constexpr int b = decltype(bi)::value;
+                constexpr int idx = (a * 8 + b) * 4;
+                const int64_t m = m_lane + b * 16;
+                const int q0 = acc_read<idx>(), q1 = acc_read<idx + 1>(), q2 = acc_read<idx + 2>(),
+                          q3 = acc_read<idx + 3>();
+                const float y0 = (float)q0 * sxm[b] * swv[a].x + biv[a].x;
+                const float y1 = (float)q1 * sxm[b] * swv[a].y + biv[a].y;
+                const float y2 = (float)q2 * sxm[b] * swv[a].z + biv[a].z;
+                const float y3 = (float)q3 * sxm[b] * swv[a].w + biv[a].w;
+                uint2 o;
+                o.x = pack_bf16x2(y0, y1);
+                o.y = pack_bf16x2(y2, y3);
+                if (FULL || (n_ok && m < g.M)) {
+                    if constexpr (DEBUG)
+                        *reinterpret_cast<int4 *>(g.acc_debug + m * g.N + n) = make_int4(q0, q1, q2, q3);
+                    *reinterpret_cast<uint2 *>(g.Y + m * g.ldy + n) = o;
+                }
+            });
+        });
+
+        m0 = m1; n0 = n1; mxc = mxn; mwc = mwn;
+    }
+}
+
+template <bool DEBUG, bool FULL>
+hipError_t launch_wide(const GemmArgs &a, hipStream_t st)
+{
+    static bool done = false;
+    GemmArgs g = a;
+    g.tiles_m = (int)((g.M + kWideBM - 1) / kWideBM);
+    g.tiles_n = (g.N + kWideBN - 1) / kWideBN;
+    auto kern = qgemm8_wide_kernel<DEBUG, FULL>;
+    if (!done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWideLds);
+        if (e != hipSuccess) return e;
+        done = true;
+    }
+    int grid = 256;
+    if (grid > g.tiles_m * g.tiles_n) grid = g.tiles_m * g.tiles_n;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kWideLds, st, g);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// k-tiles of 128 and at least two of them; 24-bit multiplies form the copy offsets
+bool wide_supports(const GemmArgs &a)
+{
+    return a.M > 0 && a.K % kWideBK == 0 && a.K >= 2 * kWideBK && a.K < (1 << 22) && a.N % 4 == 0;
+}
+
+hipError_t launch_qgemm8_wide(const GemmArgs &a, bool debug, hipStream_t st)
+{
+    if (!wide_supports(a)) return hipErrorInvalidValue;
+    const bool full = a.M % kWideBM == 0 && a.N % kWideBN == 0;
+    if (debug) return full ? launch_wide<true, true>(a, st) : launch_wide<true, false>(a, st);
+    return full ? launch_wide<false, true>(a, st) : launch_wide<false, false>(a, st);
+}
+
+}  // namespace gemm
+}  // namespace trdq
