@@ -62,6 +62,60 @@ __device__ __forceinline__ void epilogue_w8(const v4i (&acc)[TN][TM], const Gemm
     }
 }
 
+// Row-wise epilogue for full tiles.  Storing straight from the accumulator layout gives every
+// token row 32 contiguous bytes per instruction, and partial-line writes reach only about half
+// of the store bandwidth of full lines.  Here each wave first lays its WM x WN block of bf16
+// results out in LDS (its own region: no workgroup barrier, LDS serves a wave's requests in
+// order), then reads it back row by row, so that one store instruction writes whole
+// WN * 2-byte row segments (128 B for a 64-channel wave tile), 16 bytes per lane.
+// `stage` is the wave's private LDS region of WM rows of WN * 2 + 16 bytes (the pad spreads the
+// column-wise writes over the banks).
+template <int TN, int TM, bool DEBUG>
+__device__ __forceinline__ void epilogue_w8_rows(const v4i (&acc)[TN][TM], const GemmArgs &g,
+                                                 int64_t m_wave, int n_wave, int lane, int8_t *stage)
+{
+    constexpr int WN = TN * 16, WM = TM * 16;
+    constexpr int ROWB = WN * 2 + 16;
+    constexpr int LPR = WN / 8;                  // lanes per row on the way out
+    constexpr int RPI = 64 / LPR;                // rows per store instruction
+    const int l16 = lane & 15, lg = lane >> 4;
+    float sxm[TM];
+#pragma unroll
+    for (int b = 0; b < TM; ++b) sxm[b] = g.sx[m_wave + b * 16 + l16];
+    const bool has_bias = g.bias != nullptr;
+#pragma unroll
+    for (int a = 0; a < TN; ++a) {
+        const int n = n_wave + a * 16 + lg * 4;
+        const float4 s = *reinterpret_cast<const float4 *>(g.sw + n);
+        float4 bi = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (has_bias) bi = *reinterpret_cast<const float4 *>(g.bias + n);
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+            if constexpr (DEBUG) {
+                const int64_t m = m_wave + b * 16 + l16;
+                *reinterpret_cast<int4 *>(g.acc_debug + m * g.N + n) =
+                    make_int4(acc[a][b][0], acc[a][b][1], acc[a][b][2], acc[a][b][3]);
+            }
+            const float y0 = (float)acc[a][b][0] * sxm[b] * s.x + bi.x;
+            const float y1 = (float)acc[a][b][1] * sxm[b] * s.y + bi.y;
+            const float y2 = (float)acc[a][b][2] * sxm[b] * s.z + bi.z;
+            const float y3 = (float)acc[a][b][3] * sxm[b] * s.w + bi.w;
+            uint2 o;
+            o.x = pack_bf16x2(y0, y1);
+            o.y = pack_bf16x2(y2, y3);
+            *reinterpret_cast<uint2 *>(stage + (b * 16 + l16) * ROWB + (a * 16 + lg * 4) * 2) = o;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();             // compiler: keep the reads below after the writes above
+    const int r0 = lane / LPR, c = lane % LPR;
+#pragma unroll
+    for (int i = 0; i < WM / RPI; ++i) {
+        const int row = i * RPI + r0;
+        const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * ROWB + c * 16);
+        *reinterpret_cast<uint4 *>(g.Y + (m_wave + row) * g.ldy + n_wave + c * 8) = v;
+    }
+}
+
 // Conditional forms whose branch lives inside the assembly block, so that the caller's loop
 // body stays one basic block for the compiler (`on` / `steady` are wave-uniform).
 __device__ __forceinline__ void dma_1k_if(int on, uint32_t voff, const void *sbase, uint32_t lds_addr)
@@ -330,7 +384,13 @@ __global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
     interleave_hint<TN + TM, TN * TM>();
     mfma_block<TN, TM>(acc, af1, bf1);
 
-    epilogue_w8<TN, TM, DEBUG, true>(acc, g, m0 + wm * WM + l16, n0 + wn * WN + lg * 4);
+    if constexpr (4 * WM * (WN * 2 + 16) <= NS * STAGE) {
+        // every wave is done with the ring: reuse it as the epilogue's staging space
+        __syncthreads();
+        epilogue_w8_rows<TN, TM, DEBUG>(acc, g, m0 + wm * WM, n0 + wn * WN, lane, smem + wave * (WM * (WN * 2 + 16)));
+    } else {
+        epilogue_w8<TN, TM, DEBUG, true>(acc, g, m0 + wm * WM + l16, n0 + wn * WN + lg * 4);
+    }
 }
 
 // ---- persistent software-pipelined kernel -------------------------------------------------------

@@ -5,8 +5,8 @@
 // register file allows (four waves, each 128 channels x 128 tokens = 256 accumulator registers),
 // which halves the operand bytes per operation of a 128 x 128 tile.  One wave per SIMD means
 // nothing else hides instruction-issue bubbles, so the k-loop is written in assembly: 64 matrix
-// instructions per 64-deep k-step with the 16 LDS fragment reads of the next step and the 16
-// direct-to-LDS copies of a later k-tile placed between them at fixed intervals, accumulators in
+// instructions per 64-deep k-step with the 16 LDS fragment reads of the next step and the 8
+// direct-to-LDS copies of a later k-step placed between them at fixed intervals, accumulators in
 // the accumulation registers a0-a255, fragments double-buffered in v128-v255.
 //
 // Operation: Y = dequant(Xq . Wq^T) of Eq. 10's quantised product, per-token and per-channel
@@ -23,9 +23,10 @@ namespace {
 
 constexpr int kWideBM = 256;                 // tokens per tile
 constexpr int kWideBN = 256;                 // output channels per tile
-constexpr int kWideBK = 128;                 // bytes of k per k-tile (two matrix-instruction k-steps)
-constexpr int kWideStage = (kWideBM + kWideBN) * kWideBK;   // 64 KB: [tokens 256 x 128][channels 256 x 128]
-constexpr int kWideLds = 2 * kWideStage;
+constexpr int kWideBK = 64;                  // bytes of k per k-step (one matrix instruction deep)
+constexpr int kWideSlot = (kWideBM + kWideBN) * kWideBK;    // 32 KB: [tokens 256 x 64][channels 256 x 64]
+constexpr int kWideSlots = 4;
+constexpr int kWideLds = kWideSlots * kWideSlot;            // 128 KB, a power of two (the ring wraps with a mask)
 
 #define TRDQ_WIDE_CLOBBERS \
     "v108", "v109", "v110", "v111", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", \
@@ -76,16 +77,17 @@ __device__ __forceinline__ int acc_read()
     return v;
 }
 
-// LDS layout of a stage: row r of an operand at r * 128, its 16-byte chunk c at ((c ^ swizzle(r)) * 16).
-// A copy instruction moves 8 rows x 128 B: lane -> row lane / 8, chunk lane % 8 (LDS side is linear).
-// Wave w copies rows 64 w .. 64 w + 63 of both operands, 8 instructions each.
+// LDS ring of four 32 KB slots, one per k-step: row r of an operand at r * 64, its 16-byte
+// chunk c at ((c ^ swizzle(r)) * 16).  A copy instruction moves 16 rows x 64 B: lane -> row
+// lane / 4, chunk lane % 4 (the LDS side is linear).  Wave w copies rows 64 w .. 64 w + 63 of
+// both operands, 4 instructions each per k-step.
 //
-// Pipeline (k-tile q of a tile, h = k-step inside it), two stages:
-//   step A(q): multiply fragments (q,0); read fragments (q,1) from stage q
-//   step B(q): wait for k-tile q+1 (copied during B(q-1)), barrier, multiply fragments (q,1),
-//              read fragments (q+1,0) from the other stage, copy k-tile q+2 into stage q
-// The copy stream runs on into the next tile of the workgroup, so the block ends with that
-// tile's first two k-tiles landed; the block itself ends with vmcnt(0).
+// Pipeline, k-step s of a tile (fragment set s % 2):
+//   wait for the copies of k-step s+1 (issued at s-3), barrier (slot s is free, slot s+1 is
+//   complete), then 64 matrix instructions on set s % 2 with, between them, the 16 fragment
+//   reads of k-step s+1 into the other set and the 8 copies of k-step s+4 into slot s.
+// The copy stream runs on into the next tile of the workgroup; the block ends with vmcnt(0), so
+// the next tile's first four k-steps have landed when its block starts.
 template <bool DEBUG, bool FULL>
 __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
 {
@@ -98,22 +100,19 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
     const int wm = wave & 1, wn = wave >> 1;          // token half, channel half of the wave
     const int l16 = lane & 15, lg = lane >> 4;
     const int K = g.K;
-    const int KT = K / kWideBK;                       // >= 2 (checked by the launcher)
+    const int KS = K / kWideBK;                       // k-steps per tile: even, >= 4 (checked by the launcher)
     const int ntiles = g.tiles_m * g.tiles_n;
 
-    // copies: row of this lane inside the tile (first of the wave's 8 instructions) and chunk
-    // offsets for even / odd instructions (rows 8 apart differ in bit 3, which the swizzle uses)
-    const int lr = lane >> 3;
+    // copies: row of this lane inside the tile (first of the wave's 4 instructions; the others
+    // are 16 rows apart, which leaves row % 16 and so the swizzle unchanged) and chunk offset
+    const int lr = lane >> 2;
     const int rl = wave * 64 + lr;
-    const int c0 = ((lane & 7) ^ chunk_swizzle<128>(lr)) * 16;
-    const int c1 = ((lane & 7) ^ chunk_swizzle<128>(lr + 8)) * 16;
-    // fragment reads: h = 0, 1 -> chunks lg and 4 + lg of row l16 (+16 per fragment)
-    const int sw16 = chunk_swizzle<128>(l16);
-    const uint32_t xo0 = lds0 + ((wm * 128 + l16) * 8 + (lg ^ sw16)) * 16;
-    const uint32_t xo1 = lds0 + ((wm * 128 + l16) * 8 + ((4 + lg) ^ sw16)) * 16;
-    const uint32_t wo0 = xo0 - (wm * 128) * 128 + kWideBM * kWideBK + (wn * 128) * 128;
-    const uint32_t wo1 = xo1 - (wm * 128) * 128 + kWideBM * kWideBK + (wn * 128) * 128;
-    const uint32_t wv = lds0 + wave * 8192;
+    const int c0 = ((lane & 3) ^ chunk_swizzle<64>(lr)) * 16;
+    // fragment reads: chunk lg of row l16 (+16 rows per fragment)
+    const int sw16 = chunk_swizzle<64>(l16);
+    const uint32_t xo = lds0 + ((wm * 128 + l16) * 4 + (lg ^ sw16)) * 16;
+    const uint32_t wo = lds0 + kWideBM * kWideBK + ((wn * 128 + l16) * 4 + (lg ^ sw16)) * 16;
+    const uint32_t wv = lds0 + wave * 4096;
 
     auto tile_origin = [&](int L, int64_t &m0, int &n0) {
         int tm, tn;
@@ -132,25 +131,25 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
     uint64_t xp = (uint64_t)(g.Xq + m0 * K);
     uint64_t wp = (uint64_t)(wbase + (int64_t)n0 * K);
 
-    // first two k-tiles of the first tile
+    // first four k-steps of the first tile
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < kWideSlots; ++t) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int rx = (rl + 8 * i) < mxc ? (rl + 8 * i) : mxc;
-            dma_1k((uint32_t)(rx * K + ((i & 1) ? c1 : c0) + t * kWideBK), (const void *)xp,
-                   lds0 + t * kWideStage + wave * 8192 + i * 1024);
+        for (int i = 0; i < 4; ++i) {
+            const int rx = (rl + 16 * i) < mxc ? (rl + 16 * i) : mxc;
+            dma_1k((uint32_t)(rx * K + c0 + t * kWideBK), (const void *)xp,
+                   lds0 + t * kWideSlot + wave * 4096 + i * 1024);
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int rw = (rl + 8 * i) < mwc ? (rl + 8 * i) : mwc;
-            dma_1k((uint32_t)(rw * K + ((i & 1) ? c1 : c0) + t * kWideBK), (const void *)wp,
-                   lds0 + t * kWideStage + kWideBM * kWideBK + wave * 8192 + i * 1024);
+        for (int i = 0; i < 4; ++i) {
+            const int rw = (rl + 16 * i) < mwc ? (rl + 16 * i) : mwc;
+            dma_1k((uint32_t)(rw * K + c0 + t * kWideBK), (const void *)wp,
+                   lds0 + t * kWideSlot + kWideBM * kWideBK + wave * 4096 + i * 1024);
         }
     }
     wait_vmcnt<0>();
 
-    uint32_t st = 0;                                  // LDS offset of the stage holding k-tile q
+    uint32_t st = 0;                                  // LDS offset of the slot of k-step s
     for (; L < ntiles; L += gridDim.x) {
         const int Ln = L + gridDim.x;
         int64_t m1; int n1;
@@ -179,41 +178,51 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
             }
         }
 
-        uint32_t rem = (uint32_t)__builtin_amdgcn_readfirstlane(KT - 2);   // k-tiles of this tile still to copy
-        const uint32_t ktm = rem;                                           // middle iterations of the k-loop
+        uint32_t rem = (uint32_t)__builtin_amdgcn_readfirstlane(KS - 4);   // k-steps of this tile still to copy
+        const uint32_t pairs = (uint32_t)__builtin_amdgcn_readfirstlane((KS - 4) / 2);   // k-steps 3 .. KS-2, two per iteration
         uint32_t t0, cnt;
         asm volatile(R"(
-  .macro TRDQ_VOFFS maxx, maxw, ce, co
-    .irp i,0,2,4,6
-      v_add_u32 v126, \i*8, %[rl]
+  .macro TRDQ_VOFFS maxx, maxw, ce
+    .irp i,0,1,2,3
+      v_add_u32 v126, \i*16, %[rl]
       v_min_u32 v127, \maxx, v126
       v_min_u32 v126, \maxw, v126
       v_mad_u32_u24 v[108+\i], v127, %[K], \ce
-      v_mad_u32_u24 v[116+\i], v126, %[K], \ce
-    .endr
-    .irp i,1,3,5,7
-      v_add_u32 v126, \i*8, %[rl]
-      v_min_u32 v127, \maxx, v126
-      v_min_u32 v126, \maxw, v126
-      v_mad_u32_u24 v[108+\i], v127, %[K], \co
-      v_mad_u32_u24 v[116+\i], v126, %[K], \co
+      v_mad_u32_u24 v[112+\i], v126, %[K], \ce
     .endr
   .endm
   .macro TRDQ_READ set, r, vax, vaw
     .if (\r) < 8
-      ds_read_b128 v[128+(\set)*64+(\r)*4:128+(\set)*64+(\r)*4+3], \vaw offset:(\r)*2048
+      ds_read_b128 v[128+(\set)*64+(\r)*4:128+(\set)*64+(\r)*4+3], \vaw offset:(\r)*1024
     .else
-      ds_read_b128 v[160+(\set)*64+((\r)-8)*4:160+(\set)*64+((\r)-8)*4+3], \vax offset:((\r)-8)*2048
+      ds_read_b128 v[160+(\set)*64+((\r)-8)*4:160+(\set)*64+((\r)-8)*4+3], \vax offset:((\r)-8)*1024
     .endif
   .endm
   .macro TRDQ_COPY d
-    .if (\d) < 8
+    .if (\d) < 4
       global_load_lds_dwordx4 v[108+(\d)], %[xp]
     .else
       global_load_lds_dwordx4 v[108+(\d)], %[wp]
     .endif
   .endm
-  .macro TRDQ_KSTEP set, first, rd, cp, vax, vaw
+  .macro TRDQ_STEP set, first, rd, wait, vax, vaw
+    s_cmp_eq_u32 %[rem], 0
+    s_cbranch_scc0 .Ltrdq_same\@_%=
+    s_mov_b64 %[xp], %[xn]
+    s_mov_b64 %[wp], %[wn]
+    TRDQ_VOFFS %[mxn], %[mwn], %[c0]
+.Ltrdq_same\@_%=:
+    s_sub_u32 %[rem], %[rem], 1
+    s_add_u32 %[t0], %[st], 0x8000
+    s_and_b32 %[t0], %[t0], 0x1ffff
+    v_add_u32 \vax, %[t0], %[xo]
+    v_add_u32 \vaw, %[t0], %[wo]
+    .if \wait
+      s_waitcnt vmcnt(16)
+    .endif
+    s_waitcnt lgkmcnt(0)
+    s_barrier
+    s_add_u32 m0, %[st], %[wv]
     .set trdq_n, 0
     .rept 64
       .if \first
@@ -224,92 +233,65 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
       .if \rd && ((trdq_n %% 2) == 0) && (trdq_n < 32)
         TRDQ_READ 1-\set, trdq_n/2, \vax, \vaw
       .endif
-      .if \cp && ((trdq_n %% 4) == 0) && (trdq_n > 0)
-        .if trdq_n == 32
-          s_add_u32 m0, m0, 25600
+      .if ((trdq_n %% 4) == 0) && (trdq_n > 0) && (trdq_n < 32)
+        .if trdq_n == 16
+          s_add_u32 m0, m0, 13312
         .else
           s_add_u32 m0, m0, 1024
         .endif
       .endif
-      .if \cp && ((trdq_n %% 4) == 1)
+      .if ((trdq_n %% 4) == 1) && (trdq_n < 32)
         TRDQ_COPY trdq_n/4
       .endif
       .set trdq_n, trdq_n+1
     .endr
-  .endm
-  .macro TRDQ_ASTEP first
-    v_add_u32 v126, %[st], %[xo1]
-    v_add_u32 v127, %[st], %[wo1]
-    s_waitcnt lgkmcnt(0)
-    TRDQ_KSTEP 0, \first, 1, 0, v126, v127
-  .endm
-  .macro TRDQ_BSTEP wait, rd
-    s_cmp_eq_u32 %[rem], 0
-    s_cbranch_scc0 .Ltrdq_same\@_%=
-    s_mov_b64 %[xp], %[xn]
-    s_mov_b64 %[wp], %[wn]
-    TRDQ_VOFFS %[mxn], %[mwn], %[c0], %[c1]
-.Ltrdq_same\@_%=:
-    s_sub_u32 %[rem], %[rem], 1
-    s_xor_b32 %[t0], %[st], 0x10000
-    v_add_u32 v124, %[t0], %[xo0]
-    v_add_u32 v125, %[t0], %[wo0]
-    .if \wait
-      s_waitcnt vmcnt(0)
-    .endif
-    s_waitcnt lgkmcnt(0)
-    s_barrier
-    s_add_u32 m0, %[st], %[wv]
-    TRDQ_KSTEP 1, 0, \rd, 1, v124, v125
-    .irp i,108,109,110,111,112,113,114,115,116,117,118,119,120,121,122,123
-      v_add_u32 v\i, 0x80, v\i
+    .irp i,108,109,110,111,112,113,114,115
+      v_add_u32 v\i, 64, v\i
     .endr
     s_mov_b32 %[st], %[t0]
   .endm
 
-  TRDQ_VOFFS %[mxc], %[mwc], %[c0e], %[c1e]
+  TRDQ_VOFFS %[mxc], %[mwc], %[c0e]
   s_barrier
-  v_add_u32 v124, %[st], %[xo0]
-  v_add_u32 v125, %[st], %[wo0]
+  v_add_u32 v124, %[st], %[xo]
+  v_add_u32 v125, %[st], %[wo]
   .set trdq_r, 0
   .rept 16
     TRDQ_READ 0, trdq_r, v124, v125
     .set trdq_r, trdq_r+1
   .endr
-  TRDQ_ASTEP 1
-  TRDQ_BSTEP 0, 1
-  s_cmp_eq_u32 %[ktm], 0
+  TRDQ_STEP 0, 1, 1, 0, v122, v123
+  TRDQ_STEP 1, 0, 1, 0, v124, v125
+  TRDQ_STEP 0, 0, 1, 0, v122, v123
+  s_cmp_eq_u32 %[pairs], 0
   s_cbranch_scc1 .Ltrdq_tail_%=
-  s_mov_b32 %[cnt], %[ktm]
+  s_mov_b32 %[cnt], %[pairs]
 .Ltrdq_loop_%=:
-  TRDQ_ASTEP 0
-  TRDQ_BSTEP 1, 1
+  TRDQ_STEP 1, 0, 1, 1, v124, v125
+  TRDQ_STEP 0, 0, 1, 1, v122, v123
   s_sub_u32 %[cnt], %[cnt], 1
   s_cmp_lg_u32 %[cnt], 0
   s_cbranch_scc1 .Ltrdq_loop_%=
 .Ltrdq_tail_%=:
-  TRDQ_ASTEP 0
-  TRDQ_BSTEP 0, 0
+  TRDQ_STEP 1, 0, 0, 0, v124, v125
   s_waitcnt vmcnt(0)
   s_nop 7
   s_nop 7
   .purgem TRDQ_VOFFS
   .purgem TRDQ_READ
   .purgem TRDQ_COPY
-  .purgem TRDQ_KSTEP
-  .purgem TRDQ_ASTEP
-  .purgem TRDQ_BSTEP
+  .purgem TRDQ_STEP
 )"
                      // every operand the block writes is early-clobber: an input of equal value
-                     // (ktm starts equal to rem) must not share its register
+                     // must not share its register
                      : [xp] "+&s"(xp), [wp] "+&s"(wp), [rem] "+&s"(rem), [st] "+&s"(st), [t0] "=&s"(t0), [cnt] "=&s"(cnt)
                      : [xn] "s"(xn), [wn] "s"(wnx),
                        [mxc] "s"(__builtin_amdgcn_readfirstlane(mxc)), [mwc] "s"(__builtin_amdgcn_readfirstlane(mwc)),
                        [mxn] "s"(__builtin_amdgcn_readfirstlane(mxn)), [mwn] "s"(__builtin_amdgcn_readfirstlane(mwn)),
                        [K] "s"(__builtin_amdgcn_readfirstlane(K)), [wv] "s"(__builtin_amdgcn_readfirstlane(wv)),
-                       [ktm] "s"(ktm),
-                       [rl] "v"(rl), [c0] "v"(c0), [c1] "v"(c1), [c0e] "v"(c0 + 2 * kWideBK), [c1e] "v"(c1 + 2 * kWideBK),
-                       [xo0] "v"(xo0), [xo1] "v"(xo1), [wo0] "v"(wo0), [wo1] "v"(wo1)
+                       [pairs] "s"(pairs),
+                       [rl] "v"(rl), [c0] "v"(c0), [c0e] "v"(c0 + kWideSlots * kWideBK),
+                       [xo] "v"(xo), [wo] "v"(wo)
                      : "memory", "scc", "m0", TRDQ_WIDE_CLOBBERS);
 
         // epilogue: y = float(acc) * s_x[m] * s_w[n] + bias[n] -> bf16; the lane holds channels
@@ -365,10 +347,10 @@ hipError_t launch_wide(const GemmArgs &a, hipStream_t st)
 
 }  // namespace
 
-// k-tiles of 128 and at least two of them; 24-bit multiplies form the copy offsets
+// an even number of k-steps, at least four; 24-bit multiplies form the copy offsets
 bool wide_supports(const GemmArgs &a)
 {
-    return a.M > 0 && a.K % kWideBK == 0 && a.K >= 2 * kWideBK && a.K < (1 << 22) && a.N % 4 == 0;
+    return a.M > 0 && a.K % (2 * kWideBK) == 0 && a.K >= kWideSlots * kWideBK && a.K < (1 << 22) && a.N % 4 == 0;
 }
 
 hipError_t launch_qgemm8_wide(const GemmArgs &a, bool debug, hipStream_t st)
