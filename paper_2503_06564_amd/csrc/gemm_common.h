@@ -92,6 +92,10 @@ __device__ __forceinline__ void wait_vmcnt()
 int dma_num_variants();
 hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStream_t st);
 
+// int4-weight kernels on the same path (qgemm_dma.hip).
+int dma4_num_variants();
+hipError_t launch_qgemm4_dma(const GemmArgs &a, bool debug, int variant, hipStream_t st);
+
 // 256 x 256 tile kernel with a hand-scheduled main loop (qgemm_wide.hip).
 bool wide_supports(const GemmArgs &a);
 hipError_t launch_qgemm8_wide(const GemmArgs &a, bool debug, hipStream_t st);

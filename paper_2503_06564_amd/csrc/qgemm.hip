@@ -268,9 +268,12 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int
     const bool dbg = acc_debug != nullptr;
     if (w.wbits == 4) {
         // int4 keeps a second (float) accumulator set: smaller tiles, BK = one scale group
+        // variants 1 and 5: register-staged; 6, 7: direct-to-LDS (6 is the built-in choice)
         switch (variant) {
+            case 1: return launch_cfg<128, 128, 128, 2, 2, true>(a, dbg, st);
             case 5: return launch_cfg<64, 128, 128, 1, 4, true>(a, dbg, st);
-            default: return launch_cfg<128, 128, 128, 2, 2, true>(a, dbg, st);
+            case 7: return launch_qgemm4_dma(a, dbg, 1, st);
+            default: return launch_qgemm4_dma(a, dbg, 0, st);
         }
     }
     // built-in choice: the software-pipelined 128x128 kernel, two workgroups per compute unit

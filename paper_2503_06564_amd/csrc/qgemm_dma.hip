@@ -399,21 +399,6 @@ __global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
 // copied, the epilogue's stores overlap the next tile's main loop, and a second workgroup on
 // the same compute unit fills the matrix cores while this one converts and stores.
 
-// 16-byte load issued from assembly (kept out of the compiler's vmcnt bookkeeping, like the
-// LDS copies): the value is valid once a later hand-placed vmcnt wait has covered it.
-__device__ __forceinline__ float4 asm_load16(const void *p)
-{
-    float4 v;
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
-    return v;
-}
-__device__ __forceinline__ float asm_load4(const void *p)
-{
-    float v;
-    asm volatile("global_load_dword %0, %1, off" : "=v"(v) : "v"(p) : "memory");
-    return v;
-}
-
 // waits for vmcnt(NBIG) / vmcnt(N) / vmcnt(0) for sel = 2 / 1 / 0 (sel is wave-uniform)
 template <int N, int NBIG>
 __device__ __forceinline__ void wait_vmcnt_select(int sel)
@@ -515,19 +500,8 @@ __global__ __launch_bounds__(kThreads) void qgemm8_persist_kernel(GemmArgs g)
         const int8_t *xnext = g.Xq + (m1 + wave * PX * 8) * K;
         const int8_t *wnext = static_cast<const int8_t *>(g.Wc) + ((size_t)n1 + wave * PW * 8) * K;
 
-        // epilogue operands, requested now (older than every copy of this tile, so the first
-        // vmcnt wait of the k-loop covers them) and used after the k-loop
         const int64_t m_lane = m0 + wm * WM + l16;
         const int n_lane = n0 + wn * WN + lg * 4;
-        float sxm[TM];
-        float4 swv[TN], biv[TN];
-#pragma unroll
-        for (int b = 0; b < TM; ++b) sxm[b] = asm_load4(g.sx + m_lane + b * 16);
-#pragma unroll
-        for (int a = 0; a < TN; ++a) {
-            swv[a] = asm_load16(g.sw + n_lane + a * 16);
-            biv[a] = g.bias ? asm_load16(g.bias + n_lane + a * 16) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
 
         v4i acc[TN][TM];
 #pragma unroll
@@ -559,7 +533,19 @@ __global__ __launch_bounds__(kThreads) void qgemm8_persist_kernel(GemmArgs g)
             st = nst;
         }
 
-        // epilogue (full tiles only on this path): y = float(acc) * s_x * s_w + bias -> bf16
+        // epilogue (full tiles only on this path): y = float(acc) * s_x * s_w + bias -> bf16.
+        // Its operands are ordinary loads: the compiler's own wait for them also covers the
+        // copies already requested for the next tile, which costs a little overlap and keeps
+        // every register the loads write under the compiler's control.
+        float sxm[TM];
+        float4 swv[TN], biv[TN];
+#pragma unroll
+        for (int b = 0; b < TM; ++b) sxm[b] = g.sx[m_lane + b * 16];
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+            swv[a] = *reinterpret_cast<const float4 *>(g.sw + n_lane + a * 16);
+            biv[a] = g.bias ? *reinterpret_cast<const float4 *>(g.bias + n_lane + a * 16) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
 #pragma unroll
         for (int a = 0; a < TN; ++a) {
             const int n = n_lane + a * 16;
@@ -585,6 +571,198 @@ __global__ __launch_bounds__(kThreads) void qgemm8_persist_kernel(GemmArgs g)
     }
 }
 
+// ---- int4 weights on the direct-to-LDS path --------------------------------------------------------
+// Activations as in the int8 kernels (128-byte k-tiles, 8 rows per copy).  A weight row of a
+// k-tile is 64 packed bytes (one 128-channel scale group), 16 rows per copy; the lane reads the
+// 8 packed bytes of its 16 codes and widens them in registers to 16 * code (nibble moved to the
+// top of the byte: one shift-and-mask and one mask per 8 codes).  At the end of every k-tile the
+// int32 sums of the group are folded into float accumulators with the group's scales
+// (Eq. 1 per 128-input group); the factor 16 is undone with the token scale in the epilogue.
+//
+// The group's 128 scales travel with the k-tile: one more direct-to-LDS copy per wave (4 bytes
+// per lane; waves 2 and 3 write a second, unused copy so that every wave issues the same number
+// of requests and the hand-kept vmcnt arithmetic stays uniform).  Past the last k-tile the last
+// one is copied again, for the same reason.
+template <int BM, int BN, int NS, int WGM, int WGN, bool DEBUG>
+__global__ __launch_bounds__(kThreads) void qgemm4_ring_kernel(GemmArgs g)
+{
+    static_assert(WGM * WGN == 4, "four waves per workgroup");
+    static_assert(NS >= 2, "at least two stages");
+    constexpr int BK = 128;                           // = one int4 scale group
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int TM = WM / 16, TN = WN / 16;
+    constexpr int XBYTES = BM * BK, WBYTES = BN * (BK / 2), SOFF = XBYTES + WBYTES;
+    constexpr int STAGE = SOFF + 1024;                // + [2][BN] scales
+    constexpr int PX = XBYTES / 4096, PW = WBYTES / 4096;
+    constexpr int P = PX + PW + 1;                    // copies per wave and k-tile
+    static_assert(BN == 128, "one scale copy of 64 lanes per channel half");
+    static_assert(PX >= 1 && PW >= 1 && (NS - 2) * P < 64, "request counts");
+
+    extern __shared__ __align__(16) int8_t smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t *)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int l16 = lane & 15, lg = lane >> 4;
+
+    int tm_idx, tn_idx;
+    tile_map(blockIdx.x, g.tiles_m, g.tiles_n, tm_idx, tn_idx);
+    const int64_t m0 = (int64_t)tm_idx * BM;
+    const int n0 = tn_idx * BN;
+    const int K = g.K;
+    const int KT = K / BK;
+
+    // copy plan (rows past the matrix edge are clamped: loaded, never stored)
+    uint32_t voffx[PX], voffw[PW];
+#pragma unroll
+    for (int i = 0; i < PX; ++i) {
+        const int slot = (wave * PX + i) * 64 + lane;
+        const int row = slot / 8, c = (slot % 8) ^ chunk_swizzle<128>(row);
+        int64_t m = m0 + row;
+        if (m >= g.M) m = g.M - 1;
+        voffx[i] = (uint32_t)((m - m0) * K + c * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < PW; ++i) {
+        const int slot = (wave * PW + i) * 64 + lane;
+        const int row = slot / 4, c = (slot % 4) ^ ((row >> 2) & 3);   // 64-byte rows: spread rows r, r+4, r+8, r+12
+        int n = n0 + row;
+        if (n >= g.N) n = g.N - 1;
+        voffw[i] = (uint32_t)((n - n0) * (K / 2) + c * 16);
+    }
+    int ns = n0 + (wave & 1) * 64 + lane;
+    if (ns >= g.N) ns = g.N - 1;
+    const uint32_t voffs = (uint32_t)((ns - n0) * 4);
+    const int8_t *xbase = g.Xq + m0 * K;
+    const uint8_t *wbase = static_cast<const uint8_t *>(g.Wc) + (size_t)n0 * (K / 2);
+    const float *sbase_g = g.sw + n0;
+    auto issue = [&](int kt, int st) {
+        const uint32_t sbase = lds0 + st * STAGE;
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                     :: "v"(voffs), "s"(sbase_g + (size_t)kt * g.N), "s"(sbase + SOFF + wave * 256) : "memory");
+#pragma unroll
+        for (int i = 0; i < PX; ++i) dma_1k(voffx[i], xbase + kt * BK, sbase + (wave * PX + i) * 1024);
+#pragma unroll
+        for (int i = 0; i < PW; ++i) dma_1k(voffw[i], wbase + kt * (BK / 2), sbase + XBYTES + (wave * PW + i) * 1024);
+    };
+
+    // fragment read offsets inside a stage, per matrix-instruction k-step h
+    int xoff[2], woff[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        xoff[h] = ((wm * WM + l16) * 8 + ((4 * h + lg) ^ chunk_swizzle<128>(l16))) * 16;
+        woff[h] = XBYTES + (wn * WN + l16) * 64 + ((2 * h + (lg >> 1)) ^ ((l16 >> 2) & 3)) * 16 + (lg & 1) * 8;
+    }
+
+    const int n_lane = n0 + wn * WN + lg * 4;         // lane's channels: four per tile a
+    const int soff = SOFF + (wn * WN + lg * 4) * 4;   // their scales inside a stage
+
+    v4i acc[TN][TM];
+    v4f facc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b) { acc[a][b] = v4i{0, 0, 0, 0}; facc[a][b] = v4f{0.f, 0.f, 0.f, 0.f}; }
+
+    // prologue: k-tiles 0 .. NS-2
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t) issue(t < KT ? t : KT - 1, t);
+
+    int st = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+        wait_vmcnt<(NS - 2) * P>();                   // this wave's share of k-tile kt has landed
+        __syncthreads();                              // ... everyone's; the stage of k-tile kt-1 is free
+        const int nk = kt + NS - 1;
+        issue(nk < KT ? nk : KT - 1, st == 0 ? NS - 1 : st - 1);
+
+        const int8_t *stage = smem + st * STAGE;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            v4i af[TN], bf[TM];
+#pragma unroll
+            for (int a = 0; a < TN; ++a) {
+                const uint2 p = *reinterpret_cast<const uint2 *>(stage + woff[h] + a * 16 * 64);
+                af[a] = v4i{(int)((p.x << 4) & 0xF0F0F0F0u), (int)(p.x & 0xF0F0F0F0u),
+                            (int)((p.y << 4) & 0xF0F0F0F0u), (int)(p.y & 0xF0F0F0F0u)};
+            }
+#pragma unroll
+            for (int b = 0; b < TM; ++b) bf[b] = *reinterpret_cast<const v4i *>(stage + xoff[h] + b * 16 * BK);
+#pragma unroll
+            for (int a = 0; a < TN; ++a)
+#pragma unroll
+                for (int b = 0; b < TM; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[a], bf[b], acc[a][b], 0, 0, 0);
+        }
+
+        // end of scale group kt: facc += s_w[kt][n] * (16 * sum)
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+            const float4 sca = *reinterpret_cast<const float4 *>(stage + soff + a * 64);
+#pragma unroll
+            for (int b = 0; b < TM; ++b) {
+                if constexpr (DEBUG) {
+                    const int64_t m = m0 + wm * WM + b * 16 + l16;
+                    const int n = n_lane + a * 16;
+                    if (m < g.M && n < g.N)
+                        *reinterpret_cast<int4 *>(g.acc_debug + ((int64_t)kt * g.M + m) * g.N + n) =
+                            make_int4(acc[a][b][0] >> 4, acc[a][b][1] >> 4, acc[a][b][2] >> 4, acc[a][b][3] >> 4);
+                }
+                facc[a][b][0] += sca.x * (float)acc[a][b][0];
+                facc[a][b][1] += sca.y * (float)acc[a][b][1];
+                facc[a][b][2] += sca.z * (float)acc[a][b][2];
+                facc[a][b][3] += sca.w * (float)acc[a][b][3];
+                acc[a][b] = v4i{0, 0, 0, 0};
+            }
+        }
+        st = (st + 1 == NS) ? 0 : st + 1;
+    }
+    wait_vmcnt<0>();                                  // the repeated copies of the last steps
+
+    // epilogue: y = (s_x / 16) * facc + bias -> bf16
+    const int64_t m_lane = m0 + wm * WM + l16;
+    float sxm[TM];
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+        const int64_t m = m_lane + b * 16;
+        sxm[b] = m < g.M ? g.sx[m] * 0.0625f : 0.0f;
+    }
+    const bool full = m0 + BM <= g.M && n0 + BN <= g.N;      // workgroup-uniform
+    constexpr int ROWB = WN * 2 + 16;
+    if (full) __syncthreads();                        // the ring becomes the staging space below
+    int8_t *const stg = smem + wave * (WM * ROWB);
+    static_assert(4 * WM * (WN * 2 + 16) <= NS * STAGE, "staging space fits in the ring");
+#pragma unroll
+    for (int a = 0; a < TN; ++a) {
+        const int n = n_lane + a * 16;
+        const bool n_ok = n < g.N;
+        float4 bi = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (g.bias && n_ok) bi = *reinterpret_cast<const float4 *>(g.bias + n);
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+            const int64_t m = m_lane + b * 16;
+            uint2 o;
+            o.x = pack_bf16x2(sxm[b] * facc[a][b][0] + bi.x, sxm[b] * facc[a][b][1] + bi.y);
+            o.y = pack_bf16x2(sxm[b] * facc[a][b][2] + bi.z, sxm[b] * facc[a][b][3] + bi.w);
+            if (full) *reinterpret_cast<uint2 *>(stg + (b * 16 + l16) * ROWB + (a * 16 + lg * 4) * 2) = o;
+            else if (n_ok && m < g.M) *reinterpret_cast<uint2 *>(g.Y + m * g.ldy + n) = o;
+        }
+    }
+    if (full) {
+        // whole row segments, 16 bytes per lane (see epilogue_w8_rows)
+        __builtin_amdgcn_wave_barrier();
+        constexpr int LPR = WN / 8, RPI = 64 / LPR;
+        const int r0 = lane / LPR, c = lane % LPR;
+#pragma unroll
+        for (int i = 0; i < WM / RPI; ++i) {
+            const int row = i * RPI + r0;
+            const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * ROWB + c * 16);
+            *reinterpret_cast<uint4 *>(g.Y + (m0 + wm * WM + row) * g.ldy + n0 + wn * WN + c * 8) = v;
+        }
+    }
+}
+
 template <typename Kern>
 hipError_t launch_kernel(Kern kern, bool &attr_done, const GemmArgs &a, int BM, int BN, size_t smem, hipStream_t st)
 {
@@ -599,6 +777,15 @@ hipError_t launch_kernel(Kern kern, bool &attr_done, const GemmArgs &a, int BM, 
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(kThreads), smem, st, g);
     return hipGetLastError();
+}
+
+template <int BM, int BN, int NS, int WGM, int WGN>
+hipError_t launch_ring4(const GemmArgs &a, bool debug, hipStream_t st)
+{
+    static bool done[2] = {false, false};
+    const size_t smem = (size_t)NS * (BM * 128 + BN * 64 + 1024);
+    if (debug) return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, true>, done[1], a, BM, BN, smem, st);
+    return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st);
 }
 
 template <int BM, int BN, int BK, int NS, int WGM, int WGN>
@@ -646,6 +833,19 @@ hipError_t launch_persist(const GemmArgs &a, bool debug, hipStream_t st)
 }
 
 }  // namespace
+
+// int4 weights: 0: 128x128 NS3 (two workgroups per compute unit)   1: 128x128 NS2 (three)
+int dma4_num_variants() { return 2; }
+
+hipError_t launch_qgemm4_dma(const GemmArgs &a, bool debug, int variant, hipStream_t st)
+{
+    if (a.K % 128 != 0 || a.N < 4) return hipErrorInvalidValue;
+    switch (variant) {
+        case 0: return launch_ring4<128, 128, 3, 2, 2>(a, debug, st);
+        case 1: return launch_ring4<128, 128, 2, 2, 2>(a, debug, st);
+    }
+    return hipErrorInvalidValue;
+}
 
 // ring: 0: 128x128x64 NS4   1: 256x128x64 NS4   2: 128x256x64 NS4   3: 128x128x128 NS3   4: 256x128x128 NS3
 // pipe: 5: 256x128 NS3   6: 128x128 NS4   7: 128x256 NS3   8: 256x256 NS2   9: 128x128 NS2

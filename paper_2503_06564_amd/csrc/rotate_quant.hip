@@ -196,6 +196,10 @@ hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx,
     // three blocks per wave (two or one for narrow rows), then rebalance; workgroups of up to
     // 12 waves, as many per compute unit as 12 resident waves allow
     int spw = nb < 3 ? nb : 3;
+    // few token groups (less than two workgroups per compute unit): spread each row over more
+    // waves instead, so that the loads in flight still cover the memory latency
+    const int64_t groups = (M + kTokensPerWG - 1) / kTokensPerWG;
+    while (spw > 1 && groups * ((nb + spw - 1) / spw) < 256 * 8 && (nb + spw - 2) / (spw - 1) <= 12) --spw;
     const int nw = (nb + spw - 1) / spw;
     spw = (nb + nw - 1) / nw;
     const int wgs = 12 / nw > 0 ? 12 / nw : 1;

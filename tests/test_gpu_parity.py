@@ -177,10 +177,17 @@ def test_qgemm_w8_persistent_many_tiles(oracle, M, K, N, variant):
 
 
 @pytest.mark.parametrize("M,K,N", GEMM_SHAPES)
-@pytest.mark.parametrize("variant", [1, 5])
+@pytest.mark.parametrize("variant", [1, 5, 6, 7])
 def test_qgemm_w4_all_variants(oracle, M, K, N, variant):
     say(f"qgemm W4 M={M} K={K} N={N} variant={variant}")
     _linear_case(oracle, 8, M, K, N, 4, variant)
+
+
+@pytest.mark.parametrize("M,K,N", PIPE_SHAPES)
+@pytest.mark.parametrize("variant", [6, 7])
+def test_qgemm_w4_direct_to_lds_full_tiles(oracle, M, K, N, variant):
+    say(f"qgemm W4 direct-to-LDS M={M} K={K} N={N} variant={variant}")
+    _linear_case(oracle, 14, M, K, N, 4, variant)
 
 
 @pytest.mark.parametrize("wbits", [8, 4])
@@ -281,3 +288,43 @@ def test_layer_time_step_groups(oracle, wbits, fused):
         layer.forward(5, X, Y, fused=fused, Xq_ws=Xq_ws, sx_ws=sx_ws)
     assert e.value.status == trdq.ERR_MISMATCH
     layer.close()
+
+
+def test_graph_replay_matches_host_launches(oracle):
+    """rotate_quant + qgemm captured into a HIP graph: every replay, with host-launched work and
+    synchronisations between the replays, gives the bits of the host-launched path."""
+    say("graph replay of rotate_quant + qgemm")
+    M, K, N = 512, 1152, 1152
+    trdq.qgemm_set_variant(-1)
+    inputs = [wl.small_case(21 + i, M, K, N, n_outliers=8) for i in range(3)]
+    Xb0, W, d, bias = inputs[0]
+    w = trdq.prepare_weights(gu.f32_to_dev(W), gu.f32_to_dev(d), wbits=8)
+    dd, bb = gu.f32_to_dev(d), gu.f32_to_dev(bias)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        X = gu.bf16_to_dev(Xb0).clone()
+        Xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+        sx = torch.empty((M,), dtype=torch.float32, device="cuda")
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        rq = trdq.bind_rotate_quant(X, dd, Xq, sx, stream=s)
+        mm = trdq.bind_qgemm(w, Xq, sx, Y, bias=bb, stream=s)
+        rq(); mm()                      # warm-up outside the capture (one-time kernel attributes)
+        s.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            rq(); mm()
+        for Xb, _, _, _ in inputs:
+            X.copy_(gu.bf16_to_dev(Xb))
+            Y.zero_(); Xq.zero_()       # host-launched work between the replays
+            g.replay()
+            s.synchronize()
+            got = (Xq.clone(), sx.clone(), Y.clone())
+            Y.zero_(); Xq.zero_()
+            rq(); mm()
+            s.synchronize()
+            assert torch.equal(got[0], Xq) and torch.equal(got[1], sx) and torch.equal(got[2], Y)
+    ref = oracle.linear(inputs[-1][0], W, d, bias, wbits=8, exact_blas=True)
+    Wq_h, _ = w.export()
+    gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], "Y (graph replay, oracle end to end)",
+                      (Xq.cpu().numpy() != ref["Xq"]).any(axis=1), (Wq_h != ref["Wq"]).any(axis=0))
+    w.close()
