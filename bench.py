@@ -36,8 +36,10 @@ def parse():
     ap.add_argument("--no-events", action="store_true", help="no per-kernel events in the timed region")
     ap.add_argument("--event-every", type=int, default=8,
                     help="bracket the kernels with events on every n-th timed step (keeps the probe effect small)")
-    ap.add_argument("--no-graph", action="store_true",
-                    help="launch every kernel from the host instead of replaying one captured HIP graph per step")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay one captured HIP graph per step instead of launching every kernel from the host "
+                         "(same kernels; measured to make no difference here: the step is GPU-bound, and the "
+                         "profiler's kernel trace does not list kernels launched from a graph)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU work budget of the oracle's timed sample")
     ap.add_argument("--variant", type=int, default=-1, help="qgemm tile variant override")
@@ -94,6 +96,38 @@ def committed_traffic(workload):
     except OSError:
         pass
     return None
+
+
+class HipEvent:
+    """A timing event without the system-scope fence that a default event carries: a default
+    event makes the device flush its caches for the host before the next kernel may start, about
+    5 us per event here, which would land inside every bracketed interval."""
+    _hip = None
+    DISABLE_SYSTEM_FENCE = 0x20000000        # hipEventDisableSystemFence
+
+    def __init__(self):
+        import ctypes
+        if HipEvent._hip is None:
+            hip = ctypes.CDLL("libamdhip64.so")
+            hip.hipEventCreateWithFlags.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint]
+            hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+            hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+            hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+            HipEvent._hip = hip
+        self.h = ctypes.c_void_p()
+        rc = HipEvent._hip.hipEventCreateWithFlags(ctypes.byref(self.h), HipEvent.DISABLE_SYSTEM_FENCE)
+        assert rc == 0, f"hipEventCreateWithFlags: {rc}"
+
+    def record(self, stream):
+        rc = HipEvent._hip.hipEventRecord(self.h, stream.cuda_stream)
+        assert rc == 0, f"hipEventRecord: {rc}"
+
+    def elapsed_time(self, other):
+        import ctypes
+        ms = ctypes.c_float()
+        rc = HipEvent._hip.hipEventElapsedTime(ctypes.byref(ms), self.h, other.h)
+        assert rc == 0, f"hipEventElapsedTime: {rc}"
+        return ms.value
 
 
 def main():
@@ -157,9 +191,9 @@ def main():
                 calls[g, kind] = (trdq.bind_rotate_quant(X[kind, g], D[kind, g], Xq[kind], SX[kind], stream=stream),
                                   trdq.bind_qgemm(Wh[kind, g], Xq[kind], SX[kind], Y[kind], bias=B[kind],
                                                   stream=stream))
-    n_ev = len(cfg.kinds) * (2 if args.fused else 3)
+    n_ev = len(cfg.kinds) * (2 if args.fused else 3) + 1      # + one event right after the last, see below
     every = max(1, args.event_every)
-    events = {st: [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
+    events = {st: [HipEvent() for _ in range(n_ev)]
               for st in range(0, args.steps, every)} if use_events else {}
     ev = []     # (name, kind, start, end)
 
@@ -183,6 +217,11 @@ def main():
                     ev.append(("rotate_quant", kind, evs[i], evs[i + 1]))
                     ev.append(("qgemm", kind, evs[i + 1], evs[i + 2]))
                 i += len(fns) + 1
+        if record:
+            # an empty interval: what one event record costs the stream by itself.  The same cost
+            # sits between the opening event of a bracket and the start of its kernel.
+            evs[i].record(stream)
+            ev.append(("empty", "-", evs[i - 1], evs[i]))
 
     for s in range(args.warmup):
         run_step(s, False)
@@ -192,7 +231,7 @@ def main():
     # the host's per-launch cost does not throttle kernels of 10-30 us.  Steps that carry events are
     # launched from the host as before (same kernels, same arguments).
     graphs = {}
-    if not args.no_graph:
+    if args.graph:
         for g in range(n_groups):
             gr = torch.cuda.CUDAGraph()
             with torch.cuda.graph(gr, stream=stream):
@@ -236,6 +275,10 @@ def main():
         for name, kind, a, b in ev:
             per.setdefault((name, kind), []).append(a.elapsed_time(b) * 1e-3)
         kern = {}
+        empty = per.pop(("empty", "-"), [0.0])
+        ev_cost = sum(empty) / len(empty)
+        for (name, kind), ts in per.items():
+            per[name, kind] = ts = [max(t - ev_cost, 0.0) for t in ts]
         for (name, kind), ts in per.items():
             avg = sum(ts) / len(ts)
             entry = {"avg_us": avg * 1e6, "launches": len(ts)}
@@ -255,8 +298,11 @@ def main():
         out["roofline"] = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS,
                            "unit": "TOP/s", "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None,
                            "avg_launch_us": tot_t / n_launch * 1e6, "launches": n_launch,
+                           "event_cost_us": ev_cost * 1e6,
                            "timed_on": f"every {every}th of the {args.steps} timed steps (launched from the host, "
-                                       "the others replay a captured graph), events on the launch stream",
+                                       "the others replay a captured graph if --graph), events on the launch stream; "
+                                       "event_cost_us, the length of an empty event-to-event interval "
+                                       "measured in the same steps, is subtracted from every bracket",
                            "ops_per_launch": tot_ops / n_launch}
         if not args.fused:
             rq_t = sum(sum(ts) for (name, _), ts in per.items() if name == "rotate_quant")

@@ -277,8 +277,16 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int
         }
     }
     // built-in choice: the software-pipelined 128x128 kernel, two workgroups per compute unit
-    // (it hands ragged shapes to the ring kernel itself)
-    if (variant < 0) variant = kRegVariants + 9;
+    // (it hands ragged shapes to the ring kernel itself); 128x144 tiles with a four-stage ring,
+    // one workgroup per compute unit, where the deeper prefetch pays: long K, or so few tiles
+    // that one round of them covers the chip anyway
+    if (variant < 0) {
+        variant = kRegVariants + 9;
+        if (a.N % 144 == 0 && M % 128 == 0 && a.K >= 512) {
+            const int64_t tiles = (M / 128) * (a.N / 144);
+            if (a.K >= 2304 || tiles <= 256) variant = kRegVariants + 14;
+        }
+    }
     switch (variant) {
         case 0: return launch_cfg<128, 128, 64, 2, 2, false>(a, dbg, st);
         case 1: return launch_cfg<128, 128, 128, 2, 2, false>(a, dbg, st);

@@ -77,7 +77,6 @@ __device__ __forceinline__ void epilogue_w8_rows(const v4i (&acc)[TN][TM], const
     constexpr int WN = TN * 16, WM = TM * 16;
     constexpr int ROWB = WN * 2 + 16;
     constexpr int LPR = WN / 8;                  // lanes per row on the way out
-    constexpr int RPI = 64 / LPR;                // rows per store instruction
     const int l16 = lane & 15, lg = lane >> 4;
     float sxm[TM];
 #pragma unroll
@@ -107,12 +106,15 @@ __device__ __forceinline__ void epilogue_w8_rows(const v4i (&acc)[TN][TM], const
         }
     }
     __builtin_amdgcn_wave_barrier();             // compiler: keep the reads below after the writes above
-    const int r0 = lane / LPR, c = lane % LPR;
+    constexpr int CHUNKS = WM * LPR;             // 16-byte pieces of the block, row-major
 #pragma unroll
-    for (int i = 0; i < WM / RPI; ++i) {
-        const int row = i * RPI + r0;
-        const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * ROWB + c * 16);
-        *reinterpret_cast<uint4 *>(g.Y + (m_wave + row) * g.ldy + n_wave + c * 8) = v;
+    for (int i = 0; i < (CHUNKS + 63) / 64; ++i) {
+        const int id = i * 64 + lane;
+        const int row = id / LPR, c = id % LPR;
+        if (CHUNKS % 64 == 0 || id < CHUNKS) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * ROWB + c * 16);
+            *reinterpret_cast<uint4 *>(g.Y + (m_wave + row) * g.ldy + n_wave + c * 8) = v;
+        }
     }
 }
 
@@ -293,10 +295,15 @@ __global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int TM = WM / 16, TN = WN / 16;
     constexpr int CPR = BK / 16;
-    constexpr int XBYTES = BM * BK, WBYTES = BN * BK, STAGE = XBYTES + WBYTES;
-    constexpr int PX = XBYTES / 4096, PW = WBYTES / 4096;
+    // weight rows are copied 8 at a time; a channel count that does not split evenly over the
+    // four waves (BN = 144: 18 copies) is rounded up, the surplus copies repeat the last rows
+    // into LDS space nobody reads
+    constexpr int WG8 = BN / 8;                       // 8-row groups of weight rows
+    constexpr int XBYTES = BM * BK;
+    constexpr int PX = XBYTES / 4096, PW = (WG8 + 3) / 4;
+    constexpr int WBYTES = 4 * PW * 1024, STAGE = XBYTES + WBYTES;
     constexpr int P = PX + PW;
-    static_assert(PX >= 1 && PW >= 1 && (NS - 1) * P < 64, "copy count per wave out of range");
+    static_assert(BN % 16 == 0 && PX >= 1 && PX % 2 == 0 && (NS - 1) * P < 64, "copy count per wave out of range");
 
     extern __shared__ __align__(16) int8_t smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t *)smem;
@@ -317,7 +324,6 @@ __global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
     // fills LDS rows (wave*PX + i)*8 .. +7, eight 16-byte chunks each; the lane's row inside
     // the 16-row swizzle period only depends on the parity of i, so two lane offsets per
     // operand are enough and the rest of the address is scalar.
-    static_assert(PX % 2 == 0 && PW % 2 == 0, "even copy counts");
     uint32_t voff[2];
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
@@ -325,8 +331,18 @@ __global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
         voff[p] = (uint32_t)(r * K + (((lane & 7) ^ chunk_swizzle<BK>(r)) * 16));
     }
     const int8_t *xbase = g.Xq + (m0 + wave * PX * 8) * K;
-    const int8_t *wbase = static_cast<const int8_t *>(g.Wc) + ((size_t)n0 + wave * PW * 8) * K;
+    const int8_t *wbase = static_cast<const int8_t *>(g.Wc) + (size_t)n0 * K;
     const int K16 = 16 * K;
+    // weight copy i of this wave: 8-row group j = wave * PW + i (clamped to the last group)
+    uint32_t voffw[PW];
+    int wrow[PW];
+#pragma unroll
+    for (int i = 0; i < PW; ++i) {
+        int j = wave * PW + i;
+        if (j > WG8 - 1) j = WG8 - 1;
+        voffw[i] = voff[j & 1];
+        wrow[i] = __builtin_amdgcn_readfirstlane((j & ~1) * 8);
+    }
 
     auto issue = [&](int on, int kt, int st) {
         const uint32_t sbase = lds0 + st * STAGE;
@@ -336,7 +352,7 @@ __global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
             dma_1k_if(on, voff[i & 1], xs + (i >> 1) * K16, sbase + (wave * PX + i) * 1024);
 #pragma unroll
         for (int i = 0; i < PW; ++i)
-            dma_1k_if(on, voff[i & 1], ws + (i >> 1) * K16, sbase + XBYTES + (wave * PW + i) * 1024);
+            dma_1k_if(on, voffw[i], ws + wrow[i] * K, sbase + XBYTES + (wave * PW + i) * 1024);
     };
 
     int xoff[2], woff[2];
@@ -803,7 +819,7 @@ hipError_t launch_pipe(const GemmArgs &a, bool debug, hipStream_t st)
     // the pipelined kernel takes full tiles only; ragged shapes go to the ring kernel
     if (a.M % BM != 0 || a.N % BN != 0) return launch_ring<128, 128, 64, 4, 2, 2>(a, debug, st);
     static bool done[2] = {false, false};
-    const size_t smem = (size_t)NS * (BM + BN) * 128;
+    const size_t smem = (size_t)NS * (BM * 128 + 4 * ((BN / 8 + 3) / 4) * 1024);
     if (debug) return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, true>, done[1], a, BM, BN, smem, st);
     return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st);
 }
@@ -850,7 +866,8 @@ hipError_t launch_qgemm4_dma(const GemmArgs &a, bool debug, int variant, hipStre
 // ring: 0: 128x128x64 NS4   1: 256x128x64 NS4   2: 128x256x64 NS4   3: 128x128x128 NS3   4: 256x128x128 NS3
 // pipe: 5: 256x128 NS3   6: 128x128 NS4   7: 128x256 NS3   8: 256x256 NS2   9: 128x128 NS2
 // persistent: 10: 128x128 NS2 (2 workgroups per CU)   11: 256x128 NS3   12: 128x256 NS3   13: 128x128 NS4
-int dma_num_variants() { return 14; }
+// pipe, 144-channel tiles (1152 = 8 x 144: the DiT-XL/2 widths give whole rounds of 256 tiles): 14: 128x144 NS4
+int dma_num_variants() { return 15; }
 
 hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStream_t st)
 {
@@ -869,6 +886,7 @@ hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStre
         case 11: return launch_persist<256, 128, 3, 2, 2, 1>(a, debug, st);
         case 12: return launch_persist<128, 256, 3, 2, 2, 1>(a, debug, st);
         case 13: return launch_persist<128, 128, 4, 2, 2, 1>(a, debug, st);
+        case 14: return launch_pipe<128, 144, 4, 4, 1>(a, debug, st);
     }
     return hipErrorInvalidValue;
 }
