@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU work budget of the oracle's timed sample")
     ap.add_argument("--variant", type=int, default=-1, help="qgemm tile variant override")
     ap.add_argument("--groups", type=int, default=0, help="limit the number of groups prepared (0 = all)")
+    ap.add_argument("--no-warm", action="store_true",
+                    help="plain rotate_quant: do not read the following product's weights on the way")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 256 MiB device copy (a kernel of known traffic, to calibrate counters)")
     return ap.parse_args()
@@ -188,7 +190,8 @@ def main():
                 calls[g, kind] = (trdq.bind_linear_fused(X[kind, g], D[kind, g], Wh[kind, g], Y[kind],
                                                          bias=B[kind], stream=stream),)
             else:
-                calls[g, kind] = (trdq.bind_rotate_quant(X[kind, g], D[kind, g], Xq[kind], SX[kind], stream=stream),
+                calls[g, kind] = (trdq.bind_rotate_quant(X[kind, g], D[kind, g], Xq[kind], SX[kind], stream=stream,
+                                                         warm=None if args.no_warm else Wh[kind, g]),
                                   trdq.bind_qgemm(Wh[kind, g], Xq[kind], SX[kind], Y[kind], bias=B[kind],
                                                   stream=stream))
     n_ev = len(cfg.kinds) * (2 if args.fused else 3) + 1      # + one event right after the last, see below

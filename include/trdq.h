@@ -128,6 +128,14 @@ trdq_status trdq_rotate_quant(const void *X_dev, int64_t M, int K, int64_t ldx,
                               const float *diag_dev, int block,
                               int8_t *Xq_dev, float *sx_dev, void *stream);
 
+/* The same pass, which additionally reads the codes of `next` (the weights of the product that
+ * follows; NULL = plain trdq_rotate_quant) once and discards them: a few loads per lane that
+ * nothing waits for, so that trdq_qgemm does not start on weights that are cold in DRAM.
+ * Outputs and errors are those of trdq_rotate_quant; `next` is only read. */
+trdq_status trdq_rotate_quant_warm(const void *X_dev, int64_t M, int K, int64_t ldx,
+                                   const float *diag_dev, int block,
+                                   int8_t *Xq_dev, float *sx_dev, const trdq_weights *next, void *stream);
+
 /* The integer product G_t(X_t) . H_t(W) on the codes, with the dequantising epilogue:
  *   wbits 8: Y[i,n] = bf16( float(acc[i,n]) * s_x[i] * s_w[n] + bias[n] ),  acc = Xq . Wq  (int32, exact)
  *   wbits 4: Y[i,n] = bf16( s_x[i] * sum_g s_w[g,n] * float(acc_g[i,n]) + bias[n] ),

@@ -245,14 +245,28 @@ trdq_status trdq_rotate_quant(const void *X_dev, int64_t M, int K, int64_t ldx,
                               const float *diag_dev, int block,
                               int8_t *Xq_dev, float *sx_dev, void *stream)
 {
+    return trdq_rotate_quant_warm(X_dev, M, K, ldx, diag_dev, block, Xq_dev, sx_dev, nullptr, stream);
+}
+
+trdq_status trdq_rotate_quant_warm(const void *X_dev, int64_t M, int K, int64_t ldx,
+                                   const float *diag_dev, int block,
+                                   int8_t *Xq_dev, float *sx_dev, const trdq_weights *next, void *stream)
+{
     trdq_status rc = check_rotate_args(X_dev, M, K, ldx, block);
     if (rc != TRDQ_OK) return rc;
     if (M > 0 && (!Xq_dev || !sx_dev)) return TRDQ_ERR_NULL;
     if (!aligned(Xq_dev, 8) || !aligned(sx_dev, 4) || (diag_dev && !aligned(diag_dev, 16))) return TRDQ_ERR_SHAPE;
     if (K / trdq::kBlock > 64) return TRDQ_ERR_UNSUPPORTED;
     if (M == 0) return TRDQ_OK;
+    const void *warm = nullptr;
+    int64_t warm_bytes = 0;
+    if (next && next->codes) {
+        warm = next->codes;
+        warm_bytes = (int64_t)next->N * next->K / (next->wbits == 4 ? 2 : 1);
+        warm_bytes -= warm_bytes % 16;
+    }
     return hip_status(trdq::launch_rotate_quant(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev,
-                                                Xq_dev, sx_dev, static_cast<hipStream_t>(stream)));
+                                                Xq_dev, sx_dev, warm, warm_bytes, static_cast<hipStream_t>(stream)));
 }
 
 trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev, int64_t M,
@@ -358,7 +372,7 @@ trdq_status trdq_layer_forward(const trdq_layer *l, int step, const void *X_dev,
     if (fused)
         return trdq_linear_fused(X_dev, M, l->K, d, w, bias_dev, Y_dev, l->N, stream);
     if (!Xq_ws_dev || !sx_ws_dev) return TRDQ_ERR_NULL;
-    trdq_status rc = trdq_rotate_quant(X_dev, M, l->K, l->K, d, trdq::kBlock, Xq_ws_dev, sx_ws_dev, stream);
+    trdq_status rc = trdq_rotate_quant_warm(X_dev, M, l->K, l->K, d, trdq::kBlock, Xq_ws_dev, sx_ws_dev, w, stream);
     if (rc != TRDQ_OK) return rc;
     return trdq_qgemm(w, Xq_ws_dev, sx_ws_dev, M, bias_dev, Y_dev, l->N, nullptr, stream);
 }

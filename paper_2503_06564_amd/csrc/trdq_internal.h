@@ -29,8 +29,10 @@ struct Table {
 };
 
 // Kernel launchers (defined in the .hip files).  All return hipError_t of the launch.
+// warm / warm_bytes: optional device range (16-byte aligned, a multiple of 16 bytes) that the
+// kernel reads once and discards, to pull it into the memory-side cache for the next kernel.
 hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
-                               int8_t *Xq, float *sx, hipStream_t st);
+                               int8_t *Xq, float *sx, const void *warm, int64_t warm_bytes, hipStream_t st);
 hipError_t launch_rotate_quant_wide(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
                                     int8_t *Xq, float *sx, hipStream_t st);
 

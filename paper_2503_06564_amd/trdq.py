@@ -18,7 +18,7 @@ SYMBOLS = [
     "trdq_table_create", "trdq_table_lookup", "trdq_table_sizes", "trdq_table_destroy",
     "trdq_prepare_weights", "trdq_weights_info", "trdq_weights_export",
     "trdq_weights_export_packed", "trdq_weights_nbytes", "trdq_weights_destroy",
-    "trdq_rotate_quant", "trdq_qgemm", "trdq_linear_fused",
+    "trdq_rotate_quant", "trdq_rotate_quant_warm", "trdq_qgemm", "trdq_linear_fused",
     "trdq_layer_create", "trdq_layer_set_group", "trdq_layer_forward", "trdq_layer_weights",
     "trdq_layer_destroy", "trdq_qgemm_set_variant", "trdq_qgemm_num_variants",
 ]
@@ -58,6 +58,7 @@ def lib():
         L.trdq_weights_destroy.argtypes = [p]
         L.trdq_weights_destroy.restype = None
         L.trdq_rotate_quant.argtypes = [p, i64, i32, i64, p, i32, p, p, p]
+        L.trdq_rotate_quant_warm.argtypes = [p, i64, i32, i64, p, i32, p, p, p, p]
         L.trdq_qgemm.argtypes = [p, p, p, i64, p, p, i64, p, p]
         L.trdq_linear_fused.argtypes = [p, i64, i64, p, p, p, p, i64, p]
         L.trdq_layer_create.argtypes = [p, i32, i32, i32, C.POINTER(p)]
@@ -189,12 +190,17 @@ def prepare_weights(W, diag=None, block=BLOCK, wbits=8, stream=None):
 
 # ----------------------------------------------------------------- online
 
-def rotate_quant(X, diag, Xq, sx, block=BLOCK, stream=None):
-    """X: bf16 [M, K] (row stride X.stride(0)); Xq: int8 [M, K]; sx: float32 [M]."""
+def rotate_quant(X, diag, Xq, sx, block=BLOCK, stream=None, warm=None):
+    """X: bf16 [M, K] (row stride X.stride(0)); Xq: int8 [M, K]; sx: float32 [M].
+    warm: the Weights of the product that follows (their codes are read once on the way)."""
     M, K = X.shape
     ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
-    _check(lib().trdq_rotate_quant(_ptr(X), M, K, ldx, _ptr(diag), block, _ptr(Xq), _ptr(sx), _stream(stream)),
-           "trdq_rotate_quant")
+    if warm is None:
+        _check(lib().trdq_rotate_quant(_ptr(X), M, K, ldx, _ptr(diag), block, _ptr(Xq), _ptr(sx), _stream(stream)),
+               "trdq_rotate_quant")
+    else:
+        _check(lib().trdq_rotate_quant_warm(_ptr(X), M, K, ldx, _ptr(diag), block, _ptr(Xq), _ptr(sx), warm.handle,
+                                            _stream(stream)), "trdq_rotate_quant_warm")
 
 
 def qgemm(w, Xq, sx, Y, bias=None, acc_debug=None, stream=None):
@@ -216,17 +222,18 @@ def linear_fused(X, diag, w, Y, bias=None, stream=None):
 # For launch-bound loops: the arguments are converted to ctypes once; calling the returned
 # function performs exactly one C call (same entry points, same semantics).
 
-def bind_rotate_quant(X, diag, Xq, sx, block=BLOCK, stream=None):
+def bind_rotate_quant(X, diag, Xq, sx, block=BLOCK, stream=None, warm=None):
     M, K = X.shape
     ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
-    f = lib().trdq_rotate_quant
+    f = lib().trdq_rotate_quant_warm
     args = (C.c_void_p(_ptr(X)), C.c_int64(M), C.c_int(K), C.c_int64(ldx), C.c_void_p(_ptr(diag)), C.c_int(block),
-            C.c_void_p(_ptr(Xq)), C.c_void_p(_ptr(sx)), C.c_void_p(_stream(stream)))
+            C.c_void_p(_ptr(Xq)), C.c_void_p(_ptr(sx)), warm.handle if warm is not None else C.c_void_p(None),
+            C.c_void_p(_stream(stream)))
 
     def call():
         st = f(*args)
         if st != OK:
-            raise TrdqError(st, "trdq_rotate_quant")
+            raise TrdqError(st, "trdq_rotate_quant_warm")
     return call
 
 

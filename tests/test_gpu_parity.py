@@ -328,3 +328,26 @@ def test_graph_replay_matches_host_launches(oracle):
     gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], "Y (graph replay, oracle end to end)",
                       (Xq.cpu().numpy() != ref["Xq"]).any(axis=1), (Wq_h != ref["Wq"]).any(axis=0))
     w.close()
+
+
+@pytest.mark.parametrize("wbits", [8, 4])
+def test_rotate_quant_warm_read_changes_nothing(oracle, wbits):
+    """The pass that also reads the next product's weights gives the bits of the plain pass and
+    leaves the weights alone."""
+    say(f"rotate_quant with the warming read, wbits={wbits}")
+    M, K, N = 300, 1152, 400
+    Xb, W, d, _ = wl.small_case(31, M, K, N, n_outliers=8)
+    w = trdq.prepare_weights(gu.f32_to_dev(W), gu.f32_to_dev(d), wbits=wbits)
+    before = w.export()
+    X, dd = gu.bf16_to_dev(Xb), gu.f32_to_dev(d)
+    out = []
+    for warm in (None, w):
+        Xq = torch.full((M, K), 99, dtype=torch.int8, device="cuda")
+        sx = torch.full((M,), -1.0, dtype=torch.float32, device="cuda")
+        trdq.rotate_quant(X, dd, Xq, sx, warm=warm)
+        torch.cuda.synchronize()
+        out.append((Xq, sx))
+    assert torch.equal(out[0][0], out[1][0]) and torch.equal(out[0][1], out[1][1])
+    after = w.export()
+    assert np.array_equal(before[0], after[0]) and np.array_equal(before[1], after[1])
+    w.close()
