@@ -194,7 +194,7 @@ def main():
                                                          warm=None if args.no_warm else Wh[kind, g]),
                                   trdq.bind_qgemm(Wh[kind, g], Xq[kind], SX[kind], Y[kind], bias=B[kind],
                                                   stream=stream))
-    n_ev = len(cfg.kinds) * (2 if args.fused else 3) + 1      # + one event right after the last, see below
+    n_ev = len(cfg.kinds) * (2 if args.fused else 3)
     every = max(1, args.event_every)
     events = {st: [HipEvent() for _ in range(n_ev)]
               for st in range(0, args.steps, every)} if use_events else {}
@@ -221,10 +221,7 @@ def main():
                     ev.append(("qgemm", kind, evs[i + 1], evs[i + 2]))
                 i += len(fns) + 1
         if record:
-            # an empty interval: what one event record costs the stream by itself.  The same cost
-            # sits between the opening event of a bracket and the start of its kernel.
-            evs[i].record(stream)
-            ev.append(("empty", "-", evs[i - 1], evs[i]))
+            ev.append(("step", "-", evs[0], evs[i - 1]))       # the whole step, first to last event
 
     for s in range(args.warmup):
         run_step(s, False)
@@ -259,6 +256,14 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
+    if args.copy_probe:
+        # a kernel of known traffic for the counter runs: 256 MiB read + 256 MiB written
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     ms_per_step = dt / args.steps * 1e3
     value = ops_step * args.steps / dt / 1e12
     out = {
@@ -278,8 +283,17 @@ def main():
         for name, kind, a, b in ev:
             per.setdefault((name, kind), []).append(a.elapsed_time(b) * 1e-3)
         kern = {}
-        empty = per.pop(("empty", "-"), [0.0])
-        ev_cost = sum(empty) / len(empty)
+        # What a bracket adds to its kernel (the device's handling of the event records; it differs
+        # with and without a profiler attached) is calibrated from the run itself: the steps
+        # without events run back to back, so their average length is the sum of their kernels'
+        # durations; the brackets of an evented step add up to more, and the excess is spread
+        # evenly over its launches.
+        spans = per.pop(("step", "-"))
+        n_plain = args.steps - len(spans)
+        t_plain = (dt - sum(spans)) / n_plain if n_plain > 0 else 0.0
+        n_kernels = sum(len(calls[0, kind]) for kind in cfg.kinds)
+        bracket_sum = sum(sum(ts) for ts in per.values()) / len(spans)
+        ev_cost = max(0.0, (bracket_sum - t_plain) / n_kernels) if n_plain > 0 else 0.0
         for (name, kind), ts in per.items():
             per[name, kind] = ts = [max(t - ev_cost, 0.0) for t in ts]
         for (name, kind), ts in per.items():
@@ -304,8 +318,8 @@ def main():
                            "event_cost_us": ev_cost * 1e6,
                            "timed_on": f"every {every}th of the {args.steps} timed steps (launched from the host, "
                                        "the others replay a captured graph if --graph), events on the launch stream; "
-                                       "event_cost_us, the length of an empty event-to-event interval "
-                                       "measured in the same steps, is subtracted from every bracket",
+                                       "event_cost_us = (sum of an evented step's brackets - average length of "
+                                       "a step without events) / launches per step is subtracted from every bracket",
                            "ops_per_launch": tot_ops / n_launch}
         if not args.fused:
             rq_t = sum(sum(ts) for (name, _), ts in per.items() if name == "rotate_quant")
