@@ -866,8 +866,8 @@ hipError_t launch_qgemm4_dma(const GemmArgs &a, bool debug, int variant, hipStre
 // ring: 0: 128x128x64 NS4   1: 256x128x64 NS4   2: 128x256x64 NS4   3: 128x128x128 NS3   4: 256x128x128 NS3
 // pipe: 5: 256x128 NS3   6: 128x128 NS4   7: 128x256 NS3   8: 256x256 NS2   9: 128x128 NS2
 // persistent: 10: 128x128 NS2 (2 workgroups per CU)   11: 256x128 NS3   12: 128x256 NS3   13: 128x128 NS4
-// pipe, 144-channel tiles (1152 = 8 x 144: the DiT-XL/2 widths give whole rounds of 256 tiles): 14: 128x144 NS4
-int dma_num_variants() { return 15; }
+// pipe, 144-channel tiles (1152 = 8 x 144: the DiT-XL/2 widths give whole rounds of 256 tiles): 14: 128x144 NS4   15: 128x144 NS2 (two workgroups per CU)
+int dma_num_variants() { return 16; }
 
 hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStream_t st)
 {
@@ -887,6 +887,7 @@ hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStre
         case 12: return launch_persist<128, 256, 3, 2, 2, 1>(a, debug, st);
         case 13: return launch_persist<128, 128, 4, 2, 2, 1>(a, debug, st);
         case 14: return launch_pipe<128, 144, 4, 4, 1>(a, debug, st);
+        case 15: return launch_pipe<128, 144, 2, 4, 1>(a, debug, st);
     }
     return hipErrorInvalidValue;
 }
