@@ -266,6 +266,10 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int
     a.acc_debug = acc_debug; a.M = M; a.ldy = ldy; a.K = w.K; a.N = w.N;
     a.tiles_m = a.tiles_n = 0;
     const bool dbg = acc_debug != nullptr;
+    // the row-wise epilogues store 16 bytes per lane: an output whose rows are only 8-byte aligned
+    // goes to the kernels that store 8 bytes per lane
+    if (ldy % 8 != 0 || reinterpret_cast<uintptr_t>(Y) % 16 != 0)
+        return w.wbits == 4 ? launch_cfg<128, 128, 128, 2, 2, true>(a, dbg, st) : launch_qgemm8_dma(a, dbg, 0, st);
     if (w.wbits == 4) {
         // int4 keeps a second (float) accumulator set: smaller tiles, BK = one scale group
         // variants 1 and 5: register-staged; 6, 7: direct-to-LDS (6 is the built-in choice)

@@ -25,8 +25,8 @@ constexpr int kWideBM = 256;                 // tokens per tile
 constexpr int kWideBN = 256;                 // output channels per tile
 constexpr int kWideBK = 64;                  // bytes of k per k-step (one matrix instruction deep)
 constexpr int kWideSlot = (kWideBM + kWideBN) * kWideBK;    // 32 KB: [tokens 256 x 64][channels 256 x 64]
-constexpr int kWideSlots = 4;
-constexpr int kWideLds = kWideSlots * kWideSlot;            // 128 KB, a power of two (the ring wraps with a mask)
+constexpr int kWideSlots = 5;
+constexpr int kWideLds = kWideSlots * kWideSlot;            // 160 KB: all of a compute unit's LDS
 
 #define TRDQ_WIDE_CLOBBERS \
     "v108", "v109", "v110", "v111", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", \
@@ -77,15 +77,20 @@ __device__ __forceinline__ int acc_read()
     return v;
 }
 
-// LDS ring of four 32 KB slots, one per k-step: row r of an operand at r * 64, its 16-byte
+// LDS ring of five 32 KB slots, one per k-step: row r of an operand at r * 64, its 16-byte
 // chunk c at ((c ^ swizzle(r)) * 16).  A copy instruction moves 16 rows x 64 B: lane -> row
 // lane / 4, chunk lane % 4 (the LDS side is linear).  Wave w copies rows 64 w .. 64 w + 63 of
-// both operands, 4 instructions each per k-step.
+// both operands.
+//
+// Copies are issued for two k-steps at a time: the two 64-byte halves of the same 128-byte
+// lines, back to back, into two slots.  Issued a k-step apart, each half costs its own L2
+// request (twice the L2-to-L1 traffic); back to back the second half is served by the L1.
 //
 // Pipeline, k-step s of a tile (fragment set s % 2):
-//   wait for the copies of k-step s+1 (issued at s-3), barrier (slot s is free, slot s+1 is
-//   complete), then 64 matrix instructions on set s % 2 with, between them, the 16 fragment
-//   reads of k-step s+1 into the other set and the 8 copies of k-step s+4 into slot s.
+//   wait for the copies of k-step s+1, barrier (slot s is free, slot s+1 is complete), then 64
+//   matrix instructions on set s % 2 with, between them, the 16 fragment reads of k-step s+1
+//   into the other set and -- on even s -- the 16 copies of k-steps s+4 and s+5 into the slots
+//   of k-steps s-1 and s.
 // The copy stream runs on into the next tile of the workgroup; the block ends with vmcnt(0), so
 // the next tile's first four k-steps have landed when its block starts.
 template <bool DEBUG, bool FULL>
@@ -133,7 +138,7 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
 
     // first four k-steps of the first tile
 #pragma unroll
-    for (int t = 0; t < kWideSlots; ++t) {
+    for (int t = 0; t < 4; ++t) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int rx = (rl + 16 * i) < mxc ? (rl + 16 * i) : mxc;
@@ -158,29 +163,17 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
         const uint64_t xn = (uint64_t)(g.Xq + m1 * K);
         const uint64_t wnx = (uint64_t)(wbase + (int64_t)n1 * K);
 
-        // epilogue operands, requested before the k-loop
-        const int64_t m_lane = m0 + wm * 128 + l16;
-        const int n_lane = n0 + wn * 128 + lg * 4;
-        float sxm[8];
-        float4 swv[8], biv[8];
-#pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            const int64_t m = m_lane + b * 16;
-            sxm[b] = (FULL || m < g.M) ? g.sx[m] : 0.0f;
-        }
-#pragma unroll
-        for (int a = 0; a < 8; ++a) {
-            const int n = n_lane + a * 16;
-            swv[a] = biv[a] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (FULL || n < g.N) {
-                swv[a] = *reinterpret_cast<const float4 *>(g.sw + n);
-                if (g.bias) biv[a] = *reinterpret_cast<const float4 *>(g.bias + n);
-            }
-        }
+        // Epilogue operands (256 token scales, 256 channel scales, 256 biases) are copied into the
+        // ring slot that the last k-step leaves free, during that k-step: wave w fetches elements
+        // 64 w .. 64 w + 63 of each (indices clamped at the matrix edge).
+        const int64_t me = m0 + wave * 64 + lane, ne = (int64_t)n0 + wave * 64 + lane;
+        const uint32_t vmo = (uint32_t)((me < g.M ? me : g.M - 1) * 4);
+        const uint32_t vno = (uint32_t)((ne < g.N ? ne : g.N - 1) * 4);
+        const uint64_t sxb = (uint64_t)g.sx, swb = (uint64_t)g.sw, bb = (uint64_t)(g.bias ? g.bias : g.sw);
 
-        uint32_t rem = (uint32_t)__builtin_amdgcn_readfirstlane(KS - 4);   // k-steps of this tile still to copy
+        uint32_t rem = (uint32_t)__builtin_amdgcn_readfirstlane(KS / 2 - 2);   // pairs of k-steps of this tile still to copy
         const uint32_t pairs = (uint32_t)__builtin_amdgcn_readfirstlane((KS - 4) / 2);   // k-steps 3 .. KS-2, two per iteration
-        uint32_t t0, cnt;
+        uint32_t t0, cnt, sa, sb;
         asm volatile(R"(
   .macro TRDQ_VOFFS maxx, maxw, ce
     .irp i,0,1,2,3
@@ -198,31 +191,50 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
       ds_read_b128 v[160+(\set)*64+((\r)-8)*4:160+(\set)*64+((\r)-8)*4+3], \vax offset:((\r)-8)*1024
     .endif
   .endm
-  .macro TRDQ_COPY d
+  ; the copy offsets v108-v115 point at the second 64-byte half of the line; the first half is
+  ; reached with the instruction offset -64, which the hardware also adds to the LDS address
+  ; (hence the +64 in M0)
+  .macro TRDQ_COPY d, half
     .if (\d) < 4
-      global_load_lds_dwordx4 v[108+(\d)], %[xp]
+      global_load_lds_dwordx4 v[108+(\d)], %[xp] offset:((\half)-1)*64
     .else
-      global_load_lds_dwordx4 v[108+(\d)], %[wp]
+      global_load_lds_dwordx4 v[108+(\d)], %[wp] offset:((\half)-1)*64
+    .endif
+  .endm
+  .macro TRDQ_M0 base, d, half
+    .if (\d) < 4
+      s_add_u32 m0, \base, (\d)*1024+(1-(\half))*64
+    .else
+      s_add_u32 m0, \base, 16384+((\d)-4)*1024+(1-(\half))*64
     .endif
   .endm
   .macro TRDQ_STEP set, first, rd, wait, vax, vaw
-    s_cmp_eq_u32 %[rem], 0
-    s_cbranch_scc0 .Ltrdq_same\@_%=
-    s_mov_b64 %[xp], %[xn]
-    s_mov_b64 %[wp], %[wn]
-    TRDQ_VOFFS %[mxn], %[mwn], %[c0]
+    .if \set == 0
+      s_cmp_eq_u32 %[rem], 0
+      s_cbranch_scc0 .Ltrdq_same\@_%=
+      s_mov_b64 %[xp], %[xn]
+      s_mov_b64 %[wp], %[wn]
+      TRDQ_VOFFS %[mxn], %[mwn], %[c0]
 .Ltrdq_same\@_%=:
-    s_sub_u32 %[rem], %[rem], 1
+      s_sub_u32 %[rem], %[rem], 1
+    .endif
     s_add_u32 %[t0], %[st], 0x8000
-    s_and_b32 %[t0], %[t0], 0x1ffff
+    s_cmp_eq_u32 %[t0], 0x28000
+    s_cselect_b32 %[t0], 0, %[t0]
     v_add_u32 \vax, %[t0], %[xo]
     v_add_u32 \vaw, %[t0], %[wo]
+    .if \set == 0
+      s_sub_u32 %[sa], %[st], 0x8000
+      s_cmp_eq_u32 %[st], 0
+      s_cselect_b32 %[sa], 0x20000, %[sa]
+      s_add_u32 %[sa], %[sa], %[wv]
+      s_add_u32 %[sb], %[st], %[wv]
+    .endif
     .if \wait
       s_waitcnt vmcnt(16)
     .endif
     s_waitcnt lgkmcnt(0)
     s_barrier
-    s_add_u32 m0, %[st], %[wv]
     .set trdq_n, 0
     .rept 64
       .if \first
@@ -233,21 +245,27 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
       .if \rd && ((trdq_n %% 2) == 0) && (trdq_n < 32)
         TRDQ_READ 1-\set, trdq_n/2, \vax, \vaw
       .endif
-      .if ((trdq_n %% 4) == 0) && (trdq_n > 0) && (trdq_n < 32)
-        .if trdq_n == 16
-          s_add_u32 m0, m0, 13312
-        .else
-          s_add_u32 m0, m0, 1024
+      .if (\set == 0) && (trdq_n >= 32)
+        .if (trdq_n %% 4) == 0
+          TRDQ_M0 %[sa], (trdq_n-32)/4, 0
         .endif
-      .endif
-      .if ((trdq_n %% 4) == 1) && (trdq_n < 32)
-        TRDQ_COPY trdq_n/4
+        .if (trdq_n %% 4) == 1
+          TRDQ_COPY (trdq_n-32)/4, 0
+        .endif
+        .if (trdq_n %% 4) == 2
+          TRDQ_M0 %[sb], (trdq_n-32)/4, 1
+        .endif
+        .if (trdq_n %% 4) == 3
+          TRDQ_COPY (trdq_n-32)/4, 1
+        .endif
       .endif
       .set trdq_n, trdq_n+1
     .endr
-    .irp i,108,109,110,111,112,113,114,115
-      v_add_u32 v\i, 64, v\i
-    .endr
+    .if \set == 0
+      .irp i,108,109,110,111,112,113,114,115
+        v_add_u32 v\i, 0x80, v\i
+      .endr
+    .endif
     s_mov_b32 %[st], %[t0]
   .endm
 
@@ -273,52 +291,92 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
   s_cmp_lg_u32 %[cnt], 0
   s_cbranch_scc1 .Ltrdq_loop_%=
 .Ltrdq_tail_%=:
+  ; the slot of the last k-step (its fragments were read during the step before) takes the
+  ; epilogue operands: [256 s_x][256 s_w][256 bias], 4 bytes per lane and copy
+  s_add_u32 m0, %[st], %[wvp]
+  s_nop 0
+  global_load_lds_dword %[vmo], %[sxb]
+  s_add_u32 m0, m0, 1024
+  s_nop 0
+  global_load_lds_dword %[vno], %[swb]
+  s_add_u32 m0, m0, 1024
+  s_nop 0
+  global_load_lds_dword %[vno], %[bb]
   TRDQ_STEP 1, 0, 0, 0, v124, v125
   s_waitcnt vmcnt(0)
+  s_barrier
   s_nop 7
   s_nop 7
   .purgem TRDQ_VOFFS
   .purgem TRDQ_READ
   .purgem TRDQ_COPY
+  .purgem TRDQ_M0
   .purgem TRDQ_STEP
 )"
                      // every operand the block writes is early-clobber: an input of equal value
                      // must not share its register
-                     : [xp] "+&s"(xp), [wp] "+&s"(wp), [rem] "+&s"(rem), [st] "+&s"(st), [t0] "=&s"(t0), [cnt] "=&s"(cnt)
+                     : [xp] "+&s"(xp), [wp] "+&s"(wp), [rem] "+&s"(rem), [st] "+&s"(st), [t0] "=&s"(t0), [cnt] "=&s"(cnt), [sa] "=&s"(sa), [sb] "=&s"(sb)
                      : [xn] "s"(xn), [wn] "s"(wnx),
                        [mxc] "s"(__builtin_amdgcn_readfirstlane(mxc)), [mwc] "s"(__builtin_amdgcn_readfirstlane(mwc)),
                        [mxn] "s"(__builtin_amdgcn_readfirstlane(mxn)), [mwn] "s"(__builtin_amdgcn_readfirstlane(mwn)),
                        [K] "s"(__builtin_amdgcn_readfirstlane(K)), [wv] "s"(__builtin_amdgcn_readfirstlane(wv)),
-                       [pairs] "s"(pairs),
-                       [rl] "v"(rl), [c0] "v"(c0), [c0e] "v"(c0 + kWideSlots * kWideBK),
+                       [pairs] "s"(pairs), [wvp] "s"(__builtin_amdgcn_readfirstlane(lds0 + wave * 256)),
+                       [sxb] "s"(sxb), [swb] "s"(swb), [bb] "s"(bb), [vmo] "v"(vmo), [vno] "v"(vno),
+                       [rl] "v"(rl), [c0] "v"(c0 + 64), [c0e] "v"(c0 + 4 * kWideBK + 64),
                        [xo] "v"(xo), [wo] "v"(wo)
                      : "memory", "scc", "m0", TRDQ_WIDE_CLOBBERS);
 
-        // epilogue: y = float(acc) * s_x[m] * s_w[n] + bias[n] -> bf16; the lane holds channels
-        // n .. n+3 of token m for each of the 8 x 8 instruction tiles
-        static_for(std::make_integer_sequence<int, 8>{}, [&](auto ai) {
-            constexpr int a = decltype(ai)::value;
-            const int n = n_lane + a * 16;
-            const bool n_ok = FULL || n < g.N;
-            static_for(std::make_integer_sequence<int, 8>{}, [&](auto bi) {
-                constexpr int b = decltype(bi)::value;
+        // epilogue: y = float(acc) * s_x[m] * s_w[n] + bias[n] -> bf16.  The lane holds channels
+        // n .. n+3 of token m for each of the 8 x 8 instruction tiles; one token tile (16 tokens x
+        // 128 channels of the wave) at a time is laid out in the free slot and read back row by
+        // row, so that a store instruction writes four whole 256-byte row segments, 16 bytes per
+        // lane (partial-line stores reach about half of the store bandwidth).
+        const int8_t *const slot = smem + (st == 0 ? 4 * kWideSlot : st - kWideSlot);   // the last k-step's slot
+        const float *const par = reinterpret_cast<const float *>(slot);
+        constexpr int kRowB = 128 * 2 + 16;                                            // padded staging row
+        int8_t *const stg = const_cast<int8_t *>(slot) + 3072 + wave * (16 * kRowB);
+        const int64_t m_wave = m0 + wm * 128;
+        const int n_wave = n0 + wn * 128;
+        const bool has_bias = g.bias != nullptr;
+        float4 swv[8], biv[8];
+#pragma unroll
+        for (int a = 0; a < 8; ++a) {
+            swv[a] = *reinterpret_cast<const float4 *>(par + 256 + wn * 128 + a * 16 + lg * 4);
+            biv[a] = has_bias ? *reinterpret_cast<const float4 *>(par + 512 + wn * 128 + a * 16 + lg * 4)
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        static_for(std::make_integer_sequence<int, 8>{}, [&](auto bi) {
+            constexpr int b = decltype(bi)::value;
+            const float sxm = par[wm * 128 + b * 16 + l16];
+            static_for(std::make_integer_sequence<int, 8>{}, [&](auto ai) {
+                constexpr int a = decltype(ai)::value;
                 constexpr int idx = (a * 8 + b) * 4;
-                const int64_t m = m_lane + b * 16;
                 const int q0 = acc_read<idx>(), q1 = acc_read<idx + 1>(), q2 = acc_read<idx + 2>(),
                           q3 = acc_read<idx + 3>();
-                const float y0 = (float)q0 * sxm[b] * swv[a].x + biv[a].x;
-                const float y1 = (float)q1 * sxm[b] * swv[a].y + biv[a].y;
-                const float y2 = (float)q2 * sxm[b] * swv[a].z + biv[a].z;
-                const float y3 = (float)q3 * sxm[b] * swv[a].w + biv[a].w;
-                uint2 o;
-                o.x = pack_bf16x2(y0, y1);
-                o.y = pack_bf16x2(y2, y3);
-                if (FULL || (n_ok && m < g.M)) {
-                    if constexpr (DEBUG)
+                if constexpr (DEBUG) {
+                    const int64_t m = m_wave + b * 16 + l16;
+                    const int n = n_wave + a * 16 + lg * 4;
+                    if (FULL || (m < g.M && n < g.N))
                         *reinterpret_cast<int4 *>(g.acc_debug + m * g.N + n) = make_int4(q0, q1, q2, q3);
-                    *reinterpret_cast<uint2 *>(g.Y + m * g.ldy + n) = o;
                 }
+                uint2 o;
+                o.x = pack_bf16x2((float)q0 * sxm * swv[a].x + biv[a].x, (float)q1 * sxm * swv[a].y + biv[a].y);
+                o.y = pack_bf16x2((float)q2 * sxm * swv[a].z + biv[a].z, (float)q3 * sxm * swv[a].w + biv[a].w);
+                *reinterpret_cast<uint2 *>(stg + l16 * kRowB + (a * 16 + lg * 4) * 2) = o;
             });
+            __builtin_amdgcn_wave_barrier();          // compiler: reads below stay after the writes above
+            // 16 rows x 256 B = 256 pieces of 16 bytes: four per lane
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int id = i * 64 + lane;
+                const int row = id >> 4, c = id & 15;
+                const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * kRowB + c * 16);
+                const int64_t m = m_wave + b * 16 + row;
+                const int n = n_wave + c * 8;
+                if (FULL || (m < g.M && n < g.N))
+                    *reinterpret_cast<uint4 *>(g.Y + m * g.ldy + n) = v;
+            }
+            __builtin_amdgcn_wave_barrier();          // ... and the next token tile's writes after these reads
         });
 
         m0 = m1; n0 = n1; mxc = mxn; mwc = mwn;
@@ -347,10 +405,12 @@ hipError_t launch_wide(const GemmArgs &a, hipStream_t st)
 
 }  // namespace
 
-// an even number of k-steps, at least four; 24-bit multiplies form the copy offsets
+// an even number of k-steps, at least four; 24-bit multiplies form the copy offsets; the output
+// is written in 16-byte pieces of 8 channels
 bool wide_supports(const GemmArgs &a)
 {
-    return a.M > 0 && a.K % (2 * kWideBK) == 0 && a.K >= kWideSlots * kWideBK && a.K < (1 << 22) && a.N % 4 == 0;
+    return a.M > 0 && a.K % (2 * kWideBK) == 0 && a.K >= 4 * kWideBK && a.K < (1 << 22) && a.N % 8 == 0 &&
+           a.ldy % 8 == 0 && reinterpret_cast<uintptr_t>(a.Y) % 16 == 0;
 }
 
 hipError_t launch_qgemm8_wide(const GemmArgs &a, bool debug, hipStream_t st)
