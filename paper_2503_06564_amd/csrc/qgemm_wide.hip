@@ -29,39 +29,40 @@ constexpr int kWideSlots = 5;
 constexpr int kWideLds = kWideSlots * kWideSlot;            // 160 KB: all of a compute unit's LDS
 
 #define TRDQ_WIDE_CLOBBERS \
-    "v108", "v109", "v110", "v111", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", \
-    "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "v128", "v129", "v130", "v131", \
-    "v132", "v133", "v134", "v135", "v136", "v137", "v138", "v139", "v140", "v141", "v142", "v143", \
-    "v144", "v145", "v146", "v147", "v148", "v149", "v150", "v151", "v152", "v153", "v154", "v155", \
-    "v156", "v157", "v158", "v159", "v160", "v161", "v162", "v163", "v164", "v165", "v166", "v167", \
-    "v168", "v169", "v170", "v171", "v172", "v173", "v174", "v175", "v176", "v177", "v178", "v179", \
-    "v180", "v181", "v182", "v183", "v184", "v185", "v186", "v187", "v188", "v189", "v190", "v191", \
-    "v192", "v193", "v194", "v195", "v196", "v197", "v198", "v199", "v200", "v201", "v202", "v203", \
-    "v204", "v205", "v206", "v207", "v208", "v209", "v210", "v211", "v212", "v213", "v214", "v215", \
-    "v216", "v217", "v218", "v219", "v220", "v221", "v222", "v223", "v224", "v225", "v226", "v227", \
-    "v228", "v229", "v230", "v231", "v232", "v233", "v234", "v235", "v236", "v237", "v238", "v239", \
-    "v240", "v241", "v242", "v243", "v244", "v245", "v246", "v247", "v248", "v249", "v250", "v251", \
-    "v252", "v253", "v254", "v255", "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", \
-    "a10", "a11", "a12", "a13", "a14", "a15", "a16", "a17", "a18", "a19", "a20", "a21", "a22", \
-    "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31", "a32", "a33", "a34", "a35", \
-    "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47", "a48", \
-    "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", \
-    "a62", "a63", "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", \
-    "a75", "a76", "a77", "a78", "a79", "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", \
-    "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95", "a96", "a97", "a98", "a99", "a100", \
-    "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111", "a112", \
-    "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", \
-    "a125", "a126", "a127", "a128", "a129", "a130", "a131", "a132", "a133", "a134", "a135", "a136", \
-    "a137", "a138", "a139", "a140", "a141", "a142", "a143", "a144", "a145", "a146", "a147", "a148", \
-    "a149", "a150", "a151", "a152", "a153", "a154", "a155", "a156", "a157", "a158", "a159", "a160", \
-    "a161", "a162", "a163", "a164", "a165", "a166", "a167", "a168", "a169", "a170", "a171", "a172", \
-    "a173", "a174", "a175", "a176", "a177", "a178", "a179", "a180", "a181", "a182", "a183", "a184", \
-    "a185", "a186", "a187", "a188", "a189", "a190", "a191", "a192", "a193", "a194", "a195", "a196", \
-    "a197", "a198", "a199", "a200", "a201", "a202", "a203", "a204", "a205", "a206", "a207", "a208", \
-    "a209", "a210", "a211", "a212", "a213", "a214", "a215", "a216", "a217", "a218", "a219", "a220", \
-    "a221", "a222", "a223", "a224", "a225", "a226", "a227", "a228", "a229", "a230", "a231", "a232", \
-    "a233", "a234", "a235", "a236", "a237", "a238", "a239", "a240", "a241", "a242", "a243", "a244", \
-    "a245", "a246", "a247", "a248", "a249", "a250", "a251", "a252", "a253", "a254", "a255"
+    "v104", "v105", "v106", "v107", "v108", "v109", "v110", "v111", "v112", "v113", "v114", "v115", \
+    "v116", "v117", "v118", "v119", "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", \
+    "v128", "v129", "v130", "v131", "v132", "v133", "v134", "v135", "v136", "v137", "v138", "v139", \
+    "v140", "v141", "v142", "v143", "v144", "v145", "v146", "v147", "v148", "v149", "v150", "v151", \
+    "v152", "v153", "v154", "v155", "v156", "v157", "v158", "v159", "v160", "v161", "v162", "v163", \
+    "v164", "v165", "v166", "v167", "v168", "v169", "v170", "v171", "v172", "v173", "v174", "v175", \
+    "v176", "v177", "v178", "v179", "v180", "v181", "v182", "v183", "v184", "v185", "v186", "v187", \
+    "v188", "v189", "v190", "v191", "v192", "v193", "v194", "v195", "v196", "v197", "v198", "v199", \
+    "v200", "v201", "v202", "v203", "v204", "v205", "v206", "v207", "v208", "v209", "v210", "v211", \
+    "v212", "v213", "v214", "v215", "v216", "v217", "v218", "v219", "v220", "v221", "v222", "v223", \
+    "v224", "v225", "v226", "v227", "v228", "v229", "v230", "v231", "v232", "v233", "v234", "v235", \
+    "v236", "v237", "v238", "v239", "v240", "v241", "v242", "v243", "v244", "v245", "v246", "v247", \
+    "v248", "v249", "v250", "v251", "v252", "v253", "v254", "v255", "a0", "a1", "a2", "a3", "a4", \
+    "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15", "a16", "a17", "a18", \
+    "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31", \
+    "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", \
+    "a45", "a46", "a47", "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", \
+    "a58", "a59", "a60", "a61", "a62", "a63", "a64", "a65", "a66", "a67", "a68", "a69", "a70", \
+    "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79", "a80", "a81", "a82", "a83", \
+    "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95", "a96", \
+    "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", \
+    "a109", "a110", "a111", "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", \
+    "a121", "a122", "a123", "a124", "a125", "a126", "a127", "a128", "a129", "a130", "a131", "a132", \
+    "a133", "a134", "a135", "a136", "a137", "a138", "a139", "a140", "a141", "a142", "a143", "a144", \
+    "a145", "a146", "a147", "a148", "a149", "a150", "a151", "a152", "a153", "a154", "a155", "a156", \
+    "a157", "a158", "a159", "a160", "a161", "a162", "a163", "a164", "a165", "a166", "a167", "a168", \
+    "a169", "a170", "a171", "a172", "a173", "a174", "a175", "a176", "a177", "a178", "a179", "a180", \
+    "a181", "a182", "a183", "a184", "a185", "a186", "a187", "a188", "a189", "a190", "a191", "a192", \
+    "a193", "a194", "a195", "a196", "a197", "a198", "a199", "a200", "a201", "a202", "a203", "a204", \
+    "a205", "a206", "a207", "a208", "a209", "a210", "a211", "a212", "a213", "a214", "a215", "a216", \
+    "a217", "a218", "a219", "a220", "a221", "a222", "a223", "a224", "a225", "a226", "a227", "a228", \
+    "a229", "a230", "a231", "a232", "a233", "a234", "a235", "a236", "a237", "a238", "a239", "a240", \
+    "a241", "a242", "a243", "a244", "a245", "a246", "a247", "a248", "a249", "a250", "a251", "a252", \
+    "a253", "a254", "a255"
 
 template <int... Is, class F>
 __device__ __forceinline__ void static_for(std::integer_sequence<int, Is...>, F &&f)
@@ -163,9 +164,9 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
         const uint64_t xn = (uint64_t)(g.Xq + m1 * K);
         const uint64_t wnx = (uint64_t)(wbase + (int64_t)n1 * K);
 
-        // Epilogue operands (256 token scales, 256 channel scales, 256 biases) are copied into the
-        // ring slot that the last k-step leaves free, during that k-step: wave w fetches elements
-        // 64 w .. 64 w + 63 of each (indices clamped at the matrix edge).
+        // Epilogue operands (256 token scales, 256 channel scales, 256 biases): wave w fetches
+        // elements 64 w .. 64 w + 63 of each (indices clamped at the matrix edge) at the top of the
+        // block and writes them into the ring slot that the last k-step leaves free.
         const int64_t me = m0 + wave * 64 + lane, ne = (int64_t)n0 + wave * 64 + lane;
         const uint32_t vmo = (uint32_t)((me < g.M ? me : g.M - 1) * 4);
         const uint32_t vno = (uint32_t)((ne < g.N ? ne : g.N - 1) * 4);
@@ -208,7 +209,7 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
       s_add_u32 m0, \base, 16384+((\d)-4)*1024+(1-(\half))*64
     .endif
   .endm
-  .macro TRDQ_STEP set, first, rd, wait, vax, vaw
+  .macro TRDQ_STEP set, first, rd, wait, vax, vaw, par=0
     .if \set == 0
       s_cmp_eq_u32 %[rem], 0
       s_cbranch_scc0 .Ltrdq_same\@_%=
@@ -235,6 +236,13 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
     .endif
     s_waitcnt lgkmcnt(0)
     s_barrier
+    .if \par
+      ; this step's slot is free now: it takes the epilogue operands [256 s_x][256 s_w][256 bias]
+      v_add_u32 v104, %[st], %[vpo]
+      ds_write_b32 v104, v105
+      ds_write_b32 v104, v106 offset:1024
+      ds_write_b32 v104, v107 offset:2048
+    .endif
     .set trdq_n, 0
     .rept 64
       .if \first
@@ -269,6 +277,11 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
     s_mov_b32 %[st], %[t0]
   .endm
 
+  ; epilogue operands of this tile, one element of each per lane, parked in v105-v107 until the
+  ; last k-step frees a slot for them
+  global_load_dword v105, %[vmo], %[sxb]
+  global_load_dword v106, %[vno], %[swb]
+  global_load_dword v107, %[vno], %[bb]
   TRDQ_VOFFS %[mxc], %[mwc], %[c0e]
   s_barrier
   v_add_u32 v124, %[st], %[xo]
@@ -291,19 +304,10 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
   s_cmp_lg_u32 %[cnt], 0
   s_cbranch_scc1 .Ltrdq_loop_%=
 .Ltrdq_tail_%=:
-  ; the slot of the last k-step (its fragments were read during the step before) takes the
-  ; epilogue operands: [256 s_x][256 s_w][256 bias], 4 bytes per lane and copy
-  s_add_u32 m0, %[st], %[wvp]
-  s_nop 0
-  global_load_lds_dword %[vmo], %[sxb]
-  s_add_u32 m0, m0, 1024
-  s_nop 0
-  global_load_lds_dword %[vno], %[swb]
-  s_add_u32 m0, m0, 1024
-  s_nop 0
-  global_load_lds_dword %[vno], %[bb]
-  TRDQ_STEP 1, 0, 0, 0, v124, v125
-  s_waitcnt vmcnt(0)
+  ; the epilogue operands requested at the top of the block are older than the last 16 copies
+  s_waitcnt vmcnt(16)
+  TRDQ_STEP 1, 0, 0, 0, v124, v125, 1
+  s_waitcnt vmcnt(0) lgkmcnt(0)
   s_barrier
   s_nop 7
   s_nop 7
@@ -320,8 +324,9 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
                        [mxc] "s"(__builtin_amdgcn_readfirstlane(mxc)), [mwc] "s"(__builtin_amdgcn_readfirstlane(mwc)),
                        [mxn] "s"(__builtin_amdgcn_readfirstlane(mxn)), [mwn] "s"(__builtin_amdgcn_readfirstlane(mwn)),
                        [K] "s"(__builtin_amdgcn_readfirstlane(K)), [wv] "s"(__builtin_amdgcn_readfirstlane(wv)),
-                       [pairs] "s"(pairs), [wvp] "s"(__builtin_amdgcn_readfirstlane(lds0 + wave * 256)),
+                       [pairs] "s"(pairs),
                        [sxb] "s"(sxb), [swb] "s"(swb), [bb] "s"(bb), [vmo] "v"(vmo), [vno] "v"(vno),
+                       [vpo] "v"(lds0 + (uint32_t)(wave * 256 + lane * 4)),
                        [rl] "v"(rl), [c0] "v"(c0 + 64), [c0e] "v"(c0 + 4 * kWideBK + 64),
                        [xo] "v"(xo), [wo] "v"(wo)
                      : "memory", "scc", "m0", TRDQ_WIDE_CLOBBERS);
