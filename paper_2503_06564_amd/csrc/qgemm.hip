@@ -284,15 +284,16 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int
     // (it hands ragged shapes to the ring kernel itself); 128x144 tiles with a four-stage ring,
     // one workgroup per compute unit, where the deeper prefetch pays: long K with at most two
     // rounds of tiles, or so few tiles that one round of them covers the chip anyway; the
-    // 256 x 256 kernel for long K and many tiles (measured crossovers on the DiT-XL/2 widths)
+    // 256 x 256 kernel once there are well over 256 of its tiles (measured crossovers on the
+    // DiT-XL/2 widths)
     if (variant < 0) {
         variant = kRegVariants + 9;
         const int64_t tiles144 = (a.N % 144 == 0 && M % 128 == 0 && a.K >= 512) ? (M / 128) * (a.N / 144) : 0;
         const int64_t tiles256 = ((M + 255) / 256) * ((a.N + 255) / 256);
         if (tiles144 > 0 && (tiles144 <= 256 || (a.K >= 2304 && tiles144 <= 512)))
             variant = kRegVariants + 14;
-        else if (a.K >= 2304 && tiles256 >= 512 && wide_supports(a))
-            variant = kRegVariants + dma_num_variants();     // long K, many tiles: 256 x 256 tiles
+        else if (tiles256 >= 400 && wide_supports(a))
+            variant = kRegVariants + dma_num_variants();     // many tiles: 256 x 256 tiles
     }
     switch (variant) {
         case 0: return launch_cfg<128, 128, 64, 2, 2, false>(a, dbg, st);
