@@ -90,8 +90,10 @@ __device__ __forceinline__ int acc_read()
 // Pipeline, k-step s of a tile (fragment set s % 2):
 //   wait for the copies of k-step s+1, barrier (slot s is free, slot s+1 is complete), then 64
 //   matrix instructions on set s % 2 with, between them, the 16 fragment reads of k-step s+1
-//   into the other set and -- on even s -- the 16 copies of k-steps s+4 and s+5 into the slots
-//   of k-steps s-1 and s.
+//   into the other set and 8 copies: both line halves of four 16-row groups, for k-steps s+4 and
+//   s+5 (even s: activation rows) or s+3 and s+4 (odd s: weight rows), into the two slots that
+//   the preceding even step found free.  Spreading the copies over all steps matters: the copy
+//   unit of a compute unit takes 16 clocks per instruction, and bunched copies stall the waves.
 // The copy stream runs on into the next tile of the workgroup; the block ends with vmcnt(0), so
 // the next tile's first four k-steps have landed when its block starts.
 template <bool DEBUG, bool FULL>
@@ -173,16 +175,22 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
         const uint64_t sxb = (uint64_t)g.sx, swb = (uint64_t)g.sw, bb = (uint64_t)(g.bias ? g.bias : g.sw);
 
         uint32_t rem = (uint32_t)__builtin_amdgcn_readfirstlane(KS / 2 - 2);   // pairs of k-steps of this tile still to copy
+        uint32_t remw = rem;
         const uint32_t pairs = (uint32_t)__builtin_amdgcn_readfirstlane((KS - 4) / 2);   // k-steps 3 .. KS-2, two per iteration
         uint32_t t0, cnt, sa, sb;
         asm volatile(R"(
-  .macro TRDQ_VOFFS maxx, maxw, ce
+  .macro TRDQ_VOFFX maxx, ce
     .irp i,0,1,2,3
       v_add_u32 v126, \i*16, %[rl]
       v_min_u32 v127, \maxx, v126
-      v_min_u32 v126, \maxw, v126
       v_mad_u32_u24 v[108+\i], v127, %[K], \ce
-      v_mad_u32_u24 v[112+\i], v126, %[K], \ce
+    .endr
+  .endm
+  .macro TRDQ_VOFFW maxw, ce
+    .irp i,0,1,2,3
+      v_add_u32 v126, \i*16, %[rl]
+      v_min_u32 v127, \maxw, v126
+      v_mad_u32_u24 v[112+\i], v127, %[K], \ce
     .endr
   .endm
   .macro TRDQ_READ set, r, vax, vaw
@@ -214,10 +222,16 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
       s_cmp_eq_u32 %[rem], 0
       s_cbranch_scc0 .Ltrdq_same\@_%=
       s_mov_b64 %[xp], %[xn]
-      s_mov_b64 %[wp], %[wn]
-      TRDQ_VOFFS %[mxn], %[mwn], %[c0]
+      TRDQ_VOFFX %[mxn], %[c0]
 .Ltrdq_same\@_%=:
       s_sub_u32 %[rem], %[rem], 1
+    .else
+      s_cmp_eq_u32 %[remw], 0
+      s_cbranch_scc0 .Ltrdq_same\@_%=
+      s_mov_b64 %[wp], %[wn]
+      TRDQ_VOFFW %[mwn], %[c0]
+.Ltrdq_same\@_%=:
+      s_sub_u32 %[remw], %[remw], 1
     .endif
     s_add_u32 %[t0], %[st], 0x8000
     s_cmp_eq_u32 %[t0], 0x28000
@@ -232,7 +246,11 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
       s_add_u32 %[sb], %[st], %[wv]
     .endif
     .if \wait
-      s_waitcnt vmcnt(16)
+      .if \set == 0
+        s_waitcnt vmcnt(16)
+      .else
+        s_waitcnt vmcnt(8)
+      .endif
     .endif
     s_waitcnt lgkmcnt(0)
     s_barrier
@@ -253,24 +271,27 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
       .if \rd && ((trdq_n %% 2) == 0) && (trdq_n < 32)
         TRDQ_READ 1-\set, trdq_n/2, \vax, \vaw
       .endif
-      .if (\set == 0) && (trdq_n >= 32)
-        .if (trdq_n %% 4) == 0
-          TRDQ_M0 %[sa], (trdq_n-32)/4, 0
-        .endif
-        .if (trdq_n %% 4) == 1
-          TRDQ_COPY (trdq_n-32)/4, 0
-        .endif
-        .if (trdq_n %% 4) == 2
-          TRDQ_M0 %[sb], (trdq_n-32)/4, 1
-        .endif
-        .if (trdq_n %% 4) == 3
-          TRDQ_COPY (trdq_n-32)/4, 1
-        .endif
+      ; copies: the activation rows' line halves on even steps, the weight rows' on odd steps
+      .if (trdq_n %% 16) == 0
+        TRDQ_M0 %[sa], (1-\set)*0+\set*4+trdq_n/16, 0
+      .endif
+      .if (trdq_n %% 16) == 1
+        TRDQ_COPY \set*4+trdq_n/16, 0
+      .endif
+      .if (trdq_n %% 16) == 2
+        TRDQ_M0 %[sb], \set*4+trdq_n/16, 1
+      .endif
+      .if (trdq_n %% 16) == 3
+        TRDQ_COPY \set*4+trdq_n/16, 1
       .endif
       .set trdq_n, trdq_n+1
     .endr
     .if \set == 0
-      .irp i,108,109,110,111,112,113,114,115
+      .irp i,108,109,110,111
+        v_add_u32 v\i, 0x80, v\i
+      .endr
+    .else
+      .irp i,112,113,114,115
         v_add_u32 v\i, 0x80, v\i
       .endr
     .endif
@@ -282,7 +303,8 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
   global_load_dword v105, %[vmo], %[sxb]
   global_load_dword v106, %[vno], %[swb]
   global_load_dword v107, %[vno], %[bb]
-  TRDQ_VOFFS %[mxc], %[mwc], %[c0e]
+  TRDQ_VOFFX %[mxc], %[c0e]
+  TRDQ_VOFFW %[mwc], %[c0e]
   s_barrier
   v_add_u32 v124, %[st], %[xo]
   v_add_u32 v125, %[st], %[wo]
@@ -311,7 +333,8 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
   s_barrier
   s_nop 7
   s_nop 7
-  .purgem TRDQ_VOFFS
+  .purgem TRDQ_VOFFX
+  .purgem TRDQ_VOFFW
   .purgem TRDQ_READ
   .purgem TRDQ_COPY
   .purgem TRDQ_M0
@@ -319,7 +342,7 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
 )"
                      // every operand the block writes is early-clobber: an input of equal value
                      // must not share its register
-                     : [xp] "+&s"(xp), [wp] "+&s"(wp), [rem] "+&s"(rem), [st] "+&s"(st), [t0] "=&s"(t0), [cnt] "=&s"(cnt), [sa] "=&s"(sa), [sb] "=&s"(sb)
+                     : [xp] "+&s"(xp), [wp] "+&s"(wp), [rem] "+&s"(rem), [remw] "+&s"(remw), [st] "+&s"(st), [t0] "=&s"(t0), [cnt] "=&s"(cnt), [sa] "=&s"(sa), [sb] "=&s"(sb)
                      : [xn] "s"(xn), [wn] "s"(wnx),
                        [mxc] "s"(__builtin_amdgcn_readfirstlane(mxc)), [mwc] "s"(__builtin_amdgcn_readfirstlane(mwc)),
                        [mxn] "s"(__builtin_amdgcn_readfirstlane(mxn)), [mwn] "s"(__builtin_amdgcn_readfirstlane(mwn)),
