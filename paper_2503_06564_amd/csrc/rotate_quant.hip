@@ -2,21 +2,33 @@
 // int8 quantiser (Eq. 1-2, symmetric form).  One streaming pass: 2 bytes in, 1 byte out
 // per element, 4 bytes of scale per token.
 //
-// The pass is bound by the vector ALUs before it is bound by HBM (packed fp32 is not used),
-// so the 128-point Walsh-Hadamard transform is split H_128 = H_16 (x) H_8 along the element
-// index e = 8p + j and only the H_8 factor (three add stages over j, inside a lane) runs on
-// the vector ALUs.  The H_16 factor over the chunk index p runs on the matrix cores as an
-// exact fp32 product with a +-1 matrix (v_mfma_f32_16x16x4_f32, four chained instructions
-// per j): products with +-1 are exact and the accumulation is fp32, so the result has the
-// accuracy of fp32 butterflies.
+// The pass is bound by the vector ALUs before it is bound by HBM (packed fp32 is not used, and
+// an fp32 matrix instruction keeps the vector ALU of its SIMD busy: nothing else issues under
+// it), so as much of the transform as can be made exact runs on the bf16 matrix pipe, which does
+// overlap with vector work.  The 128-point Walsh-Hadamard transform is split
+// H_128 = H_16 (x) H_8 along the element index e = 8p + j:
+//
+//   u[q][j] = sum_p H_16[q][p] * d[8p + j] * x[8p + j]      (matrix pipe, K = 16 = all p)
+//   y[8q + j'] = sum_j H_8[j'][j] * u[q][j]                 (three add stages inside a lane)
+//
+// x is bf16 as it comes from memory: it is the B operand without any conversion.  The A operand
+// is H_16[q][p] * d[8p + j]: the fp32 diagonal is cut into three bf16 pieces d = d_hi + d_mid +
+// d_lo (8 + 8 + 8 mantissa bits, exact), one v_mfma_f32_16x16x16_bf16 per piece accumulating
+// into the same fp32 registers.  Every product is exact (8 x 8 bits) and the accumulation is
+// fp32, so the result has the accuracy of fp32 butterflies applied to d * x.
 //
 // Mapping.  A workgroup owns 16 tokens; its NW waves split the K/128 blocks round-robin.
 // For one block, lane (g = lane / 16, r = lane % 16) loads chunk p = 4s + g (16 bytes = 8
-// channels) of token r in load s = 0..3, which is exactly the B-operand layout of the
-// matrix instruction (k = g, n = r); the A operand is H_16[q][4s + g], a per-lane constant.
-// The result leaves chunks q = 4g .. 4g+3 of token r in lane (g, r): 32 consecutive codes,
-// two 16-byte stores.  A token's values stay in registers (at most SPW blocks per wave)
-// until the token absmax is known: per-wave maxima are exchanged through LDS.
+// channels j) of token r in load s = 0..3.  Element j of the four loads, picked out with two
+// byte permutes, is the B operand (k = 4g + s <-> p = 4s + g, n = r) of the instruction for j.
+// The pieces of d, in the same k order, are staged once per workgroup in LDS; a lane reads the
+// four of its group g with one 8-byte read and applies the signs of its row of H_16 with two
+// XORs.  The rows of H_16 are permuted so that the result leaves chunks 2g, 2g+1 and 8+2g, 9+2g
+// of token r in lane (g, r): two 16-byte stores, each of which covers 64 consecutive bytes of
+// the token over the four lanes that share r.  A token's values stay in registers (at most SPW
+// blocks per wave) until the token absmax is known: per-wave maxima are exchanged through LDS.
+#include <type_traits>
+
 #include "device_utils.h"
 #include "trdq_internal.h"
 
@@ -26,17 +38,22 @@ namespace {
 
 constexpr int kTokensPerWG = 16;
 
+typedef short v4s __attribute__((ext_vector_type(4)));
+
+// LDS bytes of the diagonal's pieces: [block][j][piece][g] x 4 bf16 (k = 4g .. 4g+3)
+__host__ __device__ constexpr size_t diag_table_bytes(int nb) { return (size_t)nb * 8 * 3 * 4 * 8; }
+
 template <int SPW, int MAXT>
 __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
     const uint16_t *__restrict__ X, int64_t M, int nb, int64_t ldx,
     const float *__restrict__ diag, int8_t *__restrict__ Xq, float *__restrict__ sx,
     const uint4 *__restrict__ warm, int64_t warm_chunks)
 {
-    extern __shared__ __align__(16) float lds[];
+    extern __shared__ __align__(16) unsigned char lds_raw[];
     const int K = nb * kBlock;
     const int nw = blockDim.x >> 6;
-    float *const d_s = lds;                          // [K] the group's diagonal
-    float *const amax_s = lds + K;                   // [2][nw][16] per-wave token maxima (double-buffered)
+    const uint2 *const tbl = reinterpret_cast<const uint2 *>(lds_raw);
+    float *const amax_s = reinterpret_cast<float *>(lds_raw + diag_table_bytes(nb));   // [2][nw][16]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -44,102 +61,164 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
     const int g = lane >> 4, r = lane & 15;
     const int64_t groups = (M + kTokensPerWG - 1) / kTokensPerWG;
 
-    // One raw block (64 bytes per lane) is always in flight: the wave walks the sequence
-    // (group, block 0), (group, block 1), ..., (next group, block 0), ... and requests an item as
-    // soon as the previous one has been unpacked.  Tokens past M are clamped to the last token:
-    // they are rotated like the others (every lane takes part in the matrix instructions) and
-    // never stored.
-    uint4 raw[4];
-    auto load_raw = [&](int i, int64_t tg) {
+    // The diagonal first: its pieces are staged while the first activations are still in flight.
+    // A thread builds whole table entries (block b, element j, lane group g): the four channels
+    // 8 (4i + g) + j, i = 0..3, of the block; there are K / 4 entries and at least K / 6 threads,
+    // so two rounds cover them.
+    const int nent = K >> 2;
+    float dv[2][4];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        int e = tid + t * (int)blockDim.x;
+        if (e >= nent) e = nent - 1;
+        const float *dp = diag + (e >> 5) * kBlock + (e & 3) * 8 + ((e >> 2) & 7);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dv[t][i] = diag ? dp[i * 32] : 1.0f;
+    }
+
+    // Two raw blocks (64 bytes per lane each) are always in flight: the wave walks the sequence
+    // (group, block 0), (group, block 1), ..., (next group, block 0), ... and requests item n + 2
+    // into the registers of item n as soon as that one has been unpacked.  Tokens past M are
+    // clamped to the last token: they are rotated like the others (every lane takes part in the
+    // matrix instructions) and never stored.
+    uint4 raw[2][4];
+    auto load_raw = [&](uint4 (&dst)[4], int i, int64_t tgl) {
         // unconditional: a block index past the row or a group past the end is clamped to valid
         // memory (a redundant, cached read in the ragged / last step) and its data is not used
         int b = wave + nw * i;                       // wave-uniform
         if (b >= nb) b = nb - 1;
-        int64_t token = tg * kTokensPerWG + r;
+        int64_t token = tgl * kTokensPerWG + r;
         if (token >= M) token = M - 1;
         const uint16_t *src = X + token * ldx + b * kBlock + g * 8;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) raw[s] = *reinterpret_cast<const uint4 *>(src + s * 32);
+        for (int s = 0; s < 4; ++s) dst[s] = *reinterpret_cast<const uint4 *>(src + s * 32);
     };
 
     int64_t tg = blockIdx.x;
-    load_raw(0, tg);                                 // in flight while the diagonal is staged
-    // Optional: read the next kernel's weights once (a couple of loads per lane, spread over the
-    // whole grid).  Nothing waits for them before the end of the kernel; they only have to pass
-    // through the memory-side cache so that the product kernel does not start on cold DRAM.
-    uint32_t warm_acc = 0;
-    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + tid; c < warm_chunks; c += (int64_t)gridDim.x * blockDim.x) {
-        const uint4 v = warm[c];
-        warm_acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    load_raw(raw[0], 0, tg);
+    if (SPW > 1) load_raw(raw[1], 1, tg);
+    else load_raw(raw[1], 0, tg + gridDim.x);
+    // Optional: read the next kernel's weights once (at most four 16-byte pieces per lane, spread
+    // over the whole grid; more than that is left cold).  They only have to pass through the
+    // memory-side cache so that the product kernel does not start on cold DRAM: the copies go
+    // straight to a 1 KB dump area in LDS that nobody reads, so they hold no registers and nothing
+    // waits for them before the end of the kernel.  (The compiler does not see them in its count
+    // of outstanding loads: its waits can only become stricter by that, never too weak, because
+    // the counter retires in order.)
+    if (warm_chunks > 0) {
+        const uint32_t dump = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_raw +
+                              (uint32_t)(diag_table_bytes(nb) + sizeof(float) * 2 * nw * 16);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int64_t c0 = ((int64_t)t * gridDim.x + blockIdx.x) * blockDim.x + (wave << 6);   // wave-uniform
+            if (c0 < warm_chunks) {
+                int64_t c = c0 + lane;
+                if (c >= warm_chunks) c = warm_chunks - 1;
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                             :: "v"((uint32_t)(c << 4)), "s"(warm), "s"(dump) : "memory", "m0");
+            }
+        }
     }
-    if (diag) {
-        for (int k = tid * 4; k < K; k += blockDim.x * 4)
-            *reinterpret_cast<float4 *>(d_s + k) = *reinterpret_cast<const float4 *>(diag + k);
-    } else {
-        for (int k = tid * 4; k < K; k += blockDim.x * 4)
-            *reinterpret_cast<float4 *>(d_s + k) = make_float4(1.f, 1.f, 1.f, 1.f);
+    // the diagonal in three bf16 pieces (truncations: each remainder is exact in fp32)
+    {
+        uint2 *const tblw = reinterpret_cast<uint2 *>(lds_raw);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int e = tid + t * (int)blockDim.x;
+            if (e < nent) {
+                uint32_t pc[3][4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float d = dv[t][i];
+                    const uint32_t hi = __float_as_uint(d) & 0xFFFF0000u;
+                    const float r1 = d - __uint_as_float(hi);
+                    const uint32_t mid = __float_as_uint(r1) & 0xFFFF0000u;
+                    const uint32_t lo = __float_as_uint(r1 - __uint_as_float(mid));  // at most 8 significant bits
+                    pc[0][i] = hi; pc[1][i] = mid; pc[2][i] = lo;
+                }
+                // entry index ((b * 8 + j) * 3 + piece) * 4 + g with e = (b * 8 + j) * 4 + g
+                uint2 *dst = tblw + (size_t)(e >> 2) * 12 + (e & 3);
+#pragma unroll
+                for (int k = 0; k < 3; ++k)
+                    dst[k * 4] = make_uint2(__builtin_amdgcn_perm(pc[k][1], pc[k][0], 0x07060302u),
+                                            __builtin_amdgcn_perm(pc[k][3], pc[k][2], 0x07060302u));
+            }
+        }
     }
     __syncthreads();
 
-    // A operand: H_16[q = r][p = 4s + g]
-    float hs[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) hs[s] = (__builtin_popcount(r & (4 * s + g)) & 1) ? -1.0f : 1.0f;
+    // Row m = 4g' + i of a result lands in lane group g', register i; the row of the A operand
+    // that lane r supplies is H_16 row q = pi(r), with pi chosen so that lane group g' receives
+    // chunks 2g', 2g'+1 (i = 0, 1) and 8 + 2g', 9 + 2g' (i = 2, 3).
+    const int qrow = (r & 2) ? 8 + 2 * (r >> 2) + (r & 1) : 2 * (r >> 2) + (r & 1);
+    // sign bits of H_16[qrow][p] for the lane's four p = 4s + g, as bf16 pairs (s = 0, 1 | 2, 3)
+    const uint32_t sg0 = ((__builtin_popcount(qrow & g) & 1) ? 0x00008000u : 0u) |
+                         ((__builtin_popcount(qrow & (4 + g)) & 1) ? 0x80000000u : 0u);
+    const uint32_t sg1 = ((__builtin_popcount(qrow & (8 + g)) & 1) ? 0x00008000u : 0u) |
+                         ((__builtin_popcount(qrow & (12 + g)) & 1) ? 0x80000000u : 0u);
 
     int parity = 0;
-    for (; tg < groups; tg += gridDim.x) {
+    // one token group; P = ring slot of its first item
+    auto do_group = [&](auto ptag, const int64_t tg) {
+        constexpr int P = decltype(ptag)::value;
         const int64_t token = tg * kTokensPerWG + r;
         const bool token_ok = token < M;
 
-        v4f out[SPW][8];   // out[i][j][q']: channel (4g + q') * 8 + j of block wave + nw*i, token r
+        v4f out[SPW][8];   // out[i][j][q']: element j of chunk (q' < 2 ? 2g + q' : 6 + 2g + q') of block wave + nw*i, token r
         float amax = 0.0f;
 #pragma unroll
         for (int i = 0; i < SPW; ++i) {
             const int b = wave + nw * i;
             if (b < nb) {
-                float w[4][8];
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const float *dp = d_s + b * kBlock + (4 * s + g) * 8;
-                    const float4 d0 = *reinterpret_cast<const float4 *>(dp);
-                    const float4 d1 = *reinterpret_cast<const float4 *>(dp + 4);
-                    const uint4 q = raw[s];
-                    // scale by the diagonal fused into the first butterfly stage (pairs j, j+1)
-                    const float t0 = bf16_hi(q.x) * d0.y, t1 = bf16_hi(q.y) * d0.w;
-                    const float t2 = bf16_hi(q.z) * d1.y, t3 = bf16_hi(q.w) * d1.w;
-                    float v[8];
-                    v[0] = __builtin_fmaf(bf16_lo(q.x), d0.x, t0);
-                    v[1] = __builtin_fmaf(bf16_lo(q.x), d0.x, -t0);
-                    v[2] = __builtin_fmaf(bf16_lo(q.y), d0.z, t1);
-                    v[3] = __builtin_fmaf(bf16_lo(q.y), d0.z, -t1);
-                    v[4] = __builtin_fmaf(bf16_lo(q.z), d1.x, t2);
-                    v[5] = __builtin_fmaf(bf16_lo(q.z), d1.x, -t2);
-                    v[6] = __builtin_fmaf(bf16_lo(q.w), d1.z, t3);
-                    v[7] = __builtin_fmaf(bf16_lo(q.w), d1.z, -t3);
-                    // stages over index bits 1 and 2
-                    const float a0 = v[0] + v[2], a2 = v[0] - v[2], a1 = v[1] + v[3], a3 = v[1] - v[3];
-                    const float a4 = v[4] + v[6], a6 = v[4] - v[6], a5 = v[5] + v[7], a7 = v[5] - v[7];
-                    w[s][0] = a0 + a4; w[s][4] = a0 - a4;
-                    w[s][1] = a1 + a5; w[s][5] = a1 - a5;
-                    w[s][2] = a2 + a6; w[s][6] = a2 - a6;
-                    w[s][3] = a3 + a7; w[s][7] = a3 - a7;
-                }
-                // the raw buffer is free: request the next item of the sequence
-                if (i + 1 < SPW) load_raw(i + 1, tg);
-                else load_raw(0, tg + gridDim.x);
-                // H_16 over the chunk index on the matrix cores: D[q][token] = sum_p H[q][p] * w[p][token]
+                // H_16 with the diagonal folded in, on the matrix pipe: three pieces per j.  The B
+                // operand is element j of the four chunks (two bf16 per register, k order s = 0..3).
+                const uint4 (&rw)[4] = raw[(P + i) & 1];
+                v4f u[8];
+                const uint2 *tb = tbl + (size_t)b * (8 * 3 * 4) + g;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
+                    const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+                    const uint32_t w0 = j < 2 ? rw[0].x : j < 4 ? rw[0].y : j < 6 ? rw[0].z : rw[0].w;
+                    const uint32_t w1 = j < 2 ? rw[1].x : j < 4 ? rw[1].y : j < 6 ? rw[1].z : rw[1].w;
+                    const uint32_t w2 = j < 2 ? rw[2].x : j < 4 ? rw[2].y : j < 6 ? rw[2].z : rw[2].w;
+                    const uint32_t w3 = j < 2 ? rw[3].x : j < 4 ? rw[3].y : j < 6 ? rw[3].z : rw[3].w;
+                    union { uint32_t w[2]; v4s v; } bop;
+                    bop.w[0] = __builtin_amdgcn_perm(w1, w0, sel);
+                    bop.w[1] = __builtin_amdgcn_perm(w3, w2, sel);
                     v4f acc = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int s = 0; s < 4; ++s)
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hs[s], w[s][j], acc, 0, 0, 0);
-                    out[i][j] = acc;
-                    amax = fmaxf(fmaxf(amax, fabsf(acc[0])), fabsf(acc[1]));     // two v_max3_f32
-                    amax = fmaxf(fmaxf(amax, fabsf(acc[2])), fabsf(acc[3]));
+                    for (int pc = 0; pc < 3; ++pc) {
+                        const uint2 c = tb[(j * 3 + pc) * 4];
+                        union { uint32_t w[2]; v4s v; } aop;
+                        aop.w[0] = c.x ^ sg0; aop.w[1] = c.y ^ sg1;
+                        acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(aop.v, bop.v, acc, 0, 0, 0);
+                    }
+                    u[j] = acc;
                 }
-            } else if (i + 1 == SPW) {
-                load_raw(0, tg + gridDim.x);         // ragged last slot: still advance the sequence
+                // these registers are free: request the item after the next one of the sequence
+                load_raw(raw[(P + i) & 1], (i + 2) % SPW, tg + (int64_t)((i + 2) / SPW) * gridDim.x);
+                // H_8 over j inside the lane, for each of the four rows
+#pragma unroll
+                for (int h = 1; h < 8; h <<= 1) {
+#pragma unroll
+                    for (int j0 = 0; j0 < 8; j0 += 2 * h) {
+#pragma unroll
+                        for (int j = j0; j < j0 + h; ++j) {
+                            const v4f a = u[j], c = u[j + h];
+                            u[j] = a + c;
+                            u[j + h] = a - c;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    out[i][j] = u[j];
+                    amax = fmaxf(fmaxf(amax, fabsf(u[j][0])), fabsf(u[j][1]));     // two v_max3_f32
+                    amax = fmaxf(fmaxf(amax, fabsf(u[j][2])), fabsf(u[j][3]));
+                }
+            } else {
+                // ragged last slot: still advance the sequence
+                load_raw(raw[(P + i) & 1], (i + 2) % SPW, tg + (int64_t)((i + 2) / SPW) * gridDim.x);
             }
         }
 
@@ -168,14 +247,21 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
                     c[2 * q + 1] = pack4_low_bytes(quant_bits(out[i][4][q], inv), quant_bits(out[i][5][q], inv),
                                                    quant_bits(out[i][6][q], inv), quant_bits(out[i][7][q], inv));
                 }
-                int8_t *dst = Xq + token * (int64_t)K + b * kBlock + g * 32;
+                int8_t *dst = Xq + token * (int64_t)K + b * kBlock + g * 16;
                 *reinterpret_cast<uint4 *>(dst) = make_uint4(c[0], c[1], c[2], c[3]);
-                *reinterpret_cast<uint4 *>(dst + 16) = make_uint4(c[4], c[5], c[6], c[7]);
+                *reinterpret_cast<uint4 *>(dst + 64) = make_uint4(c[4], c[5], c[6], c[7]);
             }
         }
+    };
+    while (tg < groups) {
+        do_group(std::integral_constant<int, 0>{}, tg);
+        tg += gridDim.x;
+        if (tg >= groups) break;
+        do_group(std::integral_constant<int, SPW & 1>{}, tg);
+        tg += gridDim.x;
     }
-    // keeps the loads above alive (never true: warm_chunks is not negative)
-    if (warm_chunks < 0 && warm_acc == 0x9E3779B9u) sx[0] = 0.0f;
+    // the copies to the dump area must have landed before the workgroup's LDS is given away
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 template <int SPW, int MAXT>
@@ -186,9 +272,10 @@ hipError_t launch_spw(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx,
     const int64_t groups = (M + kTokensPerWG - 1) / kTokensPerWG;
     int64_t grid = (int64_t)256 * wgs_per_cu;
     if (grid > groups) grid = groups;
-    const size_t smem = sizeof(float) * ((size_t)nb * kBlock + (size_t)2 * nw * 16);
+    const size_t smem = diag_table_bytes(nb) + sizeof(float) * (size_t)2 * nw * 16 + 1024;   // table, maxima, dump area
     hipLaunchKernelGGL((rotate_quant_kernel<SPW, MAXT>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
-                       X, M, nb, ldx, diag, Xq, sx, static_cast<const uint4 *>(warm), warm ? warm_bytes / 16 : 0);
+                       X, M, nb, ldx, diag, Xq, sx, static_cast<const uint4 *>(warm),
+                       (warm && warm_bytes < ((int64_t)1 << 32)) ? warm_bytes / 16 : 0);   // 32-bit byte offsets in the copy
     return hipGetLastError();
 }
 
@@ -205,15 +292,17 @@ hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx,
     const int nb = K / kBlock;
     if (nb > kRQMaxBlocks) return launch_rotate_quant_wide(X, M, K, ldx, diag, Xq, sx, st);
     // three blocks per wave (two or one for narrow rows), then rebalance; workgroups of up to
-    // 12 waves, as many per compute unit as 12 resident waves allow
+    // 12 waves, as many per compute unit as stay resident (with three blocks per wave the kernel
+    // holds 166 registers and small workgroups pack two waves per SIMD, eight per compute unit)
     int spw = nb < 3 ? nb : 3;
-    // few token groups (less than two workgroups per compute unit): spread each row over more
-    // waves instead, so that the loads in flight still cover the memory latency
+    // few token groups (fewer than six waves per compute unit): spread each row over more waves
+    // instead, so that the loads in flight still cover the memory latency
     const int64_t groups = (M + kTokensPerWG - 1) / kTokensPerWG;
-    while (spw > 1 && groups * ((nb + spw - 1) / spw) < 256 * 8 && (nb + spw - 2) / (spw - 1) <= 12) --spw;
+    while (spw > 1 && groups * ((nb + spw - 1) / spw) < 256 * 6 && (nb + spw - 2) / (spw - 1) <= 12) --spw;
     const int nw = (nb + spw - 1) / spw;
     spw = (nb + nw - 1) / nw;
-    const int wgs = 12 / nw > 0 ? 12 / nw : 1;
+    const int resident = spw == 3 ? 8 : 12;
+    const int wgs = resident / nw > 0 ? resident / nw : 1;
     const bool small = nw <= 4;      // up to 256 threads: no register cap from co-residency
     switch (spw) {
         case 1: return small ? launch_spw<1, 256>(X, M, nb, nw, ldx, diag, Xq, sx, warm, warm_bytes, wgs, st)
