@@ -70,24 +70,42 @@ __device__ __forceinline__ void epilogue_w8(const v4i (&acc)[TN][TM], const Gemm
 // WN * 2-byte row segments (128 B for a 64-channel wave tile), 16 bytes per lane.
 // `stage` is the wave's private LDS region of WM rows of WN * 2 + 16 bytes (the pad spreads the
 // column-wise writes over the banks).
+// The scales and biases a lane needs in the row-wise epilogue.  Requested before the last k-tile's
+// matrix instructions, they arrive while those run instead of stalling the epilogue.
+template <int TN, int TM>
+struct EpilogueOperands {
+    float sxm[TM];
+    float4 s[TN], bi[TN];
+    __device__ __forceinline__ void load(const GemmArgs &g, int64_t m_wave, int n_wave, int lane)
+    {
+        const int l16 = lane & 15, lg = lane >> 4;
+#pragma unroll
+        for (int b = 0; b < TM; ++b) sxm[b] = g.sx[m_wave + b * 16 + l16];
+        const bool has_bias = g.bias != nullptr;
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+            const int n = n_wave + a * 16 + lg * 4;
+            s[a] = *reinterpret_cast<const float4 *>(g.sw + n);
+            bi[a] = has_bias ? *reinterpret_cast<const float4 *>(g.bias + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+};
+
 template <int TN, int TM, bool DEBUG>
 __device__ __forceinline__ void epilogue_w8_rows(const v4i (&acc)[TN][TM], const GemmArgs &g,
-                                                 int64_t m_wave, int n_wave, int lane, int8_t *stage)
+                                                 int64_t m_wave, int n_wave, int lane, int8_t *stage,
+                                                 const EpilogueOperands<TN, TM> &eo)
 {
     constexpr int WN = TN * 16, WM = TM * 16;
     constexpr int ROWB = WN * 2 + 16;
     constexpr int LPR = WN / 8;                  // lanes per row on the way out
     const int l16 = lane & 15, lg = lane >> 4;
-    float sxm[TM];
-#pragma unroll
-    for (int b = 0; b < TM; ++b) sxm[b] = g.sx[m_wave + b * 16 + l16];
-    const bool has_bias = g.bias != nullptr;
+    const float (&sxm)[TM] = eo.sxm;
 #pragma unroll
     for (int a = 0; a < TN; ++a) {
         const int n = n_wave + a * 16 + lg * 4;
-        const float4 s = *reinterpret_cast<const float4 *>(g.sw + n);
-        float4 bi = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (has_bias) bi = *reinterpret_cast<const float4 *>(g.bias + n);
+        const float4 s = eo.s[a];
+        const float4 bi = eo.bi[a];
 #pragma unroll
         for (int b = 0; b < TM; ++b) {
             if constexpr (DEBUG) {
@@ -394,16 +412,19 @@ __global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
         interleave_hint<TN + TM, TN * TM>();
         st = nst;
     }
-    // last tile
+    // last tile (every copy has landed: ordinary loads no longer queue behind them)
+    constexpr bool kRowsEpilogue = 4 * WM * (WN * 2 + 16) <= NS * STAGE;
+    EpilogueOperands<TN, TM> eo;
+    if constexpr (kRowsEpilogue) eo.load(g, m0 + wm * WM, n0 + wn * WN, lane);
     load_frags<TN, TM, BK>(af1, bf1, smem + st * STAGE, woff[1], xoff[1]);
     mfma_block<TN, TM>(acc, af0, bf0);
     interleave_hint<TN + TM, TN * TM>();
     mfma_block<TN, TM>(acc, af1, bf1);
 
-    if constexpr (4 * WM * (WN * 2 + 16) <= NS * STAGE) {
+    if constexpr (kRowsEpilogue) {
         // every wave is done with the ring: reuse it as the epilogue's staging space
         __syncthreads();
-        epilogue_w8_rows<TN, TM, DEBUG>(acc, g, m0 + wm * WM, n0 + wn * WN, lane, smem + wave * (WM * (WN * 2 + 16)));
+        epilogue_w8_rows<TN, TM, DEBUG>(acc, g, m0 + wm * WM, n0 + wn * WN, lane, smem + wave * (WM * (WN * 2 + 16)), eo);
     } else {
         epilogue_w8<TN, TM, DEBUG, true>(acc, g, m0 + wm * WM + l16, n0 + wn * WN + lg * 4);
     }
@@ -867,7 +888,8 @@ hipError_t launch_qgemm4_dma(const GemmArgs &a, bool debug, int variant, hipStre
 // pipe: 5: 256x128 NS3   6: 128x128 NS4   7: 128x256 NS3   8: 256x256 NS2   9: 128x128 NS2
 // persistent: 10: 128x128 NS2 (2 workgroups per CU)   11: 256x128 NS3   12: 128x256 NS3   13: 128x128 NS4
 // pipe, 144-channel tiles (1152 = 8 x 144: the DiT-XL/2 widths give whole rounds of 256 tiles): 14: 128x144 NS4   15: 128x144 NS2 (two workgroups per CU)
-int dma_num_variants() { return 16; }
+// 256 tokens x 144 channels (waves 64 x 144): 16: NS2   17: NS3
+int dma_num_variants() { return 18; }
 
 hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStream_t st)
 {
@@ -888,6 +910,8 @@ hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStre
         case 13: return launch_persist<128, 128, 4, 2, 2, 1>(a, debug, st);
         case 14: return launch_pipe<128, 144, 4, 4, 1>(a, debug, st);
         case 15: return launch_pipe<128, 144, 2, 4, 1>(a, debug, st);
+        case 16: return launch_pipe<256, 144, 2, 4, 1>(a, debug, st);
+        case 17: return launch_pipe<256, 144, 3, 4, 1>(a, debug, st);
     }
     return hipErrorInvalidValue;
 }
