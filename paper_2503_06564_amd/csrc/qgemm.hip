@@ -282,17 +282,17 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int
     }
     // built-in choice (measured crossovers on the DiT-XL/2 widths): the 256 x 256 kernel once
     // there are well over 256 of its tiles; below that, where the width is a multiple of 144
-    // (1152 = 8 x 144, so whole rounds of tiles), 128 x 144 tiles: with a four-stage ring and one
-    // workgroup per compute unit where the deeper prefetch pays (long K with at most two rounds
-    // of tiles, or so few tiles that one round covers the chip anyway), else with two stages and
-    // two workgroups per compute unit; other widths take the software-pipelined 128 x 128
+    // (1152 = 8 x 144, so whole rounds of tiles), 128 x 144 tiles: at most one tile per compute
+    // unit -> one workgroup per compute unit with a four-stage ring, or for long K the kernel whose
+    // two wave groups split K inside the workgroup; more tiles -> two stages and two workgroups
+    // per compute unit; other widths take the software-pipelined 128 x 128
     // kernel, two workgroups per compute unit (it hands ragged shapes to the ring kernel itself)
     if (variant < 0) {
         variant = kRegVariants + 9;
         const int64_t tiles144 = (a.N % 144 == 0 && M % 128 == 0 && a.K >= 512) ? (M / 128) * (a.N / 144) : 0;
         const int64_t tiles256 = ((M + 255) / 256) * ((a.N + 255) / 256);
-        if (tiles144 > 0 && (tiles144 <= 256 || (a.K >= 2304 && tiles144 <= 512)))
-            variant = kRegVariants + 14;
+        if (tiles144 > 0 && tiles144 <= 256)
+            variant = a.K >= 2304 ? kRegVariants + 18 : kRegVariants + 14;
         else if (tiles256 >= 400 && wide_supports(a))
             variant = kRegVariants + dma_num_variants();
         else if (tiles144 > 0)

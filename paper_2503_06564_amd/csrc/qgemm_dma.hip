@@ -430,6 +430,165 @@ __global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
     }
 }
 
+// ---- software-pipelined kernel, two wave groups splitting K inside the workgroup ----------------
+// Same tile and pipeline as qgemm8_pipe_kernel, but with eight waves: waves 0-3 accumulate the
+// first half of the k-tiles, waves 4-7 the second half, each group on its own ring of NS stages;
+// at the end the groups swap halves of their sums through LDS and each finishes the token rows
+// of one half (the first group takes one k-tile more when their number is odd; the second then
+// sits out the last step, so that both meet at the same barriers).  For a launch of one tile per compute unit (few tokens, long K) this puts two
+// independent instruction streams on every SIMD, which overlap each other's copy issue, LDS reads
+// and barriers the way a second resident workgroup would, without a second tile to give it.
+// Needs at least NS k-tiles per group.
+template <int BM, int BN, int NS, int WGM, int WGN, bool DEBUG>
+__global__ __launch_bounds__(2 * kThreads) void qgemm8_pipe2_kernel(GemmArgs g)
+{
+    static_assert(WGM * WGN == 4, "four waves per group");
+    static_assert(NS >= 2, "at least two stages");
+    constexpr int BK = 128;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int TM = WM / 16, TN = WN / 16;
+    constexpr int CPR = BK / 16;
+    constexpr int WG8 = BN / 8;
+    constexpr int XBYTES = BM * BK;
+    constexpr int PX = XBYTES / 4096, PW = (WG8 + 3) / 4;
+    constexpr int WBYTES = 4 * PW * 1024, STAGE = XBYTES + WBYTES;
+    constexpr int P = PX + PW;
+    constexpr int RING = NS * STAGE;
+    static_assert(BN % 16 == 0 && PX >= 1 && PX % 2 == 0 && (NS - 1) * P < 64, "copy count per wave out of range");
+    static_assert(TM % 2 == 0, "each group finishes half of the token tiles");
+    constexpr int TMH = TM / 2;
+    constexpr int XCH = TN * TMH * 256 * 16;         // bytes of the sums one group hands over
+    constexpr int STG = 16 * TMH * (WN * 2 + 16);    // a wave's staging block in the epilogue
+    static_assert(XCH + 4 * STG <= RING, "hand-over area and epilogue staging must fit a group's ring");
+
+    extern __shared__ __align__(16) int8_t smem[];
+
+    const int tid = threadIdx.x & 255;
+    const int lane = tid & 63;
+    const int kg = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);      // wave group: which half of K
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int l16 = lane & 15, lg = lane >> 4;
+    int8_t *const ring = smem + kg * RING;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t *)ring;
+
+    int tm_idx, tn_idx;
+    tile_map(blockIdx.x, g.tiles_m, g.tiles_n, tm_idx, tn_idx);
+    const int64_t m0 = (int64_t)tm_idx * BM;
+    const int n0 = tn_idx * BN;
+    const int K = g.K;
+    const int KTA = K / BK;                          // k-tiles of the product
+    const int KTX = (KTA + 1) / 2;                   // steps of both groups = k-tiles of the first
+    const int KT = kg == 0 ? KTX : KTA - KTX;        // this group's k-tiles
+    const int kofs = kg * KTX * BK;                  // this group's first k
+
+    uint32_t voff[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int r = 8 * p + (lane >> 3);
+        voff[p] = (uint32_t)(r * K + (((lane & 7) ^ chunk_swizzle<BK>(r)) * 16));
+    }
+    const int8_t *xbase = g.Xq + (m0 + wave * PX * 8) * K + kofs;
+    const int8_t *wbase = static_cast<const int8_t *>(g.Wc) + (size_t)n0 * K + kofs;
+    const int K16 = 16 * K;
+    uint32_t voffw[PW];
+    int wrow[PW];
+#pragma unroll
+    for (int i = 0; i < PW; ++i) {
+        int j = wave * PW + i;
+        if (j > WG8 - 1) j = WG8 - 1;
+        voffw[i] = voff[j & 1];
+        wrow[i] = __builtin_amdgcn_readfirstlane((j & ~1) * 8);
+    }
+
+    auto issue = [&](int on, int kt, int st) {
+        const uint32_t sbase = lds0 + st * STAGE;
+        const int8_t *xs = xbase + kt * BK, *ws = wbase + kt * BK;
+#pragma unroll
+        for (int i = 0; i < PX; ++i)
+            dma_1k_if(on, voff[i & 1], xs + (i >> 1) * K16, sbase + (wave * PX + i) * 1024);
+#pragma unroll
+        for (int i = 0; i < PW; ++i)
+            dma_1k_if(on, voffw[i], ws + wrow[i] * K, sbase + XBYTES + (wave * PW + i) * 1024);
+    };
+
+    int xoff[2], woff[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int pc = (4 * h + lg) ^ chunk_swizzle<BK>(l16);
+        xoff[h] = ((wm * WM + l16) * CPR + pc) * 16;
+        woff[h] = XBYTES + ((wn * WN + l16) * CPR + pc) * 16;
+    }
+
+    v4i acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b) acc[a][b] = v4i{0, 0, 0, 0};
+    v4i af0[TN], bf0[TM], af1[TN], bf1[TM];
+
+#pragma unroll
+    for (int t = 0; t < NS; ++t) issue(t < KT, t, t);
+    wait_vmcnt_or_zero<(NS - 1) * P>(KT >= NS);
+    __syncthreads();
+    load_frags<TN, TM, BK>(af0, bf0, ring, woff[0], xoff[0]);
+
+    // both groups run the same number of iterations, so they meet at the same barriers
+    int st = 0;
+    for (int kt = 0; kt + 1 < KTX; ++kt) {
+        const int nst = (st + 1 == NS) ? 0 : st + 1;
+        const int more = kt + NS < KT;
+        load_frags<TN, TM, BK>(af1, bf1, ring + st * STAGE, woff[1], xoff[1]);
+        mfma_block<TN, TM>(acc, af0, bf0);
+        interleave_hint<TN + TM, TN * TM>();
+        wait_vmcnt_or_zero<(NS - 2) * P>(more);
+        __syncthreads();
+        issue(more, kt + NS, st);
+        load_frags<TN, TM, BK>(af0, bf0, ring + nst * STAGE, woff[0], xoff[0]);
+        mfma_block<TN, TM>(acc, af1, bf1);
+        interleave_hint<TN + TM, TN * TM>();
+        st = nst;
+    }
+    // last step (the second group has no tile left here when the count is odd)
+    const int64_t m_own = m0 + wm * WM + kg * TMH * 16;      // token rows this group finishes
+    EpilogueOperands<TN, TMH> eo;
+    eo.load(g, m_own, n0 + wn * WN, lane);
+    if (KT == KTX) {
+        load_frags<TN, TM, BK>(af1, bf1, ring + st * STAGE, woff[1], xoff[1]);
+        mfma_block<TN, TM>(acc, af0, bf0);
+        interleave_hint<TN + TM, TN * TM>();
+        mfma_block<TN, TM>(acc, af1, bf1);
+    }
+
+    // Hand-over.  Both rings are free once every wave has read its last fragments.  Each group
+    // writes the sums of the token tiles it does not finish into the other group's ring (one
+    // 16-byte piece per lane and accumulator tile), then adds what it received to its own half.
+    __syncthreads();
+    {
+        v4i *const out = reinterpret_cast<v4i *>(smem + (1 - kg) * RING);
+#pragma unroll
+        for (int a = 0; a < TN; ++a)
+#pragma unroll
+            for (int b = 0; b < TMH; ++b) {
+                if (kg == 0) out[(a * TMH + b) * 256 + tid] = acc[a][TMH + b];     // register indices stay static
+                else out[(a * TMH + b) * 256 + tid] = acc[a][b];
+            }
+    }
+    __syncthreads();
+    v4i own[TN][TMH];
+    {
+        const v4i *const in = reinterpret_cast<const v4i *>(ring);
+#pragma unroll
+        for (int a = 0; a < TN; ++a)
+#pragma unroll
+            for (int b = 0; b < TMH; ++b) {
+                const v4i o = in[(a * TMH + b) * 256 + tid];
+                own[a][b] = (kg == 0 ? acc[a][b] : acc[a][TMH + b]) + o;
+            }
+    }
+    epilogue_w8_rows<TN, TMH, DEBUG>(own, g, m_own, n0 + wn * WN, lane, ring + XCH + wave * STG, eo);
+}
+
 // ---- persistent software-pipelined kernel -------------------------------------------------------
 // A workgroup walks a list of output tiles.  The k-tile ring never drains between tiles: while
 // the last k-tiles of tile T are multiplied, the first k-tiles of tile T+1 are already being
@@ -845,6 +1004,30 @@ hipError_t launch_pipe(const GemmArgs &a, bool debug, hipStream_t st)
     return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st);
 }
 
+template <int BM, int BN, int NS, int WGM, int WGN>
+hipError_t launch_pipe2(const GemmArgs &a, bool debug, hipStream_t st)
+{
+    // full tiles and at least NS k-tiles per wave group; else the one-group kernel
+    if (a.M % BM != 0 || a.N % BN != 0 || a.K / 256 < NS) return launch_pipe<BM, BN, 2 * NS, WGM, WGN>(a, debug, st);
+    static bool done[2] = {false, false};
+    const size_t smem = (size_t)2 * NS * (BM * 128 + 4 * ((BN / 8 + 3) / 4) * 1024);
+    GemmArgs g = a;
+    g.tiles_m = (int)(g.M / BM);
+    g.tiles_n = g.N / BN;
+    auto go = [&](auto kern, bool &attr_done) -> hipError_t {
+        if (!attr_done) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(2 * kThreads), smem, st, g);
+        return hipGetLastError();
+    };
+    if (debug) return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, true>, done[1]);
+    return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, false>, done[0]);
+}
+
 template <int BM, int BN, int NS, int WGM, int WGN, int WGS_PER_CU>
 hipError_t launch_persist(const GemmArgs &a, bool debug, hipStream_t st)
 {
@@ -889,7 +1072,8 @@ hipError_t launch_qgemm4_dma(const GemmArgs &a, bool debug, int variant, hipStre
 // persistent: 10: 128x128 NS2 (2 workgroups per CU)   11: 256x128 NS3   12: 128x256 NS3   13: 128x128 NS4
 // pipe, 144-channel tiles (1152 = 8 x 144: the DiT-XL/2 widths give whole rounds of 256 tiles): 14: 128x144 NS4   15: 128x144 NS2 (two workgroups per CU)
 // 256 tokens x 144 channels (waves 64 x 144): 16: NS2   17: NS3
-int dma_num_variants() { return 18; }
+// 18: 128x144, two wave groups splitting K inside the workgroup, two stages each
+int dma_num_variants() { return 19; }
 
 hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStream_t st)
 {
@@ -912,6 +1096,7 @@ hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStre
         case 15: return launch_pipe<128, 144, 2, 4, 1>(a, debug, st);
         case 16: return launch_pipe<256, 144, 2, 4, 1>(a, debug, st);
         case 17: return launch_pipe<256, 144, 3, 4, 1>(a, debug, st);
+        case 18: return launch_pipe2<128, 144, 2, 4, 1>(a, debug, st);
     }
     return hipErrorInvalidValue;
 }

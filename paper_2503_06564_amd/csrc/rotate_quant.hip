@@ -98,27 +98,6 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
     load_raw(raw[0], 0, tg);
     if (SPW > 1) load_raw(raw[1], 1, tg);
     else load_raw(raw[1], 0, tg + gridDim.x);
-    // Optional: read the next kernel's weights once (at most four 16-byte pieces per lane, spread
-    // over the whole grid; more than that is left cold).  They only have to pass through the
-    // memory-side cache so that the product kernel does not start on cold DRAM: the copies go
-    // straight to a 1 KB dump area in LDS that nobody reads, so they hold no registers and nothing
-    // waits for them before the end of the kernel.  (The compiler does not see them in its count
-    // of outstanding loads: its waits can only become stricter by that, never too weak, because
-    // the counter retires in order.)
-    if (warm_chunks > 0) {
-        const uint32_t dump = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_raw +
-                              (uint32_t)(diag_table_bytes(nb) + sizeof(float) * 2 * nw * 16);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int64_t c0 = ((int64_t)t * gridDim.x + blockIdx.x) * blockDim.x + (wave << 6);   // wave-uniform
-            if (c0 < warm_chunks) {
-                int64_t c = c0 + lane;
-                if (c >= warm_chunks) c = warm_chunks - 1;
-                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                             :: "v"((uint32_t)(c << 4)), "s"(warm), "s"(dump) : "memory", "m0");
-            }
-        }
-    }
     // the diagonal in three bf16 pieces (truncations: each remainder is exact in fp32)
     {
         uint2 *const tblw = reinterpret_cast<uint2 *>(lds_raw);
@@ -156,6 +135,31 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
                          ((__builtin_popcount(qrow & (4 + g)) & 1) ? 0x80000000u : 0u);
     const uint32_t sg1 = ((__builtin_popcount(qrow & (8 + g)) & 1) ? 0x00008000u : 0u) |
                          ((__builtin_popcount(qrow & (12 + g)) & 1) ? 0x80000000u : 0u);
+
+    // Optional: read the next kernel's weights once (at most four 16-byte pieces per lane, spread
+    // over the whole grid; more than that is left cold).  They only have to pass through the
+    // memory-side cache so that the product kernel does not start on cold DRAM: the copies go
+    // straight to a 1 KB dump area in LDS that nobody reads, so they hold no registers and nothing
+    // waits for them before the end of the kernel.  They are issued after the first token group's
+    // rotation, when this wave's own activations have arrived and the memory system is no longer
+    // busy with the launch's first wave of loads.  (The compiler does not see them in its count
+    // of outstanding loads: its waits can only become stricter by that, never too weak, because
+    // the counter retires in order.)
+    bool warm_pending = warm_chunks > 0;
+    auto issue_warm = [&]() {
+        const uint32_t dump = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_raw +
+                              (uint32_t)(diag_table_bytes(nb) + sizeof(float) * 2 * nw * 16);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int64_t c0 = ((int64_t)t * gridDim.x + blockIdx.x) * blockDim.x + (wave << 6);   // wave-uniform
+            if (c0 < warm_chunks) {
+                int64_t c = c0 + lane;
+                if (c >= warm_chunks) c = warm_chunks - 1;
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                             :: "v"((uint32_t)(c << 4)), "s"(warm), "s"(dump) : "memory", "m0");
+            }
+        }
+    };
 
     int parity = 0;
     // one token group; P = ring slot of its first item
@@ -220,6 +224,11 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
                 // ragged last slot: still advance the sequence
                 load_raw(raw[(P + i) & 1], (i + 2) % SPW, tg + (int64_t)((i + 2) / SPW) * gridDim.x);
             }
+        }
+
+        if (warm_pending) {
+            issue_warm();
+            warm_pending = false;
         }
 
         // token absmax: over the four lane-rows of this wave, then over the waves through LDS

@@ -157,7 +157,7 @@ def test_qgemm_w8_all_variants(oracle, M, K, N, variant):
 # full-tile shapes for the software-pipelined kernels (variants 11..15), including K shorter
 # than the stage ring (one and two k-tiles) and the real layer widths
 PIPE_SHAPES = [(256, 128, 256), (512, 256, 256), (256, 1152, 512), (768, 384, 768), (512, 4608, 256), (2048, 512, 2304),
-               (1024, 1152, 1152), (384, 640, 288), (512, 256, 288)]
+               (1024, 1152, 1152), (384, 640, 288), (512, 256, 288), (256, 1024, 288), (384, 4608, 144)]
 
 
 @pytest.mark.parametrize("M,K,N", PIPE_SHAPES)
