@@ -10,7 +10,8 @@
  * What it computes (paper Sec. 3.1-3.2):
  *   F_t(X_t, W) = G_t(X_t) . H_t(W)                             (Eq. 10)
  *   G_t(X) = (X . Delta_t) . R           H_t(W) = R^T . (Delta_t^-1 . W)
- * with P = I and R^(2) = I (single block rotation), R block-diagonal with
+ * with P = I and R^(2) = I (single block rotation; the functions of the section
+ * "second rotation and zigzag permutation" add P and R^(2) of Eq. 9), R block-diagonal with
  * 2^n x 2^n blocks (the BlockDiag equation of Sec. 3.2), each block the
  * orthonormal Sylvester Hadamard matrix.  Activations are quantised per
  * token online, weights per output channel (W8) or per (input-group,
@@ -176,6 +177,97 @@ int trdq_oracle_quant_tokens(const double *V, int64_t M, int K, int8_t *Xq, doub
             Xq[i * (int64_t)K + k] = (int8_t)q;
         }
     }
+    return 0;
+}
+
+/* ------------------------------------- second rotation and zigzag permutation */
+
+/* Zigzag permutation (Sec. 3.2, "zigzag permutation"): the channels, taken in order of
+ * decreasing magnitude, are dealt one at a time to the K/B blocks: first to blocks
+ * 0, 1, ..., nb-1, then back nb-1, ..., 1, 0, and so on back and forth, so that no block
+ * keeps receiving the largest (or the smallest) of each round.  Round r fills slot r of
+ * every block.  perm[b*B + r] = the channel placed there; as a matrix, P[perm[k'], k'] = 1,
+ * i.e. (U P)[k'] = U[perm[k']].  Equal magnitudes keep their channel order. */
+int trdq_oracle_zigzag(const double *mag, int K, int B, int32_t *perm)
+{
+    if (!mag || !perm || K <= 0 || B <= 0 || K % B) return 1;
+    int nb = K / B;
+    int32_t *order = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);
+    if (!order) return 2;
+    for (int k = 0; k < K; ++k) order[k] = k;
+    /* insertion sort: decreasing magnitude, stable */
+    for (int t = 1; t < K; ++t) {
+        int32_t c = order[t];
+        int u = t - 1;
+        while (u >= 0 && mag[order[u]] < mag[c]) { order[u + 1] = order[u]; --u; }
+        order[u + 1] = c;
+    }
+    for (int r = 0; r < B; ++r)
+        for (int i = 0; i < nb; ++i) {
+            int b = (r % 2 == 0) ? i : nb - 1 - i;
+            perm[b * B + r] = order[r * nb + i];
+        }
+    free(order);
+    return 0;
+}
+
+/* out[i, k'] = V[i, perm[k']]   (right-multiplication by the permutation matrix P) */
+int trdq_oracle_permute_cols(const double *V, int64_t M, int K, const int32_t *perm, double *out)
+{
+    if (!V || !perm || !out || M < 0 || K <= 0) return 1;
+    for (int k = 0; k < K; ++k)
+        if (perm[k] < 0 || perm[k] >= K) return 1;
+    for (int64_t i = 0; i < M; ++i)
+        for (int k = 0; k < K; ++k) out[i * (int64_t)K + k] = V[i * (int64_t)K + perm[k]];
+    return 0;
+}
+
+/* V = U . R for float64 U [M, K]: the second block rotation R^(2) of Eq. 9, same blocks as R^(1). */
+int trdq_oracle_rotate_f64(const double *U, int64_t M, int K, int B, double *V)
+{
+    if (!U || !V || M < 0 || K <= 0 || B <= 0 || (B & (B - 1)) || K % B) return 1;
+    double *R = make_rotation_block(B);
+    if (!R) return 2;
+    int nb = K / B;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int b = 0; b < nb; ++b)
+            for (int j = 0; j < B; ++j) {
+                double s = 0.0;
+                for (int k = 0; k < B; ++k) s += U[i * (int64_t)K + (int64_t)b * B + k] * R[(size_t)k * B + j];
+                V[i * (int64_t)K + (int64_t)b * B + j] = s;
+            }
+    free(R);
+    return 0;
+}
+
+/* out[k', n] = Wp[perm[k'], n]   (left-multiplication by P^T) */
+int trdq_oracle_permute_rows(const double *Wp, int K, int N, const int32_t *perm, double *out)
+{
+    if (!Wp || !perm || !out || K <= 0 || N <= 0) return 1;
+    for (int k = 0; k < K; ++k)
+        if (perm[k] < 0 || perm[k] >= K) return 1;
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n) out[(size_t)k * N + n] = Wp[(size_t)perm[k] * N + n];
+    return 0;
+}
+
+/* out = R^T . Wp for float64 Wp [K, N]: the (R^(2))^T factor of H_t(W) in Eq. 9. */
+int trdq_oracle_rotate_rows_f64(const double *Wp, int K, int N, int B, double *out)
+{
+    if (!Wp || !out || K <= 0 || N <= 0 || B <= 0 || (B & (B - 1)) || K % B) return 1;
+    double *R = make_rotation_block(B);
+    if (!R) return 2;
+    int nb = K / B;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int b = 0; b < nb; ++b)
+            for (int j = 0; j < B; ++j) {
+                double s = 0.0;
+                for (int k = 0; k < B; ++k) s += R[(size_t)k * B + j] * Wp[(size_t)(b * B + k) * N + n];
+                out[(size_t)(b * B + j) * N + n] = s;
+            }
+    free(R);
     return 0;
 }
 

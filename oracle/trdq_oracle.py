@@ -4,8 +4,9 @@ TEST INFRASTRUCTURE ONLY: argument marshalling around the plain C functions,
 plus `acc_exact_blas`, the same integer product evaluated through a float64
 library matmul (every partial sum is an integer below 2^53, hence exact),
 used where the plain loop would take minutes.  The steps follow Eq. 1-2
-(symmetric form), the BlockDiag rotation and Eq. 9/10 of the paper with
-P = I and R^(2) = I.
+(symmetric form), the BlockDiag rotation and Eq. 9/10 of the paper, with
+P = I and R^(2) = I in the basic path and with the zigzag permutation and the
+second rotation in the *_rpr functions.
 """
 import ctypes as C
 import os
@@ -39,6 +40,11 @@ def lib():
         L.trdq_oracle_dequant.argtypes = [p, p, p, p, i64, i32, i32, p, p]
         L.trdq_oracle_linear.argtypes = [p, i64, i32, i64, p, i32, p, p, i32, i32,
                                          p, p, p, p, p, p]
+        L.trdq_oracle_zigzag.argtypes = [p, i32, i32, p]
+        L.trdq_oracle_permute_cols.argtypes = [p, i64, i32, p, p]
+        L.trdq_oracle_rotate_f64.argtypes = [p, i64, i32, i32, p]
+        L.trdq_oracle_permute_rows.argtypes = [p, i32, i32, p, p]
+        L.trdq_oracle_rotate_rows_f64.argtypes = [p, i32, i32, i32, p]
         L.trdq_oracle_threads.restype = i32
         _lib = L
     return _lib
@@ -133,6 +139,69 @@ def quant_weights(Wp, wbits=8, group=128):
 
 def prepare_weights(W, d=None, B=128, wbits=8):
     return quant_weights(rotate_weights(W, d, B), wbits, B)
+
+
+# ---- full G_t / H_t of Eq. 9: first rotation, zigzag permutation, second rotation ----------
+
+def zigzag(mag, B=128):
+    """Zigzag permutation of Sec. 3.2 from per-channel magnitudes; perm[k'] = source channel."""
+    mag = _c(mag, np.float64)
+    K = mag.shape[0]
+    perm = np.empty(K, dtype=np.int32)
+    _chk(lib().trdq_oracle_zigzag(_ptr(mag), K, B, _ptr(perm)), "zigzag")
+    return perm
+
+
+def permute_cols(V, perm):
+    V = _c(V, np.float64)
+    M, K = V.shape
+    perm = _c(perm, np.int32)
+    out = np.empty((M, K), dtype=np.float64)
+    _chk(lib().trdq_oracle_permute_cols(_ptr(V), M, K, _ptr(perm), _ptr(out)), "permute_cols")
+    return out
+
+
+def rotate_f64(U, B=128):
+    U = _c(U, np.float64)
+    M, K = U.shape
+    V = np.empty((M, K), dtype=np.float64)
+    _chk(lib().trdq_oracle_rotate_f64(_ptr(U), M, K, B, _ptr(V)), "rotate_f64")
+    return V
+
+
+def rotate_rpr(X_bf16, d, perm, B=128):
+    """V = (X diag(d)) R P R as float64 (G_t of Eq. 9)."""
+    return rotate_f64(permute_cols(rotate(X_bf16, d, B), perm), B)
+
+
+def rotate_quant_rpr(X_bf16, d, perm, B=128):
+    return quant_tokens(rotate_rpr(X_bf16, d, perm, B))
+
+
+def rotate_weights_rpr(W, d, perm, B=128):
+    """W' = R^T P^T R^T diag(1/d) W as float64 (H_t of Eq. 9)."""
+    W1 = rotate_weights(W, d, B)
+    K, N = W1.shape
+    perm = _c(perm, np.int32)
+    W2 = np.empty((K, N), dtype=np.float64)
+    _chk(lib().trdq_oracle_permute_rows(_ptr(W1), K, N, _ptr(perm), _ptr(W2)), "permute_rows")
+    W3 = np.empty((K, N), dtype=np.float64)
+    _chk(lib().trdq_oracle_rotate_rows_f64(_ptr(W2), K, N, B, _ptr(W3)), "rotate_rows_f64")
+    return W3
+
+
+def prepare_weights_rpr(W, d, perm, B=128, wbits=8):
+    return quant_weights(rotate_weights_rpr(W, d, perm, B), wbits, B)
+
+
+def linear_rpr(X_bf16, W, d, perm, bias=None, B=128, wbits=8, exact_blas=False):
+    """Whole path with the full G_t and H_t of Eq. 9."""
+    Xq, sx = rotate_quant_rpr(X_bf16, d, perm, B)
+    Wq, sw = prepare_weights_rpr(W, d, perm, B, wbits)
+    group = None if wbits == 8 else B
+    acc = (acc_exact_blas if exact_blas else igemm)(Xq, Wq, group)
+    Y, Yd = dequant(acc, sx, sw, bias, return_f64=True)
+    return dict(Xq=Xq, sx=sx, Wq=Wq, sw=sw, acc=acc, Y=Y, Yd=Yd)
 
 
 def pack_int4(Wq):

@@ -305,21 +305,22 @@ __device__ __forceinline__ void interleave_hint()
 // the workgroup waits for tile kt+1, passes the barrier (which also retires every read of
 // tile kt's stage), refills that stage with tile kt+NS and starts reading tile kt+1.
 template <int BM, int BN, int NS, int WGM, int WGN, bool DEBUG>
-__global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
+__global__ __launch_bounds__(WGM * WGN * 64) void qgemm8_pipe_kernel(GemmArgs g)
 {
-    static_assert(WGM * WGN == 4, "four waves per workgroup");
+    constexpr int NW = WGM * WGN;                     // waves per workgroup
+    static_assert(NW == 4 || NW == 8, "four or eight waves per workgroup");
     static_assert(NS >= 2, "at least two stages");
     constexpr int BK = 128;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int TM = WM / 16, TN = WN / 16;
     constexpr int CPR = BK / 16;
     // weight rows are copied 8 at a time; a channel count that does not split evenly over the
-    // four waves (BN = 144: 18 copies) is rounded up, the surplus copies repeat the last rows
+    // waves (BN = 144: 18 copies) is rounded up, the surplus copies repeat the last rows
     // into LDS space nobody reads
     constexpr int WG8 = BN / 8;                       // 8-row groups of weight rows
     constexpr int XBYTES = BM * BK;
-    constexpr int PX = XBYTES / 4096, PW = (WG8 + 3) / 4;
-    constexpr int WBYTES = 4 * PW * 1024, STAGE = XBYTES + WBYTES;
+    constexpr int PX = XBYTES / (NW * 1024), PW = (WG8 + NW - 1) / NW;
+    constexpr int WBYTES = NW * PW * 1024, STAGE = XBYTES + WBYTES;
     constexpr int P = PX + PW;
     static_assert(BN % 16 == 0 && PX >= 1 && PX % 2 == 0 && (NS - 1) * P < 64, "copy count per wave out of range");
 
@@ -413,7 +414,7 @@ __global__ __launch_bounds__(kThreads) void qgemm8_pipe_kernel(GemmArgs g)
         st = nst;
     }
     // last tile (every copy has landed: ordinary loads no longer queue behind them)
-    constexpr bool kRowsEpilogue = 4 * WM * (WN * 2 + 16) <= NS * STAGE;
+    constexpr bool kRowsEpilogue = NW * WM * (WN * 2 + 16) <= NS * STAGE;
     EpilogueOperands<TN, TM> eo;
     if constexpr (kRowsEpilogue) eo.load(g, m0 + wm * WM, n0 + wn * WN, lane);
     load_frags<TN, TM, BK>(af1, bf1, smem + st * STAGE, woff[1], xoff[1]);
@@ -885,11 +886,12 @@ __global__ __launch_bounds__(kThreads) void qgemm4_ring_kernel(GemmArgs g)
             }
 #pragma unroll
             for (int b = 0; b < TM; ++b) bf[b] = *reinterpret_cast<const v4i *>(stage + xoff[h] + b * 16 * BK);
+            // the first half of a scale group starts from zero (a constant operand: no registers to clear)
 #pragma unroll
             for (int a = 0; a < TN; ++a)
 #pragma unroll
                 for (int b = 0; b < TM; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[a], bf[b], acc[a][b], 0, 0, 0);
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[a], bf[b], h == 0 ? v4i{0, 0, 0, 0} : acc[a][b], 0, 0, 0);
         }
 
         // end of scale group kt: facc += s_w[kt][n] * (16 * sum)
@@ -909,7 +911,6 @@ __global__ __launch_bounds__(kThreads) void qgemm4_ring_kernel(GemmArgs g)
                 facc[a][b][1] += sca.y * (float)acc[a][b][1];
                 facc[a][b][2] += sca.z * (float)acc[a][b][2];
                 facc[a][b][3] += sca.w * (float)acc[a][b][3];
-                acc[a][b] = v4i{0, 0, 0, 0};
             }
         }
         st = (st + 1 == NS) ? 0 : st + 1;
@@ -960,7 +961,8 @@ __global__ __launch_bounds__(kThreads) void qgemm4_ring_kernel(GemmArgs g)
 }
 
 template <typename Kern>
-hipError_t launch_kernel(Kern kern, bool &attr_done, const GemmArgs &a, int BM, int BN, size_t smem, hipStream_t st)
+hipError_t launch_kernel(Kern kern, bool &attr_done, const GemmArgs &a, int BM, int BN, size_t smem, hipStream_t st,
+                         int threads = kThreads)
 {
     GemmArgs g = a;
     g.tiles_m = (int)((g.M + BM - 1) / BM);
@@ -971,7 +973,7 @@ hipError_t launch_kernel(Kern kern, bool &attr_done, const GemmArgs &a, int BM, 
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(kThreads), smem, st, g);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(threads), smem, st, g);
     return hipGetLastError();
 }
 
@@ -999,9 +1001,10 @@ hipError_t launch_pipe(const GemmArgs &a, bool debug, hipStream_t st)
     // the pipelined kernel takes full tiles only; ragged shapes go to the ring kernel
     if (a.M % BM != 0 || a.N % BN != 0) return launch_ring<128, 128, 64, 4, 2, 2>(a, debug, st);
     static bool done[2] = {false, false};
-    const size_t smem = (size_t)NS * (BM * 128 + 4 * ((BN / 8 + 3) / 4) * 1024);
-    if (debug) return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, true>, done[1], a, BM, BN, smem, st);
-    return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st);
+    constexpr int NW = WGM * WGN;
+    const size_t smem = (size_t)NS * (BM * 128 + NW * ((BN / 8 + NW - 1) / NW) * 1024);
+    if (debug) return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, true>, done[1], a, BM, BN, smem, st, NW * 64);
+    return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st, NW * 64);
 }
 
 template <int BM, int BN, int NS, int WGM, int WGN>
@@ -1073,7 +1076,8 @@ hipError_t launch_qgemm4_dma(const GemmArgs &a, bool debug, int variant, hipStre
 // pipe, 144-channel tiles (1152 = 8 x 144: the DiT-XL/2 widths give whole rounds of 256 tiles): 14: 128x144 NS4   15: 128x144 NS2 (two workgroups per CU)
 // 256 tokens x 144 channels (waves 64 x 144): 16: NS2   17: NS3
 // 18: 128x144, two wave groups splitting K inside the workgroup, two stages each
-int dma_num_variants() { return 19; }
+// 19: 256x144 NS2 with eight waves (32 x 144 each): two 128-token halves sharing one copy of the weight tile
+int dma_num_variants() { return 20; }
 
 hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStream_t st)
 {
@@ -1097,6 +1101,7 @@ hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStre
         case 16: return launch_pipe<256, 144, 2, 4, 1>(a, debug, st);
         case 17: return launch_pipe<256, 144, 3, 4, 1>(a, debug, st);
         case 18: return launch_pipe2<128, 144, 2, 4, 1>(a, debug, st);
+        case 19: return launch_pipe<256, 144, 2, 8, 1>(a, debug, st);
     }
     return hipErrorInvalidValue;
 }

@@ -401,3 +401,117 @@ def test_oracle_matches_frozen_fixture(oracle, name):
     for key in ("Xq", "Wq", "acc"):
         assert out[key].reshape(-1).tolist() == [int(t) for t in rows[key].split()]
     assert [f"{v:04x}" for v in out["Y"].reshape(-1).tolist()] == rows["Y"].split()
+
+
+# ------------------------------------- zigzag permutation and second rotation (Eq. 9)
+
+def _read_fixture(name):
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    out = {}
+    for line in open(os.path.join(here, name)):
+        if line.startswith("#") or not line.strip():
+            continue
+        key, *vals = line.split()
+        out[key] = [float(v) for v in vals]
+    return out
+
+
+def test_zigzag_hand_worked_example(oracle):
+    fx = _read_fixture("zigzag_8ch_2blocks.txt")
+    perm = oracle.zigzag(np.array(fx["mag"]), B=4)
+    assert perm.tolist() == [int(v) for v in fx["perm"]]
+
+
+def test_zigzag_is_a_balanced_permutation(oracle):
+    rng = np.random.default_rng(5)
+    K, B = 1152, 128
+    mag = np.abs(rng.standard_normal(K))
+    hot = rng.choice(K, size=8, replace=False)
+    mag[hot] *= 50.0                                   # massive-outlier channels
+    perm = oracle.zigzag(mag, B)
+    assert sorted(perm.tolist()) == list(range(K))     # a permutation: P is orthogonal
+    blocks = mag[perm].reshape(K // B, B)
+    # every round deals one channel to every block, largest first: slot r of any block holds a
+    # channel no smaller than slot r+1 of any block
+    assert np.all(blocks[:, :-1].min(axis=0) >= blocks[:, 1:].max(axis=0))
+    # the outliers are spread: no block gets two of the 8 before every block has one (9 blocks)
+    assert np.all((blocks > 10 * np.median(mag)).sum(axis=1) <= 1)
+    # two consecutive rounds give block i the ranks i and 2nb-1-i: block sums of sorted data
+    # differ by at most the first round's spread
+    sums = blocks.sum(axis=1)
+    srt = np.sort(mag)[::-1]
+    assert sums.max() - sums.min() <= srt[0] - srt[K // B - 1] + 1e-12
+    # contiguous blocks of the same data are far less balanced
+    contiguous = mag.reshape(K // B, B).sum(axis=1)
+    assert sums.max() - sums.min() < contiguous.max() - contiguous.min()
+
+
+def test_rpr_identity_permutation_undoes_the_rotation(oracle):
+    # H_B is symmetric, so R R = I: with P = I, G_t(X) = X diag(d) exactly (up to rounding)
+    rng = np.random.default_rng(6)
+    M, K, B = 5, 256, 128
+    X = _bf16(rng.standard_normal((M, K)))
+    d = np.exp(0.3 * rng.standard_normal(K)).astype(np.float32)
+    V = oracle.rotate_rpr(X, d, np.arange(K, dtype=np.int32), B)
+    U = oracle.bf16_to_f64(X) * d.astype(np.float64)
+    assert np.allclose(V, U, rtol=0, atol=1e-12 * np.abs(U).max())
+
+
+def test_rpr_matches_dense_matrices(oracle):
+    # G_t(X) = X D R P R with R and P written out as dense K x K matrices (library products)
+    rng = np.random.default_rng(7)
+    M, K, B = 6, 256, 128
+    X = _bf16(rng.standard_normal((M, K)))
+    d = np.exp(0.3 * rng.standard_normal(K)).astype(np.float32)
+    perm = rng.permutation(K).astype(np.int32)
+    Rb = scipy.linalg.hadamard(B) / np.sqrt(B)
+    R = scipy.linalg.block_diag(*([Rb] * (K // B)))
+    P = np.zeros((K, K))
+    P[perm, np.arange(K)] = 1.0                        # (U P)[k'] = U[perm[k']]
+    U = oracle.bf16_to_f64(X) * d.astype(np.float64)
+    expect = U @ R @ P @ R
+    V = oracle.rotate_rpr(X, d, perm, B)
+    assert np.allclose(V, expect, rtol=0, atol=1e-12 * np.abs(expect).max())
+    # norm preservation: R, P orthogonal
+    assert np.allclose(np.linalg.norm(V, axis=1), np.linalg.norm(U, axis=1), rtol=1e-12)
+    W = (0.02 * rng.standard_normal((K, 24))).astype(np.float32)
+    Wp = oracle.rotate_weights_rpr(W, d, perm, B)
+    expect_w = R.T @ P.T @ R.T @ (W.astype(np.float64) / d.astype(np.float64)[:, None])
+    assert np.allclose(Wp, expect_w, rtol=0, atol=1e-12 * np.abs(expect_w).max())
+
+
+def test_rpr_computational_invariance(oracle):
+    # Eq. 9: [(X D) R P R] [R^T P^T R^T (D^-1 W)] = X W, unquantised, to 1e-9
+    rng = np.random.default_rng(8)
+    M, K, N, B = 16, 1152, 40, 128
+    Xf = rng.standard_normal((M, K)).astype(np.float32)
+    Xf[:, rng.choice(K, size=8, replace=False)] *= 50.0
+    X = _bf16(Xf)
+    d = np.exp(0.3 * rng.standard_normal(K)).astype(np.float32)
+    W = (0.02 * rng.standard_normal((K, N))).astype(np.float32)
+    V1 = oracle.rotate(X, d, B)
+    perm = oracle.zigzag(np.abs(V1).max(axis=0), B)
+    V = oracle.rotate_rpr(X, d, perm, B)
+    Wp = oracle.rotate_weights_rpr(W, d, perm, B)
+    exact = oracle.bf16_to_f64(X) @ W.astype(np.float64)
+    assert np.abs(V @ Wp - exact).max() <= 1e-9 * np.abs(exact).max()
+
+
+def test_rpr_balances_the_blocks(oracle):
+    # what the permutation is for (Sec. 3.2): one block rotation leaves each block with its own
+    # outliers' energy, so blocks differ widely; after the zigzag permutation and the second
+    # rotation every block carries about the same energy
+    rng = np.random.default_rng(9)
+    M, K, B = 64, 1152, 128
+    Xf = rng.standard_normal((M, K)).astype(np.float32)
+    Xf[:, rng.choice(K, size=8, replace=False)] *= 50.0
+    X = _bf16(Xf)
+    V1 = oracle.rotate(X, None, B)
+    perm = oracle.zigzag(np.abs(V1).max(axis=0), B)
+    V2 = oracle.rotate_rpr(X, None, perm, B)
+    e1 = (V1 ** 2).reshape(M, K // B, B).sum(axis=(0, 2))
+    e2 = (V2 ** 2).reshape(M, K // B, B).sum(axis=(0, 2))
+    assert np.isclose(e1.sum(), e2.sum(), rtol=1e-12)          # orthogonal: total energy kept
+    assert e1.max() / e1.min() > 10.0                          # 8 outlier channels in 9 blocks
+    assert e2.max() / e2.min() < 1.5
