@@ -121,7 +121,7 @@ void trdq_weights_destroy(trdq_weights *w);
  *   V = (X . diag) . R,   s_x[i] = max_k |V[i,k]| / 127,
  *   Xq[i,k] = rint(V[i,k] / s_x[i]);   an all-zero row gives s_x = 0, codes 0.
  * X_dev:  bf16 [M, K], row stride ldx elements (ldx >= K, ldx % 8 == 0, 16-byte aligned base).
- * Xq_dev: int8 [M, K] dense (8-byte aligned).   sx_dev: float32 [M].
+ * Xq_dev: int8 [M, K] dense (16-byte aligned).   sx_dev: float32 [M].
  * Errors: NULL X/Xq/sx -> ERR_NULL; M < 0, K <= 0, K % 128, ldx < K, misalignment
  * -> ERR_SHAPE; block != 128 -> ERR_UNSUPPORTED. */
 trdq_status trdq_rotate_quant(const void *X_dev, int64_t M, int K, int64_t ldx,
@@ -135,6 +135,35 @@ trdq_status trdq_rotate_quant(const void *X_dev, int64_t M, int K, int64_t ldx,
 trdq_status trdq_rotate_quant_warm(const void *X_dev, int64_t M, int K, int64_t ldx,
                                    const float *diag_dev, int block,
                                    int8_t *Xq_dev, float *sx_dev, const trdq_weights *next, void *stream);
+
+/* ------------------------------------------- full transform of Eq. 9
+ * G_t(X) = (X . Delta_t) . R^(1) . P . R^(2)  and  H_t(W) = R^(2)^T . P^T . R^(1)^T . (Delta_t^-1 . W)
+ * (Sec. 3.2: first block rotation, zigzag permutation, second block rotation).  Both rotations
+ * are the block-diagonal Hadamard rotation of the calls above; the permutation is a table
+ * perm[K] of source channels, (U P)[k'] = U[perm[k']], so P P^T = I and the product is unchanged.
+ * Weights prepared with trdq_prepare_weights_rpr go with activations from
+ * trdq_rotate_quant_rpr (same diag, same perm) through the unchanged trdq_qgemm. */
+
+/* Zigzag permutation (Sec. 3.2): channels in order of decreasing magnitude are dealt to the
+ * K / block blocks back and forth (blocks 0..nb-1, then nb-1..0, ...); round r fills slot r of
+ * every block; equal magnitudes keep their channel order.  Host arrays: chan_mag_host[K] (for
+ * example the per-channel absmax of calibration activations after the first rotation),
+ * perm_host[K] (written).  Errors: NULL -> ERR_NULL; K <= 0, block <= 0, K % block -> ERR_SHAPE. */
+trdq_status trdq_zigzag_permutation(const float *chan_mag_host, int K, int block, int32_t *perm_host);
+
+/* trdq_prepare_weights with the permutation and the second rotation.  perm_dev: int32 [K] on the
+ * device, a permutation of 0..K-1 (entries are clamped to the range, not otherwise checked).
+ * Other arguments, ownership and errors as trdq_prepare_weights; NULL perm_dev -> ERR_NULL. */
+trdq_status trdq_prepare_weights_rpr(const float *W_dev, int K, int N, const float *diag_dev,
+                                     const int32_t *perm_dev, int block, int wbits, void *stream,
+                                     trdq_weights **out);
+
+/* trdq_rotate_quant with the permutation and the second rotation: V = (X . diag) . R . P . R,
+ * then the per-token quantiser.  perm_dev as above (16-byte aligned).  K up to 4608.
+ * Arguments, outputs and errors otherwise as trdq_rotate_quant; K > 4608 -> ERR_UNSUPPORTED. */
+trdq_status trdq_rotate_quant_rpr(const void *X_dev, int64_t M, int K, int64_t ldx,
+                                  const float *diag_dev, const int32_t *perm_dev, int block,
+                                  int8_t *Xq_dev, float *sx_dev, void *stream);
 
 /* The integer product G_t(X_t) . H_t(W) on the codes, with the dequantising epilogue:
  *   wbits 8: Y[i,n] = bf16( float(acc[i,n]) * s_x[i] * s_w[n] + bias[n] ),  acc = Xq . Wq  (int32, exact)

@@ -1,5 +1,6 @@
 // Host side of libtrdq: argument validation (always before the first HIP call), the
 // time-step table, weight handles, the per-layer convenience object, and the exports.
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -115,7 +116,11 @@ void trdq_table_destroy(trdq_table *t)
 
 /* ---------------------------------------------------------------- weights */
 
-trdq_status trdq_prepare_weights(const float *W_dev, int K, int N, const float *diag_dev,
+namespace {
+
+// Shared body of the two weight-preparation entry points.  perm_dev == nullptr: H_t(W) of Eq. 10
+// with one rotation; otherwise the full H_t(W) of Eq. 9 (rotation, P^T, rotation).
+trdq_status prepare_weights_impl(const float *W_dev, int K, int N, const float *diag_dev, const int32_t *perm_dev,
                                  int block, int wbits, void *stream, trdq_weights **out)
 {
     if (!out) return TRDQ_ERR_NULL;
@@ -129,36 +134,82 @@ trdq_status trdq_prepare_weights(const float *W_dev, int K, int N, const float *
     trdq_weights *w = new (std::nothrow) trdq_weights;
     if (!w) return TRDQ_ERR_ALLOC;
     w->K = K; w->N = N; w->wbits = wbits;
-    float *Wrot = nullptr, *amax = nullptr;
+    float *Wrot = nullptr, *Wrot2 = nullptr, *amax = nullptr;
     const size_t code_bytes = wbits == 8 ? (size_t)K * N : (size_t)K * N / 2;
     const size_t scale_count = wbits == 8 ? (size_t)N : (size_t)nb * N;
     trdq_status rc = TRDQ_OK;
+    bool ok = true;
     if (hipGetDevice(&w->device) != hipSuccess) { rc = TRDQ_ERR_HIP; goto fail; }
     if (hipMalloc(&w->codes, code_bytes) != hipSuccess ||
         hipMalloc(reinterpret_cast<void **>(&w->scales), scale_count * sizeof(float)) != hipSuccess ||
         hipMalloc(reinterpret_cast<void **>(&Wrot), (size_t)K * N * sizeof(float)) != hipSuccess ||
-        hipMalloc(reinterpret_cast<void **>(&amax), (size_t)nb * N * sizeof(float)) != hipSuccess) {
+        hipMalloc(reinterpret_cast<void **>(&amax), (size_t)nb * N * sizeof(float)) != hipSuccess ||
+        (perm_dev && hipMalloc(reinterpret_cast<void **>(&Wrot2), (size_t)K * N * sizeof(float)) != hipSuccess)) {
         rc = TRDQ_ERR_ALLOC;
         goto fail;
     }
-    if (trdq::launch_prepare_rotate(W_dev, K, N, diag_dev, Wrot, amax, st) != hipSuccess ||
-        trdq::launch_prepare_quant(Wrot, amax, K, N, wbits, w->codes, w->scales, st) != hipSuccess ||
-        hipStreamSynchronize(st) != hipSuccess) {
+    ok = trdq::launch_prepare_rotate(W_dev, K, N, diag_dev, nullptr, Wrot, amax, st) == hipSuccess;
+    if (ok && perm_dev) {
+        // rows gathered through the permutation, rotated again; two unnormalised rotations: 1/128
+        ok = trdq::launch_prepare_rotate(Wrot, K, N, nullptr, perm_dev, Wrot2, amax, st) == hipSuccess &&
+             trdq::launch_prepare_quant(Wrot2, amax, K, N, wbits, 0.0078125f, w->codes, w->scales, st) == hipSuccess;
+    } else if (ok) {
+        ok = trdq::launch_prepare_quant(Wrot, amax, K, N, wbits, 0.08838834764831845f, w->codes, w->scales, st) == hipSuccess;
+    }
+    if (!ok || hipStreamSynchronize(st) != hipSuccess) {
         rc = TRDQ_ERR_HIP;
         goto fail;
     }
     (void)hipFree(Wrot);
+    if (Wrot2) (void)hipFree(Wrot2);
     (void)hipFree(amax);
     *out = w;
     return TRDQ_OK;
 fail:
     (void)hipGetLastError();
     if (Wrot) (void)hipFree(Wrot);
+    if (Wrot2) (void)hipFree(Wrot2);
     if (amax) (void)hipFree(amax);
     if (w->codes) (void)hipFree(w->codes);
     if (w->scales) (void)hipFree(w->scales);
     delete w;
     return rc;
+}
+
+}  // namespace
+
+trdq_status trdq_prepare_weights(const float *W_dev, int K, int N, const float *diag_dev,
+                                 int block, int wbits, void *stream, trdq_weights **out)
+{
+    return prepare_weights_impl(W_dev, K, N, diag_dev, nullptr, block, wbits, stream, out);
+}
+
+trdq_status trdq_prepare_weights_rpr(const float *W_dev, int K, int N, const float *diag_dev,
+                                     const int32_t *perm_dev, int block, int wbits, void *stream,
+                                     trdq_weights **out)
+{
+    if (out) *out = nullptr;
+    if (!perm_dev) return TRDQ_ERR_NULL;
+    return prepare_weights_impl(W_dev, K, N, diag_dev, perm_dev, block, wbits, stream, out);
+}
+
+trdq_status trdq_zigzag_permutation(const float *chan_mag_host, int K, int block, int32_t *perm_host)
+{
+    if (!chan_mag_host || !perm_host) return TRDQ_ERR_NULL;
+    if (block <= 0 || K <= 0 || K % block != 0) return TRDQ_ERR_SHAPE;
+    // channels by decreasing magnitude (equal magnitudes keep their order), dealt to the blocks
+    // back and forth: round r fills slot r of every block, left to right on even rounds
+    std::vector<int32_t> order((size_t)K);
+    for (int k = 0; k < K; ++k) order[(size_t)k] = k;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return chan_mag_host[a] > chan_mag_host[b]; });
+    const int nb = K / block;
+    for (int t = 0; t < K; ++t) {
+        const int round = t / nb, pos = t % nb;
+        const int b = (round & 1) ? nb - 1 - pos : pos;
+        perm_host[b * block + round] = order[(size_t)t];
+    }
+    return TRDQ_OK;
 }
 
 trdq_status trdq_weights_info(const trdq_weights *w, int *K_out, int *N_out, int *wbits_out)
@@ -255,7 +306,7 @@ trdq_status trdq_rotate_quant_warm(const void *X_dev, int64_t M, int K, int64_t 
     trdq_status rc = check_rotate_args(X_dev, M, K, ldx, block);
     if (rc != TRDQ_OK) return rc;
     if (M > 0 && (!Xq_dev || !sx_dev)) return TRDQ_ERR_NULL;
-    if (!aligned(Xq_dev, 8) || !aligned(sx_dev, 4) || (diag_dev && !aligned(diag_dev, 16))) return TRDQ_ERR_SHAPE;
+    if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || (diag_dev && !aligned(diag_dev, 16))) return TRDQ_ERR_SHAPE;
     if (K / trdq::kBlock > 64) return TRDQ_ERR_UNSUPPORTED;
     if (M == 0) return TRDQ_OK;
     const void *warm = nullptr;
@@ -267,6 +318,22 @@ trdq_status trdq_rotate_quant_warm(const void *X_dev, int64_t M, int K, int64_t 
     }
     return hip_status(trdq::launch_rotate_quant(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev,
                                                 Xq_dev, sx_dev, warm, warm_bytes, static_cast<hipStream_t>(stream)));
+}
+
+trdq_status trdq_rotate_quant_rpr(const void *X_dev, int64_t M, int K, int64_t ldx,
+                                  const float *diag_dev, const int32_t *perm_dev, int block,
+                                  int8_t *Xq_dev, float *sx_dev, void *stream)
+{
+    trdq_status rc = check_rotate_args(X_dev, M, K, ldx, block);
+    if (rc != TRDQ_OK) return rc;
+    if (!perm_dev) return TRDQ_ERR_NULL;
+    if (M > 0 && (!Xq_dev || !sx_dev)) return TRDQ_ERR_NULL;
+    if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || !aligned(perm_dev, 16) || (diag_dev && !aligned(diag_dev, 16)))
+        return TRDQ_ERR_SHAPE;
+    if (!trdq::rotate_quant_rpr_supports(K)) return TRDQ_ERR_UNSUPPORTED;
+    if (M == 0) return TRDQ_OK;
+    return hip_status(trdq::launch_rotate_quant_rpr(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev,
+                                                    perm_dev, Xq_dev, sx_dev, static_cast<hipStream_t>(stream)));
 }
 
 trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev, int64_t M,

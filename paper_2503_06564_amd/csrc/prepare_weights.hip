@@ -12,11 +12,13 @@ constexpr int kCols = 64;          // output channels per workgroup
 constexpr int kPrepThreads = 256;
 
 // Kernel 1: one workgroup rotates one 128-row block of 64 columns.
-//   Wrot[b*128 + j, n] = sum_k H[k][j] * W[b*128 + k, n] / d[b*128 + k]      (unnormalised H)
+//   Wrot[b*128 + j, n] = sum_k H[k][j] * W[row(b*128 + k), n] / d[b*128 + k]      (unnormalised H)
 //   amax[b, n]         = max_j |Wrot[b*128 + j, n]|
+// row(k) = k, or perm[k] (clamped to the matrix) when a permutation is given: the P^T factor of
+// Eq. 9 in front of the second rotation.
 __global__ __launch_bounds__(kPrepThreads) void prepare_rotate_kernel(
     const float *__restrict__ W, int K, int N, const float *__restrict__ diag,
-    float *__restrict__ Wrot, float *__restrict__ amax)
+    const int32_t *__restrict__ perm, float *__restrict__ Wrot, float *__restrict__ amax)
 {
     __shared__ float tile[kBlock][kCols + 1];
     __shared__ float part[4][kCols];
@@ -30,7 +32,12 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_rotate_kernel(
     for (int k = q; k < kBlock; k += 4) {
         float w = 0.0f;
         if (col_ok) {
-            w = W[(size_t)(b * kBlock + k) * N + n];
+            int row = b * kBlock + k;
+            if (perm) {
+                row = perm[row];
+                row = row < 0 ? 0 : (row >= K ? K - 1 : row);
+            }
+            w = W[(size_t)row * N + n];
             if (diag) w = w / diag[b * kBlock + k];
         }
         tile[k][c] = w;
@@ -60,12 +67,13 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_rotate_kernel(
 
 // Kernel 2: quantise and transpose one 128-row block of 64 columns into the K-contiguous
 // layouts the product kernels read (see Weights in trdq_internal.h).
-//   wbits 8: scale[n]    = max_b amax[b, n] / (sqrt(128) * 127)
-//   wbits 4: scale[b, n] = amax[b, n]       / (sqrt(128) * 7)
+//   wbits 8: scale[n]    = max_b amax[b, n] * norm / 127
+//   wbits 4: scale[b, n] = amax[b, n]       * norm / 7
+// norm undoes the unnormalised butterflies: 1/sqrt(128) after one rotation, 1/128 after two.
 //   code = rint(Wrot * qmax / amax)   (ties to even; amax == 0 -> 0)
 template <int WBITS>
 __global__ __launch_bounds__(kPrepThreads) void prepare_quant_kernel(
-    const float *__restrict__ Wrot, const float *__restrict__ amax, int K, int N,
+    const float *__restrict__ Wrot, const float *__restrict__ amax, int K, int N, float norm,
     void *__restrict__ codes, float *__restrict__ scales)
 {
     __shared__ int8_t q8[kCols][kBlock + 16];
@@ -74,7 +82,6 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_quant_kernel(
     const int b = blockIdx.y;
     const int n0 = blockIdx.x * kCols;
     constexpr float qmax = WBITS == 8 ? 127.0f : 7.0f;
-    constexpr float rsqrtB = 0.08838834764831845f;
 
     if (threadIdx.x < kCols) {
         const int n = n0 + threadIdx.x;
@@ -82,10 +89,10 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_quant_kernel(
         if (n < N) {
             if (WBITS == 8) {
                 for (int bb = 0; bb < nb; ++bb) a = fmaxf(a, amax[(size_t)bb * N + n]);
-                if (b == 0) scales[n] = a * (rsqrtB / qmax);
+                if (b == 0) scales[n] = a * (norm / qmax);
             } else {
                 a = amax[(size_t)b * N + n];
-                scales[(size_t)b * N + n] = a * (rsqrtB / qmax);
+                scales[(size_t)b * N + n] = a * (norm / qmax);
             }
         }
         inv_s[threadIdx.x] = a > 0.0f ? qmax / a : 0.0f;
@@ -128,22 +135,22 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_quant_kernel(
 
 }  // namespace
 
-hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag, float *Wrot,
-                                 float *amax, hipStream_t st)
+hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag, const int32_t *perm,
+                                 float *Wrot, float *amax, hipStream_t st)
 {
     dim3 grid((N + kCols - 1) / kCols, K / kBlock);
-    hipLaunchKernelGGL(prepare_rotate_kernel, grid, dim3(kPrepThreads), 0, st, W, K, N, diag, Wrot, amax);
+    hipLaunchKernelGGL(prepare_rotate_kernel, grid, dim3(kPrepThreads), 0, st, W, K, N, diag, perm, Wrot, amax);
     return hipGetLastError();
 }
 
-hipError_t launch_prepare_quant(const float *Wrot, const float *amax, int K, int N, int wbits,
+hipError_t launch_prepare_quant(const float *Wrot, const float *amax, int K, int N, int wbits, float norm,
                                 void *codes, float *scales, hipStream_t st)
 {
     dim3 grid((N + kCols - 1) / kCols, K / kBlock);
     if (wbits == 8)
-        hipLaunchKernelGGL(prepare_quant_kernel<8>, grid, dim3(kPrepThreads), 0, st, Wrot, amax, K, N, codes, scales);
+        hipLaunchKernelGGL(prepare_quant_kernel<8>, grid, dim3(kPrepThreads), 0, st, Wrot, amax, K, N, norm, codes, scales);
     else
-        hipLaunchKernelGGL(prepare_quant_kernel<4>, grid, dim3(kPrepThreads), 0, st, Wrot, amax, K, N, codes, scales);
+        hipLaunchKernelGGL(prepare_quant_kernel<4>, grid, dim3(kPrepThreads), 0, st, Wrot, amax, K, N, norm, codes, scales);
     return hipGetLastError();
 }
 

@@ -36,9 +36,16 @@ hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx,
 hipError_t launch_rotate_quant_wide(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
                                     int8_t *Xq, float *sx, hipStream_t st);
 
-hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag, float *Wrot,
-                                 float *amax, hipStream_t st);
-hipError_t launch_prepare_quant(const float *Wrot, const float *amax, int K, int N, int wbits,
+// Full transform of Eq. 9 (rotation, permutation, rotation) and per-token quantisation.
+bool rotate_quant_rpr_supports(int K);
+hipError_t launch_rotate_quant_rpr(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
+                                   const int32_t *perm, int8_t *Xq, float *sx, hipStream_t st);
+
+// perm (optional): rows are read through it (row k of the input to the rotation = row perm[k]).
+// norm: what undoes the unnormalised butterflies (1/sqrt(128) per rotation applied).
+hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag, const int32_t *perm,
+                                 float *Wrot, float *amax, hipStream_t st);
+hipError_t launch_prepare_quant(const float *Wrot, const float *amax, int K, int N, int wbits, float norm,
                                 void *codes, float *scales, hipStream_t st);
 
 int qgemm_num_variants();

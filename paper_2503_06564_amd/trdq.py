@@ -21,6 +21,7 @@ SYMBOLS = [
     "trdq_rotate_quant", "trdq_rotate_quant_warm", "trdq_qgemm", "trdq_linear_fused",
     "trdq_layer_create", "trdq_layer_set_group", "trdq_layer_forward", "trdq_layer_weights",
     "trdq_layer_destroy", "trdq_qgemm_set_variant", "trdq_qgemm_num_variants",
+    "trdq_zigzag_permutation", "trdq_prepare_weights_rpr", "trdq_rotate_quant_rpr",
 ]
 
 _lib = None
@@ -68,6 +69,9 @@ def lib():
         L.trdq_layer_destroy.argtypes = [p]
         L.trdq_layer_destroy.restype = None
         L.trdq_qgemm_set_variant.argtypes = [i32]
+        L.trdq_zigzag_permutation.argtypes = [p, i32, i32, p]
+        L.trdq_prepare_weights_rpr.argtypes = [p, i32, i32, p, p, i32, i32, p, C.POINTER(p)]
+        L.trdq_rotate_quant_rpr.argtypes = [p, i64, i32, i64, p, p, i32, p, p, p]
         L.trdq_qgemm_num_variants.restype = i32
         _lib = L
     return _lib
@@ -188,7 +192,33 @@ def prepare_weights(W, diag=None, block=BLOCK, wbits=8, stream=None):
     return Weights(h)
 
 
+def zigzag_permutation(chan_mag, block=BLOCK):
+    """chan_mag: host float32 array [K] of per-channel magnitudes -> host int32 array perm[K]."""
+    import numpy as np
+    mag = np.ascontiguousarray(chan_mag, dtype=np.float32)
+    perm = np.empty(mag.shape[0], dtype=np.int32)
+    _check(lib().trdq_zigzag_permutation(_ptr(mag), mag.shape[0], block, _ptr(perm)), "trdq_zigzag_permutation")
+    return perm
+
+
+def prepare_weights_rpr(W, diag, perm, block=BLOCK, wbits=8, stream=None):
+    """Full H_t(W) of Eq. 9; perm: int32 device tensor [K]."""
+    K, N = W.shape
+    h = C.c_void_p()
+    _check(lib().trdq_prepare_weights_rpr(_ptr(W), K, N, _ptr(diag), _ptr(perm), block, wbits, _stream(stream),
+                                          C.byref(h)), "trdq_prepare_weights_rpr")
+    return Weights(h)
+
+
 # ----------------------------------------------------------------- online
+
+def rotate_quant_rpr(X, diag, perm, Xq, sx, block=BLOCK, stream=None):
+    """Full G_t(X) of Eq. 9 and the per-token quantiser; perm: int32 device tensor [K]."""
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    _check(lib().trdq_rotate_quant_rpr(_ptr(X), M, K, ldx, _ptr(diag), _ptr(perm), block, _ptr(Xq), _ptr(sx),
+                                       _stream(stream)), "trdq_rotate_quant_rpr")
+
 
 def rotate_quant(X, diag, Xq, sx, block=BLOCK, stream=None, warm=None):
     """X: bf16 [M, K] (row stride X.stride(0)); Xq: int8 [M, K]; sx: float32 [M].

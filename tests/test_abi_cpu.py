@@ -133,3 +133,42 @@ def test_layer_argument_errors():
     assert L.trdq_layer_weights(layer.handle, 7, C.byref(w)) == trdq.ERR_RANGE
     layer.close()
     L.trdq_layer_destroy(None)
+
+
+# ---- zigzag permutation (host-side entry point: checked here against the oracle) ----------
+
+@pytest.mark.parametrize("K", [128, 1152, 4608])
+def test_zigzag_matches_oracle(oracle, K):
+    rng = np.random.default_rng(K)
+    mag = np.abs(rng.standard_normal(K)).astype(np.float32)
+    mag[rng.choice(K, size=max(1, K // 144), replace=False)] *= 40.0
+    mag[5 % K] = mag[17 % K]                                     # a tie: channel order decides
+    got = trdq.zigzag_permutation(mag)
+    want = oracle.zigzag(mag.astype(np.float64), 128)
+    assert np.array_equal(got, want)
+
+
+def test_zigzag_argument_errors():
+    L = trdq.lib()
+    mag = np.ones(256, dtype=np.float32)
+    perm = np.empty(256, dtype=np.int32)
+    assert L.trdq_zigzag_permutation(None, 256, 128, perm.ctypes.data) == trdq.ERR_NULL
+    assert L.trdq_zigzag_permutation(mag.ctypes.data, 256, 128, None) == trdq.ERR_NULL
+    assert L.trdq_zigzag_permutation(mag.ctypes.data, 200, 128, perm.ctypes.data) == trdq.ERR_SHAPE
+    assert L.trdq_zigzag_permutation(mag.ctypes.data, 0, 128, perm.ctypes.data) == trdq.ERR_SHAPE
+    assert L.trdq_zigzag_permutation(mag.ctypes.data, 256, 0, perm.ctypes.data) == trdq.ERR_SHAPE
+
+
+def test_rpr_argument_errors_before_any_gpu_call():
+    L = trdq.lib()
+    out = C.c_void_p()
+    # NULL permutation, then the same checks as the one-rotation entry points
+    assert L.trdq_prepare_weights_rpr(0x1000, 256, 64, None, None, 128, 8, None, C.byref(out)) == trdq.ERR_NULL
+    assert L.trdq_prepare_weights_rpr(0x1000, 200, 64, None, 0x2000, 128, 8, None, C.byref(out)) == trdq.ERR_SHAPE
+    assert L.trdq_prepare_weights_rpr(0x1000, 256, 64, None, 0x2000, 128, 6, None, C.byref(out)) == trdq.ERR_UNSUPPORTED
+    assert L.trdq_rotate_quant_rpr(0x1000, 4, 256, 256, None, None, 128, 0x2000, 0x3000, None) == trdq.ERR_NULL
+    assert L.trdq_rotate_quant_rpr(0x1000, 4, 256, 256, None, 0x4000, 64, 0x2000, 0x3000, None) == trdq.ERR_UNSUPPORTED
+    assert L.trdq_rotate_quant_rpr(0x1000, 4, 200, 256, None, 0x4000, 128, 0x2000, 0x3000, None) == trdq.ERR_SHAPE
+    assert L.trdq_rotate_quant_rpr(0x1000, 4, 256, 256, None, 0x4004, 128, 0x2000, 0x3000, None) == trdq.ERR_SHAPE
+    assert L.trdq_rotate_quant_rpr(0x1000, 4, 128 * 37, 128 * 37, None, 0x4000, 128, 0x2000, 0x3000, None) == trdq.ERR_UNSUPPORTED
+    assert L.trdq_rotate_quant_rpr(0x1000, 0, 256, 256, None, 0x4000, 128, None, None, None) == trdq.OK
