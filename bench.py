@@ -40,6 +40,8 @@ def parse():
                     help="replay one captured HIP graph per step instead of launching every kernel from the host "
                          "(same kernels; measured to make no difference here: the step is GPU-bound, and the "
                          "profiler's kernel trace does not list kernels launched from a graph)")
+    ap.add_argument("--rpr", action="store_true",
+                    help="the full transform of Eq. 9 (rotation, zigzag permutation, rotation) instead of one rotation")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU work budget of the oracle's timed sample")
     ap.add_argument("--variant", type=int, default=-1, help="qgemm tile variant override")
@@ -159,7 +161,7 @@ def main():
     torch.cuda.set_stream(stream)
 
     # ---- resident state: per kind and group, activations, diagonal, prepared weights ----------
-    X, D, Wh, B, Y, Xq, SX = {}, {}, {}, {}, {}, {}, {}
+    X, D, Wh, B, Y, Xq, SX, P = {}, {}, {}, {}, {}, {}, {}, {}
     for kind in cfg.kinds:
         K, N = wl.LAYER_SHAPES[kind]
         Wd = torch.from_numpy(wl.make_w(cfg, kind)).to(dev)
@@ -172,7 +174,13 @@ def main():
             xb = wl.make_x(cfg, kind, step_of_g)
             X[kind, g] = torch.from_numpy(xb.view(np.int16)).to(dev).view(torch.bfloat16)
             D[kind, g] = torch.from_numpy(wl.make_diag(cfg, kind, g)).to(dev)
-            Wh[kind, g] = trdq.prepare_weights(Wd, D[kind, g], wbits=wbits)
+            if args.rpr:
+                # zigzag permutation from the per-channel absmax of this group's scaled activations
+                mag = (X[kind, g].float().abs().amax(dim=0) * D[kind, g]).cpu().numpy()
+                P[kind, g] = torch.from_numpy(trdq.zigzag_permutation(mag)).to(dev)
+                Wh[kind, g] = trdq.prepare_weights_rpr(Wd, D[kind, g], P[kind, g], wbits=wbits)
+            else:
+                Wh[kind, g] = trdq.prepare_weights(Wd, D[kind, g], wbits=wbits)
         del Wd
     torch.cuda.synchronize()
 
@@ -189,6 +197,12 @@ def main():
             if args.fused:
                 calls[g, kind] = (trdq.bind_linear_fused(X[kind, g], D[kind, g], Wh[kind, g], Y[kind],
                                                          bias=B[kind], stream=stream),)
+            elif args.rpr:
+                calls[g, kind] = (trdq.bind_rotate_quant_rpr(X[kind, g], D[kind, g], P[kind, g], Xq[kind], SX[kind],
+                                                             stream=stream,
+                                                             warm=None if args.no_warm else Wh[kind, g]),
+                                  trdq.bind_qgemm(Wh[kind, g], Xq[kind], SX[kind], Y[kind], bias=B[kind],
+                                                  stream=stream))
             else:
                 calls[g, kind] = (trdq.bind_rotate_quant(X[kind, g], D[kind, g], Xq[kind], SX[kind], stream=stream,
                                                          warm=None if args.no_warm else Wh[kind, g]),
@@ -274,7 +288,7 @@ def main():
         "dtype": "int8" if wbits == 8 else "int8xint4", "data": "synthetic",
         "tokens_per_s": M * args.steps / dt,
         "config": {"workload": cfg.name, "tokens": M, "layers": list(cfg.kinds), "groups": n_groups,
-                   "path": "fused" if args.fused else "rotate_quant+qgemm", "wbits": wbits,
+                   "path": "fused" if args.fused else ("rotate_quant_rpr+qgemm" if args.rpr else "rotate_quant+qgemm"), "wbits": wbits,
                    "launch": "hip graph per step" if graphs else "host launches"},
     }
 

@@ -160,10 +160,11 @@ trdq_status trdq_prepare_weights_rpr(const float *W_dev, int K, int N, const flo
 
 /* trdq_rotate_quant with the permutation and the second rotation: V = (X . diag) . R . P . R,
  * then the per-token quantiser.  perm_dev as above (16-byte aligned).  K up to 4608.
+ * next: as in trdq_rotate_quant_warm (the weights of the product that follows, or NULL).
  * Arguments, outputs and errors otherwise as trdq_rotate_quant; K > 4608 -> ERR_UNSUPPORTED. */
 trdq_status trdq_rotate_quant_rpr(const void *X_dev, int64_t M, int K, int64_t ldx,
                                   const float *diag_dev, const int32_t *perm_dev, int block,
-                                  int8_t *Xq_dev, float *sx_dev, void *stream);
+                                  int8_t *Xq_dev, float *sx_dev, const trdq_weights *next, void *stream);
 
 /* The integer product G_t(X_t) . H_t(W) on the codes, with the dequantising epilogue:
  *   wbits 8: Y[i,n] = bf16( float(acc[i,n]) * s_x[i] * s_w[n] + bias[n] ),  acc = Xq . Wq  (int32, exact)

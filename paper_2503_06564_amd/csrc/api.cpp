@@ -322,7 +322,7 @@ trdq_status trdq_rotate_quant_warm(const void *X_dev, int64_t M, int K, int64_t 
 
 trdq_status trdq_rotate_quant_rpr(const void *X_dev, int64_t M, int K, int64_t ldx,
                                   const float *diag_dev, const int32_t *perm_dev, int block,
-                                  int8_t *Xq_dev, float *sx_dev, void *stream)
+                                  int8_t *Xq_dev, float *sx_dev, const trdq_weights *next, void *stream)
 {
     trdq_status rc = check_rotate_args(X_dev, M, K, ldx, block);
     if (rc != TRDQ_OK) return rc;
@@ -332,8 +332,16 @@ trdq_status trdq_rotate_quant_rpr(const void *X_dev, int64_t M, int K, int64_t l
         return TRDQ_ERR_SHAPE;
     if (!trdq::rotate_quant_rpr_supports(K)) return TRDQ_ERR_UNSUPPORTED;
     if (M == 0) return TRDQ_OK;
+    const void *warm = nullptr;
+    int64_t warm_bytes = 0;
+    if (next && next->codes) {
+        warm = next->codes;
+        warm_bytes = (int64_t)next->N * next->K / (next->wbits == 4 ? 2 : 1);
+        warm_bytes -= warm_bytes % 16;
+    }
     return hip_status(trdq::launch_rotate_quant_rpr(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev,
-                                                    perm_dev, Xq_dev, sx_dev, static_cast<hipStream_t>(stream)));
+                                                    perm_dev, Xq_dev, sx_dev, warm, warm_bytes,
+                                                    static_cast<hipStream_t>(stream)));
 }
 
 trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev, int64_t M,

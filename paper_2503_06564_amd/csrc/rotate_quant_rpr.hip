@@ -44,7 +44,8 @@ template <int TOK, int SPW>
 __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
     const uint16_t *__restrict__ X, int64_t M, int nb, int64_t ldx,
     const float *__restrict__ diag, const int32_t *__restrict__ perm,
-    int8_t *__restrict__ Xq, float *__restrict__ sx)
+    int8_t *__restrict__ Xq, float *__restrict__ sx,
+    const uint4 *__restrict__ warm, int64_t warm_chunks)
 {
     static_assert(TOK == 16 || TOK == 8, "16 or 8 tokens per workgroup");
     extern __shared__ __align__(16) float lds[];
@@ -52,7 +53,7 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
     const int nw = blockDim.x >> 6;
     const int rowf = K + kRowPad;                    // floats per LDS row
     float *const T = lds;                            // [TOK][rowf]: first-rotation output
-    float *const amax_s = lds + (size_t)TOK * rowf;  // [nw][16]
+    float *const amax_s = lds + (size_t)TOK * rowf;  // [nw][16]; after it a 1 KB dump area for the weight copies
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -106,6 +107,22 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
                     *reinterpret_cast<float4 *>(dst + q * 8) = make_float4(acc[0][q], acc[1][q], acc[2][q], acc[3][q]);
                     *reinterpret_cast<float4 *>(dst + q * 8 + 4) = make_float4(acc[4][q], acc[5][q], acc[6][q], acc[7][q]);
                 }
+            }
+        }
+    }
+    // Optional: pull the following product's weight codes through the memory-side cache (see
+    // rotate_quant): up to four direct-to-LDS copies per wave into a dump area nobody reads.
+    if (warm_chunks > 0) {
+        const uint32_t dump = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float *)lds +
+                              (uint32_t)(sizeof(float) * ((size_t)TOK * rowf + (size_t)nw * 16));
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int64_t c0 = ((int64_t)t * gridDim.x + blockIdx.x) * blockDim.x + (wave << 6);   // wave-uniform
+            if (c0 < warm_chunks) {
+                int64_t c = c0 + lane;
+                if (c >= warm_chunks) c = warm_chunks - 1;
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                             :: "v"((uint32_t)(c << 4)), "s"(warm), "s"(dump) : "memory", "m0");
             }
         }
     }
@@ -182,14 +199,16 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
             *reinterpret_cast<uint4 *>(dst + 64) = make_uint4(c[4], c[5], c[6], c[7]);
         }
     }
+    // the copies to the dump area must have landed before the workgroup's LDS is given away
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 template <int TOK, int SPW>
 hipError_t launch_rpr(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx, const float *diag,
-                      const int32_t *perm, int8_t *Xq, float *sx, hipStream_t st)
+                      const int32_t *perm, int8_t *Xq, float *sx, const void *warm, int64_t warm_bytes, hipStream_t st)
 {
     const int K = nb * kBlock;
-    const size_t smem = sizeof(float) * ((size_t)TOK * (K + kRowPad) + (size_t)nw * 16);
+    const size_t smem = sizeof(float) * ((size_t)TOK * (K + kRowPad) + (size_t)nw * 16) + 1024;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(rotate_quant_rpr_kernel<TOK, SPW>),
@@ -199,7 +218,8 @@ hipError_t launch_rpr(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx,
     }
     const int64_t groups = (M + TOK - 1) / TOK;
     hipLaunchKernelGGL((rotate_quant_rpr_kernel<TOK, SPW>), dim3((unsigned)groups), dim3(64 * nw), smem, st,
-                       X, M, nb, ldx, diag, perm, Xq, sx);
+                       X, M, nb, ldx, diag, perm, Xq, sx, static_cast<const uint4 *>(warm),
+                       (warm && warm_bytes < ((int64_t)1 << 32)) ? warm_bytes / 16 : 0);
     return hipGetLastError();
 }
 
@@ -209,25 +229,26 @@ hipError_t launch_rpr(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx,
 bool rotate_quant_rpr_supports(int K) { return K > 0 && K % kBlock == 0 && K / kBlock <= 36; }
 
 hipError_t launch_rotate_quant_rpr(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
-                                   const int32_t *perm, int8_t *Xq, float *sx, hipStream_t st)
+                                   const int32_t *perm, int8_t *Xq, float *sx, const void *warm, int64_t warm_bytes,
+                                   hipStream_t st)
 {
     if (M == 0) return hipSuccess;
     if (!rotate_quant_rpr_supports(K)) return hipErrorInvalidValue;
     const int nb = K / kBlock;
     const int spw = nb <= 12 ? 1 : (nb <= 24 ? 2 : 3);
     const int nw = (nb + spw - 1) / spw;
-    const bool tok16 = (size_t)16 * (K + kRowPad) * 4 + (size_t)nw * 64 <= 150 * 1024;
+    const bool tok16 = (size_t)16 * (K + kRowPad) * 4 + (size_t)nw * 64 + 1024 <= 150 * 1024;
     if (tok16) {
         switch (spw) {
-            case 1: return launch_rpr<16, 1>(X, M, nb, nw, ldx, diag, perm, Xq, sx, st);
-            case 2: return launch_rpr<16, 2>(X, M, nb, nw, ldx, diag, perm, Xq, sx, st);
-            default: return launch_rpr<16, 3>(X, M, nb, nw, ldx, diag, perm, Xq, sx, st);
+            case 1: return launch_rpr<16, 1>(X, M, nb, nw, ldx, diag, perm, Xq, sx, warm, warm_bytes, st);
+            case 2: return launch_rpr<16, 2>(X, M, nb, nw, ldx, diag, perm, Xq, sx, warm, warm_bytes, st);
+            default: return launch_rpr<16, 3>(X, M, nb, nw, ldx, diag, perm, Xq, sx, warm, warm_bytes, st);
         }
     }
     switch (spw) {
-        case 1: return launch_rpr<8, 1>(X, M, nb, nw, ldx, diag, perm, Xq, sx, st);
-        case 2: return launch_rpr<8, 2>(X, M, nb, nw, ldx, diag, perm, Xq, sx, st);
-        default: return launch_rpr<8, 3>(X, M, nb, nw, ldx, diag, perm, Xq, sx, st);
+        case 1: return launch_rpr<8, 1>(X, M, nb, nw, ldx, diag, perm, Xq, sx, warm, warm_bytes, st);
+        case 2: return launch_rpr<8, 2>(X, M, nb, nw, ldx, diag, perm, Xq, sx, warm, warm_bytes, st);
+        default: return launch_rpr<8, 3>(X, M, nb, nw, ldx, diag, perm, Xq, sx, warm, warm_bytes, st);
     }
 }
 

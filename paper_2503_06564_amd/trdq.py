@@ -71,7 +71,7 @@ def lib():
         L.trdq_qgemm_set_variant.argtypes = [i32]
         L.trdq_zigzag_permutation.argtypes = [p, i32, i32, p]
         L.trdq_prepare_weights_rpr.argtypes = [p, i32, i32, p, p, i32, i32, p, C.POINTER(p)]
-        L.trdq_rotate_quant_rpr.argtypes = [p, i64, i32, i64, p, p, i32, p, p, p]
+        L.trdq_rotate_quant_rpr.argtypes = [p, i64, i32, i64, p, p, i32, p, p, p, p]
         L.trdq_qgemm_num_variants.restype = i32
         _lib = L
     return _lib
@@ -212,12 +212,13 @@ def prepare_weights_rpr(W, diag, perm, block=BLOCK, wbits=8, stream=None):
 
 # ----------------------------------------------------------------- online
 
-def rotate_quant_rpr(X, diag, perm, Xq, sx, block=BLOCK, stream=None):
+def rotate_quant_rpr(X, diag, perm, Xq, sx, block=BLOCK, stream=None, warm=None):
     """Full G_t(X) of Eq. 9 and the per-token quantiser; perm: int32 device tensor [K]."""
     M, K = X.shape
     ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
     _check(lib().trdq_rotate_quant_rpr(_ptr(X), M, K, ldx, _ptr(diag), _ptr(perm), block, _ptr(Xq), _ptr(sx),
-                                       _stream(stream)), "trdq_rotate_quant_rpr")
+                                       warm.handle if warm is not None else None, _stream(stream)),
+           "trdq_rotate_quant_rpr")
 
 
 def rotate_quant(X, diag, Xq, sx, block=BLOCK, stream=None, warm=None):
@@ -264,6 +265,21 @@ def bind_rotate_quant(X, diag, Xq, sx, block=BLOCK, stream=None, warm=None):
         st = f(*args)
         if st != OK:
             raise TrdqError(st, "trdq_rotate_quant_warm")
+    return call
+
+
+def bind_rotate_quant_rpr(X, diag, perm, Xq, sx, block=BLOCK, stream=None, warm=None):
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    f = lib().trdq_rotate_quant_rpr
+    args = (C.c_void_p(_ptr(X)), C.c_int64(M), C.c_int(K), C.c_int64(ldx), C.c_void_p(_ptr(diag)),
+            C.c_void_p(_ptr(perm)), C.c_int(block), C.c_void_p(_ptr(Xq)), C.c_void_p(_ptr(sx)),
+            warm.handle if warm is not None else C.c_void_p(None), C.c_void_p(_stream(stream)))
+
+    def call():
+        st = f(*args)
+        if st != OK:
+            raise TrdqError(st, "trdq_rotate_quant_rpr")
     return call
 
 

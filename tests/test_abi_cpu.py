@@ -166,9 +166,9 @@ def test_rpr_argument_errors_before_any_gpu_call():
     assert L.trdq_prepare_weights_rpr(0x1000, 256, 64, None, None, 128, 8, None, C.byref(out)) == trdq.ERR_NULL
     assert L.trdq_prepare_weights_rpr(0x1000, 200, 64, None, 0x2000, 128, 8, None, C.byref(out)) == trdq.ERR_SHAPE
     assert L.trdq_prepare_weights_rpr(0x1000, 256, 64, None, 0x2000, 128, 6, None, C.byref(out)) == trdq.ERR_UNSUPPORTED
-    assert L.trdq_rotate_quant_rpr(0x1000, 4, 256, 256, None, None, 128, 0x2000, 0x3000, None) == trdq.ERR_NULL
-    assert L.trdq_rotate_quant_rpr(0x1000, 4, 256, 256, None, 0x4000, 64, 0x2000, 0x3000, None) == trdq.ERR_UNSUPPORTED
-    assert L.trdq_rotate_quant_rpr(0x1000, 4, 200, 256, None, 0x4000, 128, 0x2000, 0x3000, None) == trdq.ERR_SHAPE
-    assert L.trdq_rotate_quant_rpr(0x1000, 4, 256, 256, None, 0x4004, 128, 0x2000, 0x3000, None) == trdq.ERR_SHAPE
-    assert L.trdq_rotate_quant_rpr(0x1000, 4, 128 * 37, 128 * 37, None, 0x4000, 128, 0x2000, 0x3000, None) == trdq.ERR_UNSUPPORTED
-    assert L.trdq_rotate_quant_rpr(0x1000, 0, 256, 256, None, 0x4000, 128, None, None, None) == trdq.OK
+    assert L.trdq_rotate_quant_rpr(0x1000, 4, 256, 256, None, None, 128, 0x2000, 0x3000, None, None) == trdq.ERR_NULL
+    assert L.trdq_rotate_quant_rpr(0x1000, 4, 256, 256, None, 0x4000, 64, 0x2000, 0x3000, None, None) == trdq.ERR_UNSUPPORTED
+    assert L.trdq_rotate_quant_rpr(0x1000, 4, 200, 256, None, 0x4000, 128, 0x2000, 0x3000, None, None) == trdq.ERR_SHAPE
+    assert L.trdq_rotate_quant_rpr(0x1000, 4, 256, 256, None, 0x4004, 128, 0x2000, 0x3000, None, None) == trdq.ERR_SHAPE
+    assert L.trdq_rotate_quant_rpr(0x1000, 4, 128 * 37, 128 * 37, None, 0x4000, 128, 0x2000, 0x3000, None, None) == trdq.ERR_UNSUPPORTED
+    assert L.trdq_rotate_quant_rpr(0x1000, 0, 256, 256, None, 0x4000, 128, None, None, None, None) == trdq.OK
