@@ -147,3 +147,48 @@ def test_config3_step_table_maps_20_steps_to_5_groups():
 def test_config4_denoiser_sweep_layers(oracle, block, step, kind):
     say(f"config 4: M=8192 block {block} {kind} step {step}")
     check_layer(oracle, wl.CONFIGS[4], kind, step, 8, block=block, fused_too=False)
+
+
+# ---- the full transform of Eq. 9 (rotation, zigzag permutation, rotation) at workload sizes ----
+
+@pytest.mark.parametrize("cfg_id,kind,step", [(1, "fc1", 0), (1, "fc2", 7), (3, "proj", 19), (3, "fc2", 0)])
+def test_rpr_full_size_sampled_rows(oracle, cfg_id, kind, step):
+    cfg = wl.CONFIGS[cfg_id]
+    say(f"config {cfg_id}: R P R {kind} step {step}, M={cfg.M}")
+    K, N = wl.LAYER_SHAPES[kind]
+    g = wl.step_to_group(cfg, step)
+    Xb = wl.make_x(cfg, kind, step)
+    M = Xb.shape[0]
+    W, d, bias = wl.make_w(cfg, kind), wl.make_diag(cfg, kind, g), wl.make_bias(cfg, kind)
+    rows = sample_rows(M, 77 * cfg_id + step)
+    # permutation from the once-rotated sample (a calibration set, as the paper builds P from activations)
+    mag = np.abs(oracle.rotate(Xb[rows], d, 128)).max(axis=0).astype(np.float32)
+    perm = trdq.zigzag_permutation(mag)
+    assert np.array_equal(perm, oracle.zigzag(mag.astype(np.float64), 128))
+    perm_d = torch.from_numpy(perm).cuda()
+    Wd, dd, bd = gu.f32_to_dev(W), gu.f32_to_dev(d), gu.f32_to_dev(bias)
+    w = trdq.prepare_weights_rpr(Wd, dd, perm_d, wbits=8)
+    X = gu.bf16_to_dev(Xb)
+    Xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+    sx = torch.empty((M,), dtype=torch.float32, device="cuda")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    trdq.rotate_quant_rpr(X, dd, perm_d, Xq, sx, warm=w)
+    trdq.qgemm(w, Xq, sx, Y, bias=bd)
+    torch.cuda.synchronize()
+
+    amax = Xq.abs().amax(dim=1)
+    live = sx > 0
+    assert bool((amax[live] == 127).all()) and bool((amax[~live] == 0).all())
+    assert bool(torch.isfinite(Y.float()).all())
+
+    ref = oracle.linear_rpr(Xb[rows], W, d, perm, bias, 128, 8, exact_blas=True)
+    idx = torch.from_numpy(rows).cuda()
+    gu.assert_codes_close(Xq[idx].cpu().numpy(), ref["Xq"], f"{kind} Xq (R P R)")
+    gu.assert_scales_close(sx[idx].cpu().numpy(), ref["sx"], f"{kind} s_x (R P R)")
+    codes, scales = w.export()
+    gu.assert_codes_close(codes, ref["Wq"], f"{kind} Wq (R P R)")
+    gu.assert_scales_close(scales, ref["sw"], f"{kind} s_w (R P R)")
+    rows_diff = (Xq[idx].cpu().numpy() != ref["Xq"]).any(axis=1)
+    cols_diff = (codes != ref["Wq"]).any(axis=0)
+    gu.assert_y_close(gu.bf16_to_host(Y[idx]), ref["Y"], f"{kind} Y (R P R)", rows_diff, cols_diff)
+    w.close()
