@@ -14,8 +14,9 @@
 //   stage 2: each wave gathers the channels perm[k'] of its output blocks from LDS, rotates them
 //            the same way and keeps the results in registers until the token maxima are known
 //            (exchanged through LDS), then quantises and stores like rotate_quant.
-// The matrix instruction needs 16 columns (tokens): with TOK = 8 lanes r >= 8 repeat token r - 8
-// and their results are dropped.  Both rotations are unnormalised; the factor 1/128 goes into
+// The matrix instruction has 16 columns: 16 tokens of one block, or, with TOK = 8, 8 tokens of
+// two blocks at once (lanes r >= 8 hold token r - 8 of the wave's second block; the +-1 operand
+// is the same for every column).  Both rotations are unnormalised; the factor 1/128 goes into
 // the scale.  Entries of perm are clamped to [0, K) on the way in, so a bad table gives wrong
 // numbers, never an access outside the row.
 #include "device_utils.h"
@@ -59,11 +60,12 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, r = lane & 15;
+    constexpr int BPI = 16 / TOK;                    // blocks a wave rotates per matrix instruction
     const int rt = r & (TOK - 1);                    // token slot of this lane
-    const bool lane_ok = r < TOK;
+    const int bsel = r / TOK;                        // which of the item's blocks this lane holds
     const int64_t tg = blockIdx.x;
     int64_t token = tg * TOK + rt;
-    const bool token_ok = lane_ok && token < M;
+    const bool token_ok = token < M;
     if (token >= M) token = M - 1;                   // clamped: rotated like the others, never stored
 
     // ---- stage 1: T[token][.] = (x * d) H_128 per block (natural row order of H_16) -----------
@@ -72,8 +74,11 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
     for (int s = 0; s < 4; ++s) hn[s] = (__builtin_popcount(r & (4 * s + g)) & 1) ? -1.0f : 1.0f;
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
-        const int b = wave + nw * i;
-        if (b < nb) {
+        const int b0 = (wave + nw * i) * BPI;        // wave-uniform: first block of the item
+        if (b0 < nb) {
+            const int bl = b0 + bsel;                // this lane's block (may be one past the end)
+            const bool b_ok = bl < nb;
+            const int b = b_ok ? bl : nb - 1;        // clamped: rotated, not written
             float w[4][8];
             const uint16_t *src = X + token * ldx + b * kBlock + g * 8;
 #pragma unroll
@@ -100,7 +105,7 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
                 for (int s = 0; s < 4; ++s)
                     acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(hn[s], w[s][j], acc[j], 0, 0, 0);
             }
-            if (lane_ok) {
+            if (b_ok) {
                 float *dst = T + (size_t)rt * rowf + b * kBlock + g * 32;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -141,8 +146,9 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
     const float *Trow = T + (size_t)rt * rowf;
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
-        const int b = wave + nw * i;
-        if (b < nb) {
+        const int b0 = (wave + nw * i) * BPI;
+        if (b0 < nb) {
+            const int b = (b0 + bsel < nb) ? b0 + bsel : nb - 1;
             float w[4][8];
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
@@ -174,17 +180,18 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
     // token absmax: over the four lane-rows of this wave, then over the waves through LDS
     amax = fmaxf(amax, __shfl_xor(amax, 16));
     amax = fmaxf(amax, __shfl_xor(amax, 32));
+    if (BPI == 2) amax = fmaxf(amax, __shfl_xor(amax, 8));       // the token's other block in this wave
     if (g == 0) amax_s[wave * 16 + r] = amax;
     __syncthreads();
     for (int wv = 0; wv < nw; ++wv) amax = fmaxf(amax, amax_s[wv * 16 + r]);
 
     // out holds 128 * V.  s_x = max|V| / 127; codes = rint(V / s_x) = rint(out * 127 / max|out|).
     const float inv = amax > 0.0f ? 127.0f / amax : 0.0f;
-    if (wave == 0 && g == 0 && token_ok) sx[token] = amax * (0.0078125f / 127.0f);
+    if (wave == 0 && g == 0 && r < TOK && token_ok) sx[token] = amax * (0.0078125f / 127.0f);
 
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
-        const int b = wave + nw * i;
+        const int b = (wave + nw * i) * BPI + bsel;
         if (b < nb && token_ok) {
             uint32_t c[8];
 #pragma unroll
@@ -235,9 +242,11 @@ hipError_t launch_rotate_quant_rpr(const uint16_t *X, int64_t M, int K, int64_t 
     if (M == 0) return hipSuccess;
     if (!rotate_quant_rpr_supports(K)) return hipErrorInvalidValue;
     const int nb = K / kBlock;
-    const int spw = nb <= 12 ? 1 : (nb <= 24 ? 2 : 3);
-    const int nw = (nb + spw - 1) / spw;
-    const bool tok16 = (size_t)16 * (K + kRowPad) * 4 + (size_t)nw * 64 + 1024 <= 150 * 1024;
+    // 16 tokens per workgroup while their rows fit LDS, else 8 tokens and two blocks per item
+    const bool tok16 = (size_t)16 * (K + kRowPad) * 4 + (size_t)12 * 64 + 1024 <= 150 * 1024;
+    const int items = tok16 ? nb : (nb + 1) / 2;
+    const int spw = items <= 12 ? 1 : (items <= 24 ? 2 : 3);
+    const int nw = (items + spw - 1) / spw;
     if (tok16) {
         switch (spw) {
             case 1: return launch_rpr<16, 1>(X, M, nb, nw, ldx, diag, perm, Xq, sx, warm, warm_bytes, st);
