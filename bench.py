@@ -175,9 +175,10 @@ def main():
             X[kind, g] = torch.from_numpy(xb.view(np.int16)).to(dev).view(torch.bfloat16)
             D[kind, g] = torch.from_numpy(wl.make_diag(cfg, kind, g)).to(dev)
             if args.rpr:
-                # zigzag permutation from the per-channel absmax of this group's scaled activations
-                mag = (X[kind, g].float().abs().amax(dim=0) * D[kind, g]).cpu().numpy()
-                P[kind, g] = torch.from_numpy(trdq.zigzag_permutation(mag)).to(dev)
+                # zigzag permutation from the per-channel absmax of this group's once-rotated activations
+                mag = torch.empty((K,), dtype=torch.float32, device=dev)
+                trdq.channel_absmax(X[kind, g], D[kind, g], mag, rotate=True)
+                P[kind, g] = torch.from_numpy(trdq.zigzag_permutation(mag.cpu().numpy())).to(dev)
                 Wh[kind, g] = trdq.prepare_weights_rpr(Wd, D[kind, g], P[kind, g], wbits=wbits)
             else:
                 Wh[kind, g] = trdq.prepare_weights(Wd, D[kind, g], wbits=wbits)

@@ -144,6 +144,31 @@ trdq_status trdq_rotate_quant_warm(const void *X_dev, int64_t M, int K, int64_t 
  * Weights prepared with trdq_prepare_weights_rpr go with activations from
  * trdq_rotate_quant_rpr (same diag, same perm) through the unchanged trdq_qgemm. */
 
+/* ---------------------------------------------------------- calibration side
+ * The per-channel statistics that the smoothing diagonal (Sec. 3.1, Eq. 5) and the zigzag
+ * permutation (Sec. 3.2) are computed from, and Eq. 5 itself.  Offline, once per time-step group,
+ * on calibration activations of that group. */
+
+/* mag_dev[k] = max over the M tokens of |(X . diag)[i, k]| (rotate == 0) or of
+ * |((X . diag) . R)[i, k]| (rotate != 0: after the first block rotation, the input of the zigzag
+ * permutation).  X_dev, ldx, diag_dev (NULL = ones), block as in trdq_rotate_quant; mag_dev:
+ * float32 [K] on the device, overwritten (M == 0 gives zeros).  Errors as trdq_rotate_quant;
+ * NULL mag_dev -> ERR_NULL. */
+trdq_status trdq_channel_absmax(const void *X_dev, int64_t M, int K, int64_t ldx, const float *diag_dev,
+                                int rotate, int block, float *mag_dev, void *stream);
+
+/* wmax_dev[k] = max_n |W[k, n]| for W_dev float32 [K, N] row-major (C_in x C_out): the weight side
+ * of Eq. 5.  Errors: NULL -> ERR_NULL; K <= 0 or N <= 0 -> ERR_SHAPE. */
+trdq_status trdq_weight_row_absmax(const float *W_dev, int K, int N, float *wmax_dev, void *stream);
+
+/* Eq. 5 in the form this library applies it: Eq. 4 divides activations by Delta, Eq. 9/10 (and
+ * every call here) multiply them by the diagonal, so diag = 1 / Delta:
+ *   diag[k] = wmax[k]^(1 - alpha) / xmax[k]^alpha,   alpha in [0, 1] the migration strength;
+ * a channel with xmax == 0 or wmax == 0 gets diag = 1.  All arrays float32 [K] on the device.
+ * Errors: NULL -> ERR_NULL; K <= 0 -> ERR_SHAPE; alpha outside [0, 1] (or NaN) -> ERR_RANGE. */
+trdq_status trdq_smooth_diag(const float *xmax_dev, const float *wmax_dev, int K, float alpha,
+                             float *diag_dev, void *stream);
+
 /* Zigzag permutation (Sec. 3.2): channels in order of decreasing magnitude are dealt to the
  * K / block blocks back and forth (blocks 0..nb-1, then nb-1..0, ...); round r fills slot r of
  * every block; equal magnitudes keep their channel order.  Host arrays: chan_mag_host[K] (for

@@ -204,6 +204,35 @@ def linear_rpr(X_bf16, W, d, perm, bias=None, B=128, wbits=8, exact_blas=False):
     return dict(Xq=Xq, sx=sx, Wq=Wq, sw=sw, acc=acc, Y=Y, Yd=Yd)
 
 
+# ---- calibration side: Eq. 5 and the statistics it and the zigzag permutation need ----------
+
+def channel_absmax(X_bf16, d=None, rotate_first=False, B=128):
+    """max over tokens of |(X diag(d))[i, k]|, or of |((X diag(d)) R)[i, k]| when rotate_first."""
+    if rotate_first:
+        V = rotate(X_bf16, d, B)
+    else:
+        V = bf16_to_f64(X_bf16)
+        if d is not None:
+            V = V * np.asarray(d, dtype=np.float64)[None, :]
+    return np.abs(V).max(axis=0) if V.shape[0] else np.zeros(V.shape[1])
+
+
+def weight_row_absmax(W):
+    return np.abs(np.asarray(W, dtype=np.float64)).max(axis=1)
+
+
+def smooth_diag(xmax, wmax, alpha):
+    """Eq. 5, Delta_j = max|X_j|^alpha / max|W_j|^(1-alpha), returned as the multiplier of the
+    activations d_j = 1 / Delta_j (Eq. 9/10 multiply X by the diagonal where Eq. 4 divides by it).
+    A channel whose activation or weight maximum is zero keeps d_j = 1."""
+    xmax = np.asarray(xmax, dtype=np.float64)
+    wmax = np.asarray(wmax, dtype=np.float64)
+    d = np.ones_like(xmax)
+    ok = (xmax > 0) & (wmax > 0)
+    d[ok] = wmax[ok] ** (1.0 - alpha) / xmax[ok] ** alpha
+    return d
+
+
 def pack_int4(Wq):
     Wq = _c(Wq, np.int8)
     K, N = Wq.shape

@@ -193,6 +193,34 @@ trdq_status trdq_prepare_weights_rpr(const float *W_dev, int K, int N, const flo
     return prepare_weights_impl(W_dev, K, N, diag_dev, perm_dev, block, wbits, stream, out);
 }
 
+trdq_status trdq_channel_absmax(const void *X_dev, int64_t M, int K, int64_t ldx, const float *diag_dev,
+                                int rotate, int block, float *mag_dev, void *stream)
+{
+    trdq_status rc = check_rotate_args(X_dev, M, K, ldx, block);
+    if (rc != TRDQ_OK) return rc;
+    if (!mag_dev) return TRDQ_ERR_NULL;
+    if (!aligned(mag_dev, 4) || (diag_dev && !aligned(diag_dev, 16))) return TRDQ_ERR_SHAPE;
+    return hip_status(trdq::launch_channel_absmax(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev,
+                                                  rotate != 0, mag_dev, static_cast<hipStream_t>(stream)));
+}
+
+trdq_status trdq_weight_row_absmax(const float *W_dev, int K, int N, float *wmax_dev, void *stream)
+{
+    if (!W_dev || !wmax_dev) return TRDQ_ERR_NULL;
+    if (K <= 0 || N <= 0) return TRDQ_ERR_SHAPE;
+    return hip_status(trdq::launch_weight_row_absmax(W_dev, K, N, wmax_dev, static_cast<hipStream_t>(stream)));
+}
+
+trdq_status trdq_smooth_diag(const float *xmax_dev, const float *wmax_dev, int K, float alpha,
+                             float *diag_dev, void *stream)
+{
+    if (!xmax_dev || !wmax_dev || !diag_dev) return TRDQ_ERR_NULL;
+    if (K <= 0) return TRDQ_ERR_SHAPE;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return TRDQ_ERR_RANGE;
+    return hip_status(trdq::launch_smooth_diag(xmax_dev, wmax_dev, K, alpha, diag_dev,
+                                               static_cast<hipStream_t>(stream)));
+}
+
 trdq_status trdq_zigzag_permutation(const float *chan_mag_host, int K, int block, int32_t *perm_host)
 {
     if (!chan_mag_host || !perm_host) return TRDQ_ERR_NULL;

@@ -49,6 +49,12 @@ hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag
 hipError_t launch_prepare_quant(const float *Wrot, const float *amax, int K, int N, int wbits, float norm,
                                 void *codes, float *scales, hipStream_t st);
 
+// Calibration-side reductions (calibrate.hip).  mag / wmax / d are device arrays of K floats.
+hipError_t launch_channel_absmax(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
+                                 bool rotate, float *mag, hipStream_t st);
+hipError_t launch_weight_row_absmax(const float *W, int K, int N, float *wmax, hipStream_t st);
+hipError_t launch_smooth_diag(const float *xmax, const float *wmax, int K, float alpha, float *d, hipStream_t st);
+
 int qgemm_num_variants();
 hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int64_t M,
                         const float *bias, uint16_t *Y, int64_t ldy, int32_t *acc_debug,

@@ -22,6 +22,7 @@ SYMBOLS = [
     "trdq_layer_create", "trdq_layer_set_group", "trdq_layer_forward", "trdq_layer_weights",
     "trdq_layer_destroy", "trdq_qgemm_set_variant", "trdq_qgemm_num_variants",
     "trdq_zigzag_permutation", "trdq_prepare_weights_rpr", "trdq_rotate_quant_rpr",
+    "trdq_channel_absmax", "trdq_weight_row_absmax", "trdq_smooth_diag",
 ]
 
 _lib = None
@@ -70,6 +71,9 @@ def lib():
         L.trdq_layer_destroy.restype = None
         L.trdq_qgemm_set_variant.argtypes = [i32]
         L.trdq_zigzag_permutation.argtypes = [p, i32, i32, p]
+        L.trdq_channel_absmax.argtypes = [p, i64, i32, i64, p, i32, i32, p, p]
+        L.trdq_weight_row_absmax.argtypes = [p, i32, i32, p, p]
+        L.trdq_smooth_diag.argtypes = [p, p, i32, C.c_float, p, p]
         L.trdq_prepare_weights_rpr.argtypes = [p, i32, i32, p, p, i32, i32, p, C.POINTER(p)]
         L.trdq_rotate_quant_rpr.argtypes = [p, i64, i32, i64, p, p, i32, p, p, p, p]
         L.trdq_qgemm_num_variants.restype = i32
@@ -190,6 +194,25 @@ def prepare_weights(W, diag=None, block=BLOCK, wbits=8, stream=None):
     _check(lib().trdq_prepare_weights(_ptr(W), K, N, _ptr(diag), block, wbits, _stream(stream), C.byref(h)),
            "trdq_prepare_weights")
     return Weights(h)
+
+
+def channel_absmax(X, diag, mag, rotate=False, block=BLOCK, stream=None):
+    """mag[k] = max_i |(X diag)[i, k]|, or of the once-rotated activations when rotate is set."""
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    _check(lib().trdq_channel_absmax(_ptr(X), M, K, ldx, _ptr(diag), int(bool(rotate)), block, _ptr(mag),
+                                     _stream(stream)), "trdq_channel_absmax")
+
+
+def weight_row_absmax(W, wmax, stream=None):
+    K, N = W.shape
+    _check(lib().trdq_weight_row_absmax(_ptr(W), K, N, _ptr(wmax), _stream(stream)), "trdq_weight_row_absmax")
+
+
+def smooth_diag(xmax, wmax, alpha, diag, stream=None):
+    """Eq. 5 as the multiplier of the activations: diag = wmax^(1-alpha) / xmax^alpha."""
+    _check(lib().trdq_smooth_diag(_ptr(xmax), _ptr(wmax), xmax.shape[0], float(alpha), _ptr(diag), _stream(stream)),
+           "trdq_smooth_diag")
 
 
 def zigzag_permutation(chan_mag, block=BLOCK):

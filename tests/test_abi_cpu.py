@@ -172,3 +172,17 @@ def test_rpr_argument_errors_before_any_gpu_call():
     assert L.trdq_rotate_quant_rpr(0x1000, 4, 256, 256, None, 0x4004, 128, 0x2000, 0x3000, None, None) == trdq.ERR_SHAPE
     assert L.trdq_rotate_quant_rpr(0x1000, 4, 128 * 37, 128 * 37, None, 0x4000, 128, 0x2000, 0x3000, None, None) == trdq.ERR_UNSUPPORTED
     assert L.trdq_rotate_quant_rpr(0x1000, 0, 256, 256, None, 0x4000, 128, None, None, None, None) == trdq.OK
+
+
+def test_calibration_argument_errors_before_any_gpu_call():
+    L = trdq.lib()
+    assert L.trdq_channel_absmax(0x1000, 4, 256, 256, None, 1, 128, None, None) == trdq.ERR_NULL
+    assert L.trdq_channel_absmax(None, 4, 256, 256, None, 1, 128, 0x2000, None) == trdq.ERR_NULL
+    assert L.trdq_channel_absmax(0x1000, 4, 200, 256, None, 1, 128, 0x2000, None) == trdq.ERR_SHAPE
+    assert L.trdq_channel_absmax(0x1000, 4, 256, 256, None, 1, 64, 0x2000, None) == trdq.ERR_UNSUPPORTED
+    assert L.trdq_weight_row_absmax(None, 256, 64, 0x2000, None) == trdq.ERR_NULL
+    assert L.trdq_weight_row_absmax(0x1000, 0, 64, 0x2000, None) == trdq.ERR_SHAPE
+    assert L.trdq_smooth_diag(None, 0x1000, 256, 0.5, 0x2000, None) == trdq.ERR_NULL
+    assert L.trdq_smooth_diag(0x1000, 0x1000, 0, 0.5, 0x2000, None) == trdq.ERR_SHAPE
+    assert L.trdq_smooth_diag(0x1000, 0x1000, 256, 1.5, 0x2000, None) == trdq.ERR_RANGE
+    assert L.trdq_smooth_diag(0x1000, 0x1000, 256, float("nan"), 0x2000, None) == trdq.ERR_RANGE

@@ -113,3 +113,82 @@ def test_linear_rpr_end_to_end(oracle, M, K, N, wbits):
     got = oracle.bf16_to_f64(bf16_to_host(Y))
     rel = np.linalg.norm(got - exact) / np.linalg.norm(exact)
     assert rel < (0.03 if wbits == 8 else 0.2), rel
+
+
+# ---- calibration side: channel statistics and Eq. 5 --------------------------------------------
+
+@pytest.mark.parametrize("M,K", [(1, 128), (37, 256), (300, 1152), (4096, 1152), (1000, 4608)])
+@pytest.mark.parametrize("rotate", [False, True])
+def test_channel_absmax_matches_oracle(oracle, M, K, rotate):
+    say(f"channel_absmax M={M} K={K} rotate={rotate}")
+    Xb, W, d, bias = wl.small_case(31, M, K, 16, n_outliers=max(1, K // 144), outlier=40.0)
+    mag = torch.full((K,), -1.0, dtype=torch.float32, device=dev())
+    trdq.channel_absmax(bf16_to_dev(Xb), f32_to_dev(d), mag, rotate=rotate)
+    torch.cuda.synchronize()
+    want = oracle.channel_absmax(Xb, d, rotate_first=rotate)
+    assert np.allclose(mag.cpu().numpy(), want, rtol=1e-5, atol=0)
+    # no diagonal, strided rows
+    buf = torch.zeros((M, K + 64), dtype=torch.bfloat16, device=dev())
+    Xs = buf[:, :K]
+    Xs.copy_(bf16_to_dev(Xb))
+    trdq.channel_absmax(Xs, None, mag, rotate=rotate)
+    torch.cuda.synchronize()
+    assert np.allclose(mag.cpu().numpy(), oracle.channel_absmax(Xb, None, rotate_first=rotate), rtol=1e-5, atol=0)
+
+
+def test_channel_absmax_no_tokens_gives_zeros():
+    mag = torch.full((256,), -1.0, dtype=torch.float32, device=dev())
+    X = torch.empty((0, 256), dtype=torch.bfloat16, device=dev())
+    trdq.channel_absmax(X, None, mag, rotate=True)
+    torch.cuda.synchronize()
+    assert bool((mag == 0).all())
+
+
+@pytest.mark.parametrize("alpha", [0.0, 0.5, 0.85, 1.0])
+def test_smoothing_diagonal_matches_oracle(oracle, alpha):
+    M, K, N = 256, 1152, 272
+    Xb, W, d, bias = wl.small_case(32, M, K, N, n_outliers=8, outlier=50.0)
+    W[5] = 0.0                                                    # a dead weight row: d = 1 there
+    xmax = torch.empty((K,), dtype=torch.float32, device=dev())
+    wmax = torch.empty((K,), dtype=torch.float32, device=dev())
+    diag = torch.empty((K,), dtype=torch.float32, device=dev())
+    trdq.channel_absmax(bf16_to_dev(Xb), None, xmax)
+    trdq.weight_row_absmax(f32_to_dev(W), wmax)
+    trdq.smooth_diag(xmax, wmax, alpha, diag)
+    torch.cuda.synchronize()
+    xo, wo = oracle.channel_absmax(Xb), oracle.weight_row_absmax(W)
+    assert np.array_equal(xmax.cpu().numpy().astype(np.float64), xo)          # maxima of bf16 values: exact
+    assert np.array_equal(wmax.cpu().numpy().astype(np.float64), wo)
+    want = oracle.smooth_diag(xo, wo, alpha)
+    assert np.allclose(diag.cpu().numpy(), want, rtol=1e-5, atol=0)
+    assert diag[5].item() == 1.0
+
+
+def test_calibrate_then_run_the_full_path(oracle):
+    """Eq. 5 diagonal and zigzag permutation computed on the GPU from the data, then the Eq. 9 path."""
+    M, K, N = 192, 1152, 288
+    Xb, W, _, bias = wl.small_case(33, M, K, N, n_outliers=8, outlier=50.0)
+    X, Wd = bf16_to_dev(Xb), f32_to_dev(W)
+    xmax = torch.empty((K,), dtype=torch.float32, device=dev())
+    wmax = torch.empty_like(xmax)
+    diag = torch.empty_like(xmax)
+    mag = torch.empty_like(xmax)
+    trdq.channel_absmax(X, None, xmax)
+    trdq.weight_row_absmax(Wd, wmax)
+    trdq.smooth_diag(xmax, wmax, 0.5, diag)
+    trdq.channel_absmax(X, diag, mag, rotate=True)
+    torch.cuda.synchronize()
+    d = diag.cpu().numpy()
+    perm = trdq.zigzag_permutation(mag.cpu().numpy())
+    perm_d = torch.from_numpy(perm).to(dev())
+    w = trdq.prepare_weights_rpr(Wd, diag, perm_d, wbits=8)
+    Xq, sx = _gpu_rotate_quant_rpr(Xb, d, perm)
+    Y, _ = gpu_qgemm(w, Xq, sx, bias, N, debug=False)
+    ref = oracle.linear_rpr(Xb, W, d, perm, bias, 128, 8, exact_blas=True)
+    codes, _ = w.export()
+    rows = np.any(Xq.cpu().numpy() != ref["Xq"], axis=1)
+    cols = np.any(codes != ref["Wq"], axis=0)
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (calibrated R P R)", skip_rows=rows, skip_cols=cols)
+    exact = oracle.bf16_to_f64(Xb) @ W.astype(np.float64) + bias.astype(np.float64)
+    got = oracle.bf16_to_f64(bf16_to_host(Y))
+    assert np.linalg.norm(got - exact) / np.linalg.norm(exact) < 0.03

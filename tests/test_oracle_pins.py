@@ -515,3 +515,53 @@ def test_rpr_balances_the_blocks(oracle):
     assert np.isclose(e1.sum(), e2.sum(), rtol=1e-12)          # orthogonal: total energy kept
     assert e1.max() / e1.min() > 10.0                          # 8 outlier channels in 9 blocks
     assert e2.max() / e2.min() < 1.5
+
+
+# ------------------------------------------------ calibration side (Eq. 5)
+
+def test_smooth_diag_closed_forms(oracle):
+    rng = np.random.default_rng(11)
+    K = 64
+    xmax = np.exp(rng.standard_normal(K) * 2.0)
+    wmax = np.exp(rng.standard_normal(K))
+    # alpha = 1: all of the range moves to the weights, every scaled activation channel peaks at 1
+    d1 = oracle.smooth_diag(xmax, wmax, 1.0)
+    assert np.allclose(xmax * d1, 1.0, rtol=1e-14)
+    # alpha = 0: the other way round, every scaled weight row peaks at 1
+    d0 = oracle.smooth_diag(xmax, wmax, 0.0)
+    assert np.allclose(wmax / d0, 1.0, rtol=1e-14)
+    # alpha = 1/2: both sides meet at the geometric mean
+    dh = oracle.smooth_diag(xmax, wmax, 0.5)
+    assert np.allclose(xmax * dh, np.sqrt(xmax * wmax), rtol=1e-14)
+    assert np.allclose(wmax / dh, np.sqrt(xmax * wmax), rtol=1e-14)
+    # Eq. 5 itself (Delta = 1 / d) for a general alpha
+    a = 0.3
+    assert np.allclose(1.0 / oracle.smooth_diag(xmax, wmax, a), xmax ** a / wmax ** (1 - a), rtol=1e-14)
+    # dead channels keep d = 1
+    xmax[3] = 0.0
+    wmax[5] = 0.0
+    d = oracle.smooth_diag(xmax, wmax, 0.5)
+    assert d[3] == 1.0 and d[5] == 1.0 and np.all(np.isfinite(d))
+
+
+def test_channel_statistics_on_data(oracle):
+    rng = np.random.default_rng(12)
+    M, K, N = 40, 256, 24
+    Xf = rng.standard_normal((M, K)).astype(np.float32)
+    Xf[:, 7] *= 60.0
+    X = _bf16(Xf)
+    W = (0.02 * rng.standard_normal((K, N))).astype(np.float32)
+    xmax = oracle.channel_absmax(X)
+    assert np.array_equal(xmax, np.abs(oracle.bf16_to_f64(X)).max(axis=0))
+    assert xmax.argmax() == 7
+    wmax = oracle.weight_row_absmax(W)
+    assert np.array_equal(wmax, np.abs(W.astype(np.float64)).max(axis=1))
+    # with d from Eq. 5 at alpha = 1/2 the scaled operands have equal per-channel maxima, and
+    # the product is unchanged (Eq. 4)
+    d = oracle.smooth_diag(xmax, wmax, 0.5)
+    assert np.allclose(oracle.channel_absmax(X, d), oracle.weight_row_absmax(W / d[:, None]), rtol=1e-6)
+    Xs = oracle.bf16_to_f64(X) * d
+    assert np.allclose(Xs @ (W / d[:, None]), oracle.bf16_to_f64(X) @ W.astype(np.float64), rtol=1e-9, atol=1e-12)
+    # rotated statistic: the maximum over tokens of the once-rotated activations
+    mag = oracle.channel_absmax(X, d.astype(np.float32), rotate_first=True)
+    assert np.array_equal(mag, np.abs(oracle.rotate(X, d.astype(np.float32), 128)).max(axis=0))
