@@ -180,6 +180,59 @@ int trdq_oracle_quant_tokens(const double *V, int64_t M, int K, int8_t *Xq, doub
     return 0;
 }
 
+/* -------------------------------------------- asymmetric activation quantiser */
+
+/* Per-token asymmetric 8-bit quantiser of Eq. 1-3:
+ *   s_i = (hi_i - lo_i) / 255,   z_i = -rint(lo_i / s_i),   q[i,k] = clamp(rint(V[i,k] / s_i) + z_i, 0, 255),
+ * so that V ~ s_i * (q - z_i).  Readings: Eq. 3 as printed has z = rint(min / s), which added in
+ * Eq. 1 would map the minimum to 2 min / s; the zero point has to be the code of the value 0, hence
+ * the minus sign.  The range is taken as lo = min(min_k V, 0), hi = max(max_k V, 0): zero is then
+ * exactly representable, z lies in [0, 255] and a constant row has a non-zero range; a row of
+ * zeros gets s = 0, z = 0 and codes 0.  Rounding: nearest, ties to even. */
+int trdq_oracle_quant_tokens_asym(const double *V, int64_t M, int K, uint8_t *Xq, double *sx, int32_t *zx)
+{
+    if (!V || !Xq || !sx || !zx || M < 0 || K <= 0) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        const double *v = V + i * (int64_t)K;
+        double lo = 0.0, hi = 0.0;
+        for (int k = 0; k < K; ++k) { if (v[k] < lo) lo = v[k]; if (v[k] > hi) hi = v[k]; }
+        if (hi == lo) {
+            sx[i] = 0.0; zx[i] = 0;
+            for (int k = 0; k < K; ++k) Xq[i * (int64_t)K + k] = 0;
+            continue;
+        }
+        double s = (hi - lo) / 255.0;
+        double z = -rint(lo / s);
+        sx[i] = s;
+        zx[i] = (int32_t)z;
+        for (int k = 0; k < K; ++k) {
+            double q = rint(v[k] / s) + z;
+            if (q > 255.0) q = 255.0;
+            if (q < 0.0) q = 0.0;
+            Xq[i * (int64_t)K + k] = (uint8_t)q;
+        }
+    }
+    return 0;
+}
+
+/* acc[i,n] = sum_k (q[i,k] - z_i) * Wq[k,n]   in int32 (|.| <= 255 * 127 * K < 2^31 for K <= 66 000):
+ * the integer part of the product of the dequantised operands s_i (q - z_i) and s_w[n] Wq. */
+int trdq_oracle_igemm_asym(const uint8_t *Xq, const int32_t *zx, const int8_t *Wq, int64_t M, int K, int N,
+                           int32_t *acc)
+{
+    if (!Xq || !zx || !Wq || !acc || M < 0 || K <= 0 || N <= 0) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int n = 0; n < N; ++n) {
+            int32_t t = 0;
+            for (int k = 0; k < K; ++k)
+                t += ((int32_t)Xq[i * (int64_t)K + k] - zx[i]) * (int32_t)Wq[(size_t)k * N + n];
+            acc[i * (int64_t)N + n] = t;
+        }
+    return 0;
+}
+
 /* ------------------------------------- second rotation and zigzag permutation */
 
 /* Zigzag permutation (Sec. 3.2, "zigzag permutation"): the channels, taken in order of

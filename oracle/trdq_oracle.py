@@ -40,6 +40,8 @@ def lib():
         L.trdq_oracle_dequant.argtypes = [p, p, p, p, i64, i32, i32, p, p]
         L.trdq_oracle_linear.argtypes = [p, i64, i32, i64, p, i32, p, p, i32, i32,
                                          p, p, p, p, p, p]
+        L.trdq_oracle_quant_tokens_asym.argtypes = [p, i64, i32, p, p, p]
+        L.trdq_oracle_igemm_asym.argtypes = [p, p, p, i64, i32, i32, p]
         L.trdq_oracle_zigzag.argtypes = [p, i32, i32, p]
         L.trdq_oracle_permute_cols.argtypes = [p, i64, i32, p, p]
         L.trdq_oracle_rotate_f64.argtypes = [p, i64, i32, i32, p]
@@ -202,6 +204,45 @@ def linear_rpr(X_bf16, W, d, perm, bias=None, B=128, wbits=8, exact_blas=False):
     acc = (acc_exact_blas if exact_blas else igemm)(Xq, Wq, group)
     Y, Yd = dequant(acc, sx, sw, bias, return_f64=True)
     return dict(Xq=Xq, sx=sx, Wq=Wq, sw=sw, acc=acc, Y=Y, Yd=Yd)
+
+
+# ---- asymmetric per-token activation quantiser (Eq. 1-3 with a zero point) --------------------
+
+def quant_tokens_asym(V):
+    """(codes uint8 [M, K] in 0..255, scales float64 [M], zero points int32 [M]); V ~ s (q - z)."""
+    V = _c(V, np.float64)
+    M, K = V.shape
+    Xq = np.empty((M, K), dtype=np.uint8)
+    sx = np.empty(M, dtype=np.float64)
+    zx = np.empty(M, dtype=np.int32)
+    _chk(lib().trdq_oracle_quant_tokens_asym(_ptr(V), M, K, _ptr(Xq), _ptr(sx), _ptr(zx)), "quant_tokens_asym")
+    return Xq, sx, zx
+
+
+def igemm_asym(Xq, zx, Wq):
+    """int32 [M, N]: sum_k (q[i,k] - z_i) Wq[k,n], the plain loop."""
+    Xq, zx, Wq = _c(Xq, np.uint8), _c(zx, np.int32), _c(Wq, np.int8)
+    M, K = Xq.shape
+    N = Wq.shape[1]
+    acc = np.empty((M, N), dtype=np.int32)
+    _chk(lib().trdq_oracle_igemm_asym(_ptr(Xq), _ptr(zx), _ptr(Wq), M, K, N, _ptr(acc)), "igemm_asym")
+    return acc
+
+
+def acc_asym_exact_blas(Xq, zx, Wq):
+    """The same sums through a float64 library matmul (all partial sums are integers below 2^53)."""
+    Xd = np.asarray(Xq).astype(np.float64) - np.asarray(zx).astype(np.float64)[:, None]
+    return (Xd @ np.asarray(Wq).astype(np.float64)).astype(np.int32)
+
+
+def linear_asym(X_bf16, W, d=None, bias=None, B=128, exact_blas=False):
+    """Rotated W8A8 linear with asymmetric per-token activations (weights stay symmetric per channel)."""
+    V = rotate(X_bf16, d, B)
+    Xq, sx, zx = quant_tokens_asym(V)
+    Wq, sw = prepare_weights(W, d, B, 8)
+    acc = acc_asym_exact_blas(Xq, zx, Wq) if exact_blas else igemm_asym(Xq, zx, Wq)
+    Y, Yd = dequant(acc, sx, sw, bias, return_f64=True)
+    return dict(Xq=Xq, sx=sx, zx=zx, Wq=Wq, sw=sw, acc=acc, Y=Y, Yd=Yd)
 
 
 # ---- calibration side: Eq. 5 and the statistics it and the zigzag permutation need ----------

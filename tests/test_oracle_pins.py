@@ -565,3 +565,89 @@ def test_channel_statistics_on_data(oracle):
     # rotated statistic: the maximum over tokens of the once-rotated activations
     mag = oracle.channel_absmax(X, d.astype(np.float32), rotate_first=True)
     assert np.array_equal(mag, np.abs(oracle.rotate(X, d.astype(np.float32), 128)).max(axis=0))
+
+
+# ------------------------------------ asymmetric activation quantiser (Eq. 1-3)
+
+def test_asym_quantiser_brute_force_rational(oracle):
+    # Eq. 1-3 evaluated in exact rational arithmetic on a tiny input (values are dyadic, so the
+    # float64 oracle must agree code for code)
+    vals = [[-3.0, 1.5, 0.25, 2.0], [0.5, 4.0, 1.0, 0.125], [-1.0, -0.5, -4.0, -2.5], [0.0, 0.0, 0.0, 0.0]]
+    V = np.array(vals, dtype=np.float64)
+    Xq, sx, zx = oracle.quant_tokens_asym(V)
+
+    def rne(fr):
+        fl = fr.numerator // fr.denominator
+        rem = fr - fl
+        if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+            return fl + 1
+        return fl
+    for i, row in enumerate(vals):
+        fr = [Fraction(v) for v in row]
+        lo, hi = min(min(fr), Fraction(0)), max(max(fr), Fraction(0))
+        if hi == lo:
+            assert sx[i] == 0 and zx[i] == 0 and not Xq[i].any()
+            continue
+        s = (hi - lo) / 255
+        z = -rne(lo / s)
+        assert zx[i] == z and 0 <= z <= 255
+        assert sx[i] == float(s)
+        for k, v in enumerate(fr):
+            assert Xq[i, k] == min(255, max(0, rne(v / s) + z))
+
+
+def test_asym_quantiser_properties(oracle):
+    rng = np.random.default_rng(21)
+    M, K = 64, 256
+    V = rng.standard_normal((M, K)) * np.exp(rng.standard_normal((M, 1)))
+    V[3] = np.abs(V[3])                 # a non-negative row: lo = 0, z = 0
+    V[4] = -np.abs(V[4])                # a non-positive row: hi = 0, z = 255
+    V[5] = 7.0                          # a constant row: range [0, 7]
+    Xq, sx, zx = oracle.quant_tokens_asym(V)
+    assert zx[3] == 0 and zx[4] == 255 and zx[5] == 0 and np.all(Xq[5] == 255)
+    # rows that straddle zero use the whole range; one-sided rows reach the end they have
+    two_sided = np.ones(M, dtype=bool)
+    two_sided[[3, 4, 5]] = False
+    assert np.all(Xq[two_sided].min(axis=1) == 0) and np.all(Xq[two_sided].max(axis=1) == 255)
+    assert Xq[3].max() == 255 and Xq[4].min() == 0
+    deq = sx[:, None] * (Xq.astype(np.float64) - zx[:, None])
+    assert np.all(np.abs(deq - V) <= 0.5 * sx[:, None] * (1 + 1e-9) + 0.5 * sx[:, None])   # rounding + zero-point rounding
+    # twice the resolution of the symmetric quantiser on a one-sided row
+    Xs, ss = oracle.quant_tokens(V[3:4])
+    assert sx[3] < 0.51 * ss[0]
+    # re-quantising the dequantised values reproduces the codes
+    Xq2, sx2, zx2 = oracle.quant_tokens_asym(deq)
+    assert np.array_equal(Xq2, Xq) and np.array_equal(zx2, zx)
+
+
+def test_asym_integer_product_is_the_product_of_dequantised_operands(oracle):
+    rng = np.random.default_rng(22)
+    M, K, N = 5, 64, 7
+    Xq = rng.integers(0, 256, size=(M, K)).astype(np.uint8)
+    zx = rng.integers(0, 256, size=M).astype(np.int32)
+    Wq = rng.integers(-127, 128, size=(K, N)).astype(np.int8)
+    acc = oracle.igemm_asym(Xq, zx, Wq)
+    brute = np.zeros((M, N), dtype=np.int64)
+    for i in range(M):
+        for n in range(N):
+            brute[i, n] = sum((int(Xq[i, k]) - int(zx[i])) * int(Wq[k, n]) for k in range(K))
+    assert np.array_equal(acc.astype(np.int64), brute)
+    assert np.array_equal(oracle.acc_asym_exact_blas(Xq, zx, Wq), acc)
+    # the form an int8 matrix unit can evaluate: signed codes q - 128 plus a column-sum correction
+    colsum = Wq.astype(np.int64).sum(axis=0)
+    signed = (Xq.astype(np.int64) - 128) @ Wq.astype(np.int64) + (128 - zx.astype(np.int64))[:, None] * colsum[None, :]
+    assert np.array_equal(signed, brute)
+
+
+def test_asym_linear_close_to_exact_product(oracle):
+    rng = np.random.default_rng(23)
+    M, K, N = 32, 1152, 48
+    Xf = rng.standard_normal((M, K)).astype(np.float32)
+    Xf[:, rng.choice(K, size=8, replace=False)] *= 50.0
+    X = _bf16(Xf)
+    W = (0.02 * rng.standard_normal((K, N))).astype(np.float32)
+    ref = oracle.linear_asym(X, W)
+    exact = oracle.bf16_to_f64(X) @ W.astype(np.float64)
+    rel_a = np.linalg.norm(ref["Yd"] - exact) / np.linalg.norm(exact)
+    rel_s = np.linalg.norm(oracle.linear(X, W)["Yd"] - exact) / np.linalg.norm(exact)
+    assert rel_a < 0.02 and rel_a < 1.2 * rel_s
