@@ -42,6 +42,8 @@ def parse():
                          "profiler's kernel trace does not list kernels launched from a graph)")
     ap.add_argument("--rpr", action="store_true",
                     help="the full transform of Eq. 9 (rotation, zigzag permutation, rotation) instead of one rotation")
+    ap.add_argument("--asym", action="store_true",
+                    help="asymmetric per-token activation codes (zero point, Eq. 1-3) instead of symmetric ones; W8 only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU work budget of the oracle's timed sample")
     ap.add_argument("--variant", type=int, default=-1, help="qgemm tile variant override")
@@ -161,7 +163,7 @@ def main():
     torch.cuda.set_stream(stream)
 
     # ---- resident state: per kind and group, activations, diagonal, prepared weights ----------
-    X, D, Wh, B, Y, Xq, SX, P = {}, {}, {}, {}, {}, {}, {}, {}
+    X, D, Wh, B, Y, Xq, SX, P, ZC = {}, {}, {}, {}, {}, {}, {}, {}, {}
     for kind in cfg.kinds:
         K, N = wl.LAYER_SHAPES[kind]
         Wd = torch.from_numpy(wl.make_w(cfg, kind)).to(dev)
@@ -169,6 +171,7 @@ def main():
         Y[kind] = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
         Xq[kind] = torch.empty((M, K), dtype=torch.int8, device=dev)
         SX[kind] = torch.empty((M,), dtype=torch.float32, device=dev)
+        ZC[kind] = torch.empty((M,), dtype=torch.int32, device=dev)
         for g in range(n_groups):
             step_of_g = next(s for s in range(cfg.n_steps) if wl.step_to_group(cfg, s) == g)
             xb = wl.make_x(cfg, kind, step_of_g)
@@ -198,6 +201,12 @@ def main():
             if args.fused:
                 calls[g, kind] = (trdq.bind_linear_fused(X[kind, g], D[kind, g], Wh[kind, g], Y[kind],
                                                          bias=B[kind], stream=stream),)
+            elif args.asym:
+                calls[g, kind] = (trdq.bind_rotate_quant_asym(X[kind, g], D[kind, g], Xq[kind], SX[kind], ZC[kind],
+                                                              stream=stream,
+                                                              warm=None if args.no_warm else Wh[kind, g]),
+                                  trdq.bind_qgemm_asym(Wh[kind, g], Xq[kind], SX[kind], ZC[kind], Y[kind],
+                                                       bias=B[kind], stream=stream))
             elif args.rpr:
                 calls[g, kind] = (trdq.bind_rotate_quant_rpr(X[kind, g], D[kind, g], P[kind, g], Xq[kind], SX[kind],
                                                              stream=stream,
@@ -289,7 +298,7 @@ def main():
         "dtype": "int8" if wbits == 8 else "int8xint4", "data": "synthetic",
         "tokens_per_s": M * args.steps / dt,
         "config": {"workload": cfg.name, "tokens": M, "layers": list(cfg.kinds), "groups": n_groups,
-                   "path": "fused" if args.fused else ("rotate_quant_rpr+qgemm" if args.rpr else "rotate_quant+qgemm"), "wbits": wbits,
+                   "path": "fused" if args.fused else ("rotate_quant_rpr+qgemm" if args.rpr else ("rotate_quant_asym+qgemm_asym" if args.asym else "rotate_quant+qgemm")), "wbits": wbits,
                    "launch": "hip graph per step" if graphs else "host launches"},
     }
 

@@ -136,13 +136,26 @@ trdq_status trdq_rotate_quant_warm(const void *X_dev, int64_t M, int K, int64_t 
                                    const float *diag_dev, int block,
                                    int8_t *Xq_dev, float *sx_dev, const trdq_weights *next, void *stream);
 
-/* ------------------------------------------- full transform of Eq. 9
- * G_t(X) = (X . Delta_t) . R^(1) . P . R^(2)  and  H_t(W) = R^(2)^T . P^T . R^(1)^T . (Delta_t^-1 . W)
- * (Sec. 3.2: first block rotation, zigzag permutation, second block rotation).  Both rotations
- * are the block-diagonal Hadamard rotation of the calls above; the permutation is a table
- * perm[K] of source channels, (U P)[k'] = U[perm[k']], so P P^T = I and the product is unchanged.
- * Weights prepared with trdq_prepare_weights_rpr go with activations from
- * trdq_rotate_quant_rpr (same diag, same perm) through the unchanged trdq_qgemm. */
+/* ------------------------------------ asymmetric activations (Eq. 1-3)
+ * The uniform quantiser of Eq. 1-3 as printed is asymmetric: per token, s = (max - min) / 255 and
+ * a zero point z, codes in 0..255, V ~ s (q - z).  The calls above use the symmetric form; this
+ * pair keeps the zero point (weights stay symmetric per output channel, int8 only):
+ *   lo = min(min_k V, 0), hi = max(max_k V, 0), s_x = (hi - lo) / 255, z = -rint(lo / s_x),
+ *   q = clamp(rint(V / s_x) + z, 0, 255);  an all-zero row gives s_x = 0, z = 0.
+ * (Eq. 3 as printed lacks the minus sign; with it the zero point is the code of the value 0.)
+ * Xq_dev receives q - 128 as int8 (what the matrix instruction takes) and zc_dev[i] = 128 - z_i
+ * (int32 [M]); trdq_qgemm_asym adds zc[i] times the column sum of the weight codes to the integer
+ * sums, which makes them sum_k (q - z) Wq exactly, then dequantises as trdq_qgemm does.
+ * acc_debug_dev (optional, int32 [M, N]) receives those corrected sums.  Other arguments, layouts
+ * and errors as trdq_rotate_quant_warm / trdq_qgemm; NULL zc -> ERR_NULL; int4 weights or
+ * K > 4608 (the quantising pass) -> ERR_UNSUPPORTED. */
+trdq_status trdq_rotate_quant_asym(const void *X_dev, int64_t M, int K, int64_t ldx,
+                                   const float *diag_dev, int block,
+                                   int8_t *Xq_dev, float *sx_dev, int32_t *zc_dev, const trdq_weights *next,
+                                   void *stream);
+trdq_status trdq_qgemm_asym(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev,
+                            const int32_t *zc_dev, int64_t M, const float *bias_dev, void *Y_dev, int64_t ldy,
+                            int32_t *acc_debug_dev, void *stream);
 
 /* ---------------------------------------------------------- calibration side
  * The per-channel statistics that the smoothing diagonal (Sec. 3.1, Eq. 5) and the zigzag
@@ -168,6 +181,14 @@ trdq_status trdq_weight_row_absmax(const float *W_dev, int K, int N, float *wmax
  * Errors: NULL -> ERR_NULL; K <= 0 -> ERR_SHAPE; alpha outside [0, 1] (or NaN) -> ERR_RANGE. */
 trdq_status trdq_smooth_diag(const float *xmax_dev, const float *wmax_dev, int K, float alpha,
                              float *diag_dev, void *stream);
+
+/* ------------------------------------------- full transform of Eq. 9
+ * G_t(X) = (X . Delta_t) . R^(1) . P . R^(2)  and  H_t(W) = R^(2)^T . P^T . R^(1)^T . (Delta_t^-1 . W)
+ * (Sec. 3.2: first block rotation, zigzag permutation, second block rotation).  Both rotations
+ * are the block-diagonal Hadamard rotation of the calls above; the permutation is a table
+ * perm[K] of source channels, (U P)[k'] = U[perm[k']], so P P^T = I and the product is unchanged.
+ * Weights prepared with trdq_prepare_weights_rpr go with activations from
+ * trdq_rotate_quant_rpr (same diag, same perm) through the unchanged trdq_qgemm. */
 
 /* Zigzag permutation (Sec. 3.2): channels in order of decreasing magnitude are dealt to the
  * K / block blocks back and forth (blocks 0..nb-1, then nb-1..0, ...); round r fills slot r of

@@ -144,7 +144,8 @@ trdq_status prepare_weights_impl(const float *W_dev, int K, int N, const float *
         hipMalloc(reinterpret_cast<void **>(&w->scales), scale_count * sizeof(float)) != hipSuccess ||
         hipMalloc(reinterpret_cast<void **>(&Wrot), (size_t)K * N * sizeof(float)) != hipSuccess ||
         hipMalloc(reinterpret_cast<void **>(&amax), (size_t)nb * N * sizeof(float)) != hipSuccess ||
-        (perm_dev && hipMalloc(reinterpret_cast<void **>(&Wrot2), (size_t)K * N * sizeof(float)) != hipSuccess)) {
+        (perm_dev && hipMalloc(reinterpret_cast<void **>(&Wrot2), (size_t)K * N * sizeof(float)) != hipSuccess) ||
+        (wbits == 8 && hipMalloc(reinterpret_cast<void **>(&w->colsum), (size_t)N * sizeof(int32_t)) != hipSuccess)) {
         rc = TRDQ_ERR_ALLOC;
         goto fail;
     }
@@ -156,6 +157,7 @@ trdq_status prepare_weights_impl(const float *W_dev, int K, int N, const float *
     } else if (ok) {
         ok = trdq::launch_prepare_quant(Wrot, amax, K, N, wbits, 0.08838834764831845f, w->codes, w->scales, st) == hipSuccess;
     }
+    if (ok && wbits == 8) ok = trdq::launch_weight_colsum(w->codes, K, N, w->colsum, st) == hipSuccess;
     if (!ok || hipStreamSynchronize(st) != hipSuccess) {
         rc = TRDQ_ERR_HIP;
         goto fail;
@@ -172,6 +174,7 @@ fail:
     if (amax) (void)hipFree(amax);
     if (w->codes) (void)hipFree(w->codes);
     if (w->scales) (void)hipFree(w->scales);
+    if (w->colsum) (void)hipFree(w->colsum);
     delete w;
     return rc;
 }
@@ -315,6 +318,7 @@ void trdq_weights_destroy(trdq_weights *w)
     if (!w) return;
     if (w->codes) (void)hipFree(w->codes);
     if (w->scales) (void)hipFree(w->scales);
+    if (w->colsum) (void)hipFree(w->colsum);
     delete w;
 }
 
@@ -345,7 +349,32 @@ trdq_status trdq_rotate_quant_warm(const void *X_dev, int64_t M, int K, int64_t 
         warm_bytes -= warm_bytes % 16;
     }
     return hip_status(trdq::launch_rotate_quant(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev,
-                                                Xq_dev, sx_dev, warm, warm_bytes, static_cast<hipStream_t>(stream)));
+                                                Xq_dev, sx_dev, nullptr, warm, warm_bytes,
+                                                static_cast<hipStream_t>(stream)));
+}
+
+trdq_status trdq_rotate_quant_asym(const void *X_dev, int64_t M, int K, int64_t ldx,
+                                   const float *diag_dev, int block,
+                                   int8_t *Xq_dev, float *sx_dev, int32_t *zc_dev, const trdq_weights *next,
+                                   void *stream)
+{
+    trdq_status rc = check_rotate_args(X_dev, M, K, ldx, block);
+    if (rc != TRDQ_OK) return rc;
+    if (M > 0 && (!Xq_dev || !sx_dev || !zc_dev)) return TRDQ_ERR_NULL;
+    if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || !aligned(zc_dev, 4) || (diag_dev && !aligned(diag_dev, 16)))
+        return TRDQ_ERR_SHAPE;
+    if (K / trdq::kBlock > 36) return TRDQ_ERR_UNSUPPORTED;
+    if (M == 0) return TRDQ_OK;
+    const void *warm = nullptr;
+    int64_t warm_bytes = 0;
+    if (next && next->codes) {
+        warm = next->codes;
+        warm_bytes = (int64_t)next->N * next->K / (next->wbits == 4 ? 2 : 1);
+        warm_bytes -= warm_bytes % 16;
+    }
+    return hip_status(trdq::launch_rotate_quant(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev,
+                                                Xq_dev, sx_dev, zc_dev, warm, warm_bytes,
+                                                static_cast<hipStream_t>(stream)));
 }
 
 trdq_status trdq_rotate_quant_rpr(const void *X_dev, int64_t M, int K, int64_t ldx,
@@ -383,8 +412,25 @@ trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float 
     if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || (acc_debug_dev && !aligned(acc_debug_dev, 16)))
         return TRDQ_ERR_SHAPE;
     if (M == 0) return TRDQ_OK;
-    return hip_status(trdq::launch_qgemm(*w, Xq_dev, sx_dev, M, bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
+    return hip_status(trdq::launch_qgemm(*w, Xq_dev, sx_dev, nullptr, M, bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
                                          acc_debug_dev, g_variant, static_cast<hipStream_t>(stream)));
+}
+
+trdq_status trdq_qgemm_asym(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev,
+                            const int32_t *zc_dev, int64_t M, const float *bias_dev, void *Y_dev, int64_t ldy,
+                            int32_t *acc_debug_dev, void *stream)
+{
+    if (!w) return TRDQ_ERR_NULL;
+    if (w->wbits != 8) return TRDQ_ERR_UNSUPPORTED;
+    trdq_status rc = check_out_args(Y_dev, M, w->N, ldy, bias_dev);
+    if (rc != TRDQ_OK) return rc;
+    if (M > 0 && (!Xq_dev || !sx_dev || !zc_dev)) return TRDQ_ERR_NULL;
+    if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || !aligned(zc_dev, 4) ||
+        (acc_debug_dev && !aligned(acc_debug_dev, 16)))
+        return TRDQ_ERR_SHAPE;
+    if (M == 0) return TRDQ_OK;
+    return hip_status(trdq::launch_qgemm(*w, Xq_dev, sx_dev, zc_dev, M, bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
+                                         acc_debug_dev, -1, static_cast<hipStream_t>(stream)));
 }
 
 trdq_status trdq_linear_fused(const void *X_dev, int64_t M, int64_t ldx, const float *diag_dev,

@@ -17,6 +17,10 @@ struct GemmArgs {
     const float *bias;     // [N] or null
     uint16_t *Y;           // [M, ldy]
     int32_t *acc_debug;    // null, [M, N] or [K/128, M, N]
+    // asymmetric activations (int8 weights only): zc[i] = 128 - z_i per token and the column sums of the
+    // weight codes; the integer sum of a product is acc + zc[i] * colsum[n].  Null otherwise.
+    const int32_t *zc = nullptr;
+    const int32_t *colsum = nullptr;
     int64_t M, ldy;
     int K, N;
     int tiles_m, tiles_n;
@@ -91,6 +95,8 @@ __device__ __forceinline__ void wait_vmcnt()
 // Direct-to-LDS int8 kernels (qgemm_dma.hip).  variant indexes the table in that file.
 int dma_num_variants();
 hipError_t launch_qgemm8_dma(const GemmArgs &a, bool debug, int variant, hipStream_t st);
+// the kernel for asymmetric activations (a.zc and a.colsum set): 128 x 128 ring kernel, any shape
+hipError_t launch_qgemm8_asym(const GemmArgs &a, bool debug, int kind, hipStream_t st);
 
 // int4-weight kernels on the same path (qgemm_dma.hip).
 int dma4_num_variants();

@@ -133,7 +133,34 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_quant_kernel(
     }
 }
 
+// colsum[n] = sum_k codes[n][k]: one wave per output channel (the zero-point term of asymmetric
+// activations needs it in the product's epilogue)
+__global__ __launch_bounds__(64) void weight_colsum_kernel(const int8_t *__restrict__ codes, int K, int N,
+                                                           int32_t *__restrict__ colsum)
+{
+    const int n = blockIdx.x;
+    const int8_t *row = codes + (size_t)n * K;
+    int t = 0;
+    for (int k = threadIdx.x * 16; k < K; k += 64 * 16) {
+        const int4 v = *reinterpret_cast<const int4 *>(row + k);
+        const int wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            t += (int)(int8_t)(wv[u] & 0xFF) + (int)(int8_t)((wv[u] >> 8) & 0xFF) +
+                 (int)(int8_t)((wv[u] >> 16) & 0xFF) + (wv[u] >> 24);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o);
+    if (threadIdx.x == 0) colsum[n] = t;
+}
+
 }  // namespace
+
+hipError_t launch_weight_colsum(const void *codes, int K, int N, int32_t *colsum, hipStream_t st)
+{
+    hipLaunchKernelGGL(weight_colsum_kernel, dim3(N), dim3(64), 0, st, static_cast<const int8_t *>(codes), K, N, colsum);
+    return hipGetLastError();
+}
 
 hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag, const int32_t *perm,
                                  float *Wrot, float *amax, hipStream_t st)

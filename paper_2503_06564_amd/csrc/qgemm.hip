@@ -256,7 +256,7 @@ hipError_t launch_cfg(const GemmArgs &a, bool debug, hipStream_t st)
 constexpr int kRegVariants = 6;
 int qgemm_num_variants() { return kRegVariants + dma_num_variants() + 1; }
 
-hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int64_t M,
+hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, const int32_t *zc, int64_t M,
                         const float *bias, uint16_t *Y, int64_t ldy, int32_t *acc_debug,
                         int variant, hipStream_t st)
 {
@@ -266,6 +266,20 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int
     a.acc_debug = acc_debug; a.M = M; a.ldy = ldy; a.K = w.K; a.N = w.N;
     a.tiles_m = a.tiles_n = 0;
     const bool dbg = acc_debug != nullptr;
+    if (zc) {
+        // asymmetric activations: int8 weights with their column sums; the 128 x 144 kernels where
+        // the symmetric path would take them or the 256 x 256 kernel, else the ring kernel
+        if (w.wbits != 8 || !w.colsum) return hipErrorInvalidValue;
+        a.zc = zc;
+        a.colsum = w.colsum;
+        int kind = 0;
+        if (a.N % 144 == 0 && M % 128 == 0 && a.K >= 512 && ldy % 8 == 0 && reinterpret_cast<uintptr_t>(Y) % 16 == 0) {
+            const int64_t tiles144 = (M / 128) * (a.N / 144);
+            kind = tiles144 > 256 ? 15 : (a.K >= 2304 ? 18 : 14);
+        }
+        if (variant >= 0) kind = variant;     // tests: 0, 14, 15 or 18
+        return launch_qgemm8_asym(a, dbg, kind, st);
+    }
     // the row-wise epilogues store 16 bytes per lane: an output whose rows are only 8-byte aligned
     // goes to the kernels that store 8 bytes per lane
     if (ldy % 8 != 0 || reinterpret_cast<uintptr_t>(Y) % 16 != 0)

@@ -21,15 +21,19 @@ namespace {
 // accumulators of channels n_lane + 16a .. +3 of token m_lane + 16b:
 //   y = float(acc) * s_x[m] * s_w[n] + bias[n]  -> bf16, one 8-byte store per tile.
 // FULL: the workgroup tile lies entirely inside the matrix (no bounds checks).
-template <int TN, int TM, bool DEBUG, bool FULL>
-__device__ __forceinline__ void epilogue_w8(const v4i (&acc)[TN][TM], const GemmArgs &g,
+// ASYM: activations carry a zero point; the codes are q - 128 and the integer sum of the product
+// of the dequantised operands is acc + (128 - z_m) * colsum[n] (exact in int32).
+template <int TN, int TM, bool DEBUG, bool FULL, bool ASYM = false>
+__device__ __forceinline__ void epilogue_w8(const v4i (&acc_in)[TN][TM], const GemmArgs &g,
                                             int64_t m_lane, int n_lane)
 {
     float sxm[TM];
+    int zcm[TM];
 #pragma unroll
     for (int b = 0; b < TM; ++b) {
         const int64_t m = m_lane + b * 16;
         sxm[b] = (FULL || m < g.M) ? g.sx[m] : 0.0f;
+        zcm[b] = (ASYM && (FULL || m < g.M)) ? g.zc[m] : 0;
     }
     const bool has_bias = g.bias != nullptr;
 #pragma unroll
@@ -37,23 +41,28 @@ __device__ __forceinline__ void epilogue_w8(const v4i (&acc)[TN][TM], const Gemm
         const int n = n_lane + a * 16;
         const bool n_ok = FULL || n < g.N;
         float4 s = make_float4(0.f, 0.f, 0.f, 0.f), bi = s;
+        int4 cs = make_int4(0, 0, 0, 0);
         if (n_ok) {
             s = *reinterpret_cast<const float4 *>(g.sw + n);
             if (has_bias) bi = *reinterpret_cast<const float4 *>(g.bias + n);
+            if (ASYM) cs = *reinterpret_cast<const int4 *>(g.colsum + n);
         }
 #pragma unroll
         for (int b = 0; b < TM; ++b) {
             const int64_t m = m_lane + b * 16;
-            const float y0 = (float)acc[a][b][0] * sxm[b] * s.x + bi.x;
-            const float y1 = (float)acc[a][b][1] * sxm[b] * s.y + bi.y;
-            const float y2 = (float)acc[a][b][2] * sxm[b] * s.z + bi.z;
-            const float y3 = (float)acc[a][b][3] * sxm[b] * s.w + bi.w;
+            v4i acc[1][1];       // the tile's sums, with the zero-point term when there is one
+            acc[0][0] = acc_in[a][b];
+            if (ASYM) acc[0][0] += v4i{zcm[b] * cs.x, zcm[b] * cs.y, zcm[b] * cs.z, zcm[b] * cs.w};
+            const float y0 = (float)acc[0][0][0] * sxm[b] * s.x + bi.x;
+            const float y1 = (float)acc[0][0][1] * sxm[b] * s.y + bi.y;
+            const float y2 = (float)acc[0][0][2] * sxm[b] * s.z + bi.z;
+            const float y3 = (float)acc[0][0][3] * sxm[b] * s.w + bi.w;
             uint2 o;
             o.x = pack_bf16x2(y0, y1);
             o.y = pack_bf16x2(y2, y3);
             if (FULL || (n_ok && m < g.M)) {
                 if constexpr (DEBUG) {
-                    int4 d = make_int4(acc[a][b][0], acc[a][b][1], acc[a][b][2], acc[a][b][3]);
+                    int4 d = make_int4(acc[0][0][0], acc[0][0][1], acc[0][0][2], acc[0][0][3]);
                     *reinterpret_cast<int4 *>(g.acc_debug + m * g.N + n) = d;
                 }
                 *reinterpret_cast<uint2 *>(g.Y + m * g.ldy + n) = o;
@@ -136,6 +145,47 @@ __device__ __forceinline__ void epilogue_w8_rows(const v4i (&acc)[TN][TM], const
     }
 }
 
+// Zero-point term of asymmetric activations in the pipelined kernels: the accumulators start at
+// (128 - z_m) * colsum[n] instead of zero, so the loop and the epilogue are those of the symmetric
+// product.  A wave requests its operands (the column sums of its WN channels, 16 bytes per lane,
+// and 128 - z of its WM tokens, 4 bytes per lane) as two direct-to-LDS copies into a private block
+// of kZpBlock bytes BEFORE the first tile copies; copies retire in order, so the wait for the
+// first tile also covers them and the multiplications run while the later tiles are in flight.
+// Lanes beyond the slice repeat its last element.  |colsum| < 2^23 (K < 65536) so that the
+// products are 24-bit multiplies.
+constexpr int kZpBlock = 1024 + 256;
+
+template <int WN, int WM>
+__device__ __forceinline__ void zero_point_request(const GemmArgs &g, int64_t m_wave, int n_wave, int lane,
+                                                   uint32_t lds_block)
+{
+    static_assert(WN / 4 <= 64 && WM <= 64, "one copy per operand");
+    const uint32_t vc = (uint32_t)((lane < WN / 4 ? lane : WN / 4 - 1) * 16);
+    const uint32_t vz = (uint32_t)((lane < WM ? lane : WM - 1) * 4);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(vc), "s"(g.colsum + n_wave), "s"(lds_block) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :: "v"(vz), "s"(g.zc + m_wave), "s"(lds_block + 1024) : "memory");
+}
+
+// `on` == 0: plain zeros (the wave group that does not carry the term)
+template <int TN, int TM>
+__device__ __forceinline__ void zero_point_init(v4i (&acc)[TN][TM], const int8_t *block, int lane, int on)
+{
+    const int l16 = lane & 15, lg = lane >> 4;
+    const int *const b32 = reinterpret_cast<const int *>(block);
+    int zcm[TM];
+#pragma unroll
+    for (int b = 0; b < TM; ++b) zcm[b] = on ? b32[256 + b * 16 + l16] : 0;
+#pragma unroll
+    for (int a = 0; a < TN; ++a) {
+        const int4 c = *reinterpret_cast<const int4 *>(b32 + a * 16 + lg * 4);
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+            acc[a][b] = v4i{__mul24(zcm[b], c.x), __mul24(zcm[b], c.y), __mul24(zcm[b], c.z), __mul24(zcm[b], c.w)};
+    }
+}
+
 // Conditional forms whose branch lives inside the assembly block, so that the caller's loop
 // body stays one basic block for the compiler (`on` / `steady` are wave-uniform).
 __device__ __forceinline__ void dma_1k_if(int on, uint32_t voff, const void *sbase, uint32_t lds_addr)
@@ -158,7 +208,7 @@ __device__ __forceinline__ void wait_vmcnt_or_zero(int steady)
                  :: "s"(__builtin_amdgcn_readfirstlane(steady)), "n"(N) : "memory", "scc");
 }
 
-template <int BM, int BN, int BK, int NS, int WGM, int WGN, bool DEBUG>
+template <int BM, int BN, int BK, int NS, int WGM, int WGN, bool DEBUG, bool ASYM = false>
 __global__ __launch_bounds__(kThreads) void qgemm8_ring_kernel(GemmArgs g)
 {
     static_assert(WGM * WGN == 4, "four waves per workgroup");
@@ -261,7 +311,7 @@ __global__ __launch_bounds__(kThreads) void qgemm8_ring_kernel(GemmArgs g)
         st = (st + 1 == NS) ? 0 : st + 1;
     }
 
-    epilogue_w8<TN, TM, DEBUG, false>(acc, g, m0 + wm * WM + l16, n0 + wn * WN + lg * 4);
+    epilogue_w8<TN, TM, DEBUG, false, ASYM>(acc, g, m0 + wm * WM + l16, n0 + wn * WN + lg * 4);
 }
 
 // ---- software-pipelined kernel ---------------------------------------------------------------
@@ -304,7 +354,7 @@ __device__ __forceinline__ void interleave_hint()
 // step 1; while one feeds the matrix cores the other is being filled.  At the end of tile kt
 // the workgroup waits for tile kt+1, passes the barrier (which also retires every read of
 // tile kt's stage), refills that stage with tile kt+NS and starts reading tile kt+1.
-template <int BM, int BN, int NS, int WGM, int WGN, bool DEBUG>
+template <int BM, int BN, int NS, int WGM, int WGN, bool DEBUG, bool ASYM = false>
 __global__ __launch_bounds__(WGM * WGN * 64) void qgemm8_pipe_kernel(GemmArgs g)
 {
     constexpr int NW = WGM * WGN;                     // waves per workgroup
@@ -383,17 +433,22 @@ __global__ __launch_bounds__(WGM * WGN * 64) void qgemm8_pipe_kernel(GemmArgs g)
     }
 
     v4i acc[TN][TM];
-#pragma unroll
-    for (int a = 0; a < TN; ++a)
-#pragma unroll
-        for (int b = 0; b < TM; ++b) acc[a][b] = v4i{0, 0, 0, 0};
     v4i af0[TN], bf0[TM], af1[TN], bf1[TM];
 
     const int KT = K / BK;
+    if constexpr (ASYM) zero_point_request<WN, WM>(g, m0 + wm * WM, n0 + wn * WN, lane, lds0 + NS * STAGE + wave * kZpBlock);
 #pragma unroll
     for (int t = 0; t < NS; ++t) issue(t < KT, t, t);
     wait_vmcnt_or_zero<(NS - 1) * P>(KT >= NS);
     __syncthreads();
+    if constexpr (ASYM) {
+        zero_point_init<TN, TM>(acc, smem + NS * STAGE + wave * kZpBlock, lane, 1);
+    } else {
+#pragma unroll
+        for (int a = 0; a < TN; ++a)
+#pragma unroll
+            for (int b = 0; b < TM; ++b) acc[a][b] = v4i{0, 0, 0, 0};
+    }
     load_frags<TN, TM, BK>(af0, bf0, smem, woff[0], xoff[0]);
 
     // The loop body is straight-line code (the conditional copy and wait branch inside their
@@ -440,7 +495,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void qgemm8_pipe_kernel(GemmArgs g)
 // independent instruction streams on every SIMD, which overlap each other's copy issue, LDS reads
 // and barriers the way a second resident workgroup would, without a second tile to give it.
 // Needs at least NS k-tiles per group.
-template <int BM, int BN, int NS, int WGM, int WGN, bool DEBUG>
+template <int BM, int BN, int NS, int WGM, int WGN, bool DEBUG, bool ASYM = false>
 __global__ __launch_bounds__(2 * kThreads) void qgemm8_pipe2_kernel(GemmArgs g)
 {
     static_assert(WGM * WGN == 4, "four waves per group");
@@ -522,16 +577,25 @@ __global__ __launch_bounds__(2 * kThreads) void qgemm8_pipe2_kernel(GemmArgs g)
     }
 
     v4i acc[TN][TM];
-#pragma unroll
-    for (int a = 0; a < TN; ++a)
-#pragma unroll
-        for (int b = 0; b < TM; ++b) acc[a][b] = v4i{0, 0, 0, 0};
     v4i af0[TN], bf0[TM], af1[TN], bf1[TM];
 
+    // asymmetric activations: both groups request the operands (same copy counts), the first carries the term
+    const int zblock = 2 * RING + (kg * 4 + wave) * kZpBlock;
+    if constexpr (ASYM)
+        zero_point_request<WN, WM>(g, m0 + wm * WM, n0 + wn * WN, lane,
+                                   (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t *)smem + zblock);
 #pragma unroll
     for (int t = 0; t < NS; ++t) issue(t < KT, t, t);
     wait_vmcnt_or_zero<(NS - 1) * P>(KT >= NS);
     __syncthreads();
+    if constexpr (ASYM) {
+        zero_point_init<TN, TM>(acc, smem + zblock, lane, kg == 0);
+    } else {
+#pragma unroll
+        for (int a = 0; a < TN; ++a)
+#pragma unroll
+            for (int b = 0; b < TM; ++b) acc[a][b] = v4i{0, 0, 0, 0};
+    }
     load_frags<TN, TM, BK>(af0, bf0, ring, woff[0], xoff[0]);
 
     // both groups run the same number of iterations, so they meet at the same barriers
@@ -986,9 +1050,20 @@ hipError_t launch_ring4(const GemmArgs &a, bool debug, hipStream_t st)
     return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st);
 }
 
+// the kernel that takes every shape with asymmetric activations (ring, 128 x 128 x 64, four stages)
+hipError_t launch_ring_asym(const GemmArgs &a, bool debug, hipStream_t st)
+{
+    static bool done[2] = {false, false};
+    constexpr int BM = 128, BN = 128, BK = 64, NS = 4;
+    const size_t smem = (size_t)NS * (BM + BN) * BK;
+    if (debug) return launch_kernel(qgemm8_ring_kernel<BM, BN, BK, NS, 2, 2, true, true>, done[1], a, BM, BN, smem, st);
+    return launch_kernel(qgemm8_ring_kernel<BM, BN, BK, NS, 2, 2, false, true>, done[0], a, BM, BN, smem, st);
+}
+
 template <int BM, int BN, int BK, int NS, int WGM, int WGN>
 hipError_t launch_ring(const GemmArgs &a, bool debug, hipStream_t st)
 {
+    if (a.zc) return launch_ring_asym(a, debug, st);
     static bool done[2] = {false, false};
     const size_t smem = (size_t)NS * (BM + BN) * BK;
     if (debug) return launch_kernel(qgemm8_ring_kernel<BM, BN, BK, NS, WGM, WGN, true>, done[1], a, BM, BN, smem, st);
@@ -1000,9 +1075,19 @@ hipError_t launch_pipe(const GemmArgs &a, bool debug, hipStream_t st)
 {
     // the pipelined kernel takes full tiles only; ragged shapes go to the ring kernel
     if (a.M % BM != 0 || a.N % BN != 0) return launch_ring<128, 128, 64, 4, 2, 2>(a, debug, st);
-    static bool done[2] = {false, false};
+    static bool done[4] = {false, false, false, false};
     constexpr int NW = WGM * WGN;
     const size_t smem = (size_t)NS * (BM * 128 + NW * ((BN / 8 + NW - 1) / NW) * 1024);
+    if (a.zc) {
+        // asymmetric activations: built for the 128 x 144 tiles only; a block of LDS per wave for the zero-point operands
+        if constexpr (BM == 128 && BN == 144 && NW == 4) {
+            const size_t smem_z = smem + NW * kZpBlock;
+            if (debug) return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, true, true>, done[3], a, BM, BN, smem_z, st, NW * 64);
+            return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, false, true>, done[2], a, BM, BN, smem_z, st, NW * 64);
+        } else {
+            return launch_ring_asym(a, debug, st);
+        }
+    }
     if (debug) return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, true>, done[1], a, BM, BN, smem, st, NW * 64);
     return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st, NW * 64);
 }
@@ -1012,8 +1097,8 @@ hipError_t launch_pipe2(const GemmArgs &a, bool debug, hipStream_t st)
 {
     // full tiles and at least NS k-tiles per wave group; else the one-group kernel
     if (a.M % BM != 0 || a.N % BN != 0 || a.K / 256 < NS) return launch_pipe<BM, BN, 2 * NS, WGM, WGN>(a, debug, st);
-    static bool done[2] = {false, false};
-    const size_t smem = (size_t)2 * NS * (BM * 128 + 4 * ((BN / 8 + 3) / 4) * 1024);
+    static bool done[4] = {false, false, false, false};
+    const size_t smem = (size_t)2 * NS * (BM * 128 + 4 * ((BN / 8 + 3) / 4) * 1024) + (a.zc ? 8 * kZpBlock : 0);
     GemmArgs g = a;
     g.tiles_m = (int)(g.M / BM);
     g.tiles_n = g.N / BN;
@@ -1027,6 +1112,10 @@ hipError_t launch_pipe2(const GemmArgs &a, bool debug, hipStream_t st)
         hipLaunchKernelGGL(kern, dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(2 * kThreads), smem, st, g);
         return hipGetLastError();
     };
+    if (a.zc) {
+        if (debug) return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, true, true>, done[3]);
+        return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, false, true>, done[2]);
+    }
     if (debug) return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, true>, done[1]);
     return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, false>, done[0]);
 }
@@ -1058,6 +1147,21 @@ hipError_t launch_persist(const GemmArgs &a, bool debug, hipStream_t st)
 }  // namespace
 
 // int4 weights: 0: 128x128 NS3 (two workgroups per compute unit)   1: 128x128 NS2 (three)
+// asymmetric activations (a.zc, a.colsum set).  kind: 0 ring (any shape); 14, 15, 18: the 128 x 144
+// kernels of the table below (they fall back to the ring kernel for shapes they do not take)
+hipError_t launch_qgemm8_asym(const GemmArgs &a, bool debug, int kind, hipStream_t st)
+{
+    if (!a.zc || !a.colsum || a.K % 128 != 0 || a.N < 4) return hipErrorInvalidValue;
+    if (a.K >= 65536) kind = 0;          // the pipelined kernels multiply column sums as 24-bit values
+    switch (kind) {
+        case 0: return launch_ring_asym(a, debug, st);
+        case 14: return launch_pipe<128, 144, 4, 4, 1>(a, debug, st);
+        case 15: return launch_pipe<128, 144, 2, 4, 1>(a, debug, st);
+        case 18: return launch_pipe2<128, 144, 2, 4, 1>(a, debug, st);
+    }
+    return hipErrorInvalidValue;
+}
+
 int dma4_num_variants() { return 2; }
 
 hipError_t launch_qgemm4_dma(const GemmArgs &a, bool debug, int variant, hipStream_t st)

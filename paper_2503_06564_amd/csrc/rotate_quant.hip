@@ -43,17 +43,21 @@ typedef short v4s __attribute__((ext_vector_type(4)));
 // LDS bytes of the diagonal's pieces: [block][j][piece][g] x 4 bf16 (k = 4g .. 4g+3)
 __host__ __device__ constexpr size_t diag_table_bytes(int nb) { return (size_t)nb * 8 * 3 * 4 * 8; }
 
-template <int SPW, int MAXT>
+// ASYM: the asymmetric quantiser of Eq. 1-3 instead (per-token minimum and maximum, zero point):
+// codes q in 0..255 are stored as q - 128 so that they stay int8 for the matrix instruction, and
+// zc[i] = 128 - z_i is what the product's epilogue needs with the weights' column sums.
+template <int SPW, int MAXT, bool ASYM>
 __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
     const uint16_t *__restrict__ X, int64_t M, int nb, int64_t ldx,
     const float *__restrict__ diag, int8_t *__restrict__ Xq, float *__restrict__ sx,
-    const uint4 *__restrict__ warm, int64_t warm_chunks)
+    int32_t *__restrict__ zc, const uint4 *__restrict__ warm, int64_t warm_chunks)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int K = nb * kBlock;
     const int nw = blockDim.x >> 6;
     const uint2 *const tbl = reinterpret_cast<const uint2 *>(lds_raw);
-    float *const amax_s = reinterpret_cast<float *>(lds_raw + diag_table_bytes(nb));   // [2][nw][16]
+    constexpr int AMW = ASYM ? 32 : 16;              // floats per wave in the exchange buffer
+    float *const amax_s = reinterpret_cast<float *>(lds_raw + diag_table_bytes(nb));   // [2][nw][AMW]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -148,7 +152,7 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
     bool warm_pending = warm_chunks > 0;
     auto issue_warm = [&]() {
         const uint32_t dump = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_raw +
-                              (uint32_t)(diag_table_bytes(nb) + sizeof(float) * 2 * nw * 16);
+                              (uint32_t)(diag_table_bytes(nb) + sizeof(float) * 2 * nw * AMW);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int64_t c0 = ((int64_t)t * gridDim.x + blockIdx.x) * blockDim.x + (wave << 6);   // wave-uniform
@@ -169,7 +173,8 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
         const bool token_ok = token < M;
 
         v4f out[SPW][8];   // out[i][j][q']: element j of chunk (q' < 2 ? 2g + q' : 6 + 2g + q') of block wave + nw*i, token r
-        float amax = 0.0f;
+        float amax = 0.0f;                 // ASYM: the token maximum (>= 0)
+        float amin = 0.0f;                 // ASYM: the token minimum (<= 0)
 #pragma unroll
         for (int i = 0; i < SPW; ++i) {
             const int b = wave + nw * i;
@@ -217,8 +222,15 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     out[i][j] = u[j];
-                    amax = fmaxf(fmaxf(amax, fabsf(u[j][0])), fabsf(u[j][1]));     // two v_max3_f32
-                    amax = fmaxf(fmaxf(amax, fabsf(u[j][2])), fabsf(u[j][3]));
+                    if constexpr (ASYM) {
+                        amax = fmaxf(fmaxf(amax, u[j][0]), u[j][1]);
+                        amax = fmaxf(fmaxf(amax, u[j][2]), u[j][3]);
+                        amin = fminf(fminf(amin, u[j][0]), u[j][1]);
+                        amin = fminf(fminf(amin, u[j][2]), u[j][3]);
+                    } else {
+                        amax = fmaxf(fmaxf(amax, fabsf(u[j][0])), fabsf(u[j][1]));     // two v_max3_f32
+                        amax = fmaxf(fmaxf(amax, fabsf(u[j][2])), fabsf(u[j][3]));
+                    }
                 }
             } else {
                 // ragged last slot: still advance the sequence
@@ -234,15 +246,46 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
         // token absmax: over the four lane-rows of this wave, then over the waves through LDS
         amax = fmaxf(amax, __shfl_xor(amax, 16));
         amax = fmaxf(amax, __shfl_xor(amax, 32));
-        float *const am = amax_s + parity * nw * 16;
-        if (g == 0) am[wave * 16 + r] = amax;
+        float *const am = amax_s + parity * nw * AMW;
+        if (g == 0) am[wave * AMW + r] = amax;
+        if constexpr (ASYM) {
+            amin = fminf(amin, __shfl_xor(amin, 16));
+            amin = fminf(amin, __shfl_xor(amin, 32));
+            if (g == 0) am[wave * AMW + 16 + r] = amin;
+        }
         __syncthreads();
-        for (int wv = 0; wv < nw; ++wv) amax = fmaxf(amax, am[wv * 16 + r]);
+        for (int wv = 0; wv < nw; ++wv) amax = fmaxf(amax, am[wv * AMW + r]);
+        if constexpr (ASYM)
+            for (int wv = 0; wv < nw; ++wv) amin = fminf(amin, am[wv * AMW + 16 + r]);
         parity ^= 1;   // the next group writes the other buffer, so one barrier per group suffices
 
-        // out holds sqrt(128) * V.  s_x = max|V| / 127; codes = rint(V / s_x) = rint(out * 127 / max|out|).
-        const float inv = amax > 0.0f ? 127.0f / amax : 0.0f;
-        if (wave == 0 && g == 0 && token_ok) sx[token] = amax * (0.08838834764831845f / 127.0f);
+        // out holds sqrt(128) * V.  Symmetric: s_x = max|V| / 127, codes = rint(V / s_x) =
+        // rint(out * 127 / max|out|).  Asymmetric (range [lo, hi] with lo <= 0 <= hi): s_x = (hi - lo) / 255,
+        // z = -rint(lo / s_x), stored code = clamp(rint(V / s_x) + z, 0, 255) - 128; the integer offset
+        // rides in the rounding constant of the same FMA.
+        float inv, magic = kRoundMagic;
+        if constexpr (ASYM) {
+            const float range = amax - amin;
+            inv = range > 0.0f ? 255.0f / range : 0.0f;
+            const float z = -rintf(amin * inv);                       // 0 .. 255
+            magic = kRoundMagic + (z - 128.0f);
+            if (wave == 0 && g == 0 && token_ok) {
+                sx[token] = range * (0.08838834764831845f / 255.0f);
+                zc[token] = 128 - (int)z;
+            }
+        } else {
+            inv = amax > 0.0f ? 127.0f / amax : 0.0f;
+            if (wave == 0 && g == 0 && token_ok) sx[token] = amax * (0.08838834764831845f / 127.0f);
+        }
+        // rounded value + offset, clamped to the int8 range, as the low byte of the float's bits
+        auto code_bits = [&](float v) -> uint32_t {
+            if constexpr (ASYM) {
+                const float t = __builtin_fmaf(v, inv, magic);
+                return __float_as_uint(__builtin_amdgcn_fmed3f(t, kRoundMagic - 128.0f, kRoundMagic + 127.0f));
+            } else {
+                return quant_bits(v, inv);
+            }
+        };
 
 #pragma unroll
         for (int i = 0; i < SPW; ++i) {
@@ -251,10 +294,10 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
                 uint32_t c[8];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    c[2 * q] = pack4_low_bytes(quant_bits(out[i][0][q], inv), quant_bits(out[i][1][q], inv),
-                                               quant_bits(out[i][2][q], inv), quant_bits(out[i][3][q], inv));
-                    c[2 * q + 1] = pack4_low_bytes(quant_bits(out[i][4][q], inv), quant_bits(out[i][5][q], inv),
-                                                   quant_bits(out[i][6][q], inv), quant_bits(out[i][7][q], inv));
+                    c[2 * q] = pack4_low_bytes(code_bits(out[i][0][q]), code_bits(out[i][1][q]),
+                                               code_bits(out[i][2][q]), code_bits(out[i][3][q]));
+                    c[2 * q + 1] = pack4_low_bytes(code_bits(out[i][4][q]), code_bits(out[i][5][q]),
+                                                   code_bits(out[i][6][q]), code_bits(out[i][7][q]));
                 }
                 int8_t *dst = Xq + token * (int64_t)K + b * kBlock + g * 16;
                 *reinterpret_cast<uint4 *>(dst) = make_uint4(c[0], c[1], c[2], c[3]);
@@ -275,16 +318,21 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
 
 template <int SPW, int MAXT>
 hipError_t launch_spw(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx, const float *diag,
-                      int8_t *Xq, float *sx, const void *warm, int64_t warm_bytes, int wgs_per_cu, hipStream_t st)
+                      int8_t *Xq, float *sx, int32_t *zc, const void *warm, int64_t warm_bytes, int wgs_per_cu,
+                      hipStream_t st)
 {
     // persistent workgroups: a few per compute unit, each walking token groups
     const int64_t groups = (M + kTokensPerWG - 1) / kTokensPerWG;
     int64_t grid = (int64_t)256 * wgs_per_cu;
     if (grid > groups) grid = groups;
-    const size_t smem = diag_table_bytes(nb) + sizeof(float) * (size_t)2 * nw * 16 + 1024;   // table, maxima, dump area
-    hipLaunchKernelGGL((rotate_quant_kernel<SPW, MAXT>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
-                       X, M, nb, ldx, diag, Xq, sx, static_cast<const uint4 *>(warm),
-                       (warm && warm_bytes < ((int64_t)1 << 32)) ? warm_bytes / 16 : 0);   // 32-bit byte offsets in the copy
+    const size_t smem = diag_table_bytes(nb) + sizeof(float) * (size_t)2 * nw * (zc ? 32 : 16) + 1024;   // table, extrema, dump area
+    const int64_t warm_chunks = (warm && warm_bytes < ((int64_t)1 << 32)) ? warm_bytes / 16 : 0;   // 32-bit byte offsets in the copy
+    if (zc)
+        hipLaunchKernelGGL((rotate_quant_kernel<SPW, MAXT, true>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
+                           X, M, nb, ldx, diag, Xq, sx, zc, static_cast<const uint4 *>(warm), warm_chunks);
+    else
+        hipLaunchKernelGGL((rotate_quant_kernel<SPW, MAXT, false>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
+                           X, M, nb, ldx, diag, Xq, sx, zc, static_cast<const uint4 *>(warm), warm_chunks);
     return hipGetLastError();
 }
 
@@ -295,11 +343,11 @@ hipError_t launch_spw(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx,
 constexpr int kRQMaxBlocks = 36;
 
 hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
-                               int8_t *Xq, float *sx, const void *warm, int64_t warm_bytes, hipStream_t st)
+                               int8_t *Xq, float *sx, int32_t *zc, const void *warm, int64_t warm_bytes, hipStream_t st)
 {
     if (M == 0) return hipSuccess;
     const int nb = K / kBlock;
-    if (nb > kRQMaxBlocks) return launch_rotate_quant_wide(X, M, K, ldx, diag, Xq, sx, st);
+    if (nb > kRQMaxBlocks) return zc ? hipErrorInvalidValue : launch_rotate_quant_wide(X, M, K, ldx, diag, Xq, sx, st);
     // three blocks per wave (two or one for narrow rows), then rebalance; workgroups of up to
     // 12 waves, as many per compute unit as stay resident (with three blocks per wave the kernel
     // holds 166 registers and small workgroups pack two waves per SIMD, eight per compute unit)
@@ -314,12 +362,12 @@ hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx,
     const int wgs = resident / nw > 0 ? resident / nw : 1;
     const bool small = nw <= 4;      // up to 256 threads: no register cap from co-residency
     switch (spw) {
-        case 1: return small ? launch_spw<1, 256>(X, M, nb, nw, ldx, diag, Xq, sx, warm, warm_bytes, wgs, st)
-                             : launch_spw<1, 768>(X, M, nb, nw, ldx, diag, Xq, sx, warm, warm_bytes, wgs, st);
-        case 2: return small ? launch_spw<2, 256>(X, M, nb, nw, ldx, diag, Xq, sx, warm, warm_bytes, wgs, st)
-                             : launch_spw<2, 768>(X, M, nb, nw, ldx, diag, Xq, sx, warm, warm_bytes, wgs, st);
-        default: return small ? launch_spw<3, 256>(X, M, nb, nw, ldx, diag, Xq, sx, warm, warm_bytes, wgs, st)
-                              : launch_spw<3, 768>(X, M, nb, nw, ldx, diag, Xq, sx, warm, warm_bytes, wgs, st);
+        case 1: return small ? launch_spw<1, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st)
+                             : launch_spw<1, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st);
+        case 2: return small ? launch_spw<2, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st)
+                             : launch_spw<2, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st);
+        default: return small ? launch_spw<3, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st)
+                              : launch_spw<3, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st);
     }
 }
 

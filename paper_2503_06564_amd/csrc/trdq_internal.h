@@ -20,6 +20,7 @@ struct Weights {
     int K = 0, N = 0, wbits = 0;
     void *codes = nullptr;
     float *scales = nullptr;
+    int32_t *colsum = nullptr;   // int8 weights: sum over k of the codes of every output channel [N]
     int device = 0;
 };
 
@@ -31,8 +32,9 @@ struct Table {
 // Kernel launchers (defined in the .hip files).  All return hipError_t of the launch.
 // warm / warm_bytes: optional device range (16-byte aligned, a multiple of 16 bytes) that the
 // kernel reads once and discards, to pull it into the memory-side cache for the next kernel.
+// zc: null (symmetric quantiser), or where the asymmetric quantiser writes 128 - z_i per token.
 hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
-                               int8_t *Xq, float *sx, const void *warm, int64_t warm_bytes, hipStream_t st);
+                               int8_t *Xq, float *sx, int32_t *zc, const void *warm, int64_t warm_bytes, hipStream_t st);
 hipError_t launch_rotate_quant_wide(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
                                     int8_t *Xq, float *sx, hipStream_t st);
 
@@ -56,7 +58,10 @@ hipError_t launch_weight_row_absmax(const float *W, int K, int N, float *wmax, h
 hipError_t launch_smooth_diag(const float *xmax, const float *wmax, int K, float alpha, float *d, hipStream_t st);
 
 int qgemm_num_variants();
-hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, int64_t M,
+// colsum[n] = sum_k codes[n][k] for int8 codes stored [N][K]
+hipError_t launch_weight_colsum(const void *codes, int K, int N, int32_t *colsum, hipStream_t st);
+// zc: null, or the per-token zero-point terms of asymmetric activations (int8 weights only)
+hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, const int32_t *zc, int64_t M,
                         const float *bias, uint16_t *Y, int64_t ldy, int32_t *acc_debug,
                         int variant, hipStream_t st);
 

@@ -23,6 +23,7 @@ SYMBOLS = [
     "trdq_layer_destroy", "trdq_qgemm_set_variant", "trdq_qgemm_num_variants",
     "trdq_zigzag_permutation", "trdq_prepare_weights_rpr", "trdq_rotate_quant_rpr",
     "trdq_channel_absmax", "trdq_weight_row_absmax", "trdq_smooth_diag",
+    "trdq_rotate_quant_asym", "trdq_qgemm_asym",
 ]
 
 _lib = None
@@ -71,6 +72,8 @@ def lib():
         L.trdq_layer_destroy.restype = None
         L.trdq_qgemm_set_variant.argtypes = [i32]
         L.trdq_zigzag_permutation.argtypes = [p, i32, i32, p]
+        L.trdq_rotate_quant_asym.argtypes = [p, i64, i32, i64, p, i32, p, p, p, p, p]
+        L.trdq_qgemm_asym.argtypes = [p, p, p, p, i64, p, p, i64, p, p]
         L.trdq_channel_absmax.argtypes = [p, i64, i32, i64, p, i32, i32, p, p]
         L.trdq_weight_row_absmax.argtypes = [p, i32, i32, p, p]
         L.trdq_smooth_diag.argtypes = [p, p, i32, C.c_float, p, p]
@@ -257,6 +260,22 @@ def rotate_quant(X, diag, Xq, sx, block=BLOCK, stream=None, warm=None):
                                             _stream(stream)), "trdq_rotate_quant_warm")
 
 
+def rotate_quant_asym(X, diag, Xq, sx, zc, block=BLOCK, stream=None, warm=None):
+    """Asymmetric per-token quantiser (Eq. 1-3): Xq int8 [M, K] holds q - 128, zc int32 [M] holds 128 - z."""
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    _check(lib().trdq_rotate_quant_asym(_ptr(X), M, K, ldx, _ptr(diag), block, _ptr(Xq), _ptr(sx), _ptr(zc),
+                                        warm.handle if warm is not None else None, _stream(stream)),
+           "trdq_rotate_quant_asym")
+
+
+def qgemm_asym(w, Xq, sx, zc, Y, bias=None, acc_debug=None, stream=None):
+    M = Xq.shape[0]
+    ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
+    _check(lib().trdq_qgemm_asym(w.handle, _ptr(Xq), _ptr(sx), _ptr(zc), M, _ptr(bias), _ptr(Y), ldy,
+                                 _ptr(acc_debug), _stream(stream)), "trdq_qgemm_asym")
+
+
 def qgemm(w, Xq, sx, Y, bias=None, acc_debug=None, stream=None):
     M = Xq.shape[0]
     ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
@@ -303,6 +322,36 @@ def bind_rotate_quant_rpr(X, diag, perm, Xq, sx, block=BLOCK, stream=None, warm=
         st = f(*args)
         if st != OK:
             raise TrdqError(st, "trdq_rotate_quant_rpr")
+    return call
+
+
+def bind_rotate_quant_asym(X, diag, Xq, sx, zc, block=BLOCK, stream=None, warm=None):
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    f = lib().trdq_rotate_quant_asym
+    args = (C.c_void_p(_ptr(X)), C.c_int64(M), C.c_int(K), C.c_int64(ldx), C.c_void_p(_ptr(diag)), C.c_int(block),
+            C.c_void_p(_ptr(Xq)), C.c_void_p(_ptr(sx)), C.c_void_p(_ptr(zc)),
+            warm.handle if warm is not None else C.c_void_p(None), C.c_void_p(_stream(stream)))
+
+    def call():
+        st = f(*args)
+        if st != OK:
+            raise TrdqError(st, "trdq_rotate_quant_asym")
+    return call
+
+
+def bind_qgemm_asym(w, Xq, sx, zc, Y, bias=None, acc_debug=None, stream=None):
+    M = Xq.shape[0]
+    ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
+    f = lib().trdq_qgemm_asym
+    args = (w.handle, C.c_void_p(_ptr(Xq)), C.c_void_p(_ptr(sx)), C.c_void_p(_ptr(zc)), C.c_int64(M),
+            C.c_void_p(_ptr(bias)), C.c_void_p(_ptr(Y)), C.c_int64(ldy), C.c_void_p(_ptr(acc_debug)),
+            C.c_void_p(_stream(stream)))
+
+    def call():
+        st = f(*args)
+        if st != OK:
+            raise TrdqError(st, "trdq_qgemm_asym")
     return call
 
 

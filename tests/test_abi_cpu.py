@@ -186,3 +186,12 @@ def test_calibration_argument_errors_before_any_gpu_call():
     assert L.trdq_smooth_diag(0x1000, 0x1000, 0, 0.5, 0x2000, None) == trdq.ERR_SHAPE
     assert L.trdq_smooth_diag(0x1000, 0x1000, 256, 1.5, 0x2000, None) == trdq.ERR_RANGE
     assert L.trdq_smooth_diag(0x1000, 0x1000, 256, float("nan"), 0x2000, None) == trdq.ERR_RANGE
+
+
+def test_asym_argument_errors_before_any_gpu_call():
+    L = trdq.lib()
+    assert L.trdq_rotate_quant_asym(0x1000, 4, 256, 256, None, 128, 0x2000, 0x3000, None, None, None) == trdq.ERR_NULL
+    assert L.trdq_rotate_quant_asym(0x1000, 4, 200, 256, None, 128, 0x2000, 0x3000, 0x4000, None, None) == trdq.ERR_SHAPE
+    assert L.trdq_rotate_quant_asym(0x1000, 4, 128 * 37, 128 * 37, None, 128, 0x2000, 0x3000, 0x4000, None, None) == trdq.ERR_UNSUPPORTED
+    assert L.trdq_rotate_quant_asym(0x1000, 0, 256, 256, None, 128, None, None, None, None, None) == trdq.OK
+    assert L.trdq_qgemm_asym(None, 0x1000, 0x2000, 0x3000, 4, None, 0x4000, 64, None, None) == trdq.ERR_NULL
