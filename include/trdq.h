@@ -250,8 +250,10 @@ trdq_status trdq_layer_set_group(trdq_layer *l, int g, const float *diag_dev, co
                                  void *stream);
 
 /* Forward at sampling step `step`: looks up the group, then runs either the fused kernel
- * (fused != 0) or rotate_quant + qgemm through the caller's workspace:
- * Xq_ws_dev int8 [M, K] and sx_ws_dev float32 [M] (both may be NULL when fused != 0).
+ * (fused > 0) or rotate_quant + qgemm through the caller's workspace (fused == 0):
+ * Xq_ws_dev int8 [M, K] and sx_ws_dev float32 [M] (both may be NULL when fused > 0).
+ * fused < 0 chooses: the fused kernel where it is the faster path (few tokens: one round of
+ * 16-token workgroups, int8 weights, K <= 1536), else the pair, which needs the workspace.
  * X_dev bf16 [M, K] dense; Y_dev bf16 [M, N] dense.
  * Errors: step outside the table -> ERR_RANGE; group not set -> ERR_MISMATCH. */
 trdq_status trdq_layer_forward(const trdq_layer *l, int step, const void *X_dev, int64_t M,

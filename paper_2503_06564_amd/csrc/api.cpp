@@ -518,7 +518,7 @@ trdq_status trdq_layer_forward(const trdq_layer *l, int step, const void *X_dev,
     if (!l->set[(size_t)g]) return TRDQ_ERR_MISMATCH;
     const trdq_weights *w = l->w[(size_t)g];
     const float *d = l->diag[(size_t)g];
-    if (fused)
+    if (fused > 0 || (fused < 0 && trdq::fused_pays(M, l->K, l->N, l->wbits)))
         return trdq_linear_fused(X_dev, M, l->K, d, w, bias_dev, Y_dev, l->N, stream);
     if (!Xq_ws_dev || !sx_ws_dev) return TRDQ_ERR_NULL;
     trdq_status rc = trdq_rotate_quant_warm(X_dev, M, l->K, l->K, d, trdq::kBlock, Xq_ws_dev, sx_ws_dev, w, stream);

@@ -6,6 +6,8 @@
 // of the output channels with the same matrix-core loop as qgemm, streaming weight tiles
 // through a double-buffered LDS stage.  The 160 KB of LDS per compute unit bound BM * K; the
 // panel height shrinks as K grows (64 tokens up to K = 1536, 32 up to 3072, 16 up to 6144).
+#include <type_traits>
+
 #include "rotate_core.h"
 
 namespace trdq {
@@ -16,6 +18,7 @@ constexpr int kThreads = 256;
 constexpr int kPad = 16;
 constexpr int kBN = 128;   // output channels per weight tile
 constexpr int kBK = 128;   // input channels per weight tile = one rotation block / scale group
+constexpr int64_t kSmallMaxWorkgroups = 512;    // few-token kernel: at most two rounds of workgroups
 
 struct FusedArgs {
     const uint16_t *X;     // bf16 [M, ldx]
@@ -227,6 +230,205 @@ __global__ __launch_bounds__(kThreads) void linear_fused_kernel(FusedArgs g)
     }
 }
 
+// ---- few tokens: one 16-token panel per workgroup, K split over eight waves ---------------------
+// With a few hundred tokens the unfused pair is bound by two launches and two chains of memory
+// latency, not by arithmetic.  Here a workgroup of eight waves owns 16 tokens and BN = 16 * TN
+// output channels.  Every weight byte of its slab meets exactly one matrix instruction (there is
+// one token tile), so staging weights in LDS would buy nothing: wave w loads the fragments of
+// its k-steps (64 input channels each; steps w, w + 8, w + 16) straight from global memory into
+// registers, all of them up front, right after the loads of the activations, so that they are
+// in flight while the panel is rotated and quantised into LDS.  Then each wave multiplies its
+// k-steps, the eight partial sums meet in LDS, and wave w finishes channel tiles w and w + 8.
+// K <= 1536 (three k-steps per wave, 108 fragment registers), int8 weights.
+constexpr int kSmallThreads = 512;
+constexpr int kSmallSteps = 3;
+
+template <int TN, int T>
+__global__ __launch_bounds__(kSmallThreads) void linear_fused_small_kernel(FusedArgs g)
+{
+    constexpr int BN = TN * 16;
+    extern __shared__ __align__(16) int8_t smem[];
+    const int K = g.K;
+    const int nb = K / kBlock;
+    const int LDX = K + kPad;
+    int8_t *const Xp = smem;                                              // [16][K + 16] int8 panel
+    float *const sxs = reinterpret_cast<float *>(smem + 16 * LDX);       // [16]
+    v4i *const part = reinterpret_cast<v4i *>(smem + 16 * LDX + 64);     // [8][TN][64] partial sums
+    float *const dl = reinterpret_cast<float *>(part);                   // [K] diagonal (before the sums need the space)
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, lg = lane >> 4;
+    const int tile = blockIdx.x % g.tiles_n, panel = blockIdx.x / g.tiles_n;
+    const int64_t m0 = (int64_t)panel * 16;
+    const int n0 = tile * BN;
+    const int KS = K / 64;
+
+    // Loads return in order, so the order of issue is the order of need: the diagonal (one 16-byte
+    // piece per thread, shared through LDS), the activations, then the weight fragments.
+    float4 dpiece = make_float4(1.f, 1.f, 1.f, 1.f);
+    if (g.diag && tid * 4 < K) dpiece = *reinterpret_cast<const float4 *>(g.diag + tid * 4);
+    const int r = wave * 2 + (lg >> 1), s = lg & 1;     // token of this lane row, and which half of its blocks
+    const int64_t token = m0 + r;
+    const bool tok_ok = token < g.M;
+    uint4 raw[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const int b = t * 2 + s;
+        raw[t] = make_uint4(0, 0, 0, 0);
+        if (tok_ok && b < nb)
+            raw[t] = *reinterpret_cast<const uint4 *>(g.X + token * g.ldx + (int64_t)b * kBlock + l16 * 8);
+    }
+
+    // this wave's weight fragments: channel n0 + 16a + l16, input channels 64 * step + 16 * lg .. + 15
+    v4i wf[kSmallSteps][TN];
+    auto load_w = [&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        const int step = wave + 8 * i;
+        if (step < KS) {
+#pragma unroll
+            for (int a = 0; a < TN; ++a) {
+                int n = n0 + a * 16 + l16;
+                if (n >= g.N) n = g.N - 1;
+                wf[i][a] = *reinterpret_cast<const v4i *>(static_cast<const int8_t *>(g.Wc) + (size_t)n * K + step * 64 + lg * 16);
+            }
+        } else {
+#pragma unroll
+            for (int a = 0; a < TN; ++a) wf[i][a] = v4i{0, 0, 0, 0};
+        }
+    };
+    load_w(std::integral_constant<int, 0>{});
+    load_w(std::integral_constant<int, 1>{});
+    if (tid * 4 < K) *reinterpret_cast<float4 *>(dl + tid * 4) = dpiece;
+    __syncthreads();
+
+    // rotate and quantise the panel into LDS
+    {
+        const LaneSigns sg(l16);
+        float v[T][8];
+        float amax = 0.0f;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int b = t * 2 + s < nb ? t * 2 + s : nb - 1;
+            const float4 d0 = *reinterpret_cast<const float4 *>(dl + b * kBlock + l16 * 8);
+            const float4 d1 = *reinterpret_cast<const float4 *>(dl + b * kBlock + l16 * 8 + 4);
+            v[t][0] = bf16_lo(raw[t].x) * d0.x;
+            v[t][1] = bf16_hi(raw[t].x) * d0.y;
+            v[t][2] = bf16_lo(raw[t].y) * d0.z;
+            v[t][3] = bf16_hi(raw[t].y) * d0.w;
+            v[t][4] = bf16_lo(raw[t].z) * d1.x;
+            v[t][5] = bf16_hi(raw[t].z) * d1.y;
+            v[t][6] = bf16_lo(raw[t].w) * d1.z;
+            v[t][7] = bf16_hi(raw[t].w) * d1.w;
+            fwht128_rows16(v[t], sg);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(v[t][j]));
+            if (t == 0) {
+                // the last k-step's fragments go out once the first block is done (the queue has drained by then)
+                __builtin_amdgcn_sched_barrier(0);
+                load_w(std::integral_constant<int, 2>{});
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        amax = row16_max(amax);
+        amax = fmaxf(amax, __shfl_xor(amax, 16));
+        const float inv = token_inv_scale(amax);
+        if (s == 0 && l16 == 0) sxs[r] = tok_ok ? token_scale(amax) : 0.0f;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int b = t * 2 + s;
+            if (b < nb) *reinterpret_cast<uint2 *>(Xp + r * LDX + b * kBlock + l16 * 8) = quant_pack8(v[t], inv);
+        }
+    }
+    __syncthreads();        // panel and scales published; every wave is done with the diagonal
+
+    v4i acc[TN];
+#pragma unroll
+    for (int a = 0; a < TN; ++a) acc[a] = v4i{0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < kSmallSteps; ++i) {
+        const int step = wave + 8 * i;
+        if (step < KS) {
+            const v4i xf = *reinterpret_cast<const v4i *>(Xp + l16 * LDX + step * 64 + lg * 16);
+#pragma unroll
+            for (int a = 0; a < TN; ++a)
+                acc[a] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[i][a], xf, acc[a], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int a = 0; a < TN; ++a) part[(wave * TN + a) * 64 + lane] = acc[a];
+    __syncthreads();
+
+    // wave w finishes channel tiles w, w + 8: lane holds channels n .. n + 3 of token m0 + l16
+    for (int a = wave; a < TN; a += 8) {
+        v4i sum = part[a * 64 + lane];
+#pragma unroll
+        for (int w = 1; w < 8; ++w) sum += part[(w * TN + a) * 64 + lane];
+        const int n = n0 + a * 16 + lg * 4;
+        const int64_t m = m0 + l16;
+        if (n < g.N && m < g.M) {
+            const float4 sw = *reinterpret_cast<const float4 *>(g.sw + n);
+            float4 bi = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (g.bias) bi = *reinterpret_cast<const float4 *>(g.bias + n);
+            const float sxm = sxs[l16];
+            uint2 o;
+            o.x = pack_bf16x2((float)sum[0] * sxm * sw.x + bi.x, (float)sum[1] * sxm * sw.y + bi.y);
+            o.y = pack_bf16x2((float)sum[2] * sxm * sw.z + bi.z, (float)sum[3] * sxm * sw.w + bi.w);
+            *reinterpret_cast<uint2 *>(g.Y + m * g.ldy + n) = o;
+        }
+    }
+}
+
+template <int TN, int T>
+hipError_t launch_small(const FusedArgs &a, hipStream_t st)
+{
+    FusedArgs g = a;
+    const int64_t panels = (g.M + 15) / 16;
+    g.tiles_n = (g.N + TN * 16 - 1) / (TN * 16);
+    const size_t smem = (size_t)16 * (g.K + kPad) + 64 + (size_t)8 * TN * 1024;
+    auto kern = linear_fused_small_kernel<TN, T>;
+    static size_t attr_smem = 0;
+    if (smem > attr_smem) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_smem = smem;
+    }
+    // consecutive workgroups take the channel tiles of one panel: with eight tiles (1152 = 8 x 144)
+    // each of the eight dies keeps seeing the same weight slab
+    hipLaunchKernelGGL(kern, dim3((unsigned)(panels * g.tiles_n)), dim3(kSmallThreads), smem, st, g);
+    return hipGetLastError();
+}
+
+// few-token kernel: int8 weights, K <= 1536, and few enough workgroups that repeating the
+// rotation per channel tile costs less than a second launch
+bool small_applies(const FusedArgs &a, int wbits)
+{
+    if (wbits != 8 || a.K > 1536) return false;
+    const int bn = a.N % 144 == 0 ? 144 : 128;
+    const int64_t wgs = ((a.M + 15) / 16) * ((a.N + bn - 1) / bn);
+    return wgs <= kSmallMaxWorkgroups;
+}
+
+template <int TN>
+hipError_t launch_small_tn(const FusedArgs &a, hipStream_t st)
+{
+    switch ((a.K / kBlock + 1) / 2) {       // blocks per lane row (two lane rows share a token)
+        case 1: return launch_small<TN, 1>(a, st);
+        case 2: return launch_small<TN, 2>(a, st);
+        case 3: return launch_small<TN, 3>(a, st);
+        case 4: return launch_small<TN, 4>(a, st);
+        case 5: return launch_small<TN, 5>(a, st);
+        default: return launch_small<TN, 6>(a, st);
+    }
+}
+
+hipError_t launch_small_any(const FusedArgs &a, hipStream_t st)
+{
+    return a.N % 144 == 0 ? launch_small_tn<9>(a, st) : launch_small_tn<8>(a, st);
+}
+
 template <int BM, int T, int S, bool W4>
 hipError_t launch_one(const FusedArgs &a, hipStream_t st)
 {
@@ -273,6 +475,15 @@ hipError_t launch_w(const FusedArgs &a, hipStream_t st)
 
 bool fused_supports(int K) { return K % kBlock == 0 && K / kBlock <= 48; }
 
+// True where the fused kernel is the faster path: the few-token kernel in a single round of
+// workgroups (measured on 1152-wide layers: 10-11.5 us against 14-15 us for the pair up to 512 tokens).
+bool fused_pays(int64_t M, int K, int N, int wbits)
+{
+    if (wbits != 8 || K > 1536 || K % kBlock != 0 || M <= 0) return false;
+    const int bn = N % 144 == 0 ? 144 : 128;
+    return ((M + 15) / 16) * ((N + bn - 1) / bn) <= 256;
+}
+
 hipError_t launch_linear_fused(const Weights &w, const uint16_t *X, int64_t M, int64_t ldx,
                                const float *diag, const float *bias, uint16_t *Y, int64_t ldy,
                                hipStream_t st)
@@ -281,6 +492,7 @@ hipError_t launch_linear_fused(const Weights &w, const uint16_t *X, int64_t M, i
     FusedArgs a;
     a.X = X; a.diag = diag; a.Wc = w.codes; a.sw = w.scales; a.bias = bias; a.Y = Y;
     a.M = M; a.ldx = ldx; a.ldy = ldy; a.K = w.K; a.N = w.N; a.tiles_n = 0; a.nsplit = 1;
+    if (small_applies(a, w.wbits)) return launch_small_any(a, st);
     return w.wbits == 4 ? launch_w<true>(a, st) : launch_w<false>(a, st);
 }
 

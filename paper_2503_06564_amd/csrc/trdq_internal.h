@@ -66,6 +66,7 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, con
                         int variant, hipStream_t st);
 
 bool fused_supports(int K);
+bool fused_pays(int64_t M, int K, int N, int wbits);
 hipError_t launch_linear_fused(const Weights &w, const uint16_t *X, int64_t M, int64_t ldx,
                                const float *diag, const float *bias, uint16_t *Y, int64_t ldy,
                                hipStream_t st);

@@ -406,8 +406,10 @@ class Layer:
                "trdq_layer_set_group")
 
     def forward(self, step, X, Y, bias=None, fused=False, Xq_ws=None, sx_ws=None, stream=None):
+        """fused: True / False, or None to let the library choose (fused for few tokens)."""
         _check(lib().trdq_layer_forward(self.handle, step, _ptr(X), X.shape[0], _ptr(bias), _ptr(Y),
-                                        1 if fused else 0, _ptr(Xq_ws), _ptr(sx_ws), _stream(stream)),
+                                        -1 if fused is None else (1 if fused else 0), _ptr(Xq_ws), _ptr(sx_ws),
+                                        _stream(stream)),
                "trdq_layer_forward")
 
     def weights(self, g):

@@ -249,6 +249,53 @@ def test_fused_matches_unfused_and_oracle(oracle, M, K, N, wbits):
     w.close()
 
 
+@pytest.mark.parametrize("K", [128, 256, 384, 640, 896, 1152, 1408, 1536])
+@pytest.mark.parametrize("M,N", [(40, 144), (512, 288), (19, 160)])
+def test_fused_few_token_kernel(oracle, M, K, N):
+    """The 16-token-panel kernel (int8 weights, K <= 1536): every count of blocks per lane row,
+    144- and 128-channel tiles, ragged token and channel counts."""
+    say(f"fused few tokens M={M} K={K} N={N}")
+    Xb, W, d, bias = wl.small_case(31, M, K, N, n_outliers=max(1, K // 144), outlier=40.0)
+    w = trdq.prepare_weights(gu.f32_to_dev(W), gu.f32_to_dev(d), wbits=8)
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    trdq.linear_fused(gu.bf16_to_dev(Xb), gu.f32_to_dev(d), w, Y, bias=gu.f32_to_dev(bias))
+    torch.cuda.synchronize()
+    ref = oracle.linear(Xb, W, d, bias, wbits=8, exact_blas=True)
+    gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], "Y fused (few tokens)")
+    # no diagonal: the kernel fills ones itself
+    w1 = trdq.prepare_weights(gu.f32_to_dev(W), None, wbits=8)
+    trdq.linear_fused(gu.bf16_to_dev(Xb), None, w1, Y)
+    torch.cuda.synchronize()
+    ref1 = oracle.linear(Xb, W, None, None, wbits=8, exact_blas=True)
+    gu.assert_y_close(gu.bf16_to_host(Y), ref1["Y"], "Y fused (few tokens, no diagonal, no bias)")
+    w.close(); w1.close()
+
+
+def test_layer_chooses_fused_for_few_tokens(oracle):
+    """fused=None: few tokens take the fused kernel (no workspace needed), many take the pair."""
+    K, N = 256, 288
+    table = trdq.Table(4, 1)
+    layer = trdq.Layer(table, K, N, 8)
+    Xb, W, d, bias = wl.small_case(13, 4096, K, N)
+    layer.set_group(0, gu.f32_to_dev(d), gu.f32_to_dev(W))
+    for M, needs_ws in ((64, False), (4096, True)):
+        X = gu.bf16_to_dev(Xb[:M])
+        Y = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+        if needs_ws:
+            with pytest.raises(trdq.TrdqError) as e:
+                layer.forward(1, X, Y, fused=None)
+            assert e.value.status == trdq.ERR_NULL
+            Xq_ws = torch.empty((M, K), dtype=torch.int8, device="cuda")
+            sx_ws = torch.empty((M,), dtype=torch.float32, device="cuda")
+            layer.forward(1, X, Y, bias=gu.f32_to_dev(bias), fused=None, Xq_ws=Xq_ws, sx_ws=sx_ws)
+        else:
+            layer.forward(1, X, Y, bias=gu.f32_to_dev(bias), fused=None)
+        torch.cuda.synchronize()
+        ref = oracle.linear(Xb[:M], W, d, bias, wbits=8)
+        gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], f"layer, library's choice, M={M}")
+    layer.close()
+
+
 def test_fused_rejects_wide_k():
     _, W, _, _ = wl.small_case(1, 1, 128 * 49, 16)
     w = trdq.prepare_weights(gu.f32_to_dev(W), None, wbits=8)
