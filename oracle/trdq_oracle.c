@@ -180,6 +180,33 @@ int trdq_oracle_quant_tokens(const double *V, int64_t M, int K, int8_t *Xq, doub
     return 0;
 }
 
+/* The same symmetric per-token quantiser at another bit-width b (Eq. 1-2 symmetric; the paper also
+ * reports W6A6, Table 3): codes in [-(2^(b-1) - 1), 2^(b-1) - 1], s_x[i] = a_i / (2^(b-1) - 1).
+ * Codes are stored one per int8.  2 <= b <= 8. */
+int trdq_oracle_quant_tokens_bits(const double *V, int64_t M, int K, int bits, int8_t *Xq, double *sx)
+{
+    if (!V || !Xq || !sx || M < 0 || K <= 0 || bits < 2 || bits > 8) return 1;
+    const double qmax = (double)((1 << (bits - 1)) - 1);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        const double *v = V + i * (int64_t)K;
+        double a = 0.0;
+        for (int k = 0; k < K; ++k) { double t = fabs(v[k]); if (t > a) a = t; }
+        double s = a / qmax;
+        sx[i] = (a == 0.0) ? 0.0 : s;
+        for (int k = 0; k < K; ++k) {
+            double q = 0.0;
+            if (a != 0.0) {
+                q = rint(v[k] / s);
+                if (q > qmax) q = qmax;
+                if (q < -qmax) q = -qmax;
+            }
+            Xq[i * (int64_t)K + k] = (int8_t)q;
+        }
+    }
+    return 0;
+}
+
 /* -------------------------------------------- asymmetric activation quantiser */
 
 /* Per-token asymmetric 8-bit quantiser of Eq. 1-3:
@@ -358,6 +385,7 @@ int trdq_oracle_rotate_weights(const float *W, int K, int N, const float *d, int
 /* Symmetric weight quantiser.
  *   wbits = 8: one scale per output channel n (per-channel granularity),
  *              s_w[n] = max_k |W'[k,n]| / 127, codes in [-127,127]; sw is [N].
+ *   wbits = 6: the same with 31 in place of 127 (the W6 of Table 3).
  *   wbits = 4: one scale per (input group of `group` rows, output channel),
  *              s_w[g,n] = max_{k in g} |W'[k,n]| / 7, codes in [-7,7]; sw is [K/group, N].
  * Wq: int8 [K, N], one code per byte for both widths.  Zero column/group -> scale 0, codes 0. */
@@ -365,9 +393,9 @@ int trdq_oracle_quant_weights(const double *Wp, int K, int N, int wbits, int gro
                               int8_t *Wq, double *sw)
 {
     if (!Wp || !Wq || !sw || K <= 0 || N <= 0) return 1;
-    if (wbits != 8 && wbits != 4) return 1;
-    double qmax = (wbits == 8) ? 127.0 : 7.0;
-    int glen = (wbits == 8) ? K : group;
+    if (wbits != 8 && wbits != 6 && wbits != 4) return 1;
+    double qmax = (double)((1 << (wbits - 1)) - 1);          /* 127, 31, 7 */
+    int glen = (wbits == 4) ? group : K;
     if (glen <= 0 || K % glen) return 1;
     int ng = K / glen;
 #pragma omp parallel for schedule(static)

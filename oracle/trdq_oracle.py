@@ -32,6 +32,7 @@ def lib():
         L.trdq_oracle_hadamard.argtypes = [i32, p]
         L.trdq_oracle_rotate.argtypes = [p, i64, i32, i64, p, i32, p]
         L.trdq_oracle_quant_tokens.argtypes = [p, i64, i32, p, p]
+        L.trdq_oracle_quant_tokens_bits.argtypes = [p, i64, i32, i32, p, p]
         L.trdq_oracle_rotate_weights.argtypes = [p, i32, i32, p, i32, p]
         L.trdq_oracle_quant_weights.argtypes = [p, i32, i32, i32, i32, p, p]
         L.trdq_oracle_pack_int4.argtypes = [p, i32, i32, p]
@@ -106,17 +107,32 @@ def rotate(X_bf16, d=None, B=128):
     return V
 
 
-def quant_tokens(V):
+def quant_tokens(V, abits=8):
+    """Per-token symmetric quantiser; abits = 8 is the path's own, other widths (Table 3's A6) go
+    through the general routine."""
     V = _c(V, np.float64)
     M, K = V.shape
     Xq = np.empty((M, K), dtype=np.int8)
     sx = np.empty(M, dtype=np.float64)
-    _chk(lib().trdq_oracle_quant_tokens(_ptr(V), M, K, _ptr(Xq), _ptr(sx)), "quant_tokens")
+    if abits == 8:
+        _chk(lib().trdq_oracle_quant_tokens(_ptr(V), M, K, _ptr(Xq), _ptr(sx)), "quant_tokens")
+    else:
+        _chk(lib().trdq_oracle_quant_tokens_bits(_ptr(V), M, K, int(abits), _ptr(Xq), _ptr(sx)), "quant_tokens_bits")
     return Xq, sx
 
 
-def rotate_quant(X_bf16, d=None, B=128):
-    return quant_tokens(rotate(X_bf16, d, B))
+def quant_tokens_bits(V, abits):
+    """The general routine at any width 2..8 (also 8: the pins compare it with quant_tokens)."""
+    V = _c(V, np.float64)
+    M, K = V.shape
+    Xq = np.empty((M, K), dtype=np.int8)
+    sx = np.empty(M, dtype=np.float64)
+    _chk(lib().trdq_oracle_quant_tokens_bits(_ptr(V), M, K, int(abits), _ptr(Xq), _ptr(sx)), "quant_tokens_bits")
+    return Xq, sx
+
+
+def rotate_quant(X_bf16, d=None, B=128, abits=8):
+    return quant_tokens(rotate(X_bf16, d, B), abits)
 
 
 def rotate_weights(W, d=None, B=128):
@@ -131,12 +147,12 @@ def rotate_weights(W, d=None, B=128):
 def quant_weights(Wp, wbits=8, group=128):
     Wp = _c(Wp, np.float64)
     K, N = Wp.shape
-    ng = 1 if wbits == 8 else K // group
+    ng = K // group if wbits == 4 else 1
     Wq = np.empty((K, N), dtype=np.int8)
     sw = np.empty((ng, N), dtype=np.float64)
     _chk(lib().trdq_oracle_quant_weights(_ptr(Wp), K, N, wbits, group, _ptr(Wq), _ptr(sw)),
          "quant_weights")
-    return Wq, (sw[0] if wbits == 8 else sw)
+    return Wq, (sw if wbits == 4 else sw[0])
 
 
 def prepare_weights(W, d=None, B=128, wbits=8):
@@ -335,13 +351,13 @@ def dequant(acc, sx, sw, bias=None, return_f64=False):
     return (Y, Yd) if return_f64 else Y
 
 
-def linear(X_bf16, W, d=None, bias=None, B=128, wbits=8, exact_blas=False):
+def linear(X_bf16, W, d=None, bias=None, B=128, wbits=8, exact_blas=False, abits=8):
     """Whole path; returns a dict with Xq, sx, Wq, sw, acc, Y (bf16 bits) and Yd (float64).
 
     exact_blas=True replaces only the integer-product step by acc_exact_blas."""
-    Xq, sx = rotate_quant(X_bf16, d, B)
+    Xq, sx = rotate_quant(X_bf16, d, B, abits)
     Wq, sw = prepare_weights(W, d, B, wbits)
-    group = None if wbits == 8 else B
+    group = B if wbits == 4 else None
     acc = (acc_exact_blas if exact_blas else igemm)(Xq, Wq, group)
     Y, Yd = dequant(acc, sx, sw, bias, return_f64=True)
     return dict(Xq=Xq, sx=sx, Wq=Wq, sw=sw, acc=acc, Y=Y, Yd=Yd)

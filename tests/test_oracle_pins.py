@@ -651,3 +651,59 @@ def test_asym_linear_close_to_exact_product(oracle):
     rel_a = np.linalg.norm(ref["Yd"] - exact) / np.linalg.norm(exact)
     rel_s = np.linalg.norm(oracle.linear(X, W)["Yd"] - exact) / np.linalg.norm(exact)
     assert rel_a < 0.02 and rel_a < 1.2 * rel_s
+
+
+# ------------------------------------ other bit-widths (the W6A6 of Table 3)
+
+@pytest.mark.parametrize("bits", [2, 4, 6, 7, 8])
+def test_quant_tokens_bits_brute_force_rational(oracle, bits):
+    # Eq. 1-2 (symmetric) in exact rational arithmetic on dyadic values, ties included
+    qmax = 2 ** (bits - 1) - 1
+    vals = [[-3.0, 1.5, 0.25, 2.0, 0.75], [0.5, 4.0, 1.0, 0.125, -4.0], [float(qmax), 0.5, 1.5, -2.5, -0.5],
+            [0.0, 0.0, 0.0, 0.0, 0.0]]
+    Xq, sx = oracle.quant_tokens_bits(np.array(vals), bits)
+
+    def rne(fr):
+        fl = fr.numerator // fr.denominator
+        rem = fr - fl
+        return fl + 1 if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1) else fl
+    for i, row in enumerate(vals):
+        fr = [Fraction(v) for v in row]
+        a = max(abs(v) for v in fr)
+        if a == 0:
+            assert sx[i] == 0 and not Xq[i].any()
+            continue
+        s = a / qmax
+        assert sx[i] == float(s)
+        for k, v in enumerate(fr):
+            assert Xq[i, k] == min(qmax, max(-qmax, rne(v / s)))
+    if qmax >= 3:                                           # scale exactly 1: the halves go to the even neighbour
+        assert sx[2] == 1.0 and Xq[2].tolist() == [qmax, 0, 2, -2, 0]
+
+
+def test_quant_tokens_bits_reduces_to_the_8_bit_quantiser(oracle):
+    V = oracle.rotate(wl.make_x(wl.CONFIGS[0], "proj", M=64))
+    V[7] = 0.0
+    a, sa = oracle.quant_tokens(V)
+    b, sb = oracle.quant_tokens_bits(V, 8)
+    assert np.array_equal(a, b) and np.array_equal(sa, sb)
+
+
+def test_six_bit_quantisers_properties(oracle):
+    B, K, N = 128, 256, 24
+    Xb, W, d, _ = wl.small_case(17, 32, K, N)
+    V = oracle.rotate(Xb, d, B)
+    Xq, sx = oracle.quant_tokens(V, abits=6)
+    assert np.all(np.abs(Xq).max(axis=1) == 31) and np.all(np.abs(Xq) <= 31)
+    assert np.allclose(sx, np.abs(V).max(axis=1) / 31, rtol=1e-15)
+    assert np.all(np.abs(V - sx[:, None] * Xq) <= sx[:, None] * (0.5 + 1e-12))
+    Wp = oracle.rotate_weights(W, d, B)
+    Wq, sw = oracle.quant_weights(Wp, 6, B)
+    assert sw.shape == (N,) and np.all(np.abs(Wq).max(axis=0) == 31)
+    assert np.allclose(sw, np.abs(Wp).max(axis=0) / 31, rtol=1e-15)
+    assert np.all(np.abs(Wp - sw * Wq) <= sw * (0.5 + 1e-12))
+    # fewer levels, larger error: W6A6 sits between W8A8 and the exact product
+    exact = oracle.bf16_to_f64(Xb) @ W.astype(np.float64)
+    e8 = np.abs(oracle.linear(Xb, W, d)["Yd"] - exact).mean()
+    e6 = np.abs(oracle.linear(Xb, W, d, wbits=6, abits=6)["Yd"] - exact).mean()
+    assert e8 < e6 < 8 * e8
