@@ -53,7 +53,7 @@ typedef enum trdq_status {
     TRDQ_ERR_NULL = 1,        /* a required pointer is NULL */
     TRDQ_ERR_SHAPE = 2,       /* K % 128 != 0, K/N <= 0, M < 0, leading dimension too small, misaligned pointer */
     TRDQ_ERR_RANGE = 3,       /* step or group out of range, bad table */
-    TRDQ_ERR_UNSUPPORTED = 4, /* wbits not in {4, 8}, block != 128, shape beyond a kernel's limit */
+    TRDQ_ERR_UNSUPPORTED = 4, /* wbits not in {4, 6, 8}, block != 128, shape beyond a kernel's limit */
     TRDQ_ERR_MISMATCH = 5,    /* handle's K / N / width does not match the call */
     TRDQ_ERR_ALLOC = 6,       /* host or device allocation failed */
     TRDQ_ERR_HIP = 7          /* a HIP runtime call or kernel launch failed */
@@ -95,7 +95,8 @@ typedef struct trdq_weights trdq_weights;
  * (temporary buffers are freed).  *out holds codes and scales in a private,
  * matrix-core friendly layout.
  * Errors: NULL W_dev/out -> ERR_NULL; K <= 0, N <= 0, K % 128 != 0, N % 16 != 0
- * -> ERR_SHAPE; block != 128 or wbits not 4/8 -> ERR_UNSUPPORTED. */
+ * -> ERR_SHAPE; block != 128 or wbits not 4/6/8 -> ERR_UNSUPPORTED
+ * (wbits 6: see "other bit-widths" below). */
 trdq_status trdq_prepare_weights(const float *W_dev, int K, int N, const float *diag_dev,
                                  int block, int wbits, void *stream, trdq_weights **out);
 
@@ -134,6 +135,18 @@ trdq_status trdq_rotate_quant(const void *X_dev, int64_t M, int K, int64_t ldx,
  * Outputs and errors are those of trdq_rotate_quant; `next` is only read. */
 trdq_status trdq_rotate_quant_warm(const void *X_dev, int64_t M, int K, int64_t ldx,
                                    const float *diag_dev, int block,
+                                   int8_t *Xq_dev, float *sx_dev, const trdq_weights *next, void *stream);
+
+/* ------------------------------------ other bit-widths (the W6A6 rows of Table 3)
+ * trdq_rotate_quant_warm with symmetric codes of abits bits: codes in +-(2^(abits-1) - 1), one per
+ * int8, s_x[i] = max_k |V[i,k]| / (2^(abits-1) - 1).  abits = 8 is trdq_rotate_quant_warm bit for
+ * bit.  trdq_prepare_weights(wbits = 6) is the weight side: per-output-channel scales and codes in
+ * +-31 in the layout of wbits = 8 (trdq_weights_info reports 6, trdq_weights_export gives int8
+ * codes and [N] scales).  trdq_qgemm, trdq_qgemm_asym and trdq_linear_fused take such weights
+ * unchanged: the product runs on the int8 matrix instructions whatever the code width.
+ * Errors as trdq_rotate_quant_warm; abits outside 2..8 -> ERR_RANGE; K > 4608 -> ERR_UNSUPPORTED. */
+trdq_status trdq_rotate_quant_bits(const void *X_dev, int64_t M, int K, int64_t ldx,
+                                   const float *diag_dev, int block, int abits,
                                    int8_t *Xq_dev, float *sx_dev, const trdq_weights *next, void *stream);
 
 /* ------------------------------------ asymmetric activations (Eq. 1-3)

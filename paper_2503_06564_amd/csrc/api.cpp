@@ -126,14 +126,16 @@ trdq_status prepare_weights_impl(const float *W_dev, int K, int N, const float *
     if (!out) return TRDQ_ERR_NULL;
     *out = nullptr;
     if (!W_dev) return TRDQ_ERR_NULL;
-    if (block != trdq::kBlock || (wbits != 8 && wbits != 4)) return TRDQ_ERR_UNSUPPORTED;
+    if (block != trdq::kBlock || (wbits != 8 && wbits != 6 && wbits != 4)) return TRDQ_ERR_UNSUPPORTED;
     if (K <= 0 || N <= 0 || K % trdq::kBlock != 0 || N % 16 != 0) return TRDQ_ERR_SHAPE;
+    const int qbits = wbits;
+    if (wbits == 6) wbits = 8;      // 6-bit codes live in the 8-bit layout; only the quantiser's range differs
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int nb = K / trdq::kBlock;
     trdq_weights *w = new (std::nothrow) trdq_weights;
     if (!w) return TRDQ_ERR_ALLOC;
-    w->K = K; w->N = N; w->wbits = wbits;
+    w->K = K; w->N = N; w->wbits = wbits; w->qbits = qbits;
     float *Wrot = nullptr, *Wrot2 = nullptr, *amax = nullptr;
     const size_t code_bytes = wbits == 8 ? (size_t)K * N : (size_t)K * N / 2;
     const size_t scale_count = wbits == 8 ? (size_t)N : (size_t)nb * N;
@@ -153,9 +155,9 @@ trdq_status prepare_weights_impl(const float *W_dev, int K, int N, const float *
     if (ok && perm_dev) {
         // rows gathered through the permutation, rotated again; two unnormalised rotations: 1/128
         ok = trdq::launch_prepare_rotate(Wrot, K, N, nullptr, perm_dev, Wrot2, amax, st) == hipSuccess &&
-             trdq::launch_prepare_quant(Wrot2, amax, K, N, wbits, 0.0078125f, w->codes, w->scales, st) == hipSuccess;
+             trdq::launch_prepare_quant(Wrot2, amax, K, N, qbits, 0.0078125f, w->codes, w->scales, st) == hipSuccess;
     } else if (ok) {
-        ok = trdq::launch_prepare_quant(Wrot, amax, K, N, wbits, 0.08838834764831845f, w->codes, w->scales, st) == hipSuccess;
+        ok = trdq::launch_prepare_quant(Wrot, amax, K, N, qbits, 0.08838834764831845f, w->codes, w->scales, st) == hipSuccess;
     }
     if (ok && wbits == 8) ok = trdq::launch_weight_colsum(w->codes, K, N, w->colsum, st) == hipSuccess;
     if (!ok || hipStreamSynchronize(st) != hipSuccess) {
@@ -248,7 +250,7 @@ trdq_status trdq_weights_info(const trdq_weights *w, int *K_out, int *N_out, int
     if (!w) return TRDQ_ERR_NULL;
     if (K_out) *K_out = w->K;
     if (N_out) *N_out = w->N;
-    if (wbits_out) *wbits_out = w->wbits;
+    if (wbits_out) *wbits_out = w->qbits;
     return TRDQ_OK;
 }
 
@@ -351,6 +353,29 @@ trdq_status trdq_rotate_quant_warm(const void *X_dev, int64_t M, int K, int64_t 
     return hip_status(trdq::launch_rotate_quant(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev,
                                                 Xq_dev, sx_dev, nullptr, warm, warm_bytes,
                                                 static_cast<hipStream_t>(stream)));
+}
+
+trdq_status trdq_rotate_quant_bits(const void *X_dev, int64_t M, int K, int64_t ldx,
+                                   const float *diag_dev, int block, int abits,
+                                   int8_t *Xq_dev, float *sx_dev, const trdq_weights *next, void *stream)
+{
+    trdq_status rc = check_rotate_args(X_dev, M, K, ldx, block);
+    if (rc != TRDQ_OK) return rc;
+    if (M > 0 && (!Xq_dev || !sx_dev)) return TRDQ_ERR_NULL;
+    if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || (diag_dev && !aligned(diag_dev, 16))) return TRDQ_ERR_SHAPE;
+    if (abits < 2 || abits > 8) return TRDQ_ERR_RANGE;
+    if (K / trdq::kBlock > 36) return TRDQ_ERR_UNSUPPORTED;
+    if (M == 0) return TRDQ_OK;
+    const void *warm = nullptr;
+    int64_t warm_bytes = 0;
+    if (next && next->codes) {
+        warm = next->codes;
+        warm_bytes = (int64_t)next->N * next->K / (next->wbits == 4 ? 2 : 1);
+        warm_bytes -= warm_bytes % 16;
+    }
+    return hip_status(trdq::launch_rotate_quant(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev,
+                                                Xq_dev, sx_dev, nullptr, warm, warm_bytes,
+                                                static_cast<hipStream_t>(stream), abits));
 }
 
 trdq_status trdq_rotate_quant_asym(const void *X_dev, int64_t M, int K, int64_t ldx,
@@ -457,7 +482,7 @@ trdq_status trdq_layer_create(const trdq_table *t, int K, int N, int wbits, trdq
     if (!out) return TRDQ_ERR_NULL;
     *out = nullptr;
     if (!t) return TRDQ_ERR_NULL;
-    if (wbits != 8 && wbits != 4) return TRDQ_ERR_UNSUPPORTED;
+    if (wbits != 8 && wbits != 6 && wbits != 4) return TRDQ_ERR_UNSUPPORTED;
     if (K <= 0 || N <= 0 || K % trdq::kBlock != 0 || N % 16 != 0) return TRDQ_ERR_SHAPE;
     trdq_layer *l = new (std::nothrow) trdq_layer;
     if (!l) return TRDQ_ERR_ALLOC;
@@ -518,7 +543,7 @@ trdq_status trdq_layer_forward(const trdq_layer *l, int step, const void *X_dev,
     if (!l->set[(size_t)g]) return TRDQ_ERR_MISMATCH;
     const trdq_weights *w = l->w[(size_t)g];
     const float *d = l->diag[(size_t)g];
-    if (fused > 0 || (fused < 0 && trdq::fused_pays(M, l->K, l->N, l->wbits)))
+    if (fused > 0 || (fused < 0 && trdq::fused_pays(M, l->K, l->N, w->wbits)))
         return trdq_linear_fused(X_dev, M, l->K, d, w, bias_dev, Y_dev, l->N, stream);
     if (!Xq_ws_dev || !sx_ws_dev) return TRDQ_ERR_NULL;
     trdq_status rc = trdq_rotate_quant_warm(X_dev, M, l->K, l->K, d, trdq::kBlock, Xq_ws_dev, sx_ws_dev, w, stream);

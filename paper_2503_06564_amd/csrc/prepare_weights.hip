@@ -67,13 +67,13 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_rotate_kernel(
 
 // Kernel 2: quantise and transpose one 128-row block of 64 columns into the K-contiguous
 // layouts the product kernels read (see Weights in trdq_internal.h).
-//   wbits 8: scale[n]    = max_b amax[b, n] * norm / 127
+//   wbits 8: scale[n]    = max_b amax[b, n] * norm / 127   (qmax = 31 in the same layout: 6-bit codes)
 //   wbits 4: scale[b, n] = amax[b, n]       * norm / 7
 // norm undoes the unnormalised butterflies: 1/sqrt(128) after one rotation, 1/128 after two.
 //   code = rint(Wrot * qmax / amax)   (ties to even; amax == 0 -> 0)
 template <int WBITS>
 __global__ __launch_bounds__(kPrepThreads) void prepare_quant_kernel(
-    const float *__restrict__ Wrot, const float *__restrict__ amax, int K, int N, float norm,
+    const float *__restrict__ Wrot, const float *__restrict__ amax, int K, int N, float norm, float qmax,
     void *__restrict__ codes, float *__restrict__ scales)
 {
     __shared__ int8_t q8[kCols][kBlock + 16];
@@ -81,7 +81,6 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_quant_kernel(
     const int nb = K / kBlock;
     const int b = blockIdx.y;
     const int n0 = blockIdx.x * kCols;
-    constexpr float qmax = WBITS == 8 ? 127.0f : 7.0f;
 
     if (threadIdx.x < kCols) {
         const int n = n0 + threadIdx.x;
@@ -174,10 +173,11 @@ hipError_t launch_prepare_quant(const float *Wrot, const float *amax, int K, int
                                 void *codes, float *scales, hipStream_t st)
 {
     dim3 grid((N + kCols - 1) / kCols, K / kBlock);
-    if (wbits == 8)
-        hipLaunchKernelGGL(prepare_quant_kernel<8>, grid, dim3(kPrepThreads), 0, st, Wrot, amax, K, N, norm, codes, scales);
+    if (wbits == 8 || wbits == 6)
+        hipLaunchKernelGGL(prepare_quant_kernel<8>, grid, dim3(kPrepThreads), 0, st, Wrot, amax, K, N, norm,
+                           wbits == 8 ? 127.0f : 31.0f, codes, scales);
     else
-        hipLaunchKernelGGL(prepare_quant_kernel<4>, grid, dim3(kPrepThreads), 0, st, Wrot, amax, K, N, norm, codes, scales);
+        hipLaunchKernelGGL(prepare_quant_kernel<4>, grid, dim3(kPrepThreads), 0, st, Wrot, amax, K, N, norm, 7.0f, codes, scales);
     return hipGetLastError();
 }
 

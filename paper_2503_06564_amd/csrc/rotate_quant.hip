@@ -50,7 +50,7 @@ template <int SPW, int MAXT, bool ASYM>
 __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
     const uint16_t *__restrict__ X, int64_t M, int nb, int64_t ldx,
     const float *__restrict__ diag, int8_t *__restrict__ Xq, float *__restrict__ sx,
-    int32_t *__restrict__ zc, const uint4 *__restrict__ warm, int64_t warm_chunks)
+    int32_t *__restrict__ zc, const uint4 *__restrict__ warm, int64_t warm_chunks, float qmax, float sx_mul)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int K = nb * kBlock;
@@ -274,8 +274,9 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
                 zc[token] = 128 - (int)z;
             }
         } else {
-            inv = amax > 0.0f ? 127.0f / amax : 0.0f;
-            if (wave == 0 && g == 0 && token_ok) sx[token] = amax * (0.08838834764831845f / 127.0f);
+            // qmax = 2^(bits-1) - 1 (127 for int8), sx_mul = (1 / sqrt(128)) / qmax, both from the host
+            inv = amax > 0.0f ? qmax / amax : 0.0f;
+            if (wave == 0 && g == 0 && token_ok) sx[token] = amax * sx_mul;
         }
         // rounded value + offset, clamped to the int8 range, as the low byte of the float's bits
         auto code_bits = [&](float v) -> uint32_t {
@@ -319,8 +320,10 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
 template <int SPW, int MAXT>
 hipError_t launch_spw(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx, const float *diag,
                       int8_t *Xq, float *sx, int32_t *zc, const void *warm, int64_t warm_bytes, int wgs_per_cu,
-                      hipStream_t st)
+                      hipStream_t st, int abits)
 {
+    const float qmax = (float)((1 << (abits - 1)) - 1);
+    const float sx_mul = 0.08838834764831845f / qmax;
     // persistent workgroups: a few per compute unit, each walking token groups
     const int64_t groups = (M + kTokensPerWG - 1) / kTokensPerWG;
     int64_t grid = (int64_t)256 * wgs_per_cu;
@@ -329,10 +332,10 @@ hipError_t launch_spw(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx,
     const int64_t warm_chunks = (warm && warm_bytes < ((int64_t)1 << 32)) ? warm_bytes / 16 : 0;   // 32-bit byte offsets in the copy
     if (zc)
         hipLaunchKernelGGL((rotate_quant_kernel<SPW, MAXT, true>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
-                           X, M, nb, ldx, diag, Xq, sx, zc, static_cast<const uint4 *>(warm), warm_chunks);
+                           X, M, nb, ldx, diag, Xq, sx, zc, static_cast<const uint4 *>(warm), warm_chunks, qmax, sx_mul);
     else
         hipLaunchKernelGGL((rotate_quant_kernel<SPW, MAXT, false>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
-                           X, M, nb, ldx, diag, Xq, sx, zc, static_cast<const uint4 *>(warm), warm_chunks);
+                           X, M, nb, ldx, diag, Xq, sx, zc, static_cast<const uint4 *>(warm), warm_chunks, qmax, sx_mul);
     return hipGetLastError();
 }
 
@@ -343,11 +346,14 @@ hipError_t launch_spw(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx,
 constexpr int kRQMaxBlocks = 36;
 
 hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
-                               int8_t *Xq, float *sx, int32_t *zc, const void *warm, int64_t warm_bytes, hipStream_t st)
+                               int8_t *Xq, float *sx, int32_t *zc, const void *warm, int64_t warm_bytes, hipStream_t st,
+                               int abits)
 {
     if (M == 0) return hipSuccess;
+    if (abits < 2 || abits > 8) return hipErrorInvalidValue;
     const int nb = K / kBlock;
-    if (nb > kRQMaxBlocks) return zc ? hipErrorInvalidValue : launch_rotate_quant_wide(X, M, K, ldx, diag, Xq, sx, st);
+    if (nb > kRQMaxBlocks)
+        return (zc || abits != 8) ? hipErrorInvalidValue : launch_rotate_quant_wide(X, M, K, ldx, diag, Xq, sx, st);
     // three blocks per wave (two or one for narrow rows), then rebalance; workgroups of up to
     // 12 waves, as many per compute unit as stay resident (with three blocks per wave the kernel
     // holds 166 registers and small workgroups pack two waves per SIMD, eight per compute unit)
@@ -362,12 +368,12 @@ hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx,
     const int wgs = resident / nw > 0 ? resident / nw : 1;
     const bool small = nw <= 4;      // up to 256 threads: no register cap from co-residency
     switch (spw) {
-        case 1: return small ? launch_spw<1, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st)
-                             : launch_spw<1, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st);
-        case 2: return small ? launch_spw<2, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st)
-                             : launch_spw<2, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st);
-        default: return small ? launch_spw<3, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st)
-                              : launch_spw<3, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st);
+        case 1: return small ? launch_spw<1, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits)
+                             : launch_spw<1, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits);
+        case 2: return small ? launch_spw<2, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits)
+                             : launch_spw<2, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits);
+        default: return small ? launch_spw<3, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits)
+                              : launch_spw<3, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits);
     }
 }
 

@@ -17,7 +17,9 @@ constexpr int kBlock = TRDQ_BLOCK;  // rotation block = int4 scale group
 //            (v << 4) & 0xF0F0F0F0 and v & 0xF0F0F0F0 give 16*code as packed int8.
 //   scales : float32 [N] (wbits 8) or [K/128, N] (wbits 4), the true s_w.
 struct Weights {
-    int K = 0, N = 0, wbits = 0;
+    int K = 0, N = 0;
+    int wbits = 0;               // storage layout: 8 (one code per byte) or 4 (packed nibbles, group scales)
+    int qbits = 0;               // width of the codes: 8, 6 (in the 8-bit layout) or 4
     void *codes = nullptr;
     float *scales = nullptr;
     int32_t *colsum = nullptr;   // int8 weights: sum over k of the codes of every output channel [N]
@@ -34,7 +36,8 @@ struct Table {
 // kernel reads once and discards, to pull it into the memory-side cache for the next kernel.
 // zc: null (symmetric quantiser), or where the asymmetric quantiser writes 128 - z_i per token.
 hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
-                               int8_t *Xq, float *sx, int32_t *zc, const void *warm, int64_t warm_bytes, hipStream_t st);
+                               int8_t *Xq, float *sx, int32_t *zc, const void *warm, int64_t warm_bytes, hipStream_t st,
+                               int abits = 8);   // symmetric codes in +-(2^(abits-1) - 1); K <= 4608 unless 8
 hipError_t launch_rotate_quant_wide(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
                                     int8_t *Xq, float *sx, hipStream_t st);
 
@@ -49,7 +52,7 @@ hipError_t launch_rotate_quant_rpr(const uint16_t *X, int64_t M, int K, int64_t 
 hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag, const int32_t *perm,
                                  float *Wrot, float *amax, hipStream_t st);
 hipError_t launch_prepare_quant(const float *Wrot, const float *amax, int K, int N, int wbits, float norm,
-                                void *codes, float *scales, hipStream_t st);
+                                void *codes, float *scales, hipStream_t st);   // wbits 8, 6 (8-bit layout) or 4
 
 // Calibration-side reductions (calibrate.hip).  mag / wmax / d are device arrays of K floats.
 hipError_t launch_channel_absmax(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,

@@ -23,7 +23,7 @@ SYMBOLS = [
     "trdq_layer_destroy", "trdq_qgemm_set_variant", "trdq_qgemm_num_variants",
     "trdq_zigzag_permutation", "trdq_prepare_weights_rpr", "trdq_rotate_quant_rpr",
     "trdq_channel_absmax", "trdq_weight_row_absmax", "trdq_smooth_diag",
-    "trdq_rotate_quant_asym", "trdq_qgemm_asym",
+    "trdq_rotate_quant_asym", "trdq_qgemm_asym", "trdq_rotate_quant_bits",
 ]
 
 _lib = None
@@ -73,6 +73,7 @@ def lib():
         L.trdq_qgemm_set_variant.argtypes = [i32]
         L.trdq_zigzag_permutation.argtypes = [p, i32, i32, p]
         L.trdq_rotate_quant_asym.argtypes = [p, i64, i32, i64, p, i32, p, p, p, p, p]
+        L.trdq_rotate_quant_bits.argtypes = [p, i64, i32, i64, p, i32, i32, p, p, p, p]
         L.trdq_qgemm_asym.argtypes = [p, p, p, p, i64, p, p, i64, p, p]
         L.trdq_channel_absmax.argtypes = [p, i64, i32, i64, p, i32, i32, p, p]
         L.trdq_weight_row_absmax.argtypes = [p, i32, i32, p, p]
@@ -167,7 +168,7 @@ class Weights:
         import numpy as np
         K, N, wbits = self.info()
         codes = np.empty((K, N), dtype=np.int8)
-        scales = np.empty((N,) if wbits == 8 else (K // BLOCK, N), dtype=np.float32)
+        scales = np.empty((K // BLOCK, N) if wbits == 4 else (N,), dtype=np.float32)
         _check(lib().trdq_weights_export(self.handle, _ptr(codes), _ptr(scales)), "trdq_weights_export")
         return codes, scales
 
@@ -258,6 +259,15 @@ def rotate_quant(X, diag, Xq, sx, block=BLOCK, stream=None, warm=None):
     else:
         _check(lib().trdq_rotate_quant_warm(_ptr(X), M, K, ldx, _ptr(diag), block, _ptr(Xq), _ptr(sx), warm.handle,
                                             _stream(stream)), "trdq_rotate_quant_warm")
+
+
+def rotate_quant_bits(X, diag, Xq, sx, abits, block=BLOCK, stream=None, warm=None):
+    """Symmetric per-token codes of `abits` bits (2..8), one per int8."""
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    _check(lib().trdq_rotate_quant_bits(_ptr(X), M, K, ldx, _ptr(diag), block, abits, _ptr(Xq), _ptr(sx),
+                                        warm.handle if warm is not None else None, _stream(stream)),
+           "trdq_rotate_quant_bits")
 
 
 def rotate_quant_asym(X, diag, Xq, sx, zc, block=BLOCK, stream=None, warm=None):

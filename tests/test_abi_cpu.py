@@ -74,7 +74,7 @@ def test_prepare_weights_argument_errors():
     assert call(FAKE, 128, 16, 128, 8, None) == trdq.ERR_NULL
     assert call(None, 128, 16, 128, 8, C.byref(h)) == trdq.ERR_NULL
     assert call(FAKE, 128, 16, 64, 8, C.byref(h)) == trdq.ERR_UNSUPPORTED
-    assert call(FAKE, 128, 16, 128, 6, C.byref(h)) == trdq.ERR_UNSUPPORTED
+    assert call(FAKE, 128, 16, 128, 5, C.byref(h)) == trdq.ERR_UNSUPPORTED
     assert call(FAKE, 100, 16, 128, 8, C.byref(h)) == trdq.ERR_SHAPE
     assert call(FAKE, 0, 16, 128, 8, C.byref(h)) == trdq.ERR_SHAPE
     assert call(FAKE, 128, 0, 128, 8, C.byref(h)) == trdq.ERR_SHAPE
@@ -165,7 +165,7 @@ def test_rpr_argument_errors_before_any_gpu_call():
     # NULL permutation, then the same checks as the one-rotation entry points
     assert L.trdq_prepare_weights_rpr(0x1000, 256, 64, None, None, 128, 8, None, C.byref(out)) == trdq.ERR_NULL
     assert L.trdq_prepare_weights_rpr(0x1000, 200, 64, None, 0x2000, 128, 8, None, C.byref(out)) == trdq.ERR_SHAPE
-    assert L.trdq_prepare_weights_rpr(0x1000, 256, 64, None, 0x2000, 128, 6, None, C.byref(out)) == trdq.ERR_UNSUPPORTED
+    assert L.trdq_prepare_weights_rpr(0x1000, 256, 64, None, 0x2000, 128, 5, None, C.byref(out)) == trdq.ERR_UNSUPPORTED
     assert L.trdq_rotate_quant_rpr(0x1000, 4, 256, 256, None, None, 128, 0x2000, 0x3000, None, None) == trdq.ERR_NULL
     assert L.trdq_rotate_quant_rpr(0x1000, 4, 256, 256, None, 0x4000, 64, 0x2000, 0x3000, None, None) == trdq.ERR_UNSUPPORTED
     assert L.trdq_rotate_quant_rpr(0x1000, 4, 200, 256, None, 0x4000, 128, 0x2000, 0x3000, None, None) == trdq.ERR_SHAPE
@@ -195,3 +195,14 @@ def test_asym_argument_errors_before_any_gpu_call():
     assert L.trdq_rotate_quant_asym(0x1000, 4, 128 * 37, 128 * 37, None, 128, 0x2000, 0x3000, 0x4000, None, None) == trdq.ERR_UNSUPPORTED
     assert L.trdq_rotate_quant_asym(0x1000, 0, 256, 256, None, 128, None, None, None, None, None) == trdq.OK
     assert L.trdq_qgemm_asym(None, 0x1000, 0x2000, 0x3000, 4, None, 0x4000, 64, None, None) == trdq.ERR_NULL
+
+
+def test_bits_argument_errors_before_any_gpu_call():
+    L = trdq.lib()
+    assert L.trdq_rotate_quant_bits(0x1000, 4, 256, 256, None, 128, 6, None, 0x3000, None, None) == trdq.ERR_NULL
+    assert L.trdq_rotate_quant_bits(0x1000, 4, 256, 256, None, 128, 9, 0x2000, 0x3000, None, None) == trdq.ERR_RANGE
+    assert L.trdq_rotate_quant_bits(0x1000, 4, 256, 256, None, 128, 1, 0x2000, 0x3000, None, None) == trdq.ERR_RANGE
+    assert L.trdq_rotate_quant_bits(0x1000, 4, 128 * 37, 128 * 37, None, 128, 6, 0x2000, 0x3000, None, None) == trdq.ERR_UNSUPPORTED
+    assert L.trdq_rotate_quant_bits(0x1000, 0, 256, 256, None, 128, 6, None, None, None, None) == trdq.OK
+    out = trdq.C.c_void_p()
+    assert L.trdq_prepare_weights(0x1000, 256, 64, None, 128, 5, None, trdq.C.byref(out)) == trdq.ERR_UNSUPPORTED
