@@ -263,6 +263,31 @@ def linear_asym(X_bf16, W, d=None, bias=None, B=128, exact_blas=False):
 
 # ---- calibration side: Eq. 5 and the statistics it and the zigzag permutation need ----------
 
+# ---- attention sharing (Sec. 3.3) ------------------------------------------------------------
+
+def cosine_similarity(A_bf16, B_bf16):
+    """Eq. 11 per row: cos(A, B) = A.B / (|A| |B|) for bf16 inputs [n, L], in float64.
+    A row where either vector is all zero has no direction: 0."""
+    A = bf16_to_f64(np.atleast_2d(A_bf16))
+    Bm = bf16_to_f64(np.atleast_2d(B_bf16))
+    out = np.zeros(A.shape[0], dtype=np.float64)
+    for i in range(A.shape[0]):
+        dot = float(np.dot(A[i], Bm[i]))
+        na = float(np.dot(A[i], A[i]))
+        nbb = float(np.dot(Bm[i], Bm[i]))
+        if na > 0.0 and nbb > 0.0:
+            out[i] = dot / (np.sqrt(na) * np.sqrt(nbb))
+    return out
+
+
+def share_plan(sim, threshold):
+    """Which transformer blocks share attention between the conditional and the unconditional
+    pass (Sec. 3.3: the blocks whose attention outputs are similar at every time step):
+    sim [n_steps, n_blocks] of Eq. 11 values -> 0/1 per block, 1 where min over the steps >= threshold."""
+    sim = np.asarray(sim, dtype=np.float64)
+    return (sim.min(axis=0) >= threshold).astype(np.int32)
+
+
 def channel_absmax(X_bf16, d=None, rotate_first=False, B=128):
     """max over tokens of |(X diag(d))[i, k]|, or of |((X diag(d)) R)[i, k]| when rotate_first."""
     if rotate_first:

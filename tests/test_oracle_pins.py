@@ -707,3 +707,50 @@ def test_six_bit_quantisers_properties(oracle):
     e8 = np.abs(oracle.linear(Xb, W, d)["Yd"] - exact).mean()
     e6 = np.abs(oracle.linear(Xb, W, d, wbits=6, abits=6)["Yd"] - exact).mean()
     assert e8 < e6 < 8 * e8
+
+
+# ------------------------------------ attention sharing (Sec. 3.3, Eq. 11)
+
+def test_cosine_similarity_closed_forms(oracle):
+    f = wl.f32_to_bf16_bits
+    a = np.array([[1.0, 0.0, 0.0, 0.0], [3.0, 4.0, 0.0, 0.0], [1.0, 2.0, -2.0, 0.5], [0.0, 0.0, 0.0, 0.0]], dtype=np.float32)
+    b = np.array([[0.0, 1.0, 0.0, 0.0], [1.0, 0.0, 0.0, 0.0], [1.0, 2.0, -2.0, 0.5], [1.0, 2.0, 3.0, 4.0]], dtype=np.float32)
+    c = oracle.cosine_similarity(f(a), f(b))
+    assert c[0] == 0.0                       # orthogonal
+    assert abs(c[1] - 0.6) < 1e-15           # the 3-4-5 triangle
+    assert abs(c[2] - 1.0) < 1e-15           # identical
+    assert c[3] == 0.0                       # a zero vector has no direction
+    assert abs(oracle.cosine_similarity(f(a[2:3]), f(-b[2:3]))[0] + 1.0) < 1e-15
+    # scale invariance (powers of two keep bf16 values exact) and symmetry
+    rng = np.random.default_rng(5)
+    x = f(rng.standard_normal((3, 257)).astype(np.float32))
+    y = f(rng.standard_normal((3, 257)).astype(np.float32))
+    c0 = oracle.cosine_similarity(x, y)
+    xs = f((oracle.bf16_to_f64(x) * 4.0).astype(np.float32))
+    ys = f((oracle.bf16_to_f64(y) * 0.125).astype(np.float32))
+    assert np.allclose(oracle.cosine_similarity(xs, ys), c0, rtol=0, atol=1e-15)
+    assert np.array_equal(oracle.cosine_similarity(y, x), c0)
+    assert np.all(np.abs(c0) <= 1.0)
+
+
+def test_cosine_similarity_exact_rational(oracle):
+    # cos^2 is rational: dot^2 / (|A|^2 |B|^2) in exact arithmetic on dyadic values
+    a = [[1.5, -2.0, 0.25, 3.0, 0.5], [0.75, 0.5, -1.0, 2.0, 4.0]]
+    b = [[0.5, 1.0, -4.0, 2.0, 0.125], [3.0, -0.25, 1.0, 1.0, 2.0]]
+    c = oracle.cosine_similarity(wl.f32_to_bf16_bits(np.array(a, dtype=np.float32)),
+                                 wl.f32_to_bf16_bits(np.array(b, dtype=np.float32)))
+    for i in range(2):
+        fa, fb = [Fraction(v) for v in a[i]], [Fraction(v) for v in b[i]]
+        dot = sum(x * y for x, y in zip(fa, fb))
+        c2 = dot * dot / (sum(x * x for x in fa) * sum(y * y for y in fb))
+        assert abs(c[i] * c[i] - float(c2)) < 1e-15 and (c[i] > 0) == (dot > 0)
+
+
+def test_share_plan(oracle):
+    sim = np.array([[0.99, 0.70, 0.95, 0.999],
+                    [0.97, 0.99, 0.95, 0.98],
+                    [0.96, 0.99, 0.94, 0.97]])
+    assert oracle.share_plan(sim, 0.95).tolist() == [1, 0, 0, 1]
+    assert oracle.share_plan(sim, 0.5).tolist() == [1, 1, 1, 1]
+    assert oracle.share_plan(sim, 0.96).tolist() == [1, 0, 0, 1]
+    assert oracle.share_plan(sim, 1.0).tolist() == [0, 0, 0, 0]
