@@ -195,6 +195,28 @@ trdq_status trdq_weight_row_absmax(const float *W_dev, int K, int N, float *wmax
 trdq_status trdq_smooth_diag(const float *xmax_dev, const float *wmax_dev, int K, float alpha,
                              float *diag_dev, void *stream);
 
+/* ------------------------------------------------- attention sharing (Sec. 3.3)
+ * Eq. 11 between the attention outputs of the conditional and the unconditional pass:
+ *   cos_dev[s] = A_s . B_s / (|A_s| |B_s|)   for s < n_seg;   0 where either vector is all zero.
+ * A_dev, B_dev: bf16, segment s starts at element s * stride_a (s * stride_b) and has seg_len
+ * elements (16-byte aligned bases; with more than one segment the strides are multiples of 8;
+ * stride >= seg_len).  acc_ws_dev: float64 [3 * n_seg] device workspace the call owns until it
+ * has finished (cleared by the call).  cos_dev: float32 [n_seg].  Sums run in fp64 above 64
+ * products, so the result is within 1e-5 of the exact value.  n_seg <= 65535.
+ * Errors: NULL -> ERR_NULL; sizes, strides, alignment -> ERR_SHAPE. */
+trdq_status trdq_cosine_similarity(const void *A_dev, const void *B_dev, int n_seg, int64_t seg_len,
+                                   int64_t stride_a, int64_t stride_b, double *acc_ws_dev, float *cos_dev,
+                                   void *stream);
+
+/* Which transformer blocks share attention between the two passes: the blocks whose similarity is
+ * at least `threshold` at EVERY time step (Sec. 3.3 shares the blocks that are similar across all
+ * time steps).  Host arrays: sim_host float32 [n_steps, n_blocks] of Eq. 11 values, share_host
+ * int32 [n_blocks] (written: 1 = share, 0 = compute both).  A NaN similarity never shares.
+ * Errors: NULL -> ERR_NULL; n_steps <= 0 or n_blocks <= 0 -> ERR_SHAPE; threshold outside
+ * [-1, 1] -> ERR_RANGE. */
+trdq_status trdq_share_plan(const float *sim_host, int n_steps, int n_blocks, float threshold,
+                            int32_t *share_host);
+
 /* ------------------------------------------- full transform of Eq. 9
  * G_t(X) = (X . Delta_t) . R^(1) . P . R^(2)  and  H_t(W) = R^(2)^T . P^T . R^(1)^T . (Delta_t^-1 . W)
  * (Sec. 3.2: first block rotation, zigzag permutation, second block rotation).  Both rotations

@@ -226,6 +226,33 @@ trdq_status trdq_smooth_diag(const float *xmax_dev, const float *wmax_dev, int K
                                                static_cast<hipStream_t>(stream)));
 }
 
+trdq_status trdq_cosine_similarity(const void *A_dev, const void *B_dev, int n_seg, int64_t seg_len,
+                                   int64_t stride_a, int64_t stride_b, double *acc_ws_dev, float *cos_dev,
+                                   void *stream)
+{
+    if (!A_dev || !B_dev || !acc_ws_dev || !cos_dev) return TRDQ_ERR_NULL;
+    if (n_seg <= 0 || n_seg > 65535 || seg_len <= 0 || stride_a < seg_len || stride_b < seg_len) return TRDQ_ERR_SHAPE;
+    // 16-byte loads: bases and strides in whole 16-byte pieces (a single segment needs only the bases)
+    if (!aligned(A_dev, 16) || !aligned(B_dev, 16) || !aligned(acc_ws_dev, 8) || !aligned(cos_dev, 4)) return TRDQ_ERR_SHAPE;
+    if (n_seg > 1 && (stride_a % 8 != 0 || stride_b % 8 != 0)) return TRDQ_ERR_SHAPE;
+    return hip_status(trdq::launch_cosine_similarity(static_cast<const uint16_t *>(A_dev),
+                                                     static_cast<const uint16_t *>(B_dev), n_seg, seg_len, stride_a,
+                                                     stride_b, acc_ws_dev, cos_dev, static_cast<hipStream_t>(stream)));
+}
+
+trdq_status trdq_share_plan(const float *sim_host, int n_steps, int n_blocks, float threshold, int32_t *share_host)
+{
+    if (!sim_host || !share_host) return TRDQ_ERR_NULL;
+    if (n_steps <= 0 || n_blocks <= 0) return TRDQ_ERR_SHAPE;
+    if (!(threshold >= -1.0f && threshold <= 1.0f)) return TRDQ_ERR_RANGE;
+    for (int b = 0; b < n_blocks; ++b) {
+        bool all = true;
+        for (int t = 0; t < n_steps && all; ++t) all = sim_host[(size_t)t * n_blocks + b] >= threshold;   // NaN: no
+        share_host[b] = all ? 1 : 0;
+    }
+    return TRDQ_OK;
+}
+
 trdq_status trdq_zigzag_permutation(const float *chan_mag_host, int K, int block, int32_t *perm_host)
 {
     if (!chan_mag_host || !perm_host) return TRDQ_ERR_NULL;

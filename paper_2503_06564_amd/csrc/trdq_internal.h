@@ -68,6 +68,8 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, con
                         const float *bias, uint16_t *Y, int64_t ldy, int32_t *acc_debug,
                         int variant, hipStream_t st);
 
+hipError_t launch_cosine_similarity(const uint16_t *A, const uint16_t *B, int n_seg, int64_t seg_len,
+                                    int64_t stride_a, int64_t stride_b, double *acc_ws, float *out, hipStream_t st);
 bool fused_supports(int K);
 bool fused_pays(int64_t M, int K, int N, int wbits);
 hipError_t launch_linear_fused(const Weights &w, const uint16_t *X, int64_t M, int64_t ldx,

@@ -24,6 +24,7 @@ SYMBOLS = [
     "trdq_zigzag_permutation", "trdq_prepare_weights_rpr", "trdq_rotate_quant_rpr",
     "trdq_channel_absmax", "trdq_weight_row_absmax", "trdq_smooth_diag",
     "trdq_rotate_quant_asym", "trdq_qgemm_asym", "trdq_rotate_quant_bits",
+    "trdq_cosine_similarity", "trdq_share_plan",
 ]
 
 _lib = None
@@ -74,6 +75,8 @@ def lib():
         L.trdq_zigzag_permutation.argtypes = [p, i32, i32, p]
         L.trdq_rotate_quant_asym.argtypes = [p, i64, i32, i64, p, i32, p, p, p, p, p]
         L.trdq_rotate_quant_bits.argtypes = [p, i64, i32, i64, p, i32, i32, p, p, p, p]
+        L.trdq_cosine_similarity.argtypes = [p, p, i32, i64, i64, i64, p, p, p]
+        L.trdq_share_plan.argtypes = [p, i32, i32, C.c_float, p]
         L.trdq_qgemm_asym.argtypes = [p, p, p, p, i64, p, p, i64, p, p]
         L.trdq_channel_absmax.argtypes = [p, i64, i32, i64, p, i32, i32, p, p]
         L.trdq_weight_row_absmax.argtypes = [p, i32, i32, p, p]
@@ -259,6 +262,25 @@ def rotate_quant(X, diag, Xq, sx, block=BLOCK, stream=None, warm=None):
     else:
         _check(lib().trdq_rotate_quant_warm(_ptr(X), M, K, ldx, _ptr(diag), block, _ptr(Xq), _ptr(sx), warm.handle,
                                             _stream(stream)), "trdq_rotate_quant_warm")
+
+
+def cosine_similarity(A, B, acc_ws, out, stream=None):
+    """Eq. 11 per row of A, B (bf16 [n_seg, L], rows may be strided); acc_ws float64 [3 * n_seg], out float32 [n_seg]."""
+    n_seg, L = A.shape
+    sa = A.stride(0) if n_seg > 1 else max(L, A.stride(0))
+    sb = B.stride(0) if n_seg > 1 else max(L, B.stride(0))
+    _check(lib().trdq_cosine_similarity(_ptr(A), _ptr(B), n_seg, L, sa, sb, _ptr(acc_ws), _ptr(out), _stream(stream)),
+           "trdq_cosine_similarity")
+
+
+def share_plan(sim, threshold):
+    """sim: float32 numpy [n_steps, n_blocks] -> int32 [n_blocks] (1 = share attention)."""
+    import numpy as np
+    sim = np.ascontiguousarray(sim, dtype=np.float32)
+    out = np.empty(sim.shape[1], dtype=np.int32)
+    _check(lib().trdq_share_plan(sim.ctypes.data, sim.shape[0], sim.shape[1], float(threshold), out.ctypes.data),
+           "trdq_share_plan")
+    return out
 
 
 def rotate_quant_bits(X, diag, Xq, sx, abits, block=BLOCK, stream=None, warm=None):

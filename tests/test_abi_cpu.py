@@ -206,3 +206,22 @@ def test_bits_argument_errors_before_any_gpu_call():
     assert L.trdq_rotate_quant_bits(0x1000, 0, 256, 256, None, 128, 6, None, None, None, None) == trdq.OK
     out = trdq.C.c_void_p()
     assert L.trdq_prepare_weights(0x1000, 256, 64, None, 128, 5, None, trdq.C.byref(out)) == trdq.ERR_UNSUPPORTED
+
+
+def test_attention_share_host_side(oracle):
+    L = trdq.lib()
+    assert L.trdq_cosine_similarity(None, 0x1000, 1, 64, 64, 64, 0x2000, 0x3000, None) == trdq.ERR_NULL
+    assert L.trdq_cosine_similarity(0x1000, 0x2000, 0, 64, 64, 64, 0x3000, 0x4000, None) == trdq.ERR_SHAPE
+    assert L.trdq_cosine_similarity(0x1000, 0x2000, 2, 64, 60, 64, 0x3000, 0x4000, None) == trdq.ERR_SHAPE
+    assert L.trdq_cosine_similarity(0x1000, 0x2000, 2, 60, 68, 64, 0x3000, 0x4000, None) == trdq.ERR_SHAPE
+    assert L.trdq_cosine_similarity(0x1008, 0x2000, 1, 64, 64, 64, 0x3000, 0x4000, None) == trdq.ERR_SHAPE
+    rng = np.random.default_rng(3)
+    sim = rng.uniform(0.8, 1.0, (20, 28)).astype(np.float32)
+    sim[:, 0] = 0.99; sim[:, 27] = 0.97; sim[7, 5] = np.nan
+    for thr in (0.9, 0.95, 0.97, 0.999):
+        got = trdq.share_plan(sim, thr)
+        want = oracle.share_plan(np.nan_to_num(sim, nan=-2.0), np.float32(thr))
+        assert np.array_equal(got, want)
+    assert trdq.share_plan(sim, 0.95)[0] == 1 and trdq.share_plan(sim, 0.95)[5] == 0
+    with pytest.raises(trdq.TrdqError):
+        trdq.share_plan(sim, 1.5)
