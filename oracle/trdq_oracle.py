@@ -263,6 +263,89 @@ def linear_asym(X_bf16, W, d=None, bias=None, B=128, exact_blas=False):
 
 # ---- calibration side: Eq. 5 and the statistics it and the zigzag permutation need ----------
 
+# ---- greedy dense block rotations (Sec. 3.2, Eq. 6-7 and the BlockDiag equation) ---------------
+
+def greedy_rotation(Xb, Qs):
+    """The rotation of ONE block by the greedy strategy of Eq. 6-7.
+
+    Xb: float64 [Mc, B] calibration activations of the block (after the diagonal).
+    Qs: float64 [N, B, B] the orthogonal matrices the method draws, one per step (each with a
+        first row of equal magnitudes); they are inputs, not generated here.
+    Step k: C1 swaps column 0 with the column that holds the largest |activation|, R^k = C1 Q_k C2
+    with C2 swapping the two columns back (Eq. 6); X <- X R^k.  R = R^1 ... R^n with
+    n = argmin_k max|X R^1 ... R^k| over k = 1..N (Eq. 7; the first minimum).
+    Returns (R [B, B], n, m) with m[k-1] = max|X R^1 ... R^k|."""
+    X = np.array(Xb, dtype=np.float64)
+    Qs = np.asarray(Qs, dtype=np.float64)
+    B = X.shape[1]
+    R = np.eye(B)
+    best_R, best_m, best_n = None, np.inf, 0
+    m = np.empty(len(Qs))
+    for k, Q in enumerate(Qs, start=1):
+        j = int(np.argmax(np.abs(X).max(axis=0)))          # first column holding the largest outlier
+        C1 = np.eye(B)
+        C1[:, [0, j]] = C1[:, [j, 0]]
+        Rk = C1 @ Q @ C1                                    # C2 = C1: the same swap undoes it
+        X = X @ Rk
+        R = R @ Rk
+        m[k - 1] = np.abs(X).max()
+        if m[k - 1] < best_m:
+            best_R, best_m, best_n = R.copy(), m[k - 1], k
+    return best_R, best_n, m
+
+
+def greedy_rotations(X_bf16, d, Qs, B=128):
+    """Eq. 6-7 block by block (the BlockDiag equation): R [K/B, B, B], n [K/B], on calibration
+    activations X (bf16 bits [Mc, K]) times the diagonal d."""
+    U = bf16_to_f64(_c(X_bf16, np.uint16))
+    if d is not None:
+        U = U * np.asarray(d, dtype=np.float32).astype(np.float64)
+    nb = U.shape[1] // B
+    Rs = np.empty((nb, B, B))
+    ns = np.empty(nb, dtype=np.int32)
+    for b in range(nb):
+        Rs[b], ns[b], _ = greedy_rotation(U[:, b * B:(b + 1) * B], Qs)
+    return Rs, ns
+
+
+def rotate_dense(X_bf16, d, Rs):
+    """V = (X diag(d)) BlockDiag(R_1 .. R_nb) as float64 (G_t of Eq. 10 with dense blocks)."""
+    U = bf16_to_f64(_c(X_bf16, np.uint16))
+    if d is not None:
+        U = U * np.asarray(d, dtype=np.float32).astype(np.float64)
+    Rs = np.asarray(Rs, dtype=np.float64)
+    B = Rs.shape[1]
+    V = np.empty_like(U)
+    for b in range(Rs.shape[0]):
+        V[:, b * B:(b + 1) * B] = U[:, b * B:(b + 1) * B] @ Rs[b]
+    return V
+
+
+def rotate_weights_dense(W, d, Rs):
+    """W' = BlockDiag(R_b)^T diag(1/d) W as float64 (H_t of Eq. 10 with dense blocks)."""
+    Wd = np.asarray(W, dtype=np.float32).astype(np.float64)
+    if d is not None:
+        Wd = Wd / np.asarray(d, dtype=np.float32).astype(np.float64)[:, None]
+    Rs = np.asarray(Rs, dtype=np.float64)
+    B = Rs.shape[1]
+    out = np.empty_like(Wd)
+    for b in range(Rs.shape[0]):
+        out[b * B:(b + 1) * B] = Rs[b].T @ Wd[b * B:(b + 1) * B]
+    return out
+
+
+def linear_dense(X_bf16, W, d, Rs, bias=None, wbits=8, exact_blas=False):
+    """Whole path with dense rotation blocks (float32 values of Rs, as the library takes them)."""
+    Rs = np.asarray(Rs, dtype=np.float32)
+    B = Rs.shape[1]
+    Xq, sx = quant_tokens(rotate_dense(X_bf16, d, Rs))
+    Wq, sw = quant_weights(rotate_weights_dense(W, d, Rs), wbits, B)
+    group = B if wbits == 4 else None
+    acc = (acc_exact_blas if exact_blas else igemm)(Xq, Wq, group)
+    Y, Yd = dequant(acc, sx, sw, bias, return_f64=True)
+    return dict(Xq=Xq, sx=sx, Wq=Wq, sw=sw, acc=acc, Y=Y, Yd=Yd)
+
+
 # ---- attention sharing (Sec. 3.3) ------------------------------------------------------------
 
 def cosine_similarity(A_bf16, B_bf16):

@@ -142,3 +142,18 @@ def small_case(seed, M, K, N, n_outliers=2, outlier=50.0, with_diag=True):
          else np.ones(K, dtype=np.float32))
     b = r.standard_normal(N, dtype=np.float32) * np.float32(0.1)
     return f32_to_bf16_bits(x), w, d, b
+
+
+def orthogonal_uniform_first_row(seed, n_mats, B=128):
+    """The random orthogonal matrices the greedy rotation search draws (Sec. 3.2): float64
+    [n_mats, B, B], each orthogonal with a first row of equal entries 1/sqrt(B).  Built from a
+    seeded Gaussian matrix whose first column is replaced by ones, orthonormalised (QR), transposed."""
+    r = np.random.default_rng(np.random.SeedSequence([77, seed, n_mats, B]))
+    out = np.empty((n_mats, B, B), dtype=np.float64)
+    for i in range(n_mats):
+        g = r.standard_normal((B, B))
+        g[:, 0] = 1.0
+        q, rr = np.linalg.qr(g)
+        q = q * np.sign(rr[0, 0])           # first column +1/sqrt(B) everywhere
+        out[i] = q.T
+    return out

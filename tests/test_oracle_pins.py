@@ -754,3 +754,96 @@ def test_share_plan(oracle):
     assert oracle.share_plan(sim, 0.5).tolist() == [1, 1, 1, 1]
     assert oracle.share_plan(sim, 0.96).tolist() == [1, 0, 0, 1]
     assert oracle.share_plan(sim, 1.0).tolist() == [0, 0, 0, 0]
+
+
+# ------------------------------------ greedy dense block rotations (Eq. 6-7)
+
+def test_dense_rotation_with_hadamard_blocks_is_the_fast_path(oracle):
+    Xb, W, d, _ = wl.small_case(23, 24, 256, 16)
+    Hn = oracle.hadamard(128).astype(np.float64) / np.sqrt(128.0)
+    Rs = np.stack([Hn, Hn])
+    assert np.allclose(oracle.rotate_dense(Xb, d, Rs), oracle.rotate(Xb, d, 128), rtol=0, atol=1e-9)
+    assert np.allclose(oracle.rotate_weights_dense(W, d, Rs), oracle.rotate_weights(W, d, 128), rtol=0, atol=1e-12)
+
+
+def test_dense_rotation_computational_invariance(oracle):
+    # non-symmetric orthogonal blocks: a transposed operand on either side breaks the identity
+    Xb, W, d, _ = wl.small_case(24, 20, 384, 24)
+    Rs = wl.orthogonal_uniform_first_row(1, 3)
+    assert np.abs(Rs[0] - Rs[0].T).max() > 0.1
+    V = oracle.rotate_dense(Xb, d, Rs)
+    Wp = oracle.rotate_weights_dense(W, d, Rs)
+    exact = oracle.bf16_to_f64(Xb) @ W.astype(np.float64)
+    assert np.allclose(V @ Wp, exact, rtol=0, atol=1e-9)
+    # block b of V only depends on block b of X
+    X2 = oracle.bf16_to_f64(Xb).copy(); X2[:, 128:256] = 0
+    V2 = oracle.rotate_dense(wl.f32_to_bf16_bits(X2.astype(np.float32)), d, Rs)
+    assert np.array_equal(V2[:, :128], V[:, :128]) and not V2[:, 128:256].any()
+
+
+def test_drawn_matrices_are_orthogonal_with_uniform_first_row():
+    Qs = wl.orthogonal_uniform_first_row(2, 4, 128)
+    for Q in Qs:
+        assert np.allclose(Q @ Q.T, np.eye(128), atol=1e-12)
+        assert np.allclose(Q[0], 1 / np.sqrt(128.0), atol=1e-12)
+
+
+def test_greedy_rotation_single_outlier_closed_form(oracle):
+    # one massive channel: C1 brings it to column 0, the uniform first row of Q spreads it evenly, so
+    # after one step every entry of a row has magnitude a / sqrt(B) (and C2 only moves two columns)
+    B, a = 128, 640.0
+    X = np.zeros((5, B)); X[:, 37] = a * np.array([1.0, -0.5, 0.25, 1.0, -1.0])
+    Qs = wl.orthogonal_uniform_first_row(3, 1, B)
+    R, n, m = oracle.greedy_rotation(X, Qs)
+    assert n == 1 and abs(m[0] - a / np.sqrt(B)) < 1e-9
+    assert np.allclose(np.abs(X @ R), np.abs(X[:, 37:38]) / np.sqrt(B) * np.ones((1, B)), atol=1e-9)
+
+
+def test_greedy_rotation_properties(oracle):
+    B, N = 128, 12
+    rng = np.random.default_rng(8)
+    X = rng.standard_normal((96, B)); X[:, [5, 77]] *= 60.0; X[3, 100] = 900.0
+    Qs = wl.orthogonal_uniform_first_row(4, N, B)
+    R, n, m = oracle.greedy_rotation(X, Qs)
+    assert np.allclose(R @ R.T, np.eye(B), atol=1e-10)              # a product of orthogonal matrices
+    assert 1 <= n <= N and m[n - 1] == m.min() and np.all(m[:n - 1] > m[n - 1])   # first minimum (Eq. 7)
+    assert abs(np.abs(X @ R).max() - m[n - 1]) < 1e-9
+    assert m[n - 1] < 0.25 * np.abs(X).max()                        # the outliers are gone
+    # Eq. 6 by hand for the first step: explicit switching matrices around Q_1
+    j = int(np.argmax(np.abs(X).max(axis=0)))
+    assert j == 100
+    C = np.eye(B); C[0, 0] = C[j, j] = 0; C[0, j] = C[j, 0] = 1
+    R1, n1, m1 = oracle.greedy_rotation(X, Qs[:1])
+    assert n1 == 1 and np.allclose(R1, C @ Qs[0] @ C, atol=1e-13)
+    # Frobenius norm (energy) is preserved
+    assert abs(np.linalg.norm(X @ R) - np.linalg.norm(X)) < 1e-8
+
+
+def test_greedy_rotation_small_block_brute_force(oracle):
+    # B = 4, two steps, every product written out element by element
+    B = 4
+    X = np.array([[1.0, -8.0, 0.5, 2.0], [0.25, 4.0, -1.0, 0.5]])
+    Qs = wl.orthogonal_uniform_first_row(5, 2, B)
+
+    def matmul(A, Bm):
+        out = [[0.0] * len(Bm[0]) for _ in A]
+        for i in range(len(A)):
+            for jj in range(len(Bm[0])):
+                out[i][jj] = sum(A[i][k] * Bm[k][jj] for k in range(len(Bm)))
+        return out
+
+    def swap_cols(A, j):
+        out = [row[:] for row in A]
+        for row in out:
+            row[0], row[j] = row[j], row[0]
+        return out
+    Xc, Rc, ms, Rs_ = X.tolist(), np.eye(B).tolist(), [], []
+    for Q in Qs:
+        col_max = [max(abs(row[j]) for row in Xc) for j in range(B)]
+        j = col_max.index(max(col_max))
+        Xc = swap_cols(matmul(swap_cols(Xc, j), Q.tolist()), j)      # X C1 Q C2
+        Rc = swap_cols(matmul(swap_cols(Rc, j), Q.tolist()), j)
+        ms.append(max(abs(v) for row in Xc for v in row)); Rs_.append(np.array(Rc))
+    R, n, m = oracle.greedy_rotation(X, Qs)
+    assert np.allclose(m, ms, atol=1e-14)
+    assert n == ms.index(min(ms)) + 1 and np.allclose(R, Rs_[n - 1], atol=1e-14)
