@@ -195,6 +195,32 @@ trdq_status trdq_weight_row_absmax(const float *W_dev, int K, int N, float *wmax
 trdq_status trdq_smooth_diag(const float *xmax_dev, const float *wmax_dev, int K, float alpha,
                              float *diag_dev, void *stream);
 
+/* ---------------------------------------------------- dense rotation blocks
+ * The BlockDiag equation of Sec. 3.2 with arbitrary orthogonal 128 x 128 blocks R_b in place of
+ * the Hadamard block (for example the greedy rotations of Eq. 6-7):
+ *   G_t(X) = (X . diag) . BlockDiag(R_b),   H_t(W) = BlockDiag(R_b)^T . (diag^-1 . W).
+ * trdq_rotation_create copies R_dev (float32 [K/128, 128, 128], block b row-major, (k, c) = the
+ * entry that takes input channel k to rotated channel c) and diag_dev (float32 [K], NULL = ones)
+ * and prepares the activation-side operand; the caller's arrays may be freed afterwards.  The
+ * blocks are taken as given: orthogonality is the caller's business (a non-orthogonal R changes
+ * the product).  Errors: NULL -> ERR_NULL; K <= 0, K % 128 -> ERR_SHAPE; block != 128 or
+ * K > 4608 -> ERR_UNSUPPORTED. */
+typedef struct trdq_rotation trdq_rotation;
+trdq_status trdq_rotation_create(const float *R_dev, const float *diag_dev, int K, int block, void *stream,
+                                 trdq_rotation **out);
+void trdq_rotation_destroy(trdq_rotation *r);
+
+/* trdq_prepare_weights with the rotation's blocks and diagonal (wbits 8, 6 or 4; layouts, handle
+ * and errors as trdq_prepare_weights; K != the rotation's K -> ERR_MISMATCH). */
+trdq_status trdq_prepare_weights_dense(const float *W_dev, int K, int N, const trdq_rotation *rot,
+                                       int wbits, void *stream, trdq_weights **out);
+
+/* trdq_rotate_quant with the rotation's blocks and diagonal: V = (X . diag) . BlockDiag(R_b),
+ * then the per-token symmetric int8 quantiser.  K is the rotation's; other arguments, layouts and
+ * errors as trdq_rotate_quant. */
+trdq_status trdq_rotate_quant_dense(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot,
+                                    int8_t *Xq_dev, float *sx_dev, void *stream);
+
 /* ------------------------------------------------- attention sharing (Sec. 3.3)
  * Eq. 11 between the attention outputs of the conditional and the unconditional pass:
  *   cos_dev[s] = A_s . B_s / (|A_s| |B_s|)   for s < n_seg;   0 where either vector is all zero.

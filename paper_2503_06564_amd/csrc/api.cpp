@@ -13,6 +13,7 @@ using trdq::Weights;
 
 struct trdq_table : Table {};
 struct trdq_weights : Weights {};
+struct trdq_rotation : trdq::Rotation {};
 
 struct trdq_layer {
     Table table;
@@ -121,7 +122,8 @@ namespace {
 // Shared body of the two weight-preparation entry points.  perm_dev == nullptr: H_t(W) of Eq. 10
 // with one rotation; otherwise the full H_t(W) of Eq. 9 (rotation, P^T, rotation).
 trdq_status prepare_weights_impl(const float *W_dev, int K, int N, const float *diag_dev, const int32_t *perm_dev,
-                                 int block, int wbits, void *stream, trdq_weights **out)
+                                 int block, int wbits, void *stream, trdq_weights **out,
+                                 const trdq::Rotation *rot = nullptr)
 {
     if (!out) return TRDQ_ERR_NULL;
     *out = nullptr;
@@ -151,12 +153,16 @@ trdq_status prepare_weights_impl(const float *W_dev, int K, int N, const float *
         rc = TRDQ_ERR_ALLOC;
         goto fail;
     }
-    ok = trdq::launch_prepare_rotate(W_dev, K, N, diag_dev, nullptr, Wrot, amax, st) == hipSuccess;
-    if (ok && perm_dev) {
+    if (rot) {
+        // dense orthonormal blocks: nothing to normalise afterwards
+        ok = trdq::launch_prepare_rotate_dense(W_dev, K, N, rot->diag, rot->R, Wrot, amax, st) == hipSuccess &&
+             trdq::launch_prepare_quant(Wrot, amax, K, N, qbits, 1.0f, w->codes, w->scales, st) == hipSuccess;
+    } else if (!(ok = trdq::launch_prepare_rotate(W_dev, K, N, diag_dev, nullptr, Wrot, amax, st) == hipSuccess)) {
+    } else if (perm_dev) {
         // rows gathered through the permutation, rotated again; two unnormalised rotations: 1/128
         ok = trdq::launch_prepare_rotate(Wrot, K, N, nullptr, perm_dev, Wrot2, amax, st) == hipSuccess &&
              trdq::launch_prepare_quant(Wrot2, amax, K, N, qbits, 0.0078125f, w->codes, w->scales, st) == hipSuccess;
-    } else if (ok) {
+    } else {
         ok = trdq::launch_prepare_quant(Wrot, amax, K, N, qbits, 0.08838834764831845f, w->codes, w->scales, st) == hipSuccess;
     }
     if (ok && wbits == 8) ok = trdq::launch_weight_colsum(w->codes, K, N, w->colsum, st) == hipSuccess;
@@ -187,6 +193,79 @@ trdq_status trdq_prepare_weights(const float *W_dev, int K, int N, const float *
                                  int block, int wbits, void *stream, trdq_weights **out)
 {
     return prepare_weights_impl(W_dev, K, N, diag_dev, nullptr, block, wbits, stream, out);
+}
+
+/* ---------------------------------------------------- dense rotation blocks */
+
+trdq_status trdq_rotation_create(const float *R_dev, const float *diag_dev, int K, int block, void *stream,
+                                 trdq_rotation **out)
+{
+    if (!out) return TRDQ_ERR_NULL;
+    *out = nullptr;
+    if (!R_dev) return TRDQ_ERR_NULL;
+    if (block != trdq::kBlock) return TRDQ_ERR_UNSUPPORTED;
+    if (K <= 0 || K % trdq::kBlock != 0) return TRDQ_ERR_SHAPE;
+    if (!trdq::rotate_quant_dense_supports(K)) return TRDQ_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    trdq_rotation *r = new (std::nothrow) trdq_rotation;
+    if (!r) return TRDQ_ERR_ALLOC;
+    r->K = K;
+    const size_t r_bytes = (size_t)K * trdq::kBlock * sizeof(float);
+    trdq_status rc = TRDQ_OK;
+    if (hipGetDevice(&r->device) != hipSuccess) { rc = TRDQ_ERR_HIP; goto fail; }
+    if (hipMalloc(reinterpret_cast<void **>(&r->R), r_bytes) != hipSuccess ||
+        hipMalloc(&r->pieces, trdq::rotation_pieces_bytes(K)) != hipSuccess ||
+        (diag_dev && hipMalloc(reinterpret_cast<void **>(&r->diag), (size_t)K * sizeof(float)) != hipSuccess)) {
+        rc = TRDQ_ERR_ALLOC;
+        goto fail;
+    }
+    if (hipMemcpyAsync(r->R, R_dev, r_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess ||
+        (diag_dev && hipMemcpyAsync(r->diag, diag_dev, (size_t)K * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) ||
+        trdq::launch_rotation_pieces(r->R, r->diag, K, r->pieces, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) {
+        rc = TRDQ_ERR_HIP;
+        goto fail;
+    }
+    *out = r;
+    return TRDQ_OK;
+fail:
+    (void)hipGetLastError();
+    if (r->R) (void)hipFree(r->R);
+    if (r->diag) (void)hipFree(r->diag);
+    if (r->pieces) (void)hipFree(r->pieces);
+    delete r;
+    return rc;
+}
+
+void trdq_rotation_destroy(trdq_rotation *r)
+{
+    if (!r) return;
+    if (r->R) (void)hipFree(r->R);
+    if (r->diag) (void)hipFree(r->diag);
+    if (r->pieces) (void)hipFree(r->pieces);
+    delete r;
+}
+
+trdq_status trdq_prepare_weights_dense(const float *W_dev, int K, int N, const trdq_rotation *rot,
+                                       int wbits, void *stream, trdq_weights **out)
+{
+    if (out) *out = nullptr;
+    if (!rot) return TRDQ_ERR_NULL;
+    if (K != rot->K) return TRDQ_ERR_MISMATCH;
+    return prepare_weights_impl(W_dev, K, N, nullptr, nullptr, trdq::kBlock, wbits, stream, out, rot);
+}
+
+trdq_status trdq_rotate_quant_dense(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot,
+                                    int8_t *Xq_dev, float *sx_dev, void *stream)
+{
+    if (!rot) return TRDQ_ERR_NULL;
+    trdq_status rc = check_rotate_args(X_dev, M, rot->K, ldx, trdq::kBlock);
+    if (rc != TRDQ_OK) return rc;
+    if (M > 0 && (!Xq_dev || !sx_dev)) return TRDQ_ERR_NULL;
+    if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4)) return TRDQ_ERR_SHAPE;
+    if (M == 0) return TRDQ_OK;
+    return hip_status(trdq::launch_rotate_quant_dense(static_cast<const uint16_t *>(X_dev), M, rot->K, ldx, rot->pieces,
+                                                      Xq_dev, sx_dev, static_cast<hipStream_t>(stream)));
 }
 
 trdq_status trdq_prepare_weights_rpr(const float *W_dev, int K, int N, const float *diag_dev,

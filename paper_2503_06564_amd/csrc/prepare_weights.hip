@@ -65,6 +65,53 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_rotate_kernel(
         amax[(size_t)b * N + n] = fmaxf(fmaxf(part[0][c], part[1][c]), fmaxf(part[2][c], part[3][c]));
 }
 
+// Kernel 1 with a dense rotation block in place of the butterflies (H_t(W) = R^T (Delta^-1 W) with
+// the blocks of the BlockDiag equation as arbitrary orthogonal matrices):
+//   Wrot[b*128 + j, n] = sum_k R_b[k][j] * W[b*128 + k, n] / d[b*128 + k]
+// Wave q of the workgroup produces rows j = 32 q .. 32 q + 31 of 64 columns; the row of R_b it
+// needs at step k is the same for all its lanes (scalar loads), the column of W comes from LDS.
+__global__ __launch_bounds__(kPrepThreads) void prepare_rotate_dense_kernel(
+    const float *__restrict__ W, int K, int N, const float *__restrict__ diag, const float *__restrict__ R,
+    float *__restrict__ Wrot, float *__restrict__ amax)
+{
+    __shared__ float tile[kBlock][kCols + 1];
+    __shared__ float part[4][kCols];
+    const int b = blockIdx.y;
+    const int n0 = blockIdx.x * kCols;
+    const int c = threadIdx.x % kCols;
+    const int q = __builtin_amdgcn_readfirstlane(threadIdx.x / kCols);     // 0..3, one wave each
+    const int n = n0 + c;
+    const bool col_ok = n < N;
+    for (int k = q; k < kBlock; k += 4) {
+        float w = 0.0f;
+        if (col_ok) {
+            w = W[(size_t)(b * kBlock + k) * N + n];
+            if (diag) w = w / diag[b * kBlock + k];
+        }
+        tile[k][c] = w;
+    }
+    __syncthreads();
+    float acc[32];
+#pragma unroll
+    for (int jj = 0; jj < 32; ++jj) acc[jj] = 0.0f;
+    const float *Rb = R + (size_t)b * kBlock * kBlock + 32 * q;
+    for (int k = 0; k < kBlock; ++k) {
+        const float w = tile[k][c];
+#pragma unroll
+        for (int jj = 0; jj < 32; ++jj) acc[jj] = __builtin_fmaf(Rb[k * kBlock + jj], w, acc[jj]);
+    }
+    float m = 0.0f;
+#pragma unroll
+    for (int jj = 0; jj < 32; ++jj) {
+        m = fmaxf(m, fabsf(acc[jj]));
+        if (col_ok) Wrot[(size_t)(b * kBlock + 32 * q + jj) * N + n] = acc[jj];
+    }
+    part[q][c] = m;
+    __syncthreads();
+    if (q == 0 && col_ok)
+        amax[(size_t)b * N + n] = fmaxf(fmaxf(part[0][c], part[1][c]), fmaxf(part[2][c], part[3][c]));
+}
+
 // Kernel 2: quantise and transpose one 128-row block of 64 columns into the K-contiguous
 // layouts the product kernels read (see Weights in trdq_internal.h).
 //   wbits 8: scale[n]    = max_b amax[b, n] * norm / 127   (qmax = 31 in the same layout: 6-bit codes)
@@ -166,6 +213,14 @@ hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag
 {
     dim3 grid((N + kCols - 1) / kCols, K / kBlock);
     hipLaunchKernelGGL(prepare_rotate_kernel, grid, dim3(kPrepThreads), 0, st, W, K, N, diag, perm, Wrot, amax);
+    return hipGetLastError();
+}
+
+hipError_t launch_prepare_rotate_dense(const float *W, int K, int N, const float *diag, const float *R,
+                                       float *Wrot, float *amax, hipStream_t st)
+{
+    dim3 grid((N + kCols - 1) / kCols, K / kBlock);
+    hipLaunchKernelGGL(prepare_rotate_dense_kernel, grid, dim3(kPrepThreads), 0, st, W, K, N, diag, R, Wrot, amax);
     return hipGetLastError();
 }
 

@@ -1,0 +1,230 @@
+// rotate_quant with dense rotation blocks: G_t(X) = (X . Delta) . BlockDiag(R_1 .. R_nb) (Eq. 10
+// with the blocks of the BlockDiag equation of Sec. 3.2 as arbitrary orthogonal 128 x 128 matrices,
+// e.g. the greedy ones of Eq. 6-7), followed by the per-token symmetric int8 quantiser.
+//
+// The rotation is a real contraction (128 x 128 per block and token), so it runs on the matrix
+// cores: out^T = R'^T . X^T per block with R' = diag(d_b) . R_b, v_mfma_f32_16x16x32_bf16.
+//   B operand: the raw bf16 activations, 16 tokens x 32 channels per instruction (a lane's 16-byte
+//              load is its operand: no conversion, no LDS).
+//   A operand: R'^T split EXACTLY into three bf16 pieces (8 + 8 + 8 mantissa bits; products with
+//              bf16 activations are exact in fp32), prepared once per rotation in the fragment
+//              order of the instruction.  The rows of an A tile are chosen so that a lane ends up
+//              with 32 consecutive output channels of one token: tile t, row 4g + j holds output
+//              channel 32 g + 4 t + j.
+// A wave rotates whole blocks of one group of 16 * TT tokens; the token maximum crosses the
+// workgroup through LDS, then the wave quantises and stores 32 bytes per lane and block.  The A pieces (96 KB per block) stream from L2;
+// with TT = 2 every piece load feeds two instructions.
+#include "device_utils.h"
+#include "trdq_internal.h"
+
+namespace trdq {
+
+namespace {
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+constexpr int kPiecesPerBlock = 3 * 4 * 8 * 64;       // 16-byte fragments per block: piece, k-step, tile, lane
+
+// pieces[(((b * 3 + p) * 4 + s) * 8 + t) * 64 + lane] = eight bf16: piece p of
+//   d[b*128 + k] * R_b[k][c],  k = 32 s + 8 (lane >> 4) + e (e = 0..7),  c = 32 (r >> 2) + 4 t + (r & 3), r = lane & 15
+__global__ __launch_bounds__(256) void rotation_pieces_kernel(const float *__restrict__ R, const float *__restrict__ diag,
+                                                              uint16_t *__restrict__ pieces)
+{
+    const int b = blockIdx.y;
+    const int idx = blockIdx.x * 256 + threadIdx.x;     // 0 .. 16383: (s, t, lane, e)
+    const int e = idx & 7, lane = (idx >> 3) & 63, t = (idx >> 9) & 7, s = idx >> 12;
+    const int r = lane & 15, g = lane >> 4;
+    const int k = 32 * s + 8 * g + e;
+    const int c = 32 * (r >> 2) + 4 * t + (r & 3);
+    float v = R[((size_t)b * kBlock + k) * kBlock + c];
+    if (diag) v *= diag[b * kBlock + k];
+    // exact three-way split by truncation
+    const uint32_t hi = __float_as_uint(v) & 0xFFFF0000u;
+    const float r1 = v - __uint_as_float(hi);
+    const uint32_t mid = __float_as_uint(r1) & 0xFFFF0000u;
+    const float r2 = r1 - __uint_as_float(mid);
+    const uint32_t lo = __float_as_uint(r2) & 0xFFFF0000u;
+    const size_t base = (size_t)b * kPiecesPerBlock * 8;
+    const size_t off = ((size_t)(s * 8 + t) * 64 + lane) * 8 + e;
+    pieces[base + off] = (uint16_t)(hi >> 16);
+    pieces[base + (size_t)1 * 4 * 8 * 64 * 8 + off] = (uint16_t)(mid >> 16);
+    pieces[base + (size_t)2 * 4 * 8 * 64 * 8 + off] = (uint16_t)(lo >> 16);
+}
+
+// One block of one token group: out[tt][t][j] = rotated channel 32 g + 4 t + j of token tile tt's
+// token l16 (this lane), amax[tt] = running maximum of |out|.  The twelve A fragments of tile t + 1
+// (three pieces x four k-steps) are requested while tile t is multiplied; the scheduling barriers
+// keep the compiler from requesting all 96 at once (which would not fit the register file).
+template <int TT>
+__device__ __forceinline__ void rotate_block_dense(const uint16_t *__restrict__ X, int64_t M, int64_t ldx,
+                                                   const uint4 *__restrict__ pieces, int b, int64_t tok0, int lane,
+                                                   float (&out)[TT][8][4], float (&amax)[TT])
+{
+    const int l16 = lane & 15, g = lane >> 4;
+    // B operands: token tile tt, k-step s: channels b*128 + 32 s + 8 g .. + 7 of token l16
+    v8bf xf[TT][4];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        int64_t token = tok0 + tt * 16 + l16;
+        if (token >= M) token = M - 1;                  // a repeated row: its results are not stored
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            union { uint4 u; v8bf v; } ld;
+            ld.u = *reinterpret_cast<const uint4 *>(X + token * ldx + b * kBlock + 32 * s + 8 * g);
+            xf[tt][s] = ld.v;
+        }
+    }
+    const uint4 *pb = pieces + (size_t)b * kPiecesPerBlock + lane;
+    uint4 fa[2][12];
+    auto request = [&](uint4 (&f)[12], int t) {
+#pragma unroll
+        for (int q = 0; q < 12; ++q) f[q] = pb[(q * 8 + t) * 64];      // q = piece * 4 + k-step
+    };
+    request(fa[0], 0);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        if (t + 1 < 8) request(fa[(t + 1) & 1], t + 1);
+        v4f acc[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) acc[tt] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 11; q >= 0; --q) {                 // smallest piece first
+            union { uint4 u; v8bf v; } a;
+            a.u = fa[t & 1][q];
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+                acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, xf[tt][q & 3], acc[tt], 0, 0, 0);
+        }
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                out[tt][t][jj] = acc[tt][jj];
+                amax[tt] = fmaxf(amax[tt], fabsf(acc[tt][jj]));
+            }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// 32 codes of one token and block -> 32 bytes at Xq[token][b*128 + 32 g]
+__device__ __forceinline__ void store_codes_dense(const float (&o)[8][4], float inv, int8_t *dst8)
+{
+    uint32_t c[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+        c[t] = pack4_low_bytes(quant_bits(o[t][0], inv), quant_bits(o[t][1], inv),
+                               quant_bits(o[t][2], inv), quant_bits(o[t][3], inv));
+    uint4 *dst = reinterpret_cast<uint4 *>(dst8);
+    dst[0] = make_uint4(c[0], c[1], c[2], c[3]);
+    dst[1] = make_uint4(c[4], c[5], c[6], c[7]);
+}
+
+// KEEP: a wave has one block (nb <= waves) and keeps its results in registers across the exchange
+// of the token maxima.  Otherwise (wide rows: several blocks per wave, whose results would not fit
+// the registers) a wave rotates its blocks twice: once for the maxima, once more to quantise.
+template <int TT, bool KEEP>
+__global__ __launch_bounds__(768) void rotate_quant_dense_kernel(
+    const uint16_t *__restrict__ X, int64_t M, int nb, int64_t ldx, const uint4 *__restrict__ pieces,
+    int8_t *__restrict__ Xq, float *__restrict__ sx)
+{
+    extern __shared__ float amax_s[];                   // [2][nw][16 * TT]
+    const int K = nb * kBlock;
+    const int nw = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+    constexpr int TOK = 16 * TT;
+    const int64_t groups = (M + TOK - 1) / TOK;
+    int parity = 0;
+
+    for (int64_t tg = blockIdx.x; tg < groups; tg += gridDim.x) {
+        const int64_t tok0 = tg * TOK;
+        float out[TT][8][4];
+        float amax[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) amax[tt] = 0.0f;
+        for (int b = wave; b < nb; b += nw)             // KEEP: at most one pass
+            rotate_block_dense<TT>(X, M, ldx, pieces, b, tok0, lane, out, amax);
+        // token maximum: over the four lane groups, then over the waves
+        float *const am = amax_s + parity * nw * TOK;
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            amax[tt] = fmaxf(amax[tt], __shfl_xor(amax[tt], 16));
+            amax[tt] = fmaxf(amax[tt], __shfl_xor(amax[tt], 32));
+            if (g == 0) am[wave * TOK + tt * 16 + l16] = amax[tt];
+        }
+        __syncthreads();
+        parity ^= 1;        // the next group writes the other buffer: one barrier per group
+        float inv[TT];
+        bool token_ok[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            float a = 0.0f;
+            for (int w = 0; w < nw; ++w) a = fmaxf(a, am[w * TOK + tt * 16 + l16]);
+            const int64_t token = tok0 + tt * 16 + l16;
+            token_ok[tt] = token < M;
+            inv[tt] = a > 0.0f ? 127.0f / a : 0.0f;
+            if (wave == 0 && g == 0 && token_ok[tt]) sx[token] = a / 127.0f;
+        }
+        if constexpr (KEEP) {
+            if (wave < nb) {
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+                    if (token_ok[tt])
+                        store_codes_dense(out[tt], inv[tt], Xq + (tok0 + tt * 16 + l16) * K + wave * kBlock + 32 * g);
+            }
+        } else {
+            for (int b = wave; b < nb; b += nw) {
+                float unused[TT];
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) unused[tt] = 0.0f;
+                rotate_block_dense<TT>(X, M, ldx, pieces, b, tok0, lane, out, unused);
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+                    if (token_ok[tt])
+                        store_codes_dense(out[tt], inv[tt], Xq + (tok0 + tt * 16 + l16) * K + b * kBlock + 32 * g);
+            }
+        }
+    }
+}
+
+template <int TT, bool KEEP>
+hipError_t launch_dense(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx, const uint4 *pieces,
+                        int8_t *Xq, float *sx, hipStream_t st)
+{
+    const int64_t groups = (M + 16 * TT - 1) / (16 * TT);
+    const int64_t grid = groups < 256 ? groups : 256;      // persistent: one workgroup per compute unit
+    const size_t smem = sizeof(float) * 2 * nw * 16 * TT;
+    hipLaunchKernelGGL((rotate_quant_dense_kernel<TT, KEEP>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
+                       X, M, nb, ldx, pieces, Xq, sx);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+size_t rotation_pieces_bytes(int K) { return (size_t)(K / kBlock) * kPiecesPerBlock * 16; }
+
+hipError_t launch_rotation_pieces(const float *R, const float *diag, int K, void *pieces, hipStream_t st)
+{
+    hipLaunchKernelGGL(rotation_pieces_kernel, dim3(64, K / kBlock), dim3(256), 0, st, R, diag,
+                       static_cast<uint16_t *>(pieces));
+    return hipGetLastError();
+}
+
+bool rotate_quant_dense_supports(int K) { return K % kBlock == 0 && K / kBlock <= 36; }
+
+hipError_t launch_rotate_quant_dense(const uint16_t *X, int64_t M, int K, int64_t ldx, const void *pieces,
+                                     int8_t *Xq, float *sx, hipStream_t st)
+{
+    if (M == 0) return hipSuccess;
+    const int nb = K / kBlock;
+    const uint4 *pc = static_cast<const uint4 *>(pieces);
+    // up to 12 blocks: a wave per block, two token tiles per piece load once there are enough
+    // tokens to keep every compute unit busy; wider rows: 12 waves sharing the blocks, two passes
+    if (nb <= 12)
+        return M >= 256 * 32 ? launch_dense<2, true>(X, M, nb, nb, ldx, pc, Xq, sx, st)
+                             : launch_dense<1, true>(X, M, nb, nb, ldx, pc, Xq, sx, st);
+    return launch_dense<1, false>(X, M, nb, 12, ldx, pc, Xq, sx, st);
+}
+
+}  // namespace trdq

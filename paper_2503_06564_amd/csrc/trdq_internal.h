@@ -26,6 +26,17 @@ struct Weights {
     int device = 0;
 };
 
+// Dense rotation blocks (the BlockDiag equation with arbitrary orthogonal blocks, e.g. Eq. 6-7):
+// the float32 blocks and the diagonal for the weight side, and the blocks with the diagonal folded
+// in, split into bf16 pieces in matrix-instruction fragment order, for the activation side.
+struct Rotation {
+    int K = 0;
+    float *R = nullptr;          // [K/128][128][128]
+    float *diag = nullptr;       // [K] or null (ones)
+    void *pieces = nullptr;
+    int device = 0;
+};
+
 struct Table {
     int n_steps = 0, n_groups = 0;
     int32_t *map = nullptr;
@@ -70,6 +81,13 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, con
 
 hipError_t launch_cosine_similarity(const uint16_t *A, const uint16_t *B, int n_seg, int64_t seg_len,
                                     int64_t stride_a, int64_t stride_b, double *acc_ws, float *out, hipStream_t st);
+size_t rotation_pieces_bytes(int K);
+hipError_t launch_rotation_pieces(const float *R, const float *diag, int K, void *pieces, hipStream_t st);
+bool rotate_quant_dense_supports(int K);
+hipError_t launch_rotate_quant_dense(const uint16_t *X, int64_t M, int K, int64_t ldx, const void *pieces,
+                                     int8_t *Xq, float *sx, hipStream_t st);
+hipError_t launch_prepare_rotate_dense(const float *W, int K, int N, const float *diag, const float *R,
+                                       float *Wrot, float *amax, hipStream_t st);
 bool fused_supports(int K);
 bool fused_pays(int64_t M, int K, int N, int wbits);
 hipError_t launch_linear_fused(const Weights &w, const uint16_t *X, int64_t M, int64_t ldx,

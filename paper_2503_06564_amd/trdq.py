@@ -25,6 +25,7 @@ SYMBOLS = [
     "trdq_channel_absmax", "trdq_weight_row_absmax", "trdq_smooth_diag",
     "trdq_rotate_quant_asym", "trdq_qgemm_asym", "trdq_rotate_quant_bits",
     "trdq_cosine_similarity", "trdq_share_plan",
+    "trdq_rotation_create", "trdq_rotation_destroy", "trdq_prepare_weights_dense", "trdq_rotate_quant_dense",
 ]
 
 _lib = None
@@ -77,6 +78,11 @@ def lib():
         L.trdq_rotate_quant_bits.argtypes = [p, i64, i32, i64, p, i32, i32, p, p, p, p]
         L.trdq_cosine_similarity.argtypes = [p, p, i32, i64, i64, i64, p, p, p]
         L.trdq_share_plan.argtypes = [p, i32, i32, C.c_float, p]
+        L.trdq_rotation_create.argtypes = [p, p, i32, i32, p, C.POINTER(p)]
+        L.trdq_rotation_destroy.argtypes = [p]
+        L.trdq_rotation_destroy.restype = None
+        L.trdq_prepare_weights_dense.argtypes = [p, i32, i32, p, i32, p, C.POINTER(p)]
+        L.trdq_rotate_quant_dense.argtypes = [p, i64, i64, p, p, p, p]
         L.trdq_qgemm_asym.argtypes = [p, p, p, p, i64, p, p, i64, p, p]
         L.trdq_channel_absmax.argtypes = [p, i64, i32, i64, p, i32, i32, p, p]
         L.trdq_weight_row_absmax.argtypes = [p, i32, i32, p, p]
@@ -262,6 +268,57 @@ def rotate_quant(X, diag, Xq, sx, block=BLOCK, stream=None, warm=None):
     else:
         _check(lib().trdq_rotate_quant_warm(_ptr(X), M, K, ldx, _ptr(diag), block, _ptr(Xq), _ptr(sx), warm.handle,
                                             _stream(stream)), "trdq_rotate_quant_warm")
+
+
+class Rotation:
+    """Dense rotation blocks R (float32 [K/128, 128, 128] on the device) with an optional diagonal."""
+
+    def __init__(self, R, diag=None, stream=None):
+        self.K = R.shape[0] * BLOCK
+        h = C.c_void_p()
+        _check(lib().trdq_rotation_create(_ptr(R), _ptr(diag), self.K, BLOCK, _stream(stream), C.byref(h)),
+               "trdq_rotation_create")
+        self.handle = h
+
+    def close(self):
+        if self.handle:
+            lib().trdq_rotation_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def prepare_weights_dense(W, rot, wbits=8, stream=None):
+    K, N = W.shape
+    h = C.c_void_p()
+    _check(lib().trdq_prepare_weights_dense(_ptr(W), K, N, rot.handle, wbits, _stream(stream), C.byref(h)),
+           "trdq_prepare_weights_dense")
+    return Weights(h)
+
+
+def rotate_quant_dense(X, rot, Xq, sx, stream=None):
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    _check(lib().trdq_rotate_quant_dense(_ptr(X), M, ldx, rot.handle, _ptr(Xq), _ptr(sx), _stream(stream)),
+           "trdq_rotate_quant_dense")
+
+
+def bind_rotate_quant_dense(X, rot, Xq, sx, stream=None):
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    f = lib().trdq_rotate_quant_dense
+    args = (C.c_void_p(_ptr(X)), C.c_int64(M), C.c_int64(ldx), rot.handle, C.c_void_p(_ptr(Xq)), C.c_void_p(_ptr(sx)),
+            C.c_void_p(_stream(stream)))
+
+    def call():
+        st = f(*args)
+        if st != OK:
+            raise TrdqError(st, "trdq_rotate_quant_dense")
+    return call
 
 
 def cosine_similarity(A, B, acc_ws, out, stream=None):

@@ -225,3 +225,16 @@ def test_attention_share_host_side(oracle):
     assert trdq.share_plan(sim, 0.95)[0] == 1 and trdq.share_plan(sim, 0.95)[5] == 0
     with pytest.raises(trdq.TrdqError):
         trdq.share_plan(sim, 1.5)
+
+
+def test_dense_rotation_argument_errors_before_any_gpu_call():
+    L = trdq.lib()
+    out = C.c_void_p()
+    assert L.trdq_rotation_create(None, None, 256, 128, None, C.byref(out)) == trdq.ERR_NULL
+    assert L.trdq_rotation_create(0x1000, None, 256, 128, None, None) == trdq.ERR_NULL
+    assert L.trdq_rotation_create(0x1000, None, 200, 128, None, C.byref(out)) == trdq.ERR_SHAPE
+    assert L.trdq_rotation_create(0x1000, None, 256, 64, None, C.byref(out)) == trdq.ERR_UNSUPPORTED
+    assert L.trdq_rotation_create(0x1000, None, 128 * 37, 128, None, C.byref(out)) == trdq.ERR_UNSUPPORTED
+    assert L.trdq_rotate_quant_dense(0x1000, 4, 256, None, 0x2000, 0x3000, None) == trdq.ERR_NULL
+    assert L.trdq_prepare_weights_dense(0x1000, 256, 64, None, 8, None, C.byref(out)) == trdq.ERR_NULL
+    L.trdq_rotation_destroy(None)

@@ -1,0 +1,119 @@
+"""GPU parity of the dense-block rotation path (the BlockDiag equation with arbitrary orthogonal
+blocks, e.g. the greedy rotations of Eq. 6-7): trdq_rotation_create, trdq_rotate_quant_dense,
+trdq_prepare_weights_dense and the unchanged product."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_06564_amd import trdq, workloads as wl
+from gpu_util import (assert_codes_close, assert_scales_close, assert_y_close, bf16_to_dev, bf16_to_host,
+                      dev, f32_to_dev)
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def _blocks(seed, K):
+    """float32 orthogonal blocks [K/128, 128, 128] (non-symmetric)."""
+    return wl.orthogonal_uniform_first_row(seed, K // 128).astype(np.float32)
+
+
+def _rq_dense(Xbits, rot):
+    M, K = Xbits.shape
+    Xq = torch.full((M, K), 99, dtype=torch.int8, device=dev())
+    sx = torch.full((M,), -1.0, dtype=torch.float32, device=dev())
+    trdq.rotate_quant_dense(bf16_to_dev(Xbits), rot, Xq, sx)
+    torch.cuda.synchronize()
+    return Xq, sx
+
+
+@pytest.mark.parametrize("M,K", [(1, 128), (37, 256), (300, 1152), (40, 2304), (64, 4608), (8200, 1152), (0, 256)])
+def test_rotate_quant_dense_matches_oracle(oracle, M, K):
+    say(f"rotate_quant_dense M={M} K={K}")
+    Xb, _, d, _ = wl.small_case(61, max(M, 1), K, 16, n_outliers=max(1, K // 144), outlier=40.0)
+    Xb = Xb[:M]
+    Rs = _blocks(K, K)
+    rot = trdq.Rotation(f32_to_dev(Rs.reshape(-1, 128)).view(-1, 128, 128), f32_to_dev(d))
+    Xq, sx = _rq_dense(Xb, rot)
+    if M:
+        Xq_o, sx_o = oracle.quant_tokens(oracle.rotate_dense(Xb, d, Rs))
+        assert_codes_close(Xq.cpu().numpy(), Xq_o, "Xq (dense blocks)")
+        assert_scales_close(sx.cpu().numpy(), sx_o, "s_x (dense blocks)")
+    rot.close()
+
+
+def test_dense_path_with_hadamard_blocks_agrees_with_the_fast_path(oracle):
+    M, K = 200, 1152
+    Xb, _, d, _ = wl.small_case(62, M, K, 16, n_outliers=8)
+    Hn = (oracle.hadamard(128).astype(np.float64) / np.sqrt(128.0)).astype(np.float32)
+    Rs = np.stack([Hn] * (K // 128))
+    rot = trdq.Rotation(f32_to_dev(Rs.reshape(-1, 128)).view(-1, 128, 128), f32_to_dev(d))
+    Xq, sx = _rq_dense(Xb, rot)
+    Xq2 = torch.empty_like(Xq); sx2 = torch.empty_like(sx)
+    trdq.rotate_quant(bf16_to_dev(Xb), f32_to_dev(d), Xq2, sx2)
+    torch.cuda.synchronize()
+    # 1/sqrt(128) is not a float32 number: the dense blocks carry its rounding, codes may differ by one LSB rarely
+    assert_codes_close(Xq.cpu().numpy(), Xq2.cpu().numpy(), "dense Hadamard blocks vs butterflies")
+    assert_scales_close(sx.cpu().numpy(), sx2.cpu().numpy().astype(np.float64), "s_x")
+    rot.close()
+
+
+@pytest.mark.parametrize("M,K,N,wbits", [(17, 256, 144, 8), (300, 1152, 272, 8), (256, 1152, 288, 8), (64, 384, 160, 4),
+                                         (130, 1152, 144, 6)])
+def test_dense_linear_end_to_end(oracle, M, K, N, wbits):
+    say(f"dense-block linear M={M} K={K} N={N} wbits={wbits}")
+    Xb, W, d, bias = wl.small_case(63, M, K, N, n_outliers=max(1, K // 144), outlier=40.0)
+    Rs = _blocks(7 + K, K)
+    rot = trdq.Rotation(f32_to_dev(Rs.reshape(-1, 128)).view(-1, 128, 128), f32_to_dev(d))
+    w = trdq.prepare_weights_dense(f32_to_dev(W), rot, wbits=wbits)
+    ref = oracle.linear_dense(Xb, W, d, Rs, bias, wbits=wbits, exact_blas=True)
+    codes, scales = w.export()
+    assert_codes_close(codes, ref["Wq"], "Wq (dense blocks)")
+    assert_scales_close(scales, ref["sw"], "s_w (dense blocks)")
+    Xq, sx = _rq_dense(Xb, rot)
+    assert_codes_close(Xq.cpu().numpy(), ref["Xq"], "Xq (dense blocks)")
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device=dev())
+    trdq.qgemm(w, Xq, sx, Y, bias=f32_to_dev(bias))
+    torch.cuda.synchronize()
+    rows = np.any(Xq.cpu().numpy() != ref["Xq"], axis=1)
+    cols = np.any(codes != ref["Wq"], axis=0)
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (dense blocks)", skip_rows=rows, skip_cols=cols)
+    # the rotation cancels: close to the unquantised product as well
+    exact = oracle.bf16_to_f64(Xb) @ W.astype(np.float64) + bias
+    err = np.abs(oracle.bf16_to_f64(bf16_to_host(Y)) - exact).mean() / np.abs(exact).mean()
+    assert err < {8: 0.04, 6: 0.12, 4: 0.4}[wbits], err
+    w.close(); rot.close()
+
+
+def test_greedy_blocks_from_the_oracle_run_on_the_gpu(oracle):
+    # Eq. 6-7 on calibration activations (oracle), applied by the GPU path to fresh activations
+    K, N, M = 256, 144, 96
+    Xcal, W, d, bias = wl.small_case(64, 128, K, N, n_outliers=3, outlier=60.0)
+    Qs = wl.orthogonal_uniform_first_row(9, 8)
+    Rs, ns = oracle.greedy_rotations(Xcal, d, Qs)
+    Rs32 = Rs.astype(np.float32)
+    Xb = wl.small_case(65, M, K, N, n_outliers=0)[0]
+    Xf = oracle.bf16_to_f64(Xb); Xf[:, :] += oracle.bf16_to_f64(Xcal[:M]) * 0.5       # same outlier channels
+    Xb = wl.f32_to_bf16_bits(Xf.astype(np.float32))
+    rot = trdq.Rotation(f32_to_dev(Rs32.reshape(-1, 128)).view(-1, 128, 128), f32_to_dev(d))
+    Xq, sx = _rq_dense(Xb, rot)
+    Xq_o, sx_o = oracle.quant_tokens(oracle.rotate_dense(Xb, d, Rs32))
+    assert_codes_close(Xq.cpu().numpy(), Xq_o, "Xq (greedy blocks)")
+    assert_scales_close(sx.cpu().numpy(), sx_o, "s_x (greedy blocks)")
+    rot.close()
+
+
+def test_dense_argument_errors():
+    R = torch.zeros((2, 128, 128), device=dev())
+    rot = trdq.Rotation(R)
+    X = torch.zeros((4, 384), dtype=torch.bfloat16, device=dev())      # K of the input != K of the rotation
+    Xq = torch.zeros((4, 384), dtype=torch.int8, device=dev())
+    sx = torch.zeros((4,), device=dev())
+    W = torch.zeros((384, 32), device=dev())
+    with pytest.raises(trdq.TrdqError) as e:
+        trdq.prepare_weights_dense(W, rot)
+    assert e.value.status == trdq.ERR_MISMATCH
+    rot.close()
