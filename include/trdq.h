@@ -210,6 +210,22 @@ trdq_status trdq_rotation_create(const float *R_dev, const float *diag_dev, int 
                                  trdq_rotation **out);
 void trdq_rotation_destroy(trdq_rotation *r);
 
+/* The greedy construction of the blocks (Eq. 6-7), block by block on calibration activations
+ * X_dev (bf16 [M, K], row stride ldx) times diag_dev (NULL = ones):
+ *   step k: C1 swaps column 0 with the first column holding the largest |activation| of the block,
+ *           R^k = C1 Q_k C2 with C2 undoing the swap, X <- X R^k;
+ *   R_b = R^1 ... R^n,  n = the first k in 1..n_steps with the smallest max|X R^1 ... R^k|.
+ * Q_dev: float64 [n_steps, 128, 128] on the device, the orthogonal matrices the method draws (each
+ * with a first row of equal entries; the same sequence serves every block); they are inputs.
+ * R_dev: float32 [K/128, 128, 128] on the device (written: what trdq_rotation_create takes).
+ * n_host: int32 [K/128] on the host (written, may be NULL).  Runs in float64; allocates its
+ * workspace (8 M K bytes and a little) and synchronises the stream.
+ * Errors: as trdq_rotate_quant for X; NULL Q/R -> ERR_NULL; M <= 0 or n_steps <= 0 -> ERR_SHAPE;
+ * n_steps > 4096 or M K > 5e8 -> ERR_UNSUPPORTED. */
+trdq_status trdq_greedy_rotation(const void *X_dev, int64_t M, int K, int64_t ldx, const float *diag_dev,
+                                 int block, const double *Q_dev, int n_steps, float *R_dev, int32_t *n_host,
+                                 void *stream);
+
 /* trdq_prepare_weights with the rotation's blocks and diagonal (wbits 8, 6 or 4; layouts, handle
  * and errors as trdq_prepare_weights; K != the rotation's K -> ERR_MISMATCH). */
 trdq_status trdq_prepare_weights_dense(const float *W_dev, int K, int N, const trdq_rotation *rot,

@@ -237,6 +237,41 @@ fail:
     return rc;
 }
 
+trdq_status trdq_greedy_rotation(const void *X_dev, int64_t M, int K, int64_t ldx, const float *diag_dev,
+                                 int block, const double *Q_dev, int n_steps, float *R_dev, int32_t *n_host,
+                                 void *stream)
+{
+    trdq_status rc = check_rotate_args(X_dev, M, K, ldx, block);
+    if (rc != TRDQ_OK) return rc;
+    if (!Q_dev || !R_dev) return TRDQ_ERR_NULL;
+    if (M <= 0 || n_steps <= 0) return TRDQ_ERR_SHAPE;
+    if (n_steps > 4096 || (double)M * K * 8.0 > 4.0e9) return TRDQ_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int nb = K / trdq::kBlock;
+    void *ws = nullptr;
+    int *n_dev = nullptr;
+    if (hipMalloc(&ws, trdq::greedy_workspace_bytes(M, K)) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&n_dev), sizeof(int) * (size_t)nb) != hipSuccess) {
+        (void)hipGetLastError();
+        if (ws) (void)hipFree(ws);
+        return TRDQ_ERR_ALLOC;
+    }
+    std::vector<int> n_tmp((size_t)nb, 0);
+    bool ok = trdq::launch_greedy_rotation(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev, Q_dev, n_steps, ws,
+                                           R_dev, n_dev, st) == hipSuccess &&
+              hipMemcpyAsync(n_tmp.data(), n_dev, sizeof(int) * (size_t)nb, hipMemcpyDeviceToHost, st) == hipSuccess &&
+              hipStreamSynchronize(st) == hipSuccess;
+    (void)hipFree(ws);
+    (void)hipFree(n_dev);
+    if (!ok) {
+        (void)hipGetLastError();
+        return TRDQ_ERR_HIP;
+    }
+    if (n_host)
+        for (int b = 0; b < nb; ++b) n_host[b] = n_tmp[(size_t)b];
+    return TRDQ_OK;
+}
+
 void trdq_rotation_destroy(trdq_rotation *r)
 {
     if (!r) return;

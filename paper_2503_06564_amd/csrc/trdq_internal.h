@@ -81,6 +81,10 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, con
 
 hipError_t launch_cosine_similarity(const uint16_t *A, const uint16_t *B, int n_seg, int64_t seg_len,
                                     int64_t stride_a, int64_t stride_b, double *acc_ws, float *out, hipStream_t st);
+size_t greedy_workspace_bytes(int64_t Mc, int K);
+hipError_t launch_greedy_rotation(const uint16_t *X, int64_t Mc, int K, int64_t ldx, const float *diag,
+                                  const double *Q, int n_steps, void *workspace, float *R_out, int *n_out_dev,
+                                  hipStream_t st);
 size_t rotation_pieces_bytes(int K);
 hipError_t launch_rotation_pieces(const float *R, const float *diag, int K, void *pieces, hipStream_t st);
 bool rotate_quant_dense_supports(int K);

@@ -26,6 +26,7 @@ SYMBOLS = [
     "trdq_rotate_quant_asym", "trdq_qgemm_asym", "trdq_rotate_quant_bits",
     "trdq_cosine_similarity", "trdq_share_plan",
     "trdq_rotation_create", "trdq_rotation_destroy", "trdq_prepare_weights_dense", "trdq_rotate_quant_dense",
+    "trdq_greedy_rotation",
 ]
 
 _lib = None
@@ -83,6 +84,7 @@ def lib():
         L.trdq_rotation_destroy.restype = None
         L.trdq_prepare_weights_dense.argtypes = [p, i32, i32, p, i32, p, C.POINTER(p)]
         L.trdq_rotate_quant_dense.argtypes = [p, i64, i64, p, p, p, p]
+        L.trdq_greedy_rotation.argtypes = [p, i64, i32, i64, p, i32, p, i32, p, p, p]
         L.trdq_qgemm_asym.argtypes = [p, p, p, p, i64, p, p, i64, p, p]
         L.trdq_channel_absmax.argtypes = [p, i64, i32, i64, p, i32, i32, p, p]
         L.trdq_weight_row_absmax.argtypes = [p, i32, i32, p, p]
@@ -290,6 +292,18 @@ class Rotation:
             self.close()
         except Exception:
             pass
+
+
+def greedy_rotation(X, diag, Q, R_out, block=BLOCK, stream=None):
+    """Eq. 6-7 per block: X bf16 [M, K], Q float64 [n_steps, 128, 128], R_out float32 [K/128, 128, 128] (written).
+    Returns the chosen step counts as a numpy int32 array [K/128]."""
+    import numpy as np
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    n = np.zeros(K // block, dtype=np.int32)
+    _check(lib().trdq_greedy_rotation(_ptr(X), M, K, ldx, _ptr(diag), block, _ptr(Q), Q.shape[0], _ptr(R_out),
+                                      n.ctypes.data, _stream(stream)), "trdq_greedy_rotation")
+    return n
 
 
 def prepare_weights_dense(W, rot, wbits=8, stream=None):

@@ -238,3 +238,14 @@ def test_dense_rotation_argument_errors_before_any_gpu_call():
     assert L.trdq_rotate_quant_dense(0x1000, 4, 256, None, 0x2000, 0x3000, None) == trdq.ERR_NULL
     assert L.trdq_prepare_weights_dense(0x1000, 256, 64, None, 8, None, C.byref(out)) == trdq.ERR_NULL
     L.trdq_rotation_destroy(None)
+
+
+def test_greedy_rotation_argument_errors_before_any_gpu_call():
+    L = trdq.lib()
+    call = L.trdq_greedy_rotation
+    assert call(0x1000, 16, 256, 256, None, 128, None, 4, 0x3000, None, None) == trdq.ERR_NULL
+    assert call(0x1000, 16, 256, 256, None, 128, 0x2000, 4, None, None, None) == trdq.ERR_NULL
+    assert call(0x1000, 16, 200, 256, None, 128, 0x2000, 4, 0x3000, None, None) == trdq.ERR_SHAPE
+    assert call(0x1000, 0, 256, 256, None, 128, 0x2000, 4, 0x3000, None, None) == trdq.ERR_SHAPE
+    assert call(0x1000, 16, 256, 256, None, 128, 0x2000, 0, 0x3000, None, None) == trdq.ERR_SHAPE
+    assert call(0x1000, 16, 256, 256, None, 128, 0x2000, 5000, 0x3000, None, None) == trdq.ERR_UNSUPPORTED

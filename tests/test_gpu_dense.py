@@ -117,3 +117,53 @@ def test_dense_argument_errors():
         trdq.prepare_weights_dense(W, rot)
     assert e.value.status == trdq.ERR_MISMATCH
     rot.close()
+
+
+@pytest.mark.parametrize("Mc,K,n_steps", [(128, 256, 8), (1000, 1152, 16), (37, 128, 1), (300, 384, 40)])
+def test_greedy_rotation_matches_oracle(oracle, Mc, K, n_steps):
+    say(f"greedy rotation Mc={Mc} K={K} steps={n_steps}")
+    Xcal, _, d, _ = wl.small_case(66, Mc, K, 16, n_outliers=max(2, K // 100), outlier=60.0)
+    Qs = wl.orthogonal_uniform_first_row(10, n_steps)
+    R = torch.zeros((K // 128, 128, 128), dtype=torch.float32, device=dev())
+    n = trdq.greedy_rotation(bf16_to_dev(Xcal), f32_to_dev(d), torch.from_numpy(Qs).to(dev()), R)
+    torch.cuda.synchronize()
+    Rs, ns = oracle.greedy_rotations(Xcal, d, Qs)
+    assert np.array_equal(n, ns), (n, ns)
+    Rg = R.cpu().numpy().astype(np.float64)
+    assert np.abs(Rg - Rs).max() < 1e-6          # float64 on both sides, stored as float32
+    for b in range(K // 128):
+        assert np.abs(Rg[b] @ Rg[b].T - np.eye(128)).max() < 1e-5
+    # and the blocks do what they are for: the largest rotated calibration activation is what the oracle says
+    U = oracle.bf16_to_f64(Xcal) * d.astype(np.float64)
+    for b in range(K // 128):
+        got = np.abs(U[:, b * 128:(b + 1) * 128] @ Rg[b]).max()
+        _, _, m = oracle.greedy_rotation(U[:, b * 128:(b + 1) * 128], Qs)
+        assert abs(got - m[ns[b] - 1]) <= 1e-5 * m[ns[b] - 1]
+
+
+def test_greedy_rotation_end_to_end_beats_no_rotation(oracle):
+    # calibrate on one batch, run the rotated linear on another with the same outlier channels
+    K, N, M = 384, 144, 200
+    Xcal, W, d, bias = wl.small_case(67, 256, K, N, n_outliers=4, outlier=80.0)
+    Qs = wl.orthogonal_uniform_first_row(11, 24)
+    R = torch.zeros((K // 128, 128, 128), dtype=torch.float32, device=dev())
+    trdq.greedy_rotation(bf16_to_dev(Xcal), f32_to_dev(d), torch.from_numpy(Qs).to(dev()), R)
+    rot = trdq.Rotation(R, f32_to_dev(d))
+    w = trdq.prepare_weights_dense(f32_to_dev(W), rot, wbits=8)
+    Xf = oracle.bf16_to_f64(Xcal[:M]) * np.random.default_rng(3).uniform(0.5, 1.5, (M, 1))
+    Xb = wl.f32_to_bf16_bits(Xf.astype(np.float32))
+    Xq, sx = _rq_dense(Xb, rot)
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device=dev())
+    trdq.qgemm(w, Xq, sx, Y, bias=f32_to_dev(bias))
+    torch.cuda.synchronize()
+    ref = oracle.linear_dense(Xb, W, d, R.cpu().numpy(), bias, exact_blas=True)
+    rows = np.any(Xq.cpu().numpy() != ref["Xq"], axis=1)
+    cols = np.any(w.export()[0] != ref["Wq"], axis=0)
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (greedy blocks)", skip_rows=rows, skip_cols=cols)
+    exact = oracle.bf16_to_f64(Xb) @ W.astype(np.float64) + bias
+    err_rot = np.abs(oracle.bf16_to_f64(bf16_to_host(Y)) - exact).mean()
+    # the same W8A8 quantisers without any rotation (identity blocks) lose much more to the outliers
+    eye = np.stack([np.eye(128, dtype=np.float32)] * (K // 128))
+    err_plain = np.abs(oracle.linear_dense(Xb, W, d, eye, bias)["Yd"] - exact).mean()
+    assert err_rot < 0.5 * err_plain, (err_rot, err_plain)
+    w.close(); rot.close()
