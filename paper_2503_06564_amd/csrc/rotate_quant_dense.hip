@@ -122,8 +122,8 @@ __device__ __forceinline__ void store_codes_dense(const float (&o)[8][4], float 
 // KEEP: a wave has one block (nb <= waves) and keeps its results in registers across the exchange
 // of the token maxima.  Otherwise (wide rows: several blocks per wave, whose results would not fit
 // the registers) a wave rotates its blocks twice: once for the maxima, once more to quantise.
-template <int TT, bool KEEP>
-__global__ __launch_bounds__(768) void rotate_quant_dense_kernel(
+template <int TT, bool KEEP, int MAXT>
+__global__ __launch_bounds__(MAXT) void rotate_quant_dense_kernel(
     const uint16_t *__restrict__ X, int64_t M, int nb, int64_t ldx, const uint4 *__restrict__ pieces,
     int8_t *__restrict__ Xq, float *__restrict__ sx)
 {
@@ -188,14 +188,14 @@ __global__ __launch_bounds__(768) void rotate_quant_dense_kernel(
     }
 }
 
-template <int TT, bool KEEP>
+template <int TT, bool KEEP, int MAXT = 768>
 hipError_t launch_dense(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx, const uint4 *pieces,
                         int8_t *Xq, float *sx, hipStream_t st)
 {
     const int64_t groups = (M + 16 * TT - 1) / (16 * TT);
     const int64_t grid = groups < 256 ? groups : 256;      // persistent: one workgroup per compute unit
     const size_t smem = sizeof(float) * 2 * nw * 16 * TT;
-    hipLaunchKernelGGL((rotate_quant_dense_kernel<TT, KEEP>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
+    hipLaunchKernelGGL((rotate_quant_dense_kernel<TT, KEEP, MAXT>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
                        X, M, nb, ldx, pieces, Xq, sx);
     return hipGetLastError();
 }
@@ -224,7 +224,9 @@ hipError_t launch_rotate_quant_dense(const uint16_t *X, int64_t M, int K, int64_
     if (nb <= 12)
         return M >= 256 * 32 ? launch_dense<2, true>(X, M, nb, nb, ldx, pc, Xq, sx, st)
                              : launch_dense<1, true>(X, M, nb, nb, ldx, pc, Xq, sx, st);
-    return launch_dense<1, false>(X, M, nb, 12, ldx, pc, Xq, sx, st);
+    // (with many tokens: eight waves, which leaves the registers for two token tiles per piece load)
+    return M >= 8192 ? launch_dense<2, false, 512>(X, M, nb, 8, ldx, pc, Xq, sx, st)
+                     : launch_dense<1, false>(X, M, nb, 12, ldx, pc, Xq, sx, st);
 }
 
 }  // namespace trdq

@@ -30,7 +30,9 @@ def _rq_dense(Xbits, rot):
     return Xq, sx
 
 
-@pytest.mark.parametrize("M,K", [(1, 128), (37, 256), (300, 1152), (40, 2304), (64, 4608), (8200, 1152), (0, 256)])
+# one block per wave with one and (from 8192 tokens) two token tiles; wide rows (more than 12 blocks) likewise
+@pytest.mark.parametrize("M,K", [(1, 128), (37, 256), (300, 1152), (40, 2304), (64, 4608), (8200, 1152), (8200, 1664),
+                                 (0, 256)])
 def test_rotate_quant_dense_matches_oracle(oracle, M, K):
     say(f"rotate_quant_dense M={M} K={K}")
     Xb, _, d, _ = wl.small_case(61, max(M, 1), K, 16, n_outliers=max(1, K // 144), outlier=40.0)
