@@ -192,3 +192,108 @@ def test_rpr_full_size_sampled_rows(oracle, cfg_id, kind, step):
     cols_diff = (codes != ref["Wq"]).any(axis=0)
     gu.assert_y_close(gu.bf16_to_host(Y[idx]), ref["Y"], f"{kind} Y (R P R)", rows_diff, cols_diff)
     w.close()
+
+
+# ---- asymmetric activations, W6A6 and dense rotation blocks at workload sizes (sampled rows) ----
+
+@pytest.mark.parametrize("cfg_id,kind,step", [(1, "qkv", 0), (1, "proj", 3), (1, "fc1", 7), (1, "fc2", 7), (3, "fc1", 19)])
+def test_asym_full_size_sampled_rows(oracle, cfg_id, kind, step):
+    cfg = wl.CONFIGS[cfg_id]
+    say(f"config {cfg_id}: asymmetric activations {kind} step {step}, M={cfg.M}")
+    K, N = wl.LAYER_SHAPES[kind]
+    g = wl.step_to_group(cfg, step)
+    Xb = wl.make_x(cfg, kind, step)
+    M = Xb.shape[0]
+    W, d, bias = wl.make_w(cfg, kind), wl.make_diag(cfg, kind, g), wl.make_bias(cfg, kind)
+    dd = gu.f32_to_dev(d)
+    w = trdq.prepare_weights(gu.f32_to_dev(W), dd, wbits=8)
+    Xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+    sx = torch.empty((M,), dtype=torch.float32, device="cuda")
+    zc = torch.empty((M,), dtype=torch.int32, device="cuda")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    trdq.rotate_quant_asym(gu.bf16_to_dev(Xb), dd, Xq, sx, zc, warm=w)
+    trdq.qgemm_asym(w, Xq, sx, zc, Y, bias=gu.f32_to_dev(bias))
+    torch.cuda.synchronize()
+    # all tokens: both ends of the code range are used (the range contains zero), zero points in range
+    assert bool((Xq.amax(dim=1)[sx > 0] == 127).all()) and bool((Xq.amin(dim=1)[sx > 0] == -128).all())
+    assert bool(((zc >= -127) & (zc <= 128)).all()) and bool(torch.isfinite(Y.float()).all())
+    rows = sample_rows(M, 77 * cfg.cfg + step)
+    idx = torch.from_numpy(rows).cuda()
+    ref = oracle.linear_asym(Xb[rows], W, d, bias, exact_blas=True)
+    q = Xq[idx].cpu().numpy().astype(np.int16) + 128
+    z = 128 - zc[idx].cpu().numpy()
+    shifted = z != ref["zx"]
+    assert np.abs(z - ref["zx"]).max() <= 1 and shifted.sum() <= 1
+    gu.assert_codes_close(q[~shifted], ref["Xq"][~shifted], f"{kind} Xq (asymmetric)")
+    gu.assert_scales_close(sx[idx].cpu().numpy(), ref["sx"], f"{kind} s_x (asymmetric)")
+    codes, scales = w.export()
+    rows_diff = (q != ref["Xq"]).any(axis=1) | shifted
+    cols_diff = (codes != ref["Wq"]).any(axis=0)
+    gu.assert_y_close(gu.bf16_to_host(Y[idx]), ref["Y"], f"{kind} Y (asymmetric)", rows_diff, cols_diff)
+    # identical codes and zero points: the integer sums, then the epilogue, in float64
+    acc = oracle.acc_asym_exact_blas(q.astype(np.uint8), z.astype(np.int32), codes)
+    want = gu.bits_to_f64(oracle.dequant(acc, sx[idx].cpu().numpy(), scales, bias))
+    got = gu.bits_to_f64(gu.bf16_to_host(Y[idx]))
+    row = np.abs(want).max(axis=1, keepdims=True)
+    assert np.all(np.abs(got - want) <= np.abs(want) * 2.0 ** -7 + row * 1e-5)
+    w.close()
+
+
+@pytest.mark.parametrize("kind", ["proj", "fc2"])
+def test_w6a6_full_size_sampled_rows(oracle, kind):
+    cfg = wl.CONFIGS[1]
+    say(f"config 1: W6A6 {kind}, M={cfg.M}")
+    K, N = wl.LAYER_SHAPES[kind]
+    Xb = wl.make_x(cfg, kind, 2)
+    M = Xb.shape[0]
+    W, d, bias = wl.make_w(cfg, kind), wl.make_diag(cfg, kind, wl.step_to_group(cfg, 2)), wl.make_bias(cfg, kind)
+    dd = gu.f32_to_dev(d)
+    w = trdq.prepare_weights(gu.f32_to_dev(W), dd, wbits=6)
+    Xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+    sx = torch.empty((M,), dtype=torch.float32, device="cuda")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    trdq.rotate_quant_bits(gu.bf16_to_dev(Xb), dd, Xq, sx, 6, warm=w)
+    trdq.qgemm(w, Xq, sx, Y, bias=gu.f32_to_dev(bias))
+    torch.cuda.synchronize()
+    assert bool((Xq.abs().amax(dim=1)[sx > 0] == 31).all())
+    rows = sample_rows(M, 55)
+    idx = torch.from_numpy(rows).cuda()
+    ref = oracle.linear(Xb[rows], W, d, bias, wbits=6, abits=6, exact_blas=True)
+    gu.assert_codes_close(Xq[idx].cpu().numpy(), ref["Xq"], f"{kind} Xq (6 bits)")
+    codes, scales = w.export()
+    gu.assert_codes_close(codes, ref["Wq"], f"{kind} Wq (6 bits)")
+    rows_diff = (Xq[idx].cpu().numpy() != ref["Xq"]).any(axis=1)
+    cols_diff = (codes != ref["Wq"]).any(axis=0)
+    gu.assert_y_close(gu.bf16_to_host(Y[idx]), ref["Y"], f"{kind} Y (W6A6)", rows_diff, cols_diff)
+    w.close()
+
+
+@pytest.mark.parametrize("cfg_id,kind", [(1, "proj"), (1, "fc2"), (3, "qkv")])
+def test_dense_blocks_full_size_sampled_rows(oracle, cfg_id, kind):
+    cfg = wl.CONFIGS[cfg_id]
+    say(f"config {cfg_id}: dense rotation blocks {kind}, M={cfg.M}")
+    K, N = wl.LAYER_SHAPES[kind]
+    Xb = wl.make_x(cfg, kind, 1)
+    M = Xb.shape[0]
+    W, d, bias = wl.make_w(cfg, kind), wl.make_diag(cfg, kind, wl.step_to_group(cfg, 1)), wl.make_bias(cfg, kind)
+    Rs = wl.orthogonal_uniform_first_row(300 + K, K // 128).astype(np.float32)
+    rot = trdq.Rotation(gu.f32_to_dev(Rs.reshape(-1, 128)).view(-1, 128, 128), gu.f32_to_dev(d))
+    w = trdq.prepare_weights_dense(gu.f32_to_dev(W), rot, wbits=8)
+    Xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+    sx = torch.empty((M,), dtype=torch.float32, device="cuda")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    trdq.rotate_quant_dense(gu.bf16_to_dev(Xb), rot, Xq, sx)
+    trdq.qgemm(w, Xq, sx, Y, bias=gu.f32_to_dev(bias))
+    torch.cuda.synchronize()
+    assert bool((Xq.abs().amax(dim=1)[sx > 0] == 127).all())
+    rows = sample_rows(M, 66)
+    idx = torch.from_numpy(rows).cuda()
+    ref = oracle.linear_dense(Xb[rows], W, d, Rs, bias, exact_blas=True)
+    gu.assert_codes_close(Xq[idx].cpu().numpy(), ref["Xq"], f"{kind} Xq (dense blocks)")
+    gu.assert_scales_close(sx[idx].cpu().numpy(), ref["sx"], f"{kind} s_x (dense blocks)")
+    codes, scales = w.export()
+    gu.assert_codes_close(codes, ref["Wq"], f"{kind} Wq (dense blocks)")
+    rows_diff = (Xq[idx].cpu().numpy() != ref["Xq"]).any(axis=1)
+    cols_diff = (codes != ref["Wq"]).any(axis=0)
+    gu.assert_y_close(gu.bf16_to_host(Y[idx]), ref["Y"], f"{kind} Y (dense blocks)", rows_diff, cols_diff)
+    w.close(); rot.close()
