@@ -346,6 +346,60 @@ def linear_dense(X_bf16, W, d, Rs, bias=None, wbits=8, exact_blas=False):
     return dict(Xq=Xq, sx=sx, Wq=Wq, sw=sw, acc=acc, Y=Y, Yd=Yd)
 
 
+def rotate_dense_rpr(X_bf16, d, R1s, perm, R2s):
+    """V = (X diag(d)) BlockDiag(R1) P BlockDiag(R2) as float64: G_t of Eq. 10 in full, with dense
+    blocks for both rotations; (U P)[k'] = U[perm[k']]."""
+    V1 = rotate_dense(X_bf16, d, R1s)
+    V2 = V1[:, np.asarray(perm, dtype=np.int64)]
+    R2s = np.asarray(R2s, dtype=np.float64)
+    B = R2s.shape[1]
+    out = np.empty_like(V2)
+    for b in range(R2s.shape[0]):
+        out[:, b * B:(b + 1) * B] = V2[:, b * B:(b + 1) * B] @ R2s[b]
+    return out
+
+
+def rotate_weights_dense_rpr(W, d, R1s, perm, R2s):
+    """W' = BlockDiag(R2)^T P^T BlockDiag(R1)^T diag(1/d) W as float64 (H_t of Eq. 10 in full)."""
+    W1 = rotate_weights_dense(W, d, R1s)
+    W2 = W1[np.asarray(perm, dtype=np.int64)]                 # (P^T W1)[k'] = W1[perm[k']]
+    R2s = np.asarray(R2s, dtype=np.float64)
+    B = R2s.shape[1]
+    out = np.empty_like(W2)
+    for b in range(R2s.shape[0]):
+        out[b * B:(b + 1) * B] = R2s[b].T @ W2[b * B:(b + 1) * B]
+    return out
+
+
+def linear_dense_rpr(X_bf16, W, d, R1s, perm, R2s, bias=None, wbits=8, exact_blas=False):
+    R1s = np.asarray(R1s, dtype=np.float32)
+    R2s = np.asarray(R2s, dtype=np.float32)
+    B = R1s.shape[1]
+    Xq, sx = quant_tokens(rotate_dense_rpr(X_bf16, d, R1s, perm, R2s))
+    Wq, sw = quant_weights(rotate_weights_dense_rpr(W, d, R1s, perm, R2s), wbits, B)
+    group = B if wbits == 4 else None
+    acc = (acc_exact_blas if exact_blas else igemm)(Xq, Wq, group)
+    Y, Yd = dequant(acc, sx, sw, bias, return_f64=True)
+    return dict(Xq=Xq, sx=sx, Wq=Wq, sw=sw, acc=acc, Y=Y, Yd=Yd)
+
+
+def calibrate_time_rotation(X_bf16, d, Qs1, Qs2, B=128):
+    """The per-group calibration of Sec. 3.2 end to end on calibration activations X (times d):
+    greedy first rotation (Eq. 6-7), zigzag permutation from the per-channel maxima after it, greedy
+    second rotation on the rotated, permuted activations.  Returns (R1s, n1, perm, R2s, n2)."""
+    R1s, n1 = greedy_rotations(X_bf16, d, Qs1, B)
+    R1s32 = R1s.astype(np.float32)
+    V1 = rotate_dense(X_bf16, d, R1s32)
+    perm = zigzag(np.abs(V1).max(axis=0), B)
+    V2 = V1[:, perm.astype(np.int64)]
+    nb = V2.shape[1] // B
+    R2s = np.empty((nb, B, B))
+    n2 = np.empty(nb, dtype=np.int32)
+    for b in range(nb):
+        R2s[b], n2[b], _ = greedy_rotation(V2[:, b * B:(b + 1) * B], Qs2)
+    return R1s32, n1, perm, R2s.astype(np.float32), n2
+
+
 # ---- attention sharing (Sec. 3.3) ------------------------------------------------------------
 
 def cosine_similarity(A_bf16, B_bf16):

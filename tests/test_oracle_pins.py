@@ -847,3 +847,51 @@ def test_greedy_rotation_small_block_brute_force(oracle):
     R, n, m = oracle.greedy_rotation(X, Qs)
     assert np.allclose(m, ms, atol=1e-14)
     assert n == ms.index(min(ms)) + 1 and np.allclose(R, Rs_[n - 1], atol=1e-14)
+
+
+# ------------------------------------ Eq. 10 in full with dense blocks (R1, P, R2)
+
+def test_dense_rpr_reduces_to_the_hadamard_form(oracle):
+    Xb, W, d, _ = wl.small_case(25, 24, 384, 16)
+    Hn = oracle.hadamard(128).astype(np.float64) / np.sqrt(128.0)
+    Rs = np.stack([Hn] * 3)
+    perm = oracle.zigzag(np.abs(oracle.rotate(Xb, d, 128)).max(axis=0), 128)
+    assert np.allclose(oracle.rotate_dense_rpr(Xb, d, Rs, perm, Rs), oracle.rotate_rpr(Xb, d, perm, 128), rtol=0, atol=1e-9)
+    assert np.allclose(oracle.rotate_weights_dense_rpr(W, d, Rs, perm, Rs), oracle.rotate_weights_rpr(W, d, perm, 128),
+                       rtol=0, atol=1e-12)
+
+
+def test_dense_rpr_computational_invariance(oracle):
+    Xb, W, d, _ = wl.small_case(26, 20, 384, 24)
+    R1, R2 = wl.orthogonal_uniform_first_row(6, 3), wl.orthogonal_uniform_first_row(7, 3)
+    perm = np.random.default_rng(4).permutation(384).astype(np.int32)
+    V = oracle.rotate_dense_rpr(Xb, d, R1, perm, R2)
+    Wp = oracle.rotate_weights_dense_rpr(W, d, R1, perm, R2)
+    exact = oracle.bf16_to_f64(Xb) @ W.astype(np.float64)
+    assert np.allclose(V @ Wp, exact, rtol=0, atol=1e-9)
+    # the three factors as explicit K x K matrices
+    K = 384
+    def blockdiag(Rs):
+        M = np.zeros((K, K))
+        for b in range(3):
+            M[b * 128:(b + 1) * 128, b * 128:(b + 1) * 128] = Rs[b]
+        return M
+    P = np.zeros((K, K)); P[perm, np.arange(K)] = 1.0          # (U P)[k'] = U[perm[k']]
+    G = np.diag(d.astype(np.float64)) @ blockdiag(R1) @ P @ blockdiag(R2)
+    assert np.allclose(V, oracle.bf16_to_f64(Xb) @ G, rtol=0, atol=1e-9)
+    Hm = blockdiag(R2).T @ P.T @ blockdiag(R1).T @ np.diag(1.0 / d.astype(np.float64))
+    assert np.allclose(Wp, Hm @ W.astype(np.float64), rtol=0, atol=1e-12)
+
+
+def test_time_rotation_calibration_flattens_outliers(oracle):
+    Xb, _, d, _ = wl.small_case(27, 128, 256, 16, n_outliers=3, outlier=60.0)
+    Q1, Q2 = wl.orthogonal_uniform_first_row(8, 10), wl.orthogonal_uniform_first_row(9, 10)
+    R1, n1, perm, R2, n2 = oracle.calibrate_time_rotation(Xb, d, Q1, Q2)
+    assert sorted(perm.tolist()) == list(range(256))
+    for Rs in (R1, R2):
+        for b in range(2):
+            assert np.abs(Rs[b].astype(np.float64) @ Rs[b].astype(np.float64).T - np.eye(128)).max() < 1e-5
+    raw = np.abs(oracle.bf16_to_f64(Xb) * d).max()
+    one = np.abs(oracle.rotate_dense(Xb, d, R1)).max()
+    two = np.abs(oracle.rotate_dense_rpr(Xb, d, R1, perm, R2)).max()
+    assert one < 0.3 * raw and two < 0.3 * raw
