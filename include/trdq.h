@@ -237,6 +237,19 @@ trdq_status trdq_prepare_weights_dense(const float *W_dev, int K, int N, const t
 trdq_status trdq_rotate_quant_dense(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot,
                                     int8_t *Xq_dev, float *sx_dev, void *stream);
 
+/* Eq. 10 in full with dense blocks:  G_t(X) = (X . diag) . BlockDiag(R1) . P . BlockDiag(R2)  and
+ * H_t(W) = BlockDiag(R2)^T . P^T . BlockDiag(R1)^T . (diag^-1 . W).  rot1 carries the diagonal and
+ * the first rotation; rot2 the second rotation and must have been created WITHOUT a diagonal
+ * (else ERR_MISMATCH); perm_dev: int32 [K] on the device, (U P)[k'] = U[perm[k']] as for
+ * trdq_rotate_quant_rpr.  Other arguments, layouts and errors as the one-rotation calls above;
+ * the activation side takes K <= 1536 (ERR_UNSUPPORTED beyond). */
+trdq_status trdq_prepare_weights_dense_rpr(const float *W_dev, int K, int N, const trdq_rotation *rot1,
+                                           const int32_t *perm_dev, const trdq_rotation *rot2, int wbits,
+                                           void *stream, trdq_weights **out);
+trdq_status trdq_rotate_quant_dense_rpr(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot1,
+                                        const int32_t *perm_dev, const trdq_rotation *rot2,
+                                        int8_t *Xq_dev, float *sx_dev, void *stream);
+
 /* ------------------------------------------------- attention sharing (Sec. 3.3)
  * Eq. 11 between the attention outputs of the conditional and the unconditional pass:
  *   cos_dev[s] = A_s . B_s / (|A_s| |B_s|)   for s < n_seg;   0 where either vector is all zero.

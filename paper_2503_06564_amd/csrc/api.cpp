@@ -123,7 +123,7 @@ namespace {
 // with one rotation; otherwise the full H_t(W) of Eq. 9 (rotation, P^T, rotation).
 trdq_status prepare_weights_impl(const float *W_dev, int K, int N, const float *diag_dev, const int32_t *perm_dev,
                                  int block, int wbits, void *stream, trdq_weights **out,
-                                 const trdq::Rotation *rot = nullptr)
+                                 const trdq::Rotation *rot = nullptr, const trdq::Rotation *rot2 = nullptr)
 {
     if (!out) return TRDQ_ERR_NULL;
     *out = nullptr;
@@ -153,12 +153,18 @@ trdq_status prepare_weights_impl(const float *W_dev, int K, int N, const float *
         rc = TRDQ_ERR_ALLOC;
         goto fail;
     }
-    if (rot) {
+    if (rot && rot2) {
+        // Eq. 10 in full with dense blocks: first rotation, rows gathered through the permutation, second rotation
+        ok = trdq::launch_prepare_rotate_dense(W_dev, K, N, rot->diag, nullptr, rot->R, Wrot, amax, st) == hipSuccess &&
+             trdq::launch_prepare_rotate_dense(Wrot, K, N, nullptr, perm_dev, rot2->R, Wrot2, amax, st) == hipSuccess &&
+             trdq::launch_prepare_quant(Wrot2, amax, K, N, qbits, 1.0f, w->codes, w->scales, st) == hipSuccess;
+    } else if (rot) {
         // dense orthonormal blocks: nothing to normalise afterwards
-        ok = trdq::launch_prepare_rotate_dense(W_dev, K, N, rot->diag, rot->R, Wrot, amax, st) == hipSuccess &&
+        ok = trdq::launch_prepare_rotate_dense(W_dev, K, N, rot->diag, nullptr, rot->R, Wrot, amax, st) == hipSuccess &&
              trdq::launch_prepare_quant(Wrot, amax, K, N, qbits, 1.0f, w->codes, w->scales, st) == hipSuccess;
     } else if (!(ok = trdq::launch_prepare_rotate(W_dev, K, N, diag_dev, nullptr, Wrot, amax, st) == hipSuccess)) {
     } else if (perm_dev) {
+        // (the Hadamard form of Eq. 9)
         // rows gathered through the permutation, rotated again; two unnormalised rotations: 1/128
         ok = trdq::launch_prepare_rotate(Wrot, K, N, nullptr, perm_dev, Wrot2, amax, st) == hipSuccess &&
              trdq::launch_prepare_quant(Wrot2, amax, K, N, qbits, 0.0078125f, w->codes, w->scales, st) == hipSuccess;
@@ -215,6 +221,7 @@ trdq_status trdq_rotation_create(const float *R_dev, const float *diag_dev, int 
     if (hipGetDevice(&r->device) != hipSuccess) { rc = TRDQ_ERR_HIP; goto fail; }
     if (hipMalloc(reinterpret_cast<void **>(&r->R), r_bytes) != hipSuccess ||
         hipMalloc(&r->pieces, trdq::rotation_pieces_bytes(K)) != hipSuccess ||
+        hipMalloc(&r->frags32, trdq::rotation_frags32_bytes(K)) != hipSuccess ||
         (diag_dev && hipMalloc(reinterpret_cast<void **>(&r->diag), (size_t)K * sizeof(float)) != hipSuccess)) {
         rc = TRDQ_ERR_ALLOC;
         goto fail;
@@ -222,6 +229,7 @@ trdq_status trdq_rotation_create(const float *R_dev, const float *diag_dev, int 
     if (hipMemcpyAsync(r->R, R_dev, r_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess ||
         (diag_dev && hipMemcpyAsync(r->diag, diag_dev, (size_t)K * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) ||
         trdq::launch_rotation_pieces(r->R, r->diag, K, r->pieces, st) != hipSuccess ||
+        trdq::launch_rotation_frags32(r->R, K, r->frags32, st) != hipSuccess ||
         hipStreamSynchronize(st) != hipSuccess) {
         rc = TRDQ_ERR_HIP;
         goto fail;
@@ -233,6 +241,7 @@ fail:
     if (r->R) (void)hipFree(r->R);
     if (r->diag) (void)hipFree(r->diag);
     if (r->pieces) (void)hipFree(r->pieces);
+    if (r->frags32) (void)hipFree(r->frags32);
     delete r;
     return rc;
 }
@@ -278,6 +287,7 @@ void trdq_rotation_destroy(trdq_rotation *r)
     if (r->R) (void)hipFree(r->R);
     if (r->diag) (void)hipFree(r->diag);
     if (r->pieces) (void)hipFree(r->pieces);
+    if (r->frags32) (void)hipFree(r->frags32);
     delete r;
 }
 
@@ -288,6 +298,33 @@ trdq_status trdq_prepare_weights_dense(const float *W_dev, int K, int N, const t
     if (!rot) return TRDQ_ERR_NULL;
     if (K != rot->K) return TRDQ_ERR_MISMATCH;
     return prepare_weights_impl(W_dev, K, N, nullptr, nullptr, trdq::kBlock, wbits, stream, out, rot);
+}
+
+trdq_status trdq_prepare_weights_dense_rpr(const float *W_dev, int K, int N, const trdq_rotation *rot1,
+                                           const int32_t *perm_dev, const trdq_rotation *rot2, int wbits,
+                                           void *stream, trdq_weights **out)
+{
+    if (out) *out = nullptr;
+    if (!rot1 || !rot2 || !perm_dev) return TRDQ_ERR_NULL;
+    if (K != rot1->K || K != rot2->K || rot2->diag) return TRDQ_ERR_MISMATCH;
+    return prepare_weights_impl(W_dev, K, N, nullptr, perm_dev, trdq::kBlock, wbits, stream, out, rot1, rot2);
+}
+
+trdq_status trdq_rotate_quant_dense_rpr(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot1,
+                                        const int32_t *perm_dev, const trdq_rotation *rot2,
+                                        int8_t *Xq_dev, float *sx_dev, void *stream)
+{
+    if (!rot1 || !rot2 || !perm_dev) return TRDQ_ERR_NULL;
+    if (rot1->K != rot2->K || rot2->diag) return TRDQ_ERR_MISMATCH;
+    trdq_status rc = check_rotate_args(X_dev, M, rot1->K, ldx, trdq::kBlock);
+    if (rc != TRDQ_OK) return rc;
+    if (M > 0 && (!Xq_dev || !sx_dev)) return TRDQ_ERR_NULL;
+    if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || !aligned(perm_dev, 4)) return TRDQ_ERR_SHAPE;
+    if (!trdq::rotate_quant_dense_rpr_supports(rot1->K)) return TRDQ_ERR_UNSUPPORTED;
+    if (M == 0) return TRDQ_OK;
+    return hip_status(trdq::launch_rotate_quant_dense_rpr(static_cast<const uint16_t *>(X_dev), M, rot1->K, ldx,
+                                                          rot1->pieces, perm_dev, rot2->frags32, Xq_dev, sx_dev,
+                                                          static_cast<hipStream_t>(stream)));
 }
 
 trdq_status trdq_rotate_quant_dense(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot,

@@ -71,8 +71,8 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_rotate_kernel(
 // Wave q of the workgroup produces rows j = 32 q .. 32 q + 31 of 64 columns; the row of R_b it
 // needs at step k is the same for all its lanes (scalar loads), the column of W comes from LDS.
 __global__ __launch_bounds__(kPrepThreads) void prepare_rotate_dense_kernel(
-    const float *__restrict__ W, int K, int N, const float *__restrict__ diag, const float *__restrict__ R,
-    float *__restrict__ Wrot, float *__restrict__ amax)
+    const float *__restrict__ W, int K, int N, const float *__restrict__ diag, const int32_t *__restrict__ perm,
+    const float *__restrict__ R, float *__restrict__ Wrot, float *__restrict__ amax)
 {
     __shared__ float tile[kBlock][kCols + 1];
     __shared__ float part[4][kCols];
@@ -85,7 +85,12 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_rotate_dense_kernel(
     for (int k = q; k < kBlock; k += 4) {
         float w = 0.0f;
         if (col_ok) {
-            w = W[(size_t)(b * kBlock + k) * N + n];
+            int row = b * kBlock + k;
+            if (perm) {                                  // the P^T factor in front of a second rotation
+                row = perm[row];
+                row = row < 0 ? 0 : (row >= K ? K - 1 : row);
+            }
+            w = W[(size_t)row * N + n];
             if (diag) w = w / diag[b * kBlock + k];
         }
         tile[k][c] = w;
@@ -216,11 +221,11 @@ hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag
     return hipGetLastError();
 }
 
-hipError_t launch_prepare_rotate_dense(const float *W, int K, int N, const float *diag, const float *R,
-                                       float *Wrot, float *amax, hipStream_t st)
+hipError_t launch_prepare_rotate_dense(const float *W, int K, int N, const float *diag, const int32_t *perm,
+                                       const float *R, float *Wrot, float *amax, hipStream_t st)
 {
     dim3 grid((N + kCols - 1) / kCols, K / kBlock);
-    hipLaunchKernelGGL(prepare_rotate_dense_kernel, grid, dim3(kPrepThreads), 0, st, W, K, N, diag, R, Wrot, amax);
+    hipLaunchKernelGGL(prepare_rotate_dense_kernel, grid, dim3(kPrepThreads), 0, st, W, K, N, diag, perm, R, Wrot, amax);
     return hipGetLastError();
 }
 

@@ -74,7 +74,11 @@ __device__ __forceinline__ void rotate_block_dense(const uint16_t *__restrict__ 
             xf[tt][s] = ld.v;
         }
     }
-    const uint4 *pb = pieces + (size_t)b * kPiecesPerBlock + lane;
+    // (the offset passes through an empty assembly statement: where a wave keeps its block for every
+    // token group the fragment loads would otherwise be hoisted out of the group loop, all 96 of them)
+    int lane_off = lane;
+    asm volatile("" : "+v"(lane_off));
+    const uint4 *pb = pieces + (size_t)b * kPiecesPerBlock + lane_off;
     uint4 fa[2][12];
     auto request = [&](uint4 (&f)[12], int t) {
 #pragma unroll
@@ -188,6 +192,109 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_dense_kernel(
     }
 }
 
+// ---- Eq. 10 in full with dense blocks: (X . Delta) . BlockDiag(R1) . P . BlockDiag(R2) -----------
+// frags32[((b * 8 + t) * 8 + s4) * 64 + lane] = four floats: R_b[4 s + g][c(t, r)] for the k-steps
+// s = 4 s4 .. 4 s4 + 3 of v_mfma_f32_16x16x4_f32 (lane = 16 g + r, c(t, r) as for the bf16 pieces):
+// the A operand of the SECOND rotation, whose B operand is fp32 (first-rotation results).
+__global__ __launch_bounds__(256) void rotation_frags32_kernel(const float *__restrict__ R, float *__restrict__ frags)
+{
+    const int b = blockIdx.y;
+    const int idx = blockIdx.x * 256 + threadIdx.x;     // 0 .. 16383: (t, s4, lane, i)
+    const int i = idx & 3, lane = (idx >> 2) & 63, s4 = (idx >> 8) & 7, t = idx >> 11;
+    const int r = lane & 15, g = lane >> 4;
+    const int k = 4 * (4 * s4 + i) + g;
+    const int c = 32 * (r >> 2) + 4 * t + (r & 3);
+    frags[(size_t)b * kBlock * kBlock + idx] = R[((size_t)b * kBlock + k) * kBlock + c];
+}
+
+// One workgroup (a wave per block, at most 12) per group of 16 tokens.  Stage 1 is the dense
+// first rotation (bf16 pieces, as above) into an fp32 row buffer T in LDS; stage 2 gathers
+// T[perm[.]] as the B operand of fp32 matrix instructions against the second rotation's
+// fragments; then the token maximum, the codes and the stores as in the one-rotation kernel.
+__global__ __launch_bounds__(768) void rotate_quant_dense_rpr_kernel(
+    const uint16_t *__restrict__ X, int64_t M, int nb, int64_t ldx, const uint4 *__restrict__ pieces1,
+    const int32_t *__restrict__ perm, const float4 *__restrict__ frags2, int8_t *__restrict__ Xq, float *__restrict__ sx)
+{
+    extern __shared__ __align__(16) float lds_f[];
+    const int K = nb * kBlock;
+    const int LDT = K + 4;
+    float *const T = lds_f;                              // [16][K + 4]
+    float *const amax_s = lds_f + 16 * LDT;              // [2][nw][16]
+    const int nw = blockDim.x >> 6;
+    int *const srcs = reinterpret_cast<int *>(amax_s + 2 * nw * 16);     // [nw][128]
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+    const int64_t groups = (M + 15) / 16;
+    const int b = wave;                                  // nw == nb
+
+    // where the second rotation's inputs sit in a row of T: input channel k of block b is channel perm[b*128 + k]
+    for (int k = lane; k < kBlock; k += 64) {
+        const int p = perm[b * kBlock + k];
+        srcs[b * kBlock + k] = p < 0 ? 0 : (p >= K ? K - 1 : p);
+    }
+    __builtin_amdgcn_wave_barrier();     // a wave only reads its own entries (LDS serves a wave's requests in order)
+    int parity = 0;
+    for (int64_t tg = blockIdx.x; tg < groups; tg += gridDim.x) {
+        const int64_t tok0 = tg * 16;
+        float out[1][8][4];
+        float unused[1] = {0.0f};
+        rotate_block_dense<1>(X, M, ldx, pieces1, b, tok0, lane, out, unused);
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            *reinterpret_cast<float4 *>(T + l16 * LDT + b * kBlock + 32 * g + 4 * t) =
+                make_float4(out[0][t][0], out[0][t][1], out[0][t][2], out[0][t][3]);
+        __syncthreads();
+        float bv[32];
+#pragma unroll
+        for (int s = 0; s < 32; ++s) bv[s] = T[l16 * LDT + srcs[b * kBlock + 4 * s + g]];      // k-step s: k = 4 s + g
+        float amax = 0.0f;
+        int lane_off = lane;                 // as in rotate_block_dense: keep the loads inside the group loop
+        asm volatile("" : "+v"(lane_off));
+        const float4 *fb = frags2 + (size_t)b * (kBlock * kBlock / 4) + lane_off;
+        float4 fa2[2][8];
+        auto request2 = [&](float4 (&f)[8], int t) {
+#pragma unroll
+            for (int s4 = 0; s4 < 8; ++s4) f[s4] = fb[(t * 8 + s4) * 64];
+        };
+        request2(fa2[0], 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            if (t + 1 < 8) request2(fa2[(t + 1) & 1], t + 1);
+            v4f acc = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s4 = 0; s4 < 8; ++s4) {
+                const float4 a4 = fa2[t & 1][s4];
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, bv[4 * s4 + 0], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, bv[4 * s4 + 1], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, bv[4 * s4 + 2], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, bv[4 * s4 + 3], acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                out[0][t][j] = acc[j];
+                amax = fmaxf(amax, fabsf(acc[j]));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        float *const am = amax_s + parity * nw * 16;
+        amax = fmaxf(amax, __shfl_xor(amax, 16));
+        amax = fmaxf(amax, __shfl_xor(amax, 32));
+        if (g == 0) am[wave * 16 + l16] = amax;
+        __syncthreads();        // also: every wave has read its inputs from T before the next group overwrites it
+        parity ^= 1;
+        float a = 0.0f;
+        for (int w = 0; w < nw; ++w) a = fmaxf(a, am[w * 16 + l16]);
+        const int64_t token = tok0 + l16;
+        const float inv = a > 0.0f ? 127.0f / a : 0.0f;
+        if (token < M) {
+            if (wave == 0 && g == 0) sx[token] = a / 127.0f;
+            store_codes_dense(out[0], inv, Xq + token * K + b * kBlock + 32 * g);
+        }
+    }
+}
+
 template <int TT, bool KEEP, int MAXT = 768>
 hipError_t launch_dense(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx, const uint4 *pieces,
                         int8_t *Xq, float *sx, hipStream_t st)
@@ -211,7 +318,36 @@ hipError_t launch_rotation_pieces(const float *R, const float *diag, int K, void
     return hipGetLastError();
 }
 
+size_t rotation_frags32_bytes(int K) { return (size_t)K * kBlock * sizeof(float); }
+
+hipError_t launch_rotation_frags32(const float *R, int K, void *frags, hipStream_t st)
+{
+    hipLaunchKernelGGL(rotation_frags32_kernel, dim3(64, K / kBlock), dim3(256), 0, st, R, static_cast<float *>(frags));
+    return hipGetLastError();
+}
+
 bool rotate_quant_dense_supports(int K) { return K % kBlock == 0 && K / kBlock <= 36; }
+bool rotate_quant_dense_rpr_supports(int K) { return K % kBlock == 0 && K / kBlock <= 12; }
+
+hipError_t launch_rotate_quant_dense_rpr(const uint16_t *X, int64_t M, int K, int64_t ldx, const void *pieces1,
+                                         const int32_t *perm, const void *frags2, int8_t *Xq, float *sx, hipStream_t st)
+{
+    if (M == 0) return hipSuccess;
+    const int nb = K / kBlock;
+    const int64_t groups = (M + 15) / 16;
+    const int64_t grid = groups < 256 ? groups : 256;
+    const size_t smem = sizeof(float) * ((size_t)16 * (K + 4) + 2 * nb * 16) + sizeof(int) * (size_t)K;
+    static size_t attr_smem = 0;
+    if (smem > attr_smem) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(rotate_quant_dense_rpr_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_smem = smem;
+    }
+    hipLaunchKernelGGL(rotate_quant_dense_rpr_kernel, dim3((unsigned)grid), dim3(64 * nb), smem, st, X, M, nb, ldx,
+                       static_cast<const uint4 *>(pieces1), perm, static_cast<const float4 *>(frags2), Xq, sx);
+    return hipGetLastError();
+}
 
 hipError_t launch_rotate_quant_dense(const uint16_t *X, int64_t M, int K, int64_t ldx, const void *pieces,
                                      int8_t *Xq, float *sx, hipStream_t st)

@@ -33,7 +33,8 @@ struct Rotation {
     int K = 0;
     float *R = nullptr;          // [K/128][128][128]
     float *diag = nullptr;       // [K] or null (ones)
-    void *pieces = nullptr;
+    void *pieces = nullptr;      // diag . R_b as bf16 pieces (operand of a first or only rotation)
+    void *frags32 = nullptr;     // R_b as float fragments (operand of a second rotation)
     int device = 0;
 };
 
@@ -90,8 +91,13 @@ hipError_t launch_rotation_pieces(const float *R, const float *diag, int K, void
 bool rotate_quant_dense_supports(int K);
 hipError_t launch_rotate_quant_dense(const uint16_t *X, int64_t M, int K, int64_t ldx, const void *pieces,
                                      int8_t *Xq, float *sx, hipStream_t st);
-hipError_t launch_prepare_rotate_dense(const float *W, int K, int N, const float *diag, const float *R,
-                                       float *Wrot, float *amax, hipStream_t st);
+hipError_t launch_prepare_rotate_dense(const float *W, int K, int N, const float *diag, const int32_t *perm,
+                                       const float *R, float *Wrot, float *amax, hipStream_t st);
+size_t rotation_frags32_bytes(int K);
+hipError_t launch_rotation_frags32(const float *R, int K, void *frags, hipStream_t st);
+bool rotate_quant_dense_rpr_supports(int K);
+hipError_t launch_rotate_quant_dense_rpr(const uint16_t *X, int64_t M, int K, int64_t ldx, const void *pieces1,
+                                         const int32_t *perm, const void *frags2, int8_t *Xq, float *sx, hipStream_t st);
 bool fused_supports(int K);
 bool fused_pays(int64_t M, int K, int N, int wbits);
 hipError_t launch_linear_fused(const Weights &w, const uint16_t *X, int64_t M, int64_t ldx,

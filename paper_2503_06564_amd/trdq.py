@@ -26,7 +26,7 @@ SYMBOLS = [
     "trdq_rotate_quant_asym", "trdq_qgemm_asym", "trdq_rotate_quant_bits",
     "trdq_cosine_similarity", "trdq_share_plan",
     "trdq_rotation_create", "trdq_rotation_destroy", "trdq_prepare_weights_dense", "trdq_rotate_quant_dense",
-    "trdq_greedy_rotation",
+    "trdq_greedy_rotation", "trdq_prepare_weights_dense_rpr", "trdq_rotate_quant_dense_rpr",
 ]
 
 _lib = None
@@ -85,6 +85,8 @@ def lib():
         L.trdq_prepare_weights_dense.argtypes = [p, i32, i32, p, i32, p, C.POINTER(p)]
         L.trdq_rotate_quant_dense.argtypes = [p, i64, i64, p, p, p, p]
         L.trdq_greedy_rotation.argtypes = [p, i64, i32, i64, p, i32, p, i32, p, p, p]
+        L.trdq_prepare_weights_dense_rpr.argtypes = [p, i32, i32, p, p, p, i32, p, C.POINTER(p)]
+        L.trdq_rotate_quant_dense_rpr.argtypes = [p, i64, i64, p, p, p, p, p, p]
         L.trdq_qgemm_asym.argtypes = [p, p, p, p, i64, p, p, i64, p, p]
         L.trdq_channel_absmax.argtypes = [p, i64, i32, i64, p, i32, i32, p, p]
         L.trdq_weight_row_absmax.argtypes = [p, i32, i32, p, p]
@@ -319,6 +321,21 @@ def rotate_quant_dense(X, rot, Xq, sx, stream=None):
     ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
     _check(lib().trdq_rotate_quant_dense(_ptr(X), M, ldx, rot.handle, _ptr(Xq), _ptr(sx), _stream(stream)),
            "trdq_rotate_quant_dense")
+
+
+def prepare_weights_dense_rpr(W, rot1, perm, rot2, wbits=8, stream=None):
+    K, N = W.shape
+    h = C.c_void_p()
+    _check(lib().trdq_prepare_weights_dense_rpr(_ptr(W), K, N, rot1.handle, _ptr(perm), rot2.handle, wbits,
+                                                _stream(stream), C.byref(h)), "trdq_prepare_weights_dense_rpr")
+    return Weights(h)
+
+
+def rotate_quant_dense_rpr(X, rot1, perm, rot2, Xq, sx, stream=None):
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    _check(lib().trdq_rotate_quant_dense_rpr(_ptr(X), M, ldx, rot1.handle, _ptr(perm), rot2.handle, _ptr(Xq), _ptr(sx),
+                                             _stream(stream)), "trdq_rotate_quant_dense_rpr")
 
 
 def bind_rotate_quant_dense(X, rot, Xq, sx, stream=None):

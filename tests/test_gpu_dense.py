@@ -169,3 +169,76 @@ def test_greedy_rotation_end_to_end_beats_no_rotation(oracle):
     err_plain = np.abs(oracle.linear_dense(Xb, W, d, eye, bias)["Yd"] - exact).mean()
     assert err_rot < 0.5 * err_plain, (err_rot, err_plain)
     w.close(); rot.close()
+
+
+# ---- Eq. 10 in full with dense blocks: first rotation, permutation, second rotation ----
+
+def _rot(Rs, d=None):
+    return trdq.Rotation(f32_to_dev(Rs.reshape(-1, 128)).view(-1, 128, 128), None if d is None else f32_to_dev(d))
+
+
+@pytest.mark.parametrize("M,K", [(1, 128), (37, 256), (300, 1152), (64, 1536), (530, 384), (0, 256)])
+def test_rotate_quant_dense_rpr_matches_oracle(oracle, M, K):
+    say(f"rotate_quant_dense_rpr M={M} K={K}")
+    Xb, _, d, _ = wl.small_case(71, max(M, 1), K, 16, n_outliers=max(1, K // 144), outlier=40.0)
+    Xb = Xb[:M]
+    R1, R2 = _blocks(K + 1, K), _blocks(K + 2, K)
+    perm = np.random.default_rng(K).permutation(K).astype(np.int32)
+    rot1, rot2 = _rot(R1, d), _rot(R2)
+    Xq = torch.full((M, K), 99, dtype=torch.int8, device=dev())
+    sx = torch.full((M,), -1.0, dtype=torch.float32, device=dev())
+    trdq.rotate_quant_dense_rpr(bf16_to_dev(Xb), rot1, torch.from_numpy(perm).to(dev()), rot2, Xq, sx)
+    torch.cuda.synchronize()
+    if M:
+        Xq_o, sx_o = oracle.quant_tokens(oracle.rotate_dense_rpr(Xb, d, R1, perm, R2))
+        assert_codes_close(Xq.cpu().numpy(), Xq_o, "Xq (dense R1 P R2)")
+        assert_scales_close(sx.cpu().numpy(), sx_o, "s_x (dense R1 P R2)")
+    rot1.close(); rot2.close()
+
+
+@pytest.mark.parametrize("M,K,N,wbits", [(17, 256, 144, 8), (300, 1152, 272, 8), (64, 384, 160, 4)])
+def test_dense_rpr_linear_end_to_end(oracle, M, K, N, wbits):
+    say(f"dense R1 P R2 linear M={M} K={K} N={N} wbits={wbits}")
+    Xb, W, d, bias = wl.small_case(72, M, K, N, n_outliers=max(1, K // 144), outlier=40.0)
+    R1, R2 = _blocks(K + 3, K), _blocks(K + 4, K)
+    perm = oracle.zigzag(np.abs(oracle.rotate_dense(Xb, d, R1)).max(axis=0), 128).astype(np.int32)
+    rot1, rot2 = _rot(R1, d), _rot(R2)
+    perm_dev = torch.from_numpy(perm).to(dev())
+    w = trdq.prepare_weights_dense_rpr(f32_to_dev(W), rot1, perm_dev, rot2, wbits=wbits)
+    ref = oracle.linear_dense_rpr(Xb, W, d, R1, perm, R2, bias, wbits=wbits, exact_blas=True)
+    codes, scales = w.export()
+    assert_codes_close(codes, ref["Wq"], "Wq (dense R1 P R2)")
+    assert_scales_close(scales, ref["sw"], "s_w (dense R1 P R2)")
+    Xq = torch.empty((M, K), dtype=torch.int8, device=dev())
+    sx = torch.empty((M,), dtype=torch.float32, device=dev())
+    trdq.rotate_quant_dense_rpr(bf16_to_dev(Xb), rot1, perm_dev, rot2, Xq, sx)
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device=dev())
+    trdq.qgemm(w, Xq, sx, Y, bias=f32_to_dev(bias))
+    torch.cuda.synchronize()
+    assert_codes_close(Xq.cpu().numpy(), ref["Xq"], "Xq (dense R1 P R2)")
+    rows = np.any(Xq.cpu().numpy() != ref["Xq"], axis=1)
+    cols = np.any(codes != ref["Wq"], axis=0)
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (dense R1 P R2)", skip_rows=rows, skip_cols=cols)
+    w.close(); rot1.close(); rot2.close()
+
+
+def test_dense_rpr_argument_errors():
+    R = torch.zeros((2, 128, 128), device=dev())
+    d = torch.ones((256,), device=dev())
+    rot1, rot2_bad, rot2 = trdq.Rotation(R, d), trdq.Rotation(R, d), trdq.Rotation(R)
+    X = torch.zeros((4, 256), dtype=torch.bfloat16, device=dev())
+    Xq = torch.zeros((4, 256), dtype=torch.int8, device=dev())
+    sx = torch.zeros((4,), device=dev())
+    perm = torch.arange(256, dtype=torch.int32, device=dev())
+    with pytest.raises(trdq.TrdqError) as e:
+        trdq.rotate_quant_dense_rpr(X, rot1, perm, rot2_bad, Xq, sx)      # the second rotation carries a diagonal
+    assert e.value.status == trdq.ERR_MISMATCH
+    Rw = torch.zeros((13, 128, 128), device=dev())
+    wide1, wide2 = trdq.Rotation(Rw), trdq.Rotation(Rw)
+    Xw = torch.zeros((4, 13 * 128), dtype=torch.bfloat16, device=dev())
+    with pytest.raises(trdq.TrdqError) as e:
+        trdq.rotate_quant_dense_rpr(Xw, wide1, torch.arange(13 * 128, dtype=torch.int32, device=dev()), wide2,
+                                    torch.zeros((4, 13 * 128), dtype=torch.int8, device=dev()), sx)
+    assert e.value.status == trdq.ERR_UNSUPPORTED
+    for r in (rot1, rot2_bad, rot2, wide1, wide2):
+        r.close()
