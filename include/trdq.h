@@ -226,6 +226,19 @@ trdq_status trdq_greedy_rotation(const void *X_dev, int64_t M, int K, int64_t ld
                                  int block, const double *Q_dev, int n_steps, float *R_dev, int32_t *n_host,
                                  void *stream);
 
+/* The rest of the per-group calibration of Sec. 3.2 when the first rotation is dense:
+ * trdq_channel_absmax_dense: mag_dev[k] = max_i |((X . diag) . BlockDiag(R_b))[i, k]| with the
+ *   rotation's blocks and diagonal (float32 [K] on the device, overwritten): the magnitudes the
+ *   zigzag permutation is dealt from.  Errors as trdq_channel_absmax.
+ * trdq_greedy_rotation_second: trdq_greedy_rotation for the SECOND rotation of Eq. 10: the search runs
+ *   on ((X . diag) . BlockDiag(R1))[:, perm] (computed in float64 from rot1's float32 blocks) instead
+ *   of X . diag.  perm_dev int32 [K] on the device; other arguments and errors as trdq_greedy_rotation. */
+trdq_status trdq_channel_absmax_dense(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot,
+                                      float *mag_dev, void *stream);
+trdq_status trdq_greedy_rotation_second(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot1,
+                                        const int32_t *perm_dev, const double *Q_dev, int n_steps, float *R_dev,
+                                        int32_t *n_host, void *stream);
+
 /* trdq_prepare_weights with the rotation's blocks and diagonal (wbits 8, 6 or 4; layouts, handle
  * and errors as trdq_prepare_weights; K != the rotation's K -> ERR_MISMATCH). */
 trdq_status trdq_prepare_weights_dense(const float *W_dev, int K, int N, const trdq_rotation *rot,

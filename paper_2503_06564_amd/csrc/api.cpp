@@ -246,9 +246,44 @@ fail:
     return rc;
 }
 
+namespace {
+trdq_status greedy_impl(const void *X_dev, int64_t M, int K, int64_t ldx, const float *diag_dev, int block,
+                        const float *R1_dev, const int32_t *perm_dev, const double *Q_dev, int n_steps, float *R_dev,
+                        int32_t *n_host, void *stream);
+}
+
 trdq_status trdq_greedy_rotation(const void *X_dev, int64_t M, int K, int64_t ldx, const float *diag_dev,
                                  int block, const double *Q_dev, int n_steps, float *R_dev, int32_t *n_host,
                                  void *stream)
+{
+    return greedy_impl(X_dev, M, K, ldx, diag_dev, block, nullptr, nullptr, Q_dev, n_steps, R_dev, n_host, stream);
+}
+
+trdq_status trdq_greedy_rotation_second(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot1,
+                                        const int32_t *perm_dev, const double *Q_dev, int n_steps, float *R_dev,
+                                        int32_t *n_host, void *stream)
+{
+    if (!rot1 || !perm_dev) return TRDQ_ERR_NULL;
+    return greedy_impl(X_dev, M, rot1->K, ldx, rot1->diag, trdq::kBlock, rot1->R, perm_dev, Q_dev, n_steps, R_dev,
+                       n_host, stream);
+}
+
+trdq_status trdq_channel_absmax_dense(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot,
+                                      float *mag_dev, void *stream)
+{
+    if (!rot) return TRDQ_ERR_NULL;
+    trdq_status rc = check_rotate_args(X_dev, M, rot->K, ldx, trdq::kBlock);
+    if (rc != TRDQ_OK) return rc;
+    if (!mag_dev) return TRDQ_ERR_NULL;
+    if (!aligned(mag_dev, 4)) return TRDQ_ERR_SHAPE;
+    return hip_status(trdq::launch_channel_absmax_dense(static_cast<const uint16_t *>(X_dev), M, rot->K, ldx, rot->pieces,
+                                                        mag_dev, static_cast<hipStream_t>(stream)));
+}
+
+namespace {
+trdq_status greedy_impl(const void *X_dev, int64_t M, int K, int64_t ldx, const float *diag_dev, int block,
+                        const float *R1_dev, const int32_t *perm_dev, const double *Q_dev, int n_steps, float *R_dev,
+                        int32_t *n_host, void *stream)
 {
     trdq_status rc = check_rotate_args(X_dev, M, K, ldx, block);
     if (rc != TRDQ_OK) return rc;
@@ -266,8 +301,8 @@ trdq_status trdq_greedy_rotation(const void *X_dev, int64_t M, int K, int64_t ld
         return TRDQ_ERR_ALLOC;
     }
     std::vector<int> n_tmp((size_t)nb, 0);
-    bool ok = trdq::launch_greedy_rotation(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev, Q_dev, n_steps, ws,
-                                           R_dev, n_dev, st) == hipSuccess &&
+    bool ok = trdq::launch_greedy_rotation(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev, R1_dev, perm_dev,
+                                           Q_dev, n_steps, ws, R_dev, n_dev, st) == hipSuccess &&
               hipMemcpyAsync(n_tmp.data(), n_dev, sizeof(int) * (size_t)nb, hipMemcpyDeviceToHost, st) == hipSuccess &&
               hipStreamSynchronize(st) == hipSuccess;
     (void)hipFree(ws);
@@ -280,6 +315,7 @@ trdq_status trdq_greedy_rotation(const void *X_dev, int64_t M, int K, int64_t ld
         for (int b = 0; b < nb; ++b) n_host[b] = n_tmp[(size_t)b];
     return TRDQ_OK;
 }
+}  // namespace
 
 void trdq_rotation_destroy(trdq_rotation *r)
 {

@@ -36,6 +36,29 @@ __global__ __launch_bounds__(256) void greedy_init_kernel(const uint16_t *__rest
     if (blockIdx.x == 0 && threadIdx.x == 0) { best_m[b] = __longlong_as_double(0x7FF0000000000000ll); best_n[b] = 0; }
 }
 
+// The same for the SECOND rotation of Eq. 10: the working matrix starts from the activations after the
+// first rotation and the permutation, Xw[b][i][j] = ((X . d) . BlockDiag(R1))[i][perm[b*128 + j]], in fp64
+// on the float32 values of R1.  One workgroup per (token, block), a thread per channel.
+__global__ __launch_bounds__(128) void greedy_init2_kernel(const uint16_t *__restrict__ X, int64_t Mc, int K, int64_t ldx,
+                                                           const float *__restrict__ diag, const float *__restrict__ R1,
+                                                           const int32_t *__restrict__ perm, double *__restrict__ Xw)
+{
+    const int64_t i = blockIdx.x;
+    const int b = blockIdx.y, j = threadIdx.x;
+    int p = perm[b * kBlock + j];
+    p = p < 0 ? 0 : (p >= K ? K - 1 : p);
+    const int kb = p / kBlock, c = p % kBlock;
+    const uint16_t *x = X + i * ldx + kb * kBlock;
+    const float *r = R1 + (size_t)kb * kBlock * kBlock + c;
+    double acc = 0.0;
+    for (int k = 0; k < kBlock; ++k) {
+        double v = (double)__uint_as_float((uint32_t)x[k] << 16);
+        if (diag) v *= (double)diag[kb * kBlock + k];
+        acc = fma(v, (double)r[k * kBlock], acc);
+    }
+    Xw[((int64_t)b * Mc + i) * kBlock + j] = acc;
+}
+
 __global__ void greedy_clear_kernel(unsigned long long *colmax, int n)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -138,6 +161,7 @@ size_t greedy_workspace_bytes(int64_t Mc, int K)
 }
 
 hipError_t launch_greedy_rotation(const uint16_t *X, int64_t Mc, int K, int64_t ldx, const float *diag,
+                                  const float *R1, const int32_t *perm,
                                   const double *Q, int n_steps, void *workspace, float *R_out, int *n_out_dev,
                                   hipStream_t st)
 {
@@ -154,6 +178,8 @@ hipError_t launch_greedy_rotation(const uint16_t *X, int64_t Mc, int K, int64_t 
     unsigned init_grid = (unsigned)((rows * kBlock + 255) / 256);
     if (init_grid > 1024) init_grid = 1024;
     hipLaunchKernelGGL(greedy_init_kernel, dim3(init_grid, nb), dim3(256), 0, st, X, Mc, nb, ldx, diag, Xw, Racc, best_m, best_n);
+    if (R1)     // second rotation: replace the working activations by the rotated, permuted ones
+        hipLaunchKernelGGL(greedy_init2_kernel, dim3((unsigned)Mc, nb), dim3(128), 0, st, X, Mc, K, ldx, diag, R1, perm, Xw);
     unsigned cm_grid = (unsigned)((Mc + 63) / 64);
     if (cm_grid > 64) cm_grid = 64;
     if (cm_grid < 1) cm_grid = 1;

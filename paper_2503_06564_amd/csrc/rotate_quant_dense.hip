@@ -295,6 +295,47 @@ __global__ __launch_bounds__(768) void rotate_quant_dense_rpr_kernel(
     }
 }
 
+// mag[k] = max over the tokens of |((X . d) . BlockDiag(R_b))[i][k]| (what the zigzag permutation is dealt
+// from when the first rotation is dense).  A wave per (token group, block); the 16 tokens of a lane
+// row are reduced with row moves, one lane per row merges with an atomic maximum on the bit patterns.
+__global__ __launch_bounds__(256) void channel_absmax_dense_kernel(const uint16_t *__restrict__ X, int64_t M, int nb,
+                                                                   int64_t ldx, const uint4 *__restrict__ pieces,
+                                                                   float *__restrict__ mag)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+    const int b = blockIdx.y;
+    const int64_t groups = (M + 15) / 16;
+    float mx[8][4];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) mx[t][j] = 0.0f;
+    for (int64_t tg = (int64_t)blockIdx.x * 4 + wave; tg < groups; tg += (int64_t)gridDim.x * 4) {
+        float out[1][8][4];
+        float unused[1] = {0.0f};
+        rotate_block_dense<1>(X, M, ldx, pieces, b, tg * 16, lane, out, unused);   // rows past M repeat the last token
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mx[t][j] = fmaxf(mx[t][j], fabsf(out[0][t][j]));
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float m = row16_max(mx[t][j]);
+            if (l16 == 0) atomicMax(reinterpret_cast<unsigned int *>(mag + b * kBlock + 32 * g + 4 * t + j), __float_as_uint(m));
+        }
+}
+
+__global__ void dense_fill_zero_kernel(float *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+
 template <int TT, bool KEEP, int MAXT = 768>
 hipError_t launch_dense(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx, const uint4 *pieces,
                         int8_t *Xq, float *sx, hipStream_t st)
@@ -323,6 +364,21 @@ size_t rotation_frags32_bytes(int K) { return (size_t)K * kBlock * sizeof(float)
 hipError_t launch_rotation_frags32(const float *R, int K, void *frags, hipStream_t st)
 {
     hipLaunchKernelGGL(rotation_frags32_kernel, dim3(64, K / kBlock), dim3(256), 0, st, R, static_cast<float *>(frags));
+    return hipGetLastError();
+}
+
+hipError_t launch_channel_absmax_dense(const uint16_t *X, int64_t M, int K, int64_t ldx, const void *pieces,
+                                       float *mag, hipStream_t st)
+{
+    hipLaunchKernelGGL(dense_fill_zero_kernel, dim3((K + 255) / 256), dim3(256), 0, st, mag, K);
+    if (M == 0) return hipGetLastError();
+    const int nb = K / kBlock;
+    const int64_t groups = (M + 15) / 16;
+    int64_t chunks = (groups + 3) / 4;
+    const int64_t most = (256 * 8 + nb - 1) / nb;       // about eight workgroups per compute unit over all blocks
+    if (chunks > most) chunks = most;
+    hipLaunchKernelGGL(channel_absmax_dense_kernel, dim3((unsigned)chunks, nb), dim3(256), 0, st, X, M, nb, ldx,
+                       static_cast<const uint4 *>(pieces), mag);
     return hipGetLastError();
 }
 

@@ -84,8 +84,11 @@ hipError_t launch_cosine_similarity(const uint16_t *A, const uint16_t *B, int n_
                                     int64_t stride_a, int64_t stride_b, double *acc_ws, float *out, hipStream_t st);
 size_t greedy_workspace_bytes(int64_t Mc, int K);
 hipError_t launch_greedy_rotation(const uint16_t *X, int64_t Mc, int K, int64_t ldx, const float *diag,
+                                  const float *R1, const int32_t *perm,   // null, or: start from ((X d) R1)[:, perm]
                                   const double *Q, int n_steps, void *workspace, float *R_out, int *n_out_dev,
                                   hipStream_t st);
+hipError_t launch_channel_absmax_dense(const uint16_t *X, int64_t M, int K, int64_t ldx, const void *pieces,
+                                       float *mag, hipStream_t st);
 size_t rotation_pieces_bytes(int K);
 hipError_t launch_rotation_pieces(const float *R, const float *diag, int K, void *pieces, hipStream_t st);
 bool rotate_quant_dense_supports(int K);

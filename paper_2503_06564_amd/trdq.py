@@ -27,6 +27,7 @@ SYMBOLS = [
     "trdq_cosine_similarity", "trdq_share_plan",
     "trdq_rotation_create", "trdq_rotation_destroy", "trdq_prepare_weights_dense", "trdq_rotate_quant_dense",
     "trdq_greedy_rotation", "trdq_prepare_weights_dense_rpr", "trdq_rotate_quant_dense_rpr",
+    "trdq_channel_absmax_dense", "trdq_greedy_rotation_second",
 ]
 
 _lib = None
@@ -87,6 +88,8 @@ def lib():
         L.trdq_greedy_rotation.argtypes = [p, i64, i32, i64, p, i32, p, i32, p, p, p]
         L.trdq_prepare_weights_dense_rpr.argtypes = [p, i32, i32, p, p, p, i32, p, C.POINTER(p)]
         L.trdq_rotate_quant_dense_rpr.argtypes = [p, i64, i64, p, p, p, p, p, p]
+        L.trdq_channel_absmax_dense.argtypes = [p, i64, i64, p, p, p]
+        L.trdq_greedy_rotation_second.argtypes = [p, i64, i64, p, p, p, i32, p, p, p]
         L.trdq_qgemm_asym.argtypes = [p, p, p, p, i64, p, p, i64, p, p]
         L.trdq_channel_absmax.argtypes = [p, i64, i32, i64, p, i32, i32, p, p]
         L.trdq_weight_row_absmax.argtypes = [p, i32, i32, p, p]
@@ -305,6 +308,24 @@ def greedy_rotation(X, diag, Q, R_out, block=BLOCK, stream=None):
     n = np.zeros(K // block, dtype=np.int32)
     _check(lib().trdq_greedy_rotation(_ptr(X), M, K, ldx, _ptr(diag), block, _ptr(Q), Q.shape[0], _ptr(R_out),
                                       n.ctypes.data, _stream(stream)), "trdq_greedy_rotation")
+    return n
+
+
+def channel_absmax_dense(X, rot, mag, stream=None):
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    _check(lib().trdq_channel_absmax_dense(_ptr(X), M, ldx, rot.handle, _ptr(mag), _stream(stream)),
+           "trdq_channel_absmax_dense")
+
+
+def greedy_rotation_second(X, rot1, perm, Q, R_out, stream=None):
+    """Eq. 6-7 for the second rotation: the search runs on ((X d) R1)[:, perm]."""
+    import numpy as np
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    n = np.zeros(K // BLOCK, dtype=np.int32)
+    _check(lib().trdq_greedy_rotation_second(_ptr(X), M, ldx, rot1.handle, _ptr(perm), _ptr(Q), Q.shape[0], _ptr(R_out),
+                                             n.ctypes.data, _stream(stream)), "trdq_greedy_rotation_second")
     return n
 
 

@@ -249,3 +249,12 @@ def test_greedy_rotation_argument_errors_before_any_gpu_call():
     assert call(0x1000, 0, 256, 256, None, 128, 0x2000, 4, 0x3000, None, None) == trdq.ERR_SHAPE
     assert call(0x1000, 16, 256, 256, None, 128, 0x2000, 0, 0x3000, None, None) == trdq.ERR_SHAPE
     assert call(0x1000, 16, 256, 256, None, 128, 0x2000, 5000, 0x3000, None, None) == trdq.ERR_UNSUPPORTED
+
+
+def test_dense_calibration_argument_errors_before_any_gpu_call():
+    L = trdq.lib()
+    assert L.trdq_channel_absmax_dense(0x1000, 4, 256, None, 0x2000, None) == trdq.ERR_NULL
+    assert L.trdq_greedy_rotation_second(0x1000, 4, 256, None, 0x2000, 0x3000, 4, 0x4000, None, None) == trdq.ERR_NULL
+    out = C.c_void_p()
+    assert L.trdq_prepare_weights_dense_rpr(0x1000, 256, 64, None, 0x2000, None, 8, None, C.byref(out)) == trdq.ERR_NULL
+    assert L.trdq_rotate_quant_dense_rpr(0x1000, 4, 256, None, 0x2000, None, 0x3000, 0x4000, None) == trdq.ERR_NULL

@@ -242,3 +242,61 @@ def test_dense_rpr_argument_errors():
     assert e.value.status == trdq.ERR_UNSUPPORTED
     for r in (rot1, rot2_bad, rot2, wide1, wide2):
         r.close()
+
+
+@pytest.mark.parametrize("Mc,K,steps", [(128, 256, 6), (500, 1152, 10)])
+def test_time_rotation_calibration_chain(oracle, Mc, K, steps):
+    """Sec. 3.2 end to end on the GPU: greedy R1, channel maxima after it, zigzag P, greedy R2 on the
+    rotated and permuted activations; every stage against the oracle, then the rotated linear."""
+    say(f"calibration chain Mc={Mc} K={K} steps={steps}")
+    N = 144
+    Xcal, W, d, bias = wl.small_case(73, Mc, K, N, n_outliers=max(2, K // 100), outlier=60.0)
+    Q1 = wl.orthogonal_uniform_first_row(12, steps)
+    Q2 = wl.orthogonal_uniform_first_row(13, steps)
+    X = bf16_to_dev(Xcal)
+    dd = f32_to_dev(d)
+    nb = K // 128
+    # first rotation
+    R1 = torch.zeros((nb, 128, 128), dtype=torch.float32, device=dev())
+    n1 = trdq.greedy_rotation(X, dd, torch.from_numpy(Q1).to(dev()), R1)
+    R1_o, n1_o = oracle.greedy_rotations(Xcal, d, Q1)
+    assert np.array_equal(n1, n1_o) and np.abs(R1.cpu().numpy() - R1_o).max() < 1e-6
+    rot1 = trdq.Rotation(R1, dd)
+    R1h = R1.cpu().numpy()
+    # channel maxima after it, permutation
+    mag = torch.full((K,), -1.0, dtype=torch.float32, device=dev())
+    trdq.channel_absmax_dense(X, rot1, mag)
+    torch.cuda.synchronize()
+    V1 = oracle.rotate_dense(Xcal, d, R1h)
+    assert np.allclose(mag.cpu().numpy(), np.abs(V1).max(axis=0), rtol=1e-5, atol=0)
+    perm = trdq.zigzag_permutation(mag.cpu().numpy())
+    assert np.array_equal(perm, oracle.zigzag(mag.cpu().numpy().astype(np.float64), 128))
+    perm_dev = torch.from_numpy(perm).to(dev())
+    # second rotation on the rotated, permuted activations
+    R2 = torch.zeros((nb, 128, 128), dtype=torch.float32, device=dev())
+    n2 = trdq.greedy_rotation_second(X, rot1, perm_dev, torch.from_numpy(Q2).to(dev()), R2)
+    V2 = V1[:, perm.astype(np.int64)]
+    for b in range(nb):
+        R2_o, n2_o, _ = oracle.greedy_rotation(V2[:, b * 128:(b + 1) * 128], Q2)
+        assert n2[b] == n2_o and np.abs(R2[b].cpu().numpy() - R2_o).max() < 1e-6
+    rot2 = trdq.Rotation(R2)
+    # the rotated linear with what was calibrated
+    M = min(Mc, 96)
+    Xb = Xcal[:M]
+    w = trdq.prepare_weights_dense_rpr(f32_to_dev(W), rot1, perm_dev, rot2)
+    Xq = torch.empty((M, K), dtype=torch.int8, device=dev())
+    sx = torch.empty((M,), dtype=torch.float32, device=dev())
+    trdq.rotate_quant_dense_rpr(bf16_to_dev(Xb), rot1, perm_dev, rot2, Xq, sx)
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device=dev())
+    trdq.qgemm(w, Xq, sx, Y, bias=f32_to_dev(bias))
+    torch.cuda.synchronize()
+    ref = oracle.linear_dense_rpr(Xb, W, d, R1h, perm, R2.cpu().numpy(), bias, exact_blas=True)
+    rows = np.any(Xq.cpu().numpy() != ref["Xq"], axis=1)
+    cols = np.any(w.export()[0] != ref["Wq"], axis=0)
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (calibrated R1 P R2)", skip_rows=rows, skip_cols=cols)
+    exact = oracle.bf16_to_f64(Xb) @ W.astype(np.float64) + bias
+    err = np.abs(oracle.bf16_to_f64(bf16_to_host(Y)) - exact).mean()
+    eye = np.stack([np.eye(128, dtype=np.float32)] * nb)
+    err_plain = np.abs(oracle.linear_dense(Xb, W, d, eye, bias)["Yd"] - exact).mean()
+    assert err < 0.5 * err_plain, (err, err_plain)
+    w.close(); rot1.close(); rot2.close()
