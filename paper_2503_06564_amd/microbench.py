@@ -1,0 +1,128 @@
+"""Timings of the entry points outside bench.py's step (one MI355X, synthetic inputs):
+
+    python -m paper_2503_06564_amd.microbench fused      # trdq_linear_fused against the unfused pair, 16..4096 tokens
+    python -m paper_2503_06564_amd.microbench dense      # dense-block rotate+quantise passes against the Hadamard ones
+    python -m paper_2503_06564_amd.microbench greedy     # greedy construction of the rotation blocks (Eq. 6-7)
+    python -m paper_2503_06564_amd.microbench cosine     # Eq. 11 on attention-sized tensors
+    python -m paper_2503_06564_amd.microbench all
+
+Back-to-back launches between two events on the launch stream, cycling through a few input sets;
+one line of JSON per measurement.  Inputs are N(0, 1) activations and seeded orthogonal blocks; the
+figures do not depend on the values."""
+import argparse
+import json
+import time
+
+import numpy as np
+import torch
+
+from . import trdq, workloads as wl
+
+
+def _timeit(fn, iters=50, warm=5):
+    st = torch.cuda.current_stream()
+    for i in range(warm):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(st)
+    for i in range(iters):
+        fn(i)
+    e1.record(st)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / iters          # microseconds
+
+
+def _out(**kw):
+    print(json.dumps(kw), flush=True)
+
+
+def fused(dev):
+    for kind in ("proj", "qkv"):
+        K, N = wl.LAYER_SHAPES[kind]
+        for M in (16, 128, 256, 512, 1024, 2048, 4096):
+            R = 4
+            g = torch.Generator(device="cpu").manual_seed(0)
+            Xs = [torch.randn((M, K), generator=g).to(torch.bfloat16).to(dev) for _ in range(R)]
+            d = torch.ones(K, device=dev) * 1.25
+            Xq = torch.empty((M, K), dtype=torch.int8, device=dev)
+            sx = torch.empty((M,), device=dev)
+            Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+            W = torch.randn((K, N), generator=g).to(dev) * 0.02
+            bias = torch.zeros(N, device=dev)
+            ws = [trdq.prepare_weights(W, d, wbits=8) for _ in range(R)]
+            fu = [trdq.bind_linear_fused(Xs[i], d, ws[i], Y, bias=bias) for i in range(R)]
+            rq = [trdq.bind_rotate_quant(Xs[i], d, Xq, sx, warm=ws[i]) for i in range(R)]
+            gm = [trdq.bind_qgemm(ws[i], Xq, sx, Y, bias=bias) for i in range(R)]
+
+            def pair(i):
+                rq[i % R]()
+                gm[i % R]()
+            _out(what="linear_fused vs rotate_quant+qgemm", layer=kind, tokens=M,
+                 fused_us=round(_timeit(lambda i: fu[i % R](), 200, 10), 2), pair_us=round(_timeit(pair, 200, 10), 2))
+
+
+def dense(dev):
+    for M in (4096, 32768):
+        for K in (1152, 4608):
+            R = 4
+            Xs = [torch.randn((M, K), device=dev).to(torch.bfloat16) for _ in range(R)]
+            d = torch.ones(K, device=dev) * 1.25
+            R1 = torch.from_numpy(wl.orthogonal_uniform_first_row(1, K // 128).astype(np.float32)).to(dev)
+            rot1 = trdq.Rotation(R1, d)
+            perm = torch.randperm(K, device=dev).to(torch.int32)
+            Xq = torch.empty((M, K), dtype=torch.int8, device=dev)
+            sx = torch.empty((M,), device=dev)
+            row = dict(what="rotate+quantise passes", tokens=M, K=K,
+                       hadamard_us=round(_timeit(lambda i: trdq.rotate_quant(Xs[i % R], d, Xq, sx)), 1),
+                       dense_us=round(_timeit(lambda i: trdq.rotate_quant_dense(Xs[i % R], rot1, Xq, sx)), 1),
+                       hadamard_rpr_us=round(_timeit(lambda i: trdq.rotate_quant_rpr(Xs[i % R], d, perm, Xq, sx)), 1))
+            if K <= 1536:
+                R2 = torch.from_numpy(wl.orthogonal_uniform_first_row(2, K // 128).astype(np.float32)).to(dev)
+                rot2 = trdq.Rotation(R2)
+                row["dense_rpr_us"] = round(_timeit(lambda i: trdq.rotate_quant_dense_rpr(Xs[i % R], rot1, perm, rot2, Xq, sx)), 1)
+            _out(**row)
+
+
+def greedy(dev):
+    for Mc, K, steps in ((4096, 1152, 64), (4096, 4608, 64), (1024, 1152, 256)):
+        X = torch.randn((Mc, K), device=dev).to(torch.bfloat16)
+        d = torch.ones(K, device=dev)
+        Q = torch.from_numpy(wl.orthogonal_uniform_first_row(1, steps)).to(dev)
+        Rout = torch.zeros((K // 128, 128, 128), device=dev)
+        trdq.greedy_rotation(X, d, Q, Rout)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n = trdq.greedy_rotation(X, d, Q, Rout)
+        torch.cuda.synchronize()
+        t = time.perf_counter() - t0
+        _out(what="greedy_rotation (Eq. 6-7)", calibration_tokens=Mc, K=K, steps=steps, ms=round(t * 1e3, 2),
+             us_per_step=round(t / steps * 1e6, 1), chosen_steps=n.tolist())
+
+
+def cosine(dev):
+    for n, L in ((1, 4096 * 1152), (28, 4096 * 1152), (16, 256 * 1152)):
+        R = 2
+        As = [torch.randn((n, L), device=dev).to(torch.bfloat16) for _ in range(R)]
+        Bs = [torch.randn((n, L), device=dev).to(torch.bfloat16) for _ in range(R)]
+        ws = torch.zeros(3 * n, dtype=torch.float64, device=dev)
+        out = torch.zeros(n, device=dev)
+        t = _timeit(lambda i: trdq.cosine_similarity(As[i % R], Bs[i % R], ws, out), 20, 3)
+        _out(what="cosine_similarity (Eq. 11)", segments=n, elements=L, us=round(t, 1), tb_per_s=round(4 * n * L / t / 1e6, 2))
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("what", choices=["fused", "dense", "greedy", "cosine", "all"])
+    a = ap.parse_args()
+    if not torch.cuda.is_available():
+        raise SystemExit("microbench needs the GPU")
+    trdq.lib()
+    dev = torch.device("cuda:0")
+    for name, fn in (("fused", fused), ("dense", dense), ("greedy", greedy), ("cosine", cosine)):
+        if a.what in (name, "all"):
+            fn(dev)
+
+
+if __name__ == "__main__":
+    main()
