@@ -261,6 +261,16 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, con
                         int variant, hipStream_t st)
 {
     if (M == 0) return hipSuccess;
+    // A ragged token count would send the whole product to the kernel that takes any shape.  With the
+    // built-in choice and int8 weights, the whole 256-token (or 128-token) panels go to the fast kernels
+    // and only the remaining rows to that kernel, as a second launch on the same stream.
+    if (variant < 0 && w.wbits == 8 && M >= 1024 && M % 128 != 0) {
+        const int64_t head = M - M % (M % 256 < 128 ? 256 : 128);
+        hipError_t e = launch_qgemm(w, Xq, sx, zc, head, bias, Y, ldy, acc_debug, variant, st);
+        if (e != hipSuccess) return e;
+        return launch_qgemm(w, Xq + head * w.K, sx + head, zc ? zc + head : nullptr, M - head, bias, Y + head * ldy, ldy,
+                            acc_debug ? acc_debug + head * w.N : nullptr, variant, st);
+    }
     GemmArgs a;
     a.Xq = Xq; a.Wc = w.codes; a.sx = sx; a.sw = w.scales; a.bias = bias; a.Y = Y;
     a.acc_debug = acc_debug; a.M = M; a.ldy = ldy; a.K = w.K; a.N = w.N;

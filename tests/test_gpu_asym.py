@@ -71,7 +71,7 @@ def test_rotate_quant_asym_one_sided_and_zero_rows(oracle):
 # splitting K (even and odd numbers of k-tiles), two workgroups per compute unit (more than 256 tiles)
 @pytest.mark.parametrize("M,K,N", [(1, 128, 16), (17, 256, 144), (300, 4608, 272), (513, 384, 400), (1024, 1152, 1152),
                                    (256, 1152, 288), (256, 2304, 144), (384, 4608, 144), (256, 2432, 144),
-                                   (4224, 512, 1152)])
+                                   (4224, 512, 1152), (1100, 1152, 1152), (1407, 2304, 144)])
 def test_linear_asym_end_to_end(oracle, M, K, N):
     say(f"linear asymmetric M={M} K={K} N={N}")
     Xb, W, d, bias = wl.small_case(42, M, K, N, n_outliers=max(1, K // 144), outlier=40.0)

@@ -167,6 +167,15 @@ def test_qgemm_w8_pipelined_full_tiles(oracle, M, K, N, variant):
     _linear_case(oracle, 13, M, K, N, 8, variant)
 
 
+# ragged token counts with the built-in choice: whole panels on the fast kernels, the remaining rows on the
+# kernel that takes any shape (two launches); tails shorter and longer than 128 rows, 144- and 128-wide tiles
+@pytest.mark.parametrize("M,K,N", [(1100, 1152, 1152), (1025, 256, 288), (2180, 384, 400), (1407, 2304, 144),
+                                   (4100, 512, 1152)])
+def test_qgemm_w8_ragged_tokens_split(oracle, M, K, N):
+    say(f"qgemm W8 ragged tokens M={M} K={K} N={N}")
+    _linear_case(oracle, 15, M, K, N, 8, -1)
+
+
 # more output tiles than compute units (workgroups of the persistent kernels walk several
 # tiles), with two and three k-tiles, ragged and full edges, both tile orders
 @pytest.mark.parametrize("M,K,N", [(4352, 256, 4400), (4096, 384, 4608), (2304, 1152, 1152)])
