@@ -67,9 +67,9 @@ const char *trdq_status_str(trdq_status s);
 int trdq_abi_version(void);
 
 /* ------------------------------------------------------------------ table
- * Time-step -> group table ("activations select R, P and Delta based on the
- * current time-step", Sec. 3.2 Time-Steps Awareness; t in {1..N}, Eq. 10;
- * indexed here by sampling-step index 0..n_steps-1).  Host object. */
+ * Time-step -> group table: the diagonal, rotation and permutation in use depend on
+ * the sampling step (Sec. 3.2, the paragraph on time-step awareness; t in {1..N},
+ * Eq. 10; indexed here by sampling-step index 0..n_steps-1).  Host object. */
 typedef struct trdq_table trdq_table;
 
 /* map_host: n_steps entries in [0, n_groups), copied; NULL selects the contiguous
@@ -118,7 +118,7 @@ void trdq_weights_destroy(trdq_weights *w);
 
 /* ----------------------------------------------------------------- online
  * G_t(X_t) of Eq. 10 followed by the per-token dynamic quantiser (Sec. 3.1,
- * Eq. 1-2 symmetric; "quantization parameters computed online", Sec. 3.2):
+ * Eq. 1-2 symmetric; the scale comes from the row itself at run time, Sec. 3.2):
  *   V = (X . diag) . R,   s_x[i] = max_k |V[i,k]| / 127,
  *   Xq[i,k] = rint(V[i,k] / s_x[i]);   an all-zero row gives s_x = 0, codes 0.
  * X_dev:  bf16 [M, K], row stride ldx elements (ldx >= K, ldx % 8 == 0, 16-byte aligned base).

@@ -10,8 +10,8 @@
  * What it computes (paper Sec. 3.1-3.2):
  *   F_t(X_t, W) = G_t(X_t) . H_t(W)                             (Eq. 10)
  *   G_t(X) = (X . Delta_t) . R           H_t(W) = R^T . (Delta_t^-1 . W)
- * with P = I and R^(2) = I (single block rotation; the functions of the section
- * "second rotation and zigzag permutation" add P and R^(2) of Eq. 9), R block-diagonal with
+ * with P = I and R^(2) = I (single block rotation; the functions further down that
+ * permute channels and rotate a second time add P and R^(2) of Eq. 9), R block-diagonal with
  * 2^n x 2^n blocks (the BlockDiag equation of Sec. 3.2), each block the
  * orthonormal Sylvester Hadamard matrix.  Activations are quantised per
  * token online, weights per output channel (W8) or per (input-group,
@@ -76,8 +76,8 @@ double trdq_oracle_bf16_to_f64(uint16_t h) { return bf16_bits_to_f64(h); }
 /* ------------------------------------------------------- time-step table */
 
 /* Default step -> group map: contiguous, near-equal partition of the
- * sampling steps ("divides the sampling process based on time-steps",
- * abstract; t in {1..N}, Eq. 10 -- indexed here from 0). */
+ * sampling steps (the method splits the sampling process by time step and keeps
+ * one set of parameters per part: abstract; t in {1..N}, Eq. 10 -- indexed here from 0). */
 int trdq_oracle_table_default(int n_steps, int n_groups, int32_t *map)
 {
     if (n_steps <= 0 || n_groups <= 0 || n_groups > n_steps || !map) return 1;
