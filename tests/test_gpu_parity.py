@@ -176,6 +176,25 @@ def test_qgemm_w8_ragged_tokens_split(oracle, M, K, N):
     _linear_case(oracle, 15, M, K, N, 8, -1)
 
 
+def _random_shapes(n, seed):
+    r = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(n):
+        M = int(r.choice([r.integers(1, 64), r.integers(64, 1200), r.integers(1200, 5000)]))
+        K = 128 * int(r.integers(1, 13))
+        N = int(r.choice([16 * r.integers(1, 80), 144 * r.integers(1, 9), 128 * r.integers(1, 10)]))
+        shapes.append((M, K, N))
+    return shapes
+
+
+# seeded random shapes through the built-in choice: whatever kernel, split or fallback the shape selects
+@pytest.mark.parametrize("M,K,N", _random_shapes(16, 2024))
+@pytest.mark.parametrize("wbits", [8, 4])
+def test_linear_random_shapes_builtin_choice(oracle, M, K, N, wbits):
+    say(f"random shape M={M} K={K} N={N} wbits={wbits}")
+    _linear_case(oracle, 16, M, K, N, wbits, -1)
+
+
 # more output tiles than compute units (workgroups of the persistent kernels walk several
 # tiles), with two and three k-tiles, ragged and full edges, both tile orders
 @pytest.mark.parametrize("M,K,N", [(4352, 256, 4400), (4096, 384, 4608), (2304, 1152, 1152)])
