@@ -123,11 +123,10 @@ __device__ __forceinline__ void store_codes_dense(const float (&o)[8][4], float 
     dst[1] = make_uint4(c[4], c[5], c[6], c[7]);
 }
 
-// KEEP: a wave has one block (nb <= waves) and keeps its results in registers across the exchange
-// of the token maxima.  Otherwise (wide rows: several blocks per wave, whose results would not fit
-// the registers) a wave rotates its blocks twice: once for the maxima, once more to quantise.
-template <int TT, bool KEEP, int MAXT>
-__global__ __launch_bounds__(MAXT) void rotate_quant_dense_kernel(
+// A wave has one block (nb <= waves <= 12) and keeps its results in registers across the exchange of
+// the token maxima.  Wider rows take the block-resident kernels further down.
+template <int TT>
+__global__ __launch_bounds__(768) void rotate_quant_dense_kernel(
     const uint16_t *__restrict__ X, int64_t M, int nb, int64_t ldx, const uint4 *__restrict__ pieces,
     int8_t *__restrict__ Xq, float *__restrict__ sx)
 {
@@ -147,8 +146,7 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_dense_kernel(
         float amax[TT];
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) amax[tt] = 0.0f;
-        for (int b = wave; b < nb; b += nw)             // KEEP: at most one pass
-            rotate_block_dense<TT>(X, M, ldx, pieces, b, tok0, lane, out, amax);
+        if (wave < nb) rotate_block_dense<TT>(X, M, ldx, pieces, wave, tok0, lane, out, amax);
         // token maximum: over the four lane groups, then over the waves
         float *const am = amax_s + parity * nw * TOK;
 #pragma unroll
@@ -170,26 +168,161 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_dense_kernel(
             inv[tt] = a > 0.0f ? 127.0f / a : 0.0f;
             if (wave == 0 && g == 0 && token_ok[tt]) sx[token] = a / 127.0f;
         }
-        if constexpr (KEEP) {
-            if (wave < nb) {
+        if (wave < nb) {
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-                    if (token_ok[tt])
-                        store_codes_dense(out[tt], inv[tt], Xq + (tok0 + tt * 16 + l16) * K + wave * kBlock + 32 * g);
-            }
-        } else {
-            for (int b = wave; b < nb; b += nw) {
-                float unused[TT];
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) unused[tt] = 0.0f;
-                rotate_block_dense<TT>(X, M, ldx, pieces, b, tok0, lane, out, unused);
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-                    if (token_ok[tt])
-                        store_codes_dense(out[tt], inv[tt], Xq + (tok0 + tt * 16 + l16) * K + b * kBlock + 32 * g);
-            }
+            for (int tt = 0; tt < TT; ++tt)
+                if (token_ok[tt])
+                    store_codes_dense(out[tt], inv[tt], Xq + (tok0 + tt * 16 + l16) * K + wave * kBlock + 32 * g);
         }
     }
+}
+
+// ---- wide rows: a workgroup per block, its pieces resident in LDS -----------------------------
+// Rows wider than 12 blocks do not fit the kernel above (a wave per block, results kept in
+// registers).  Here a workgroup of eight waves takes ONE block, copies its pieces to LDS once and
+// walks its share of the token tiles, TT at a time per wave (every LDS fragment read feeds TT
+// matrix instructions); the activation fragments come straight from global memory, each wave its
+// own tokens, one group of tiles ahead.  The token maximum spans blocks, i.e. workgroups, so there
+// are two passes: QUANT = false merges |out| maxima into sx with atomic maxima on the bit patterns
+// (non-negative floats order like integers; sx cleared before), QUANT = true repeats the products,
+// quantises and stores; a last kernel turns the maxima in sx into scales.
+template <bool QUANT, int TT>
+__global__ __launch_bounds__(512) void rotate_dense_block_kernel(
+    const uint16_t *__restrict__ X, int64_t M, int nb, int64_t ldx, const uint4 *__restrict__ pieces,
+    float *__restrict__ sx, int8_t *__restrict__ Xq)
+{
+    extern __shared__ __align__(16) uint4 lds_pieces[];           // [12][8][64] fragments of this block
+    const int K = nb * kBlock;
+    const int b = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+    for (int i = threadIdx.x; i < kPiecesPerBlock; i += 512) lds_pieces[i] = pieces[(size_t)b * kPiecesPerBlock + i];
+    __syncthreads();
+
+    constexpr int TOK = 16 * TT;
+    const int64_t groups = (M + TOK - 1) / TOK;                   // groups of TT 16-token tiles
+    const int64_t stride = (int64_t)gridDim.x * 8;
+    auto load_x = [&](v8bf (&xf)[TT][4], int64_t gr) {
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            int64_t token = gr * TOK + tt * 16 + l16;
+            if (token >= M) token = M - 1;                        // repeated rows: their results are not stored
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                union { uint4 u; v8bf v; } ld;
+                ld.u = *reinterpret_cast<const uint4 *>(X + token * ldx + b * kBlock + 32 * s + 8 * g);
+                xf[tt][s] = ld.v;
+            }
+        }
+    };
+    int64_t gr = (int64_t)blockIdx.x * 8 + wave;
+    v8bf xcur[TT][4], xnext[TT][4];
+    if (gr < groups) load_x(xcur, gr);
+    for (; gr < groups; gr += stride) {
+        const int64_t nxt = gr + stride < groups ? gr + stride : gr;  // the last iteration re-reads its own tiles
+        load_x(xnext, nxt);
+        float inv[TT], amax[TT];
+        int64_t token[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            token[tt] = gr * TOK + tt * 16 + l16;
+            amax[tt] = 0.0f;
+            inv[tt] = 0.0f;
+            if constexpr (QUANT) {
+                if (token[tt] < M) {
+                    const float a = sx[token[tt]];
+                    inv[tt] = a > 0.0f ? 127.0f / a : 0.0f;
+                }
+            }
+        }
+        uint32_t code[QUANT ? TT : 1][8];
+        int lane_off = lane;                                      // keeps the fragment reads inside this loop
+        asm volatile("" : "+v"(lane_off));
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            v4f acc[TT];
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) acc[tt] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int q = 11; q >= 0; --q) {                       // smallest piece first
+                union { uint4 u; v8bf v; } a;
+                a.u = lds_pieces[(q * 8 + t) * 64 + lane_off];
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+                    acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, xcur[tt][q & 3], acc[tt], 0, 0, 0);
+            }
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                if constexpr (QUANT)
+                    code[tt][t] = pack4_low_bytes(quant_bits(acc[tt][0], inv[tt]), quant_bits(acc[tt][1], inv[tt]),
+                                                  quant_bits(acc[tt][2], inv[tt]), quant_bits(acc[tt][3], inv[tt]));
+                else
+                    amax[tt] = fmaxf(amax[tt], fmaxf(fmaxf(fabsf(acc[tt][0]), fabsf(acc[tt][1])),
+                                                     fmaxf(fabsf(acc[tt][2]), fabsf(acc[tt][3]))));
+            }
+        }
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            if constexpr (QUANT) {
+                if (token[tt] < M) {
+                    uint4 *dst = reinterpret_cast<uint4 *>(Xq + token[tt] * K + b * kBlock + 32 * g);
+                    dst[0] = make_uint4(code[tt][0], code[tt][1], code[tt][2], code[tt][3]);
+                    dst[1] = make_uint4(code[tt][4], code[tt][5], code[tt][6], code[tt][7]);
+                }
+            } else {
+                float m = fmaxf(amax[tt], __shfl_xor(amax[tt], 16));
+                m = fmaxf(m, __shfl_xor(m, 32));
+                if (g == 0 && token[tt] < M) atomicMax(reinterpret_cast<unsigned int *>(sx + token[tt]), __float_as_uint(m));
+            }
+        }
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) xcur[tt][s] = xnext[tt][s];
+    }
+}
+
+__global__ void dense_clear_kernel(float *sx, int64_t M)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < M) sx[i] = 0.0f;
+}
+
+__global__ void dense_scale_kernel(float *sx, int64_t M)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < M) sx[i] = sx[i] / 127.0f;
+}
+
+template <int TT>
+hipError_t launch_dense_blocks(const uint16_t *X, int64_t M, int nb, int64_t ldx, const uint4 *pieces,
+                               int8_t *Xq, float *sx, hipStream_t st)
+{
+    const int64_t groups = (M + 16 * TT - 1) / (16 * TT);
+    int64_t chunks = 256 / nb;                  // rounded down: a 257th workgroup would wait for a second round
+    const int64_t most = (groups + 7) / 8;
+    if (chunks > most) chunks = most;
+    if (chunks < 1) chunks = 1;
+    const size_t smem = (size_t)kPiecesPerBlock * 16;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(rotate_dense_block_kernel<false, TT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(rotate_dense_block_kernel<true, TT>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    const unsigned mg = (unsigned)((M + 255) / 256);
+    hipLaunchKernelGGL(dense_clear_kernel, dim3(mg), dim3(256), 0, st, sx, M);
+    hipLaunchKernelGGL((rotate_dense_block_kernel<false, TT>), dim3((unsigned)chunks, nb), dim3(512), smem, st,
+                       X, M, nb, ldx, pieces, sx, Xq);
+    hipLaunchKernelGGL((rotate_dense_block_kernel<true, TT>), dim3((unsigned)chunks, nb), dim3(512), smem, st,
+                       X, M, nb, ldx, pieces, sx, Xq);
+    hipLaunchKernelGGL(dense_scale_kernel, dim3(mg), dim3(256), 0, st, sx, M);
+    return hipGetLastError();
 }
 
 // ---- Eq. 10 in full with dense blocks: (X . Delta) . BlockDiag(R1) . P . BlockDiag(R2) -----------
@@ -336,14 +469,14 @@ __global__ void dense_fill_zero_kernel(float *p, int n)
     if (i < n) p[i] = 0.0f;
 }
 
-template <int TT, bool KEEP, int MAXT = 768>
+template <int TT>
 hipError_t launch_dense(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx, const uint4 *pieces,
                         int8_t *Xq, float *sx, hipStream_t st)
 {
     const int64_t groups = (M + 16 * TT - 1) / (16 * TT);
     const int64_t grid = groups < 256 ? groups : 256;      // persistent: one workgroup per compute unit
     const size_t smem = sizeof(float) * 2 * nw * 16 * TT;
-    hipLaunchKernelGGL((rotate_quant_dense_kernel<TT, KEEP, MAXT>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
+    hipLaunchKernelGGL((rotate_quant_dense_kernel<TT>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
                        X, M, nb, ldx, pieces, Xq, sx);
     return hipGetLastError();
 }
@@ -411,14 +544,12 @@ hipError_t launch_rotate_quant_dense(const uint16_t *X, int64_t M, int K, int64_
     if (M == 0) return hipSuccess;
     const int nb = K / kBlock;
     const uint4 *pc = static_cast<const uint4 *>(pieces);
-    // up to 12 blocks: a wave per block, two token tiles per piece load once there are enough
-    // tokens to keep every compute unit busy; wider rows: 12 waves sharing the blocks, two passes
+    // Up to 12 blocks: one kernel, a wave per block of a 16-token group (two token tiles per piece load once
+    // there are enough tokens to keep every compute unit busy), pieces from L2, activations read once.
+    // Wider rows: a workgroup per block with its pieces in LDS, two passes over the activations.
     if (nb <= 12)
-        return M >= 256 * 32 ? launch_dense<2, true>(X, M, nb, nb, ldx, pc, Xq, sx, st)
-                             : launch_dense<1, true>(X, M, nb, nb, ldx, pc, Xq, sx, st);
-    // (with many tokens: eight waves, which leaves the registers for two token tiles per piece load)
-    return M >= 8192 ? launch_dense<2, false, 512>(X, M, nb, 8, ldx, pc, Xq, sx, st)
-                     : launch_dense<1, false>(X, M, nb, 12, ldx, pc, Xq, sx, st);
+        return M >= 8192 ? launch_dense<2>(X, M, nb, nb, ldx, pc, Xq, sx, st) : launch_dense<1>(X, M, nb, nb, ldx, pc, Xq, sx, st);
+    return launch_dense_blocks<2>(X, M, nb, ldx, pc, Xq, sx, st);
 }
 
 }  // namespace trdq

@@ -30,7 +30,8 @@ def _rq_dense(Xbits, rot):
     return Xq, sx
 
 
-# one block per wave with one and (from 8192 tokens) two token tiles; wide rows (more than 12 blocks) likewise
+# a wave per block of a 16-token group, one and (from 8192 tokens on) two token tiles per piece load; rows wider
+# than 12 blocks: a workgroup per block with its pieces in LDS, two passes
 @pytest.mark.parametrize("M,K", [(1, 128), (37, 256), (300, 1152), (40, 2304), (64, 4608), (8200, 1152), (8200, 1664),
                                  (0, 256)])
 def test_rotate_quant_dense_matches_oracle(oracle, M, K):
