@@ -52,9 +52,10 @@ __global__ __launch_bounds__(256) void rotation_pieces_kernel(const float *__res
 }
 
 // One block of one token group: out[tt][t][j] = rotated channel 32 g + 4 t + j of token tile tt's
-// token l16 (this lane), amax[tt] = running maximum of |out|.  The twelve A fragments of tile t + 1
-// (three pieces x four k-steps) are requested while tile t is multiplied; the scheduling barriers
-// keep the compiler from requesting all 96 at once (which would not fit the register file).
+// token l16 (this lane), amax[tt] = running maximum of |out|.  The A fragments (three pieces x four
+// k-steps per tile) are requested one chunk ahead of the products; the scheduling barriers keep the
+// compiler from requesting all 96 at once (which would not fit the register file) and from sinking
+// the requests to just before their use (which would expose every load's latency).
 template <int TT>
 __device__ __forceinline__ void rotate_block_dense(const uint16_t *__restrict__ X, int64_t M, int64_t ldx,
                                                    const uint4 *__restrict__ pieces, int b, int64_t tok0, int lane,
@@ -79,33 +80,43 @@ __device__ __forceinline__ void rotate_block_dense(const uint16_t *__restrict__ 
     int lane_off = lane;
     asm volatile("" : "+v"(lane_off));
     const uint4 *pb = pieces + (size_t)b * kPiecesPerBlock + lane_off;
-    uint4 fa[2][12];
-    auto request = [&](uint4 (&f)[12], int t) {
+    // The 96 fragments go through a two-deep ring of chunks of six (half a tile: k-steps and pieces in the
+    // order they are multiplied, smallest piece first): chunk i + 1 is requested, then chunk i multiplied.
+    constexpr int CH = 6, NCH = 12 / CH;
+    uint4 fa[2][CH];
+    auto request = [&](uint4 (&f)[CH], int i) {          // chunk i: tile i / NCH, fragments q = 11 - CH (i % NCH) - e
+        const int t = i / NCH, q0 = 11 - CH * (i % NCH);
 #pragma unroll
-        for (int q = 0; q < 12; ++q) f[q] = pb[(q * 8 + t) * 64];      // q = piece * 4 + k-step
+        for (int e = 0; e < CH; ++e) f[e] = pb[((q0 - e) * 8 + t) * 64];      // q = piece * 4 + k-step
     };
     request(fa[0], 0);
+    v4f acc[TT];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        if (t + 1 < 8) request(fa[(t + 1) & 1], t + 1);
-        v4f acc[TT];
+    for (int i = 0; i < 8 * NCH; ++i) {
+        if (i + 1 < 8 * NCH) request(fa[(i + 1) & 1], i + 1);
+        __builtin_amdgcn_sched_barrier(0);      // the requests go out before this chunk's products, not after them
+        const int t = i / NCH, q0 = 11 - CH * (i % NCH);
+        if (i % NCH == 0) {
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) acc[tt] = v4f{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int q = 11; q >= 0; --q) {                 // smallest piece first
-            union { uint4 u; v8bf v; } a;
-            a.u = fa[t & 1][q];
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt)
-                acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, xf[tt][q & 3], acc[tt], 0, 0, 0);
+            for (int tt = 0; tt < TT; ++tt) acc[tt] = v4f{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt)
+        for (int e = 0; e < CH; ++e) {
+            union { uint4 u; v8bf v; } a;
+            a.u = fa[i & 1][e];
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                out[tt][t][jj] = acc[tt][jj];
-                amax[tt] = fmaxf(amax[tt], fabsf(acc[tt][jj]));
-            }
+            for (int tt = 0; tt < TT; ++tt)
+                acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, xf[tt][(q0 - e) & 3], acc[tt], 0, 0, 0);
+        }
+        if (i % NCH == NCH - 1) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    out[tt][t][jj] = acc[tt][jj];
+                    amax[tt] = fmaxf(amax[tt], fabsf(acc[tt][jj]));
+                }
+        }
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -239,19 +250,30 @@ __global__ __launch_bounds__(512) void rotate_dense_block_kernel(
         uint32_t code[QUANT ? TT : 1][8];
         int lane_off = lane;                                      // keeps the fragment reads inside this loop
         asm volatile("" : "+v"(lane_off));
+        // the twelve fragments of tile t + 1 are read from LDS while tile t is multiplied (the scheduling
+        // barriers keep the reads ahead of the products; left alone, each read is placed right before its use)
+        uint4 fa[2][12];
+        auto request = [&](uint4 (&f)[12], int t) {
+#pragma unroll
+            for (int q = 0; q < 12; ++q) f[q] = lds_pieces[(q * 8 + t) * 64 + lane_off];
+        };
+        request(fa[0], 0);
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
+            if (t + 1 < 8) request(fa[(t + 1) & 1], t + 1);
+            __builtin_amdgcn_sched_barrier(0);
             v4f acc[TT];
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) acc[tt] = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int q = 11; q >= 0; --q) {                       // smallest piece first
                 union { uint4 u; v8bf v; } a;
-                a.u = lds_pieces[(q * 8 + t) * 64 + lane_off];
+                a.u = fa[t & 1][q];
 #pragma unroll
                 for (int tt = 0; tt < TT; ++tt)
                     acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, xcur[tt][q & 3], acc[tt], 0, 0, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
                 if constexpr (QUANT)
@@ -395,6 +417,7 @@ __global__ __launch_bounds__(768) void rotate_quant_dense_rpr_kernel(
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             if (t + 1 < 8) request2(fa2[(t + 1) & 1], t + 1);
+            __builtin_amdgcn_sched_barrier(0);
             v4f acc = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s4 = 0; s4 < 8; ++s4) {
