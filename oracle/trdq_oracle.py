@@ -251,12 +251,25 @@ def acc_asym_exact_blas(Xq, zx, Wq):
     return (Xd @ np.asarray(Wq).astype(np.float64)).astype(np.int32)
 
 
-def linear_asym(X_bf16, W, d=None, bias=None, B=128, exact_blas=False):
-    """Rotated W8A8 linear with asymmetric per-token activations (weights stay symmetric per channel)."""
+def igemm_asym_groups(Xq, zx, Wq, group, exact_blas=False):
+    """int32 [K/group, M, N]: the sums of igemm_asym per group of `group` input channels (the int4
+    weights carry one scale per group and output channel)."""
+    Xq, zx, Wq = _c(Xq, np.uint8), _c(zx, np.int32), _c(Wq, np.int8)
+    K = Xq.shape[1]
+    f = acc_asym_exact_blas if exact_blas else igemm_asym
+    return np.stack([f(Xq[:, k0:k0 + group], zx, Wq[k0:k0 + group]) for k0 in range(0, K, group)])
+
+
+def linear_asym(X_bf16, W, d=None, bias=None, B=128, exact_blas=False, wbits=8):
+    """Rotated linear with asymmetric per-token activations (Eq. 1-3); weights stay symmetric, per
+    output channel (wbits 8, 6) or per group of B input channels and output channel (wbits 4)."""
     V = rotate(X_bf16, d, B)
     Xq, sx, zx = quant_tokens_asym(V)
-    Wq, sw = prepare_weights(W, d, B, 8)
-    acc = acc_asym_exact_blas(Xq, zx, Wq) if exact_blas else igemm_asym(Xq, zx, Wq)
+    Wq, sw = prepare_weights(W, d, B, wbits)
+    if wbits == 4:
+        acc = igemm_asym_groups(Xq, zx, Wq, B, exact_blas)
+    else:
+        acc = acc_asym_exact_blas(Xq, zx, Wq) if exact_blas else igemm_asym(Xq, zx, Wq)
     Y, Yd = dequant(acc, sx, sw, bias, return_f64=True)
     return dict(Xq=Xq, sx=sx, zx=zx, Wq=Wq, sw=sw, acc=acc, Y=Y, Yd=Yd)
 

@@ -895,3 +895,24 @@ def test_time_rotation_calibration_flattens_outliers(oracle):
     one = np.abs(oracle.rotate_dense(Xb, d, R1)).max()
     two = np.abs(oracle.rotate_dense_rpr(Xb, d, R1, perm, R2)).max()
     assert one < 0.3 * raw and two < 0.3 * raw
+
+
+def test_asym_int4_groups(oracle):
+    # asymmetric activations against int4 weights: per-group sums of (q - z) w; the signed-code / column-sum
+    # identity holds group by group, and the result is the float product of the dequantised operands
+    Xb, W, d, bias = wl.small_case(28, 6, 256, 16, n_outliers=2)
+    ref = oracle.linear_asym(Xb, W, d, bias, wbits=4)
+    Xq, zx, Wq, sw, sx = ref["Xq"], ref["zx"], ref["Wq"], ref["sw"], ref["sx"]
+    assert ref["acc"].shape == (2, 6, 16) and sw.shape == (2, 16) and np.abs(Wq).max() == 7
+    signed = oracle.igemm((Xq.astype(np.int16) - 128).astype(np.int8), Wq, 128)          # [2, 6, 16]
+    colsum = Wq.astype(np.int64).reshape(2, 128, 16).sum(axis=1)                         # [2, 16]
+    want = signed + (128 - zx.astype(np.int64))[None, :, None] * colsum[:, None, :]
+    assert np.array_equal(ref["acc"], want)
+    assert np.array_equal(ref["acc"], oracle.igemm_asym_groups(Xq, zx, Wq, 128, exact_blas=True))
+    Xhat = sx[:, None] * (Xq.astype(np.float64) - zx[:, None])
+    What = np.repeat(sw, 128, axis=0) * Wq
+    assert np.allclose(ref["Yd"], Xhat @ What + bias, rtol=1e-12, atol=1e-12)
+    # brute force of one entry
+    i, n = 3, 5
+    t = sum(sw[k // 128, n] * float((int(Xq[i, k]) - int(zx[i])) * int(Wq[k, n])) for k in range(256))
+    assert abs(ref["Yd"][i, n] - (sx[i] * t + bias[n])) < 1e-9
