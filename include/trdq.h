@@ -152,16 +152,19 @@ trdq_status trdq_rotate_quant_bits(const void *X_dev, int64_t M, int K, int64_t 
 /* ------------------------------------ asymmetric activations (Eq. 1-3)
  * The uniform quantiser of Eq. 1-3 as printed is asymmetric: per token, s = (max - min) / 255 and
  * a zero point z, codes in 0..255, V ~ s (q - z).  The calls above use the symmetric form; this
- * pair keeps the zero point (weights stay symmetric per output channel, int8 only):
+ * pair keeps the zero point (weights stay symmetric: per output channel for wbits 8 / 6, per
+ * 128-channel group and output channel for wbits 4):
  *   lo = min(min_k V, 0), hi = max(max_k V, 0), s_x = (hi - lo) / 255, z = -rint(lo / s_x),
  *   q = clamp(rint(V / s_x) + z, 0, 255);  an all-zero row gives s_x = 0, z = 0.
  * (Eq. 3 as printed lacks the minus sign; with it the zero point is the code of the value 0.)
  * Xq_dev receives q - 128 as int8 (what the matrix instruction takes) and zc_dev[i] = 128 - z_i
  * (int32 [M]); trdq_qgemm_asym adds zc[i] times the column sum of the weight codes to the integer
  * sums, which makes them sum_k (q - z) Wq exactly, then dequantises as trdq_qgemm does.
- * acc_debug_dev (optional, int32 [M, N]) receives those corrected sums.  Other arguments, layouts
- * and errors as trdq_rotate_quant_warm / trdq_qgemm; NULL zc -> ERR_NULL; int4 weights or
- * K > 4608 (the quantising pass) -> ERR_UNSUPPORTED. */
+ * acc_debug_dev (optional, int32 [M, N]) receives those corrected sums.  With int4 weights the
+ * zero-point term is added after the group scales, in float (zc[i] times a per-channel constant
+ * prepared with the weights), and acc_debug_dev ([K/128, M, N]) receives the uncorrected group
+ * sums of the stored codes q - 128.  Other arguments, layouts and errors as trdq_rotate_quant_warm /
+ * trdq_qgemm; NULL zc -> ERR_NULL; K > 4608 (the quantising pass) -> ERR_UNSUPPORTED. */
 trdq_status trdq_rotate_quant_asym(const void *X_dev, int64_t M, int K, int64_t ldx,
                                    const float *diag_dev, int block,
                                    int8_t *Xq_dev, float *sx_dev, int32_t *zc_dev, const trdq_weights *next,

@@ -149,7 +149,8 @@ trdq_status prepare_weights_impl(const float *W_dev, int K, int N, const float *
         hipMalloc(reinterpret_cast<void **>(&Wrot), (size_t)K * N * sizeof(float)) != hipSuccess ||
         hipMalloc(reinterpret_cast<void **>(&amax), (size_t)nb * N * sizeof(float)) != hipSuccess ||
         (perm_dev && hipMalloc(reinterpret_cast<void **>(&Wrot2), (size_t)K * N * sizeof(float)) != hipSuccess) ||
-        (wbits == 8 && hipMalloc(reinterpret_cast<void **>(&w->colsum), (size_t)N * sizeof(int32_t)) != hipSuccess)) {
+        (wbits == 8 && hipMalloc(reinterpret_cast<void **>(&w->colsum), (size_t)N * sizeof(int32_t)) != hipSuccess) ||
+        (wbits == 4 && hipMalloc(reinterpret_cast<void **>(&w->colsumw), (size_t)N * sizeof(float)) != hipSuccess)) {
         rc = TRDQ_ERR_ALLOC;
         goto fail;
     }
@@ -172,6 +173,7 @@ trdq_status prepare_weights_impl(const float *W_dev, int K, int N, const float *
         ok = trdq::launch_prepare_quant(Wrot, amax, K, N, qbits, 0.08838834764831845f, w->codes, w->scales, st) == hipSuccess;
     }
     if (ok && wbits == 8) ok = trdq::launch_weight_colsum(w->codes, K, N, w->colsum, st) == hipSuccess;
+    if (ok && wbits == 4) ok = trdq::launch_weight_colsumw4(w->codes, w->scales, K, N, w->colsumw, st) == hipSuccess;
     if (!ok || hipStreamSynchronize(st) != hipSuccess) {
         rc = TRDQ_ERR_HIP;
         goto fail;
@@ -189,6 +191,7 @@ fail:
     if (w->codes) (void)hipFree(w->codes);
     if (w->scales) (void)hipFree(w->scales);
     if (w->colsum) (void)hipFree(w->colsum);
+    if (w->colsumw) (void)hipFree(w->colsumw);
     delete w;
     return rc;
 }
@@ -535,6 +538,7 @@ void trdq_weights_destroy(trdq_weights *w)
     if (w->codes) (void)hipFree(w->codes);
     if (w->scales) (void)hipFree(w->scales);
     if (w->colsum) (void)hipFree(w->colsum);
+    if (w->colsumw) (void)hipFree(w->colsumw);
     delete w;
 }
 
@@ -660,7 +664,6 @@ trdq_status trdq_qgemm_asym(const trdq_weights *w, const int8_t *Xq_dev, const f
                             int32_t *acc_debug_dev, void *stream)
 {
     if (!w) return TRDQ_ERR_NULL;
-    if (w->wbits != 8) return TRDQ_ERR_UNSUPPORTED;
     trdq_status rc = check_out_args(Y_dev, M, w->N, ldy, bias_dev);
     if (rc != TRDQ_OK) return rc;
     if (M > 0 && (!Xq_dev || !sx_dev || !zc_dev)) return TRDQ_ERR_NULL;

@@ -17,10 +17,12 @@ struct GemmArgs {
     const float *bias;     // [N] or null
     uint16_t *Y;           // [M, ldy]
     int32_t *acc_debug;    // null, [M, N] or [K/128, M, N]
-    // asymmetric activations (int8 weights only): zc[i] = 128 - z_i per token and the column sums of the
-    // weight codes; the integer sum of a product is acc + zc[i] * colsum[n].  Null otherwise.
+    // asymmetric activations: zc[i] = 128 - z_i per token, and with int8 weights the column sums of the
+    // weight codes (the integer sum of a product is acc + zc[i] * colsum[n]), with int4 weights
+    // colsumw[n] = 16 * sum_g s_w[g][n] * colsum_g[n] (the scaled term, added in float).  Null otherwise.
     const int32_t *zc = nullptr;
     const int32_t *colsum = nullptr;
+    const float *colsumw = nullptr;
     int64_t M, ldy;
     int K, N;
     int tiles_m, tiles_n;

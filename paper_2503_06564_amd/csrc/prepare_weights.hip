@@ -221,6 +221,32 @@ hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag
     return hipGetLastError();
 }
 
+// int4 weights: colsumw[n] = 16 * sum_g s_w[g][n] * (sum over the 128 codes of group g), one wave per
+// output channel; a lane sums two packed bytes (four codes) per group.
+__global__ __launch_bounds__(64) void weight_colsumw4_kernel(const uint8_t *__restrict__ codes, const float *__restrict__ scales,
+                                                             int K, int N, float *__restrict__ colsumw)
+{
+    const int n = blockIdx.x, lane = threadIdx.x;
+    const uint8_t *row = codes + (size_t)n * (K / 2);
+    float t = 0.0f;
+    for (int g = 0; g < K / kBlock; ++g) {
+        // 64 bytes per group; lane takes byte `lane`: two codes as signed nibbles
+        const uint32_t b = row[g * 64 + lane];
+        int s = (int)((b & 0xF) ^ 8) - 8 + (int)(((b >> 4) & 0xF) ^ 8) - 8;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+        t += scales[(size_t)g * N + n] * (float)s;
+    }
+    if (lane == 0) colsumw[n] = 16.0f * t;
+}
+
+hipError_t launch_weight_colsumw4(const void *codes, const float *scales, int K, int N, float *colsumw, hipStream_t st)
+{
+    hipLaunchKernelGGL(weight_colsumw4_kernel, dim3(N), dim3(64), 0, st, static_cast<const uint8_t *>(codes), scales, K, N,
+                       colsumw);
+    return hipGetLastError();
+}
+
 hipError_t launch_prepare_rotate_dense(const float *W, int K, int N, const float *diag, const int32_t *perm,
                                        const float *R, float *Wrot, float *amax, hipStream_t st)
 {

@@ -276,6 +276,14 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, con
     a.acc_debug = acc_debug; a.M = M; a.ldy = ldy; a.K = w.K; a.N = w.N;
     a.tiles_m = a.tiles_n = 0;
     const bool dbg = acc_debug != nullptr;
+    if (zc && w.wbits == 4) {
+        // asymmetric activations against int4 weights: the scaled zero-point term is one multiply-add per
+        // output in the epilogue of the int4 kernel
+        if (!w.colsumw) return hipErrorInvalidValue;
+        a.zc = zc;
+        a.colsumw = w.colsumw;
+        return launch_qgemm4_dma(a, dbg, 0, st);
+    }
     if (zc) {
         // asymmetric activations: int8 weights with their column sums; the 128 x 144 kernels where
         // the symmetric path would take them or the 256 x 256 kernel, else the ring kernel

@@ -844,7 +844,11 @@ __global__ __launch_bounds__(kThreads) void qgemm8_persist_kernel(GemmArgs g)
 // per lane; waves 2 and 3 write a second, unused copy so that every wave issues the same number
 // of requests and the hand-kept vmcnt arithmetic stays uniform).  Past the last k-tile the last
 // one is copied again, for the same reason.
-template <int BM, int BN, int NS, int WGM, int WGN, bool DEBUG>
+// ASYM: asymmetric activations (codes q - 128, zc = 128 - z per token).  The zero-point term of group g
+// is zc * colsum_g[n]; scaled and summed over the groups it is zc * cw[n] with the per-channel float
+// cw[n] = 16 * sum_g s_w[g][n] * colsum_g[n] prepared with the weights, so it costs one multiply-add
+// per output in the epilogue.
+template <int BM, int BN, int NS, int WGM, int WGN, bool DEBUG, bool ASYM = false>
 __global__ __launch_bounds__(kThreads) void qgemm4_ring_kernel(GemmArgs g)
 {
     static_assert(WGM * WGN == 4, "four waves per workgroup");
@@ -983,11 +987,12 @@ __global__ __launch_bounds__(kThreads) void qgemm4_ring_kernel(GemmArgs g)
 
     // epilogue: y = (s_x / 16) * facc + bias -> bf16
     const int64_t m_lane = m0 + wm * WM + l16;
-    float sxm[TM];
+    float sxm[TM], zcf[TM];
 #pragma unroll
     for (int b = 0; b < TM; ++b) {
         const int64_t m = m_lane + b * 16;
         sxm[b] = m < g.M ? g.sx[m] * 0.0625f : 0.0f;
+        zcf[b] = (ASYM && m < g.M) ? (float)g.zc[m] : 0.0f;
     }
     const bool full = m0 + BM <= g.M && n0 + BN <= g.N;      // workgroup-uniform
     constexpr int ROWB = WN * 2 + 16;
@@ -998,14 +1003,17 @@ __global__ __launch_bounds__(kThreads) void qgemm4_ring_kernel(GemmArgs g)
     for (int a = 0; a < TN; ++a) {
         const int n = n_lane + a * 16;
         const bool n_ok = n < g.N;
-        float4 bi = make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 bi = make_float4(0.f, 0.f, 0.f, 0.f), cw = bi;
         if (g.bias && n_ok) bi = *reinterpret_cast<const float4 *>(g.bias + n);
+        if (ASYM && n_ok) cw = *reinterpret_cast<const float4 *>(g.colsumw + n);
 #pragma unroll
         for (int b = 0; b < TM; ++b) {
             const int64_t m = m_lane + b * 16;
+            v4f t = facc[a][b];
+            if constexpr (ASYM) t += v4f{zcf[b] * cw.x, zcf[b] * cw.y, zcf[b] * cw.z, zcf[b] * cw.w};
             uint2 o;
-            o.x = pack_bf16x2(sxm[b] * facc[a][b][0] + bi.x, sxm[b] * facc[a][b][1] + bi.y);
-            o.y = pack_bf16x2(sxm[b] * facc[a][b][2] + bi.z, sxm[b] * facc[a][b][3] + bi.w);
+            o.x = pack_bf16x2(sxm[b] * t[0] + bi.x, sxm[b] * t[1] + bi.y);
+            o.y = pack_bf16x2(sxm[b] * t[2] + bi.z, sxm[b] * t[3] + bi.w);
             if (full) *reinterpret_cast<uint2 *>(stg + (b * 16 + l16) * ROWB + (a * 16 + lg * 4) * 2) = o;
             else if (n_ok && m < g.M) *reinterpret_cast<uint2 *>(g.Y + m * g.ldy + n) = o;
         }
@@ -1046,6 +1054,12 @@ hipError_t launch_ring4(const GemmArgs &a, bool debug, hipStream_t st)
 {
     static bool done[2] = {false, false};
     const size_t smem = (size_t)NS * (BM * 128 + BN * 64 + 1024);
+    if (a.zc) {
+        static bool done_z[2] = {false, false};
+        if (!a.colsumw) return hipErrorInvalidValue;
+        if (debug) return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, true, true>, done_z[1], a, BM, BN, smem, st);
+        return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, false, true>, done_z[0], a, BM, BN, smem, st);
+    }
     if (debug) return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, true>, done[1], a, BM, BN, smem, st);
     return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st);
 }

@@ -23,6 +23,7 @@ struct Weights {
     void *codes = nullptr;
     float *scales = nullptr;
     int32_t *colsum = nullptr;   // int8 weights: sum over k of the codes of every output channel [N]
+    float *colsumw = nullptr;    // int4 weights: 16 * sum_g s_w[g][n] * (sum of the codes of group g) [N]
     int device = 0;
 };
 
@@ -63,6 +64,7 @@ hipError_t launch_rotate_quant_rpr(const uint16_t *X, int64_t M, int K, int64_t 
 // norm: what undoes the unnormalised butterflies (1/sqrt(128) per rotation applied).
 hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag, const int32_t *perm,
                                  float *Wrot, float *amax, hipStream_t st);
+hipError_t launch_weight_colsumw4(const void *codes, const float *scales, int K, int N, float *colsumw, hipStream_t st);
 hipError_t launch_prepare_quant(const float *Wrot, const float *amax, int K, int N, int wbits, float norm,
                                 void *codes, float *scales, hipStream_t st);   // wbits 8, 6 (8-bit layout) or 4
 

@@ -100,13 +100,29 @@ def test_linear_asym_end_to_end(oracle, M, K, N):
     w.close()
 
 
-def test_qgemm_asym_rejects_int4_weights():
-    W = torch.randn((256, 32), device=dev()) * 0.02
-    w = trdq.prepare_weights(W, None, wbits=4)
-    Xq = torch.zeros((4, 256), dtype=torch.int8, device=dev())
-    sx = torch.ones((4,), device=dev())
-    zc = torch.zeros((4,), dtype=torch.int32, device=dev())
-    Y = torch.zeros((4, 32), dtype=torch.bfloat16, device=dev())
-    with pytest.raises(trdq.TrdqError) as e:
-        trdq.qgemm_asym(w, Xq, sx, zc, Y)
-    assert e.value.status == trdq.ERR_UNSUPPORTED
+@pytest.mark.parametrize("M,K,N", [(1, 128, 16), (17, 256, 144), (300, 4608, 272), (513, 384, 400), (1024, 1152, 1152)])
+def test_linear_asym_int4_weights(oracle, M, K, N):
+    say(f"linear asymmetric W4 M={M} K={K} N={N}")
+    Xb, W, d, bias = wl.small_case(43, M, K, N, n_outliers=max(1, K // 144), outlier=40.0)
+    w = trdq.prepare_weights(f32_to_dev(W), f32_to_dev(d), wbits=4)
+    Xq, sx, zc = _gpu_rq_asym(Xb, d, warm=w)
+    shifted = _compare_codes(oracle, Xb, d, Xq, sx, zc)
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device=dev())
+    trdq.qgemm_asym(w, Xq, sx, zc, Y, bias=f32_to_dev(bias))
+    torch.cuda.synchronize()
+    codes, scales = w.export()
+    q = (Xq.cpu().numpy().astype(np.int16) + 128).astype(np.uint8)
+    z = (128 - zc.cpu().numpy()).astype(np.int32)
+    # the oracle's epilogue on the GPU's own codes and zero points
+    acc = oracle.igemm_asym_groups(q, z, codes, 128, exact_blas=True)
+    y_same = oracle.dequant(acc, sx.cpu().numpy(), scales, bias)
+    want = oracle.bf16_to_f64(y_same)
+    got = oracle.bf16_to_f64(bf16_to_host(Y))
+    row = np.abs(want).max(axis=1, keepdims=True)
+    # fp32 group sums and a float zero-point term that cancels part of them: one bf16 step plus 1e-4 of the row's magnitude
+    assert np.all(np.abs(got - want) <= np.abs(want) * 2.0 ** -7 + row * 1e-4)
+    ref = oracle.linear_asym(Xb, W, d, bias, exact_blas=True, wbits=4)
+    rows = np.any(q != ref["Xq"], axis=1) | shifted
+    cols = np.any(codes != ref["Wq"], axis=0)
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (asymmetric, int4 weights)", skip_rows=rows, skip_cols=cols)
+    w.close()
