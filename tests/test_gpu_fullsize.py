@@ -297,3 +297,37 @@ def test_dense_blocks_full_size_sampled_rows(oracle, cfg_id, kind):
     cols_diff = (codes != ref["Wq"]).any(axis=0)
     gu.assert_y_close(gu.bf16_to_host(Y[idx]), ref["Y"], f"{kind} Y (dense blocks)", rows_diff, cols_diff)
     w.close(); rot.close()
+
+
+def test_two_million_tokens_64_bit_offsets(oracle):
+    """2 000 037 tokens x 1152 channels: byte offsets beyond 2^32 in X, element offsets beyond 2^31 in Xq;
+    sampled rows (first and last tiles, random ones) against the oracle, properties over all tokens."""
+    M, K, N = 2_000_037, 1152, 144
+    say(f"large M: {M} x {K} -> {N}")
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    X = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")
+    for r0 in range(0, M, 262144):                       # in pieces: no float32 copy of the whole matrix
+        r1 = min(M, r0 + 262144)
+        X[r0:r1] = torch.randn((r1 - r0, K), generator=gen, device="cuda").to(torch.bfloat16)
+    X[:, 100] *= 40.0                                    # an outlier channel
+    _, W, d, bias = wl.small_case(91, 1, K, N)
+    dd = gu.f32_to_dev(d)
+    w = trdq.prepare_weights(gu.f32_to_dev(W), dd, wbits=8)
+    Xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+    sx = torch.empty((M,), dtype=torch.float32, device="cuda")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    trdq.rotate_quant(X, dd, Xq, sx, warm=w)
+    trdq.qgemm(w, Xq, sx, Y, bias=gu.f32_to_dev(bias))
+    torch.cuda.synchronize()
+    assert bool((Xq.abs().amax(dim=1) == 127).all()) and bool((sx > 0).all())
+    rows = sample_rows(M, 123, n_random=96, edge=40)
+    idx = torch.from_numpy(rows).cuda()
+    Xb = X[idx].view(torch.int16).cpu().numpy().view(np.uint16)
+    ref = oracle.linear(Xb, W, d, bias, wbits=8, exact_blas=True)
+    gu.assert_codes_close(Xq[idx].cpu().numpy(), ref["Xq"], "Xq (2M tokens)")
+    gu.assert_scales_close(sx[idx].cpu().numpy(), ref["sx"], "s_x (2M tokens)")
+    codes, _ = w.export()
+    rows_diff = (Xq[idx].cpu().numpy() != ref["Xq"]).any(axis=1)
+    cols_diff = (codes != ref["Wq"]).any(axis=0)
+    gu.assert_y_close(gu.bf16_to_host(Y[idx]), ref["Y"], "Y (2M tokens)", rows_diff, cols_diff)
+    w.close()
