@@ -426,3 +426,41 @@ def test_rotate_quant_warm_read_changes_nothing(oracle, wbits):
     after = w.export()
     assert np.array_equal(before[0], after[0]) and np.array_equal(before[1], after[1])
     w.close()
+
+
+def test_shared_handles_on_two_streams(oracle):
+    """The same prepared weights, rotation tables and layer used from two streams at once (handles are
+    read-only after creation): every stream's outputs are the bits of the same calls issued one at a time."""
+    say("two streams sharing the handles")
+    M, K, N = 1024, 1152, 1152
+    trdq.qgemm_set_variant(-1)
+    cases = [wl.small_case(40 + i, M, K, N, n_outliers=8) for i in range(2)]
+    _, W, d, bias = cases[0]
+    dd, bd = gu.f32_to_dev(d), gu.f32_to_dev(bias)
+    w = trdq.prepare_weights(gu.f32_to_dev(W), dd, wbits=8)
+    Xs = [gu.bf16_to_dev(c[0]) for c in cases]
+    ref_out = []
+    for X in Xs:                                          # one at a time on the current stream
+        Xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+        sx = torch.empty((M,), dtype=torch.float32, device="cuda")
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        trdq.rotate_quant(X, dd, Xq, sx, warm=w)
+        trdq.qgemm(w, Xq, sx, Y, bias=bd)
+        torch.cuda.synchronize()
+        ref_out.append(Y)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    bufs = [(torch.empty((M, K), dtype=torch.int8, device="cuda"), torch.empty((M,), dtype=torch.float32, device="cuda"),
+             torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")) for _ in range(2)]
+    torch.cuda.synchronize()
+    for rep in range(8):                                  # interleaved launches, no synchronisation in between
+        for i in range(2):
+            Xq, sx, Y = bufs[i]
+            trdq.rotate_quant(Xs[i], dd, Xq, sx, stream=streams[i], warm=w)
+            trdq.qgemm(w, Xq, sx, Y, bias=bd, stream=streams[i])
+    torch.cuda.synchronize()
+    for i in range(2):
+        assert torch.equal(bufs[i][2], ref_out[i]), f"stream {i}"
+    ref = oracle.linear(cases[1][0], W, d, bias, wbits=8, exact_blas=True)
+    gu.assert_y_close(gu.bf16_to_host(bufs[1][2]), ref["Y"], "Y (second stream)",
+                      (bufs[1][0].cpu().numpy() != ref["Xq"]).any(axis=1), (w.export()[0] != ref["Wq"]).any(axis=0))
+    w.close()
