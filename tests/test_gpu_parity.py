@@ -464,3 +464,57 @@ def test_shared_handles_on_two_streams(oracle):
     gu.assert_y_close(gu.bf16_to_host(bufs[1][2]), ref["Y"], "Y (second stream)",
                       (bufs[1][0].cpu().numpy() != ref["Xq"]).any(axis=1), (w.export()[0] != ref["Wq"]).any(axis=0))
     w.close()
+
+
+def test_graph_replay_of_the_multi_kernel_calls():
+    """The calls that launch several kernels and clear accumulators themselves (with fill kernels, not
+    memsets) replay from a HIP graph: asymmetric pair, the two-pass dense-block pass, Eq. 11."""
+    say("graph replay: asymmetric pair, wide dense pass, cosine similarity")
+    M, K, N = 256, 1664, 144                   # 13 blocks: the block-resident, two-pass dense form
+    inputs = [wl.small_case(50 + i, M, K, N, n_outliers=8) for i in range(3)]
+    _, W, d, bias = inputs[0]
+    dd, bb = gu.f32_to_dev(d), gu.f32_to_dev(bias)
+    w = trdq.prepare_weights(gu.f32_to_dev(W), dd, wbits=8)
+    Rs = wl.orthogonal_uniform_first_row(3, K // 128).astype(np.float32)
+    rot = trdq.Rotation(gu.f32_to_dev(Rs.reshape(-1, 128)).view(-1, 128, 128), dd)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        X = gu.bf16_to_dev(inputs[0][0]).clone()
+        Xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+        sx = torch.empty((M,), dtype=torch.float32, device="cuda")
+        zc = torch.empty((M,), dtype=torch.int32, device="cuda")
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        Xq2 = torch.empty((M, K), dtype=torch.int8, device="cuda")
+        sx2 = torch.empty((M,), dtype=torch.float32, device="cuda")
+        ws = torch.zeros((3 * 4,), dtype=torch.float64, device="cuda")
+        cs = torch.empty((4,), dtype=torch.float32, device="cuda")
+        A4, B4 = X[:4], X[4:8]
+
+        def calls():
+            trdq.rotate_quant_asym(X, dd, Xq, sx, zc, stream=s)
+            trdq.qgemm_asym(w, Xq, sx, zc, Y, bias=bb, stream=s)
+            trdq.rotate_quant_dense(X, rot, Xq2, sx2, stream=s)
+            trdq.cosine_similarity(A4, B4, ws, cs, stream=s)
+        outs = (Xq, sx, zc, Y, Xq2, sx2, cs)
+        calls()                               # warm-up outside the capture (one-time kernel attributes)
+        s.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            calls()
+        for Xb, _, _, _ in inputs:
+            X.copy_(gu.bf16_to_dev(Xb))
+            for t in outs:
+                t.zero_()                     # host-launched work between the replays
+            g.replay()
+            s.synchronize()
+            got = [t.clone() for t in outs]
+            for t in outs:
+                t.zero_()
+            calls()
+            s.synchronize()
+            for a, b in zip(got, outs):
+                if a.dtype == torch.float32 and a.numel() == 4:
+                    assert torch.allclose(a, b, rtol=0, atol=1e-6)      # fp64 atomics: order may differ in the last bits
+                else:
+                    assert torch.equal(a, b)
+    w.close(); rot.close()
