@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--asym", action="store_true",
                     help="asymmetric per-token activation codes (zero point, Eq. 1-3) instead of symmetric ones; W8 only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-measured-peaks", action="store_true",
+                    help="skip the yardstick kernels that give roofline.measured_peak")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU work budget of the oracle's timed sample")
     ap.add_argument("--variant", type=int, default=-1, help="qgemm tile variant override")
     ap.add_argument("--groups", type=int, default=0, help="limit the number of groups prepared (0 = all)")
@@ -354,6 +356,21 @@ def main():
 
     if "roofline" in out:
         out["roofline"]["traffic"] = committed_traffic(cfg.name)
+        if not args.no_measured_peaks:
+            # after the timed region: the chip's own ceilings for the two bounding operations
+            # (register-only int8 matrix issue; a pass of 2 bytes read + 1 written per element)
+            from paper_2503_06564_amd.microbench import measure_peaks
+            shapes = sorted({(M, wl.LAYER_SHAPES[kind][0]) for kind in cfg.kinds})
+            pk = measure_peaks(dev, quick=True, stream_sizes=shapes)
+            out["roofline"]["measured_peak"] = pk["mfma_i8_tops"]
+            out["roofline"]["frac_of_measured"] = out["roofline"]["achieved"] / pk["mfma_i8_tops"]
+            if "roofline_rotate_quant" in out:
+                # the same mix of shapes as the step's rotate_quant launches, streamed without arithmetic
+                rq = out["roofline_rotate_quant"]
+                t_y = sum(pk["stream_us"][f"{M}x{wl.LAYER_SHAPES[kind][0]}"] for kind in cfg.kinds) * 1e-6
+                b_y = sum(3.0 * M * wl.LAYER_SHAPES[kind][0] for kind in cfg.kinds)
+                rq["measured_peak"] = b_y / t_y / 1e9
+                rq["frac_of_measured"] = rq["achieved"] / rq["measured_peak"]
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, wl, args.cpu_seconds)

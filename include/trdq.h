@@ -376,6 +376,27 @@ void trdq_layer_destroy(trdq_layer *l);
 trdq_status trdq_qgemm_set_variant(int variant);
 int trdq_qgemm_num_variants(void);
 
+/* -------------------------------------------------------------- yardsticks
+ * Two kernels that do nothing but the bounding operation of the path, for callers that report a
+ * kernel's rate against what the chip delivers as well as against its published peaks.
+ * Neither is part of the layer.
+ *
+ * trdq_peak_mfma_i8: `workgroups` workgroups of `waves` (1..8) waves; each wave issues
+ * iters x 8 independent int8 16x16x64 matrix instructions from registers (operands of ones).
+ * sink_dev int32 [workgroups * waves * 64] receives, per lane, the sum of its 32 accumulator
+ * elements = 32 * 64 * iters (checkable; iters <= 2^20 keeps it inside int32).
+ * *ops_host (may be NULL) <- operations of the launch, 2 * 16*16*64 per instruction.
+ * Errors: workgroups outside 1..65536, waves outside 1..8, iters outside 1..2^20 -> ERR_RANGE.
+ *
+ * trdq_peak_stream: reads n_elems 16-bit elements and writes the low byte of each (2 bytes in,
+ * 1 byte out per element -- the traffic mix of trdq_rotate_quant -- with no arithmetic), 16 bytes
+ * per load.  src_dev 16-byte aligned, dst_dev int8 [n_elems] 8-byte aligned, n_elems % 8 == 0
+ * (else ERR_SHAPE); the two buffers must not overlap.  n_elems == 0 is a no-op.
+ * Both are asynchronous on `stream` and allocate nothing. */
+trdq_status trdq_peak_mfma_i8(int32_t *sink_dev, int workgroups, int waves, int iters, int64_t *ops_host,
+                              void *stream);
+trdq_status trdq_peak_stream(const void *src_dev, void *dst_dev, int64_t n_elems, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

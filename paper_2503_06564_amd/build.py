@@ -10,7 +10,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtrdq.so")
 
-SOURCES = ["api.cpp", "rotate_quant.hip", "rotate_quant_wide.hip", "rotate_quant_rpr.hip", "calibrate.hip", "greedy_rotation.hip", "rotate_quant_dense.hip", "attention_share.hip", "prepare_weights.hip", "qgemm.hip", "qgemm_dma.hip", "qgemm_wide.hip", "fused.hip"]
+SOURCES = ["api.cpp", "rotate_quant.hip", "rotate_quant_wide.hip", "rotate_quant_rpr.hip", "calibrate.hip", "greedy_rotation.hip", "rotate_quant_dense.hip", "attention_share.hip", "prepare_weights.hip", "qgemm.hip", "qgemm_dma.hip", "qgemm_wide.hip", "fused.hip", "peaks.hip"]
 
 # packed-FP32 instructions are switched off for every device compile
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",

@@ -430,6 +430,27 @@ trdq_status trdq_cosine_similarity(const void *A_dev, const void *B_dev, int n_s
                                                      stride_b, acc_ws_dev, cos_dev, static_cast<hipStream_t>(stream)));
 }
 
+trdq_status trdq_peak_mfma_i8(int32_t *sink_dev, int workgroups, int waves, int iters, int64_t *ops_host,
+                              void *stream)
+{
+    if (!sink_dev) return TRDQ_ERR_NULL;
+    if (workgroups <= 0 || workgroups > 65536 || waves <= 0 || waves > 8 || iters <= 0 || iters > (1 << 20))
+        return TRDQ_ERR_RANGE;
+    if (!aligned(sink_dev, 4)) return TRDQ_ERR_SHAPE;
+    // one 16x16x64 instruction: 16*16*64 multiply-adds
+    if (ops_host) *ops_host = (int64_t)workgroups * waves * iters * trdq::peak_mfma_independent() * 2 * 16 * 16 * 64;
+    return hip_status(trdq::launch_peak_mfma_i8(sink_dev, workgroups, waves, iters, static_cast<hipStream_t>(stream)));
+}
+
+trdq_status trdq_peak_stream(const void *src_dev, void *dst_dev, int64_t n_elems, void *stream)
+{
+    if (n_elems < 0 || n_elems % 8 != 0) return TRDQ_ERR_SHAPE;
+    if (n_elems == 0) return TRDQ_OK;
+    if (!src_dev || !dst_dev) return TRDQ_ERR_NULL;
+    if (!aligned(src_dev, 16) || !aligned(dst_dev, 8)) return TRDQ_ERR_SHAPE;
+    return hip_status(trdq::launch_peak_stream(src_dev, dst_dev, n_elems, static_cast<hipStream_t>(stream)));
+}
+
 trdq_status trdq_share_plan(const float *sim_host, int n_steps, int n_blocks, float threshold, int32_t *share_host)
 {
     if (!sim_host || !share_host) return TRDQ_ERR_NULL;

@@ -84,6 +84,10 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, con
 
 hipError_t launch_cosine_similarity(const uint16_t *A, const uint16_t *B, int n_seg, int64_t seg_len,
                                     int64_t stride_a, int64_t stride_b, double *acc_ws, float *out, hipStream_t st);
+// yardstick kernels (peaks.hip)
+int peak_mfma_independent();
+hipError_t launch_peak_mfma_i8(int32_t *sink, int workgroups, int waves, int iters, hipStream_t st);
+hipError_t launch_peak_stream(const void *src, void *dst, int64_t n_elems, hipStream_t st);
 size_t greedy_workspace_bytes(int64_t Mc, int K);
 hipError_t launch_greedy_rotation(const uint16_t *X, int64_t Mc, int K, int64_t ldx, const float *diag,
                                   const float *R1, const int32_t *perm,   // null, or: start from ((X d) R1)[:, perm]

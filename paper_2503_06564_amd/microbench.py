@@ -4,6 +4,7 @@
     python -m paper_2503_06564_amd.microbench dense      # dense-block rotate+quantise passes against the Hadamard ones
     python -m paper_2503_06564_amd.microbench greedy     # greedy construction of the rotation blocks (Eq. 6-7)
     python -m paper_2503_06564_amd.microbench cosine     # Eq. 11 on attention-sized tensors
+    python -m paper_2503_06564_amd.microbench peaks      # the chip's own ceilings: int8 matrix issue, streaming 2 B in / 1 B out
     python -m paper_2503_06564_amd.microbench all
 
 Back-to-back launches between two events on the launch stream, cycling through a few input sets;
@@ -111,15 +112,57 @@ def cosine(dev):
         _out(what="cosine_similarity (Eq. 11)", segments=n, elements=L, us=round(t, 1), tb_per_s=round(4 * n * L / t / 1e6, 2))
 
 
+def measure_peaks(dev, quick=False, emit=None, stream_sizes=None):
+    """What the chip delivers on the two bounding operations alone: int8 matrix instructions issued
+    from registers by every SIMD (TOP/s), and a pass that reads two bytes and writes one per element
+    (GB/s) at the rotate-and-quantise sizes.  `quick`: one launch shape for the matrix yardstick; `stream_sizes`: (tokens, K) pairs.
+    `emit`, if given, receives one record per measurement."""
+    emit = emit or (lambda **kw: None)
+    res = {}
+    best = 0.0
+    shapes = ((1024, 4),) if quick else ((256, 4), (256, 8), (512, 4), (1024, 4))
+    iters = 20000
+    for wgs, waves in shapes:
+        sink = torch.zeros(wgs * waves * 64, dtype=torch.int32, device=dev)
+        ops = [0]
+
+        def run(i):
+            ops[0] = trdq.peak_mfma_i8(sink, wgs, waves, iters)
+        t = _timeit(run, 5, 2)
+        tops = ops[0] / t / 1e6
+        if int(sink.min()) != 32 * 64 * iters or int(sink.max()) != 32 * 64 * iters:
+            raise RuntimeError("matrix-issue yardstick: wrong accumulator sum")
+        emit(what="peak int8 matrix issue (registers only)", workgroups=wgs, waves=waves, us=round(t, 1),
+             tops=round(tops, 1))
+        best = max(best, tops)
+    res["mfma_i8_tops"] = best
+    res["stream_gbs"] = {}
+    sizes = stream_sizes or ((4096, 1152), (4096, 4608), (32768, 1152), (32768, 4608))
+    for M, K in sizes:
+        R = 2 if M * K > (1 << 26) else 4
+        src = [torch.randint(0, 1 << 15, (M, K), dtype=torch.int16, device=dev) for _ in range(R)]
+        dst = [torch.empty((M, K), dtype=torch.int8, device=dev) for _ in range(R)]
+        t = _timeit(lambda i: trdq.peak_stream(src[i % R], dst[i % R]), 20 if M * K > (1 << 26) else 100, 5)
+        gbs = 3.0 * M * K / t / 1e3
+        emit(what="peak stream (2 B read + 1 B written per element)", tokens=M, K=K, us=round(t, 2), gb_per_s=round(gbs, 0))
+        res["stream_gbs"][f"{M}x{K}"] = gbs
+        res.setdefault("stream_us", {})[f"{M}x{K}"] = t
+    return res
+
+
+def peaks(dev):
+    measure_peaks(dev, emit=_out)
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["fused", "dense", "greedy", "cosine", "all"])
+    ap.add_argument("what", choices=["fused", "dense", "greedy", "cosine", "peaks", "all"])
     a = ap.parse_args()
     if not torch.cuda.is_available():
         raise SystemExit("microbench needs the GPU")
     trdq.lib()
     dev = torch.device("cuda:0")
-    for name, fn in (("fused", fused), ("dense", dense), ("greedy", greedy), ("cosine", cosine)):
+    for name, fn in (("fused", fused), ("dense", dense), ("greedy", greedy), ("cosine", cosine), ("peaks", peaks)):
         if a.what in (name, "all"):
             fn(dev)
 

@@ -28,6 +28,7 @@ SYMBOLS = [
     "trdq_rotation_create", "trdq_rotation_destroy", "trdq_prepare_weights_dense", "trdq_rotate_quant_dense",
     "trdq_greedy_rotation", "trdq_prepare_weights_dense_rpr", "trdq_rotate_quant_dense_rpr",
     "trdq_channel_absmax_dense", "trdq_greedy_rotation_second",
+    "trdq_peak_mfma_i8", "trdq_peak_stream",
 ]
 
 _lib = None
@@ -80,6 +81,8 @@ def lib():
         L.trdq_rotate_quant_bits.argtypes = [p, i64, i32, i64, p, i32, i32, p, p, p, p]
         L.trdq_cosine_similarity.argtypes = [p, p, i32, i64, i64, i64, p, p, p]
         L.trdq_share_plan.argtypes = [p, i32, i32, C.c_float, p]
+        L.trdq_peak_mfma_i8.argtypes = [p, i32, i32, i32, C.POINTER(C.c_int64), p]
+        L.trdq_peak_stream.argtypes = [p, p, i64, p]
         L.trdq_rotation_create.argtypes = [p, p, i32, i32, p, C.POINTER(p)]
         L.trdq_rotation_destroy.argtypes = [p]
         L.trdq_rotation_destroy.restype = None
@@ -380,6 +383,19 @@ def cosine_similarity(A, B, acc_ws, out, stream=None):
     sb = B.stride(0) if n_seg > 1 else max(L, B.stride(0))
     _check(lib().trdq_cosine_similarity(_ptr(A), _ptr(B), n_seg, L, sa, sb, _ptr(acc_ws), _ptr(out), _stream(stream)),
            "trdq_cosine_similarity")
+
+
+def peak_mfma_i8(sink, workgroups, waves, iters, stream=None):
+    """Yardstick: iters x 8 register-only int8 matrix instructions per wave; returns the launch's operation count."""
+    ops = C.c_int64(0)
+    _check(lib().trdq_peak_mfma_i8(_ptr(sink), workgroups, waves, iters, C.byref(ops), _stream(stream)),
+           "trdq_peak_mfma_i8")
+    return ops.value
+
+
+def peak_stream(src, dst, stream=None):
+    """Yardstick: dst (int8) <- low byte of every 16-bit element of src; 2 bytes read, 1 written per element."""
+    _check(lib().trdq_peak_stream(_ptr(src), _ptr(dst), src.numel(), _stream(stream)), "trdq_peak_stream")
 
 
 def share_plan(sim, threshold):
