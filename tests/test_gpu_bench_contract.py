@@ -30,5 +30,9 @@ def test_bench_json_line():
     assert rf["bound"] == "mfma" and rf["unit"] == "TOP/s" and rf["peak"] == 5000.0
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-9 and 0 < rf["frac"] < 1
     assert rf["traffic"] is None or rf["traffic"] > 1e6
+    # the chip's own ceiling from the yardstick kernel: below the published peak, above what the path reaches
+    assert rf["achieved"] < rf["measured_peak"] <= 5000.0 * 1.02
+    rq = d["roofline_rotate_quant"]
+    assert rq["bound"] == "hbm" and rq["achieved"] < rq["measured_peak"] <= 8000.0
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["unit"] == "TOP/s" and cb["cores"] >= 1 and cb["value"] > 0 and cb["sample"]
