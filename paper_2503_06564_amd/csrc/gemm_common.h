@@ -42,17 +42,24 @@ __device__ __forceinline__ int xcd_remap(int bid, int ntiles)
 // ~64 tiles a die has in flight form an 8 x 8 block: 8 activation panels + 8 weight panels fit
 // its 4 MB L2, instead of every round streaming the whole weight matrix through it.
 // (Needs tiles_m % 8 == 0; otherwise the plain run-per-die order is used.)
+// Every die pulls what it touches through its own L2: with 8 bands that is the activations once
+// and the weights 8 times.  When the weights are the larger part of that (few token panels, many
+// channel tiles) the dies form a 4 x 2 grid instead -- 4 bands, each split between two dies by
+// channel halves -- which fetches the activations twice and the weights 4 times.
 __device__ __forceinline__ void tile_map(int id, int tiles_m, int tiles_n, int &tm, int &tn)
 {
     if ((tiles_m & 7) == 0) {
-        const int per = tiles_m >> 3;                // token panels per die
         const int xcd = id & 7, i = id >> 3;         // i-th work item of this die
+        const bool halves = (tiles_n & 1) == 0 && 8 * tiles_n > 3 * tiles_m;
+        const int per = halves ? tiles_m >> 2 : tiles_m >> 3;     // token panels per die
+        const int cols = halves ? tiles_n >> 1 : tiles_n;          // channel tiles per die
         const int gm = per < 8 ? per : 8;
-        const int group = i / (gm * tiles_n);
-        const int j = i - group * gm * tiles_n;
+        const int group = i / (gm * cols);
+        const int j = i - group * gm * cols;
         const int rows = (per - group * gm) < gm ? (per - group * gm) : gm;   // last group may be short
-        tn = j / rows;
-        tm = xcd * per + group * gm + (j - tn * rows);
+        const int c = j / rows;
+        tn = (halves ? (xcd >> 2) * cols : 0) + c;
+        tm = (halves ? (xcd & 3) : xcd) * per + group * gm + (j - c * rows);
     } else {
         const int t = xcd_remap(id, tiles_m * tiles_n);
         tm = t / tiles_n;
