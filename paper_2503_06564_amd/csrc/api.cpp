@@ -3,13 +3,35 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "trdq_internal.h"
 
 using trdq::Table;
 using trdq::Weights;
+
+namespace trdq {
+
+hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes)
+{
+    static std::mutex mu;
+    static std::map<std::pair<const void *, int>, size_t> set_bytes;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    size_t &cur = set_bytes[std::make_pair(kernel, dev)];
+    if (bytes <= cur) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) cur = bytes;
+    return e;
+}
+
+}  // namespace trdq
 
 struct trdq_table : Table {};
 struct trdq_weights : Weights {};

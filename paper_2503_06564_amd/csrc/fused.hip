@@ -388,13 +388,7 @@ hipError_t launch_small(const FusedArgs &a, hipStream_t st)
     g.tiles_n = (g.N + TN * 16 - 1) / (TN * 16);
     const size_t smem = (size_t)16 * (g.K + kPad) + 64 + (size_t)8 * TN * 1024;
     auto kern = linear_fused_small_kernel<TN, T>;
-    static size_t attr_smem = 0;
-    if (smem > attr_smem) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_smem = smem;
-    }
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
     // consecutive workgroups take the channel tiles of one panel: with eight tiles (1152 = 8 x 144)
     // each of the eight dies keeps seeing the same weight slab
     hipLaunchKernelGGL(kern, dim3((unsigned)(panels * g.tiles_n)), dim3(kSmallThreads), smem, st, g);
@@ -442,13 +436,7 @@ hipError_t launch_one(const FusedArgs &a, hipStream_t st)
     g.nsplit = (g.tiles_n + tiles_per - 1) / tiles_per;   // no workgroup without a channel tile
     const size_t smem = (size_t)BM * (g.K + kPad) + 2 * (size_t)kBN * (kBK + kPad) + BM * sizeof(float);
     auto kern = linear_fused_kernel<BM, T, S, W4>;
-    static size_t attr_smem = 0;
-    if (smem > attr_smem) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_smem = smem;
-    }
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)panels, (unsigned)g.nsplit), dim3(kThreads), smem, st, g);
     return hipGetLastError();
 }

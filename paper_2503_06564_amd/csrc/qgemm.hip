@@ -235,15 +235,10 @@ hipError_t launch_cfg(const GemmArgs &a, bool debug, hipStream_t st)
     g.tiles_n = (g.N + BN - 1) / BN;
     const size_t smem = 2 * (size_t)(BM + BN) * (BK + kPad);
     const dim3 grid((unsigned)(g.tiles_m * g.tiles_n));
-    static bool attr_done[2] = {false, false};
     auto kern = debug ? qgemm_kernel<BM, BN, BK, WGM, WGN, W4, true>
                       : qgemm_kernel<BM, BN, BK, WGM, WGN, W4, false>;
-    if (smem > 64 * 1024 && !attr_done[debug]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_done[debug] = true;
-    }
+    if (smem > 64 * 1024)
+        if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, st, g);
     return hipGetLastError();
 }

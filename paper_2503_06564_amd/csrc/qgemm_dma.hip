@@ -1033,18 +1033,13 @@ __global__ __launch_bounds__(kThreads) void qgemm4_ring_kernel(GemmArgs g)
 }
 
 template <typename Kern>
-hipError_t launch_kernel(Kern kern, bool &attr_done, const GemmArgs &a, int BM, int BN, size_t smem, hipStream_t st,
+hipError_t launch_kernel(Kern kern, const GemmArgs &a, int BM, int BN, size_t smem, hipStream_t st,
                          int threads = kThreads)
 {
     GemmArgs g = a;
     g.tiles_m = (int)((g.M + BM - 1) / BM);
     g.tiles_n = (g.N + BN - 1) / BN;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(threads), smem, st, g);
     return hipGetLastError();
 }
@@ -1052,36 +1047,32 @@ hipError_t launch_kernel(Kern kern, bool &attr_done, const GemmArgs &a, int BM, 
 template <int BM, int BN, int NS, int WGM, int WGN>
 hipError_t launch_ring4(const GemmArgs &a, bool debug, hipStream_t st)
 {
-    static bool done[2] = {false, false};
     const size_t smem = (size_t)NS * (BM * 128 + BN * 64 + 1024);
     if (a.zc) {
-        static bool done_z[2] = {false, false};
         if (!a.colsumw) return hipErrorInvalidValue;
-        if (debug) return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, true, true>, done_z[1], a, BM, BN, smem, st);
-        return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, false, true>, done_z[0], a, BM, BN, smem, st);
+        if (debug) return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, true, true>, a, BM, BN, smem, st);
+        return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, false, true>, a, BM, BN, smem, st);
     }
-    if (debug) return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, true>, done[1], a, BM, BN, smem, st);
-    return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st);
+    if (debug) return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, true>, a, BM, BN, smem, st);
+    return launch_kernel(qgemm4_ring_kernel<BM, BN, NS, WGM, WGN, false>, a, BM, BN, smem, st);
 }
 
 // the kernel that takes every shape with asymmetric activations (ring, 128 x 128 x 64, four stages)
 hipError_t launch_ring_asym(const GemmArgs &a, bool debug, hipStream_t st)
 {
-    static bool done[2] = {false, false};
     constexpr int BM = 128, BN = 128, BK = 64, NS = 4;
     const size_t smem = (size_t)NS * (BM + BN) * BK;
-    if (debug) return launch_kernel(qgemm8_ring_kernel<BM, BN, BK, NS, 2, 2, true, true>, done[1], a, BM, BN, smem, st);
-    return launch_kernel(qgemm8_ring_kernel<BM, BN, BK, NS, 2, 2, false, true>, done[0], a, BM, BN, smem, st);
+    if (debug) return launch_kernel(qgemm8_ring_kernel<BM, BN, BK, NS, 2, 2, true, true>, a, BM, BN, smem, st);
+    return launch_kernel(qgemm8_ring_kernel<BM, BN, BK, NS, 2, 2, false, true>, a, BM, BN, smem, st);
 }
 
 template <int BM, int BN, int BK, int NS, int WGM, int WGN>
 hipError_t launch_ring(const GemmArgs &a, bool debug, hipStream_t st)
 {
     if (a.zc) return launch_ring_asym(a, debug, st);
-    static bool done[2] = {false, false};
     const size_t smem = (size_t)NS * (BM + BN) * BK;
-    if (debug) return launch_kernel(qgemm8_ring_kernel<BM, BN, BK, NS, WGM, WGN, true>, done[1], a, BM, BN, smem, st);
-    return launch_kernel(qgemm8_ring_kernel<BM, BN, BK, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st);
+    if (debug) return launch_kernel(qgemm8_ring_kernel<BM, BN, BK, NS, WGM, WGN, true>, a, BM, BN, smem, st);
+    return launch_kernel(qgemm8_ring_kernel<BM, BN, BK, NS, WGM, WGN, false>, a, BM, BN, smem, st);
 }
 
 template <int BM, int BN, int NS, int WGM, int WGN>
@@ -1089,21 +1080,20 @@ hipError_t launch_pipe(const GemmArgs &a, bool debug, hipStream_t st)
 {
     // the pipelined kernel takes full tiles only; ragged shapes go to the ring kernel
     if (a.M % BM != 0 || a.N % BN != 0) return launch_ring<128, 128, 64, 4, 2, 2>(a, debug, st);
-    static bool done[4] = {false, false, false, false};
     constexpr int NW = WGM * WGN;
     const size_t smem = (size_t)NS * (BM * 128 + NW * ((BN / 8 + NW - 1) / NW) * 1024);
     if (a.zc) {
         // asymmetric activations: built for the 128 x 144 tiles only; a block of LDS per wave for the zero-point operands
         if constexpr (BM == 128 && BN == 144 && NW == 4) {
             const size_t smem_z = smem + NW * kZpBlock;
-            if (debug) return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, true, true>, done[3], a, BM, BN, smem_z, st, NW * 64);
-            return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, false, true>, done[2], a, BM, BN, smem_z, st, NW * 64);
+            if (debug) return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, true, true>, a, BM, BN, smem_z, st, NW * 64);
+            return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, false, true>, a, BM, BN, smem_z, st, NW * 64);
         } else {
             return launch_ring_asym(a, debug, st);
         }
     }
-    if (debug) return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, true>, done[1], a, BM, BN, smem, st, NW * 64);
-    return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, false>, done[0], a, BM, BN, smem, st, NW * 64);
+    if (debug) return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, true>, a, BM, BN, smem, st, NW * 64);
+    return launch_kernel(qgemm8_pipe_kernel<BM, BN, NS, WGM, WGN, false>, a, BM, BN, smem, st, NW * 64);
 }
 
 template <int BM, int BN, int NS, int WGM, int WGN>
@@ -1111,27 +1101,21 @@ hipError_t launch_pipe2(const GemmArgs &a, bool debug, hipStream_t st)
 {
     // full tiles and at least NS k-tiles per wave group; else the one-group kernel
     if (a.M % BM != 0 || a.N % BN != 0 || a.K / 256 < NS) return launch_pipe<BM, BN, 2 * NS, WGM, WGN>(a, debug, st);
-    static bool done[4] = {false, false, false, false};
     const size_t smem = (size_t)2 * NS * (BM * 128 + 4 * ((BN / 8 + 3) / 4) * 1024) + (a.zc ? 8 * kZpBlock : 0);
     GemmArgs g = a;
     g.tiles_m = (int)(g.M / BM);
     g.tiles_n = g.N / BN;
-    auto go = [&](auto kern, bool &attr_done) -> hipError_t {
-        if (!attr_done) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+    auto go = [&](auto kern) -> hipError_t {
+        if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(2 * kThreads), smem, st, g);
         return hipGetLastError();
     };
     if (a.zc) {
-        if (debug) return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, true, true>, done[3]);
-        return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, false, true>, done[2]);
+        if (debug) return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, true, true>);
+        return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, false, true>);
     }
-    if (debug) return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, true>, done[1]);
-    return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, false>, done[0]);
+    if (debug) return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, true>);
+    return go(qgemm8_pipe2_kernel<BM, BN, NS, WGM, WGN, false>);
 }
 
 template <int BM, int BN, int NS, int WGM, int WGN, int WGS_PER_CU>
@@ -1139,19 +1123,13 @@ hipError_t launch_persist(const GemmArgs &a, bool debug, hipStream_t st)
 {
     // full tiles and at least NS k-tiles; everything else goes to the ring kernel
     if (a.M % BM != 0 || a.N % BN != 0 || a.K / 128 < NS) return launch_ring<128, 128, 64, 4, 2, 2>(a, debug, st);
-    static bool done[2] = {false, false};
     GemmArgs g = a;
     g.tiles_m = (int)(g.M / BM);
     g.tiles_n = g.N / BN;
     const size_t smem = (size_t)NS * (BM + BN) * 128;
     auto kern = debug ? qgemm8_persist_kernel<BM, BN, NS, WGM, WGN, true>
                       : qgemm8_persist_kernel<BM, BN, NS, WGM, WGN, false>;
-    if (!done[debug]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        done[debug] = true;
-    }
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
     int grid = 256 * WGS_PER_CU;
     if (grid > g.tiles_m * g.tiles_n) grid = g.tiles_m * g.tiles_n;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), smem, st, g);

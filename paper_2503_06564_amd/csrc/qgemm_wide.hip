@@ -414,17 +414,11 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
 template <bool DEBUG, bool FULL>
 hipError_t launch_wide(const GemmArgs &a, hipStream_t st)
 {
-    static bool done = false;
     GemmArgs g = a;
     g.tiles_m = (int)((g.M + kWideBM - 1) / kWideBM);
     g.tiles_n = (g.N + kWideBN - 1) / kWideBN;
     auto kern = qgemm8_wide_kernel<DEBUG, FULL>;
-    if (!done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWideLds);
-        if (e != hipSuccess) return e;
-        done = true;
-    }
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), kWideLds); e != hipSuccess) return e;
     int grid = 256;
     if (grid > g.tiles_m * g.tiles_n) grid = g.tiles_m * g.tiles_n;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kWideLds, st, g);

@@ -327,16 +327,12 @@ hipError_t launch_dense_blocks(const uint16_t *X, int64_t M, int nb, int64_t ldx
     if (chunks > most) chunks = most;
     if (chunks < 1) chunks = 1;
     const size_t smem = (size_t)kPiecesPerBlock * 16;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(rotate_dense_block_kernel<false, TT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(rotate_dense_block_kernel<true, TT>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(rotate_dense_block_kernel<false, TT>), smem);
+        e != hipSuccess)
+        return e;
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(rotate_dense_block_kernel<true, TT>), smem);
+        e != hipSuccess)
+        return e;
     const unsigned mg = (unsigned)((M + 255) / 256);
     hipLaunchKernelGGL(dense_clear_kernel, dim3(mg), dim3(256), 0, st, sx, M);
     hipLaunchKernelGGL((rotate_dense_block_kernel<false, TT>), dim3((unsigned)chunks, nb), dim3(512), smem, st,
@@ -549,13 +545,9 @@ hipError_t launch_rotate_quant_dense_rpr(const uint16_t *X, int64_t M, int K, in
     const int64_t groups = (M + 15) / 16;
     const int64_t grid = groups < 256 ? groups : 256;
     const size_t smem = sizeof(float) * ((size_t)16 * (K + 4) + 2 * nb * 16) + sizeof(int) * (size_t)K;
-    static size_t attr_smem = 0;
-    if (smem > attr_smem) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(rotate_quant_dense_rpr_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_smem = smem;
-    }
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(rotate_quant_dense_rpr_kernel), smem);
+        e != hipSuccess)
+        return e;
     hipLaunchKernelGGL(rotate_quant_dense_rpr_kernel, dim3((unsigned)grid), dim3(64 * nb), smem, st, X, M, nb, ldx,
                        static_cast<const uint4 *>(pieces1), perm, static_cast<const float4 *>(frags2), Xq, sx);
     return hipGetLastError();

@@ -216,13 +216,9 @@ hipError_t launch_rpr(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx,
 {
     const int K = nb * kBlock;
     const size_t smem = sizeof(float) * ((size_t)TOK * (K + kRowPad) + (size_t)nw * 16) + 1024;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(rotate_quant_rpr_kernel<TOK, SPW>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(rotate_quant_rpr_kernel<TOK, SPW>), 160 * 1024);
+        e != hipSuccess)
+        return e;
     const int64_t groups = (M + TOK - 1) / TOK;
     hipLaunchKernelGGL((rotate_quant_rpr_kernel<TOK, SPW>), dim3((unsigned)groups), dim3(64 * nw), smem, st,
                        X, M, nb, ldx, diag, perm, Xq, sx, static_cast<const uint4 *>(warm),

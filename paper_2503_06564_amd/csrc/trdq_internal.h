@@ -84,6 +84,11 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, con
 
 hipError_t launch_cosine_similarity(const uint16_t *A, const uint16_t *B, int n_seg, int64_t seg_len,
                                     int64_t stride_a, int64_t stride_b, double *acc_ws, float *out, hipStream_t st);
+// Raises a kernel's dynamic-LDS limit to at least `bytes` on the current device.  The attribute
+// belongs to the (kernel, device) pair; what has been set is remembered per pair, so the HIP call
+// happens once for each and callers may ask before every launch (thread-safe).
+hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes);
+
 // yardstick kernels (peaks.hip)
 int peak_mfma_independent();
 hipError_t launch_peak_mfma_i8(int32_t *sink, int workgroups, int waves, int iters, hipStream_t st);
