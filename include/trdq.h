@@ -37,7 +37,9 @@
  *     data pointers may be NULL (an empty tensor has no storage).
  *   - NaN / Inf in X or W are not detected; the result is then unspecified.
  *   - Handles are immutable after creation: concurrent forward calls on
- *     different streams may share them.
+ *     different streams may share them.  A handle's buffers live on the device
+ *     that was current when it was created; a launch that is given a handle
+ *     while another device is current returns ERR_MISMATCH.
  */
 #ifndef TRDQ_H
 #define TRDQ_H

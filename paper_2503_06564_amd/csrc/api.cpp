@@ -53,6 +53,14 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 
 inline trdq_status hip_status(hipError_t e) { return e == hipSuccess ? TRDQ_OK : TRDQ_ERR_HIP; }
 
+// A handle's buffers live on the device that was current when it was created.
+trdq_status check_device(int handle_device)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return TRDQ_ERR_HIP;
+    return dev == handle_device ? TRDQ_OK : TRDQ_ERR_MISMATCH;
+}
+
 // Data pointers may be NULL when M == 0 (an empty tensor has no storage).
 trdq_status check_rotate_args(const void *X, int64_t M, int K, int64_t ldx, int block)
 {
@@ -301,6 +309,7 @@ trdq_status trdq_channel_absmax_dense(const void *X_dev, int64_t M, int64_t ldx,
     if (rc != TRDQ_OK) return rc;
     if (!mag_dev) return TRDQ_ERR_NULL;
     if (!aligned(mag_dev, 4)) return TRDQ_ERR_SHAPE;
+    if (trdq_status rd = check_device(rot->device); rd != TRDQ_OK) return rd;
     return hip_status(trdq::launch_channel_absmax_dense(static_cast<const uint16_t *>(X_dev), M, rot->K, ldx, rot->pieces,
                                                         mag_dev, static_cast<hipStream_t>(stream)));
 }
@@ -383,6 +392,8 @@ trdq_status trdq_rotate_quant_dense_rpr(const void *X_dev, int64_t M, int64_t ld
     if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || !aligned(perm_dev, 4)) return TRDQ_ERR_SHAPE;
     if (!trdq::rotate_quant_dense_rpr_supports(rot1->K)) return TRDQ_ERR_UNSUPPORTED;
     if (M == 0) return TRDQ_OK;
+    if (trdq_status rd = check_device(rot1->device); rd != TRDQ_OK) return rd;
+    if (trdq_status rd = check_device(rot2->device); rd != TRDQ_OK) return rd;
     return hip_status(trdq::launch_rotate_quant_dense_rpr(static_cast<const uint16_t *>(X_dev), M, rot1->K, ldx,
                                                           rot1->pieces, perm_dev, rot2->frags32, Xq_dev, sx_dev,
                                                           static_cast<hipStream_t>(stream)));
@@ -397,6 +408,7 @@ trdq_status trdq_rotate_quant_dense(const void *X_dev, int64_t M, int64_t ldx, c
     if (M > 0 && (!Xq_dev || !sx_dev)) return TRDQ_ERR_NULL;
     if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4)) return TRDQ_ERR_SHAPE;
     if (M == 0) return TRDQ_OK;
+    if (trdq_status rd = check_device(rot->device); rd != TRDQ_OK) return rd;
     return hip_status(trdq::launch_rotate_quant_dense(static_cast<const uint16_t *>(X_dev), M, rot->K, ldx, rot->pieces,
                                                       Xq_dev, sx_dev, static_cast<hipStream_t>(stream)));
 }
@@ -607,6 +619,7 @@ trdq_status trdq_rotate_quant_warm(const void *X_dev, int64_t M, int K, int64_t 
     const void *warm = nullptr;
     int64_t warm_bytes = 0;
     if (next && next->codes) {
+        if (trdq_status rd = check_device(next->device); rd != TRDQ_OK) return rd;
         warm = next->codes;
         warm_bytes = (int64_t)next->N * next->K / (next->wbits == 4 ? 2 : 1);
         warm_bytes -= warm_bytes % 16;
@@ -630,6 +643,7 @@ trdq_status trdq_rotate_quant_bits(const void *X_dev, int64_t M, int K, int64_t 
     const void *warm = nullptr;
     int64_t warm_bytes = 0;
     if (next && next->codes) {
+        if (trdq_status rd = check_device(next->device); rd != TRDQ_OK) return rd;
         warm = next->codes;
         warm_bytes = (int64_t)next->N * next->K / (next->wbits == 4 ? 2 : 1);
         warm_bytes -= warm_bytes % 16;
@@ -654,6 +668,7 @@ trdq_status trdq_rotate_quant_asym(const void *X_dev, int64_t M, int K, int64_t 
     const void *warm = nullptr;
     int64_t warm_bytes = 0;
     if (next && next->codes) {
+        if (trdq_status rd = check_device(next->device); rd != TRDQ_OK) return rd;
         warm = next->codes;
         warm_bytes = (int64_t)next->N * next->K / (next->wbits == 4 ? 2 : 1);
         warm_bytes -= warm_bytes % 16;
@@ -678,6 +693,7 @@ trdq_status trdq_rotate_quant_rpr(const void *X_dev, int64_t M, int K, int64_t l
     const void *warm = nullptr;
     int64_t warm_bytes = 0;
     if (next && next->codes) {
+        if (trdq_status rd = check_device(next->device); rd != TRDQ_OK) return rd;
         warm = next->codes;
         warm_bytes = (int64_t)next->N * next->K / (next->wbits == 4 ? 2 : 1);
         warm_bytes -= warm_bytes % 16;
@@ -698,6 +714,7 @@ trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float 
     if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || (acc_debug_dev && !aligned(acc_debug_dev, 16)))
         return TRDQ_ERR_SHAPE;
     if (M == 0) return TRDQ_OK;
+    if (trdq_status rd = check_device(w->device); rd != TRDQ_OK) return rd;
     return hip_status(trdq::launch_qgemm(*w, Xq_dev, sx_dev, nullptr, M, bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
                                          acc_debug_dev, g_variant, static_cast<hipStream_t>(stream)));
 }
@@ -714,6 +731,7 @@ trdq_status trdq_qgemm_asym(const trdq_weights *w, const int8_t *Xq_dev, const f
         (acc_debug_dev && !aligned(acc_debug_dev, 16)))
         return TRDQ_ERR_SHAPE;
     if (M == 0) return TRDQ_OK;
+    if (trdq_status rd = check_device(w->device); rd != TRDQ_OK) return rd;
     return hip_status(trdq::launch_qgemm(*w, Xq_dev, sx_dev, zc_dev, M, bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
                                          acc_debug_dev, -1, static_cast<hipStream_t>(stream)));
 }
@@ -730,6 +748,7 @@ trdq_status trdq_linear_fused(const void *X_dev, int64_t M, int64_t ldx, const f
     if (diag_dev && !aligned(diag_dev, 16)) return TRDQ_ERR_SHAPE;
     if (!trdq::fused_supports(w->K)) return TRDQ_ERR_UNSUPPORTED;
     if (M == 0) return TRDQ_OK;
+    if (trdq_status rd = check_device(w->device); rd != TRDQ_OK) return rd;
     return hip_status(trdq::launch_linear_fused(*w, static_cast<const uint16_t *>(X_dev), M, ldx, diag_dev,
                                                 bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
                                                 static_cast<hipStream_t>(stream)));
