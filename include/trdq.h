@@ -260,7 +260,8 @@ trdq_status trdq_rotate_quant_dense(const void *X_dev, int64_t M, int64_t ldx, c
  * the first rotation; rot2 the second rotation and must have been created WITHOUT a diagonal
  * (else ERR_MISMATCH); perm_dev: int32 [K] on the device, (U P)[k'] = U[perm[k']] as for
  * trdq_rotate_quant_rpr.  Other arguments, layouts and errors as the one-rotation calls above;
- * the activation side takes K <= 1536 (ERR_UNSUPPORTED beyond). */
+ * the activation side takes K <= 4608 (ERR_UNSUPPORTED beyond): 16-token workgroups up to K = 1536,
+ * 8-token workgroups that run the second rotation twice (maxima, then codes) for wider rows. */
 trdq_status trdq_prepare_weights_dense_rpr(const float *W_dev, int K, int N, const trdq_rotation *rot1,
                                            const int32_t *perm_dev, const trdq_rotation *rot2, int wbits,
                                            void *stream, trdq_weights **out);

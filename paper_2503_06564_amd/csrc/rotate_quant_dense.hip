@@ -447,6 +447,112 @@ __global__ __launch_bounds__(768) void rotate_quant_dense_rpr_kernel(
     }
 }
 
+// Rows wider than 12 blocks (up to 36): the once-rotated fp32 rows of 16 tokens no longer fit LDS, so a
+// workgroup of 12 waves takes 8 tokens (their rows: 8 x (K + 4) floats, 148 KB at K = 4608) and every wave
+// several blocks, one after the other.  The matrix instructions still have 16 token columns: stage 1
+// rotates 16 consecutive tokens and keeps the first 8, stage 2 reads row (column mod 8).  A wave cannot hold
+// the results of three blocks across the exchange of the token maxima, so stage 2 runs twice: once for the
+// maxima, once more for the codes.  The gather indices come straight from `perm` (cached reads).
+__global__ __launch_bounds__(768) void rotate_quant_dense_rpr_wide_kernel(
+    const uint16_t *__restrict__ X, int64_t M, int nb, int64_t ldx, const uint4 *__restrict__ pieces1,
+    const int32_t *__restrict__ perm, const float4 *__restrict__ frags2, int8_t *__restrict__ Xq, float *__restrict__ sx)
+{
+    extern __shared__ __align__(16) float lds_f[];
+    const int K = nb * kBlock;
+    const int LDT = K + 4;
+    float *const T = lds_f;                              // [8][K + 4]
+    float *const amax_s = lds_f + 8 * LDT;               // [2][nw][16]
+    const int nw = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+    const int row = l16 & 7;
+    const int64_t groups = (M + 7) / 8;
+
+    // second rotation of block b on the gathered rows: o[t][j] = channel b*128 + 32 g + 4 t + j of token `row`;
+    // returns the lane's largest magnitude
+    auto second = [&](int b, float (&o)[8][4]) -> float {
+        float bv[32];
+#pragma unroll
+        for (int s = 0; s < 32; ++s) {                   // k-step s: k = 4 s + g
+            int p = perm[b * kBlock + 4 * s + g];
+            p = p < 0 ? 0 : (p >= K ? K - 1 : p);
+            bv[s] = T[row * LDT + p];
+        }
+        float amax = 0.0f;
+        int lane_off = lane;                             // keeps the fragment loads inside the block loop
+        asm volatile("" : "+v"(lane_off));
+        const float4 *fb = frags2 + (size_t)b * (kBlock * kBlock / 4) + lane_off;
+        float4 fa2[2][8];
+        auto request2 = [&](float4 (&f)[8], int t) {
+#pragma unroll
+            for (int s4 = 0; s4 < 8; ++s4) f[s4] = fb[(t * 8 + s4) * 64];
+        };
+        request2(fa2[0], 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            if (t + 1 < 8) request2(fa2[(t + 1) & 1], t + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            v4f acc = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s4 = 0; s4 < 8; ++s4) {
+                const float4 a4 = fa2[t & 1][s4];
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, bv[4 * s4 + 0], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, bv[4 * s4 + 1], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, bv[4 * s4 + 2], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, bv[4 * s4 + 3], acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                o[t][j] = acc[j];
+                amax = fmaxf(amax, fabsf(acc[j]));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        return amax;
+    };
+
+    int parity = 0;
+    for (int64_t tg = blockIdx.x; tg < groups; tg += gridDim.x) {
+        const int64_t tok0 = tg * 8;
+        for (int b = wave; b < nb; b += nw) {
+            float out[1][8][4];
+            float unused[1] = {0.0f};
+            rotate_block_dense<1>(X, M, ldx, pieces1, b, tok0, lane, out, unused);   // tokens tok0 .. tok0 + 15 (clamped to M - 1)
+            if (l16 < 8) {
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    *reinterpret_cast<float4 *>(T + l16 * LDT + b * kBlock + 32 * g + 4 * t) =
+                        make_float4(out[0][t][0], out[0][t][1], out[0][t][2], out[0][t][3]);
+            }
+        }
+        __syncthreads();
+        float amax = 0.0f;
+        for (int b = wave; b < nb; b += nw) {
+            float o[8][4];
+            amax = fmaxf(amax, second(b, o));
+        }
+        float *const am = amax_s + parity * nw * 16;
+        amax = fmaxf(amax, __shfl_xor(amax, 16));
+        amax = fmaxf(amax, __shfl_xor(amax, 32));
+        if (g == 0) am[wave * 16 + l16] = amax;
+        __syncthreads();
+        parity ^= 1;
+        float a = 0.0f;
+        for (int w = 0; w < nw; ++w) a = fmaxf(a, am[w * 16 + l16]);
+        const int64_t token = tok0 + row;
+        const float inv = a > 0.0f ? 127.0f / a : 0.0f;
+        if (wave == 0 && lane < 8 && token < M) sx[token] = a / 127.0f;
+        for (int b = wave; b < nb; b += nw) {
+            float o[8][4];
+            second(b, o);
+            if (l16 < 8 && token < M) store_codes_dense(o, inv, Xq + token * K + b * kBlock + 32 * g);
+        }
+        __syncthreads();                                 // every wave has read T before the next group overwrites it
+    }
+}
+
 // mag[k] = max over the tokens of |((X . d) . BlockDiag(R_b))[i][k]| (what the zigzag permutation is dealt
 // from when the first rotation is dense).  A wave per (token group, block); the 16 tokens of a lane
 // row are reduced with row moves, one lane per row merges with an atomic maximum on the bit patterns.
@@ -535,13 +641,25 @@ hipError_t launch_channel_absmax_dense(const uint16_t *X, int64_t M, int K, int6
 }
 
 bool rotate_quant_dense_supports(int K) { return K % kBlock == 0 && K / kBlock <= 36; }
-bool rotate_quant_dense_rpr_supports(int K) { return K % kBlock == 0 && K / kBlock <= 12; }
+bool rotate_quant_dense_rpr_supports(int K) { return K % kBlock == 0 && K / kBlock <= 36; }
 
 hipError_t launch_rotate_quant_dense_rpr(const uint16_t *X, int64_t M, int K, int64_t ldx, const void *pieces1,
                                          const int32_t *perm, const void *frags2, int8_t *Xq, float *sx, hipStream_t st)
 {
     if (M == 0) return hipSuccess;
     const int nb = K / kBlock;
+    if (nb > 12) {
+        // wide rows: 8 tokens per workgroup of 12 waves
+        const int64_t groups8 = (M + 7) / 8;
+        const int64_t grid8 = groups8 < 256 ? groups8 : 256;
+        const size_t smem8 = sizeof(float) * ((size_t)8 * (K + 4) + 2 * 12 * 16);
+        if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(rotate_quant_dense_rpr_wide_kernel), smem8);
+            e != hipSuccess)
+            return e;
+        hipLaunchKernelGGL(rotate_quant_dense_rpr_wide_kernel, dim3((unsigned)grid8), dim3(64 * 12), smem8, st, X, M, nb,
+                           ldx, static_cast<const uint4 *>(pieces1), perm, static_cast<const float4 *>(frags2), Xq, sx);
+        return hipGetLastError();
+    }
     const int64_t groups = (M + 15) / 16;
     const int64_t grid = groups < 256 ? groups : 256;
     const size_t smem = sizeof(float) * ((size_t)16 * (K + 4) + 2 * nb * 16) + sizeof(int) * (size_t)K;

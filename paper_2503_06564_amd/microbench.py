@@ -101,10 +101,10 @@ def dense(dev):
                        hadamard_us=round(_timeit(lambda i: trdq.rotate_quant(Xs[i % R], d, Xq, sx)), 1),
                        dense_us=round(_timeit(lambda i: trdq.rotate_quant_dense(Xs[i % R], rot1, Xq, sx)), 1),
                        hadamard_rpr_us=round(_timeit(lambda i: trdq.rotate_quant_rpr(Xs[i % R], d, perm, Xq, sx)), 1))
-            if K <= 1536:
-                R2 = torch.from_numpy(wl.orthogonal_uniform_first_row(2, K // 128).astype(np.float32)).to(dev)
-                rot2 = trdq.Rotation(R2)
-                row["dense_rpr_us"] = round(_timeit(lambda i: trdq.rotate_quant_dense_rpr(Xs[i % R], rot1, perm, rot2, Xq, sx)), 1)
+            R2 = torch.from_numpy(wl.orthogonal_uniform_first_row(2, K // 128).astype(np.float32)).to(dev)
+            rot2 = trdq.Rotation(R2)
+            row["dense_rpr_us"] = round(_timeit(lambda i: trdq.rotate_quant_dense_rpr(Xs[i % R], rot1, perm, rot2, Xq, sx),
+                                                20 if M * K > (1 << 26) else 50), 1)
             _out(**row)
 
 

@@ -178,7 +178,9 @@ def _rot(Rs, d=None):
     return trdq.Rotation(f32_to_dev(Rs.reshape(-1, 128)).view(-1, 128, 128), None if d is None else f32_to_dev(d))
 
 
-@pytest.mark.parametrize("M,K", [(1, 128), (37, 256), (300, 1152), (64, 1536), (530, 384), (0, 256)])
+# K > 1536 takes the 8-token kernel: 13 blocks (waves with one and with two blocks), 18, 36; token counts around 8
+@pytest.mark.parametrize("M,K", [(1, 128), (37, 256), (300, 1152), (64, 1536), (530, 384), (0, 256),
+                                 (1, 1664), (40, 1664), (9, 2304), (70, 4608), (263, 4608)])
 def test_rotate_quant_dense_rpr_matches_oracle(oracle, M, K):
     say(f"rotate_quant_dense_rpr M={M} K={K}")
     Xb, _, d, _ = wl.small_case(71, max(M, 1), K, 16, n_outliers=max(1, K // 144), outlier=40.0)
@@ -197,7 +199,7 @@ def test_rotate_quant_dense_rpr_matches_oracle(oracle, M, K):
     rot1.close(); rot2.close()
 
 
-@pytest.mark.parametrize("M,K,N,wbits", [(17, 256, 144, 8), (300, 1152, 272, 8), (64, 384, 160, 4)])
+@pytest.mark.parametrize("M,K,N,wbits", [(17, 256, 144, 8), (300, 1152, 272, 8), (64, 384, 160, 4), (50, 4608, 144, 8)])
 def test_dense_rpr_linear_end_to_end(oracle, M, K, N, wbits):
     say(f"dense R1 P R2 linear M={M} K={K} N={N} wbits={wbits}")
     Xb, W, d, bias = wl.small_case(72, M, K, N, n_outliers=max(1, K // 144), outlier=40.0)
@@ -234,14 +236,10 @@ def test_dense_rpr_argument_errors():
     with pytest.raises(trdq.TrdqError) as e:
         trdq.rotate_quant_dense_rpr(X, rot1, perm, rot2_bad, Xq, sx)      # the second rotation carries a diagonal
     assert e.value.status == trdq.ERR_MISMATCH
-    Rw = torch.zeros((13, 128, 128), device=dev())
-    wide1, wide2 = trdq.Rotation(Rw), trdq.Rotation(Rw)
-    Xw = torch.zeros((4, 13 * 128), dtype=torch.bfloat16, device=dev())
     with pytest.raises(trdq.TrdqError) as e:
-        trdq.rotate_quant_dense_rpr(Xw, wide1, torch.arange(13 * 128, dtype=torch.int32, device=dev()), wide2,
-                                    torch.zeros((4, 13 * 128), dtype=torch.int8, device=dev()), sx)
+        trdq.Rotation(torch.zeros((37, 128, 128), device=dev()))          # more than 36 blocks: no kernel takes them
     assert e.value.status == trdq.ERR_UNSUPPORTED
-    for r in (rot1, rot2_bad, rot2, wide1, wide2):
+    for r in (rot1, rot2_bad, rot2):
         r.close()
 
 

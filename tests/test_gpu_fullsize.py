@@ -331,3 +331,41 @@ def test_two_million_tokens_64_bit_offsets(oracle):
     cols_diff = (codes != ref["Wq"]).any(axis=0)
     gu.assert_y_close(gu.bf16_to_host(Y[idx]), ref["Y"], "Y (2M tokens)", rows_diff, cols_diff)
     w.close()
+
+
+# Both rotations dense (Eq. 10 as printed) at config 1's sizes: K = 1152 takes the 16-token kernel, K = 4608 the
+# 8-token one; sampled rows against the oracle (the rotation acts on a row alone, the weights are exact).
+@pytest.mark.parametrize("kind", ["proj", "fc2"])
+def test_dense_chain_full_size_sampled_rows(oracle, kind):
+    cfg = wl.CONFIGS[1]
+    say(f"config 1: dense R1 P R2 {kind}, M={cfg.M}")
+    K, N = wl.LAYER_SHAPES[kind]
+    Xb = wl.make_x(cfg, kind, 2)
+    M = Xb.shape[0]
+    W, d, bias = wl.make_w(cfg, kind), wl.make_diag(cfg, kind, wl.step_to_group(cfg, 2)), wl.make_bias(cfg, kind)
+    R1 = wl.orthogonal_uniform_first_row(500 + K, K // 128).astype(np.float32)
+    R2 = wl.orthogonal_uniform_first_row(600 + K, K // 128).astype(np.float32)
+    rot1 = trdq.Rotation(gu.f32_to_dev(R1.reshape(-1, 128)).view(-1, 128, 128), gu.f32_to_dev(d))
+    rot2 = trdq.Rotation(gu.f32_to_dev(R2.reshape(-1, 128)).view(-1, 128, 128))
+    # the permutation is an input of both sides: dealt by the oracle from its own once-rotated activations
+    perm = oracle.zigzag(np.abs(oracle.rotate_dense(Xb, d, R1)).max(axis=0), 128).astype(np.int32)
+    perm_dev = torch.from_numpy(perm).cuda()
+    w = trdq.prepare_weights_dense_rpr(gu.f32_to_dev(W), rot1, perm_dev, rot2, wbits=8)
+    Xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+    sx = torch.empty((M,), dtype=torch.float32, device="cuda")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    trdq.rotate_quant_dense_rpr(gu.bf16_to_dev(Xb), rot1, perm_dev, rot2, Xq, sx)
+    trdq.qgemm(w, Xq, sx, Y, bias=gu.f32_to_dev(bias))
+    torch.cuda.synchronize()
+    assert bool((Xq.abs().amax(dim=1)[sx > 0] == 127).all())
+    rows = sample_rows(M, 66)
+    idx = torch.from_numpy(rows).cuda()
+    ref = oracle.linear_dense_rpr(Xb[rows], W, d, R1, perm, R2, bias, exact_blas=True)
+    gu.assert_codes_close(Xq[idx].cpu().numpy(), ref["Xq"], f"{kind} Xq (dense R1 P R2)")
+    gu.assert_scales_close(sx[idx].cpu().numpy(), ref["sx"], f"{kind} s_x (dense R1 P R2)")
+    codes, scales = w.export()
+    gu.assert_codes_close(codes, ref["Wq"], f"{kind} Wq (dense R1 P R2)")
+    rows_diff = (Xq[idx].cpu().numpy() != ref["Xq"]).any(axis=1)
+    cols_diff = (codes != ref["Wq"]).any(axis=0)
+    gu.assert_y_close(gu.bf16_to_host(Y[idx]), ref["Y"], f"{kind} Y (dense R1 P R2)", rows_diff, cols_diff)
+    w.close(); rot1.close(); rot2.close()
