@@ -65,7 +65,7 @@ def cpu_baseline(cfg, wl, budget_s):
     group = None if cfg.wbits[0] == 8 else 128
     ops, tokens, spent, groups = 0, 0, 0.0, 0
     for g in range(cfg.n_groups):
-        step = next(s for s in range(cfg.n_steps) if wl.step_to_group(cfg, s) == g)
+        step = next(s for s in range(cfg.n_steps) if wl.draw_group(cfg, s) == g)
         prepared = {}
         for kind in cfg.kinds:                       # untimed: inputs and the offline weight side
             d = wl.make_diag(cfg, kind, g)
@@ -175,7 +175,7 @@ def main():
         SX[kind] = torch.empty((M,), dtype=torch.float32, device=dev)
         ZC[kind] = torch.empty((M,), dtype=torch.int32, device=dev)
         for g in range(n_groups):
-            step_of_g = next(s for s in range(cfg.n_steps) if wl.step_to_group(cfg, s) == g)
+            step_of_g = next(s for s in range(cfg.n_steps) if wl.draw_group(cfg, s) == g)
             xb = wl.make_x(cfg, kind, step_of_g)
             X[kind, g] = torch.from_numpy(xb.view(np.int16)).to(dev).view(torch.bfloat16)
             D[kind, g] = torch.from_numpy(wl.make_diag(cfg, kind, g)).to(dev)

@@ -70,8 +70,10 @@ def bf16_bits_to_f32(h):
     return (np.asarray(h, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
 
 
-def step_to_group(config, step):
-    """Contiguous near-equal partition of the sampling steps into groups."""
+def draw_group(config, step):
+    """Which of the config's n_groups seeded draws (activations, outlier scale) a sampling step reads:
+    steps are dealt to the draws in contiguous near-equal runs.  This is part of the input recipe only;
+    the method's own step -> group table is the library's (trdq_table_*) and, separately, the oracle's."""
     return (step * config.n_groups) // config.n_steps
 
 
@@ -88,7 +90,7 @@ def outlier_scale(config, kind, step):
         return 50.0
     if config.cfg == 3:
         return 20.0 + 80.0 * step / (config.n_steps - 1)
-    g = step_to_group(config, step)
+    g = draw_group(config, step)
     return float(_rng(_TAG_OS, config.cfg, kind, 0, g).uniform(10.0, 80.0))
 
 
@@ -100,7 +102,7 @@ def make_x(config, kind, step=0, M=None, rows=None):
     a subset of row indices of the full-size tensor without changing values."""
     K = LAYER_SHAPES[kind][0]
     M = config.M if M is None else M
-    index = step if config.cfg == 3 else step_to_group(config, step)
+    index = step if config.cfg == 3 else draw_group(config, step)
     x = _rng(_TAG_X, config.cfg, kind, 0, index).standard_normal((M, K), dtype=np.float32)
     ch = outlier_channels(config, kind)
     x[:, ch] *= np.float32(outlier_scale(config, kind, step))

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 from paper_2503_06564_amd import trdq, workloads as wl
-from gpu_util import (assert_codes_close, assert_scales_close, assert_y_close, bf16_to_dev, bf16_to_host,
+from gpu_util import (assert_codes_close, assert_scales_close, assert_y_close, assert_y_same_codes, narrow_code_masks, bf16_to_dev, bf16_to_host,
                       dev, f32_to_dev)
 
 pytestmark = pytest.mark.gpu
@@ -74,9 +74,10 @@ def test_w6a6_linear_end_to_end(oracle, M, K, N, fused):
         torch.cuda.synchronize()
         want = oracle.acc_exact_blas(Xq.cpu().numpy(), codes)
         assert np.array_equal(acc.cpu().numpy(), want)
-        rows = np.any(Xq.cpu().numpy() != ref["Xq"], axis=1)
-        cols = np.any(codes != ref["Wq"], axis=0)
-        assert_y_close(bf16_to_host(Y), ref["Y"], "Y (W6A6)", skip_rows=rows, skip_cols=cols)
+        assert_y_close(bf16_to_host(Y), ref["Y"], "Y (W6A6)",
+                       *narrow_code_masks(6, 6, Xq.cpu().numpy(), ref["Xq"], codes, ref["Wq"]))
+        y_same = oracle.dequant(want, sx.cpu().numpy(), scales, bias)
+        assert_y_same_codes(bf16_to_host(Y), y_same, "Y (W6A6, same codes)")
     w.close()
 
 

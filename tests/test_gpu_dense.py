@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2503_06564_amd import trdq, workloads as wl
-from gpu_util import (assert_codes_close, assert_scales_close, assert_y_close, bf16_to_dev, bf16_to_host,
+from gpu_util import (assert_codes_close, assert_scales_close, assert_y_close, narrow_code_masks, bf16_to_dev, bf16_to_host,
                       dev, f32_to_dev)
 
 pytestmark = pytest.mark.gpu
@@ -81,9 +81,8 @@ def test_dense_linear_end_to_end(oracle, M, K, N, wbits):
     Y = torch.zeros((M, N), dtype=torch.bfloat16, device=dev())
     trdq.qgemm(w, Xq, sx, Y, bias=f32_to_dev(bias))
     torch.cuda.synchronize()
-    rows = np.any(Xq.cpu().numpy() != ref["Xq"], axis=1)
-    cols = np.any(codes != ref["Wq"], axis=0)
-    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (dense blocks)", skip_rows=rows, skip_cols=cols)
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (dense blocks)",
+                   *narrow_code_masks(8, wbits, None, None, codes, ref["Wq"]))
     # the rotation cancels: close to the unquantised product as well
     exact = oracle.bf16_to_f64(Xb) @ W.astype(np.float64) + bias
     err = np.abs(oracle.bf16_to_f64(bf16_to_host(Y)) - exact).mean() / np.abs(exact).mean()
@@ -160,9 +159,9 @@ def test_greedy_rotation_end_to_end_beats_no_rotation(oracle):
     trdq.qgemm(w, Xq, sx, Y, bias=f32_to_dev(bias))
     torch.cuda.synchronize()
     ref = oracle.linear_dense(Xb, W, d, R.cpu().numpy(), bias, exact_blas=True)
-    rows = np.any(Xq.cpu().numpy() != ref["Xq"], axis=1)
-    cols = np.any(w.export()[0] != ref["Wq"], axis=0)
-    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (greedy blocks)", skip_rows=rows, skip_cols=cols)
+    assert_codes_close(Xq.cpu().numpy(), ref["Xq"], "Xq (greedy blocks)")
+    assert_codes_close(w.export()[0], ref["Wq"], "Wq (greedy blocks)")
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (greedy blocks)")
     exact = oracle.bf16_to_f64(Xb) @ W.astype(np.float64) + bias
     err_rot = np.abs(oracle.bf16_to_f64(bf16_to_host(Y)) - exact).mean()
     # the same W8A8 quantisers without any rotation (identity blocks) lose much more to the outliers
@@ -219,9 +218,7 @@ def test_dense_rpr_linear_end_to_end(oracle, M, K, N, wbits):
     trdq.qgemm(w, Xq, sx, Y, bias=f32_to_dev(bias))
     torch.cuda.synchronize()
     assert_codes_close(Xq.cpu().numpy(), ref["Xq"], "Xq (dense R1 P R2)")
-    rows = np.any(Xq.cpu().numpy() != ref["Xq"], axis=1)
-    cols = np.any(codes != ref["Wq"], axis=0)
-    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (dense R1 P R2)", skip_rows=rows, skip_cols=cols)
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (dense R1 P R2)")
     w.close(); rot1.close(); rot2.close()
 
 
@@ -290,9 +287,9 @@ def test_time_rotation_calibration_chain(oracle, Mc, K, steps):
     trdq.qgemm(w, Xq, sx, Y, bias=f32_to_dev(bias))
     torch.cuda.synchronize()
     ref = oracle.linear_dense_rpr(Xb, W, d, R1h, perm, R2.cpu().numpy(), bias, exact_blas=True)
-    rows = np.any(Xq.cpu().numpy() != ref["Xq"], axis=1)
-    cols = np.any(w.export()[0] != ref["Wq"], axis=0)
-    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (calibrated R1 P R2)", skip_rows=rows, skip_cols=cols)
+    assert_codes_close(Xq.cpu().numpy(), ref["Xq"], "Xq (calibrated R1 P R2)")
+    assert_codes_close(w.export()[0], ref["Wq"], "Wq (calibrated R1 P R2)")
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (calibrated R1 P R2)")
     exact = oracle.bf16_to_f64(Xb) @ W.astype(np.float64) + bias
     err = np.abs(oracle.bf16_to_f64(bf16_to_host(Y)) - exact).mean()
     eye = np.stack([np.eye(128, dtype=np.float32)] * nb)

@@ -131,11 +131,15 @@ def _linear_case(oracle, seed, M, K, N, wbits, variant, with_bias=True, ldy=None
     assert np.array_equal(acc.cpu().numpy(), want_acc), "int32 accumulators differ"
     # epilogue on the same codes and scales
     y_same = oracle.dequant(want_acc, sx.cpu().numpy(), sw_h, bias)
-    gu.assert_y_close(gu.bf16_to_host(Y), y_same, "Y (same codes)")
-    # (iii) against the oracle's own end-to-end quantised output
+    gu.assert_y_same_codes(gu.bf16_to_host(Y), y_same, "Y (same codes)")
+    # (i) codes and scales, (iii) outputs against the oracle's own end-to-end quantised result
     ref = oracle.linear(Xb, W, d, bias, wbits=wbits, exact_blas=True)
+    gu.assert_codes_close(Xq_h, ref["Xq"], "Xq")
+    gu.assert_codes_close(Wq_h, ref["Wq"], "Wq")
+    gu.assert_scales_close(sx.cpu().numpy(), ref["sx"], "s_x")
+    gu.assert_scales_close(sw_h, ref["sw"], "s_w")
     worst = gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], "Y (oracle end to end)",
-                              (Xq_h != ref["Xq"]).any(axis=1), (Wq_h != ref["Wq"]).any(axis=0))
+                              *gu.narrow_code_masks(8, wbits, Xq_h, ref["Xq"], Wq_h, ref["Wq"]))
     # without the debug output the result is the same
     Y2, _ = gu.gpu_qgemm(w, Xq, sx, bias, N, debug=False, ldy=ldy)
     assert torch.equal(Y2, Y)
@@ -350,8 +354,10 @@ def test_layer_time_step_groups(oracle, wbits, fused):
     X = gu.bf16_to_dev(Xb)
     Xq_ws = torch.empty((M, K), dtype=torch.int8, device="cuda")
     sx_ws = torch.empty((M,), dtype=torch.float32, device="cuda")
+    want_map = oracle.table_default(20, 5)             # the oracle's step -> group map, not the product's
+    assert [table.lookup(s) for s in range(20)] == [int(v) for v in want_map]
     for step in (0, 3, 9, 19):
-        g = table.lookup(step)
+        g = int(want_map[step])
         Y = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
         layer.forward(step, X, Y, bias=gu.f32_to_dev(bias), fused=fused, Xq_ws=Xq_ws, sx_ws=sx_ws)
         torch.cuda.synchronize()
@@ -400,8 +406,9 @@ def test_graph_replay_matches_host_launches(oracle):
             assert torch.equal(got[0], Xq) and torch.equal(got[1], sx) and torch.equal(got[2], Y)
     ref = oracle.linear(inputs[-1][0], W, d, bias, wbits=8, exact_blas=True)
     Wq_h, _ = w.export()
-    gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], "Y (graph replay, oracle end to end)",
-                      (Xq.cpu().numpy() != ref["Xq"]).any(axis=1), (Wq_h != ref["Wq"]).any(axis=0))
+    gu.assert_codes_close(Xq.cpu().numpy(), ref["Xq"], "Xq (graph replay)")
+    gu.assert_codes_close(Wq_h, ref["Wq"], "Wq (graph replay)")
+    gu.assert_y_close(gu.bf16_to_host(Y), ref["Y"], "Y (graph replay, oracle end to end)")
     w.close()
 
 
@@ -461,8 +468,8 @@ def test_shared_handles_on_two_streams(oracle):
     for i in range(2):
         assert torch.equal(bufs[i][2], ref_out[i]), f"stream {i}"
     ref = oracle.linear(cases[1][0], W, d, bias, wbits=8, exact_blas=True)
-    gu.assert_y_close(gu.bf16_to_host(bufs[1][2]), ref["Y"], "Y (second stream)",
-                      (bufs[1][0].cpu().numpy() != ref["Xq"]).any(axis=1), (w.export()[0] != ref["Wq"]).any(axis=0))
+    gu.assert_codes_close(bufs[1][0].cpu().numpy(), ref["Xq"], "Xq (second stream)")
+    gu.assert_y_close(gu.bf16_to_host(bufs[1][2]), ref["Y"], "Y (second stream)")
     w.close()
 
 

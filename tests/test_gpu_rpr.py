@@ -10,7 +10,7 @@ import pytest
 import torch
 
 from paper_2503_06564_amd import trdq, workloads as wl
-from gpu_util import (assert_codes_close, assert_scales_close, assert_y_close, bf16_to_dev, bf16_to_host,
+from gpu_util import (assert_codes_close, assert_scales_close, assert_y_close, assert_y_same_codes, narrow_code_masks, bf16_to_dev, bf16_to_host,
                       dev, f32_to_dev, gpu_qgemm)
 
 pytestmark = pytest.mark.gpu
@@ -105,9 +105,9 @@ def test_linear_rpr_end_to_end(oracle, M, K, N, wbits):
     acc_o = oracle.acc_exact_blas(Xq.cpu().numpy(), codes, group)
     assert np.array_equal(acc.cpu().numpy(), acc_o), "int32 sums differ on the GPU's own codes"
     ref = oracle.linear_rpr(Xb, W, d, perm, bias, 128, wbits, exact_blas=True)
-    rows = np.any(Xq.cpu().numpy() != ref["Xq"], axis=1)
-    cols = np.any(codes != ref["Wq"], axis=0)
-    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (R P R)", skip_rows=rows, skip_cols=cols)
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (R P R)", *narrow_code_masks(8, wbits, None, None, codes, ref["Wq"]))
+    y_same = oracle.dequant(acc_o, sx.cpu().numpy(), scales, bias)
+    assert_y_same_codes(bf16_to_host(Y), y_same, "Y (R P R, same codes)")
     # the product is unchanged by the transform (Eq. 9): close to the unquantised X W + bias
     exact = oracle.bf16_to_f64(Xb) @ W.astype(np.float64) + bias.astype(np.float64)
     got = oracle.bf16_to_f64(bf16_to_host(Y))
@@ -186,9 +186,9 @@ def test_calibrate_then_run_the_full_path(oracle):
     Y, _ = gpu_qgemm(w, Xq, sx, bias, N, debug=False)
     ref = oracle.linear_rpr(Xb, W, d, perm, bias, 128, 8, exact_blas=True)
     codes, _ = w.export()
-    rows = np.any(Xq.cpu().numpy() != ref["Xq"], axis=1)
-    cols = np.any(codes != ref["Wq"], axis=0)
-    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (calibrated R P R)", skip_rows=rows, skip_cols=cols)
+    assert_codes_close(Xq.cpu().numpy(), ref["Xq"], "Xq (calibrated R P R)")
+    assert_codes_close(codes, ref["Wq"], "Wq (calibrated R P R)")
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (calibrated R P R)")
     exact = oracle.bf16_to_f64(Xb) @ W.astype(np.float64) + bias.astype(np.float64)
     got = oracle.bf16_to_f64(bf16_to_host(Y))
     assert np.linalg.norm(got - exact) / np.linalg.norm(exact) < 0.03

@@ -377,7 +377,7 @@ def test_table_default_partition(oracle, n_steps, n_groups):
     assert np.all(np.diff(m) >= 0) and np.all(np.diff(m) <= 1)       # monotone, contiguous
     sizes = np.bincount(m, minlength=n_groups)
     assert sizes.max() - sizes.min() <= 1
-    assert [wl.step_to_group(type("C", (), dict(n_steps=n_steps, n_groups=n_groups)), s)
+    assert [wl.draw_group(type("C", (), dict(n_steps=n_steps, n_groups=n_groups)), s)
             for s in range(n_steps)] == m.tolist()
 
 
