@@ -303,7 +303,8 @@ trdq_status trdq_share_plan(const float *sim_host, int n_steps, int n_blocks, fl
  * K / block blocks back and forth (blocks 0..nb-1, then nb-1..0, ...); round r fills slot r of
  * every block; equal magnitudes keep their channel order.  Host arrays: chan_mag_host[K] (for
  * example the per-channel absmax of calibration activations after the first rotation),
- * perm_host[K] (written).  Errors: NULL -> ERR_NULL; K <= 0, block <= 0, K % block -> ERR_SHAPE. */
+ * perm_host[K] (written).  Errors: NULL -> ERR_NULL; K <= 0, block <= 0, K % block -> ERR_SHAPE;
+ * a magnitude that is NaN or infinite -> ERR_RANGE. */
 trdq_status trdq_zigzag_permutation(const float *chan_mag_host, int K, int block, int32_t *perm_host);
 
 /* trdq_prepare_weights with the permutation and the second rotation.  perm_dev: int32 [K] on the
@@ -340,7 +341,9 @@ trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float 
  * trdq_qgemm up to the rounding order of the fp32 rotation (an activation code may differ by
  * one LSB on a rare element, within the same tolerance).  K is taken from the handle.
  * Errors as the two calls above; K beyond the fused kernel's on-chip panel
- * (K > 6144) -> ERR_UNSUPPORTED. */
+ * (K > 6144) -> ERR_UNSUPPORTED; weights that were folded with another transform than the
+ * one block rotation this kernel applies (trdq_prepare_weights_rpr, _dense, _dense_rpr)
+ * -> ERR_MISMATCH. */
 trdq_status trdq_linear_fused(const void *X_dev, int64_t M, int64_t ldx, const float *diag_dev,
                               const trdq_weights *w, const float *bias_dev,
                               void *Y_dev, int64_t ldy, void *stream);
@@ -374,7 +377,8 @@ void trdq_layer_destroy(trdq_layer *l);
 
 /* --------------------------------------------------------------- selection
  * Tile-shape override for trdq_qgemm, for tuning and tests: variant < 0 restores the
- * built-in choice.  Process-wide; not thread-safe against concurrent qgemm calls.
+ * built-in choice.  Process-wide (one atomic value: a concurrent trdq_qgemm sees the old or the
+ * new choice, and every choice computes the same result).
  * Unknown variant -> ERR_RANGE. */
 trdq_status trdq_qgemm_set_variant(int variant);
 int trdq_qgemm_num_variants(void);

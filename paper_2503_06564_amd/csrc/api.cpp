@@ -1,6 +1,8 @@
 // Host side of libtrdq: argument validation (always before the first HIP call), the
 // time-step table, weight handles, the per-layer convenience object, and the exports.
 #include <algorithm>
+#include <atomic>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <map>
@@ -31,6 +33,24 @@ hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes)
     return e;
 }
 
+int num_cus()
+{
+    static std::mutex mu;
+    static std::map<int, int> cus;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return 256; }
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cus.find(dev);
+    if (it != cus.end()) return it->second;
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+        (void)hipGetLastError();
+        n = 256;
+    }
+    cus[dev] = n;
+    return n;
+}
+
 }  // namespace trdq
 
 struct trdq_table : Table {};
@@ -47,7 +67,7 @@ struct trdq_layer {
 
 namespace {
 
-int g_variant = -1;
+std::atomic<int> g_variant{-1};   // test hook (trdq_qgemm_set_variant); -1 = the built-in choice
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -168,6 +188,7 @@ trdq_status prepare_weights_impl(const float *W_dev, int K, int N, const float *
     trdq_weights *w = new (std::nothrow) trdq_weights;
     if (!w) return TRDQ_ERR_ALLOC;
     w->K = K; w->N = N; w->wbits = wbits; w->qbits = qbits;
+    w->rotation = rot ? (rot2 ? trdq::kRotDenseRPR : trdq::kRotDense) : (perm_dev ? trdq::kRotHadamardRPR : trdq::kRotHadamard);
     float *Wrot = nullptr, *Wrot2 = nullptr, *amax = nullptr;
     const size_t code_bytes = wbits == 8 ? (size_t)K * N : (size_t)K * N / 2;
     const size_t scale_count = wbits == 8 ? (size_t)N : (size_t)nb * N;
@@ -502,6 +523,8 @@ trdq_status trdq_zigzag_permutation(const float *chan_mag_host, int K, int block
 {
     if (!chan_mag_host || !perm_host) return TRDQ_ERR_NULL;
     if (block <= 0 || K <= 0 || K % block != 0) return TRDQ_ERR_SHAPE;
+    for (int k = 0; k < K; ++k)
+        if (!std::isfinite(chan_mag_host[k])) return TRDQ_ERR_RANGE;   // NaN has no place in an order
     // channels by decreasing magnitude (equal magnitudes keep their order), dealt to the blocks
     // back and forth: round r fills slot r of every block, left to right on even rounds
     std::vector<int32_t> order((size_t)K);
@@ -716,7 +739,7 @@ trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float 
     if (M == 0) return TRDQ_OK;
     if (trdq_status rd = check_device(w->device); rd != TRDQ_OK) return rd;
     return hip_status(trdq::launch_qgemm(*w, Xq_dev, sx_dev, nullptr, M, bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
-                                         acc_debug_dev, g_variant, static_cast<hipStream_t>(stream)));
+                                         acc_debug_dev, g_variant.load(std::memory_order_relaxed), static_cast<hipStream_t>(stream)));
 }
 
 trdq_status trdq_qgemm_asym(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev,
@@ -747,6 +770,7 @@ trdq_status trdq_linear_fused(const void *X_dev, int64_t M, int64_t ldx, const f
     if (rc != TRDQ_OK) return rc;
     if (diag_dev && !aligned(diag_dev, 16)) return TRDQ_ERR_SHAPE;
     if (!trdq::fused_supports(w->K)) return TRDQ_ERR_UNSUPPORTED;
+    if (w->rotation != trdq::kRotHadamard) return TRDQ_ERR_MISMATCH;   // the kernel applies the one-rotation transform
     if (M == 0) return TRDQ_OK;
     if (trdq_status rd = check_device(w->device); rd != TRDQ_OK) return rd;
     return hip_status(trdq::launch_linear_fused(*w, static_cast<const uint16_t *>(X_dev), M, ldx, diag_dev,
@@ -854,7 +878,7 @@ void trdq_layer_destroy(trdq_layer *l)
 trdq_status trdq_qgemm_set_variant(int variant)
 {
     if (variant >= trdq::qgemm_num_variants()) return TRDQ_ERR_RANGE;
-    g_variant = variant < 0 ? -1 : variant;
+    g_variant.store(variant < 0 ? -1 : variant, std::memory_order_relaxed);
     return TRDQ_OK;
 }
 

@@ -429,8 +429,8 @@ hipError_t launch_one(const FusedArgs &a, hipStream_t st)
     FusedArgs g = a;
     const int64_t panels = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + kBN - 1) / kBN;
-    // enough workgroups to fill 256 compute units twice; every extra split repeats the prologue
-    int64_t want = (512 + panels - 1) / panels;
+    // enough workgroups to fill the compute units twice; every extra split repeats the prologue
+    int64_t want = (2 * num_cus() + panels - 1) / panels;
     want = want < 1 ? 1 : (want > g.tiles_n ? g.tiles_n : want);
     const int tiles_per = (int)((g.tiles_n + want - 1) / want);
     g.nsplit = (g.tiles_n + tiles_per - 1) / tiles_per;   // no workgroup without a channel tile
@@ -469,7 +469,7 @@ bool fused_pays(int64_t M, int K, int N, int wbits)
 {
     if (wbits != 8 || K > 1536 || K % kBlock != 0 || M <= 0) return false;
     const int bn = N % 144 == 0 ? 144 : 128;
-    return ((M + 15) / 16) * ((N + bn - 1) / bn) <= 256;
+    return ((M + 15) / 16) * ((N + bn - 1) / bn) <= num_cus();
 }
 
 hipError_t launch_linear_fused(const Weights &w, const uint16_t *X, int64_t M, int64_t ldx,

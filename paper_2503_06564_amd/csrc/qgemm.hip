@@ -288,7 +288,7 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, con
         int kind = 0;
         if (a.N % 144 == 0 && M % 128 == 0 && a.K >= 512 && ldy % 8 == 0 && reinterpret_cast<uintptr_t>(Y) % 16 == 0) {
             const int64_t tiles144 = (M / 128) * (a.N / 144);
-            kind = tiles144 > 256 ? 15 : (a.K >= 2304 ? 18 : 14);
+            kind = tiles144 > num_cus() ? 15 : (a.K >= 2304 ? 18 : 14);
         }
         if (variant >= 0) kind = variant;     // tests: 0, 14, 15 or 18
         return launch_qgemm8_asym(a, dbg, kind, st);
@@ -318,7 +318,7 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, con
         variant = kRegVariants + 9;
         const int64_t tiles144 = (a.N % 144 == 0 && M % 128 == 0 && a.K >= 512) ? (M / 128) * (a.N / 144) : 0;
         const int64_t tiles256 = ((M + 255) / 256) * ((a.N + 255) / 256);
-        if (tiles144 > 0 && tiles144 <= 256)
+        if (tiles144 > 0 && tiles144 <= num_cus())
             variant = a.K >= 2304 ? kRegVariants + 18 : kRegVariants + 14;
         else if (tiles256 >= 400 && wide_supports(a))
             variant = kRegVariants + dma_num_variants();

@@ -1130,7 +1130,7 @@ hipError_t launch_persist(const GemmArgs &a, bool debug, hipStream_t st)
     auto kern = debug ? qgemm8_persist_kernel<BM, BN, NS, WGM, WGN, true>
                       : qgemm8_persist_kernel<BM, BN, NS, WGM, WGN, false>;
     if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
-    int grid = 256 * WGS_PER_CU;
+    int grid = num_cus() * WGS_PER_CU;
     if (grid > g.tiles_m * g.tiles_n) grid = g.tiles_m * g.tiles_n;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), smem, st, g);
     return hipGetLastError();

@@ -419,7 +419,7 @@ hipError_t launch_wide(const GemmArgs &a, hipStream_t st)
     g.tiles_n = (g.N + kWideBN - 1) / kWideBN;
     auto kern = qgemm8_wide_kernel<DEBUG, FULL>;
     if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), kWideLds); e != hipSuccess) return e;
-    int grid = 256;
+    int grid = num_cus();
     if (grid > g.tiles_m * g.tiles_n) grid = g.tiles_m * g.tiles_n;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kWideLds, st, g);
     return hipGetLastError();

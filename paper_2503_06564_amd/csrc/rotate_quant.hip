@@ -326,7 +326,7 @@ hipError_t launch_spw(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx,
     const float sx_mul = 0.08838834764831845f / qmax;
     // persistent workgroups: a few per compute unit, each walking token groups
     const int64_t groups = (M + kTokensPerWG - 1) / kTokensPerWG;
-    int64_t grid = (int64_t)256 * wgs_per_cu;
+    int64_t grid = (int64_t)num_cus() * wgs_per_cu;
     if (grid > groups) grid = groups;
     const size_t smem = diag_table_bytes(nb) + sizeof(float) * (size_t)2 * nw * (zc ? 32 : 16) + 1024;   // table, extrema, dump area
     const int64_t warm_chunks = (warm && warm_bytes < ((int64_t)1 << 32)) ? warm_bytes / 16 : 0;   // 32-bit byte offsets in the copy
@@ -361,7 +361,7 @@ hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx,
     // few token groups (fewer than six waves per compute unit): spread each row over more waves
     // instead, so that the loads in flight still cover the memory latency
     const int64_t groups = (M + kTokensPerWG - 1) / kTokensPerWG;
-    while (spw > 1 && groups * ((nb + spw - 1) / spw) < 256 * 6 && (nb + spw - 2) / (spw - 1) <= 12) --spw;
+    while (spw > 1 && groups * ((nb + spw - 1) / spw) < (int64_t)num_cus() * 6 && (nb + spw - 2) / (spw - 1) <= 12) --spw;
     const int nw = (nb + spw - 1) / spw;
     spw = (nb + nw - 1) / nw;
     const int resident = spw == 3 ? 8 : 12;

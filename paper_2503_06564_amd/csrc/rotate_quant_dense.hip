@@ -322,7 +322,7 @@ hipError_t launch_dense_blocks(const uint16_t *X, int64_t M, int nb, int64_t ldx
                                int8_t *Xq, float *sx, hipStream_t st)
 {
     const int64_t groups = (M + 16 * TT - 1) / (16 * TT);
-    int64_t chunks = 256 / nb;                  // rounded down: a 257th workgroup would wait for a second round
+    int64_t chunks = num_cus() / nb;            // rounded down: one workgroup more than compute units would wait for a second round
     const int64_t most = (groups + 7) / 8;
     if (chunks > most) chunks = most;
     if (chunks < 1) chunks = 1;
@@ -599,7 +599,7 @@ hipError_t launch_dense(const uint16_t *X, int64_t M, int nb, int nw, int64_t ld
                         int8_t *Xq, float *sx, hipStream_t st)
 {
     const int64_t groups = (M + 16 * TT - 1) / (16 * TT);
-    const int64_t grid = groups < 256 ? groups : 256;      // persistent: one workgroup per compute unit
+    const int64_t grid = groups < num_cus() ? groups : num_cus();      // persistent: one workgroup per compute unit
     const size_t smem = sizeof(float) * 2 * nw * 16 * TT;
     hipLaunchKernelGGL((rotate_quant_dense_kernel<TT>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
                        X, M, nb, ldx, pieces, Xq, sx);
@@ -651,7 +651,7 @@ hipError_t launch_rotate_quant_dense_rpr(const uint16_t *X, int64_t M, int K, in
     if (nb > 12) {
         // wide rows: 8 tokens per workgroup of 12 waves
         const int64_t groups8 = (M + 7) / 8;
-        const int64_t grid8 = groups8 < 256 ? groups8 : 256;
+        const int64_t grid8 = groups8 < num_cus() ? groups8 : num_cus();
         const size_t smem8 = sizeof(float) * ((size_t)8 * (K + 4) + 2 * 12 * 16);
         if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(rotate_quant_dense_rpr_wide_kernel), smem8);
             e != hipSuccess)
@@ -661,7 +661,7 @@ hipError_t launch_rotate_quant_dense_rpr(const uint16_t *X, int64_t M, int K, in
         return hipGetLastError();
     }
     const int64_t groups = (M + 15) / 16;
-    const int64_t grid = groups < 256 ? groups : 256;
+    const int64_t grid = groups < num_cus() ? groups : num_cus();
     const size_t smem = sizeof(float) * ((size_t)16 * (K + 4) + 2 * nb * 16) + sizeof(int) * (size_t)K;
     if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(rotate_quant_dense_rpr_kernel), smem);
         e != hipSuccess)

@@ -10,6 +10,9 @@ namespace trdq {
 
 constexpr int kBlock = TRDQ_BLOCK;  // rotation block = int4 scale group
 
+// The transform folded into a weight set; the fused kernel and the layer object apply kRotHadamard only.
+enum { kRotHadamard = 0, kRotHadamardRPR = 1, kRotDense = 2, kRotDenseRPR = 3 };
+
 // Device-side weight set of one time-step group (H_t(W) of Eq. 10, quantised).
 //   wbits 8: codes = int8  [N, K]   (K contiguous: the transposed canonical matrix)
 //   wbits 4: codes = uint8 [N, K/2]; every 4 bytes hold 8 consecutive k of one output
@@ -22,6 +25,7 @@ struct Weights {
     int qbits = 0;               // width of the codes: 8, 6 (in the 8-bit layout) or 4
     void *codes = nullptr;
     float *scales = nullptr;
+    int rotation = 0;            // which transform was folded in (kRot*): the activation side must apply the same one
     int32_t *colsum = nullptr;   // int8 weights: sum over k of the codes of every output channel [N]
     float *colsumw = nullptr;    // int4 weights: 16 * sum_g s_w[g][n] * (sum of the codes of group g) [N]
     int device = 0;
@@ -88,6 +92,8 @@ hipError_t launch_cosine_similarity(const uint16_t *A, const uint16_t *B, int n_
 // belongs to the (kernel, device) pair; what has been set is remembered per pair, so the HIP call
 // happens once for each and callers may ask before every launch (thread-safe).
 hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes);
+// Compute units of the current device (read once per device; 256 if the query fails).
+int num_cus();
 
 // yardstick kernels (peaks.hip)
 int peak_mfma_independent();

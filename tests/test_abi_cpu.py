@@ -157,6 +157,9 @@ def test_zigzag_argument_errors():
     assert L.trdq_zigzag_permutation(mag.ctypes.data, 200, 128, perm.ctypes.data) == trdq.ERR_SHAPE
     assert L.trdq_zigzag_permutation(mag.ctypes.data, 0, 128, perm.ctypes.data) == trdq.ERR_SHAPE
     assert L.trdq_zigzag_permutation(mag.ctypes.data, 256, 0, perm.ctypes.data) == trdq.ERR_SHAPE
+    for bad in (np.nan, np.inf, -np.inf):              # a magnitude that cannot be ordered
+        m2 = mag.copy(); m2[17] = bad
+        assert L.trdq_zigzag_permutation(m2.ctypes.data, 256, 128, perm.ctypes.data) == trdq.ERR_RANGE
 
 
 def test_rpr_argument_errors_before_any_gpu_call():

@@ -192,3 +192,17 @@ def test_calibrate_then_run_the_full_path(oracle):
     exact = oracle.bf16_to_f64(Xb) @ W.astype(np.float64) + bias.astype(np.float64)
     got = oracle.bf16_to_f64(bf16_to_host(Y))
     assert np.linalg.norm(got - exact) / np.linalg.norm(exact) < 0.03
+
+
+def test_fused_refuses_weights_folded_with_another_transform(oracle):
+    """The fused kernel applies the one-rotation transform: weights folded with R P R (or dense blocks)
+    are refused instead of multiplied with the wrong activations."""
+    M, K, N = 32, 256, 144
+    Xb, W, d, bias = wl.small_case(29, M, K, N)
+    perm_d = torch.from_numpy(oracle.zigzag(np.arange(K, dtype=np.float64), 128).astype(np.int32)).to(dev())
+    w = trdq.prepare_weights_rpr(f32_to_dev(W), f32_to_dev(d), perm_d, wbits=8)
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device=dev())
+    with pytest.raises(trdq.TrdqError) as e:
+        trdq.linear_fused(bf16_to_dev(Xb), f32_to_dev(d), w, Y)
+    assert e.value.status == trdq.ERR_MISMATCH
+    w.close()
