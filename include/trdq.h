@@ -282,6 +282,20 @@ trdq_status trdq_cosine_similarity(const void *A_dev, const void *B_dev, int n_s
                                    int64_t stride_a, int64_t stride_b, double *acc_ws_dev, float *cos_dev,
                                    void *stream);
 
+/* The same call for callers that cannot allocate device memory or bring a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the accumulators live
+ * in a fixed array inside the library, 3 float64 per segment for at most TRDQ_COSINE_STATIC_MAX_SEG
+ * segments (96 KB, held by every GPU the library runs on until the process ends).  The call
+ * allocates nothing, clears the accumulators it uses with a fill kernel (no memset: it may be
+ * captured) and is asynchronous on `stream`.  All calls on one GPU share the array: two such calls
+ * that overlap in time on one GPU (different streams, or different threads) race; callers order
+ * them.  Arguments, result and accuracy as trdq_cosine_similarity.
+ * Errors: NULL -> ERR_NULL; sizes, strides, alignment -> ERR_SHAPE; n_seg beyond the maximum ->
+ * ERR_RANGE (before any device work). */
+#define TRDQ_COSINE_STATIC_MAX_SEG 4096
+trdq_status trdq_cosine_similarity_static(const void *A_dev, const void *B_dev, int n_seg, int64_t seg_len,
+                                          int64_t stride_a, int64_t stride_b, float *cos_dev, void *stream);
+
 /* Which transformer blocks share attention between the two passes: the blocks whose similarity is
  * at least `threshold` at EVERY time step (Sec. 3.3 shares the blocks that are similar across all
  * time steps).  Host arrays: sim_host float32 [n_steps, n_blocks] of Eq. 11 values, share_host

@@ -485,6 +485,21 @@ trdq_status trdq_cosine_similarity(const void *A_dev, const void *B_dev, int n_s
                                                      stride_b, acc_ws_dev, cos_dev, static_cast<hipStream_t>(stream)));
 }
 
+trdq_status trdq_cosine_similarity_static(const void *A_dev, const void *B_dev, int n_seg, int64_t seg_len,
+                                          int64_t stride_a, int64_t stride_b, float *cos_dev, void *stream)
+{
+    if (!A_dev || !B_dev || !cos_dev) return TRDQ_ERR_NULL;
+    if (n_seg <= 0 || seg_len <= 0 || stride_a < seg_len || stride_b < seg_len) return TRDQ_ERR_SHAPE;
+    if (n_seg > trdq::kCosineStaticMaxSeg) return TRDQ_ERR_RANGE;      // beyond the fixed accumulator array
+    if (!aligned(A_dev, 16) || !aligned(B_dev, 16) || !aligned(cos_dev, 4)) return TRDQ_ERR_SHAPE;
+    if (n_seg > 1 && (stride_a % 8 != 0 || stride_b % 8 != 0)) return TRDQ_ERR_SHAPE;
+    double *acc = nullptr;
+    if (trdq::cosine_static_scratch(&acc) != hipSuccess) { (void)hipGetLastError(); return TRDQ_ERR_HIP; }
+    return hip_status(trdq::launch_cosine_similarity(static_cast<const uint16_t *>(A_dev),
+                                                     static_cast<const uint16_t *>(B_dev), n_seg, seg_len, stride_a,
+                                                     stride_b, acc, cos_dev, static_cast<hipStream_t>(stream)));
+}
+
 trdq_status trdq_peak_mfma_i8(int32_t *sink_dev, int workgroups, int waves, int iters, int64_t *ops_host,
                               void *stream)
 {

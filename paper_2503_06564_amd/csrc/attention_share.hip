@@ -8,6 +8,9 @@
 // cosine.  The order of the atomic adds varies from run to run; in fp64 that moves the result
 // by parts in 10^16.
 #include "device_utils.h"
+#include <map>
+#include <mutex>
+
 #include "trdq_internal.h"
 
 namespace trdq {
@@ -81,7 +84,32 @@ __global__ void cosine_finish_kernel(const double *__restrict__ acc, int n_seg, 
     out[s] = (na > 0.0 && nb > 0.0) ? (float)(d / (sqrt(na) * sqrt(nb))) : 0.0f;
 }
 
+// Accumulators of the entry point that allocates nothing: three float64 sums per segment, held by
+// every GPU the library runs on until the process ends (96 KB).  Host code never passes this name to
+// a kernel or a runtime call: it asks for the device's address of the array once per device
+// (static_scratch below) and uses that pointer.
+__device__ __align__(256) double scratch[3 * kCosineStaticMaxSeg];
+
 }  // namespace
+
+hipError_t cosine_static_scratch(double **out)
+{
+    static std::mutex mu;
+    static std::map<int, double *> per_device;      // each GPU holds its own copy at its own address
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = per_device.find(dev);
+    if (it == per_device.end()) {
+        double *ptr = nullptr;
+        if (hipError_t e = hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch)); e != hipSuccess)
+            return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        it = per_device.emplace(dev, ptr).first;
+    }
+    *out = it->second;
+    return hipSuccess;
+}
 
 hipError_t launch_cosine_similarity(const uint16_t *A, const uint16_t *B, int n_seg, int64_t seg_len,
                                     int64_t stride_a, int64_t stride_b, double *acc_ws, float *out, hipStream_t st)

@@ -88,6 +88,10 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, con
 
 hipError_t launch_cosine_similarity(const uint16_t *A, const uint16_t *B, int n_seg, int64_t seg_len,
                                     int64_t stride_a, int64_t stride_b, double *acc_ws, float *out, hipStream_t st);
+// Most segments the entry point without a workspace argument takes, and the current device's address of its
+// file-scope accumulator array (looked up once per device, with that device current; thread-safe).
+constexpr int kCosineStaticMaxSeg = TRDQ_COSINE_STATIC_MAX_SEG;
+hipError_t cosine_static_scratch(double **out);
 // Raises a kernel's dynamic-LDS limit to at least `bytes` on the current device.  The attribute
 // belongs to the (kernel, device) pair; what has been set is remembered per pair, so the HIP call
 // happens once for each and callers may ask before every launch (thread-safe).

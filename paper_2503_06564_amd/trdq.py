@@ -24,7 +24,7 @@ SYMBOLS = [
     "trdq_zigzag_permutation", "trdq_prepare_weights_rpr", "trdq_rotate_quant_rpr",
     "trdq_channel_absmax", "trdq_weight_row_absmax", "trdq_smooth_diag",
     "trdq_rotate_quant_asym", "trdq_qgemm_asym", "trdq_rotate_quant_bits",
-    "trdq_cosine_similarity", "trdq_share_plan",
+    "trdq_cosine_similarity", "trdq_cosine_similarity_static", "trdq_share_plan",
     "trdq_rotation_create", "trdq_rotation_destroy", "trdq_prepare_weights_dense", "trdq_rotate_quant_dense",
     "trdq_greedy_rotation", "trdq_prepare_weights_dense_rpr", "trdq_rotate_quant_dense_rpr",
     "trdq_channel_absmax_dense", "trdq_greedy_rotation_second",
@@ -80,6 +80,7 @@ def lib():
         L.trdq_rotate_quant_asym.argtypes = [p, i64, i32, i64, p, i32, p, p, p, p, p]
         L.trdq_rotate_quant_bits.argtypes = [p, i64, i32, i64, p, i32, i32, p, p, p, p]
         L.trdq_cosine_similarity.argtypes = [p, p, i32, i64, i64, i64, p, p, p]
+        L.trdq_cosine_similarity_static.argtypes = [p, p, i32, i64, i64, i64, p, p]
         L.trdq_share_plan.argtypes = [p, i32, i32, C.c_float, p]
         L.trdq_peak_mfma_i8.argtypes = [p, i32, i32, i32, C.POINTER(C.c_int64), p]
         L.trdq_peak_stream.argtypes = [p, p, i64, p]
@@ -383,6 +384,19 @@ def cosine_similarity(A, B, acc_ws, out, stream=None):
     sb = B.stride(0) if n_seg > 1 else max(L, B.stride(0))
     _check(lib().trdq_cosine_similarity(_ptr(A), _ptr(B), n_seg, L, sa, sb, _ptr(acc_ws), _ptr(out), _stream(stream)),
            "trdq_cosine_similarity")
+
+
+COSINE_STATIC_MAX_SEG = 4096
+
+
+def cosine_similarity_static(A, B, out, stream=None):
+    """cosine_similarity without a workspace: the accumulators are a fixed array inside the library
+    (at most COSINE_STATIC_MAX_SEG segments; calls that overlap on one GPU race)."""
+    n_seg, L = A.shape
+    sa = A.stride(0) if n_seg > 1 else max(L, A.stride(0))
+    sb = B.stride(0) if n_seg > 1 else max(L, B.stride(0))
+    _check(lib().trdq_cosine_similarity_static(_ptr(A), _ptr(B), n_seg, L, sa, sb, _ptr(out), _stream(stream)),
+           "trdq_cosine_similarity_static")
 
 
 def peak_mfma_i8(sink, workgroups, waves, iters, stream=None):

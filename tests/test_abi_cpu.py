@@ -218,6 +218,13 @@ def test_attention_share_host_side(oracle):
     assert L.trdq_cosine_similarity(0x1000, 0x2000, 2, 64, 60, 64, 0x3000, 0x4000, None) == trdq.ERR_SHAPE
     assert L.trdq_cosine_similarity(0x1000, 0x2000, 2, 60, 68, 64, 0x3000, 0x4000, None) == trdq.ERR_SHAPE
     assert L.trdq_cosine_similarity(0x1008, 0x2000, 1, 64, 64, 64, 0x3000, 0x4000, None) == trdq.ERR_SHAPE
+    # the variant that allocates nothing: the same checks, and its fixed maximum, before any device work
+    assert L.trdq_cosine_similarity_static(None, 0x1000, 1, 64, 64, 64, 0x3000, None) == trdq.ERR_NULL
+    assert L.trdq_cosine_similarity_static(0x1000, 0x2000, 0, 64, 64, 64, 0x4000, None) == trdq.ERR_SHAPE
+    assert L.trdq_cosine_similarity_static(0x1000, 0x2000, 2, 64, 60, 64, 0x4000, None) == trdq.ERR_SHAPE
+    assert L.trdq_cosine_similarity_static(0x1008, 0x2000, 1, 64, 64, 64, 0x4000, None) == trdq.ERR_SHAPE
+    assert L.trdq_cosine_similarity_static(0x1000, 0x2000, trdq.COSINE_STATIC_MAX_SEG + 1, 64, 64, 64, 0x4000,
+                                           None) == trdq.ERR_RANGE
     rng = np.random.default_rng(3)
     sim = rng.uniform(0.8, 1.0, (20, 28)).astype(np.float32)
     sim[:, 0] = 0.99; sim[:, 27] = 0.97; sim[7, 5] = np.nan
