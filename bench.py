@@ -34,8 +34,12 @@ def parse():
     ap.add_argument("--config", type=int, default=1, help="workload config id (1 = the metric's)")
     ap.add_argument("--fused", action="store_true", help="use the fused kernel instead of rotate_quant + qgemm")
     ap.add_argument("--no-events", action="store_true", help="no per-kernel events in the timed region")
-    ap.add_argument("--event-every", type=int, default=8,
-                    help="bracket the kernels with events on every n-th timed step (keeps the probe effect small)")
+    ap.add_argument("--event-every", type=int, default=0,
+                    help="bracket the kernels with events on every n-th timed step (keeps the probe effect small); "
+                         "0 = max(1, steps // 10), so that at least ten launches stand behind every kernel figure")
+    ap.add_argument("--no-tiled", action="store_true",
+                    help="row-major activation codes for every linear (trdq_rotate_quant + trdq_qgemm), also where "
+                         "the library prefers the block-tiled pair")
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per step instead of launching every kernel from the host "
                          "(same kernels; measured to make no difference here: the step is GPU-bound, and the "
@@ -198,6 +202,7 @@ def main():
 
     # one pre-marshalled C call per launch (the binding converts the arguments once)
     calls = {}
+    tiled_kinds = set()
     for g in range(n_groups):
         for kind in cfg.kinds:
             if args.fused:
@@ -215,13 +220,22 @@ def main():
                                                              warm=None if args.no_warm else Wh[kind, g]),
                                   trdq.bind_qgemm(Wh[kind, g], Xq[kind], SX[kind], Y[kind], bias=B[kind],
                                                   stream=stream))
+            elif not args.no_tiled and args.variant < 0 and trdq.qgemm_tiled_preferred(Wh[kind, g], M):
+                # the shapes for which the library itself (trdq_layer_forward) takes the block-tiled pair;
+                # Xq[kind] holds M * K bytes in either form (M is a multiple of 128 here)
+                tiled_kinds.add(kind)
+                calls[g, kind] = (trdq.bind_rotate_quant_tiled(X[kind, g], D[kind, g], Xq[kind], SX[kind],
+                                                               stream=stream,
+                                                               warm=None if args.no_warm else Wh[kind, g]),
+                                  trdq.bind_qgemm_tiled(Wh[kind, g], Xq[kind], SX[kind], Y[kind], bias=B[kind],
+                                                        stream=stream))
             else:
                 calls[g, kind] = (trdq.bind_rotate_quant(X[kind, g], D[kind, g], Xq[kind], SX[kind], stream=stream,
                                                          warm=None if args.no_warm else Wh[kind, g]),
                                   trdq.bind_qgemm(Wh[kind, g], Xq[kind], SX[kind], Y[kind], bias=B[kind],
                                                   stream=stream))
     n_ev = len(cfg.kinds) * (2 if args.fused else 3)
-    every = max(1, args.event_every)
+    every = args.event_every if args.event_every > 0 else max(1, args.steps // 10)
     events = {st: [HipEvent() for _ in range(n_ev)]
               for st in range(0, args.steps, every)} if use_events else {}
     ev = []     # (name, kind, start, end)
@@ -301,6 +315,7 @@ def main():
         "tokens_per_s": M * args.steps / dt,
         "config": {"workload": cfg.name, "tokens": M, "layers": list(cfg.kinds), "groups": n_groups,
                    "path": "fused" if args.fused else ("rotate_quant_rpr+qgemm" if args.rpr else ("rotate_quant_asym+qgemm_asym" if args.asym else "rotate_quant+qgemm")), "wbits": wbits,
+                   "block_tiled_codes": sorted(tiled_kinds),
                    "launch": "hip graph per step" if graphs else "host launches"},
     }
 
@@ -324,7 +339,7 @@ def main():
             per[name, kind] = ts = [max(t - ev_cost, 0.0) for t in ts]
         for (name, kind), ts in per.items():
             avg = sum(ts) / len(ts)
-            entry = {"avg_us": avg * 1e6, "launches": len(ts)}
+            entry = {"avg_us": avg * 1e6, "median_us": sorted(ts)[len(ts) // 2] * 1e6, "launches": len(ts)}
             if name in ("qgemm", "fused"):
                 entry["tops"] = gemm_ops[kind] / avg / 1e12
                 entry["frac_int8_peak"] = entry["tops"] / INT8_MFMA_PEAK_TOPS
@@ -355,7 +370,12 @@ def main():
                                             "traffic": None}
 
     if "roofline" in out:
+        # HBM bytes per launch are not measured by this run: they come from the committed counter summary
+        # of the same command (two rocprofv3 --pmc runs), or stay null when there is none
         out["roofline"]["traffic"] = committed_traffic(cfg.name)
+        out["roofline"]["traffic_source"] = (f"profiles/qgemm_hbm_traffic_{cfg.name}.txt (rocprofv3 --pmc FETCH_SIZE / "
+                                             "WRITE_SIZE of this command, committed; not measured in this run)"
+                                             if out["roofline"]["traffic"] is not None else None)
         if not args.no_measured_peaks:
             # after the timed region: the chip's own ceilings for the two bounding operations
             # (register-only int8 matrix issue; a pass of 2 bytes read + 1 written per element)

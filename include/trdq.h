@@ -113,7 +113,9 @@ trdq_status trdq_weights_export(const trdq_weights *w, int8_t *codes_host, float
  * (two's complement nibbles, even k in the low nibble).  wbits 8 -> ERR_MISMATCH. */
 trdq_status trdq_weights_export_packed(const trdq_weights *w, uint8_t *packed_host);
 
-/* Device bytes held by the handle (codes + scales). */
+/* Bytes of the weight format (codes + scales): K*N + 4N for wbits 8, K*N/2 + 4*(K/128)*N for wbits 4.
+ * An int8 set whose N is a multiple of 144 holds its codes a second time, block-tiled for
+ * trdq_qgemm_tiled (another K*N bytes of device memory, not part of this figure). */
 trdq_status trdq_weights_nbytes(const trdq_weights *w, int64_t *nbytes_out);
 
 void trdq_weights_destroy(trdq_weights *w);
@@ -349,6 +351,34 @@ trdq_status trdq_rotate_quant_rpr(const void *X_dev, int64_t M, int K, int64_t l
 trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev, int64_t M,
                        const float *bias_dev, void *Y_dev, int64_t ldy,
                        int32_t *acc_debug_dev, void *stream);
+
+/* ---- the same pair on block-tiled activation codes (Eq. 10's product; int8 weights) ----
+ * The codes of trdq_rotate_quant in 1 KB blocks of 16 tokens x 64 input channels: code (m, k) at
+ *   ((m / 16) * (K / 64) + k / 64) * 1024 + (m % 16) * 64 + k % 64,
+ * trdq_xq_tiled_nbytes(M, K) = ceil(M / 16) * 16 * K bytes (16-byte aligned; rows of a last,
+ * partial group of 16 are not written).  A block is one operand fragment of the int8 matrix
+ * instruction and one direct-to-LDS copy of eight whole cache lines, which lets the product run
+ * 256-token tiles with two workgroups per compute unit (see qgemm_tiled.hip).
+ * trdq_rotate_quant_tiled: arguments, values and errors of trdq_rotate_quant_warm; K <= 4608
+ *   (wider -> ERR_UNSUPPORTED).  Codes and scales are those of trdq_rotate_quant, bit for bit.
+ * trdq_xq_untile: Xq_dev [M, K] dense <- Xt_dev (for inspection and for the row-major calls).
+ * trdq_qgemm_tiled: arguments, values and errors of trdq_qgemm with Xt_dev in place of Xq_dev.
+ *   Takes the shapes for which trdq_qgemm_tiled_supported(w, M) is 1 -- int8 weights (wbits 8
+ *   or 6) with N % 144 == 0, M % 128 == 0 -- and an output with ldy % 8 == 0 on a 16-byte
+ *   aligned base; anything else -> ERR_UNSUPPORTED (use trdq_qgemm on row-major codes).
+ *   The integer sums are those of trdq_qgemm (exact), the epilogue is the same arithmetic. */
+int64_t trdq_xq_tiled_nbytes(int64_t M, int K);      /* -1 for M < 0, K <= 0 or K % 128 != 0 */
+trdq_status trdq_rotate_quant_tiled(const void *X_dev, int64_t M, int K, int64_t ldx,
+                                    const float *diag_dev, int block,
+                                    int8_t *Xt_dev, float *sx_dev, const trdq_weights *next, void *stream);
+trdq_status trdq_xq_untile(const int8_t *Xt_dev, int64_t M, int K, int8_t *Xq_dev, void *stream);
+int trdq_qgemm_tiled_supported(const trdq_weights *w, int64_t M);
+/* 1 where the tiled pair is also the faster one by the library's measured rule (more than one
+ * 128 x 144 output tile per compute unit, K <= 4608): what trdq_layer_forward takes by itself. */
+int trdq_qgemm_tiled_preferred(const trdq_weights *w, int64_t M);
+trdq_status trdq_qgemm_tiled(const trdq_weights *w, const int8_t *Xt_dev, const float *sx_dev, int64_t M,
+                             const float *bias_dev, void *Y_dev, int64_t ldy,
+                             int32_t *acc_debug_dev, void *stream);
 
 /* Fused variant: rotate -> quantise -> integer product -> epilogue in ONE kernel; the int8
  * activations never travel through HBM.  Same arithmetic as trdq_rotate_quant followed by

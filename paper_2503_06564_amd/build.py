@@ -10,7 +10,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtrdq.so")
 
-SOURCES = ["api.cpp", "rotate_quant.hip", "rotate_quant_wide.hip", "rotate_quant_rpr.hip", "calibrate.hip", "greedy_rotation.hip", "rotate_quant_dense.hip", "attention_share.hip", "prepare_weights.hip", "qgemm.hip", "qgemm_dma.hip", "qgemm_wide.hip", "fused.hip", "peaks.hip"]
+SOURCES = ["api.cpp", "rotate_quant.hip", "rotate_quant_wide.hip", "rotate_quant_rpr.hip", "calibrate.hip", "greedy_rotation.hip", "rotate_quant_dense.hip", "attention_share.hip", "prepare_weights.hip", "qgemm.hip", "qgemm_dma.hip", "qgemm_wide.hip", "qgemm_tiled.hip", "fused.hip", "peaks.hip"]
 
 # packed-FP32 instructions are switched off for every device compile
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
@@ -21,6 +21,7 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
 # per-source extra flags: keep the matrix-instruction accumulators of the pipelined product kernel
 # in ordinary VGPRs (no accumulator-register copies around the loop)
 SOURCE_FLAGS = {"qgemm_dma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+                "qgemm_tiled.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
                 # ... and have the first kernel arguments delivered in registers at wave launch instead
                 # of fetched by the kernel's first instructions (a fraction of a microsecond per launch)
                 "rotate_quant.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-mllvm", "-amdgpu-kernarg-preload-count=16"],

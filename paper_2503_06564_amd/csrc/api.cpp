@@ -224,6 +224,12 @@ trdq_status prepare_weights_impl(const float *W_dev, int K, int N, const float *
         ok = trdq::launch_prepare_quant(Wrot, amax, K, N, qbits, 0.08838834764831845f, w->codes, w->scales, st) == hipSuccess;
     }
     if (ok && wbits == 8) ok = trdq::launch_weight_colsum(w->codes, K, N, w->colsum, st) == hipSuccess;
+    // widths the block-tiled product takes (whole 144-channel tiles): a second copy of the codes in 1 KB blocks
+    if (ok && wbits == 8 && N % 144 == 0) {
+        if (hipMalloc(&w->codes_tiled, code_bytes) != hipSuccess) { rc = TRDQ_ERR_ALLOC; goto fail; }
+        ok = trdq::launch_retile_rows(static_cast<const int8_t *>(w->codes), static_cast<int8_t *>(w->codes_tiled), N, K,
+                                      true, st) == hipSuccess;
+    }
     if (ok && wbits == 4) ok = trdq::launch_weight_colsumw4(w->codes, w->scales, K, N, w->colsumw, st) == hipSuccess;
     if (!ok || hipStreamSynchronize(st) != hipSuccess) {
         rc = TRDQ_ERR_HIP;
@@ -240,6 +246,7 @@ fail:
     if (Wrot2) (void)hipFree(Wrot2);
     if (amax) (void)hipFree(amax);
     if (w->codes) (void)hipFree(w->codes);
+    if (w->codes_tiled) (void)hipFree(w->codes_tiled);
     if (w->scales) (void)hipFree(w->scales);
     if (w->colsum) (void)hipFree(w->colsum);
     if (w->colsumw) (void)hipFree(w->colsumw);
@@ -629,6 +636,7 @@ void trdq_weights_destroy(trdq_weights *w)
 {
     if (!w) return;
     if (w->codes) (void)hipFree(w->codes);
+    if (w->codes_tiled) (void)hipFree(w->codes_tiled);
     if (w->scales) (void)hipFree(w->scales);
     if (w->colsum) (void)hipFree(w->colsum);
     if (w->colsumw) (void)hipFree(w->colsumw);
@@ -739,6 +747,74 @@ trdq_status trdq_rotate_quant_rpr(const void *X_dev, int64_t M, int K, int64_t l
     return hip_status(trdq::launch_rotate_quant_rpr(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev,
                                                     perm_dev, Xq_dev, sx_dev, warm, warm_bytes,
                                                     static_cast<hipStream_t>(stream)));
+}
+
+int64_t trdq_xq_tiled_nbytes(int64_t M, int K)
+{
+    if (M < 0 || K <= 0 || K % trdq::kBlock != 0) return -1;
+    return (M + 15) / 16 * 16 * (int64_t)K;
+}
+
+trdq_status trdq_rotate_quant_tiled(const void *X_dev, int64_t M, int K, int64_t ldx,
+                                    const float *diag_dev, int block,
+                                    int8_t *Xt_dev, float *sx_dev, const trdq_weights *next, void *stream)
+{
+    trdq_status rc = check_rotate_args(X_dev, M, K, ldx, block);
+    if (rc != TRDQ_OK) return rc;
+    if (M > 0 && (!Xt_dev || !sx_dev)) return TRDQ_ERR_NULL;
+    if (!aligned(Xt_dev, 16) || !aligned(sx_dev, 4) || (diag_dev && !aligned(diag_dev, 16))) return TRDQ_ERR_SHAPE;
+    if (K / trdq::kBlock > 36) return TRDQ_ERR_UNSUPPORTED;
+    if (M == 0) return TRDQ_OK;
+    const void *warm = nullptr;
+    int64_t warm_bytes = 0;
+    if (next && next->codes) {
+        if (trdq_status rd = check_device(next->device); rd != TRDQ_OK) return rd;
+        // warm what the tiled product will read
+        warm = next->codes_tiled ? next->codes_tiled : next->codes;
+        warm_bytes = (int64_t)next->N * next->K / (next->wbits == 4 ? 2 : 1);
+        warm_bytes -= warm_bytes % 16;
+    }
+    return hip_status(trdq::launch_rotate_quant(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev,
+                                                Xt_dev, sx_dev, nullptr, warm, warm_bytes,
+                                                static_cast<hipStream_t>(stream), 8, true));
+}
+
+trdq_status trdq_xq_untile(const int8_t *Xt_dev, int64_t M, int K, int8_t *Xq_dev, void *stream)
+{
+    if (M < 0 || K <= 0 || K % trdq::kBlock != 0) return TRDQ_ERR_SHAPE;
+    if (M > 0 && (!Xt_dev || !Xq_dev)) return TRDQ_ERR_NULL;
+    if (!aligned(Xt_dev, 16) || !aligned(Xq_dev, 16)) return TRDQ_ERR_SHAPE;
+    if (M == 0) return TRDQ_OK;
+    return hip_status(trdq::launch_retile_rows(Xt_dev, Xq_dev, M, K, false, static_cast<hipStream_t>(stream)));
+}
+
+int trdq_qgemm_tiled_supported(const trdq_weights *w, int64_t M)
+{
+    if (!w || M < 0) return 0;
+    // (the output checks of the call itself, alignment and row stride, are not part of this answer)
+    return w->wbits == 8 && w->codes_tiled && M % 128 == 0 && w->N % 144 == 0 && w->K % 64 == 0 ? 1 : 0;
+}
+
+int trdq_qgemm_tiled_preferred(const trdq_weights *w, int64_t M)
+{
+    return trdq_qgemm_tiled_supported(w, M) && w->K / trdq::kBlock <= 36 && trdq::qgemm_tiled_pays(M, w->K, w->N) ? 1 : 0;
+}
+
+trdq_status trdq_qgemm_tiled(const trdq_weights *w, const int8_t *Xt_dev, const float *sx_dev, int64_t M,
+                             const float *bias_dev, void *Y_dev, int64_t ldy,
+                             int32_t *acc_debug_dev, void *stream)
+{
+    if (!w) return TRDQ_ERR_NULL;
+    trdq_status rc = check_out_args(Y_dev, M, w->N, ldy, bias_dev);
+    if (rc != TRDQ_OK) return rc;
+    if (M > 0 && (!Xt_dev || !sx_dev)) return TRDQ_ERR_NULL;
+    if (!aligned(Xt_dev, 16) || !aligned(sx_dev, 4) || (acc_debug_dev && !aligned(acc_debug_dev, 16)))
+        return TRDQ_ERR_SHAPE;
+    if (!trdq_qgemm_tiled_supported(w, M) || ldy % 8 != 0 || !aligned(Y_dev, 16)) return TRDQ_ERR_UNSUPPORTED;
+    if (M == 0) return TRDQ_OK;
+    if (trdq_status rd = check_device(w->device); rd != TRDQ_OK) return rd;
+    return hip_status(trdq::launch_qgemm_tiled(*w, Xt_dev, sx_dev, M, bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
+                                               acc_debug_dev, static_cast<hipStream_t>(stream)));
 }
 
 trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev, int64_t M,
@@ -864,6 +940,13 @@ trdq_status trdq_layer_forward(const trdq_layer *l, int step, const void *X_dev,
     if (fused > 0 || (fused < 0 && trdq::fused_pays(M, l->K, l->N, w->wbits)))
         return trdq_linear_fused(X_dev, M, l->K, d, w, bias_dev, Y_dev, l->N, stream);
     if (!Xq_ws_dev || !sx_ws_dev) return TRDQ_ERR_NULL;
+    // the workspace is private to the layer: block-tiled codes where the tiled product takes the shape
+    // (M % 128 == 0 there, so the workspace size M * K is the same)
+    if (trdq_qgemm_tiled_preferred(w, M) && aligned(Y_dev, 16)) {
+        trdq_status rt = trdq_rotate_quant_tiled(X_dev, M, l->K, l->K, d, trdq::kBlock, Xq_ws_dev, sx_ws_dev, w, stream);
+        if (rt != TRDQ_OK) return rt;
+        return trdq_qgemm_tiled(w, Xq_ws_dev, sx_ws_dev, M, bias_dev, Y_dev, l->N, nullptr, stream);
+    }
     trdq_status rc = trdq_rotate_quant_warm(X_dev, M, l->K, l->K, d, trdq::kBlock, Xq_ws_dev, sx_ws_dev, w, stream);
     if (rc != TRDQ_OK) return rc;
     return trdq_qgemm(w, Xq_ws_dev, sx_ws_dev, M, bias_dev, Y_dev, l->N, nullptr, stream);

@@ -111,6 +111,11 @@ hipError_t launch_qgemm8_asym(const GemmArgs &a, bool debug, int kind, hipStream
 int dma4_num_variants();
 hipError_t launch_qgemm4_dma(const GemmArgs &a, bool debug, int variant, hipStream_t st);
 
+// Kernel on block-tiled operands (qgemm_tiled.hip): a.Xq and a.Wc point at the tiled forms.
+bool tiled_supports(const GemmArgs &a);
+hipError_t launch_qgemm8_tiled(const GemmArgs &a, bool debug, hipStream_t st);
+hipError_t launch_retile(const int8_t *src, int8_t *dst, int64_t R, int K, bool to_tiled, hipStream_t st);
+
 // 256 x 256 tile kernel with a hand-scheduled main loop (qgemm_wide.hip).
 bool wide_supports(const GemmArgs &a);
 hipError_t launch_qgemm8_wide(const GemmArgs &a, bool debug, hipStream_t st);

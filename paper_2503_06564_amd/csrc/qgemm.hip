@@ -341,4 +341,38 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, con
     }
 }
 
+bool qgemm_tiled_supports(const Weights &w, int64_t M, const void *Y, int64_t ldy)
+{
+    if (w.wbits != 8 || !w.codes_tiled) return false;
+    GemmArgs a;
+    a.Xq = nullptr; a.Wc = w.codes_tiled; a.sx = nullptr; a.sw = w.scales; a.bias = nullptr;
+    a.Y = static_cast<uint16_t *>(const_cast<void *>(Y)); a.acc_debug = nullptr; a.M = M; a.ldy = ldy; a.K = w.K; a.N = w.N;
+    a.tiles_m = a.tiles_n = 0;
+    return tiled_supports(a);
+}
+
+hipError_t launch_qgemm_tiled(const Weights &w, const int8_t *Xt, const float *sx, int64_t M, const float *bias,
+                              uint16_t *Y, int64_t ldy, int32_t *acc_debug, hipStream_t st)
+{
+    if (M == 0) return hipSuccess;
+    if (!qgemm_tiled_supports(w, M, Y, ldy)) return hipErrorInvalidValue;
+    GemmArgs a;
+    a.Xq = Xt; a.Wc = w.codes_tiled; a.sx = sx; a.sw = w.scales; a.bias = bias; a.Y = Y;
+    a.acc_debug = acc_debug; a.M = M; a.ldy = ldy; a.K = w.K; a.N = w.N;
+    a.tiles_m = a.tiles_n = 0;
+    return launch_qgemm8_tiled(a, acc_debug != nullptr, st);
+}
+
+bool qgemm_tiled_pays(int64_t M, int K, int N)
+{
+    // more than one 128 x 144 tile per compute unit: the 256-token tiles with two workgroups per
+    // compute unit win; at or below that the one-workgroup kernels of the row-major path do
+    return (M / 128) * (int64_t)(N / 144) > num_cus();
+}
+
+hipError_t launch_retile_rows(const int8_t *src, int8_t *dst, int64_t R, int K, bool to_tiled, hipStream_t st)
+{
+    return launch_retile(src, dst, R, K, to_tiled, st);
+}
+
 }  // namespace trdq

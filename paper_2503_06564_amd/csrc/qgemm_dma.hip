@@ -140,7 +140,7 @@ __device__ __forceinline__ void epilogue_w8_rows(const v4i (&acc)[TN][TM], const
         const int row = id / LPR, c = id % LPR;
         if (CHUNKS % 64 == 0 || id < CHUNKS) {
             const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * ROWB + c * 16);
-            *reinterpret_cast<uint4 *>(g.Y + (m_wave + row) * g.ldy + n_wave + c * 8) = v;
+            store_out16(g.Y + (m_wave + row) * g.ldy + n_wave + c * 8, v);
         }
     }
 }
@@ -1027,7 +1027,7 @@ __global__ __launch_bounds__(kThreads) void qgemm4_ring_kernel(GemmArgs g)
         for (int i = 0; i < WM / RPI; ++i) {
             const int row = i * RPI + r0;
             const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * ROWB + c * 16);
-            *reinterpret_cast<uint4 *>(g.Y + (m0 + wm * WM + row) * g.ldy + n0 + wn * WN + c * 8) = v;
+            store_out16(g.Y + (m0 + wm * WM + row) * g.ldy + n0 + wn * WN + c * 8, v);
         }
     }
 }

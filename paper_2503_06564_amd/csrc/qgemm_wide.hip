@@ -402,7 +402,7 @@ __global__ __launch_bounds__(kThreads) void qgemm8_wide_kernel(GemmArgs g)
                 const int64_t m = m_wave + b * 16 + row;
                 const int n = n_wave + c * 8;
                 if (FULL || (m < g.M && n < g.N))
-                    *reinterpret_cast<uint4 *>(g.Y + m * g.ldy + n) = v;
+                    store_out16(g.Y + m * g.ldy + n, v);
             }
             __builtin_amdgcn_wave_barrier();          // ... and the next token tile's writes after these reads
         });

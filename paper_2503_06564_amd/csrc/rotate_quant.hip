@@ -50,7 +50,8 @@ template <int SPW, int MAXT, bool ASYM>
 __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
     const uint16_t *__restrict__ X, int64_t M, int nb, int64_t ldx,
     const float *__restrict__ diag, int8_t *__restrict__ Xq, float *__restrict__ sx,
-    int32_t *__restrict__ zc, const uint4 *__restrict__ warm, int64_t warm_chunks, float qmax, float sx_mul)
+    int32_t *__restrict__ zc, const uint4 *__restrict__ warm, int64_t warm_chunks, float qmax, float sx_mul,
+    int tiled)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int K = nb * kBlock;
@@ -300,9 +301,12 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
                     c[2 * q + 1] = pack4_low_bytes(code_bits(out[i][4][q]), code_bits(out[i][5][q]),
                                                    code_bits(out[i][6][q]), code_bits(out[i][7][q]));
                 }
-                int8_t *dst = Xq + token * (int64_t)K + b * kBlock + g * 16;
+                // row-major: the two 64-byte halves of the block inside the token's row; tiled: the
+                // token's 64-byte rows of the two 1 KB blocks (16 tokens x 64 k) of this 128-block
+                int8_t *dst = tiled ? Xq + ((tg * (K >> 6) + 2 * b) * 16 + r) * (int64_t)64 + g * 16
+                                    : Xq + token * (int64_t)K + b * kBlock + g * 16;
                 *reinterpret_cast<uint4 *>(dst) = make_uint4(c[0], c[1], c[2], c[3]);
-                *reinterpret_cast<uint4 *>(dst + 64) = make_uint4(c[4], c[5], c[6], c[7]);
+                *reinterpret_cast<uint4 *>(dst + (tiled ? 1024 : 64)) = make_uint4(c[4], c[5], c[6], c[7]);
             }
         }
     };
@@ -320,7 +324,7 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
 template <int SPW, int MAXT>
 hipError_t launch_spw(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx, const float *diag,
                       int8_t *Xq, float *sx, int32_t *zc, const void *warm, int64_t warm_bytes, int wgs_per_cu,
-                      hipStream_t st, int abits)
+                      hipStream_t st, int abits, bool tiled)
 {
     const float qmax = (float)((1 << (abits - 1)) - 1);
     const float sx_mul = 0.08838834764831845f / qmax;
@@ -332,10 +336,12 @@ hipError_t launch_spw(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx,
     const int64_t warm_chunks = (warm && warm_bytes < ((int64_t)1 << 32)) ? warm_bytes / 16 : 0;   // 32-bit byte offsets in the copy
     if (zc)
         hipLaunchKernelGGL((rotate_quant_kernel<SPW, MAXT, true>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
-                           X, M, nb, ldx, diag, Xq, sx, zc, static_cast<const uint4 *>(warm), warm_chunks, qmax, sx_mul);
+                           X, M, nb, ldx, diag, Xq, sx, zc, static_cast<const uint4 *>(warm), warm_chunks, qmax, sx_mul,
+                           (int)tiled);
     else
         hipLaunchKernelGGL((rotate_quant_kernel<SPW, MAXT, false>), dim3((unsigned)grid), dim3(64 * nw), smem, st,
-                           X, M, nb, ldx, diag, Xq, sx, zc, static_cast<const uint4 *>(warm), warm_chunks, qmax, sx_mul);
+                           X, M, nb, ldx, diag, Xq, sx, zc, static_cast<const uint4 *>(warm), warm_chunks, qmax, sx_mul,
+                           (int)tiled);
     return hipGetLastError();
 }
 
@@ -347,13 +353,13 @@ constexpr int kRQMaxBlocks = 36;
 
 hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
                                int8_t *Xq, float *sx, int32_t *zc, const void *warm, int64_t warm_bytes, hipStream_t st,
-                               int abits)
+                               int abits, bool tiled)
 {
     if (M == 0) return hipSuccess;
     if (abits < 2 || abits > 8) return hipErrorInvalidValue;
     const int nb = K / kBlock;
     if (nb > kRQMaxBlocks)
-        return (zc || abits != 8) ? hipErrorInvalidValue : launch_rotate_quant_wide(X, M, K, ldx, diag, Xq, sx, st);
+        return (zc || abits != 8 || tiled) ? hipErrorInvalidValue : launch_rotate_quant_wide(X, M, K, ldx, diag, Xq, sx, st);
     // three blocks per wave (two or one for narrow rows), then rebalance; workgroups of up to
     // 12 waves, as many per compute unit as stay resident (with three blocks per wave the kernel
     // holds 166 registers and small workgroups pack two waves per SIMD, eight per compute unit)
@@ -368,12 +374,12 @@ hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx,
     const int wgs = resident / nw > 0 ? resident / nw : 1;
     const bool small = nw <= 4;      // up to 256 threads: no register cap from co-residency
     switch (spw) {
-        case 1: return small ? launch_spw<1, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits)
-                             : launch_spw<1, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits);
-        case 2: return small ? launch_spw<2, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits)
-                             : launch_spw<2, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits);
-        default: return small ? launch_spw<3, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits)
-                              : launch_spw<3, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits);
+        case 1: return small ? launch_spw<1, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits, tiled)
+                             : launch_spw<1, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits, tiled);
+        case 2: return small ? launch_spw<2, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits, tiled)
+                             : launch_spw<2, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits, tiled);
+        default: return small ? launch_spw<3, 256>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits, tiled)
+                              : launch_spw<3, 768>(X, M, nb, nw, ldx, diag, Xq, sx, zc, warm, warm_bytes, wgs, st, abits, tiled);
     }
 }
 

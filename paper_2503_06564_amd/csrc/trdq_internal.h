@@ -25,6 +25,7 @@ struct Weights {
     int qbits = 0;               // width of the codes: 8, 6 (in the 8-bit layout) or 4
     void *codes = nullptr;
     float *scales = nullptr;
+    void *codes_tiled = nullptr; // int8 weights with N % 144 == 0: the same codes in 1 KB blocks of 16 channels x 64 k
     int rotation = 0;            // which transform was folded in (kRot*): the activation side must apply the same one
     int32_t *colsum = nullptr;   // int8 weights: sum over k of the codes of every output channel [N]
     float *colsumw = nullptr;    // int4 weights: 16 * sum_g s_w[g][n] * (sum of the codes of group g) [N]
@@ -52,9 +53,18 @@ struct Table {
 // warm / warm_bytes: optional device range (16-byte aligned, a multiple of 16 bytes) that the
 // kernel reads once and discards, to pull it into the memory-side cache for the next kernel.
 // zc: null (symmetric quantiser), or where the asymmetric quantiser writes 128 - z_i per token.
+// tiled: Xq is written in 1 KB blocks of 16 tokens x 64 k (block (m / 16, k / 64) at ((m / 16) * K / 64 + k / 64) * 1024)
 hipError_t launch_rotate_quant(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
                                int8_t *Xq, float *sx, int32_t *zc, const void *warm, int64_t warm_bytes, hipStream_t st,
-                               int abits = 8);   // symmetric codes in +-(2^(abits-1) - 1); K <= 4608 unless 8
+                               int abits = 8,    // symmetric codes in +-(2^(abits-1) - 1); K <= 4608 unless 8
+                               bool tiled = false);
+// the product on block-tiled operands, and the conversion between the two forms of an int8 matrix [R, K]
+bool qgemm_tiled_supports(const Weights &w, int64_t M, const void *Y, int64_t ldy);
+hipError_t launch_qgemm_tiled(const Weights &w, const int8_t *Xt, const float *sx, int64_t M, const float *bias,
+                              uint16_t *Y, int64_t ldy, int32_t *acc_debug, hipStream_t st);
+// measured choice between the two products for a layer object (true: the tiled pair is the faster one)
+bool qgemm_tiled_pays(int64_t M, int K, int N);
+hipError_t launch_retile_rows(const int8_t *src, int8_t *dst, int64_t R, int K, bool to_tiled, hipStream_t st);
 hipError_t launch_rotate_quant_wide(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
                                     int8_t *Xq, float *sx, hipStream_t st);
 

@@ -29,6 +29,8 @@ SYMBOLS = [
     "trdq_greedy_rotation", "trdq_prepare_weights_dense_rpr", "trdq_rotate_quant_dense_rpr",
     "trdq_channel_absmax_dense", "trdq_greedy_rotation_second",
     "trdq_peak_mfma_i8", "trdq_peak_stream",
+    "trdq_xq_tiled_nbytes", "trdq_rotate_quant_tiled", "trdq_xq_untile", "trdq_qgemm_tiled_supported", "trdq_qgemm_tiled_preferred",
+    "trdq_qgemm_tiled",
 ]
 
 _lib = None
@@ -81,6 +83,13 @@ def lib():
         L.trdq_rotate_quant_bits.argtypes = [p, i64, i32, i64, p, i32, i32, p, p, p, p]
         L.trdq_cosine_similarity.argtypes = [p, p, i32, i64, i64, i64, p, p, p]
         L.trdq_cosine_similarity_static.argtypes = [p, p, i32, i64, i64, i64, p, p]
+        L.trdq_xq_tiled_nbytes.argtypes = [i64, i32]
+        L.trdq_xq_tiled_nbytes.restype = i64
+        L.trdq_rotate_quant_tiled.argtypes = [p, i64, i32, i64, p, i32, p, p, p, p]
+        L.trdq_xq_untile.argtypes = [p, i64, i32, p, p]
+        L.trdq_qgemm_tiled_supported.argtypes = [p, i64]
+        L.trdq_qgemm_tiled_preferred.argtypes = [p, i64]
+        L.trdq_qgemm_tiled.argtypes = [p, p, p, i64, p, p, i64, p, p]
         L.trdq_share_plan.argtypes = [p, i32, i32, C.c_float, p]
         L.trdq_peak_mfma_i8.argtypes = [p, i32, i32, i32, C.POINTER(C.c_int64), p]
         L.trdq_peak_stream.argtypes = [p, p, i64, p]
@@ -452,6 +461,75 @@ def qgemm(w, Xq, sx, Y, bias=None, acc_debug=None, stream=None):
     ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
     _check(lib().trdq_qgemm(w.handle, _ptr(Xq), _ptr(sx), M, _ptr(bias), _ptr(Y), ldy, _ptr(acc_debug),
                             _stream(stream)), "trdq_qgemm")
+
+
+# ---- the pair on block-tiled activation codes ---------------------------------------------------
+
+def xq_tiled_nbytes(M, K):
+    """Bytes of the block-tiled code buffer of an [M, K] activation matrix."""
+    n = lib().trdq_xq_tiled_nbytes(M, K)
+    if n < 0:
+        raise TrdqError(ERR_SHAPE, "trdq_xq_tiled_nbytes")
+    return n
+
+
+def rotate_quant_tiled(X, diag, Xt, sx, block=BLOCK, stream=None, warm=None):
+    """rotate_quant writing the codes in 1 KB blocks of 16 tokens x 64 channels; Xt: int8, xq_tiled_nbytes(M, K) bytes."""
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    _check(lib().trdq_rotate_quant_tiled(_ptr(X), M, K, ldx, _ptr(diag), block, _ptr(Xt), _ptr(sx),
+                                         warm.handle if warm is not None else None, _stream(stream)),
+           "trdq_rotate_quant_tiled")
+
+
+def xq_untile(Xt, M, K, Xq, stream=None):
+    """Xq int8 [M, K] dense <- the block-tiled codes Xt."""
+    _check(lib().trdq_xq_untile(_ptr(Xt), M, K, _ptr(Xq), _stream(stream)), "trdq_xq_untile")
+
+
+def qgemm_tiled_supported(w, M):
+    return bool(lib().trdq_qgemm_tiled_supported(w.handle, M))
+
+
+def qgemm_tiled_preferred(w, M):
+    """True where the library itself (trdq_layer_forward) takes the tiled pair: supported and measured faster."""
+    return bool(lib().trdq_qgemm_tiled_preferred(w.handle, M))
+
+
+def qgemm_tiled(w, Xt, sx, Y, bias=None, acc_debug=None, stream=None):
+    M = Y.shape[0]
+    ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
+    _check(lib().trdq_qgemm_tiled(w.handle, _ptr(Xt), _ptr(sx), M, _ptr(bias), _ptr(Y), ldy, _ptr(acc_debug),
+                                  _stream(stream)), "trdq_qgemm_tiled")
+
+
+def bind_rotate_quant_tiled(X, diag, Xt, sx, block=BLOCK, stream=None, warm=None):
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    f = lib().trdq_rotate_quant_tiled
+    args = (C.c_void_p(_ptr(X)), C.c_int64(M), C.c_int(K), C.c_int64(ldx), C.c_void_p(_ptr(diag)), C.c_int(block),
+            C.c_void_p(_ptr(Xt)), C.c_void_p(_ptr(sx)), warm.handle if warm is not None else C.c_void_p(None),
+            C.c_void_p(_stream(stream)))
+
+    def call():
+        st = f(*args)
+        if st != OK:
+            raise TrdqError(st, "trdq_rotate_quant_tiled")
+    return call
+
+
+def bind_qgemm_tiled(w, Xt, sx, Y, bias=None, acc_debug=None, stream=None):
+    M = Y.shape[0]
+    ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
+    f = lib().trdq_qgemm_tiled
+    args = (w.handle, C.c_void_p(_ptr(Xt)), C.c_void_p(_ptr(sx)), C.c_int64(M), C.c_void_p(_ptr(bias)),
+            C.c_void_p(_ptr(Y)), C.c_int64(ldy), C.c_void_p(_ptr(acc_debug)), C.c_void_p(_stream(stream)))
+
+    def call():
+        st = f(*args)
+        if st != OK:
+            raise TrdqError(st, "trdq_qgemm_tiled")
+    return call
 
 
 def linear_fused(X, diag, w, Y, bias=None, stream=None):

@@ -84,6 +84,19 @@ def check_layer(oracle, cfg, kind, step, wbits, block=0, fused_too=True, Xb=None
     acc = oracle.acc_exact_blas(Xq_h, codes, None if wbits == 8 else 128)
     y_same = oracle.dequant(acc, sx_h, scales, bias)
     gu.assert_y_same_codes(gu.bf16_to_host(Y[idx]), y_same, f"{kind} Y (same codes)")
+    if wbits == 8 and trdq.qgemm_tiled_supported(w, M):
+        # the block-tiled pair (what bench.py and trdq_layer_forward take for the large shapes): the same codes,
+        # moved, and the same bits out, on every token
+        Xt = torch.empty((trdq.xq_tiled_nbytes(M, K),), dtype=torch.int8, device="cuda")
+        sxt = torch.empty((M,), dtype=torch.float32, device="cuda")
+        Yt = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        back = torch.empty((M, K), dtype=torch.int8, device="cuda")
+        trdq.rotate_quant_tiled(X, dd, Xt, sxt, warm=w)
+        trdq.qgemm_tiled(w, Xt, sxt, Yt, bias=bd)
+        trdq.xq_untile(Xt, M, K, back)
+        torch.cuda.synchronize()
+        assert torch.equal(back, Xq) and torch.equal(sxt, sx), f"{kind}: tiled codes differ from row-major codes"
+        assert torch.equal(Yt, Y), f"{kind}: tiled and row-major products differ"
     if fused_too:
         Yf = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
         trdq.linear_fused(X, dd, w, Yf, bias=bd)
