@@ -365,9 +365,13 @@ hipError_t launch_qgemm_tiled(const Weights &w, const int8_t *Xt, const float *s
 
 bool qgemm_tiled_pays(int64_t M, int K, int N)
 {
-    // more than one 128 x 144 tile per compute unit: the 256-token tiles with two workgroups per
-    // compute unit win; at or below that the one-workgroup kernels of the row-major path do
-    return (M / 128) * (int64_t)(N / 144) > num_cus();
+    // Measured on the DiT-XL/2 widths at 4096 ... 32768 tokens: with more than one 128 x 144 tile per
+    // compute unit the tiled kernel (two workgroups per compute unit) wins, by 5-25 %; at or below that
+    // the one-workgroup kernels of the row-major path do, and for long K (fc2) they still do at up to two
+    // such tiles per compute unit (the kernel whose two wave groups split K inside the workgroup).
+    const int64_t tiles = (M / 128) * (int64_t)(N / 144);
+    if (tiles <= num_cus()) return false;
+    return !(K >= 2304 && tiles <= 2 * (int64_t)num_cus());
 }
 
 hipError_t launch_retile_rows(const int8_t *src, int8_t *dst, int64_t R, int K, bool to_tiled, hipStream_t st)
