@@ -95,12 +95,12 @@ def cpu_baseline(cfg, wl, budget_s):
                       f"{spent:.1f} s of CPU work"}
 
 
-def committed_traffic(workload):
+def committed_traffic(workload, config):
     """HBM bytes per qgemm launch from the committed counter summary of this workload, or None.
 
     The figure comes from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of this same
     command, scaled by the copy-kernel calibration; the summary file states the commands."""
-    path = os.path.join(ROOT, "profiles", f"qgemm_hbm_traffic_{workload}.txt")
+    path = os.path.join(ROOT, "profiles", f"bench_config{config}_{workload}.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -340,6 +340,9 @@ def main():
         for (name, kind), ts in per.items():
             avg = sum(ts) / len(ts)
             entry = {"avg_us": avg * 1e6, "median_us": sorted(ts)[len(ts) // 2] * 1e6, "launches": len(ts)}
+            if avg <= 0.0:                 # a bracket no longer than its calibrated cost (profiler attached): no rate
+                kern[f"{name}:{kind}"] = entry
+                continue
             if name in ("qgemm", "fused"):
                 entry["tops"] = gemm_ops[kind] / avg / 1e12
                 entry["frac_int8_peak"] = entry["tops"] / INT8_MFMA_PEAK_TOPS
@@ -352,17 +355,17 @@ def main():
         tot_t = sum(sum(ts) for (name, _), ts in per.items() if name == dom)
         n_launch = sum(len(ts) for (name, _), ts in per.items() if name == dom)
         tot_ops = sum(gemm_ops[kind] * len(ts) for (name, kind), ts in per.items() if name == dom)
-        achieved = tot_ops / tot_t / 1e12
+        achieved = tot_ops / tot_t / 1e12 if tot_t > 0 else 0.0
         out["roofline"] = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS,
                            "unit": "TOP/s", "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None,
-                           "avg_launch_us": tot_t / n_launch * 1e6, "launches": n_launch,
+                           "avg_launch_us": tot_t / max(n_launch, 1) * 1e6, "launches": n_launch,
                            "event_cost_us": ev_cost * 1e6,
                            "timed_on": f"every {every}th of the {args.steps} timed steps (launched from the host, "
                                        "the others replay a captured graph if --graph), events on the launch stream; "
                                        "event_cost_us = (sum of an evented step's brackets - average length of "
                                        "a step without events) / launches per step is subtracted from every bracket",
-                           "ops_per_launch": tot_ops / n_launch}
-        if not args.fused:
+                           "ops_per_launch": tot_ops / max(n_launch, 1)}
+        if not args.fused and sum(sum(ts) for (name, _), ts in per.items() if name == "rotate_quant") > 0:
             rq_t = sum(sum(ts) for (name, _), ts in per.items() if name == "rotate_quant")
             rq_b = sum(rq_bytes[kind] * len(ts) for (name, kind), ts in per.items() if name == "rotate_quant")
             out["roofline_rotate_quant"] = {"bound": "hbm", "achieved": rq_b / rq_t / 1e9, "peak": HBM_PEAK_GBS,
@@ -372,8 +375,8 @@ def main():
     if "roofline" in out:
         # HBM bytes per launch are not measured by this run: they come from the committed counter summary
         # of the same command (two rocprofv3 --pmc runs), or stay null when there is none
-        out["roofline"]["traffic"] = committed_traffic(cfg.name)
-        out["roofline"]["traffic_source"] = (f"profiles/qgemm_hbm_traffic_{cfg.name}.txt (rocprofv3 --pmc FETCH_SIZE / "
+        out["roofline"]["traffic"] = committed_traffic(cfg.name, args.config)
+        out["roofline"]["traffic_source"] = (f"profiles/bench_config{args.config}_{cfg.name}.txt (rocprofv3 --pmc FETCH_SIZE / "
                                              "WRITE_SIZE of this command, committed; not measured in this run)"
                                              if out["roofline"]["traffic"] is not None else None)
         if not args.no_measured_peaks:
