@@ -260,6 +260,63 @@ int trdq_oracle_igemm_asym(const uint8_t *Xq, const int32_t *zx, const int8_t *W
     return 0;
 }
 
+/* ------------------------------------------------ asymmetric weight quantiser */
+
+/* Eq. 1-3 applied to the transformed weights H_t(W), one range per output channel n (Sec. 3.1:
+ * weights per channel), in the reading of the activation quantiser above:
+ *   lo_n = min(min_k W'[k,n], 0),  hi_n = max(max_k W'[k,n], 0),  s_n = (hi_n - lo_n) / (2^bits - 1),
+ *   z_n = -rint(lo_n / s_n),  q[k,n] = clamp(rint(W'[k,n] / s_n) + z_n, 0, 2^bits - 1),  W' ~ s_n (q - z_n).
+ * An all-zero column gets s = 0, z = 0, codes 0. */
+int trdq_oracle_quant_weights_asym(const double *Wp, int K, int N, int bits, uint8_t *Wq, double *sw, int32_t *zw)
+{
+    if (!Wp || !Wq || !sw || !zw || K <= 0 || N <= 0 || bits < 2 || bits > 8) return 1;
+    const double qmax = (double)((1 << bits) - 1);
+    for (int n = 0; n < N; ++n) {
+        double lo = 0.0, hi = 0.0;
+        for (int k = 0; k < K; ++k) {
+            double w = Wp[(size_t)k * N + n];
+            if (w < lo) lo = w;
+            if (w > hi) hi = w;
+        }
+        if (hi == lo) {
+            sw[n] = 0.0; zw[n] = 0;
+            for (int k = 0; k < K; ++k) Wq[(size_t)k * N + n] = 0;
+            continue;
+        }
+        double s = (hi - lo) / qmax;
+        double z = -rint(lo / s);
+        sw[n] = s;
+        zw[n] = (int32_t)z;
+        for (int k = 0; k < K; ++k) {
+            double q = rint(Wp[(size_t)k * N + n] / s) + z;
+            if (q > qmax) q = qmax;
+            if (q < 0.0) q = 0.0;
+            Wq[(size_t)k * N + n] = (uint8_t)q;
+        }
+    }
+    return 0;
+}
+
+/* acc[i,n] = sum_k (qx[i,k] - zx[i]) * (qw[k,n] - zw[n]): the integer part of the product of the
+ * dequantised operands when both carry a zero point (zx may be NULL: symmetric activation codes).
+ * Activation codes come as int16 so that signed (symmetric) and unsigned (asymmetric) ones fit.
+ * |acc| <= 255 * 255 * K < 2^31 for K <= 33 000. */
+int trdq_oracle_igemm_asym2(const int16_t *Xq, const int32_t *zx, const uint8_t *Wq, const int32_t *zw,
+                            int64_t M, int K, int N, int32_t *acc)
+{
+    if (!Xq || !Wq || !zw || !acc || M < 0 || K <= 0 || N <= 0) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int n = 0; n < N; ++n) {
+            int32_t t = 0;
+            const int32_t z = zx ? zx[i] : 0;
+            for (int k = 0; k < K; ++k)
+                t += ((int32_t)Xq[i * (int64_t)K + k] - z) * ((int32_t)Wq[(size_t)k * N + n] - zw[n]);
+            acc[i * (int64_t)N + n] = t;
+        }
+    return 0;
+}
+
 /* ------------------------------------- second rotation and zigzag permutation */
 
 /* Zigzag permutation (Sec. 3.2, "zigzag permutation"): the channels, taken in order of

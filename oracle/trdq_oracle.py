@@ -43,6 +43,8 @@ def lib():
                                          p, p, p, p, p, p]
         L.trdq_oracle_quant_tokens_asym.argtypes = [p, i64, i32, p, p, p]
         L.trdq_oracle_igemm_asym.argtypes = [p, p, p, i64, i32, i32, p]
+        L.trdq_oracle_quant_weights_asym.argtypes = [p, i32, i32, i32, p, p, p]
+        L.trdq_oracle_igemm_asym2.argtypes = [p, p, p, p, i64, i32, i32, p]
         L.trdq_oracle_zigzag.argtypes = [p, i32, i32, p]
         L.trdq_oracle_permute_cols.argtypes = [p, i64, i32, p, p]
         L.trdq_oracle_rotate_f64.argtypes = [p, i64, i32, i32, p]
@@ -272,6 +274,58 @@ def linear_asym(X_bf16, W, d=None, bias=None, B=128, exact_blas=False, wbits=8):
         acc = acc_asym_exact_blas(Xq, zx, Wq) if exact_blas else igemm_asym(Xq, zx, Wq)
     Y, Yd = dequant(acc, sx, sw, bias, return_f64=True)
     return dict(Xq=Xq, sx=sx, zx=zx, Wq=Wq, sw=sw, acc=acc, Y=Y, Yd=Yd)
+
+
+# ---- asymmetric weights (Eq. 1-3 applied to H_t(W), one range per output channel) --------------
+
+def quant_weights_asym(Wp, bits=8):
+    """(codes uint8 [K, N] in 0..2^bits-1, scales float64 [N], zero points int32 [N]); W' ~ s (q - z)."""
+    Wp = _c(Wp, np.float64)
+    K, N = Wp.shape
+    Wq = np.empty((K, N), dtype=np.uint8)
+    sw = np.empty(N, dtype=np.float64)
+    zw = np.empty(N, dtype=np.int32)
+    _chk(lib().trdq_oracle_quant_weights_asym(_ptr(Wp), K, N, bits, _ptr(Wq), _ptr(sw), _ptr(zw)), "quant_weights_asym")
+    return Wq, sw, zw
+
+
+def prepare_weights_asym(W, d=None, B=128, bits=8):
+    return quant_weights_asym(rotate_weights(W, d, B), bits)
+
+
+def igemm_asym2(Xq, zx, Wq, zw):
+    """int32 [M, N]: sum_k (qx[i,k] - zx_i) (qw[k,n] - zw_n), the plain loop; zx None = symmetric activation codes."""
+    Xq, zx, Wq, zw = _c(Xq, np.int16), _c(zx, np.int32), _c(Wq, np.uint8), _c(zw, np.int32)
+    M, K = Xq.shape
+    N = Wq.shape[1]
+    acc = np.empty((M, N), dtype=np.int32)
+    _chk(lib().trdq_oracle_igemm_asym2(_ptr(Xq), _ptr(zx), _ptr(Wq), _ptr(zw), M, K, N, _ptr(acc)), "igemm_asym2")
+    return acc
+
+
+def acc_asym2_exact_blas(Xq, zx, Wq, zw):
+    """The same sums through a float64 library matmul (all partial sums are integers below 2^53)."""
+    Xd = np.asarray(Xq).astype(np.float64)
+    if zx is not None:
+        Xd = Xd - np.asarray(zx).astype(np.float64)[:, None]
+    Wd = np.asarray(Wq).astype(np.float64) - np.asarray(zw).astype(np.float64)[None, :]
+    return (Xd @ Wd).astype(np.int32)
+
+
+def linear_asym_weights(X_bf16, W, d=None, bias=None, B=128, exact_blas=False, act_asym=False, wbits=8):
+    """Rotated linear with asymmetric per-output-channel weights (Eq. 1-3 on H_t(W)); activations
+    symmetric per token, or asymmetric too (act_asym)."""
+    V = rotate(X_bf16, d, B)
+    if act_asym:
+        Xq, sx, zx = quant_tokens_asym(V)
+    else:
+        Xq, sx = quant_tokens(V)
+        zx = None
+    Wq, sw, zw = prepare_weights_asym(W, d, B, wbits)
+    f = acc_asym2_exact_blas if exact_blas else igemm_asym2
+    acc = f(Xq, zx, Wq, zw)
+    Y, Yd = dequant(acc, sx, sw, bias, return_f64=True)
+    return dict(Xq=Xq, sx=sx, zx=zx, Wq=Wq, sw=sw, zw=zw, acc=acc, Y=Y, Yd=Yd)
 
 
 # ---- calibration side: Eq. 5 and the statistics it and the zigzag permutation need ----------

@@ -653,6 +653,113 @@ def test_asym_linear_close_to_exact_product(oracle):
     assert rel_a < 0.02 and rel_a < 1.2 * rel_s
 
 
+# ------------------------------------ asymmetric weight quantiser (Eq. 1-3 on H_t(W), per output channel)
+
+@pytest.mark.parametrize("bits", [4, 6, 8])
+def test_asym_weight_quantiser_brute_force_rational(oracle, bits):
+    # exact rational arithmetic on dyadic values: the float64 oracle must agree code for code
+    cols = [[-3.0, 1.5, 0.25, 2.0, -0.75], [0.5, 4.0, 1.0, 0.125, 2.5], [-1.0, -0.5, -4.0, -2.5, -0.25],
+            [0.0, 0.0, 0.0, 0.0, 0.0]]
+    Wp = np.array(cols, dtype=np.float64).T.copy()           # [K = 5, N = 4]: one list per output channel
+    Wq, sw, zw = oracle.quant_weights_asym(Wp, bits)
+    qmax = 2 ** bits - 1
+
+    def rne(fr):
+        fl = fr.numerator // fr.denominator
+        rem = fr - fl
+        return fl + 1 if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1) else fl
+    for n, col in enumerate(cols):
+        fr = [Fraction(v) for v in col]
+        lo, hi = min(min(fr), Fraction(0)), max(max(fr), Fraction(0))
+        if hi == lo:
+            assert sw[n] == 0 and zw[n] == 0 and not Wq[:, n].any()
+            continue
+        s = (hi - lo) / qmax
+        z = -rne(lo / s)
+        assert zw[n] == z and 0 <= z <= qmax and sw[n] == float(s)
+        for k, v in enumerate(fr):
+            assert Wq[k, n] == min(qmax, max(0, rne(v / s) + z))
+
+
+def test_asym_weight_quantiser_properties(oracle):
+    rng = np.random.default_rng(31)
+    K, N = 256, 48
+    Wp = rng.standard_normal((K, N)) * 0.02 + rng.normal(0, 0.02, (1, N))     # columns with a non-zero mean
+    Wp[:, 3] = np.abs(Wp[:, 3])             # one-sided columns
+    Wp[:, 4] = -np.abs(Wp[:, 4])
+    Wp[:, 5] = 0.0
+    Wq, sw, zw = oracle.quant_weights_asym(Wp, 8)
+    assert zw[3] == 0 and zw[4] == 255 and zw[5] == 0 and sw[5] == 0 and not Wq[:, 5].any()
+    live = np.ones(N, dtype=bool); live[[3, 4, 5]] = False
+    both = live & (Wp.min(axis=0) < 0) & (Wp.max(axis=0) > 0)       # columns that straddle zero use the whole range
+    assert both.sum() > N // 2
+    assert np.all(Wq[:, both].min(axis=0) == 0) and np.all(Wq[:, both].max(axis=0) == 255)
+    deq = sw[None, :] * (Wq.astype(np.float64) - zw[None, :])
+    assert np.all(np.abs(deq - Wp) <= sw[None, :] * (1 + 1e-9))             # rounding + zero-point rounding
+    # a column with a large mean is resolved finer than by the symmetric quantiser (range hi - lo < 2 absmax)
+    Ws, ss = oracle.quant_weights(Wp, 8)
+    assert np.all(sw[live] * 255 <= ss[live] * 254 * (1 + 1e-12))
+    assert np.mean((deq[:, live] - Wp[:, live]) ** 2) < np.mean((ss[live] * Ws[:, live] - Wp[:, live]) ** 2)
+    # re-quantising the dequantised values reproduces the codes
+    Wq2, sw2, zw2 = oracle.quant_weights_asym(deq, 8)
+    assert np.array_equal(Wq2, Wq) and np.array_equal(zw2, zw)
+
+
+def test_asym2_integer_product_is_the_product_of_dequantised_operands(oracle):
+    rng = np.random.default_rng(32)
+    M, K, N = 5, 64, 7
+    Wq = rng.integers(0, 256, size=(K, N)).astype(np.uint8)
+    zw = rng.integers(0, 256, size=N).astype(np.int32)
+    for act_asym in (False, True):
+        if act_asym:
+            Xq = rng.integers(0, 256, size=(M, K)).astype(np.int16)
+            zx = rng.integers(0, 256, size=M).astype(np.int32)
+        else:
+            Xq = rng.integers(-127, 128, size=(M, K)).astype(np.int16)
+            zx = None
+        acc = oracle.igemm_asym2(Xq, zx, Wq, zw)
+        zi = np.zeros(M, dtype=np.int64) if zx is None else zx.astype(np.int64)
+        brute = np.zeros((M, N), dtype=np.int64)
+        for i in range(M):
+            for n in range(N):
+                brute[i, n] = sum((int(Xq[i, k]) - int(zi[i])) * (int(Wq[k, n]) - int(zw[n])) for k in range(K))
+        assert np.array_equal(acc.astype(np.int64), brute)
+        assert np.array_equal(oracle.acc_asym2_exact_blas(Xq, zx, Wq, zw), acc)
+        # the form an int8 matrix unit evaluates: signed codes (q - 128) on both sides (activations as they are
+        # when symmetric) plus the rank-one corrections with the row sums and column sums of the signed codes
+        xs = Xq.astype(np.int64) - (128 if act_asym else 0)
+        zcx = (128 - zi) if act_asym else np.zeros(M, dtype=np.int64)
+        ws = Wq.astype(np.int64) - 128
+        zcw = 128 - zw.astype(np.int64)
+        signed = (xs @ ws + zcx[:, None] * ws.sum(axis=0)[None, :] + xs.sum(axis=1)[:, None] * zcw[None, :]
+                  + K * zcx[:, None] * zcw[None, :])
+        assert np.array_equal(signed, brute)
+    # symmetric weights are the special case z = 128 of the signed form: reduces to the pinned igemm_asym
+    Xq = rng.integers(0, 256, size=(M, K)).astype(np.uint8)
+    zx = rng.integers(0, 256, size=M).astype(np.int32)
+    Ws = rng.integers(-127, 128, size=(K, N)).astype(np.int8)
+    assert np.array_equal(oracle.igemm_asym2(Xq.astype(np.int16), zx, (Ws.astype(np.int16) + 128).astype(np.uint8),
+                                             np.full(N, 128, np.int32)), oracle.igemm_asym(Xq, zx, Ws))
+
+
+@pytest.mark.parametrize("act_asym", [False, True])
+def test_asym_weights_linear_close_to_exact_product(oracle, act_asym):
+    rng = np.random.default_rng(33)
+    M, K, N = 32, 1152, 48
+    Xf = rng.standard_normal((M, K)).astype(np.float32)
+    Xf[:, rng.choice(K, size=8, replace=False)] *= 50.0
+    X = _bf16(Xf)
+    W = (0.02 * rng.standard_normal((K, N))).astype(np.float32)
+    ref = oracle.linear_asym_weights(X, W, act_asym=act_asym)
+    exact = oracle.bf16_to_f64(X) @ W.astype(np.float64)
+    rel_a = np.linalg.norm(ref["Yd"] - exact) / np.linalg.norm(exact)
+    rel_s = np.linalg.norm(oracle.linear(X, W)["Yd"] - exact) / np.linalg.norm(exact)
+    assert rel_a < 0.02 and rel_a < 1.2 * rel_s
+    # the plain loop and the exact library product agree bit for bit
+    ref2 = oracle.linear_asym_weights(X, W, act_asym=act_asym, exact_blas=True)
+    assert np.array_equal(ref["acc"], ref2["acc"]) and np.array_equal(ref["Y"], ref2["Y"])
+
+
 # ------------------------------------ other bit-widths (the W6A6 of Table 3)
 
 @pytest.mark.parametrize("bits", [2, 4, 6, 7, 8])
