@@ -177,6 +177,34 @@ trdq_status trdq_qgemm_asym(const trdq_weights *w, const int8_t *Xq_dev, const f
                             const int32_t *zc_dev, int64_t M, const float *bias_dev, void *Y_dev, int64_t ldy,
                             int32_t *acc_debug_dev, void *stream);
 
+/* ------------------------------------ asymmetric weights (Eq. 1-3 on H_t(W))
+ * The quantiser of Eq. 1-3 with a zero point applied to the transformed weights, one range per
+ * output channel (Sec. 3.1: weights per channel), int8 storage:
+ *   lo_n = min(min_k W'[k,n], 0), hi_n = max(max_k W'[k,n], 0), s_w[n] = (hi_n - lo_n) / 255,
+ *   z_w[n] = -rint(lo_n / s_w[n]),  q[k,n] = clamp(rint(W'[k,n] / s_w[n]) + z_w[n], 0, 255);
+ *   an all-zero channel gives s_w = 0, z_w = 0.
+ * trdq_prepare_weights_asym: arguments and errors of trdq_prepare_weights; wbits must be 8
+ *   (else ERR_UNSUPPORTED).  The set stores q - 128 as int8: trdq_weights_export gives those
+ *   stored codes ([K, N]) and the scales, trdq_weights_export_zero_points the z_w (int32 [N] on the
+ *   host; ERR_MISMATCH for a symmetric set).
+ * trdq_qgemm_asym_weights: the product for such a set,
+ *   acc[i,n] = sum_k (qx[i,k] - zx[i]) (q[k,n] - z_w[n])   (exact in int32; zx = 0 for symmetric codes),
+ *   Y = bf16(acc * s_x[i] * s_w[n] + bias[n]).
+ *   Xq_dev / sx_dev come from trdq_rotate_quant (zc_dev NULL) or from trdq_rotate_quant_asym (zc_dev
+ *   its third output).  rowsum_ws_dev: int32 [M] device workspace; the call fills it with the
+ *   per-token sums of the stored activation codes (a small kernel ahead of the product), which the
+ *   epilogue needs for the z_w term.  acc_debug_dev (optional, int32 [M, N]) receives acc.
+ *   Every other product entry point (trdq_qgemm, trdq_qgemm_asym, trdq_qgemm_tiled,
+ *   trdq_linear_fused) refuses an asymmetric set with ERR_MISMATCH, and this one a symmetric set.
+ *   Other arguments and errors as trdq_qgemm; NULL rowsum_ws -> ERR_NULL. */
+trdq_status trdq_prepare_weights_asym(const float *W_dev, int K, int N, const float *diag_dev,
+                                      int block, int wbits, void *stream, trdq_weights **out);
+trdq_status trdq_weights_export_zero_points(const trdq_weights *w, int32_t *zw_host);
+trdq_status trdq_qgemm_asym_weights(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev,
+                                    const int32_t *zc_dev, int32_t *rowsum_ws_dev, int64_t M,
+                                    const float *bias_dev, void *Y_dev, int64_t ldy,
+                                    int32_t *acc_debug_dev, void *stream);
+
 /* ---------------------------------------------------------- calibration side
  * The per-channel statistics that the smoothing diagonal (Sec. 3.1, Eq. 5) and the zigzag
  * permutation (Sec. 3.2) are computed from, and Eq. 5 itself.  Offline, once per time-step group,

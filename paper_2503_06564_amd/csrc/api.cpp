@@ -262,6 +262,64 @@ trdq_status trdq_prepare_weights(const float *W_dev, int K, int N, const float *
     return prepare_weights_impl(W_dev, K, N, diag_dev, nullptr, block, wbits, stream, out);
 }
 
+trdq_status trdq_prepare_weights_asym(const float *W_dev, int K, int N, const float *diag_dev,
+                                      int block, int wbits, void *stream, trdq_weights **out)
+{
+    if (!out) return TRDQ_ERR_NULL;
+    *out = nullptr;
+    if (!W_dev) return TRDQ_ERR_NULL;
+    if (block != trdq::kBlock || wbits != 8) return TRDQ_ERR_UNSUPPORTED;
+    if (K <= 0 || N <= 0 || K % trdq::kBlock != 0 || N % 16 != 0) return TRDQ_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int nb = K / trdq::kBlock;
+    trdq_weights *w = new (std::nothrow) trdq_weights;
+    if (!w) return TRDQ_ERR_ALLOC;
+    w->K = K; w->N = N; w->wbits = 8; w->qbits = 8;
+    w->rotation = trdq::kRotHadamard;
+    float *Wrot = nullptr, *amax = nullptr, *lohi = nullptr;
+    trdq_status rc = TRDQ_OK;
+    bool ok = true;
+    if (hipGetDevice(&w->device) != hipSuccess) { rc = TRDQ_ERR_HIP; goto fail; }
+    if (hipMalloc(&w->codes, (size_t)K * N) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&w->scales), (size_t)N * sizeof(float)) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&w->colsum), (size_t)N * sizeof(int32_t)) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&w->zcw), (size_t)N * sizeof(int32_t)) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&Wrot), (size_t)K * N * sizeof(float)) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&amax), (size_t)nb * N * sizeof(float)) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&lohi), (size_t)2 * N * sizeof(float)) != hipSuccess) {
+        rc = TRDQ_ERR_ALLOC;
+        goto fail;
+    }
+    ok = trdq::launch_prepare_rotate(W_dev, K, N, diag_dev, nullptr, Wrot, amax, st) == hipSuccess &&
+         trdq::launch_prepare_quant_asym(Wrot, lohi, K, N, 0.08838834764831845f, w->codes, w->scales, w->zcw, st) == hipSuccess &&
+         trdq::launch_weight_colsum(w->codes, K, N, w->colsum, st) == hipSuccess;
+    if (!ok || hipStreamSynchronize(st) != hipSuccess) { rc = TRDQ_ERR_HIP; goto fail; }
+    (void)hipFree(Wrot); (void)hipFree(amax); (void)hipFree(lohi);
+    *out = w;
+    return TRDQ_OK;
+fail:
+    (void)hipGetLastError();
+    if (Wrot) (void)hipFree(Wrot);
+    if (amax) (void)hipFree(amax);
+    if (lohi) (void)hipFree(lohi);
+    if (w->codes) (void)hipFree(w->codes);
+    if (w->scales) (void)hipFree(w->scales);
+    if (w->colsum) (void)hipFree(w->colsum);
+    if (w->zcw) (void)hipFree(w->zcw);
+    delete w;
+    return rc;
+}
+
+trdq_status trdq_weights_export_zero_points(const trdq_weights *w, int32_t *zw_host)
+{
+    if (!w || !zw_host) return TRDQ_ERR_NULL;
+    if (!w->zcw) return TRDQ_ERR_MISMATCH;
+    if (hipDeviceSynchronize() != hipSuccess) return TRDQ_ERR_HIP;
+    if (hipMemcpy(zw_host, w->zcw, sizeof(int32_t) * (size_t)w->N, hipMemcpyDeviceToHost) != hipSuccess) return TRDQ_ERR_HIP;
+    for (int n = 0; n < w->N; ++n) zw_host[n] = 128 - zw_host[n];
+    return TRDQ_OK;
+}
+
 /* ---------------------------------------------------- dense rotation blocks */
 
 trdq_status trdq_rotation_create(const float *R_dev, const float *diag_dev, int K, int block, void *stream,
@@ -639,6 +697,7 @@ void trdq_weights_destroy(trdq_weights *w)
     if (w->codes_tiled) (void)hipFree(w->codes_tiled);
     if (w->scales) (void)hipFree(w->scales);
     if (w->colsum) (void)hipFree(w->colsum);
+    if (w->zcw) (void)hipFree(w->zcw);
     if (w->colsumw) (void)hipFree(w->colsumw);
     delete w;
 }
@@ -827,10 +886,32 @@ trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float 
     if (M > 0 && (!Xq_dev || !sx_dev)) return TRDQ_ERR_NULL;
     if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || (acc_debug_dev && !aligned(acc_debug_dev, 16)))
         return TRDQ_ERR_SHAPE;
+    if (w->zcw) return TRDQ_ERR_MISMATCH;       // asymmetric weights need the row sums: trdq_qgemm_asym_weights
     if (M == 0) return TRDQ_OK;
     if (trdq_status rd = check_device(w->device); rd != TRDQ_OK) return rd;
     return hip_status(trdq::launch_qgemm(*w, Xq_dev, sx_dev, nullptr, M, bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
                                          acc_debug_dev, g_variant.load(std::memory_order_relaxed), static_cast<hipStream_t>(stream)));
+}
+
+trdq_status trdq_qgemm_asym_weights(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev,
+                                    const int32_t *zc_dev, int32_t *rowsum_ws_dev, int64_t M,
+                                    const float *bias_dev, void *Y_dev, int64_t ldy,
+                                    int32_t *acc_debug_dev, void *stream)
+{
+    if (!w) return TRDQ_ERR_NULL;
+    trdq_status rc = check_out_args(Y_dev, M, w->N, ldy, bias_dev);
+    if (rc != TRDQ_OK) return rc;
+    if (M > 0 && (!Xq_dev || !sx_dev || !rowsum_ws_dev)) return TRDQ_ERR_NULL;
+    if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || !aligned(rowsum_ws_dev, 4) || (zc_dev && !aligned(zc_dev, 4)) ||
+        (acc_debug_dev && !aligned(acc_debug_dev, 16)))
+        return TRDQ_ERR_SHAPE;
+    if (!w->zcw) return TRDQ_ERR_MISMATCH;
+    if (M == 0) return TRDQ_OK;
+    if (trdq_status rd = check_device(w->device); rd != TRDQ_OK) return rd;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (trdq::launch_xq_rowsum(Xq_dev, M, w->K, rowsum_ws_dev, st) != hipSuccess) { (void)hipGetLastError(); return TRDQ_ERR_HIP; }
+    return hip_status(trdq::launch_qgemm(*w, Xq_dev, sx_dev, zc_dev, M, bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
+                                         acc_debug_dev, -1, st, rowsum_ws_dev));
 }
 
 trdq_status trdq_qgemm_asym(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev,
@@ -844,6 +925,7 @@ trdq_status trdq_qgemm_asym(const trdq_weights *w, const int8_t *Xq_dev, const f
     if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || !aligned(zc_dev, 4) ||
         (acc_debug_dev && !aligned(acc_debug_dev, 16)))
         return TRDQ_ERR_SHAPE;
+    if (w->zcw) return TRDQ_ERR_MISMATCH;       // asymmetric weights: trdq_qgemm_asym_weights
     if (M == 0) return TRDQ_OK;
     if (trdq_status rd = check_device(w->device); rd != TRDQ_OK) return rd;
     return hip_status(trdq::launch_qgemm(*w, Xq_dev, sx_dev, zc_dev, M, bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
@@ -862,6 +944,7 @@ trdq_status trdq_linear_fused(const void *X_dev, int64_t M, int64_t ldx, const f
     if (diag_dev && !aligned(diag_dev, 16)) return TRDQ_ERR_SHAPE;
     if (!trdq::fused_supports(w->K)) return TRDQ_ERR_UNSUPPORTED;
     if (w->rotation != trdq::kRotHadamard) return TRDQ_ERR_MISMATCH;   // the kernel applies the one-rotation transform
+    if (w->zcw) return TRDQ_ERR_MISMATCH;                              // ... and carries no zero points
     if (M == 0) return TRDQ_OK;
     if (trdq_status rd = check_device(w->device); rd != TRDQ_OK) return rd;
     return hip_status(trdq::launch_linear_fused(*w, static_cast<const uint16_t *>(X_dev), M, ldx, diag_dev,

@@ -23,6 +23,10 @@ struct GemmArgs {
     const int32_t *zc = nullptr;
     const int32_t *colsum = nullptr;
     const float *colsumw = nullptr;
+    // asymmetric weights: zcw[n] = 128 - z_w[n] and rowsum[i] = sum_k Xq[i][k] of the stored activation codes; the
+    // integer sum of the product is acc + zc[i] colsum[n] + zcw[n] (rowsum[i] + K zc[i]).  Null otherwise.
+    const int32_t *zcw = nullptr;
+    const int32_t *rowsum = nullptr;
     int64_t M, ldy;
     int K, N;
     int tiles_m, tiles_n;

@@ -184,6 +184,67 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_quant_kernel(
     }
 }
 
+// Asymmetric weights (Eq. 1-3 on H_t(W), one range per output channel).  Kernel A: lo[n] = min(min_k Wrot[k,n], 0),
+// hi[n] = max(max_k Wrot[k,n], 0) over the whole column, one thread per channel.
+__global__ __launch_bounds__(kPrepThreads) void column_minmax_kernel(const float *__restrict__ Wrot, int K, int N,
+                                                                      float *__restrict__ lo, float *__restrict__ hi)
+{
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    float a = 0.0f, b = 0.0f;
+    for (int k = 0; k < K; ++k) {
+        const float w = Wrot[(size_t)k * N + n];
+        a = fminf(a, w);
+        b = fmaxf(b, w);
+    }
+    lo[n] = a;
+    hi[n] = b;
+}
+
+// Kernel B: s[n] = (hi - lo) * norm / 255, z[n] = -rint(lo * 255 / (hi - lo)), code = clamp(rint(w * 255 / (hi - lo)) + z,
+// 0, 255), stored as code - 128 (the operand type of the int8 matrix instruction) in the [N, K] layout; zcw[n] = 128 - z,
+// so that q - z = stored + zcw.  The integer offset rides in the rounding constant of one fused multiply-add.
+__global__ __launch_bounds__(kPrepThreads) void prepare_quant_asym_kernel(
+    const float *__restrict__ Wrot, const float *__restrict__ lo, const float *__restrict__ hi, int K, int N, float norm,
+    int8_t *__restrict__ codes, float *__restrict__ scales, int32_t *__restrict__ zcw)
+{
+    __shared__ int8_t q8[kCols][kBlock + 16];
+    __shared__ float inv_s[kCols], magic_s[kCols];
+    const int b = blockIdx.y;
+    const int n0 = blockIdx.x * kCols;
+    if (threadIdx.x < kCols) {
+        const int n = n0 + threadIdx.x;
+        float inv = 0.0f, z = 0.0f;
+        if (n < N) {
+            const float range = hi[n] - lo[n];
+            inv = range > 0.0f ? 255.0f / range : 0.0f;
+            z = -rintf(lo[n] * inv);
+            if (b == 0) {
+                scales[n] = range * (norm / 255.0f);
+                zcw[n] = 128 - (int)z;
+            }
+        }
+        inv_s[threadIdx.x] = inv;
+        magic_s[threadIdx.x] = kRoundMagic + (z - 128.0f);
+    }
+    __syncthreads();
+    const int c = threadIdx.x % kCols;
+    const int q = threadIdx.x / kCols;
+    const int n = n0 + c;
+    for (int k = q; k < kBlock; k += 4) {
+        const float w = n < N ? Wrot[(size_t)(b * kBlock + k) * N + n] : 0.0f;
+        const float t = __builtin_fmaf(w, inv_s[c], magic_s[c]);
+        q8[c][k] = (int8_t)(__float_as_uint(__builtin_amdgcn_fmed3f(t, kRoundMagic - 128.0f, kRoundMagic + 127.0f)) & 0xFF);
+    }
+    __syncthreads();
+    for (int ch = threadIdx.x; ch < kCols * (kBlock / 16); ch += kPrepThreads) {
+        const int cc = ch / (kBlock / 16), kk = (ch % (kBlock / 16)) * 16;
+        if (n0 + cc < N)
+            *reinterpret_cast<uint4 *>(codes + (size_t)(n0 + cc) * K + b * kBlock + kk) =
+                *reinterpret_cast<const uint4 *>(&q8[cc][kk]);
+    }
+}
+
 // colsum[n] = sum_k codes[n][k]: one wave per output channel (the zero-point term of asymmetric
 // activations needs it in the product's epilogue)
 __global__ __launch_bounds__(64) void weight_colsum_kernel(const int8_t *__restrict__ codes, int K, int N,
@@ -206,6 +267,47 @@ __global__ __launch_bounds__(64) void weight_colsum_kernel(const int8_t *__restr
 }
 
 }  // namespace
+
+hipError_t launch_prepare_quant_asym(const float *Wrot, float *lohi, int K, int N, float norm, void *codes, float *scales,
+                                     int32_t *zcw, hipStream_t st)
+{
+    float *lo = lohi, *hi = lohi + N;
+    hipLaunchKernelGGL(column_minmax_kernel, dim3((N + kPrepThreads - 1) / kPrepThreads), dim3(kPrepThreads), 0, st, Wrot, K, N,
+                       lo, hi);
+    dim3 grid((N + kCols - 1) / kCols, K / kBlock);
+    hipLaunchKernelGGL(prepare_quant_asym_kernel, grid, dim3(kPrepThreads), 0, st, Wrot, lo, hi, K, N, norm,
+                       static_cast<int8_t *>(codes), scales, zcw);
+    return hipGetLastError();
+}
+
+// rowsum[i] = sum_k Xq[i][k]: one wave per token (the zero-point term of asymmetric weights needs it)
+__global__ __launch_bounds__(256) void xq_rowsum_kernel(const int8_t *__restrict__ Xq, int64_t M, int K,
+                                                        int32_t *__restrict__ rowsum)
+{
+    const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= M) return;
+    const int lane = threadIdx.x & 63;
+    const int8_t *row = Xq + i * K;
+    int t = 0;
+    for (int k = lane * 16; k < K; k += 64 * 16) {
+        const int4 v = *reinterpret_cast<const int4 *>(row + k);
+        const int wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            t += (int)(int8_t)(wv[u] & 0xFF) + (int)(int8_t)((wv[u] >> 8) & 0xFF) +
+                 (int)(int8_t)((wv[u] >> 16) & 0xFF) + (wv[u] >> 24);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o);
+    if (lane == 0) rowsum[i] = t;
+}
+
+hipError_t launch_xq_rowsum(const int8_t *Xq, int64_t M, int K, int32_t *rowsum, hipStream_t st)
+{
+    if (M <= 0) return hipSuccess;
+    hipLaunchKernelGGL(xq_rowsum_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, Xq, M, K, rowsum);
+    return hipGetLastError();
+}
 
 hipError_t launch_weight_colsum(const void *codes, int K, int N, int32_t *colsum, hipStream_t st)
 {

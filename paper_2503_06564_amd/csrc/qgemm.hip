@@ -253,9 +253,20 @@ int qgemm_num_variants() { return kRegVariants + dma_num_variants() + 1; }
 
 hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, const int32_t *zc, int64_t M,
                         const float *bias, uint16_t *Y, int64_t ldy, int32_t *acc_debug,
-                        int variant, hipStream_t st)
+                        int variant, hipStream_t st, const int32_t *rowsum)
 {
     if (M == 0) return hipSuccess;
+    if (w.zcw) {
+        // asymmetric weights (int8, per output channel): zero-point terms on both sides in the epilogue of
+        // the kernel that takes any shape
+        if (w.wbits != 8 || !w.colsum || !rowsum) return hipErrorInvalidValue;
+        GemmArgs a;
+        a.Xq = Xq; a.Wc = w.codes; a.sx = sx; a.sw = w.scales; a.bias = bias; a.Y = Y;
+        a.acc_debug = acc_debug; a.M = M; a.ldy = ldy; a.K = w.K; a.N = w.N;
+        a.tiles_m = a.tiles_n = 0;
+        a.zc = zc; a.colsum = w.colsum; a.zcw = w.zcw; a.rowsum = rowsum;
+        return launch_qgemm8_asym(a, acc_debug != nullptr, 0, st);
+    }
     // A ragged token count would send the whole product to the kernel that takes any shape.  With the
     // built-in choice and int8 weights, the whole 256-token (or 128-token) panels go to the fast kernels
     // and only the remaining rows to that kernel, as a second launch on the same stream.

@@ -28,12 +28,14 @@ __device__ __forceinline__ void epilogue_w8(const v4i (&acc_in)[TN][TM], const G
                                             int64_t m_lane, int n_lane)
 {
     float sxm[TM];
-    int zcm[TM];
+    int zcm[TM], rsm[TM];
 #pragma unroll
     for (int b = 0; b < TM; ++b) {
         const int64_t m = m_lane + b * 16;
         sxm[b] = (FULL || m < g.M) ? g.sx[m] : 0.0f;
-        zcm[b] = (ASYM && (FULL || m < g.M)) ? g.zc[m] : 0;
+        zcm[b] = (ASYM && g.zc && (FULL || m < g.M)) ? g.zc[m] : 0;
+        // asymmetric weights: the token's factor of zcw[n] in the zero-point terms
+        rsm[b] = (ASYM && g.zcw && (FULL || m < g.M)) ? g.rowsum[m] + g.K * zcm[b] : 0;
     }
     const bool has_bias = g.bias != nullptr;
 #pragma unroll
@@ -41,18 +43,21 @@ __device__ __forceinline__ void epilogue_w8(const v4i (&acc_in)[TN][TM], const G
         const int n = n_lane + a * 16;
         const bool n_ok = FULL || n < g.N;
         float4 s = make_float4(0.f, 0.f, 0.f, 0.f), bi = s;
-        int4 cs = make_int4(0, 0, 0, 0);
+        int4 cs = make_int4(0, 0, 0, 0), zw = cs;
         if (n_ok) {
             s = *reinterpret_cast<const float4 *>(g.sw + n);
             if (has_bias) bi = *reinterpret_cast<const float4 *>(g.bias + n);
             if (ASYM) cs = *reinterpret_cast<const int4 *>(g.colsum + n);
+            if (ASYM && g.zcw) zw = *reinterpret_cast<const int4 *>(g.zcw + n);
         }
 #pragma unroll
         for (int b = 0; b < TM; ++b) {
             const int64_t m = m_lane + b * 16;
             v4i acc[1][1];       // the tile's sums, with the zero-point term when there is one
             acc[0][0] = acc_in[a][b];
-            if (ASYM) acc[0][0] += v4i{zcm[b] * cs.x, zcm[b] * cs.y, zcm[b] * cs.z, zcm[b] * cs.w};
+            if (ASYM)
+                acc[0][0] += v4i{zcm[b] * cs.x + rsm[b] * zw.x, zcm[b] * cs.y + rsm[b] * zw.y,
+                                 zcm[b] * cs.z + rsm[b] * zw.z, zcm[b] * cs.w + rsm[b] * zw.w};
             const float y0 = (float)acc[0][0][0] * sxm[b] * s.x + bi.x;
             const float y1 = (float)acc[0][0][1] * sxm[b] * s.y + bi.y;
             const float y2 = (float)acc[0][0][2] * sxm[b] * s.z + bi.z;
@@ -1143,8 +1148,11 @@ hipError_t launch_persist(const GemmArgs &a, bool debug, hipStream_t st)
 // kernels of the table below (they fall back to the ring kernel for shapes they do not take)
 hipError_t launch_qgemm8_asym(const GemmArgs &a, bool debug, int kind, hipStream_t st)
 {
-    if (!a.zc || !a.colsum || a.K % 128 != 0 || a.N < 4) return hipErrorInvalidValue;
-    if (a.K >= 65536) kind = 0;          // the pipelined kernels multiply column sums as 24-bit values
+    if ((!a.zc && !a.zcw) || !a.colsum || a.K % 128 != 0 || a.N < 4) return hipErrorInvalidValue;
+    if (a.zcw && !a.rowsum) return hipErrorInvalidValue;
+    // the pipelined kernels multiply column sums as 24-bit values and carry the activations' term only:
+    // long K and asymmetric weights take the kernel that adds the terms in its epilogue
+    if (a.K >= 65536 || a.zcw) kind = 0;
     switch (kind) {
         case 0: return launch_ring_asym(a, debug, st);
         case 14: return launch_pipe<128, 144, 4, 4, 1>(a, debug, st);

@@ -28,6 +28,7 @@ struct Weights {
     void *codes_tiled = nullptr; // int8 weights with N % 144 == 0: the same codes in 1 KB blocks of 16 channels x 64 k
     int rotation = 0;            // which transform was folded in (kRot*): the activation side must apply the same one
     int32_t *colsum = nullptr;   // int8 weights: sum over k of the codes of every output channel [N]
+    int32_t *zcw = nullptr;      // asymmetric int8 weights (Eq. 1-3 per output channel): 128 - z_w [N]; codes hold q - 128
     float *colsumw = nullptr;    // int4 weights: 16 * sum_g s_w[g][n] * (sum of the codes of group g) [N]
     int device = 0;
 };
@@ -78,6 +79,10 @@ hipError_t launch_rotate_quant_rpr(const uint16_t *X, int64_t M, int K, int64_t 
 // norm: what undoes the unnormalised butterflies (1/sqrt(128) per rotation applied).
 hipError_t launch_prepare_rotate(const float *W, int K, int N, const float *diag, const int32_t *perm,
                                  float *Wrot, float *amax, hipStream_t st);
+// asymmetric weight quantiser: lohi = scratch of 2 N floats; codes [N, K] = q - 128, scales [N], zcw [N] = 128 - z
+hipError_t launch_prepare_quant_asym(const float *Wrot, float *lohi, int K, int N, float norm, void *codes, float *scales,
+                                     int32_t *zcw, hipStream_t st);
+hipError_t launch_xq_rowsum(const int8_t *Xq, int64_t M, int K, int32_t *rowsum, hipStream_t st);
 hipError_t launch_weight_colsumw4(const void *codes, const float *scales, int K, int N, float *colsumw, hipStream_t st);
 hipError_t launch_prepare_quant(const float *Wrot, const float *amax, int K, int N, int wbits, float norm,
                                 void *codes, float *scales, hipStream_t st);   // wbits 8, 6 (8-bit layout) or 4
@@ -92,9 +97,10 @@ int qgemm_num_variants();
 // colsum[n] = sum_k codes[n][k] for int8 codes stored [N][K]
 hipError_t launch_weight_colsum(const void *codes, int K, int N, int32_t *colsum, hipStream_t st);
 // zc: null, or the per-token zero-point terms of asymmetric activations (int8 weights only)
+// rowsum: with asymmetric weights (w.zcw), the per-token sums of the activation codes as stored
 hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, const int32_t *zc, int64_t M,
                         const float *bias, uint16_t *Y, int64_t ldy, int32_t *acc_debug,
-                        int variant, hipStream_t st);
+                        int variant, hipStream_t st, const int32_t *rowsum = nullptr);
 
 hipError_t launch_cosine_similarity(const uint16_t *A, const uint16_t *B, int n_seg, int64_t seg_len,
                                     int64_t stride_a, int64_t stride_b, double *acc_ws, float *out, hipStream_t st);

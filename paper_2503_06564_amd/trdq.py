@@ -31,6 +31,7 @@ SYMBOLS = [
     "trdq_peak_mfma_i8", "trdq_peak_stream",
     "trdq_xq_tiled_nbytes", "trdq_rotate_quant_tiled", "trdq_xq_untile", "trdq_qgemm_tiled_supported", "trdq_qgemm_tiled_preferred",
     "trdq_qgemm_tiled",
+    "trdq_prepare_weights_asym", "trdq_weights_export_zero_points", "trdq_qgemm_asym_weights",
 ]
 
 _lib = None
@@ -90,6 +91,9 @@ def lib():
         L.trdq_qgemm_tiled_supported.argtypes = [p, i64]
         L.trdq_qgemm_tiled_preferred.argtypes = [p, i64]
         L.trdq_qgemm_tiled.argtypes = [p, p, p, i64, p, p, i64, p, p]
+        L.trdq_prepare_weights_asym.argtypes = [p, i32, i32, p, i32, i32, p, C.POINTER(p)]
+        L.trdq_weights_export_zero_points.argtypes = [p, p]
+        L.trdq_qgemm_asym_weights.argtypes = [p, p, p, p, p, i64, p, p, i64, p, p]
         L.trdq_share_plan.argtypes = [p, i32, i32, C.c_float, p]
         L.trdq_peak_mfma_i8.argtypes = [p, i32, i32, i32, C.POINTER(C.c_int64), p]
         L.trdq_peak_stream.argtypes = [p, p, i64, p]
@@ -454,6 +458,32 @@ def qgemm_asym(w, Xq, sx, zc, Y, bias=None, acc_debug=None, stream=None):
     ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
     _check(lib().trdq_qgemm_asym(w.handle, _ptr(Xq), _ptr(sx), _ptr(zc), M, _ptr(bias), _ptr(Y), ldy,
                                  _ptr(acc_debug), _stream(stream)), "trdq_qgemm_asym")
+
+
+def prepare_weights_asym(W, diag, block=BLOCK, wbits=8, stream=None):
+    """Weights with a zero point per output channel (Eq. 1-3 on H_t(W)); int8 storage of q - 128."""
+    K, N = W.shape
+    h = C.c_void_p()
+    _check(lib().trdq_prepare_weights_asym(_ptr(W), K, N, _ptr(diag), block, wbits, _stream(stream), C.byref(h)),
+           "trdq_prepare_weights_asym")
+    return Weights(h)
+
+
+def weights_zero_points(w):
+    """z_w int32 [N] (host) of an asymmetric weight set."""
+    import numpy as np
+    K, N, _ = w.info()
+    z = np.empty(N, dtype=np.int32)
+    _check(lib().trdq_weights_export_zero_points(w.handle, _ptr(z)), "trdq_weights_export_zero_points")
+    return z
+
+
+def qgemm_asym_weights(w, Xq, sx, zc, rowsum_ws, Y, bias=None, acc_debug=None, stream=None):
+    """Product against asymmetric weights; zc None for symmetric activation codes; rowsum_ws int32 [M] workspace."""
+    M = Xq.shape[0]
+    ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
+    _check(lib().trdq_qgemm_asym_weights(w.handle, _ptr(Xq), _ptr(sx), _ptr(zc), _ptr(rowsum_ws), M, _ptr(bias),
+                                         _ptr(Y), ldy, _ptr(acc_debug), _stream(stream)), "trdq_qgemm_asym_weights")
 
 
 def qgemm(w, Xq, sx, Y, bias=None, acc_debug=None, stream=None):

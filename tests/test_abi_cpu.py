@@ -284,3 +284,15 @@ def test_dense_calibration_argument_errors_before_any_gpu_call():
     out = C.c_void_p()
     assert L.trdq_prepare_weights_dense_rpr(0x1000, 256, 64, None, 0x2000, None, 8, None, C.byref(out)) == trdq.ERR_NULL
     assert L.trdq_rotate_quant_dense_rpr(0x1000, 4, 256, None, 0x2000, None, 0x3000, 0x4000, None) == trdq.ERR_NULL
+
+
+def test_asym_weight_calls_check_arguments_before_any_gpu_call():
+    L = trdq.lib()
+    import ctypes as C
+    h = C.c_void_p()
+    assert L.trdq_prepare_weights_asym(None, 256, 16, None, 128, 8, None, C.byref(h)) == trdq.ERR_NULL
+    assert L.trdq_prepare_weights_asym(0x1000, 256, 16, None, 128, 4, None, C.byref(h)) == trdq.ERR_UNSUPPORTED
+    assert L.trdq_prepare_weights_asym(0x1000, 200, 16, None, 128, 8, None, C.byref(h)) == trdq.ERR_SHAPE
+    assert L.trdq_prepare_weights_asym(0x1000, 256, 16, None, 128, 8, None, None) == trdq.ERR_NULL
+    assert L.trdq_weights_export_zero_points(None, 0x1000) == trdq.ERR_NULL
+    assert L.trdq_qgemm_asym_weights(None, 0x1000, 0x2000, None, 0x3000, 4, None, 0x4000, 16, None, None) == trdq.ERR_NULL
