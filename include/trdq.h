@@ -366,6 +366,15 @@ trdq_status trdq_rotate_quant_rpr(const void *X_dev, int64_t M, int K, int64_t l
                                   const float *diag_dev, const int32_t *perm_dev, int block,
                                   int8_t *Xq_dev, float *sx_dev, const trdq_weights *next, void *stream);
 
+/* trdq_rotate_quant_rpr with the asymmetric per-token quantiser of Eq. 1-3 on the fully transformed
+ * activations: codes q - 128 and zc_dev[i] = 128 - z_i exactly as trdq_rotate_quant_asym writes them
+ * (to be multiplied by trdq_qgemm_asym against weights from trdq_prepare_weights_rpr).
+ * Errors as trdq_rotate_quant_rpr; NULL zc -> ERR_NULL. */
+trdq_status trdq_rotate_quant_rpr_asym(const void *X_dev, int64_t M, int K, int64_t ldx,
+                                       const float *diag_dev, const int32_t *perm_dev, int block,
+                                       int8_t *Xq_dev, float *sx_dev, int32_t *zc_dev, const trdq_weights *next,
+                                       void *stream);
+
 /* The integer product G_t(X_t) . H_t(W) on the codes, with the dequantising epilogue:
  *   wbits 8: Y[i,n] = bf16( float(acc[i,n]) * s_x[i] * s_w[n] + bias[n] ),  acc = Xq . Wq  (int32, exact)
  *   wbits 4: Y[i,n] = bf16( s_x[i] * sum_g s_w[g,n] * float(acc_g[i,n]) + bias[n] ),

@@ -328,6 +328,15 @@ def linear_asym_weights(X_bf16, W, d=None, bias=None, B=128, exact_blas=False, a
     return dict(Xq=Xq, sx=sx, zx=zx, Wq=Wq, sw=sw, zw=zw, acc=acc, Y=Y, Yd=Yd)
 
 
+def linear_rpr_asym(X_bf16, W, d, perm, bias=None, B=128, exact_blas=False):
+    """The full G_t of Eq. 9 followed by the asymmetric per-token quantiser of Eq. 1-3; weights as linear_rpr (int8)."""
+    Xq, sx, zx = quant_tokens_asym(rotate_rpr(X_bf16, d, perm, B))
+    Wq, sw = prepare_weights_rpr(W, d, perm, B, 8)
+    acc = acc_asym_exact_blas(Xq, zx, Wq) if exact_blas else igemm_asym(Xq, zx, Wq)
+    Y, Yd = dequant(acc, sx, sw, bias, return_f64=True)
+    return dict(Xq=Xq, sx=sx, zx=zx, Wq=Wq, sw=sw, acc=acc, Y=Y, Yd=Yd)
+
+
 # ---- calibration side: Eq. 5 and the statistics it and the zigzag permutation need ----------
 
 # ---- greedy dense block rotations (Sec. 3.2, Eq. 6-7 and the BlockDiag equation) ---------------

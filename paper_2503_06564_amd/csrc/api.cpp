@@ -876,6 +876,33 @@ trdq_status trdq_qgemm_tiled(const trdq_weights *w, const int8_t *Xt_dev, const 
                                                acc_debug_dev, static_cast<hipStream_t>(stream)));
 }
 
+trdq_status trdq_rotate_quant_rpr_asym(const void *X_dev, int64_t M, int K, int64_t ldx,
+                                       const float *diag_dev, const int32_t *perm_dev, int block,
+                                       int8_t *Xq_dev, float *sx_dev, int32_t *zc_dev, const trdq_weights *next,
+                                       void *stream)
+{
+    trdq_status rc = check_rotate_args(X_dev, M, K, ldx, block);
+    if (rc != TRDQ_OK) return rc;
+    if (!perm_dev) return TRDQ_ERR_NULL;
+    if (M > 0 && (!Xq_dev || !sx_dev || !zc_dev)) return TRDQ_ERR_NULL;
+    if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || !aligned(zc_dev, 4) || !aligned(perm_dev, 16) ||
+        (diag_dev && !aligned(diag_dev, 16)))
+        return TRDQ_ERR_SHAPE;
+    if (!trdq::rotate_quant_rpr_supports(K)) return TRDQ_ERR_UNSUPPORTED;
+    if (M == 0) return TRDQ_OK;
+    const void *warm = nullptr;
+    int64_t warm_bytes = 0;
+    if (next && next->codes) {
+        if (trdq_status rd = check_device(next->device); rd != TRDQ_OK) return rd;
+        warm = next->codes;
+        warm_bytes = (int64_t)next->N * next->K / (next->wbits == 4 ? 2 : 1);
+        warm_bytes -= warm_bytes % 16;
+    }
+    return hip_status(trdq::launch_rotate_quant_rpr(static_cast<const uint16_t *>(X_dev), M, K, ldx, diag_dev,
+                                                    perm_dev, Xq_dev, sx_dev, warm, warm_bytes,
+                                                    static_cast<hipStream_t>(stream), zc_dev));
+}
+
 trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float *sx_dev, int64_t M,
                        const float *bias_dev, void *Y_dev, int64_t ldy,
                        int32_t *acc_debug_dev, void *stream)

@@ -45,16 +45,18 @@ template <int TOK, int SPW>
 __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
     const uint16_t *__restrict__ X, int64_t M, int nb, int64_t ldx,
     const float *__restrict__ diag, const int32_t *__restrict__ perm,
-    int8_t *__restrict__ Xq, float *__restrict__ sx,
+    int8_t *__restrict__ Xq, float *__restrict__ sx, int32_t *__restrict__ zc,
     const uint4 *__restrict__ warm, int64_t warm_chunks)
 {
+    // zc != null: the asymmetric quantiser of Eq. 1-3 (codes stored as q - 128, zc[i] = 128 - z_i), as in rotate_quant
     static_assert(TOK == 16 || TOK == 8, "16 or 8 tokens per workgroup");
+    const bool asym = zc != nullptr;
     extern __shared__ __align__(16) float lds[];
     const int K = nb * kBlock;
     const int nw = blockDim.x >> 6;
     const int rowf = K + kRowPad;                    // floats per LDS row
     float *const T = lds;                            // [TOK][rowf]: first-rotation output
-    float *const amax_s = lds + (size_t)TOK * rowf;  // [nw][16]; after it a 1 KB dump area for the weight copies
+    float *const amax_s = lds + (size_t)TOK * rowf;  // [2][nw][16] (maxima, minima); after it a 1 KB dump area for the weight copies
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -119,7 +121,7 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
     // rotate_quant): up to four direct-to-LDS copies per wave into a dump area nobody reads.
     if (warm_chunks > 0) {
         const uint32_t dump = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float *)lds +
-                              (uint32_t)(sizeof(float) * ((size_t)TOK * rowf + (size_t)nw * 16));
+                              (uint32_t)(sizeof(float) * ((size_t)TOK * rowf + (size_t)nw * 32));
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int64_t c0 = ((int64_t)t * gridDim.x + blockIdx.x) * blockDim.x + (wave << 6);   // wave-uniform
@@ -143,6 +145,7 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
 
     v4f out[SPW][8];
     float amax = 0.0f;
+    float amin = 0.0f;                               // asymmetric: the token minimum (<= 0); amax is then the maximum (>= 0)
     const float *Trow = T + (size_t)rt * rowf;
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
@@ -171,8 +174,13 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
                 for (int s = 0; s < 4; ++s)
                     acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hs[s], w[s][j], acc, 0, 0, 0);
                 out[i][j] = acc;
-                amax = fmaxf(fmaxf(amax, fabsf(acc[0])), fabsf(acc[1]));
-                amax = fmaxf(fmaxf(amax, fabsf(acc[2])), fabsf(acc[3]));
+                if (asym) {
+                    amax = fmaxf(fmaxf(amax, fmaxf(acc[0], acc[1])), fmaxf(acc[2], acc[3]));
+                    amin = fminf(fminf(amin, fminf(acc[0], acc[1])), fminf(acc[2], acc[3]));
+                } else {
+                    amax = fmaxf(fmaxf(amax, fabsf(acc[0])), fabsf(acc[1]));
+                    amax = fmaxf(fmaxf(amax, fabsf(acc[2])), fabsf(acc[3]));
+                }
             }
         }
     }
@@ -181,13 +189,41 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
     amax = fmaxf(amax, __shfl_xor(amax, 16));
     amax = fmaxf(amax, __shfl_xor(amax, 32));
     if (BPI == 2) amax = fmaxf(amax, __shfl_xor(amax, 8));       // the token's other block in this wave
-    if (g == 0) amax_s[wave * 16 + r] = amax;
+    amin = fminf(amin, __shfl_xor(amin, 16));
+    amin = fminf(amin, __shfl_xor(amin, 32));
+    if (BPI == 2) amin = fminf(amin, __shfl_xor(amin, 8));
+    if (g == 0) {
+        amax_s[wave * 16 + r] = amax;
+        amax_s[(nw + wave) * 16 + r] = amin;
+    }
     __syncthreads();
-    for (int wv = 0; wv < nw; ++wv) amax = fmaxf(amax, amax_s[wv * 16 + r]);
+    for (int wv = 0; wv < nw; ++wv) {
+        amax = fmaxf(amax, amax_s[wv * 16 + r]);
+        amin = fminf(amin, amax_s[(nw + wv) * 16 + r]);
+    }
 
-    // out holds 128 * V.  s_x = max|V| / 127; codes = rint(V / s_x) = rint(out * 127 / max|out|).
-    const float inv = amax > 0.0f ? 127.0f / amax : 0.0f;
-    if (wave == 0 && g == 0 && r < TOK && token_ok) sx[token] = amax * (0.0078125f / 127.0f);
+    // out holds 128 * V.  Symmetric: s_x = max|V| / 127; codes = rint(V / s_x) = rint(out * 127 / max|out|).
+    // Asymmetric (range [lo, hi] with lo <= 0 <= hi): s_x = (hi - lo) / 255, z = -rint(lo / s_x), stored code =
+    // clamp(rint(V / s_x) + z, 0, 255) - 128; the integer offset rides in the rounding constant of the same FMA.
+    float inv, magic = kRoundMagic;
+    if (asym) {
+        const float range = amax - amin;
+        inv = range > 0.0f ? 255.0f / range : 0.0f;
+        const float z = -rintf(amin * inv);
+        magic = kRoundMagic + (z - 128.0f);
+        if (wave == 0 && g == 0 && r < TOK && token_ok) {
+            sx[token] = range * (0.0078125f / 255.0f);
+            zc[token] = 128 - (int)z;
+        }
+    } else {
+        inv = amax > 0.0f ? 127.0f / amax : 0.0f;
+        if (wave == 0 && g == 0 && r < TOK && token_ok) sx[token] = amax * (0.0078125f / 127.0f);
+    }
+    auto code_bits = [&](float v) -> uint32_t {
+        const float t = __builtin_fmaf(v, inv, magic);
+        // symmetric codes cannot leave +-127; the clamp only acts on the asymmetric range ends
+        return __float_as_uint(__builtin_amdgcn_fmed3f(t, kRoundMagic - 128.0f, kRoundMagic + 127.0f));
+    };
 
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
@@ -196,10 +232,10 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
             uint32_t c[8];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                c[2 * q] = pack4_low_bytes(quant_bits(out[i][0][q], inv), quant_bits(out[i][1][q], inv),
-                                           quant_bits(out[i][2][q], inv), quant_bits(out[i][3][q], inv));
-                c[2 * q + 1] = pack4_low_bytes(quant_bits(out[i][4][q], inv), quant_bits(out[i][5][q], inv),
-                                               quant_bits(out[i][6][q], inv), quant_bits(out[i][7][q], inv));
+                c[2 * q] = pack4_low_bytes(code_bits(out[i][0][q]), code_bits(out[i][1][q]),
+                                           code_bits(out[i][2][q]), code_bits(out[i][3][q]));
+                c[2 * q + 1] = pack4_low_bytes(code_bits(out[i][4][q]), code_bits(out[i][5][q]),
+                                               code_bits(out[i][6][q]), code_bits(out[i][7][q]));
             }
             int8_t *dst = Xq + token * (int64_t)K + b * kBlock + g * 16;
             *reinterpret_cast<uint4 *>(dst) = make_uint4(c[0], c[1], c[2], c[3]);
@@ -212,16 +248,17 @@ __global__ __launch_bounds__(768) void rotate_quant_rpr_kernel(
 
 template <int TOK, int SPW>
 hipError_t launch_rpr(const uint16_t *X, int64_t M, int nb, int nw, int64_t ldx, const float *diag,
-                      const int32_t *perm, int8_t *Xq, float *sx, const void *warm, int64_t warm_bytes, hipStream_t st)
+                      const int32_t *perm, int8_t *Xq, float *sx, int32_t *zc, const void *warm, int64_t warm_bytes,
+                      hipStream_t st)
 {
     const int K = nb * kBlock;
-    const size_t smem = sizeof(float) * ((size_t)TOK * (K + kRowPad) + (size_t)nw * 16) + 1024;
+    const size_t smem = sizeof(float) * ((size_t)TOK * (K + kRowPad) + (size_t)nw * 32) + 1024;
     if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(rotate_quant_rpr_kernel<TOK, SPW>), 160 * 1024);
         e != hipSuccess)
         return e;
     const int64_t groups = (M + TOK - 1) / TOK;
     hipLaunchKernelGGL((rotate_quant_rpr_kernel<TOK, SPW>), dim3((unsigned)groups), dim3(64 * nw), smem, st,
-                       X, M, nb, ldx, diag, perm, Xq, sx, static_cast<const uint4 *>(warm),
+                       X, M, nb, ldx, diag, perm, Xq, sx, zc, static_cast<const uint4 *>(warm),
                        (warm && warm_bytes < ((int64_t)1 << 32)) ? warm_bytes / 16 : 0);
     return hipGetLastError();
 }
@@ -233,27 +270,27 @@ bool rotate_quant_rpr_supports(int K) { return K > 0 && K % kBlock == 0 && K / k
 
 hipError_t launch_rotate_quant_rpr(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
                                    const int32_t *perm, int8_t *Xq, float *sx, const void *warm, int64_t warm_bytes,
-                                   hipStream_t st)
+                                   hipStream_t st, int32_t *zc)
 {
     if (M == 0) return hipSuccess;
     if (!rotate_quant_rpr_supports(K)) return hipErrorInvalidValue;
     const int nb = K / kBlock;
     // 16 tokens per workgroup while their rows fit LDS, else 8 tokens and two blocks per item
-    const bool tok16 = (size_t)16 * (K + kRowPad) * 4 + (size_t)12 * 64 + 1024 <= 150 * 1024;
+    const bool tok16 = (size_t)16 * (K + kRowPad) * 4 + (size_t)12 * 128 + 1024 <= 150 * 1024;
     const int items = tok16 ? nb : (nb + 1) / 2;
     const int spw = items <= 12 ? 1 : (items <= 24 ? 2 : 3);
     const int nw = (items + spw - 1) / spw;
     if (tok16) {
         switch (spw) {
-            case 1: return launch_rpr<16, 1>(X, M, nb, nw, ldx, diag, perm, Xq, sx, warm, warm_bytes, st);
-            case 2: return launch_rpr<16, 2>(X, M, nb, nw, ldx, diag, perm, Xq, sx, warm, warm_bytes, st);
-            default: return launch_rpr<16, 3>(X, M, nb, nw, ldx, diag, perm, Xq, sx, warm, warm_bytes, st);
+            case 1: return launch_rpr<16, 1>(X, M, nb, nw, ldx, diag, perm, Xq, sx, zc, warm, warm_bytes, st);
+            case 2: return launch_rpr<16, 2>(X, M, nb, nw, ldx, diag, perm, Xq, sx, zc, warm, warm_bytes, st);
+            default: return launch_rpr<16, 3>(X, M, nb, nw, ldx, diag, perm, Xq, sx, zc, warm, warm_bytes, st);
         }
     }
     switch (spw) {
-        case 1: return launch_rpr<8, 1>(X, M, nb, nw, ldx, diag, perm, Xq, sx, warm, warm_bytes, st);
-        case 2: return launch_rpr<8, 2>(X, M, nb, nw, ldx, diag, perm, Xq, sx, warm, warm_bytes, st);
-        default: return launch_rpr<8, 3>(X, M, nb, nw, ldx, diag, perm, Xq, sx, warm, warm_bytes, st);
+        case 1: return launch_rpr<8, 1>(X, M, nb, nw, ldx, diag, perm, Xq, sx, zc, warm, warm_bytes, st);
+        case 2: return launch_rpr<8, 2>(X, M, nb, nw, ldx, diag, perm, Xq, sx, zc, warm, warm_bytes, st);
+        default: return launch_rpr<8, 3>(X, M, nb, nw, ldx, diag, perm, Xq, sx, zc, warm, warm_bytes, st);
     }
 }
 

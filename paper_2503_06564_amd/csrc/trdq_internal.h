@@ -73,7 +73,7 @@ hipError_t launch_rotate_quant_wide(const uint16_t *X, int64_t M, int K, int64_t
 bool rotate_quant_rpr_supports(int K);
 hipError_t launch_rotate_quant_rpr(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
                                    const int32_t *perm, int8_t *Xq, float *sx, const void *warm, int64_t warm_bytes,
-                                   hipStream_t st);
+                                   hipStream_t st, int32_t *zc = nullptr);   // zc: asymmetric codes, as launch_rotate_quant
 
 // perm (optional): rows are read through it (row k of the input to the rotation = row perm[k]).
 // norm: what undoes the unnormalised butterflies (1/sqrt(128) per rotation applied).

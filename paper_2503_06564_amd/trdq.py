@@ -31,7 +31,7 @@ SYMBOLS = [
     "trdq_peak_mfma_i8", "trdq_peak_stream",
     "trdq_xq_tiled_nbytes", "trdq_rotate_quant_tiled", "trdq_xq_untile", "trdq_qgemm_tiled_supported", "trdq_qgemm_tiled_preferred",
     "trdq_qgemm_tiled",
-    "trdq_prepare_weights_asym", "trdq_weights_export_zero_points", "trdq_qgemm_asym_weights",
+    "trdq_rotate_quant_rpr_asym", "trdq_prepare_weights_asym", "trdq_weights_export_zero_points", "trdq_qgemm_asym_weights",
 ]
 
 _lib = None
@@ -91,6 +91,7 @@ def lib():
         L.trdq_qgemm_tiled_supported.argtypes = [p, i64]
         L.trdq_qgemm_tiled_preferred.argtypes = [p, i64]
         L.trdq_qgemm_tiled.argtypes = [p, p, p, i64, p, p, i64, p, p]
+        L.trdq_rotate_quant_rpr_asym.argtypes = [p, i64, i32, i64, p, p, i32, p, p, p, p, p]
         L.trdq_prepare_weights_asym.argtypes = [p, i32, i32, p, i32, i32, p, C.POINTER(p)]
         L.trdq_weights_export_zero_points.argtypes = [p, p]
         L.trdq_qgemm_asym_weights.argtypes = [p, p, p, p, p, i64, p, p, i64, p, p]
@@ -458,6 +459,15 @@ def qgemm_asym(w, Xq, sx, zc, Y, bias=None, acc_debug=None, stream=None):
     ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
     _check(lib().trdq_qgemm_asym(w.handle, _ptr(Xq), _ptr(sx), _ptr(zc), M, _ptr(bias), _ptr(Y), ldy,
                                  _ptr(acc_debug), _stream(stream)), "trdq_qgemm_asym")
+
+
+def rotate_quant_rpr_asym(X, diag, perm, Xq, sx, zc, block=BLOCK, stream=None, warm=None):
+    """rotate_quant_rpr with asymmetric codes (q - 128 in Xq, 128 - z in zc)."""
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    _check(lib().trdq_rotate_quant_rpr_asym(_ptr(X), M, K, ldx, _ptr(diag), _ptr(perm), block, _ptr(Xq), _ptr(sx),
+                                            _ptr(zc), warm.handle if warm is not None else None, _stream(stream)),
+           "trdq_rotate_quant_rpr_asym")
 
 
 def prepare_weights_asym(W, diag, block=BLOCK, wbits=8, stream=None):

@@ -206,3 +206,39 @@ def test_fused_refuses_weights_folded_with_another_transform(oracle):
         trdq.linear_fused(bf16_to_dev(Xb), f32_to_dev(d), w, Y)
     assert e.value.status == trdq.ERR_MISMATCH
     w.close()
+
+
+@pytest.mark.parametrize("M,K,N", [(17, 256, 144), (300, 1152, 272), (130, 4608, 144), (1024, 1152, 1152)])
+def test_rpr_with_asymmetric_activation_codes(oracle, M, K, N):
+    """Eq. 9's transform followed by the asymmetric quantiser of Eq. 1-3 (trdq_rotate_quant_rpr_asym), multiplied
+    by trdq_qgemm_asym against weights from trdq_prepare_weights_rpr."""
+    say(f"R P R, asymmetric codes M={M} K={K} N={N}")
+    from gpu_util import assert_asym_codes_close
+    Xb, W, d, bias = wl.small_case(26, M, K, N, n_outliers=max(1, K // 144), outlier=40.0)
+    perm = trdq.zigzag_permutation(_perm_for(oracle, Xb, d).astype(np.float32))
+    perm_d = torch.from_numpy(perm).to(dev())
+    w = trdq.prepare_weights_rpr(f32_to_dev(W), f32_to_dev(d), perm_d, wbits=8)
+    Xq = torch.full((M, K), 99, dtype=torch.int8, device=dev())
+    sx = torch.full((M,), -1.0, dtype=torch.float32, device=dev())
+    zc = torch.full((M,), -999, dtype=torch.int32, device=dev())
+    trdq.rotate_quant_rpr_asym(bf16_to_dev(Xb), f32_to_dev(d), perm_d, Xq, sx, zc, warm=w)
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device=dev())
+    acc = torch.full((M, N), -7, dtype=torch.int32, device=dev())
+    trdq.qgemm_asym(w, Xq, sx, zc, Y, bias=f32_to_dev(bias), acc_debug=acc)
+    torch.cuda.synchronize()
+    ref = oracle.linear_rpr_asym(Xb, W, d, perm, bias, exact_blas=True)
+    q = Xq.cpu().numpy().astype(np.int16) + 128
+    z = (128 - zc.cpu().numpy()).astype(np.int32)
+    assert_asym_codes_close(q, z, ref["Xq"], ref["zx"], "Xq (R P R, asymmetric)")
+    assert_scales_close(sx.cpu().numpy(), ref["sx"], "s_x (R P R, asymmetric)")
+    codes, scales = w.export()
+    assert_codes_close(codes, ref["Wq"], "Wq (R P R)")
+    want = oracle.acc_asym_exact_blas(q.astype(np.uint8), z, codes)
+    assert np.array_equal(acc.cpu().numpy(), want), "integer sums differ on the GPU's own codes"
+    assert_y_same_codes(bf16_to_host(Y), oracle.dequant(want, sx.cpu().numpy(), scales, bias), "Y (same codes)")
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (R P R, asymmetric)")
+    # the symmetric pass is untouched by the new option: bits of the plain call
+    Xq2, sx2 = _gpu_rotate_quant_rpr(Xb, d, perm)
+    Xq_o, sx_o = oracle.rotate_quant_rpr(Xb, d, perm, 128)
+    assert_codes_close(Xq2.cpu().numpy(), Xq_o, "Xq (R P R, symmetric)")
+    w.close()

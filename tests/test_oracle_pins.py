@@ -760,6 +760,29 @@ def test_asym_weights_linear_close_to_exact_product(oracle, act_asym):
     assert np.array_equal(ref["acc"], ref2["acc"]) and np.array_equal(ref["Y"], ref2["Y"])
 
 
+def test_rpr_asym_reduces_to_its_parts(oracle):
+    # with the identity permutation the two Hadamard rotations cancel (H is symmetric and orthogonal), so the
+    # Eq. 9 transform is X . Delta and its asymmetric codes are those of the plain quantiser on X . Delta;
+    # with a real permutation the product stays close to the exact one
+    rng = np.random.default_rng(41)
+    M, K, N = 24, 256, 32
+    Xf = rng.standard_normal((M, K)).astype(np.float32)
+    Xf[:, 5] *= 30.0
+    X = _bf16(Xf)
+    d = rng.lognormal(0, 0.3, K).astype(np.float32)
+    W = (0.02 * rng.standard_normal((K, N))).astype(np.float32)
+    ident = np.arange(K, dtype=np.int32)
+    ref = oracle.linear_rpr_asym(X, W, d, ident)
+    V = oracle.bf16_to_f64(X) * d.astype(np.float64)[None, :]
+    Xq, sx, zx = oracle.quant_tokens_asym(V)
+    assert np.array_equal(ref["zx"], zx) and np.mean(ref["Xq"] != Xq) < 1e-3 and np.allclose(ref["sx"], sx, rtol=1e-12)
+    perm = oracle.zigzag(np.abs(oracle.rotate(X, d, 128)).max(axis=0), 128).astype(np.int32)
+    ref = oracle.linear_rpr_asym(X, W, d, perm)
+    exact = oracle.bf16_to_f64(X) @ W.astype(np.float64)
+    assert np.linalg.norm(ref["Yd"] - exact) / np.linalg.norm(exact) < 0.02
+    assert np.array_equal(ref["acc"], oracle.linear_rpr_asym(X, W, d, perm, exact_blas=True)["acc"])
+
+
 # ------------------------------------ other bit-widths (the W6A6 of Table 3)
 
 @pytest.mark.parametrize("bits", [2, 4, 6, 7, 8])
