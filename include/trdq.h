@@ -429,6 +429,16 @@ trdq_status trdq_linear_fused(const void *X_dev, int64_t M, int64_t ldx, const f
                               const trdq_weights *w, const float *bias_dev,
                               void *Y_dev, int64_t ldy, void *stream);
 
+/* The same kernel with the asymmetric per-token quantiser of Eq. 1-3 (the arithmetic of
+ * trdq_rotate_quant_asym followed by trdq_qgemm_asym): every token gets a scale from its
+ * range and a zero point, the codes and zero points stay on chip, and the epilogue adds the
+ * zero-point term (128 - z_m) * colsum[n] to the integer sums before dequantising, so the
+ * sums are exactly those of (q - z) * w.  Weights in the int8 layout only (8- or 6-bit codes,
+ * symmetric); packed int4 weights -> ERR_UNSUPPORTED; otherwise errors as trdq_linear_fused. */
+trdq_status trdq_linear_fused_asym(const void *X_dev, int64_t M, int64_t ldx, const float *diag_dev,
+                                   const trdq_weights *w, const float *bias_dev,
+                                   void *Y_dev, int64_t ldy, void *stream);
+
 /* ------------------------------------------------------------------ layer
  * Convenience: one linear layer = the step table + one diagonal and one prepared
  * weight set per group (H_t depends on t, so each group keeps its own weights). */

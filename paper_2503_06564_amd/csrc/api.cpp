@@ -959,9 +959,9 @@ trdq_status trdq_qgemm_asym(const trdq_weights *w, const int8_t *Xq_dev, const f
                                          acc_debug_dev, -1, static_cast<hipStream_t>(stream)));
 }
 
-trdq_status trdq_linear_fused(const void *X_dev, int64_t M, int64_t ldx, const float *diag_dev,
-                              const trdq_weights *w, const float *bias_dev,
-                              void *Y_dev, int64_t ldy, void *stream)
+static trdq_status linear_fused_impl(const void *X_dev, int64_t M, int64_t ldx, const float *diag_dev,
+                                     const trdq_weights *w, const float *bias_dev,
+                                     void *Y_dev, int64_t ldy, void *stream, bool asym)
 {
     if (!w) return TRDQ_ERR_NULL;
     trdq_status rc = check_rotate_args(X_dev, M, w->K, ldx, trdq::kBlock);
@@ -971,12 +971,27 @@ trdq_status trdq_linear_fused(const void *X_dev, int64_t M, int64_t ldx, const f
     if (diag_dev && !aligned(diag_dev, 16)) return TRDQ_ERR_SHAPE;
     if (!trdq::fused_supports(w->K)) return TRDQ_ERR_UNSUPPORTED;
     if (w->rotation != trdq::kRotHadamard) return TRDQ_ERR_MISMATCH;   // the kernel applies the one-rotation transform
-    if (w->zcw) return TRDQ_ERR_MISMATCH;                              // ... and carries no zero points
+    if (w->zcw) return TRDQ_ERR_MISMATCH;                              // ... and no zero points of the weights
+    if (asym && w->wbits != 8) return TRDQ_ERR_UNSUPPORTED;            // zero points of the tokens: int8 layout only
     if (M == 0) return TRDQ_OK;
     if (trdq_status rd = check_device(w->device); rd != TRDQ_OK) return rd;
     return hip_status(trdq::launch_linear_fused(*w, static_cast<const uint16_t *>(X_dev), M, ldx, diag_dev,
                                                 bias_dev, static_cast<uint16_t *>(Y_dev), ldy,
-                                                static_cast<hipStream_t>(stream)));
+                                                static_cast<hipStream_t>(stream), asym));
+}
+
+trdq_status trdq_linear_fused(const void *X_dev, int64_t M, int64_t ldx, const float *diag_dev,
+                              const trdq_weights *w, const float *bias_dev,
+                              void *Y_dev, int64_t ldy, void *stream)
+{
+    return linear_fused_impl(X_dev, M, ldx, diag_dev, w, bias_dev, Y_dev, ldy, stream, false);
+}
+
+trdq_status trdq_linear_fused_asym(const void *X_dev, int64_t M, int64_t ldx, const float *diag_dev,
+                                   const trdq_weights *w, const float *bias_dev,
+                                   void *Y_dev, int64_t ldy, void *stream)
+{
+    return linear_fused_impl(X_dev, M, ldx, diag_dev, w, bias_dev, Y_dev, ldy, stream, true);
 }
 
 /* ------------------------------------------------------------------ layer */

@@ -26,6 +26,7 @@ struct FusedArgs {
     const void *Wc;
     const float *sw;
     const float *bias;
+    const int32_t *colsum; // ASYM kernels: sum over k of the weight codes of every output channel [N]
     uint16_t *Y;
     int64_t M, ldx, ldy;
     int K, N;
@@ -33,10 +34,14 @@ struct FusedArgs {
     int nsplit;            // workgroups sharing one token panel
 };
 
-// BM tokens per panel, S lane-rows per token in the prologue, T blocks per lane-row
-template <int BM, int T, int S, bool W4>
+// BM tokens per panel, S lane-rows per token in the prologue, T blocks per lane-row.
+// ASYM: the panel is quantised with the asymmetric form of Eq. 1-3 (per-token zero point z, codes
+// stored as q - 128); the epilogue adds (128 - z_m) * colsum[n] to the integer sums, which makes
+// them the exact sums of (q - z) * w.  Int8 weights only.
+template <int BM, int T, int S, bool W4, bool ASYM = false>
 __global__ __launch_bounds__(kThreads) void linear_fused_kernel(FusedArgs g)
 {
+    static_assert(!(W4 && ASYM), "zero points are carried for int8 weights only");
     constexpr int WM = BM >= 64 ? 32 : BM;           // wave tile (tokens)
     constexpr int WGM = BM / WM, WGN = 4 / WGM;
     constexpr int WN = kBN / WGN;
@@ -51,6 +56,7 @@ __global__ __launch_bounds__(kThreads) void linear_fused_kernel(FusedArgs g)
     int8_t *const Xp = smem;                              // [BM][K + 16]   int8 panel
     int8_t *const Ws = smem + BM * LDX;                   // [2][kBN][LDW]  weight stages
     float *const sxs = reinterpret_cast<float *>(Ws + 2 * kBN * LDW);   // [BM]
+    int *const zcs = reinterpret_cast<int *>(sxs + BM);                 // [BM] 128 - z (ASYM)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -67,16 +73,32 @@ __global__ __launch_bounds__(kThreads) void linear_fused_kernel(FusedArgs g)
             const int64_t token = m0 + r;
             const bool ok = r < BM && token < g.M;
             float v[T][8];
-            float amax;
-            rotate_token<T, S>(g.X + token * g.ldx, ok, nb, s, l16, g.diag, sg, v, amax);
-            const float inv = token_inv_scale(amax);
-            if (r < BM) {
-                if (s == 0 && l16 == 0) sxs[r] = ok ? token_scale(amax) : 0.0f;
+            float amax, amin;
+            rotate_token<T, S, ASYM>(g.X + token * g.ldx, ok, nb, s, l16, g.diag, sg, v, amax, amin);
+            if constexpr (ASYM) {
+                const TokenRangeQuant q(amin, amax);
+                if (r < BM) {
+                    if (s == 0 && l16 == 0) {
+                        sxs[r] = ok ? q.scale : 0.0f;
+                        zcs[r] = ok ? q.zc : 0;
+                    }
 #pragma unroll
-                for (int t = 0; t < T; ++t) {
-                    const int b = t * S + s;
-                    if (b < nb)
-                        *reinterpret_cast<uint2 *>(Xp + r * LDX + b * kBlock + l16 * 8) = quant_pack8(v[t], inv);
+                    for (int t = 0; t < T; ++t) {
+                        const int b = t * S + s;
+                        if (b < nb)
+                            *reinterpret_cast<uint2 *>(Xp + r * LDX + b * kBlock + l16 * 8) = q.pack8(v[t]);
+                    }
+                }
+            } else {
+                const float inv = token_inv_scale(amax);
+                if (r < BM) {
+                    if (s == 0 && l16 == 0) sxs[r] = ok ? token_scale(amax) : 0.0f;
+#pragma unroll
+                    for (int t = 0; t < T; ++t) {
+                        const int b = t * S + s;
+                        if (b < nb)
+                            *reinterpret_cast<uint2 *>(Xp + r * LDX + b * kBlock + l16 * 8) = quant_pack8(v[t], inv);
+                    }
                 }
             }
         }
@@ -198,12 +220,18 @@ __global__ __launch_bounds__(kThreads) void linear_fused_kernel(FusedArgs g)
                 float4 s = make_float4(1.f, 1.f, 1.f, 1.f), bi = make_float4(0.f, 0.f, 0.f, 0.f);
                 if constexpr (!W4) s = *reinterpret_cast<const float4 *>(g.sw + n);
                 if (g.bias) bi = *reinterpret_cast<const float4 *>(g.bias + n);
+                int4 cs = make_int4(0, 0, 0, 0);
+                if constexpr (ASYM) cs = *reinterpret_cast<const int4 *>(g.colsum + n);
 #pragma unroll
                 for (int b = 0; b < TM; ++b) {
                     const int r = wm * WM + b * 16 + l16;
                     const int64_t m = m0 + r;
                     if (m >= g.M) continue;
                     const float sxm = W4 ? sxs[r] * 0.0625f : sxs[r];
+                    if constexpr (ASYM) {
+                        const int zc = zcs[r];
+                        acc[a][b] += v4i{zc * cs.x, zc * cs.y, zc * cs.z, zc * cs.w};
+                    }
                     float y0, y1, y2, y3;
                     if constexpr (W4) {
                         y0 = sxm * facc[a][b][0] + bi.x;
@@ -243,7 +271,7 @@ __global__ __launch_bounds__(kThreads) void linear_fused_kernel(FusedArgs g)
 constexpr int kSmallThreads = 512;
 constexpr int kSmallSteps = 3;
 
-template <int TN, int T>
+template <int TN, int T, bool ASYM = false>
 __global__ __launch_bounds__(kSmallThreads) void linear_fused_small_kernel(FusedArgs g)
 {
     constexpr int BN = TN * 16;
@@ -253,7 +281,8 @@ __global__ __launch_bounds__(kSmallThreads) void linear_fused_small_kernel(Fused
     const int LDX = K + kPad;
     int8_t *const Xp = smem;                                              // [16][K + 16] int8 panel
     float *const sxs = reinterpret_cast<float *>(smem + 16 * LDX);       // [16]
-    v4i *const part = reinterpret_cast<v4i *>(smem + 16 * LDX + 64);     // [8][TN][64] partial sums
+    int *const zcs = reinterpret_cast<int *>(smem + 16 * LDX + 64);      // [16] 128 - z (ASYM)
+    v4i *const part = reinterpret_cast<v4i *>(smem + 16 * LDX + 128);    // [8][TN][64] partial sums
     float *const dl = reinterpret_cast<float *>(part);                   // [K] diagonal (before the sums need the space)
 
     const int tid = threadIdx.x;
@@ -307,7 +336,7 @@ __global__ __launch_bounds__(kSmallThreads) void linear_fused_small_kernel(Fused
     {
         const LaneSigns sg(l16);
         float v[T][8];
-        float amax = 0.0f;
+        float amax = 0.0f, amin = 0.0f;
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             const int b = t * 2 + s < nb ? t * 2 + s : nb - 1;
@@ -323,7 +352,14 @@ __global__ __launch_bounds__(kSmallThreads) void linear_fused_small_kernel(Fused
             v[t][7] = bf16_hi(raw[t].w) * d1.w;
             fwht128_rows16(v[t], sg);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(v[t][j]));
+            for (int j = 0; j < 8; ++j) {
+                if constexpr (ASYM) {
+                    amax = fmaxf(amax, v[t][j]);
+                    amin = fminf(amin, v[t][j]);
+                } else {
+                    amax = fmaxf(amax, fabsf(v[t][j]));
+                }
+            }
             if (t == 0) {
                 // the last k-step's fragments go out once the first block is done (the queue has drained by then)
                 __builtin_amdgcn_sched_barrier(0);
@@ -333,12 +369,27 @@ __global__ __launch_bounds__(kSmallThreads) void linear_fused_small_kernel(Fused
         }
         amax = row16_max(amax);
         amax = fmaxf(amax, __shfl_xor(amax, 16));
-        const float inv = token_inv_scale(amax);
-        if (s == 0 && l16 == 0) sxs[r] = tok_ok ? token_scale(amax) : 0.0f;
+        if constexpr (ASYM) {
+            amin = -row16_max(-amin);
+            amin = fminf(amin, __shfl_xor(amin, 16));
+            const TokenRangeQuant q(amin, amax);
+            if (s == 0 && l16 == 0) {
+                sxs[r] = tok_ok ? q.scale : 0.0f;
+                zcs[r] = tok_ok ? q.zc : 0;
+            }
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            const int b = t * 2 + s;
-            if (b < nb) *reinterpret_cast<uint2 *>(Xp + r * LDX + b * kBlock + l16 * 8) = quant_pack8(v[t], inv);
+            for (int t = 0; t < T; ++t) {
+                const int b = t * 2 + s;
+                if (b < nb) *reinterpret_cast<uint2 *>(Xp + r * LDX + b * kBlock + l16 * 8) = q.pack8(v[t]);
+            }
+        } else {
+            const float inv = token_inv_scale(amax);
+            if (s == 0 && l16 == 0) sxs[r] = tok_ok ? token_scale(amax) : 0.0f;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const int b = t * 2 + s;
+                if (b < nb) *reinterpret_cast<uint2 *>(Xp + r * LDX + b * kBlock + l16 * 8) = quant_pack8(v[t], inv);
+            }
         }
     }
     __syncthreads();        // panel and scales published; every wave is done with the diagonal
@@ -372,6 +423,11 @@ __global__ __launch_bounds__(kSmallThreads) void linear_fused_small_kernel(Fused
             float4 bi = make_float4(0.f, 0.f, 0.f, 0.f);
             if (g.bias) bi = *reinterpret_cast<const float4 *>(g.bias + n);
             const float sxm = sxs[l16];
+            if constexpr (ASYM) {
+                const int4 cs = *reinterpret_cast<const int4 *>(g.colsum + n);
+                const int zc = zcs[l16];
+                sum += v4i{zc * cs.x, zc * cs.y, zc * cs.z, zc * cs.w};
+            }
             uint2 o;
             o.x = pack_bf16x2((float)sum[0] * sxm * sw.x + bi.x, (float)sum[1] * sxm * sw.y + bi.y);
             o.y = pack_bf16x2((float)sum[2] * sxm * sw.z + bi.z, (float)sum[3] * sxm * sw.w + bi.w);
@@ -380,14 +436,14 @@ __global__ __launch_bounds__(kSmallThreads) void linear_fused_small_kernel(Fused
     }
 }
 
-template <int TN, int T>
+template <int TN, int T, bool ASYM>
 hipError_t launch_small(const FusedArgs &a, hipStream_t st)
 {
     FusedArgs g = a;
     const int64_t panels = (g.M + 15) / 16;
     g.tiles_n = (g.N + TN * 16 - 1) / (TN * 16);
-    const size_t smem = (size_t)16 * (g.K + kPad) + 64 + (size_t)8 * TN * 1024;
-    auto kern = linear_fused_small_kernel<TN, T>;
+    const size_t smem = (size_t)16 * (g.K + kPad) + 128 + (size_t)8 * TN * 1024;
+    auto kern = linear_fused_small_kernel<TN, T, ASYM>;
     if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
     // consecutive workgroups take the channel tiles of one panel: with eight tiles (1152 = 8 x 144)
     // each of the eight dies keeps seeing the same weight slab
@@ -405,25 +461,26 @@ bool small_applies(const FusedArgs &a, int wbits)
     return wgs <= kSmallMaxWorkgroups;
 }
 
-template <int TN>
+template <int TN, bool ASYM>
 hipError_t launch_small_tn(const FusedArgs &a, hipStream_t st)
 {
     switch ((a.K / kBlock + 1) / 2) {       // blocks per lane row (two lane rows share a token)
-        case 1: return launch_small<TN, 1>(a, st);
-        case 2: return launch_small<TN, 2>(a, st);
-        case 3: return launch_small<TN, 3>(a, st);
-        case 4: return launch_small<TN, 4>(a, st);
-        case 5: return launch_small<TN, 5>(a, st);
-        default: return launch_small<TN, 6>(a, st);
+        case 1: return launch_small<TN, 1, ASYM>(a, st);
+        case 2: return launch_small<TN, 2, ASYM>(a, st);
+        case 3: return launch_small<TN, 3, ASYM>(a, st);
+        case 4: return launch_small<TN, 4, ASYM>(a, st);
+        case 5: return launch_small<TN, 5, ASYM>(a, st);
+        default: return launch_small<TN, 6, ASYM>(a, st);
     }
 }
 
+template <bool ASYM>
 hipError_t launch_small_any(const FusedArgs &a, hipStream_t st)
 {
-    return a.N % 144 == 0 ? launch_small_tn<9>(a, st) : launch_small_tn<8>(a, st);
+    return a.N % 144 == 0 ? launch_small_tn<9, ASYM>(a, st) : launch_small_tn<8, ASYM>(a, st);
 }
 
-template <int BM, int T, int S, bool W4>
+template <int BM, int T, int S, bool W4, bool ASYM>
 hipError_t launch_one(const FusedArgs &a, hipStream_t st)
 {
     FusedArgs g = a;
@@ -434,29 +491,29 @@ hipError_t launch_one(const FusedArgs &a, hipStream_t st)
     want = want < 1 ? 1 : (want > g.tiles_n ? g.tiles_n : want);
     const int tiles_per = (int)((g.tiles_n + want - 1) / want);
     g.nsplit = (g.tiles_n + tiles_per - 1) / tiles_per;   // no workgroup without a channel tile
-    const size_t smem = (size_t)BM * (g.K + kPad) + 2 * (size_t)kBN * (kBK + kPad) + BM * sizeof(float);
-    auto kern = linear_fused_kernel<BM, T, S, W4>;
+    const size_t smem = (size_t)BM * (g.K + kPad) + 2 * (size_t)kBN * (kBK + kPad) + 2 * BM * sizeof(float);
+    auto kern = linear_fused_kernel<BM, T, S, W4, ASYM>;
     if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)panels, (unsigned)g.nsplit), dim3(kThreads), smem, st, g);
     return hipGetLastError();
 }
 
-template <int BM, int S, bool W4>
+template <int BM, int S, bool W4, bool ASYM>
 hipError_t launch_t(int T, const FusedArgs &a, hipStream_t st)
 {
-    if (T <= 3) return launch_one<BM, 3, S, W4>(a, st);
-    if (T <= 6) return launch_one<BM, 6, S, W4>(a, st);
-    if (T <= 9) return launch_one<BM, 9, S, W4>(a, st);
-    return launch_one<BM, 12, S, W4>(a, st);
+    if (T <= 3) return launch_one<BM, 3, S, W4, ASYM>(a, st);
+    if (T <= 6) return launch_one<BM, 6, S, W4, ASYM>(a, st);
+    if (T <= 9) return launch_one<BM, 9, S, W4, ASYM>(a, st);
+    return launch_one<BM, 12, S, W4, ASYM>(a, st);
 }
 
-template <bool W4>
+template <bool W4, bool ASYM = false>
 hipError_t launch_w(const FusedArgs &a, hipStream_t st)
 {
     const int nb = a.K / kBlock;
-    if (nb <= 12) return launch_t<64, 1, W4>(nb, a, st);
-    if (nb <= 24) return launch_t<32, 2, W4>((nb + 1) / 2, a, st);
-    return launch_t<16, 4, W4>((nb + 3) / 4, a, st);
+    if (nb <= 12) return launch_t<64, 1, W4, ASYM>(nb, a, st);
+    if (nb <= 24) return launch_t<32, 2, W4, ASYM>((nb + 1) / 2, a, st);
+    return launch_t<16, 4, W4, ASYM>((nb + 3) / 4, a, st);
 }
 
 }  // namespace
@@ -474,13 +531,15 @@ bool fused_pays(int64_t M, int K, int N, int wbits)
 
 hipError_t launch_linear_fused(const Weights &w, const uint16_t *X, int64_t M, int64_t ldx,
                                const float *diag, const float *bias, uint16_t *Y, int64_t ldy,
-                               hipStream_t st)
+                               hipStream_t st, bool asym)
 {
     if (M == 0) return hipSuccess;
+    if (asym && (w.wbits != 8 || !w.colsum)) return hipErrorInvalidValue;
     FusedArgs a;
-    a.X = X; a.diag = diag; a.Wc = w.codes; a.sw = w.scales; a.bias = bias; a.Y = Y;
+    a.X = X; a.diag = diag; a.Wc = w.codes; a.sw = w.scales; a.bias = bias; a.colsum = w.colsum; a.Y = Y;
     a.M = M; a.ldx = ldx; a.ldy = ldy; a.K = w.K; a.N = w.N; a.tiles_n = 0; a.nsplit = 1;
-    if (small_applies(a, w.wbits)) return launch_small_any(a, st);
+    if (small_applies(a, w.wbits)) return asym ? launch_small_any<true>(a, st) : launch_small_any<false>(a, st);
+    if (asym) return launch_w<false, true>(a, st);
     return w.wbits == 4 ? launch_w<true>(a, st) : launch_w<false>(a, st);
 }
 

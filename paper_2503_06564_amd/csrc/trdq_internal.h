@@ -142,6 +142,6 @@ bool fused_supports(int K);
 bool fused_pays(int64_t M, int K, int N, int wbits);
 hipError_t launch_linear_fused(const Weights &w, const uint16_t *X, int64_t M, int64_t ldx,
                                const float *diag, const float *bias, uint16_t *Y, int64_t ldy,
-                               hipStream_t st);
+                               hipStream_t st, bool asym = false);
 
 }  // namespace trdq

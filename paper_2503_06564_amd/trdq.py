@@ -18,7 +18,7 @@ SYMBOLS = [
     "trdq_table_create", "trdq_table_lookup", "trdq_table_sizes", "trdq_table_destroy",
     "trdq_prepare_weights", "trdq_weights_info", "trdq_weights_export",
     "trdq_weights_export_packed", "trdq_weights_nbytes", "trdq_weights_destroy",
-    "trdq_rotate_quant", "trdq_rotate_quant_warm", "trdq_qgemm", "trdq_linear_fused",
+    "trdq_rotate_quant", "trdq_rotate_quant_warm", "trdq_qgemm", "trdq_linear_fused", "trdq_linear_fused_asym",
     "trdq_layer_create", "trdq_layer_set_group", "trdq_layer_forward", "trdq_layer_weights",
     "trdq_layer_destroy", "trdq_qgemm_set_variant", "trdq_qgemm_num_variants",
     "trdq_zigzag_permutation", "trdq_prepare_weights_rpr", "trdq_rotate_quant_rpr",
@@ -72,6 +72,7 @@ def lib():
         L.trdq_rotate_quant_warm.argtypes = [p, i64, i32, i64, p, i32, p, p, p, p]
         L.trdq_qgemm.argtypes = [p, p, p, i64, p, p, i64, p, p]
         L.trdq_linear_fused.argtypes = [p, i64, i64, p, p, p, p, i64, p]
+        L.trdq_linear_fused_asym.argtypes = [p, i64, i64, p, p, p, p, i64, p]
         L.trdq_layer_create.argtypes = [p, i32, i32, i32, C.POINTER(p)]
         L.trdq_layer_set_group.argtypes = [p, i32, p, p, p]
         L.trdq_layer_forward.argtypes = [p, i32, p, i64, p, p, i32, p, p, p]
@@ -578,6 +579,14 @@ def linear_fused(X, diag, w, Y, bias=None, stream=None):
     ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
     _check(lib().trdq_linear_fused(_ptr(X), M, ldx, _ptr(diag), w.handle, _ptr(bias), _ptr(Y), ldy,
                                    _stream(stream)), "trdq_linear_fused")
+
+
+def linear_fused_asym(X, diag, w, Y, bias=None, stream=None):
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    ldy = Y.stride(0) if M > 1 else max(Y.shape[1], Y.stride(0))
+    _check(lib().trdq_linear_fused_asym(_ptr(X), M, ldx, _ptr(diag), w.handle, _ptr(bias), _ptr(Y), ldy,
+                                        _stream(stream)), "trdq_linear_fused_asym")
 
 
 # ---- pre-marshalled calls ---------------------------------------------------------------------

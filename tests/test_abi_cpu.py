@@ -296,3 +296,8 @@ def test_asym_weight_calls_check_arguments_before_any_gpu_call():
     assert L.trdq_prepare_weights_asym(0x1000, 256, 16, None, 128, 8, None, None) == trdq.ERR_NULL
     assert L.trdq_weights_export_zero_points(None, 0x1000) == trdq.ERR_NULL
     assert L.trdq_qgemm_asym_weights(None, 0x1000, 0x2000, None, 0x3000, 4, None, 0x4000, 16, None, None) == trdq.ERR_NULL
+
+
+def test_fused_asym_checks_arguments_before_any_gpu_call():
+    L = trdq.lib()
+    assert L.trdq_linear_fused_asym(0x1000, 4, 256, None, None, None, 0x2000, 16, None) == trdq.ERR_NULL

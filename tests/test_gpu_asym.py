@@ -115,3 +115,64 @@ def test_linear_asym_int4_weights(oracle, M, K, N):
     assert_y_close(bf16_to_host(Y), ref["Y"], "Y (asymmetric, int4 weights)",
                    *narrow_code_masks(8, 4, None, None, codes, ref["Wq"]))
     w.close()
+
+
+# both fused kernels: few tokens (one 16-token panel per workgroup, K <= 1536) and the general one
+# (panels of 64, 32 and 16 tokens as K grows); ragged token and channel counts, with and without a diagonal
+@pytest.mark.parametrize("M,K,N,wbits", [(1, 128, 16, 8), (17, 256, 144, 8), (256, 1152, 1152, 8), (100, 1152, 272, 6),
+                                         (1100, 1152, 1152, 8), (513, 384, 400, 8), (300, 2304, 272, 8),
+                                         (200, 4608, 144, 8), (1024, 1152, 3456, 6)])
+def test_linear_fused_asym_matches_oracle(oracle, M, K, N, wbits):
+    say(f"linear fused asymmetric M={M} K={K} N={N} wbits={wbits}")
+    Xb, W, d, bias = wl.small_case(45, M, K, N, n_outliers=max(1, K // 144), outlier=40.0)
+    w = trdq.prepare_weights(f32_to_dev(W), f32_to_dev(d), wbits=wbits)
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device=dev())
+    trdq.linear_fused_asym(bf16_to_dev(Xb), f32_to_dev(d), w, Y, bias=f32_to_dev(bias))
+    torch.cuda.synchronize()
+    codes, _ = w.export()
+    ref = oracle.linear_asym(Xb, W, d, bias, exact_blas=True, wbits=wbits)
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (fused, asymmetric, oracle end to end)",
+                   *narrow_code_masks(8, wbits, None, None, codes, ref["Wq"]))
+    # the unfused pair on the same inputs: same arithmetic up to the rounding order of the rotation
+    Xq, sx, zc = _gpu_rq_asym(Xb, d)
+    Yp = torch.zeros_like(Y)
+    trdq.qgemm_asym(w, Xq, sx, zc, Yp, bias=f32_to_dev(bias))
+    torch.cuda.synchronize()
+    assert_y_close(bf16_to_host(Y), bf16_to_host(Yp), "Y (fused against the pair)")
+    w.close()
+
+
+def test_linear_fused_asym_without_diagonal_and_one_sided_rows(oracle):
+    K, N = 256, 144
+    x = np.zeros((5, K), dtype=np.float32)
+    x[0, 0] = 3.0
+    x[2, :128] = 1.0
+    x[3, :128] = -2.0
+    x[4] = np.linspace(-1.0, 2.0, K)
+    Xb = wl.f32_to_bf16_bits(x)
+    _, W, _, bias = wl.small_case(46, 5, K, N)
+    w = trdq.prepare_weights(f32_to_dev(W), None, wbits=8)
+    Y = torch.full((5, N), 7.0, dtype=torch.bfloat16, device=dev())
+    trdq.linear_fused_asym(bf16_to_dev(Xb), None, w, Y, bias=f32_to_dev(bias))
+    torch.cuda.synchronize()
+    ref = oracle.linear_asym(Xb, W, None, bias, exact_blas=True)
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (fused, asymmetric, special rows)")
+    # the all-zero token yields the bias alone
+    assert np.array_equal(bf16_to_host(Y)[1], wl.f32_to_bf16_bits(bias.astype(np.float32)))
+    w.close()
+
+
+def test_linear_fused_asym_refusals():
+    _, W, d, _ = wl.small_case(47, 4, 256, 32)
+    X = torch.zeros((4, 256), dtype=torch.bfloat16, device=dev())
+    Y = torch.zeros((4, 32), dtype=torch.bfloat16, device=dev())
+    w4 = trdq.prepare_weights(f32_to_dev(W), f32_to_dev(d), wbits=4)
+    with pytest.raises(trdq.TrdqError) as e:
+        trdq.linear_fused_asym(X, f32_to_dev(d), w4, Y)
+    assert e.value.status == trdq.ERR_UNSUPPORTED
+    w4.close()
+    wa = trdq.prepare_weights_asym(f32_to_dev(W), f32_to_dev(d))
+    with pytest.raises(trdq.TrdqError) as e:
+        trdq.linear_fused_asym(X, f32_to_dev(d), wa, Y)
+    assert e.value.status == trdq.ERR_MISMATCH
+    wa.close()
