@@ -410,8 +410,9 @@ trdq_status trdq_rotate_quant_tiled(const void *X_dev, int64_t M, int K, int64_t
                                     int8_t *Xt_dev, float *sx_dev, const trdq_weights *next, void *stream);
 trdq_status trdq_xq_untile(const int8_t *Xt_dev, int64_t M, int K, int8_t *Xq_dev, void *stream);
 int trdq_qgemm_tiled_supported(const trdq_weights *w, int64_t M);
-/* 1 where the tiled pair is also the faster one by the library's measured rule (more than one
- * 128 x 144 output tile per compute unit, K <= 4608): what trdq_layer_forward takes by itself. */
+/* 1 where the tiled pair is also the faster one by the library's measured rule (K <= 4608 and
+ * either more than one 128 x 144 output tile per compute unit, or at most one and K >= 1024):
+ * what trdq_layer_forward takes by itself. */
 int trdq_qgemm_tiled_preferred(const trdq_weights *w, int64_t M);
 trdq_status trdq_qgemm_tiled(const trdq_weights *w, const int8_t *Xt_dev, const float *sx_dev, int64_t M,
                              const float *bias_dev, void *Y_dev, int64_t ldy,

@@ -136,26 +136,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
-// 16-byte store of finished output.  TRDQ_STORE_POLICY (build-time experiment switch): 0 plain,
-// 1 sc1, 2 sc0 sc1 (written through to memory), 3 nt
-#ifndef TRDQ_STORE_POLICY
-#define TRDQ_STORE_POLICY 0
-#endif
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ void store_out16(void *p, uint4 v)
-{
-#if TRDQ_STORE_POLICY == 0
-    *reinterpret_cast<uint4 *>(p) = v;
-#else
-    const u32x4_t w = {v.x, v.y, v.z, v.w};
-#if TRDQ_STORE_POLICY == 1
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(p), "v"(w) : "memory");
-#elif TRDQ_STORE_POLICY == 2
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" :: "v"(p), "v"(w) : "memory");
-#else
-    asm volatile("global_store_dwordx4 %0, %1, off nt" :: "v"(p), "v"(w) : "memory");
-#endif
-#endif
-}
+// 16-byte store of finished output
+__device__ __forceinline__ void store_out16(void *p, uint4 v) { *reinterpret_cast<uint4 *>(p) = v; }
 
 }  // namespace trdq

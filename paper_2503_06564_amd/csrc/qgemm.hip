@@ -376,12 +376,13 @@ hipError_t launch_qgemm_tiled(const Weights &w, const int8_t *Xt, const float *s
 
 bool qgemm_tiled_pays(int64_t M, int K, int N)
 {
-    // Measured on the DiT-XL/2 widths at 4096 ... 32768 tokens: with more than one 128 x 144 tile per
-    // compute unit the tiled kernel (two workgroups per compute unit) wins, by 5-25 %; at or below that
-    // the one-workgroup kernels of the row-major path do, and for long K (fc2) they still do at up to two
-    // such tiles per compute unit (the kernel whose two wave groups split K inside the workgroup).
+    // Measured on the DiT-XL/2 widths at 256 ... 32768 tokens.  Up to one 128 x 144 tile per compute
+    // unit the kernel that splits K between two wave pairs wins for K >= 1024 (by 5 % at K = 1152, 15-20 %
+    // at K = 4608); with more tiles the kernel with two workgroups per compute unit does, by 5-30 %,
+    // except for long K at up to two tiles per compute unit, where the row-major kernel whose wave groups
+    // split K is level with it.
     const int64_t tiles = (M / 128) * (int64_t)(N / 144);
-    if (tiles <= num_cus()) return false;
+    if (tiles <= num_cus()) return K >= 1024;
     return !(K >= 2304 && tiles <= 2 * (int64_t)num_cus());
 }
 

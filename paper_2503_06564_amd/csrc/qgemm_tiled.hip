@@ -33,10 +33,7 @@ namespace {
 
 constexpr int kBN = 144;                     // channels per tile
 constexpr int kTN = kBN / 16;                // weight fragments per k-step
-#ifndef TRDQ_X_NS
-#define TRDQ_X_NS 3
-#endif
-constexpr int kNS = TRDQ_X_NS;               // stages of the ring
+constexpr int kNS = 3;                       // stages of the ring
 constexpr int kStageBig = (256 / 16 + kTN) * 1024;
 constexpr int kParOff = 3 * kStageBig;     // epilogue operands: [144 s_w][pad][144 bias][pad][256 s_x]
 constexpr int kParSw = 0, kParBias = 1024, kParSx = 2048;
@@ -84,9 +81,6 @@ __device__ __forceinline__ void run_tile(const GemmArgs &g, int tm, int tn, int8
     static_assert(2 * PMIN + 4 < 64, "vmcnt is a 6-bit counter");
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t *)smem;
-#ifdef TRDQ_X_PROF
-    const uint64_t prof_t0 = wall_clock64();
-#endif
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -143,9 +137,6 @@ __device__ __forceinline__ void run_tile(const GemmArgs &g, int tm, int tn, int8
     }
     __syncthreads();
 
-#ifdef TRDQ_X_PROF
-    const uint64_t prof_t1 = wall_clock64();
-#endif
     const int fro = blk_off(l16, lg);                 // the lane's piece of a fragment block
     v4i acc[kTN][TM];
 #pragma unroll
@@ -173,11 +164,7 @@ __device__ __forceinline__ void run_tile(const GemmArgs &g, int tm, int tn, int8
         const int8_t *const nxt = smem + nst * STAGE + fro;
         if constexpr (REFILL) {
             wait_vmcnt<WAITN>();                               // step kt+1 has landed (this wave's share)
-#ifndef TRDQ_X_NOBAR
             __syncthreads();                                   // ... everyone's; step kt's stage is retired
-#endif
-#ifndef TRDQ_X_NOCOPY
-#endif
 #pragma unroll
             for (int b = 0; b < TM; ++b)
                 bf[1 - PAR][b] = *reinterpret_cast<const v4i *>(nxt + (wave * TM + b) * 1024);
@@ -187,17 +174,11 @@ __device__ __forceinline__ void run_tile(const GemmArgs &g, int tm, int tn, int8
             constexpr int a = decltype(a_tag)::value;
 #pragma unroll
             for (int b = 0; b < TM; ++b)
-#ifndef TRDQ_X_NOMFMA
                 acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[a], bf[PAR][b], acc[a][b], 0, 0, 0);
-#else
-                acc[a][b] += af[a] ^ bf[PAR][b];
-#endif
             if constexpr (REFILL) af[a] = *reinterpret_cast<const v4i *>(nxt + (XB + a) * 1024);
-#ifndef TRDQ_X_NOCOPY
             // the copies of the step three ahead go out one at a time between the matrix instructions
             // (bunched, they stall the wave at the compute unit's copy path)
             if constexpr (ISSUE && a < TM + 3) issue_one(std::integral_constant<int, a>{}, kt + kNS, st);
-#endif
             if constexpr (REFILL) __builtin_amdgcn_sched_barrier(0);
         });
         st = nst;
@@ -219,9 +200,6 @@ __device__ __forceinline__ void run_tile(const GemmArgs &g, int tm, int tn, int8
     step(I0{}, Yes{}, No{}, I0{}, KT - 2);            // the last step's blocks: nothing younger is in flight
     step(I1{}, No{}, No{}, I0{}, KT - 1);
 
-#ifdef TRDQ_X_PROF
-    const uint64_t prof_t2 = wall_clock64();
-#endif
     // ---- epilogue: y = float(acc) * s_x[m] * s_w[n] + bias[n] -> bf16.  One token tile (16 tokens x
     // 144 channels) at a time is laid out in the wave's part of the idle ring and read back row by
     // row, so that a store instruction writes whole 288-byte row segments, 16 bytes per lane.
@@ -262,15 +240,6 @@ __device__ __forceinline__ void run_tile(const GemmArgs &g, int tm, int tn, int8
         }
         __builtin_amdgcn_wave_barrier();
     }
-#ifdef TRDQ_X_PROF
-    if (tid == 0 && g.acc_debug) {
-        uint32_t hw, xcc;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-        uint64_t *o = reinterpret_cast<uint64_t *>(g.acc_debug) + (int64_t)blockIdx.x * 8;
-        o[0] = prof_t0; o[1] = prof_t1; o[2] = prof_t2; o[3] = wall_clock64(); o[4] = hw; o[5] = xcc; o[6] = BM;
-    }
-#endif
 }
 
 template <bool DEBUG>
@@ -279,9 +248,6 @@ __global__ __launch_bounds__(kThreads, 2) void qgemm8_tiled_kernel(GemmArgs g, i
     extern __shared__ __align__(16) int8_t smem[];
     const int id = blockIdx.x;
     const int tiles_n = g.N / kBN;
-#ifdef TRDQ_X_PRIO
-    if (id < (int)gridDim.x / 2) __builtin_amdgcn_s_setprio(3);
-#endif
     int tm, tn;
     if (id < n_big) {
         tile_map(id, (int)(g.M / 256), nbn, tm, tn);
@@ -290,6 +256,224 @@ __global__ __launch_bounds__(kThreads, 2) void qgemm8_tiled_kernel(GemmArgs g, i
         tile_map(id - n_big, (int)(g.M / 128), tiles_n - nbn, tm, tn);
         run_tile<128, DEBUG>(g, tm, tn + nbn, smem);
     }
+}
+
+// ---- one tile per compute unit: K split over two wave pairs --------------------------------------
+// A launch with no more 128 x 144 tiles than compute units has nothing to put beside a tile, and a
+// 128-token tile run by four waves as above means wave tiles of 32 x 144, whose fragment reads
+// (0.6 KB per matrix instruction) bound the loop.  Here the four waves share the tile as two token
+// halves x two halves of K: every wave keeps the 64 x 144 wave tile, each pair walks its half of
+// the k-steps on a ring of its own (NS stages of 17 KB: 8 activation + 9 weight blocks), and all
+// four meet at one barrier per k-step.  Such a tile pulls 17 KB through the compute unit's copy
+// path per 72 matrix instructions, and that path delivers about 120 KB/us with nothing else going
+// on (measured), so the loop runs at the rate of the copies and what counts is how many of them
+// are in flight: two pairs x four stages keep three quarters of a 136 KB ring in flight (four
+// pairs x two stages, eight waves, kept half of it and was 20 % slower; whether the blocks came
+// from L2 or from behind it made no difference).
+// At the end the two partial sums of each token sub-tile (16 tokens x 144 channels) meet in LDS,
+// each pair adding up and finishing two of the four sub-tiles of both token halves.
+// Needs K % 128 == 0 (the same number of k-steps for both pairs) and at least NS k-steps per pair;
+// NS is 4, or 3 where the number of k-steps per pair is odd (the main loop takes two at a time).
+constexpr int kKsStage = (8 + kTN) * 1024;
+constexpr int kKsCopies = 9;                         // per wave and k-step
+constexpr int kKsPairs = 2;
+template <int NS> constexpr int ks_par_off() { return kKsPairs * NS * kKsStage; }
+template <int NS> constexpr int ks_lds() { return ks_par_off<NS>() + 3072; }
+
+template <int NS, bool DEBUG>
+__global__ __launch_bounds__(128 * kKsPairs) void qgemm8_tiled_ksplit_kernel(GemmArgs g)
+{
+    constexpr int NG = kKsPairs;
+    extern __shared__ __align__(16) int8_t smem[];
+    constexpr int TM = 4;
+    constexpr int P = kKsCopies;
+    constexpr int RING = NS * kKsStage;
+    constexpr int PAROFF = ks_par_off<NS>();
+    static_assert((NS - 1) * P < 64, "vmcnt is a 6-bit counter");
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t *)smem;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int mw = wave & 1, kg = wave >> 1;         // token half, part of K
+    const int l16 = lane & 15, lg = lane >> 4;
+    int tm, tn;
+    tile_map(blockIdx.x, (int)(g.M / 128), g.N / kBN, tm, tn);
+    const int KT = g.K >> 6;                          // k-steps of the product
+    const int KTg = KT / NG;                          // of one pair: even, at least NS
+    const int64_t m0 = (int64_t)tm * 128;
+    const int n0 = tn * kBN;
+
+    const int64_t gstride = (int64_t)KT * 1024;      // bytes from one 16-row group to the next
+    const int64_t kofs = (int64_t)kg * KTg * 1024;   // this pair's first k-step
+    const int8_t *const xsrc = g.Xq + (m0 / 16 + mw * TM) * gstride + kofs;
+    const int8_t *const wsrc = static_cast<const int8_t *>(g.Wc) + (int64_t)(n0 / 16) * gstride + kofs;
+    const uint32_t voff = (uint32_t)blk_off(lane >> 2, lane & 3);
+    int8_t *const ring = smem + kg * RING;
+    const uint32_t ring0 = lds0 + kg * RING;
+
+    // this wave's nine copies of a k-step: its own four activation blocks, and weight blocks 0..4
+    // (first wave of the pair) or 5..8 and 8 once more (second wave: equal counts keep the waits uniform)
+    const int8_t *src[P];
+    uint32_t dst[P];
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+        src[b] = xsrc + b * gstride;
+        dst[b] = (uint32_t)((mw * TM + b) * 1024);
+    }
+#pragma unroll
+    for (int i = 0; i < P - TM; ++i) {
+        const int blk = mw == 0 ? i : (5 + i < kTN ? 5 + i : kTN - 1);
+        src[TM + i] = wsrc + blk * gstride;
+        dst[TM + i] = (uint32_t)((8 + blk) * 1024);
+    }
+    auto issue_one = [&](auto c_tag, int s, int st) {
+        constexpr int c = decltype(c_tag)::value;
+        dma_1k(voff, src[c] + (int64_t)s * 1024, ring0 + st * kKsStage + dst[c]);
+    };
+    auto issue = [&](int s, int st) {
+        static_for_n<P>([&](auto c) { issue_one(c, s, st); });
+    };
+
+    // epilogue operands first (older than every tile copy, so the first wait covers them)
+    {
+        const uint32_t par = lds0 + PAROFF;
+        const uint32_t v36 = (uint32_t)((lane < kBN / 4 ? lane : kBN / 4 - 1) * 16);
+        const uint32_t vsx = (uint32_t)((lane < 128 / 4 ? lane : 128 / 4 - 1) * 16);
+        copy_1k_if(wave == 0, v36, g.sw + n0, par + kParSw);
+        copy_1k_if(wave == 1 && g.bias != nullptr, v36, g.bias ? g.bias + n0 : g.sw, par + kParBias);
+        if (wave == 1 && g.bias == nullptr)
+            *reinterpret_cast<uint4 *>(smem + PAROFF + kParBias + lane * 16) = make_uint4(0u, 0u, 0u, 0u);
+        copy_1k_if(wave == 2, vsx, g.sx + m0, par + kParSx);
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) issue(s, s);
+    wait_vmcnt<(NS - 1) * P>();                       // step 0 and the operands above
+    __syncthreads();
+
+    const int fro = blk_off(l16, lg);
+    v4i acc[kTN][TM];
+#pragma unroll
+    for (int a = 0; a < kTN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b) acc[a][b] = v4i{0, 0, 0, 0};
+    v4i af[kTN], bf[2][TM];
+#pragma unroll
+    for (int a = 0; a < kTN; ++a) af[a] = *reinterpret_cast<const v4i *>(ring + (8 + a) * 1024 + fro);
+#pragma unroll
+    for (int b = 0; b < TM; ++b) bf[0][b] = *reinterpret_cast<const v4i *>(ring + (mw * TM + b) * 1024 + fro);
+
+    int st = 0;
+    // One k-step on activation fragment set PAR.  REFILL: the next step exists: wait until at most
+    // WAITN younger copies are in flight (then it has landed), barrier, and read its fragments while
+    // this step's matrix instructions run.  ISSUE: the step NS ahead exists and is requested into
+    // this step's stage, whose fragments are all in registers by now.
+    auto step = [&](auto par_tag, auto refill_tag, auto issue_tag, auto wait_tag, int kt) {
+        constexpr int PAR = decltype(par_tag)::value;
+        constexpr bool REFILL = decltype(refill_tag)::value;
+        constexpr bool ISSUE = decltype(issue_tag)::value;
+        constexpr int WAITN = decltype(wait_tag)::value;
+        const int nst = (st + 1 == NS) ? 0 : st + 1;
+        const int8_t *const nxt = ring + nst * kKsStage + fro;
+        if constexpr (REFILL) {
+            wait_vmcnt<WAITN>();
+            __syncthreads();
+#pragma unroll
+            for (int b = 0; b < TM; ++b)
+                bf[1 - PAR][b] = *reinterpret_cast<const v4i *>(nxt + (mw * TM + b) * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        static_for_n<kTN>([&](auto a_tag) {
+            constexpr int a = decltype(a_tag)::value;
+#pragma unroll
+            for (int b = 0; b < TM; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[a], bf[PAR][b], acc[a][b], 0, 0, 0);
+            if constexpr (REFILL) af[a] = *reinterpret_cast<const v4i *>(nxt + (8 + a) * 1024);
+            if constexpr (ISSUE && a < P) issue_one(std::integral_constant<int, a>{}, kt + NS, st);
+            if constexpr (REFILL) __builtin_amdgcn_sched_barrier(0);
+        });
+        st = nst;
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using Yes = std::integral_constant<bool, true>;
+    using No = std::integral_constant<bool, false>;
+    using WFull = std::integral_constant<int, (NS - 2) * P>;
+    int kt = 0;
+    for (; kt + NS < KTg; kt += 2) {                  // KTg - NS is even (the launcher picks NS by the parity of KTg)
+        step(I0{}, Yes{}, Yes{}, WFull{}, kt);
+        step(I1{}, Yes{}, Yes{}, WFull{}, kt + 1);
+    }
+    // the last NS steps request nothing; step j of them leaves NS - 2 - j younger steps in flight
+    static_for_n<NS>([&](auto j_tag) {
+        constexpr int j = decltype(j_tag)::value;
+        using Par = std::integral_constant<int, j & 1>;
+        if constexpr (j + 1 < NS) step(Par{}, Yes{}, No{}, std::integral_constant<int, (NS - 2 - j) * P>{}, kt + j);
+        else step(Par{}, No{}, No{}, I0{}, kt + j);
+    });
+
+    // ---- the partial sums of every token sub-tile meet in LDS ------------------------------------
+    __syncthreads();                                  // every wave has read its last fragments
+    v4i *const xch = reinterpret_cast<v4i *>(smem);
+    constexpr int ROWB = kBN * 2 + 16;
+    int8_t *stg;
+    {
+        // Pair q finishes sub-tiles 2q, 2q + 1: each wave lays down the two it does not finish
+        // ([4 waves][2][9][64]) and adds what the other pair's wave of its token half left for it.
+        {
+            v4i *const out = xch + (wave * 2 * kTN) * 64 + lane;
+#pragma unroll
+            for (int a = 0; a < kTN; ++a) {
+                out[a * 64] = kg == 0 ? acc[a][2] : acc[a][0];
+                out[(kTN + a) * 64] = kg == 0 ? acc[a][3] : acc[a][1];
+            }
+        }
+        __syncthreads();
+        {
+            const v4i *const in = xch + (((1 - kg) * 2 + mw) * 2 * kTN) * 64 + lane;
+#pragma unroll
+            for (int a = 0; a < kTN; ++a) {
+                const v4i p0 = in[a * 64], p1 = in[(kTN + a) * 64];
+                if (kg == 0) { acc[a][0] += p0; acc[a][1] += p1; }
+                else { acc[a][2] += p0; acc[a][3] += p1; }
+            }
+        }
+        stg = smem + 4 * 2 * kTN * 1024 + wave * (16 * ROWB);   // behind the exchange area
+    }
+
+    // ---- epilogue of this wave's sub-tiles: 16 tokens x all 144 channels each ---------------------
+    const float *const par = reinterpret_cast<const float *>(smem + PAROFF);
+    static_for_n<TM>([&](auto b_tag) {
+        constexpr int b = decltype(b_tag)::value;
+        if (b * NG / TM == kg) {                      // wave-uniform
+            const int64_t m_own = m0 + mw * 64 + b * 16;
+            const float sxm = par[kParSx / 4 + mw * 64 + b * 16 + l16];
+#pragma unroll
+            for (int a = 0; a < kTN; ++a) {
+                const float4 s = *reinterpret_cast<const float4 *>(par + kParSw / 4 + a * 16 + lg * 4);
+                const float4 bi = *reinterpret_cast<const float4 *>(par + kParBias / 4 + a * 16 + lg * 4);
+                if constexpr (DEBUG) {
+                    *reinterpret_cast<int4 *>(g.acc_debug + (m_own + l16) * g.N + n0 + a * 16 + lg * 4) =
+                        make_int4(acc[a][b][0], acc[a][b][1], acc[a][b][2], acc[a][b][3]);
+                }
+                uint2 o;
+                o.x = pack_bf16x2((float)acc[a][b][0] * sxm * s.x + bi.x, (float)acc[a][b][1] * sxm * s.y + bi.y);
+                o.y = pack_bf16x2((float)acc[a][b][2] * sxm * s.z + bi.z, (float)acc[a][b][3] * sxm * s.w + bi.w);
+                *reinterpret_cast<uint2 *>(stg + l16 * ROWB + (a * 16 + lg * 4) * 2) = o;
+            }
+            __builtin_amdgcn_wave_barrier();
+            constexpr int LPR = kBN / 8;
+#pragma unroll
+            for (int i = 0; i < (16 * LPR + 63) / 64; ++i) {
+                const int id = i * 64 + lane;
+                if (id < 16 * LPR) {
+                    const int row = id / LPR, c = id - row * LPR;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * ROWB + c * 16);
+                    store_out16(g.Y + (m_own + row) * g.ldy + n0 + c * 8, v);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    });
 }
 
 // 16 bytes per thread between the row-major form [R, K] and the block form
@@ -324,9 +508,6 @@ void tiled_split(int64_t M, int N, int &n_big, int &nbn)
     const int64_t slots = 2 * (int64_t)num_cus();
     const int64_t p128 = M / 128;
     n_big = 0; nbn = 0;
-#ifdef TRDQ_X_ALLSMALL
-    return;
-#endif
     if (M % 256 != 0 || p128 * T <= slots) return;
     // tiles(nbn) = (M / 256) * nbn + (M / 128) * (T - nbn) <= slots
     int64_t need = (p128 * T - slots + (p128 / 2) - 1) / (p128 / 2);
@@ -334,9 +515,30 @@ void tiled_split(int64_t M, int N, int &n_big, int &nbn)
     n_big = (int)((M / 256) * nbn);
 }
 
+// The kernel that splits K inside the workgroup: two pairs, four stages for an even number of
+// k-steps per pair and three for an odd one (the main loop takes the steps two at a time).
+bool tiled_ksplit_applies(const GemmArgs &a)
+{
+    return a.K % 128 == 0 && a.K >= 1024 && (a.M / 128) * (int64_t)(a.N / kBN) <= num_cus();
+}
+
+template <int NS>
+hipError_t launch_ksplit(const GemmArgs &a, bool debug, hipStream_t st)
+{
+    GemmArgs g = a;
+    constexpr int lds = ks_lds<NS>();
+    auto go = [&](auto kern) -> hipError_t {
+        if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds); e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, dim3((unsigned)((a.M / 128) * (a.N / kBN))), dim3(256), lds, st, g);
+        return hipGetLastError();
+    };
+    return debug ? go(qgemm8_tiled_ksplit_kernel<NS, true>) : go(qgemm8_tiled_ksplit_kernel<NS, false>);
+}
+
 hipError_t launch_qgemm8_tiled(const GemmArgs &a, bool debug, hipStream_t st)
 {
     if (!tiled_supports(a)) return hipErrorInvalidValue;
+    if (tiled_ksplit_applies(a)) return ((a.K / 128) & 1) ? launch_ksplit<3>(a, debug, st) : launch_ksplit<4>(a, debug, st);
     int n_big, nbn;
     tiled_split(a.M, a.N, n_big, nbn);
     const int64_t total = n_big + (a.M / 128) * (a.N / kBN - nbn);
@@ -346,9 +548,6 @@ hipError_t launch_qgemm8_tiled(const GemmArgs &a, bool debug, hipStream_t st)
         hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(kThreads), kTiledLds, st, g, n_big, nbn);
         return hipGetLastError();
     };
-#ifdef TRDQ_X_PROF
-    debug = false;                                    // the debug pointer receives time stamps instead
-#endif
     return debug ? go(qgemm8_tiled_kernel<true>) : go(qgemm8_tiled_kernel<false>);
 }
 

@@ -49,8 +49,11 @@ def test_rotate_quant_tiled_is_rotate_quant_moved(oracle, M, K):
 
 # tall tiles only, short tiles only, both in one launch (more short tiles than two per compute unit),
 # one and several k-step pairs, the real layer widths
+# the last five reach the kernel that splits K over four wave pairs (at most one 128 x 144 tile per compute
+# unit, K a multiple of 512): two, four and six k-steps per pair, one tile and a full round of tiles
 TILED_SHAPES = [(128, 128, 144), (256, 256, 144), (384, 384, 288), (1024, 1152, 1152), (4096, 128, 3456),
-                (4096, 1152, 3456), (2048, 4608, 1152), (8192, 256, 1152), (3840, 640, 2304)]
+                (4096, 1152, 3456), (2048, 4608, 1152), (8192, 256, 1152), (3840, 640, 2304),
+                (128, 1024, 144), (256, 1024, 288), (384, 1536, 144), (1152, 2048, 432), (256, 1280, 144), (256, 1152, 288), (4096, 4608, 1152)]
 
 
 @pytest.mark.parametrize("M,K,N", TILED_SHAPES)
