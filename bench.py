@@ -387,6 +387,9 @@ def main():
             pk = measure_peaks(dev, quick=True, stream_sizes=shapes)
             out["roofline"]["measured_peak"] = pk["mfma_i8_tops"]
             out["roofline"]["frac_of_measured"] = out["roofline"]["achieved"] / pk["mfma_i8_tops"]
+            # the same register-only loop on random operand bytes (the clock drops with the pipes' power draw)
+            out["roofline"]["measured_peak_random_operands"] = pk["mfma_i8_data_tops"]
+            out["roofline"]["frac_of_measured_random_operands"] = out["roofline"]["achieved"] / pk["mfma_i8_data_tops"]
             if "roofline_rotate_quant" in out:
                 # the same mix of shapes as the step's rotate_quant launches, streamed without arithmetic
                 rq = out["roofline_rotate_quant"]

@@ -391,7 +391,9 @@ trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float 
 
 /* ---- the same pair on block-tiled activation codes (Eq. 10's product; int8 weights) ----
  * The codes of trdq_rotate_quant in 1 KB blocks of 16 tokens x 64 input channels: code (m, k) at
- *   ((m / 16) * (K / 64) + k / 64) * 1024 + (m % 16) * 64 + k % 64,
+ *   ((m / 16) * (K / 64) + k / 64) * 1024 + ((k % 64) / 16) * 256 + (m % 16) * 16 + k % 16
+ * (inside a block, 16 bytes of k of the 16 tokens lie together: the lane order of the int8
+ * matrix instruction's operand),
  * trdq_xq_tiled_nbytes(M, K) = ceil(M / 16) * 16 * K bytes (16-byte aligned; rows of a last,
  * partial group of 16 are not written).  A block is one operand fragment of the int8 matrix
  * instruction and one direct-to-LDS copy of eight whole cache lines, which lets the product run
@@ -487,6 +489,15 @@ int trdq_qgemm_num_variants(void);
  * *ops_host (may be NULL) <- operations of the launch, 2 * 16*16*64 per instruction.
  * Errors: workgroups outside 1..65536, waves outside 1..8, iters outside 1..2^20 -> ERR_RANGE.
  *
+ * trdq_peak_mfma_i8_data: the same loop on operands of pseudo-random bytes.  The chip sets its clock
+ * by the power it draws, and a matrix pipe draws more the more of its inputs toggle: this is the
+ * yardstick for a product of quantised codes, the one above the one for the published figure.
+ * Lane t of a workgroup (t = threadIdx) holds, as 16 bytes each, A fragments i = 0, 1 and B
+ * fragments i = 0..3 whose 32-bit word j is h(977 t + 31 i + 7 j + 1) resp. h(131 t + 17 i + 3 j + 5),
+ * h(x): x ^= x >> 16; x *= 0x7feb352d; x ^= x >> 15; x *= 0x846ca68b; x ^= x >> 16 (mod 2^32);
+ * accumulator k = 0..7 multiplies A[k & 1] by B[k >> 1]; sink_dev receives, per lane, the sum of
+ * its 32 accumulator elements (wrapping in int32).  Arguments and errors as trdq_peak_mfma_i8.
+ *
  * trdq_peak_stream: reads n_elems 16-bit elements and writes the low byte of each (2 bytes in,
  * 1 byte out per element -- the traffic mix of trdq_rotate_quant -- with no arithmetic), 16 bytes
  * per load.  src_dev 16-byte aligned, dst_dev int8 [n_elems] 8-byte aligned, n_elems % 8 == 0
@@ -494,6 +505,8 @@ int trdq_qgemm_num_variants(void);
  * Both are asynchronous on `stream` and allocate nothing. */
 trdq_status trdq_peak_mfma_i8(int32_t *sink_dev, int workgroups, int waves, int iters, int64_t *ops_host,
                               void *stream);
+trdq_status trdq_peak_mfma_i8_data(int32_t *sink_dev, int workgroups, int waves, int iters, int64_t *ops_host,
+                                   void *stream);
 trdq_status trdq_peak_stream(const void *src_dev, void *dst_dev, int64_t n_elems, void *stream);
 
 #ifdef __cplusplus

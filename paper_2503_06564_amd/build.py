@@ -29,8 +29,8 @@ SOURCE_FLAGS = {"qgemm_dma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
                 "calibrate.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
-def _compile(src, extra):
-    obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
+def _compile(src, extra, obj_dir):
+    obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
     cmd = ["hipcc", *FLAGS, *SOURCE_FLAGS.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     out = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
@@ -40,18 +40,22 @@ def _compile(src, extra):
     return obj, out
 
 
-def build(verbose=False, extra=()):
-    os.makedirs(OBJ_DIR, exist_ok=True)
+def build(verbose=False, extra=(), lib=None, obj_dir=None):
+    """Compiles every source and links the library; lib / obj_dir name another output (a build with
+    extra preprocessor switches, e.g. the phase probe) beside the default one."""
+    lib = lib or LIB
+    obj_dir = obj_dir or OBJ_DIR
+    os.makedirs(obj_dir, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        results = list(ex.map(lambda s: _compile(s, list(extra)), SOURCES))
+        results = list(ex.map(lambda s: _compile(s, list(extra), obj_dir), SOURCES))
     if verbose:
         for _, out in results:
             if out:
                 print(out)
     objs = [o for o, _ in results]
-    cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs]
+    cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", lib, *objs]
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":

@@ -565,8 +565,8 @@ trdq_status trdq_cosine_similarity_static(const void *A_dev, const void *B_dev, 
                                                      stride_b, acc, cos_dev, static_cast<hipStream_t>(stream)));
 }
 
-trdq_status trdq_peak_mfma_i8(int32_t *sink_dev, int workgroups, int waves, int iters, int64_t *ops_host,
-                              void *stream)
+static trdq_status peak_mfma_impl(int32_t *sink_dev, int workgroups, int waves, int iters, int64_t *ops_host,
+                                  void *stream, bool random_data)
 {
     if (!sink_dev) return TRDQ_ERR_NULL;
     if (workgroups <= 0 || workgroups > 65536 || waves <= 0 || waves > 8 || iters <= 0 || iters > (1 << 20))
@@ -574,7 +574,20 @@ trdq_status trdq_peak_mfma_i8(int32_t *sink_dev, int workgroups, int waves, int 
     if (!aligned(sink_dev, 4)) return TRDQ_ERR_SHAPE;
     // one 16x16x64 instruction: 16*16*64 multiply-adds
     if (ops_host) *ops_host = (int64_t)workgroups * waves * iters * trdq::peak_mfma_independent() * 2 * 16 * 16 * 64;
-    return hip_status(trdq::launch_peak_mfma_i8(sink_dev, workgroups, waves, iters, static_cast<hipStream_t>(stream)));
+    return hip_status(trdq::launch_peak_mfma_i8(sink_dev, workgroups, waves, iters, static_cast<hipStream_t>(stream),
+                                                random_data));
+}
+
+trdq_status trdq_peak_mfma_i8(int32_t *sink_dev, int workgroups, int waves, int iters, int64_t *ops_host,
+                              void *stream)
+{
+    return peak_mfma_impl(sink_dev, workgroups, waves, iters, ops_host, stream, false);
+}
+
+trdq_status trdq_peak_mfma_i8_data(int32_t *sink_dev, int workgroups, int waves, int iters, int64_t *ops_host,
+                                   void *stream)
+{
+    return peak_mfma_impl(sink_dev, workgroups, waves, iters, ops_host, stream, true);
 }
 
 trdq_status trdq_peak_stream(const void *src_dev, void *dst_dev, int64_t n_elems, void *stream)

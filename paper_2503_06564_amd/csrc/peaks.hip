@@ -41,6 +41,44 @@ __global__ __launch_bounds__(512) void peak_mfma_i8_kernel(int32_t *sink, int it
     sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+__device__ __forceinline__ uint32_t hash32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
+    return x;
+}
+
+// The same loop on operands of pseudo-random bytes (two A and four B fragments, so that consecutive
+// instructions see different inputs).  What a matrix pipe draws depends on how many of its inputs
+// toggle, and the chip sets its clock by what it draws: this is the yardstick for a product of
+// quantised codes, the one above the one for the published figure.
+__global__ __launch_bounds__(512) void peak_mfma_i8_data_kernel(int32_t *sink, int iters)
+{
+    v4i a[2], b[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i][j] = (int)hash32(threadIdx.x * 977u + i * 31u + j * 7u + 1u);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) b[i][j] = (int)hash32(threadIdx.x * 131u + i * 17u + j * 3u + 5u);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) asm volatile("" : "+v"(a[i]));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(b[i]));
+    v4i acc[kIndependent];
+#pragma unroll
+    for (int k = 0; k < kIndependent; ++k) acc[k] = v4i{0, 0, 0, 0};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int k = 0; k < kIndependent; ++k)
+            acc[k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[k & 1], b[k >> 1], acc[k], 0, 0, 0);
+    }
+    int32_t s = 0;
+#pragma unroll
+    for (int k = 0; k < kIndependent; ++k) s += acc[k].x + acc[k].y + acc[k].z + acc[k].w;
+    sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 // NT: non-temporal accesses, which pay off once the buffers no longer fit the last-level cache
 template <bool NT>
 __global__ __launch_bounds__(256) void peak_stream_kernel(const v4u *__restrict__ src, v2u *__restrict__ dst,
@@ -61,9 +99,10 @@ __global__ __launch_bounds__(256) void peak_stream_kernel(const v4u *__restrict_
 
 int peak_mfma_independent() { return kIndependent; }
 
-hipError_t launch_peak_mfma_i8(int32_t *sink, int workgroups, int waves, int iters, hipStream_t st)
+hipError_t launch_peak_mfma_i8(int32_t *sink, int workgroups, int waves, int iters, hipStream_t st, bool random_data)
 {
-    hipLaunchKernelGGL(peak_mfma_i8_kernel, dim3(workgroups), dim3(64 * waves), 0, st, sink, iters);
+    if (random_data) hipLaunchKernelGGL(peak_mfma_i8_data_kernel, dim3(workgroups), dim3(64 * waves), 0, st, sink, iters);
+    else hipLaunchKernelGGL(peak_mfma_i8_kernel, dim3(workgroups), dim3(64 * waves), 0, st, sink, iters);
     return hipGetLastError();
 }
 

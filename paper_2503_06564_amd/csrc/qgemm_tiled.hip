@@ -11,9 +11,10 @@
 // workgroups fit a compute unit only if a k-step is 64 bytes deep (three stages of 25 KB each),
 // and a 64-byte-deep copy of row-major operands fetches half cache lines, which doubles the
 // traffic between L2 and L1.  Hence both operands are stored in 1 KB blocks of 16 rows x 64 bytes
-// of k (block (row / 16, k / 64) at ((row / 16) * K / 64 + k / 64) * 1024, rows 64 bytes apart):
+// of k (block (row / 16, k / 64) at ((row / 16) * K / 64 + k / 64) * 1024; inside a block the
+// 16-byte piece p of row r at p * 256 + r * 16, the lane order of the matrix instruction's operand):
 // one direct-to-LDS copy moves one block, eight whole cache lines, and one block is one operand
-// fragment of v_mfma_i32_16x16x64_i8.  trdq_rotate_quant_tiled writes activations in this form;
+// fragment of v_mfma_i32_16x16x64_i8, read back from LDS as 1 KB in lane order.  trdq_rotate_quant_tiled writes activations in this form;
 // the weights get a second copy of their codes in it when they are prepared.
 //
 // A launch may mix tile heights: workgroups [0, n_big) take 256-token tiles over the first nbn
@@ -50,8 +51,10 @@ __device__ __forceinline__ void static_for_n(F &&f)
     static_for_seq(std::make_integer_sequence<int, N>{}, f);
 }
 
-// 16-byte piece p of row r of a block sits at r * 64 + ((p ^ swizzle(r)) * 16) in LDS
-__device__ __forceinline__ int blk_off(int r, int p) { return r * 64 + ((p ^ chunk_swizzle<64>(r)) * 16); }
+// A block in memory and in LDS: the 16-byte piece p (16 bytes of k) of row r sits at p * 256 + r * 16,
+// which is lane (16 p + r)'s operand of the matrix instruction at 16 bytes per lane: a copy and a
+// fragment read both move the block's 1 KB in lane order, free of LDS bank conflicts.
+__device__ __forceinline__ int blk_off(int r, int p) { return p * 256 + r * 16; }
 
 __device__ __forceinline__ void copy_1k_if(int on, uint32_t voff, const void *sbase, uint32_t lds_addr)
 {
@@ -81,6 +84,10 @@ __device__ __forceinline__ void run_tile(const GemmArgs &g, int tm, int tn, int8
     static_assert(2 * PMIN + 4 < 64, "vmcnt is a 6-bit counter");
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t *)smem;
+#ifdef TRDQ_PROBE_PHASES
+    const uint64_t clk_c0 = __builtin_readcyclecounter();
+    const uint64_t clk_t0 = wall_clock64();
+#endif
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -92,7 +99,7 @@ __device__ __forceinline__ void run_tile(const GemmArgs &g, int tm, int tn, int8
     const int64_t gstride = (int64_t)KT * 1024;      // bytes from one 16-row group to the next
     const int8_t *const xsrc = g.Xq + (m0 / 16 + wave * TM) * gstride;
     const int8_t *const wsrc = static_cast<const int8_t *>(g.Wc) + (int64_t)(n0 / 16) * gstride;
-    const uint32_t voff = (uint32_t)blk_off(lane >> 2, lane & 3);
+    const uint32_t voff = (uint32_t)(lane * 16);        // copies keep the block's order
 
     const int8_t *xs[TM], *ws[2];
 #pragma unroll
@@ -137,6 +144,10 @@ __device__ __forceinline__ void run_tile(const GemmArgs &g, int tm, int tn, int8
     }
     __syncthreads();
 
+#ifdef TRDQ_PROBE_PHASES
+    const uint64_t clk_c1 = __builtin_readcyclecounter();
+    const uint64_t clk_t1 = wall_clock64();
+#endif
     const int fro = blk_off(l16, lg);                 // the lane's piece of a fragment block
     v4i acc[kTN][TM];
 #pragma unroll
@@ -200,6 +211,10 @@ __device__ __forceinline__ void run_tile(const GemmArgs &g, int tm, int tn, int8
     step(I0{}, Yes{}, No{}, I0{}, KT - 2);            // the last step's blocks: nothing younger is in flight
     step(I1{}, No{}, No{}, I0{}, KT - 1);
 
+#ifdef TRDQ_PROBE_PHASES
+    const uint64_t clk_c2 = __builtin_readcyclecounter();
+    const uint64_t clk_t2 = wall_clock64();
+#endif
     // ---- epilogue: y = float(acc) * s_x[m] * s_w[n] + bias[n] -> bf16.  One token tile (16 tokens x
     // 144 channels) at a time is laid out in the wave's part of the idle ring and read back row by
     // row, so that a store instruction writes whole 288-byte row segments, 16 bytes per lane.
@@ -240,6 +255,18 @@ __device__ __forceinline__ void run_tile(const GemmArgs &g, int tm, int tn, int8
         }
         __builtin_amdgcn_wave_barrier();
     }
+#ifdef TRDQ_PROBE_PHASES
+    if (tid == 0 && g.acc_debug) {
+        const uint64_t clk_c3 = __builtin_readcyclecounter();
+        uint32_t hw, xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        uint64_t *o = reinterpret_cast<uint64_t *>(g.acc_debug) + (int64_t)blockIdx.x * 16;
+        o[0] = clk_t0; o[1] = clk_t1; o[2] = clk_t2; o[3] = wall_clock64();
+        o[4] = clk_c0; o[5] = clk_c1; o[6] = clk_c2; o[7] = clk_c3;
+        o[8] = hw; o[9] = xcc; o[10] = BM; o[11] = 1;
+    }
+#endif
 }
 
 template <bool DEBUG>
@@ -307,7 +334,7 @@ __global__ __launch_bounds__(128 * kKsPairs) void qgemm8_tiled_ksplit_kernel(Gem
     const int64_t kofs = (int64_t)kg * KTg * 1024;   // this pair's first k-step
     const int8_t *const xsrc = g.Xq + (m0 / 16 + mw * TM) * gstride + kofs;
     const int8_t *const wsrc = static_cast<const int8_t *>(g.Wc) + (int64_t)(n0 / 16) * gstride + kofs;
-    const uint32_t voff = (uint32_t)blk_off(lane >> 2, lane & 3);
+    const uint32_t voff = (uint32_t)(lane * 16);        // copies keep the block's order
     int8_t *const ring = smem + kg * RING;
     const uint32_t ring0 = lds0 + kg * RING;
 
@@ -485,7 +512,7 @@ __global__ void retile_kernel(const int8_t *__restrict__ src, int8_t *__restrict
     if (idx >= R * cpr) return;
     const int64_t row = idx / cpr;
     const int c = (int)(idx - row * cpr);
-    const int64_t t = ((row >> 4) * (K >> 6) + (c >> 2)) * 1024 + (row & 15) * 64 + (c & 3) * 16;
+    const int64_t t = ((row >> 4) * (K >> 6) + (c >> 2)) * 1024 + (c & 3) * 256 + (row & 15) * 16;
     const int64_t r = row * K + (int64_t)c * 16;
     if (TO_TILED) *reinterpret_cast<uint4 *>(dst + t) = *reinterpret_cast<const uint4 *>(src + r);
     else *reinterpret_cast<uint4 *>(dst + r) = *reinterpret_cast<const uint4 *>(src + t);
@@ -548,6 +575,9 @@ hipError_t launch_qgemm8_tiled(const GemmArgs &a, bool debug, hipStream_t st)
         hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(kThreads), kTiledLds, st, g, n_big, nbn);
         return hipGetLastError();
     };
+#ifdef TRDQ_PROBE_PHASES
+    debug = false;                                    // the debug pointer receives time stamps instead
+#endif
     return debug ? go(qgemm8_tiled_kernel<true>) : go(qgemm8_tiled_kernel<false>);
 }
 

@@ -301,9 +301,9 @@ __global__ __launch_bounds__(MAXT) void rotate_quant_kernel(
                     c[2 * q + 1] = pack4_low_bytes(code_bits(out[i][4][q]), code_bits(out[i][5][q]),
                                                    code_bits(out[i][6][q]), code_bits(out[i][7][q]));
                 }
-                // row-major: the two 64-byte halves of the block inside the token's row; tiled: the
-                // token's 64-byte rows of the two 1 KB blocks (16 tokens x 64 k) of this 128-block
-                int8_t *dst = tiled ? Xq + ((tg * (K >> 6) + 2 * b) * 16 + r) * (int64_t)64 + g * 16
+                // row-major: the two 64-byte halves of the block inside the token's row; tiled: piece g of
+                // token r in the two 1 KB blocks (16 tokens x 64 k, piece-major) of this 128-block
+                int8_t *dst = tiled ? Xq + (tg * (K >> 6) + 2 * b) * (int64_t)1024 + g * 256 + r * 16
                                     : Xq + token * (int64_t)K + b * kBlock + g * 16;
                 *reinterpret_cast<uint4 *>(dst) = make_uint4(c[0], c[1], c[2], c[3]);
                 *reinterpret_cast<uint4 *>(dst + (tiled ? 1024 : 64)) = make_uint4(c[4], c[5], c[6], c[7]);

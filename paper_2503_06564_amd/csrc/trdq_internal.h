@@ -117,7 +117,7 @@ int num_cus();
 
 // yardstick kernels (peaks.hip)
 int peak_mfma_independent();
-hipError_t launch_peak_mfma_i8(int32_t *sink, int workgroups, int waves, int iters, hipStream_t st);
+hipError_t launch_peak_mfma_i8(int32_t *sink, int workgroups, int waves, int iters, hipStream_t st, bool random_data = false);
 hipError_t launch_peak_stream(const void *src, void *dst, int64_t n_elems, hipStream_t st);
 size_t greedy_workspace_bytes(int64_t Mc, int K);
 hipError_t launch_greedy_rotation(const uint16_t *X, int64_t Mc, int K, int64_t ldx, const float *diag,

@@ -159,6 +159,21 @@ def measure_peaks(dev, quick=False, emit=None, stream_sizes=None):
              tops=round(tops, 1))
         best = max(best, tops)
     res["mfma_i8_tops"] = best
+    # the same loop on pseudo-random operand bytes: the clock the chip holds while its matrix pipes
+    # work on data that toggles, which is what a product of quantised codes runs at
+    best_data = 0.0
+    for wgs, waves in shapes:
+        sink = torch.zeros(wgs * waves * 64, dtype=torch.int32, device=dev)
+        ops = [0]
+
+        def run_data(i):
+            ops[0] = trdq.peak_mfma_i8(sink, wgs, waves, iters, random_data=True)
+        t = _timeit(run_data, 5, 2)
+        tops = ops[0] / t / 1e6
+        emit(what="peak int8 matrix issue (registers only, random operand bytes)", workgroups=wgs, waves=waves,
+             us=round(t, 1), tops=round(tops, 1))
+        best_data = max(best_data, tops)
+    res["mfma_i8_data_tops"] = best_data
     res["stream_gbs"] = {}
     sizes = stream_sizes or ((4096, 1152), (4096, 4608), (32768, 1152), (32768, 4608))
     for M, K in sizes:

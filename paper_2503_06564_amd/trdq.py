@@ -28,7 +28,7 @@ SYMBOLS = [
     "trdq_rotation_create", "trdq_rotation_destroy", "trdq_prepare_weights_dense", "trdq_rotate_quant_dense",
     "trdq_greedy_rotation", "trdq_prepare_weights_dense_rpr", "trdq_rotate_quant_dense_rpr",
     "trdq_channel_absmax_dense", "trdq_greedy_rotation_second",
-    "trdq_peak_mfma_i8", "trdq_peak_stream",
+    "trdq_peak_mfma_i8", "trdq_peak_mfma_i8_data", "trdq_peak_stream",
     "trdq_xq_tiled_nbytes", "trdq_rotate_quant_tiled", "trdq_xq_untile", "trdq_qgemm_tiled_supported", "trdq_qgemm_tiled_preferred",
     "trdq_qgemm_tiled",
     "trdq_rotate_quant_rpr_asym", "trdq_prepare_weights_asym", "trdq_weights_export_zero_points", "trdq_qgemm_asym_weights",
@@ -98,6 +98,7 @@ def lib():
         L.trdq_qgemm_asym_weights.argtypes = [p, p, p, p, p, i64, p, p, i64, p, p]
         L.trdq_share_plan.argtypes = [p, i32, i32, C.c_float, p]
         L.trdq_peak_mfma_i8.argtypes = [p, i32, i32, i32, C.POINTER(C.c_int64), p]
+        L.trdq_peak_mfma_i8_data.argtypes = [p, i32, i32, i32, C.POINTER(C.c_int64), p]
         L.trdq_peak_stream.argtypes = [p, p, i64, p]
         L.trdq_rotation_create.argtypes = [p, p, i32, i32, p, C.POINTER(p)]
         L.trdq_rotation_destroy.argtypes = [p]
@@ -414,11 +415,13 @@ def cosine_similarity_static(A, B, out, stream=None):
            "trdq_cosine_similarity_static")
 
 
-def peak_mfma_i8(sink, workgroups, waves, iters, stream=None):
-    """Yardstick: iters x 8 register-only int8 matrix instructions per wave; returns the launch's operation count."""
+def peak_mfma_i8(sink, workgroups, waves, iters, stream=None, random_data=False):
+    """Yardstick: iters x 8 register-only int8 matrix instructions per wave, on operands of ones or of
+    pseudo-random bytes; returns the launch's operation count."""
     ops = C.c_int64(0)
-    _check(lib().trdq_peak_mfma_i8(_ptr(sink), workgroups, waves, iters, C.byref(ops), _stream(stream)),
-           "trdq_peak_mfma_i8")
+    f = lib().trdq_peak_mfma_i8_data if random_data else lib().trdq_peak_mfma_i8
+    _check(f(_ptr(sink), workgroups, waves, iters, C.byref(ops), _stream(stream)),
+           "trdq_peak_mfma_i8_data" if random_data else "trdq_peak_mfma_i8")
     return ops.value
 
 

@@ -245,6 +245,8 @@ def test_yardstick_argument_errors_before_any_gpu_call():
     assert L.trdq_peak_mfma_i8(0x1000, 256, 4, 0, None, None) == trdq.ERR_RANGE
     assert L.trdq_peak_mfma_i8(0x1000, 256, 4, (1 << 20) + 1, None, None) == trdq.ERR_RANGE
     assert L.trdq_peak_mfma_i8(0x1002, 256, 4, 10, None, None) == trdq.ERR_SHAPE
+    assert L.trdq_peak_mfma_i8_data(None, 256, 4, 10, None, None) == trdq.ERR_NULL
+    assert L.trdq_peak_mfma_i8_data(0x1000, 256, 9, 10, None, None) == trdq.ERR_RANGE
     assert L.trdq_peak_stream(0x1000, 0x2000, 12, None) == trdq.ERR_SHAPE
     assert L.trdq_peak_stream(0x1000, 0x2000, -8, None) == trdq.ERR_SHAPE
     assert L.trdq_peak_stream(None, 0x2000, 8, None) == trdq.ERR_NULL

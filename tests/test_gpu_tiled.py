@@ -19,7 +19,8 @@ def say(msg):
 def tile_host(a):
     """[M, K] int8 (M % 16 == 0) -> the block-tiled byte order, on the host, from the stated formula."""
     M, K = a.shape
-    return np.ascontiguousarray(a.reshape(M // 16, 16, K // 64, 64).transpose(0, 2, 1, 3)).reshape(-1)
+    # [row group][row][k block][piece][16 bytes] -> [row group][k block][piece][row][16 bytes]
+    return np.ascontiguousarray(a.reshape(M // 16, 16, K // 64, 4, 16).transpose(0, 2, 3, 1, 4)).reshape(-1)
 
 
 @pytest.mark.parametrize("M,K", [(16, 128), (37, 256), (128, 1152), (1000, 1152), (130, 4608), (4096, 1152)])
