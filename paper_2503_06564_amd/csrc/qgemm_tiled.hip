@@ -53,7 +53,7 @@ __device__ __forceinline__ void static_for_n(F &&f)
 
 // A block in memory and in LDS: the 16-byte piece p (16 bytes of k) of row r sits at p * 256 + r * 16,
 // which is lane (16 p + r)'s operand of the matrix instruction at 16 bytes per lane: a copy and a
-// fragment read both move the block's 1 KB in lane order, free of LDS bank conflicts.
+// fragment read both move the block's 1 KB in lane order.
 __device__ __forceinline__ int blk_off(int r, int p) { return p * 256 + r * 16; }
 
 __device__ __forceinline__ void copy_1k_if(int on, uint32_t voff, const void *sbase, uint32_t lds_addr)
