@@ -225,13 +225,21 @@ __device__ __forceinline__ void run_tile(const GemmArgs &g, int tm, int tn, int8
     constexpr int ROWB = kBN * 2 + 16;
     int8_t *const stg = smem + wave * (16 * ROWB);
     const int64_t m_wave = m0 + wave * (BM / 4);
+    // The lane's channel scales and biases are read one channel tile ahead of their use: read where
+    // they are used, every one of the 9 x TM reads waits out an LDS round trip with nothing else to issue.
+    const float *const psw = par + kParSw / 4 + lg * 4, *const pbi = par + kParBias / 4 + lg * 4;
+    float4 s_nxt = *reinterpret_cast<const float4 *>(psw), bi_nxt = *reinterpret_cast<const float4 *>(pbi);
 #pragma unroll
     for (int b = 0; b < TM; ++b) {
         const float sxm = par[kParSx / 4 + wave * (BM / 4) + b * 16 + l16];
 #pragma unroll
         for (int a = 0; a < kTN; ++a) {
-            const float4 s = *reinterpret_cast<const float4 *>(par + kParSw / 4 + a * 16 + lg * 4);
-            const float4 bi = *reinterpret_cast<const float4 *>(par + kParBias / 4 + a * 16 + lg * 4);
+            const float4 s = s_nxt, bi = bi_nxt;
+            {
+                const int an = (a + 1) % kTN;         // wraps to the first tile for the next token tile
+                s_nxt = *reinterpret_cast<const float4 *>(psw + an * 16);
+                bi_nxt = *reinterpret_cast<const float4 *>(pbi + an * 16);
+            }
             if constexpr (DEBUG) {
                 const int64_t m = m_wave + b * 16 + l16;
                 *reinterpret_cast<int4 *>(g.acc_debug + m * g.N + n0 + a * 16 + lg * 4) =
@@ -469,6 +477,12 @@ __global__ __launch_bounds__(128 * kKsPairs) void qgemm8_tiled_ksplit_kernel(Gem
 
     // ---- epilogue of this wave's sub-tiles: 16 tokens x all 144 channels each ---------------------
     const float *const par = reinterpret_cast<const float *>(smem + PAROFF);
+    float4 sw_r[kTN], bi_r[kTN];                      // the lane's channel scales and biases, read once
+#pragma unroll
+    for (int a = 0; a < kTN; ++a) {
+        sw_r[a] = *reinterpret_cast<const float4 *>(par + kParSw / 4 + a * 16 + lg * 4);
+        bi_r[a] = *reinterpret_cast<const float4 *>(par + kParBias / 4 + a * 16 + lg * 4);
+    }
     static_for_n<TM>([&](auto b_tag) {
         constexpr int b = decltype(b_tag)::value;
         if (b * NG / TM == kg) {                      // wave-uniform
@@ -476,8 +490,8 @@ __global__ __launch_bounds__(128 * kKsPairs) void qgemm8_tiled_ksplit_kernel(Gem
             const float sxm = par[kParSx / 4 + mw * 64 + b * 16 + l16];
 #pragma unroll
             for (int a = 0; a < kTN; ++a) {
-                const float4 s = *reinterpret_cast<const float4 *>(par + kParSw / 4 + a * 16 + lg * 4);
-                const float4 bi = *reinterpret_cast<const float4 *>(par + kParBias / 4 + a * 16 + lg * 4);
+                const float4 s = sw_r[a];
+                const float4 bi = bi_r[a];
                 if constexpr (DEBUG) {
                     *reinterpret_cast<int4 *>(g.acc_debug + (m_own + l16) * g.N + n0 + a * 16 + lg * 4) =
                         make_int4(acc[a][b][0], acc[a][b][1], acc[a][b][2], acc[a][b][3]);
