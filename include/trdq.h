@@ -114,8 +114,9 @@ trdq_status trdq_weights_export(const trdq_weights *w, int8_t *codes_host, float
 trdq_status trdq_weights_export_packed(const trdq_weights *w, uint8_t *packed_host);
 
 /* Bytes of the weight format (codes + scales): K*N + 4N for wbits 8, K*N/2 + 4*(K/128)*N for wbits 4.
- * An int8 set whose N is a multiple of 144 holds its codes a second time, block-tiled for
- * trdq_qgemm_tiled (another K*N bytes of device memory, not part of this figure). */
+ * An int8 set whose N is a multiple of 144, and an int4 set whose N is a multiple of 128, holds
+ * its codes a second time, block-tiled for trdq_qgemm_tiled (another K*N resp. K*N/2 bytes of
+ * device memory, not part of this figure). */
 trdq_status trdq_weights_nbytes(const trdq_weights *w, int64_t *nbytes_out);
 
 void trdq_weights_destroy(trdq_weights *w);
@@ -389,7 +390,7 @@ trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float 
                        const float *bias_dev, void *Y_dev, int64_t ldy,
                        int32_t *acc_debug_dev, void *stream);
 
-/* ---- the same pair on block-tiled activation codes (Eq. 10's product; int8 weights) ----
+/* ---- the same pair on block-tiled activation codes (Eq. 10's product; int8 and int4 weights) ----
  * The codes of trdq_rotate_quant in 1 KB blocks of 16 tokens x 64 input channels: code (m, k) at
  *   ((m / 16) * (K / 64) + k / 64) * 1024 + ((k % 64) / 16) * 256 + (m % 16) * 16 + k % 16
  * (inside a block, 16 bytes of k of the 16 tokens lie together: the lane order of the int8
@@ -402,10 +403,15 @@ trdq_status trdq_qgemm(const trdq_weights *w, const int8_t *Xq_dev, const float 
  *   (wider -> ERR_UNSUPPORTED).  Codes and scales are those of trdq_rotate_quant, bit for bit.
  * trdq_xq_untile: Xq_dev [M, K] dense <- Xt_dev (for inspection and for the row-major calls).
  * trdq_qgemm_tiled: arguments, values and errors of trdq_qgemm with Xt_dev in place of Xq_dev.
- *   Takes the shapes for which trdq_qgemm_tiled_supported(w, M) is 1 -- int8 weights (wbits 8
- *   or 6) with N % 144 == 0, M % 128 == 0 -- and an output with ldy % 8 == 0 on a 16-byte
+ *   Takes the shapes for which trdq_qgemm_tiled_supported(w, M) is 1 -- M % 128 == 0 and either
+ *   int8 weights (wbits 8 or 6) with N % 144 == 0, or int4 weights with N % 128 == 0 and at
+ *   least three scale groups (K >= 384) -- and an output with ldy % 8 == 0 on a 16-byte
  *   aligned base; anything else -> ERR_UNSUPPORTED (use trdq_qgemm on row-major codes).
- *   The integer sums are those of trdq_qgemm (exact), the epilogue is the same arithmetic. */
+ *   The integer sums are those of trdq_qgemm (exact; acc_debug_dev as there, [K/128, M, N] for
+ *   int4 weights), the epilogue is the same arithmetic, and so are the float folds of the int4
+ *   scale groups, in the same order: the outputs are those of trdq_qgemm bit for bit.
+ *   Such weight sets keep a second copy of their codes in the block form (K * N more bytes for
+ *   int8, K * N / 2 for int4). */
 int64_t trdq_xq_tiled_nbytes(int64_t M, int K);      /* -1 for M < 0, K <= 0 or K % 128 != 0 */
 trdq_status trdq_rotate_quant_tiled(const void *X_dev, int64_t M, int K, int64_t ldx,
                                     const float *diag_dev, int block,
@@ -413,8 +419,9 @@ trdq_status trdq_rotate_quant_tiled(const void *X_dev, int64_t M, int K, int64_t
 trdq_status trdq_xq_untile(const int8_t *Xt_dev, int64_t M, int K, int8_t *Xq_dev, void *stream);
 int trdq_qgemm_tiled_supported(const trdq_weights *w, int64_t M);
 /* 1 where the tiled pair is also the faster one by the library's measured rule (K <= 4608 and
- * either more than one 128 x 144 output tile per compute unit, or at most one and K >= 1024):
- * what trdq_layer_forward takes by itself. */
+ * either more than one 128 x 144 output tile per compute unit, or at most one and K >= 1024;
+ * int4 weights: at least one 128 x 128 tile per compute unit): what trdq_layer_forward takes by
+ * itself. */
 int trdq_qgemm_tiled_preferred(const trdq_weights *w, int64_t M);
 trdq_status trdq_qgemm_tiled(const trdq_weights *w, const int8_t *Xt_dev, const float *sx_dev, int64_t M,
                              const float *bias_dev, void *Y_dev, int64_t ldy,

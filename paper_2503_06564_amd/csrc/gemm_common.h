@@ -119,6 +119,10 @@ hipError_t launch_qgemm4_dma(const GemmArgs &a, bool debug, int variant, hipStre
 bool tiled_supports(const GemmArgs &a);
 hipError_t launch_qgemm8_tiled(const GemmArgs &a, bool debug, hipStream_t st);
 hipError_t launch_retile(const int8_t *src, int8_t *dst, int64_t R, int K, bool to_tiled, hipStream_t st);
+// int4 weights on block-tiled operands (qgemm_tiled.hip): a.Wc holds the block form of the packed codes
+bool tiled4_supports(const GemmArgs &a);
+hipError_t launch_qgemm4_tiled(const GemmArgs &a, bool debug, hipStream_t st);
+hipError_t launch_retile_w4(const void *src, void *dst, int64_t N, int K, hipStream_t st);
 
 // 256 x 256 tile kernel with a hand-scheduled main loop (qgemm_wide.hip).
 bool wide_supports(const GemmArgs &a);

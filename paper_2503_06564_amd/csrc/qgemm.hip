@@ -354,12 +354,12 @@ hipError_t launch_qgemm(const Weights &w, const int8_t *Xq, const float *sx, con
 
 bool qgemm_tiled_supports(const Weights &w, int64_t M, const void *Y, int64_t ldy)
 {
-    if (w.wbits != 8 || !w.codes_tiled) return false;
+    if (!w.codes_tiled || (w.wbits != 8 && w.wbits != 4)) return false;
     GemmArgs a;
     a.Xq = nullptr; a.Wc = w.codes_tiled; a.sx = nullptr; a.sw = w.scales; a.bias = nullptr;
     a.Y = static_cast<uint16_t *>(const_cast<void *>(Y)); a.acc_debug = nullptr; a.M = M; a.ldy = ldy; a.K = w.K; a.N = w.N;
     a.tiles_m = a.tiles_n = 0;
-    return tiled_supports(a);
+    return w.wbits == 4 ? tiled4_supports(a) : tiled_supports(a);
 }
 
 hipError_t launch_qgemm_tiled(const Weights &w, const int8_t *Xt, const float *sx, int64_t M, const float *bias,
@@ -371,7 +371,7 @@ hipError_t launch_qgemm_tiled(const Weights &w, const int8_t *Xt, const float *s
     a.Xq = Xt; a.Wc = w.codes_tiled; a.sx = sx; a.sw = w.scales; a.bias = bias; a.Y = Y;
     a.acc_debug = acc_debug; a.M = M; a.ldy = ldy; a.K = w.K; a.N = w.N;
     a.tiles_m = a.tiles_n = 0;
-    return launch_qgemm8_tiled(a, acc_debug != nullptr, st);
+    return w.wbits == 4 ? launch_qgemm4_tiled(a, acc_debug != nullptr, st) : launch_qgemm8_tiled(a, acc_debug != nullptr, st);
 }
 
 bool qgemm_tiled_pays(int64_t M, int K, int N)
@@ -384,6 +384,11 @@ bool qgemm_tiled_pays(int64_t M, int K, int N)
     const int64_t tiles = (M / 128) * (int64_t)(N / 144);
     if (tiles <= num_cus()) return K >= 1024;
     return !(K >= 2304 && tiles <= 2 * (int64_t)num_cus());
+}
+
+hipError_t launch_retile_w4_codes(const void *src, void *dst, int64_t N, int K, hipStream_t st)
+{
+    return launch_retile_w4(src, dst, N, K, st);
 }
 
 hipError_t launch_retile_rows(const int8_t *src, int8_t *dst, int64_t R, int K, bool to_tiled, hipStream_t st)

@@ -517,6 +517,269 @@ __global__ __launch_bounds__(128 * kKsPairs) void qgemm8_tiled_ksplit_kernel(Gem
     });
 }
 
+// ---- int4 weights on block-tiled operands ---------------------------------------------------------
+// Eq. 10's product with 4-bit weight codes and one scale per 128 input channels and output channel.
+// Activations as above (1 KB blocks).  Weights: the 8 packed bytes that hold 16 consecutive input
+// channels of one output channel (byte j of a 4-byte word = code(k0 + j) | code(k0 + 4 + j) << 4, as
+// in the row-major form) are the unit; a block is 16 output channels x 64 input channels = 512 bytes,
+// unit (n, q = k / 16) at ((n / 16) * (K / 64) + q / 4) * 512 + (q % 4) * 128 + (n % 16) * 8: lane order
+// again, 8 bytes per lane.  A lane widens its unit to 16 * code in registers (one shift-and-mask and
+// one mask per word), the matrix instruction is the int8 one, and after the two k-steps of a scale
+// group the int32 sums are folded into float accumulators with the group's scales; the factor 16
+// leaves with the token scale in the epilogue.
+//
+// 128 x 128 tiles, four waves as 2 x 2 (64 x 64 wave tiles: 64 + 64 accumulator registers), two
+// workgroups per compute unit, a ring of five stages of 13 KB (8 activation blocks, 8 weight blocks, the
+// group's 128 scales).  Per wave and k-step four copies: two activation blocks, 1 KB of weight blocks
+// (two of them), 256 bytes of scales (waves 2 and 3 copy them a second time into a spare area, and
+// the scales travel with both k-steps of their group, so that every wave issues the same number of
+// requests per step; past the last k-step the last one is copied again, for the same reason).
+// The fold of group g is spread over the first k-step of group g + 1: tile by tile, the eight vector
+// instructions of a tile right before the matrix instruction that starts the tile's next sum from
+// zero, so that they run under the matrix instructions of the tiles before.
+constexpr int kW4BM = 128, kW4BN = 128;
+constexpr int kW4NS = 5;
+constexpr int kW4XOff = 0, kW4WOff = 8192, kW4SOff = 12288;
+constexpr int kW4Stage = 13312;
+constexpr int kW4ParOff = kW4NS * kW4Stage;          // epilogue operands: [128 bias][128 s_x]
+constexpr int kW4Lds = kW4ParOff + 2048;             // 68608 B
+constexpr int kW4Copies = 4;
+
+__device__ __forceinline__ void copy_256_if(int on, uint32_t voff, const void *sbase, uint32_t lds_addr)
+{
+    asm volatile("s_cmp_eq_u32 %3, 0\n\ts_cbranch_scc1 .Lskip%=\n\t"
+                 "s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1\n"
+                 ".Lskip%=:"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr), "s"(__builtin_amdgcn_readfirstlane(on))
+                 : "memory", "scc");
+}
+
+template <bool DEBUG>
+__global__ __launch_bounds__(kThreads, 2) void qgemm4_tiled_kernel(GemmArgs g)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    constexpr int TM = 4, TN = 4, NS = kW4NS, P = kW4Copies;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t *)smem;
+#ifdef TRDQ_PROBE_PHASES
+    const uint64_t clk_c0 = __builtin_readcyclecounter();
+    const uint64_t clk_t0 = wall_clock64();
+#endif
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+    const int l16 = lane & 15, lg = lane >> 4;
+    int tm, tn;
+    tile_map(blockIdx.x, (int)(g.M / kW4BM), g.N / kW4BN, tm, tn);
+    const int KT = g.K >> 6;                          // k-steps: even, at least NS
+    const int64_t m0 = (int64_t)tm * kW4BM;
+    const int n0 = tn * kW4BN;
+
+    const int64_t xstride = (int64_t)KT * 1024;      // bytes from one 16-token group to the next
+    const int64_t wstride = (int64_t)KT * 512;       // ... one 16-channel group to the next
+    const int8_t *const xsrc = g.Xq + (m0 / 16 + 2 * wave) * xstride;
+    const uint8_t *const wsrc = static_cast<const uint8_t *>(g.Wc) + (int64_t)(n0 / 16 + 2 * wave) * wstride;
+    const uint32_t voff = (uint32_t)(lane * 16);
+    // the weight copy moves two blocks: lanes 0-31 the first, lanes 32-63 the one a channel group further
+    const uint32_t voffw = (uint32_t)((lane & 31) * 16) + (lane >= 32 ? (uint32_t)wstride : 0u);
+    const float *const ssrc = g.sw + n0 + (wave & 1) * 64;
+    const uint32_t voffs = (uint32_t)(lane * 4);
+    auto issue_one = [&](auto c_tag, int s, int st) {
+        constexpr int c = decltype(c_tag)::value;
+        const uint32_t sbase = lds0 + st * kW4Stage;
+        if constexpr (c < 2) dma_1k(voff, xsrc + c * xstride + (int64_t)s * 1024, sbase + kW4XOff + (2 * wave + c) * 1024);
+        else if constexpr (c == 2) dma_1k(voffw, wsrc + (int64_t)s * 512, sbase + kW4WOff + wave * 1024);
+        else copy_256_if(1, voffs, ssrc + (int64_t)(s >> 1) * g.N, sbase + kW4SOff + wave * 256);
+    };
+    auto issue = [&](int s, int st) {
+        static_for_n<P>([&](auto c) { issue_one(c, s, st); });
+    };
+
+    // epilogue operands first: wave 0 the biases, wave 1 the token scales (half a copy each)
+    {
+        const uint32_t par = lds0 + kW4ParOff;
+        const uint32_t v32 = (uint32_t)((lane & 31) * 16);
+        copy_1k_if(wave == 0 && g.bias != nullptr, v32, g.bias ? g.bias + n0 : g.sw, par);
+        if (wave == 0 && g.bias == nullptr)
+            *reinterpret_cast<uint4 *>(smem + kW4ParOff + lane * 16) = make_uint4(0u, 0u, 0u, 0u);
+        copy_1k_if(wave == 1, v32, g.sx + m0, par + 1024);
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) issue(s, s);
+    wait_vmcnt<(NS - 1) * P>();
+    __syncthreads();
+#ifdef TRDQ_PROBE_PHASES
+    const uint64_t clk_c1 = __builtin_readcyclecounter();
+    const uint64_t clk_t1 = wall_clock64();
+#endif
+
+    const int xfr = kW4XOff + (wm * TM) * 1024 + lane * 16;
+    const int wfr = kW4WOff + (wn * TN) * 512 + lane * 8;
+    const int sfr = kW4SOff + (wn * 64 + lg * 4) * 4;
+    auto widen = [](uint2 p) {
+        return v4i{(int)((p.x << 4) & 0xF0F0F0F0u), (int)(p.x & 0xF0F0F0F0u),
+                   (int)((p.y << 4) & 0xF0F0F0F0u), (int)(p.y & 0xF0F0F0F0u)};
+    };
+    v4i acc[TN][TM];
+    v4f facc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b) { acc[a][b] = v4i{0, 0, 0, 0}; facc[a][b] = v4f{0.f, 0.f, 0.f, 0.f}; }
+    v4i af[TN], bf[2][TM];
+    uint2 raw[TN];
+    float4 sc[TN];
+#pragma unroll
+    for (int a = 0; a < TN; ++a) {
+        af[a] = widen(*reinterpret_cast<const uint2 *>(smem + wfr + a * 512));
+        sc[a] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int b = 0; b < TM; ++b) bf[0][b] = *reinterpret_cast<const v4i *>(smem + xfr + b * 1024);
+
+    const int n_lane = n0 + wn * 64 + lg * 4;
+    const int64_t m_lane0 = m0 + wm * 64 + l16;
+    int st = 0;
+    // One k-step.  HALF 0 starts the sums of a scale group (folding the group before, tile by tile, with
+    // the scales read one group earlier) and ends by reading the new group's scales; HALF 1 continues the sums.
+    auto step = [&](auto half_tag, auto fold_tag, auto next_tag, int kt) {
+        constexpr int HALF = decltype(half_tag)::value;
+        constexpr bool fold_prev = decltype(fold_tag)::value;     // a group before this one exists
+        constexpr bool has_next = decltype(next_tag)::value;      // a k-step after this one exists
+        const int nst = (st + 1 == NS) ? 0 : st + 1;
+        const int8_t *const nxt = smem + nst * kW4Stage;
+        wait_vmcnt<(NS - 2) * P>();
+        __syncthreads();
+        if constexpr (has_next) {
+#pragma unroll
+            for (int b = 0; b < TM; ++b) bf[1 - HALF][b] = *reinterpret_cast<const v4i *>(nxt + xfr + b * 1024);
+#pragma unroll
+            for (int a = 0; a < TN; ++a) raw[a] = *reinterpret_cast<const uint2 *>(nxt + wfr + a * 512);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        static_for_n<TN>([&](auto a_tag) {
+            constexpr int a = decltype(a_tag)::value;
+#pragma unroll
+            for (int b = 0; b < TM; ++b) {
+                if constexpr (HALF == 0) {
+                    if constexpr (fold_prev) {
+                        if constexpr (DEBUG) {
+                            const int64_t m = m_lane0 + b * 16;
+                            *reinterpret_cast<int4 *>(g.acc_debug + ((int64_t)((kt >> 1) - 1) * g.M + m) * g.N + n_lane + a * 16) =
+                                make_int4(acc[a][b][0] >> 4, acc[a][b][1] >> 4, acc[a][b][2] >> 4, acc[a][b][3] >> 4);
+                        }
+                        facc[a][b][0] += sc[a].x * (float)acc[a][b][0];
+                        facc[a][b][1] += sc[a].y * (float)acc[a][b][1];
+                        facc[a][b][2] += sc[a].z * (float)acc[a][b][2];
+                        facc[a][b][3] += sc[a].w * (float)acc[a][b][3];
+                    }
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[a], bf[HALF][b], v4i{0, 0, 0, 0}, 0, 0, 0);
+                } else {
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[a], bf[HALF][b], acc[a][b], 0, 0, 0);
+                }
+            }
+            if constexpr (has_next) af[a] = widen(raw[a]);
+            issue_one(std::integral_constant<int, a>{}, kt + NS < KT ? kt + NS : KT - 1, st);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        // The group's scales, once the fold of the group before is done, from the NEXT step's stage (they
+        // travel with both steps of the group): that stage is not given away before the next barrier,
+        // this step's is being refilled by the other waves already.
+        if constexpr (HALF == 0) {
+#pragma unroll
+            for (int a = 0; a < TN; ++a) sc[a] = *reinterpret_cast<const float4 *>(nxt + sfr + a * 64);
+        }
+        st = nst;
+    };
+    using H0 = std::integral_constant<int, 0>;
+    using H1 = std::integral_constant<int, 1>;
+    using Yes = std::integral_constant<bool, true>;
+    using No = std::integral_constant<bool, false>;
+    step(H0{}, No{}, Yes{}, 0);                       // at least three groups (the launcher checks)
+    step(H1{}, No{}, Yes{}, 1);
+    int kt = 2;
+    for (; kt + 2 < KT; kt += 2) {
+        step(H0{}, Yes{}, Yes{}, kt);
+        step(H1{}, No{}, Yes{}, kt + 1);
+    }
+    step(H0{}, Yes{}, Yes{}, kt);
+    step(H1{}, No{}, No{}, kt + 1);
+    wait_vmcnt<0>();                                  // the repeated copies of the last steps
+#ifdef TRDQ_PROBE_PHASES
+    const uint64_t clk_c2 = __builtin_readcyclecounter();
+    const uint64_t clk_t2 = wall_clock64();
+#endif
+    // the last group's fold
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+            if constexpr (DEBUG) {
+                const int64_t m = m_lane0 + b * 16;
+                *reinterpret_cast<int4 *>(g.acc_debug + ((int64_t)((KT >> 1) - 1) * g.M + m) * g.N + n_lane + a * 16) =
+                    make_int4(acc[a][b][0] >> 4, acc[a][b][1] >> 4, acc[a][b][2] >> 4, acc[a][b][3] >> 4);
+            }
+            facc[a][b][0] += sc[a].x * (float)acc[a][b][0];
+            facc[a][b][1] += sc[a].y * (float)acc[a][b][1];
+            facc[a][b][2] += sc[a].z * (float)acc[a][b][2];
+            facc[a][b][3] += sc[a].w * (float)acc[a][b][3];
+        }
+
+    // ---- epilogue: y = (s_x / 16) * facc + bias -> bf16, one 16-token tile at a time through the idle ring
+    __syncthreads();
+    const float *const par = reinterpret_cast<const float *>(smem + kW4ParOff);
+    constexpr int ROWB = 64 * 2 + 16;                 // a wave's 64 channels of one token, padded
+    int8_t *const stg = smem + wave * (16 * ROWB);
+    float4 bi_r[TN];
+#pragma unroll
+    for (int a = 0; a < TN; ++a) bi_r[a] = *reinterpret_cast<const float4 *>(par + wn * 64 + a * 16 + lg * 4);
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+        const float sxm = par[256 + wm * 64 + b * 16 + l16] * 0.0625f;
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+            uint2 o;
+            o.x = pack_bf16x2(sxm * facc[a][b][0] + bi_r[a].x, sxm * facc[a][b][1] + bi_r[a].y);
+            o.y = pack_bf16x2(sxm * facc[a][b][2] + bi_r[a].z, sxm * facc[a][b][3] + bi_r[a].w);
+            *reinterpret_cast<uint2 *>(stg + l16 * ROWB + (a * 16 + lg * 4) * 2) = o;
+        }
+        __builtin_amdgcn_wave_barrier();
+        // 16 rows x 128 bytes = 128 pieces of 16 bytes: two per lane
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int id = i * 64 + lane;
+            const int row = id >> 3, c = id & 7;
+            const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * ROWB + c * 16);
+            store_out16(g.Y + (m0 + wm * 64 + b * 16 + row) * g.ldy + n0 + wn * 64 + c * 8, v);
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+#ifdef TRDQ_PROBE_PHASES
+    if (tid == 0 && g.acc_debug) {
+        const uint64_t clk_c3 = __builtin_readcyclecounter();
+        uint32_t hw, xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        uint64_t *o = reinterpret_cast<uint64_t *>(g.acc_debug) + (int64_t)blockIdx.x * 16;
+        o[0] = clk_t0; o[1] = clk_t1; o[2] = clk_t2; o[3] = wall_clock64();
+        o[4] = clk_c0; o[5] = clk_c1; o[6] = clk_c2; o[7] = clk_c3;
+        o[8] = hw; o[9] = xcc; o[10] = 128; o[11] = 1;
+    }
+#endif
+}
+
+// 8-byte units between the row-major packed form [N, K / 2] and the block form above
+__global__ void retile_w4_kernel(const uint2 *__restrict__ src, uint2 *__restrict__ dst, int64_t N, int K)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int upr = K >> 4;                           // units per channel
+    if (idx >= N * upr) return;
+    const int64_t n = idx / upr;
+    const int q = (int)(idx - n * upr);
+    const int64_t t = ((n >> 4) * (K >> 6) + (q >> 2)) * 64 + (q & 3) * 16 + (n & 15);
+    dst[t] = src[idx];
+}
+
 // 16 bytes per thread between the row-major form [R, K] and the block form
 template <bool TO_TILED>
 __global__ void retile_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst, int64_t R, int K)
@@ -593,6 +856,36 @@ hipError_t launch_qgemm8_tiled(const GemmArgs &a, bool debug, hipStream_t st)
     debug = false;                                    // the debug pointer receives time stamps instead
 #endif
     return debug ? go(qgemm8_tiled_kernel<true>) : go(qgemm8_tiled_kernel<false>);
+}
+
+bool tiled4_supports(const GemmArgs &a)
+{
+    return a.M > 0 && a.M % kW4BM == 0 && a.N % kW4BN == 0 && a.K % 128 == 0 && a.K >= 64 * kW4NS + 64 && a.ldy % 8 == 0 &&
+           reinterpret_cast<uintptr_t>(a.Y) % 16 == 0 && !a.zc;
+}
+
+hipError_t launch_qgemm4_tiled(const GemmArgs &a, bool debug, hipStream_t st)
+{
+    if (!tiled4_supports(a)) return hipErrorInvalidValue;
+    GemmArgs g = a;
+    auto go = [&](auto kern) -> hipError_t {
+        if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), kW4Lds); e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, dim3((unsigned)((a.M / kW4BM) * (a.N / kW4BN))), dim3(kThreads), kW4Lds, st, g);
+        return hipGetLastError();
+    };
+#ifdef TRDQ_PROBE_PHASES
+    debug = false;                                    // the debug pointer receives time stamps instead
+#endif
+    return debug ? go(qgemm4_tiled_kernel<true>) : go(qgemm4_tiled_kernel<false>);
+}
+
+hipError_t launch_retile_w4(const void *src, void *dst, int64_t N, int K, hipStream_t st)
+{
+    const int64_t n = N * (K / 16);
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(retile_w4_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const uint2 *>(src), static_cast<uint2 *>(dst), N, K);
+    return hipGetLastError();
 }
 
 hipError_t launch_retile(const int8_t *src, int8_t *dst, int64_t R, int K, bool to_tiled, hipStream_t st)

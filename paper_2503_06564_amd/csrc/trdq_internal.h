@@ -66,6 +66,7 @@ hipError_t launch_qgemm_tiled(const Weights &w, const int8_t *Xt, const float *s
 // measured choice between the two products for a layer object (true: the tiled pair is the faster one)
 bool qgemm_tiled_pays(int64_t M, int K, int N);
 hipError_t launch_retile_rows(const int8_t *src, int8_t *dst, int64_t R, int K, bool to_tiled, hipStream_t st);
+hipError_t launch_retile_w4_codes(const void *src, void *dst, int64_t N, int K, hipStream_t st);
 hipError_t launch_rotate_quant_wide(const uint16_t *X, int64_t M, int K, int64_t ldx, const float *diag,
                                     int8_t *Xq, float *sx, hipStream_t st);
 

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2503_06564_amd import trdq, workloads as wl
-from gpu_util import (assert_codes_close, assert_scales_close, assert_y_close, assert_y_same_codes, bf16_to_dev,
+from gpu_util import (narrow_code_masks, assert_codes_close, assert_scales_close, assert_y_close, assert_y_same_codes, bf16_to_dev,
                       bf16_to_host, dev, f32_to_dev)
 
 pytestmark = pytest.mark.gpu
@@ -93,6 +93,65 @@ def test_qgemm_tiled_matches_oracle(oracle, M, K, N, with_bias):
     torch.cuda.synchronize()
     assert torch.equal(Y2, Y)
     assert torch.equal(Y3, Y), "tiled and row-major products differ"
+    w.close()
+
+
+# int4 weights: 128 x 128 tiles, three scale groups (the least the kernel takes), ragged counts of tiles per
+# compute unit, the real layer widths
+TILED4_SHAPES = [(128, 384, 128), (256, 512, 256), (384, 1152, 1152), (1024, 4608, 1152), (4096, 1152, 3456),
+                 (2048, 640, 4608)]
+
+
+@pytest.mark.parametrize("M,K,N", TILED4_SHAPES)
+@pytest.mark.parametrize("with_bias", [True, False])
+def test_qgemm_tiled_int4_matches_oracle(oracle, M, K, N, with_bias):
+    say(f"qgemm_tiled int4 M={M} K={K} N={N} bias={with_bias}")
+    Xb, W, d, bias = wl.small_case(75, M, K, N, n_outliers=max(1, K // 144))
+    bias = bias if with_bias else None
+    w = trdq.prepare_weights(f32_to_dev(W), f32_to_dev(d), wbits=4)
+    assert trdq.qgemm_tiled_supported(w, M)
+    X, dd = bf16_to_dev(Xb), f32_to_dev(d)
+    Xt = torch.empty((trdq.xq_tiled_nbytes(M, K),), dtype=torch.int8, device=dev())
+    sx = torch.empty((M,), dtype=torch.float32, device=dev())
+    trdq.rotate_quant_tiled(X, dd, Xt, sx, warm=w)
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device=dev())
+    acc = torch.full((K // 128, M, N), -7, dtype=torch.int32, device=dev())
+    trdq.qgemm_tiled(w, Xt, sx, Y, bias=f32_to_dev(bias), acc_debug=acc)
+    Xq = torch.empty((M, K), dtype=torch.int8, device=dev())
+    trdq.xq_untile(Xt, M, K, Xq)
+    torch.cuda.synchronize()
+    Xq_h, (Wq_h, sw_h) = Xq.cpu().numpy(), w.export()
+    # the per-group integer sums, bit-exact on the GPU's own codes
+    want_acc = oracle.acc_exact_blas(Xq_h, Wq_h, 128)
+    assert np.array_equal(acc.cpu().numpy(), want_acc), "int32 group sums differ"
+    y_same = oracle.dequant(want_acc, sx.cpu().numpy(), sw_h, bias)
+    assert_y_same_codes(bf16_to_host(Y), y_same, "Y (int4, same codes)")
+    ref = oracle.linear(Xb, W, d, bias, wbits=4, exact_blas=True)
+    assert_codes_close(Xq_h, ref["Xq"], "Xq")
+    assert_codes_close(Wq_h, ref["Wq"], "Wq (int4)")
+    assert_y_close(bf16_to_host(Y), ref["Y"], "Y (int4, oracle end to end)",
+                   *narrow_code_masks(8, 4, None, None, Wq_h, ref["Wq"]))
+    # without the debug output, and against the row-major pair: the same bits (same order of the float folds)
+    Y2 = torch.zeros_like(Y)
+    trdq.qgemm_tiled(w, Xt, sx, Y2, bias=f32_to_dev(bias))
+    Y3 = torch.zeros_like(Y)
+    trdq.qgemm(w, Xq, sx, Y3, bias=f32_to_dev(bias))
+    torch.cuda.synchronize()
+    assert torch.equal(Y2, Y)
+    assert torch.equal(Y3, Y), "tiled and row-major int4 products differ"
+    w.close()
+
+
+def test_qgemm_tiled_int4_refuses_what_it_does_not_take():
+    _, W, d, _ = wl.small_case(76, 4, 256, 128)
+    w = trdq.prepare_weights(f32_to_dev(W), f32_to_dev(d), wbits=4)              # two scale groups: too short
+    assert not trdq.qgemm_tiled_supported(w, 128)
+    Xt = torch.zeros((128 * 256,), dtype=torch.int8, device=dev())
+    sx = torch.ones((128,), dtype=torch.float32, device=dev())
+    Y = torch.zeros((128, 128), dtype=torch.bfloat16, device=dev())
+    with pytest.raises(trdq.TrdqError) as e:
+        trdq.qgemm_tiled(w, Xt, sx, Y)
+    assert e.value.status == trdq.ERR_UNSUPPORTED
     w.close()
 
 
