@@ -326,6 +326,10 @@ __global__ __launch_bounds__(128 * kKsPairs) void qgemm8_tiled_ksplit_kernel(Gem
     constexpr int PAROFF = ks_par_off<NS>();
     static_assert((NS - 1) * P < 64, "vmcnt is a 6-bit counter");
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t *)smem;
+#ifdef TRDQ_PROBE_PHASES
+    const uint64_t clk_c0 = __builtin_readcyclecounter();
+    const uint64_t clk_t0 = wall_clock64();
+#endif
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -384,6 +388,10 @@ __global__ __launch_bounds__(128 * kKsPairs) void qgemm8_tiled_ksplit_kernel(Gem
     for (int s = 0; s < NS; ++s) issue(s, s);
     wait_vmcnt<(NS - 1) * P>();                       // step 0 and the operands above
     __syncthreads();
+#ifdef TRDQ_PROBE_PHASES
+    const uint64_t clk_c1 = __builtin_readcyclecounter();
+    const uint64_t clk_t1 = wall_clock64();
+#endif
 
     const int fro = blk_off(l16, lg);
     v4i acc[kTN][TM];
@@ -446,6 +454,10 @@ __global__ __launch_bounds__(128 * kKsPairs) void qgemm8_tiled_ksplit_kernel(Gem
         else step(Par{}, No{}, No{}, I0{}, kt + j);
     });
 
+#ifdef TRDQ_PROBE_PHASES
+    const uint64_t clk_c2 = __builtin_readcyclecounter();
+    const uint64_t clk_t2 = wall_clock64();
+#endif
     // ---- the partial sums of every token sub-tile meet in LDS ------------------------------------
     __syncthreads();                                  // every wave has read its last fragments
     v4i *const xch = reinterpret_cast<v4i *>(smem);
@@ -515,6 +527,18 @@ __global__ __launch_bounds__(128 * kKsPairs) void qgemm8_tiled_ksplit_kernel(Gem
             __builtin_amdgcn_wave_barrier();
         }
     });
+#ifdef TRDQ_PROBE_PHASES
+    if (tid == 0 && g.acc_debug) {
+        const uint64_t clk_c3 = __builtin_readcyclecounter();
+        uint32_t hw, xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        uint64_t *o = reinterpret_cast<uint64_t *>(g.acc_debug) + (int64_t)blockIdx.x * 16;
+        o[0] = clk_t0; o[1] = clk_t1; o[2] = clk_t2; o[3] = wall_clock64();
+        o[4] = clk_c0; o[5] = clk_c1; o[6] = clk_c2; o[7] = clk_c3;
+        o[8] = hw; o[9] = xcc; o[10] = 128; o[11] = 2;                 // 2: the K-split kernel
+    }
+#endif
 }
 
 // ---- int4 weights on block-tiled operands ---------------------------------------------------------
@@ -763,7 +787,7 @@ __global__ __launch_bounds__(kThreads, 2) void qgemm4_tiled_kernel(GemmArgs g)
         uint64_t *o = reinterpret_cast<uint64_t *>(g.acc_debug) + (int64_t)blockIdx.x * 16;
         o[0] = clk_t0; o[1] = clk_t1; o[2] = clk_t2; o[3] = wall_clock64();
         o[4] = clk_c0; o[5] = clk_c1; o[6] = clk_c2; o[7] = clk_c3;
-        o[8] = hw; o[9] = xcc; o[10] = 128; o[11] = 1;
+        o[8] = hw; o[9] = xcc; o[10] = 128; o[11] = 4;                 // 4: the int4 kernel
     }
 #endif
 }
@@ -836,6 +860,9 @@ hipError_t launch_ksplit(const GemmArgs &a, bool debug, hipStream_t st)
         hipLaunchKernelGGL(kern, dim3((unsigned)((a.M / 128) * (a.N / kBN))), dim3(256), lds, st, g);
         return hipGetLastError();
     };
+#ifdef TRDQ_PROBE_PHASES
+    debug = false;                                    // the debug pointer receives time stamps instead
+#endif
     return debug ? go(qgemm8_tiled_ksplit_kernel<NS, true>) : go(qgemm8_tiled_ksplit_kernel<NS, false>);
 }
 
