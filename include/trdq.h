@@ -292,13 +292,25 @@ trdq_status trdq_rotate_quant_dense(const void *X_dev, int64_t M, int64_t ldx, c
  * (else ERR_MISMATCH); perm_dev: int32 [K] on the device, (U P)[k'] = U[perm[k']] as for
  * trdq_rotate_quant_rpr.  Other arguments, layouts and errors as the one-rotation calls above;
  * the activation side takes K <= 4608 (ERR_UNSUPPORTED beyond): 16-token workgroups up to K = 1536,
- * 8-token workgroups that run the second rotation twice (maxima, then codes) for wider rows. */
+ * 8-token workgroups that run the second rotation twice (maxima, then codes) for wider rows.
+ * trdq_rotate_quant_dense_rpr_ws is the same operation with a device workspace, which rows wider than
+ * K = 1536 use for a faster form (a workgroup per block with the rotation resident in LDS; the once-rotated
+ * values cross the permutation through the workspace as float32): ws_dev holds at least
+ * trdq_rotate_quant_dense_rpr_ws_nbytes(M, K) bytes (4 (K + 1) roundup(M, 32); 0 for K <= 1536 or M <= 0, and
+ * then ws_dev may be NULL), 16-byte aligned, and belongs to the call until it has finished on its stream;
+ * nothing in it needs to be kept or cleared between calls.  ERR_NULL without it, ERR_SHAPE if it is too
+ * small or misaligned, ERR_UNSUPPORTED from 2^32 workspace elements (16 GiB) on; otherwise arguments, results and errors as trdq_rotate_quant_dense_rpr (the two
+ * forms round differently in the last float32 bits, so single codes may differ by one step). */
 trdq_status trdq_prepare_weights_dense_rpr(const float *W_dev, int K, int N, const trdq_rotation *rot1,
                                            const int32_t *perm_dev, const trdq_rotation *rot2, int wbits,
                                            void *stream, trdq_weights **out);
 trdq_status trdq_rotate_quant_dense_rpr(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot1,
                                         const int32_t *perm_dev, const trdq_rotation *rot2,
                                         int8_t *Xq_dev, float *sx_dev, void *stream);
+size_t trdq_rotate_quant_dense_rpr_ws_nbytes(int64_t M, int K);
+trdq_status trdq_rotate_quant_dense_rpr_ws(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot1,
+                                           const int32_t *perm_dev, const trdq_rotation *rot2,
+                                           int8_t *Xq_dev, float *sx_dev, void *ws_dev, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------- attention sharing (Sec. 3.3)
  * Eq. 11 between the attention outputs of the conditional and the unconditional pass:

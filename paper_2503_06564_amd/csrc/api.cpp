@@ -471,9 +471,11 @@ trdq_status trdq_prepare_weights_dense_rpr(const float *W_dev, int K, int N, con
     return prepare_weights_impl(W_dev, K, N, nullptr, perm_dev, trdq::kBlock, wbits, stream, out, rot1, rot2);
 }
 
-trdq_status trdq_rotate_quant_dense_rpr(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot1,
-                                        const int32_t *perm_dev, const trdq_rotation *rot2,
-                                        int8_t *Xq_dev, float *sx_dev, void *stream)
+namespace {
+
+trdq_status rotate_quant_dense_rpr_impl(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot1,
+                                        const int32_t *perm_dev, const trdq_rotation *rot2, int8_t *Xq_dev,
+                                        float *sx_dev, bool with_ws, void *ws_dev, size_t ws_bytes, void *stream)
 {
     if (!rot1 || !rot2 || !perm_dev) return TRDQ_ERR_NULL;
     if (rot1->K != rot2->K || rot2->diag) return TRDQ_ERR_MISMATCH;
@@ -482,12 +484,45 @@ trdq_status trdq_rotate_quant_dense_rpr(const void *X_dev, int64_t M, int64_t ld
     if (M > 0 && (!Xq_dev || !sx_dev)) return TRDQ_ERR_NULL;
     if (!aligned(Xq_dev, 16) || !aligned(sx_dev, 4) || !aligned(perm_dev, 4)) return TRDQ_ERR_SHAPE;
     if (!trdq::rotate_quant_dense_rpr_supports(rot1->K)) return TRDQ_ERR_UNSUPPORTED;
+    const size_t need = with_ws ? trdq::rotate_quant_dense_rpr_workspace_bytes(M, rot1->K) : 0;
+    if (need >= ((size_t)4 << 32)) return TRDQ_ERR_UNSUPPORTED;      // the kernels index the workspace with 32 bits
+    if (need > 0) {
+        if (!ws_dev) return TRDQ_ERR_NULL;
+        if (!aligned(ws_dev, 16) || ws_bytes < need) return TRDQ_ERR_SHAPE;
+    }
     if (M == 0) return TRDQ_OK;
     if (trdq_status rd = check_device(rot1->device); rd != TRDQ_OK) return rd;
     if (trdq_status rd = check_device(rot2->device); rd != TRDQ_OK) return rd;
+    if (need > 0)
+        return hip_status(trdq::launch_rotate_quant_dense_rpr_ws(static_cast<const uint16_t *>(X_dev), M, rot1->K, ldx,
+                                                                 rot1->pieces, perm_dev, rot2->pieces, Xq_dev, sx_dev,
+                                                                 static_cast<float *>(ws_dev),
+                                                                 static_cast<hipStream_t>(stream)));
     return hip_status(trdq::launch_rotate_quant_dense_rpr(static_cast<const uint16_t *>(X_dev), M, rot1->K, ldx,
                                                           rot1->pieces, perm_dev, rot2->frags32, Xq_dev, sx_dev,
                                                           static_cast<hipStream_t>(stream)));
+}
+
+}  // namespace
+
+trdq_status trdq_rotate_quant_dense_rpr(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot1,
+                                        const int32_t *perm_dev, const trdq_rotation *rot2,
+                                        int8_t *Xq_dev, float *sx_dev, void *stream)
+{
+    return rotate_quant_dense_rpr_impl(X_dev, M, ldx, rot1, perm_dev, rot2, Xq_dev, sx_dev, false, nullptr, 0, stream);
+}
+
+size_t trdq_rotate_quant_dense_rpr_ws_nbytes(int64_t M, int K)
+{
+    if (M <= 0 || K <= 0 || K % trdq::kBlock != 0) return 0;
+    return trdq::rotate_quant_dense_rpr_workspace_bytes(M, K);
+}
+
+trdq_status trdq_rotate_quant_dense_rpr_ws(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot1,
+                                           const int32_t *perm_dev, const trdq_rotation *rot2,
+                                           int8_t *Xq_dev, float *sx_dev, void *ws_dev, size_t ws_bytes, void *stream)
+{
+    return rotate_quant_dense_rpr_impl(X_dev, M, ldx, rot1, perm_dev, rot2, Xq_dev, sx_dev, true, ws_dev, ws_bytes, stream);
 }
 
 trdq_status trdq_rotate_quant_dense(const void *X_dev, int64_t M, int64_t ldx, const trdq_rotation *rot,

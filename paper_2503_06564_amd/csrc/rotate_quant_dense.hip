@@ -194,26 +194,90 @@ __global__ __launch_bounds__(768) void rotate_quant_dense_kernel(
 // walks its share of the token tiles, TT at a time per wave (every LDS fragment read feeds TT
 // matrix instructions); the activation fragments come straight from global memory, each wave its
 // own tokens, one group of tiles ahead.  The token maximum spans blocks, i.e. workgroups, so there
-// are two passes: QUANT = false merges |out| maxima into sx with atomic maxima on the bit patterns
-// (non-negative floats order like integers; sx cleared before), QUANT = true repeats the products,
+// are two passes: kSinkMaxima merges |out| maxima into sx with atomic maxima on the bit patterns
+// (non-negative floats order like integers; sx cleared before), kSinkCodes repeats the products,
 // quantises and stores; a last kernel turns the maxima in sx into scales.
-template <bool QUANT, int TT>
+//
+// The same kernel carries Eq. 10 with both rotations dense for wide rows, in three launches around a
+// workspace T of once-rotated values, float32, CHANNEL-major ([K][ldt], ldt = tokens rounded up to 32):
+//   kSinkRows          first rotation; the operands of the matrix instruction trade places, so that a lane
+//                      ends up with four consecutive tokens of one channel and stores them as 16 bytes of T;
+//   GATHER + kSinkMaxima / kSinkCodes
+//                      second rotation; a lane's operand element k of a k-step is T[perm[b*128 + k]][token]
+//                      (a 4-byte load; the 16 tokens of a lane row are 64 consecutive bytes; the 128 row
+//                      numbers wait in LDS), float32, so it is split exactly into three bf16 pieces like the
+//                      rotation itself, and the product takes the six piece pairs down to 2^-24 of |r||t|
+//                      (hi.hi, hi.mid, mid.hi, mid.mid, hi.lo, lo.hi), each rotation fragment read from LDS
+//                      once for all its pairs.
+// (Tried and no faster, same box, 4096 and 32768 tokens of 4608 channels: rows of T written in permuted order
+// so that the second rotation reads consecutive rows; 16-byte loads of T with a change of layout through
+// LDS instead of the 4-byte ones; two accumulator chains instead of four.)
+enum DenseSink { kSinkMaxima = 0, kSinkCodes = 1, kSinkRows = 2 };
+
+// eight float32 -> their exact three-way split by truncation, each piece eight bf16 in operand order
+// (a byte permute takes the upper halves of two words: no masks for the packing)
+__device__ __forceinline__ void split3_bf16(const float (&v)[8], v8bf &hi, v8bf &mid, v8bf &lo)
+{
+    union { uint32_t u[4]; v8bf v; } h, m, l;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float v0 = v[2 * i], v1 = v[2 * i + 1];
+        const uint32_t b0 = __float_as_uint(v0), b1 = __float_as_uint(v1);
+        const float r0 = v0 - __uint_as_float(b0 & 0xFFFF0000u), r1 = v1 - __uint_as_float(b1 & 0xFFFF0000u);
+        const uint32_t c0 = __float_as_uint(r0), c1 = __float_as_uint(r1);
+        const float s0 = r0 - __uint_as_float(c0 & 0xFFFF0000u), s1 = r1 - __uint_as_float(c1 & 0xFFFF0000u);
+        h.u[i] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);
+        m.u[i] = __builtin_amdgcn_perm(c1, c0, 0x07060302u);
+        l.u[i] = __builtin_amdgcn_perm(__float_as_uint(s1), __float_as_uint(s0), 0x07060302u);
+    }
+    hi = h.v;
+    mid = m.v;
+    lo = l.v;
+}
+
+template <int SINK, int TT, bool GATHER>
 __global__ __launch_bounds__(512) void rotate_dense_block_kernel(
     const uint16_t *__restrict__ X, int64_t M, int nb, int64_t ldx, const uint4 *__restrict__ pieces,
-    float *__restrict__ sx, int8_t *__restrict__ Xq)
+    float *__restrict__ amax_tok, float *__restrict__ scale_out, int8_t *__restrict__ Xq,
+    const float *__restrict__ Tin, const int32_t *__restrict__ perm, float *__restrict__ Tout, int64_t ldt)
 {
+    // one token tile of the float32 operand is requested a group ahead (like the bf16 one); two tiles are
+    // requested at the top of their own group (no registers to hold both across the products), and the
+    // wave that shares the SIMD covers the wait
+    constexpr bool AHEAD = GATHER && TT == 1;
+    static_assert(!(GATHER && SINK == kSinkRows), "the second rotation ends in maxima or codes");
+    constexpr bool QUANT = SINK == kSinkCodes;
     extern __shared__ __align__(16) uint4 lds_pieces[];           // [12][8][64] fragments of this block
     const int K = nb * kBlock;
     const int b = blockIdx.y;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, g = lane >> 4;
-    for (int i = threadIdx.x; i < kPiecesPerBlock; i += 512) lds_pieces[i] = pieces[(size_t)b * kPiecesPerBlock + i];
+    {   // the block's pieces: all twelve requests of a lane in flight, then the LDS writes
+        static_assert(kPiecesPerBlock % 512 == 0, "whole rounds of the workgroup");
+        constexpr int ROUNDS = kPiecesPerBlock / 512;
+        uint4 tmp[ROUNDS];
+#pragma unroll
+        for (int i = 0; i < ROUNDS; ++i) tmp[i] = pieces[(size_t)b * kPiecesPerBlock + i * 512 + threadIdx.x];
+#pragma unroll
+        for (int i = 0; i < ROUNDS; ++i) lds_pieces[i * 512 + threadIdx.x] = tmp[i];
+    }
+    // second rotation: the rows of T that are the block's 128 input channels, and behind them eight waves' worth
+    // of rows in which finished codes wait (64 x 8 words per token tile)
+    int *const rowtab = reinterpret_cast<int *>(lds_pieces + kPiecesPerBlock);
+    uint32_t *const code_lds = reinterpret_cast<uint32_t *>(rowtab + kBlock) + wave * (TT * 8 * 64);
+    if constexpr (GATHER) {
+        if (threadIdx.x < kBlock) {
+            int p = perm[b * kBlock + threadIdx.x];
+            rowtab[threadIdx.x] = p < 0 ? 0 : (p >= K ? K - 1 : p);
+        }
+    }
     __syncthreads();
 
     constexpr int TOK = 16 * TT;
     const int64_t groups = (M + TOK - 1) / TOK;                   // groups of TT 16-token tiles
     const int64_t stride = (int64_t)gridDim.x * 8;
+    // bf16 source: the lane's operand is 16 bytes of its token's row
     auto load_x = [&](v8bf (&xf)[TT][4], int64_t gr) {
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
@@ -227,12 +291,50 @@ __global__ __launch_bounds__(512) void rotate_dense_block_kernel(
             }
         }
     };
+    // float32 source: rows of T (token-padded, so tokens past M read what the first rotation wrote for its
+    // repeated rows); element e of k-step s is row rowtab[32 s + 8 g + e], token l16 of the tile
+    auto gather_x = [&](float (&raw)[4][8], int64_t gr, int tt) {
+        const float *const tile = Tin + gr * TOK + tt * 16 + l16;
+        int g8 = 8 * g;
+        asm volatile("" : "+v"(g8));                              // keeps the row-number reads inside the group loop
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int4 r0 = *reinterpret_cast<const int4 *>(rowtab + 32 * s + g8);
+            const int4 r1 = *reinterpret_cast<const int4 *>(rowtab + 32 * s + g8 + 4);
+            raw[s][0] = tile[(int64_t)r0.x * ldt]; raw[s][1] = tile[(int64_t)r0.y * ldt];
+            raw[s][2] = tile[(int64_t)r0.z * ldt]; raw[s][3] = tile[(int64_t)r0.w * ldt];
+            raw[s][4] = tile[(int64_t)r1.x * ldt]; raw[s][5] = tile[(int64_t)r1.y * ldt];
+            raw[s][6] = tile[(int64_t)r1.z * ldt]; raw[s][7] = tile[(int64_t)r1.w * ldt];
+        }
+    };
+    auto to_operands = [&](const float (&raw)[4][8], v8bf (&hi)[4], v8bf (&mid)[4], v8bf (&lo)[4]) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) split3_bf16(raw[s], hi[s], mid[s], lo[s]);
+    };
     int64_t gr = (int64_t)blockIdx.x * 8 + wave;
-    v8bf xcur[TT][4], xnext[TT][4];
-    if (gr < groups) load_x(xcur, gr);
+    v8bf xcur[TT][4], xnext[GATHER ? 1 : TT][4];
+    v8bf xmid[GATHER ? TT : 1][4], xlo[GATHER ? TT : 1][4];
+    float raw[GATHER ? TT : 1][4][8];
+    if (gr < groups) {
+        if constexpr (AHEAD) {
+            gather_x(raw[0], gr, 0);
+            to_operands(raw[0], xcur[0], xmid[0], xlo[0]);
+        } else if constexpr (!GATHER) {
+            load_x(xcur, gr);
+        }
+    }
     for (; gr < groups; gr += stride) {
         const int64_t nxt = gr + stride < groups ? gr + stride : gr;  // the last iteration re-reads its own tiles
-        load_x(xnext, nxt);
+        if constexpr (AHEAD) {
+            gather_x(raw[0], nxt, 0);
+        } else if constexpr (GATHER) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) gather_x(raw[tt], gr, tt);
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) to_operands(raw[tt], xcur[tt], xmid[tt], xlo[tt]);
+        } else {
+            load_x(xnext, nxt);
+        }
         float inv[TT], amax[TT];
         int64_t token[TT];
 #pragma unroll
@@ -242,66 +344,150 @@ __global__ __launch_bounds__(512) void rotate_dense_block_kernel(
             inv[tt] = 0.0f;
             if constexpr (QUANT) {
                 if (token[tt] < M) {
-                    const float a = sx[token[tt]];
+                    const float a = amax_tok[token[tt]];
                     inv[tt] = a > 0.0f ? 127.0f / a : 0.0f;
+                    if (scale_out != nullptr && b == 0 && g == 0) scale_out[token[tt]] = a / 127.0f;
                 }
             }
         }
-        uint32_t code[QUANT ? TT : 1][8];
+        if constexpr (SINK == kSinkRows) {                        // the first block's workgroups clear the maxima
+            if (amax_tok != nullptr && b == 0 && lane < TOK) amax_tok[gr * TOK + lane] = 0.0f;
+        }
+        // the codes of a finished tile wait in registers, or (second rotation, short of registers) in LDS
+        uint32_t code[QUANT && !GATHER ? TT : 1][8];
         int lane_off = lane;                                      // keeps the fragment reads inside this loop
         asm volatile("" : "+v"(lane_off));
-        // the twelve fragments of tile t + 1 are read from LDS while tile t is multiplied (the scheduling
-        // barriers keep the reads ahead of the products; left alone, each read is placed right before its use)
-        uint4 fa[2][12];
-        auto request = [&](uint4 (&f)[12], int t) {
-#pragma unroll
-            for (int q = 0; q < 12; ++q) f[q] = lds_pieces[(q * 8 + t) * 64 + lane_off];
-        };
-        request(fa[0], 0);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            if (t + 1 < 8) request(fa[(t + 1) & 1], t + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            v4f acc[TT];
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt) acc[tt] = v4f{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int q = 11; q >= 0; --q) {                       // smallest piece first
-                union { uint4 u; v8bf v; } a;
-                a.u = fa[t & 1][q];
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-                    acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, xcur[tt][q & 3], acc[tt], 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
+        // what becomes of a finished tile t (acc[tt][j]: see the sinks above)
+        auto finish_tile = [&](int t, const v4f (&acc)[TT]) {
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
-                if constexpr (QUANT)
-                    code[tt][t] = pack4_low_bytes(quant_bits(acc[tt][0], inv[tt]), quant_bits(acc[tt][1], inv[tt]),
-                                                  quant_bits(acc[tt][2], inv[tt]), quant_bits(acc[tt][3], inv[tt]));
-                else
+                if constexpr (SINK == kSinkCodes) {
+                    const uint32_t c = pack4_low_bytes(quant_bits(acc[tt][0], inv[tt]), quant_bits(acc[tt][1], inv[tt]),
+                                                       quant_bits(acc[tt][2], inv[tt]), quant_bits(acc[tt][3], inv[tt]));
+                    if constexpr (GATHER) code_lds[(tt * 8 + t) * 64 + lane] = c;
+                    else code[tt][t] = c;
+                } else if constexpr (SINK == kSinkMaxima)
                     amax[tt] = fmaxf(amax[tt], fmaxf(fmaxf(fabsf(acc[tt][0]), fabsf(acc[tt][1])),
                                                      fmaxf(fabsf(acc[tt][2]), fabsf(acc[tt][3]))));
+                else                                              // tokens 4 g .. 4 g + 3 of channel c(t, l16)
+                    *reinterpret_cast<float4 *>(Tout + (int64_t)(b * kBlock + 32 * (l16 >> 2) + 4 * t + (l16 & 3)) * ldt +
+                                                gr * TOK + tt * 16 + 4 * g) =
+                        make_float4(acc[tt][0], acc[tt][1], acc[tt][2], acc[tt][3]);
+            }
+        };
+        if constexpr (GATHER) {
+            // Fragments in chunks of four (one piece's k-steps of one tile, smallest piece first) through a ring
+            // of three: chunk i + 2 is read from LDS while chunk i is multiplied, 4, 8 or 12 instructions
+            // (the low piece meets the operand's high piece, the middle one its high and middle, the high one all three).
+            uint4 fr[3][4];
+            auto request4 = [&](uint4 (&f)[4], int i) {
+                const int t = i / 3, p = 2 - i % 3;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) f[s] = lds_pieces[((p * 4 + s) * 8 + t) * 64 + lane_off];
+            };
+            request4(fr[0], 0);
+            request4(fr[1], 1);
+            // Four accumulator chains taken in turn (k-step by k-step, token tile by token tile), so that an
+            // instruction never waits for the one before it in its own chain; they are summed when the tile is done.
+            constexpr int NCH = 4 / TT;
+            v4f ch[TT][NCH];
+#pragma unroll
+            for (int i = 0; i < 24; ++i) {
+                if (i + 2 < 24) request4(fr[(i + 2) % 3], i + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                const int p = 2 - i % 3;
+                if (i % 3 == 0) {
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                        for (int c = 0; c < NCH; ++c) ch[tt][c] = v4f{0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+                for (int bp = 2; bp >= 0; --bp) {                 // the operand's piece: low, middle, high
+                    if (bp + p > 2) continue;                     // pairs below 2^-24 are left out
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        union { uint4 u; v8bf v; } a;
+                        a.u = fr[i % 3][s];
+#pragma unroll
+                        for (int tt = 0; tt < TT; ++tt) {
+                            const v8bf x = bp == 2 ? xlo[tt][s] : (bp == 1 ? xmid[tt][s] : xcur[tt][s]);
+                            ch[tt][s % NCH] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, x, ch[tt][s % NCH], 0, 0, 0);
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (i % 3 == 2) {
+                    v4f acc[TT];
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) {
+                        if constexpr (NCH == 4) acc[tt] = (ch[tt][0] + ch[tt][1]) + (ch[tt][2] + ch[tt][3]);
+                        else acc[tt] = ch[tt][0] + ch[tt][1];
+                    }
+                    finish_tile(i / 3, acc);
+                }
+            }
+        } else {
+            // the twelve fragments of tile t + 1 are read from LDS while tile t is multiplied (the scheduling
+            // barriers keep the reads ahead of the products; left alone, each read is placed right before its use)
+            uint4 fa[2][12];
+            auto request = [&](uint4 (&f)[12], int t) {
+#pragma unroll
+                for (int q = 0; q < 12; ++q) f[q] = lds_pieces[(q * 8 + t) * 64 + lane_off];
+            };
+            request(fa[0], 0);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                if (t + 1 < 8) request(fa[(t + 1) & 1], t + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                v4f acc[TT];
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) acc[tt] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int q = 11; q >= 0; --q) {                   // smallest piece first
+                    union { uint4 u; v8bf v; } a;
+                    a.u = fa[t & 1][q];
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) {
+                        if constexpr (SINK == kSinkRows)          // rows = tokens, columns = the tile's channels
+                            acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xcur[tt][q & 3], a.v, acc[tt], 0, 0, 0);
+                        else
+                            acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, xcur[tt][q & 3], acc[tt], 0, 0, 0);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                finish_tile(t, acc);
             }
         }
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
-            if constexpr (QUANT) {
+            if constexpr (SINK == kSinkCodes) {
+                uint32_t c[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    if constexpr (GATHER) c[t] = code_lds[(tt * 8 + t) * 64 + lane];
+                    else c[t] = code[tt][t];
+                }
                 if (token[tt] < M) {
                     uint4 *dst = reinterpret_cast<uint4 *>(Xq + token[tt] * K + b * kBlock + 32 * g);
-                    dst[0] = make_uint4(code[tt][0], code[tt][1], code[tt][2], code[tt][3]);
-                    dst[1] = make_uint4(code[tt][4], code[tt][5], code[tt][6], code[tt][7]);
+                    dst[0] = make_uint4(c[0], c[1], c[2], c[3]);
+                    dst[1] = make_uint4(c[4], c[5], c[6], c[7]);
                 }
-            } else {
+            } else if constexpr (SINK == kSinkMaxima) {
                 float m = fmaxf(amax[tt], __shfl_xor(amax[tt], 16));
                 m = fmaxf(m, __shfl_xor(m, 32));
-                if (g == 0 && token[tt] < M) atomicMax(reinterpret_cast<unsigned int *>(sx + token[tt]), __float_as_uint(m));
+                if (g == 0 && token[tt] < M)
+                    atomicMax(reinterpret_cast<unsigned int *>(amax_tok + token[tt]), __float_as_uint(m));
             }
         }
+        if constexpr (AHEAD) {
+            to_operands(raw[0], xcur[0], xmid[0], xlo[0]);
+        } else if constexpr (!GATHER) {
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt)
+            for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-            for (int s = 0; s < 4; ++s) xcur[tt][s] = xnext[tt][s];
+                for (int s = 0; s < 4; ++s) xcur[tt][s] = xnext[tt][s];
+        }
     }
 }
 
@@ -317,28 +503,45 @@ __global__ void dense_scale_kernel(float *sx, int64_t M)
     if (i < M) sx[i] = sx[i] / 127.0f;
 }
 
+// workgroups along the token axis for the block-resident kernels: as many as fit one round of compute units
+int dense_block_chunks(int64_t groups, int nb)
+{
+    int64_t chunks = num_cus() / nb;            // rounded down: one workgroup more than compute units would wait for a second round
+    const int64_t most = (groups + 7) / 8;
+    if (chunks > most) chunks = most;
+    return chunks < 1 ? 1 : (int)chunks;
+}
+
+template <int SINK, int TT, bool GATHER>
+hipError_t launch_dense_block_pass(const uint16_t *X, int64_t M, int nb, int64_t ldx, const uint4 *pieces,
+                                   float *amax_tok, float *scale_out, int8_t *Xq, const float *Tin, const int32_t *perm, float *Tout, int64_t ldt,
+                                   hipStream_t st)
+{
+    // behind the pieces: the second rotation's 128 row numbers and eight waves' parked codes
+    const size_t smem = (size_t)kPiecesPerBlock * 16 + (GATHER ? kBlock * sizeof(int) + 8 * TT * 8 * 64 * sizeof(uint32_t) : 0);
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(rotate_dense_block_kernel<SINK, TT, GATHER>), smem);
+        e != hipSuccess)
+        return e;
+    const int64_t groups = (M + 16 * TT - 1) / (16 * TT);
+    hipLaunchKernelGGL((rotate_dense_block_kernel<SINK, TT, GATHER>), dim3((unsigned)dense_block_chunks(groups, nb), nb),
+                       dim3(512), smem, st, X, M, nb, ldx, pieces, amax_tok, scale_out, Xq, Tin, perm, Tout, ldt);
+    return hipGetLastError();
+}
+
 template <int TT>
 hipError_t launch_dense_blocks(const uint16_t *X, int64_t M, int nb, int64_t ldx, const uint4 *pieces,
                                int8_t *Xq, float *sx, hipStream_t st)
 {
-    const int64_t groups = (M + 16 * TT - 1) / (16 * TT);
-    int64_t chunks = num_cus() / nb;            // rounded down: one workgroup more than compute units would wait for a second round
-    const int64_t most = (groups + 7) / 8;
-    if (chunks > most) chunks = most;
-    if (chunks < 1) chunks = 1;
-    const size_t smem = (size_t)kPiecesPerBlock * 16;
-    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(rotate_dense_block_kernel<false, TT>), smem);
-        e != hipSuccess)
-        return e;
-    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(rotate_dense_block_kernel<true, TT>), smem);
-        e != hipSuccess)
-        return e;
     const unsigned mg = (unsigned)((M + 255) / 256);
     hipLaunchKernelGGL(dense_clear_kernel, dim3(mg), dim3(256), 0, st, sx, M);
-    hipLaunchKernelGGL((rotate_dense_block_kernel<false, TT>), dim3((unsigned)chunks, nb), dim3(512), smem, st,
-                       X, M, nb, ldx, pieces, sx, Xq);
-    hipLaunchKernelGGL((rotate_dense_block_kernel<true, TT>), dim3((unsigned)chunks, nb), dim3(512), smem, st,
-                       X, M, nb, ldx, pieces, sx, Xq);
+    if (hipError_t e = launch_dense_block_pass<kSinkMaxima, TT, false>(X, M, nb, ldx, pieces, sx, nullptr, Xq, nullptr, nullptr,
+                                                                       nullptr, 0, st);
+        e != hipSuccess)
+        return e;
+    if (hipError_t e = launch_dense_block_pass<kSinkCodes, TT, false>(X, M, nb, ldx, pieces, sx, nullptr, Xq, nullptr, nullptr,
+                                                                      nullptr, 0, st);
+        e != hipSuccess)
+        return e;
     hipLaunchKernelGGL(dense_scale_kernel, dim3(mg), dim3(256), 0, st, sx, M);
     return hipGetLastError();
 }
@@ -642,6 +845,47 @@ hipError_t launch_channel_absmax_dense(const uint16_t *X, int64_t M, int K, int6
 
 bool rotate_quant_dense_supports(int K) { return K % kBlock == 0 && K / kBlock <= 36; }
 bool rotate_quant_dense_rpr_supports(int K) { return K % kBlock == 0 && K / kBlock <= 36; }
+
+// Rows wider than 12 blocks have a second form that goes through a workspace: the once-rotated values,
+// float32, channel-major, tokens rounded up to 32 (the first rotation writes whole groups of 32 tokens),
+// and behind them one row more for the tokens' maxima.
+static int64_t dense_ws_ldt(int64_t M) { return (M + 31) / 32 * 32; }
+
+size_t rotate_quant_dense_rpr_workspace_bytes(int64_t M, int K)
+{
+    if (K / kBlock <= 12 || M <= 0) return 0;
+    return ((size_t)K + 1) * (size_t)dense_ws_ldt(M) * sizeof(float);
+}
+
+hipError_t launch_rotate_quant_dense_rpr_ws(const uint16_t *X, int64_t M, int K, int64_t ldx, const void *pieces1,
+                                            const int32_t *perm, const void *pieces2, int8_t *Xq, float *sx,
+                                            float *T, hipStream_t st)
+{
+    if (M == 0) return hipSuccess;
+    const int nb = K / kBlock;
+    const int64_t ldt = dense_ws_ldt(M);
+    float *const amax_tok = T + (size_t)K * ldt;
+    // first rotation (also clears the maxima); second rotation for the maxima; again for the codes and the scales
+    if (hipError_t e = launch_dense_block_pass<kSinkRows, 2, false>(X, M, nb, ldx, static_cast<const uint4 *>(pieces1),
+                                                                    amax_tok, nullptr, Xq, nullptr, nullptr, T, ldt, st);
+        e != hipSuccess)
+        return e;
+    const uint4 *const p2 = static_cast<const uint4 *>(pieces2);
+    // Two token tiles per fragment read halve the LDS traffic of the second rotation (4-5 % from 8192 tokens on);
+    // with fewer tokens a wave has too few groups of 32 for that to make up for the coarser split of the work.
+    if (M >= 8192) {
+        if (hipError_t e = launch_dense_block_pass<kSinkMaxima, 2, true>(X, M, nb, ldx, p2, amax_tok, nullptr, Xq, T, perm,
+                                                                         nullptr, ldt, st);
+            e != hipSuccess)
+            return e;
+        return launch_dense_block_pass<kSinkCodes, 2, true>(X, M, nb, ldx, p2, amax_tok, sx, Xq, T, perm, nullptr, ldt, st);
+    }
+    if (hipError_t e = launch_dense_block_pass<kSinkMaxima, 1, true>(X, M, nb, ldx, p2, amax_tok, nullptr, Xq, T, perm,
+                                                                     nullptr, ldt, st);
+        e != hipSuccess)
+        return e;
+    return launch_dense_block_pass<kSinkCodes, 1, true>(X, M, nb, ldx, p2, amax_tok, sx, Xq, T, perm, nullptr, ldt, st);
+}
 
 hipError_t launch_rotate_quant_dense_rpr(const uint16_t *X, int64_t M, int K, int64_t ldx, const void *pieces1,
                                          const int32_t *perm, const void *frags2, int8_t *Xq, float *sx, hipStream_t st)

@@ -139,6 +139,11 @@ hipError_t launch_rotation_frags32(const float *R, int K, void *frags, hipStream
 bool rotate_quant_dense_rpr_supports(int K);
 hipError_t launch_rotate_quant_dense_rpr(const uint16_t *X, int64_t M, int K, int64_t ldx, const void *pieces1,
                                          const int32_t *perm, const void *frags2, int8_t *Xq, float *sx, hipStream_t st);
+// wide rows (more than 12 blocks) through a workspace of once-rotated values; pieces2: the second rotation's bf16 pieces
+size_t rotate_quant_dense_rpr_workspace_bytes(int64_t M, int K);
+hipError_t launch_rotate_quant_dense_rpr_ws(const uint16_t *X, int64_t M, int K, int64_t ldx, const void *pieces1,
+                                            const int32_t *perm, const void *pieces2, int8_t *Xq, float *sx,
+                                            float *T, hipStream_t st);
 bool fused_supports(int K);
 bool fused_pays(int64_t M, int K, int N, int wbits);
 hipError_t launch_linear_fused(const Weights &w, const uint16_t *X, int64_t M, int64_t ldx,

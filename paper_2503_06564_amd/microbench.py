@@ -105,6 +105,12 @@ def dense(dev):
             rot2 = trdq.Rotation(R2)
             row["dense_rpr_us"] = round(_timeit(lambda i: trdq.rotate_quant_dense_rpr(Xs[i % R], rot1, perm, rot2, Xq, sx),
                                                 20 if M * K > (1 << 26) else 50), 1)
+            nbytes = trdq.rotate_quant_dense_rpr_ws_nbytes(M, K)
+            if nbytes:
+                ws = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
+                row["dense_rpr_ws_us"] = round(_timeit(
+                    lambda i: trdq.rotate_quant_dense_rpr_ws(Xs[i % R], rot1, perm, rot2, Xq, sx, ws)), 1)
+                row["workspace_MB"] = round(nbytes / 1e6, 1)
             _out(**row)
 
 

@@ -27,6 +27,7 @@ SYMBOLS = [
     "trdq_cosine_similarity", "trdq_cosine_similarity_static", "trdq_share_plan",
     "trdq_rotation_create", "trdq_rotation_destroy", "trdq_prepare_weights_dense", "trdq_rotate_quant_dense",
     "trdq_greedy_rotation", "trdq_prepare_weights_dense_rpr", "trdq_rotate_quant_dense_rpr",
+    "trdq_rotate_quant_dense_rpr_ws", "trdq_rotate_quant_dense_rpr_ws_nbytes",
     "trdq_channel_absmax_dense", "trdq_greedy_rotation_second",
     "trdq_peak_mfma_i8", "trdq_peak_mfma_i8_data", "trdq_peak_stream",
     "trdq_xq_tiled_nbytes", "trdq_rotate_quant_tiled", "trdq_xq_untile", "trdq_qgemm_tiled_supported", "trdq_qgemm_tiled_preferred",
@@ -108,6 +109,9 @@ def lib():
         L.trdq_greedy_rotation.argtypes = [p, i64, i32, i64, p, i32, p, i32, p, p, p]
         L.trdq_prepare_weights_dense_rpr.argtypes = [p, i32, i32, p, p, p, i32, p, C.POINTER(p)]
         L.trdq_rotate_quant_dense_rpr.argtypes = [p, i64, i64, p, p, p, p, p, p]
+        L.trdq_rotate_quant_dense_rpr_ws.argtypes = [p, i64, i64, p, p, p, p, p, p, C.c_size_t, p]
+        L.trdq_rotate_quant_dense_rpr_ws_nbytes.argtypes = [i64, i32]
+        L.trdq_rotate_quant_dense_rpr_ws_nbytes.restype = C.c_size_t
         L.trdq_channel_absmax_dense.argtypes = [p, i64, i64, p, p, p]
         L.trdq_greedy_rotation_second.argtypes = [p, i64, i64, p, p, p, i32, p, p, p]
         L.trdq_qgemm_asym.argtypes = [p, p, p, p, i64, p, p, i64, p, p]
@@ -377,6 +381,20 @@ def rotate_quant_dense_rpr(X, rot1, perm, rot2, Xq, sx, stream=None):
     ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
     _check(lib().trdq_rotate_quant_dense_rpr(_ptr(X), M, ldx, rot1.handle, _ptr(perm), rot2.handle, _ptr(Xq), _ptr(sx),
                                              _stream(stream)), "trdq_rotate_quant_dense_rpr")
+
+
+def rotate_quant_dense_rpr_ws_nbytes(M, K):
+    """bytes of device workspace rotate_quant_dense_rpr_ws needs (0 up to K = 1536)"""
+    return int(lib().trdq_rotate_quant_dense_rpr_ws_nbytes(M, K))
+
+
+def rotate_quant_dense_rpr_ws(X, rot1, perm, rot2, Xq, sx, ws, stream=None):
+    """rotate_quant_dense_rpr with a device workspace `ws` (any dtype, contiguous; None where none is needed)"""
+    M, K = X.shape
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(lib().trdq_rotate_quant_dense_rpr_ws(_ptr(X), M, ldx, rot1.handle, _ptr(perm), rot2.handle, _ptr(Xq), _ptr(sx),
+                                                _ptr(ws), ws_bytes, _stream(stream)), "trdq_rotate_quant_dense_rpr_ws")
 
 
 def bind_rotate_quant_dense(X, rot, Xq, sx, stream=None):

@@ -286,6 +286,16 @@ def test_dense_calibration_argument_errors_before_any_gpu_call():
     out = C.c_void_p()
     assert L.trdq_prepare_weights_dense_rpr(0x1000, 256, 64, None, 0x2000, None, 8, None, C.byref(out)) == trdq.ERR_NULL
     assert L.trdq_rotate_quant_dense_rpr(0x1000, 4, 256, None, 0x2000, None, 0x3000, 0x4000, None) == trdq.ERR_NULL
+    assert L.trdq_rotate_quant_dense_rpr_ws(0x1000, 4, 256, None, 0x2000, None, 0x3000, 0x4000, 0x5000, 64, None) == trdq.ERR_NULL
+
+
+def test_dense_rpr_workspace_size():
+    n = trdq.rotate_quant_dense_rpr_ws_nbytes
+    assert n(4096, 4608) == 4 * 4609 * 4096          # K rows of once-rotated values and one of maxima
+    assert n(33, 2304) == 4 * 2305 * 64              # tokens rounded up to 32
+    assert n(1, 1664) == 4 * 1665 * 32
+    assert n(100, 1536) == 0 and n(100, 128) == 0    # up to 12 blocks: no workspace
+    assert n(0, 4608) == 0 and n(-3, 4608) == 0 and n(8, 4600) == 0 and n(8, 0) == 0
 
 
 def test_asym_weight_calls_check_arguments_before_any_gpu_call():

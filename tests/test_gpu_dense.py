@@ -198,6 +198,56 @@ def test_rotate_quant_dense_rpr_matches_oracle(oracle, M, K):
     rot1.close(); rot2.close()
 
 
+# the workspace form: block-resident kernels around float32 once-rotated values (K > 1536); up to K = 1536 it is the
+# plain call.  13 blocks and 36, token counts around the 16- and 32-token groups and beyond one round of workgroups.
+# (from 8192 tokens on the second rotation takes two token tiles per fragment read)
+@pytest.mark.parametrize("M,K", [(1, 1664), (40, 1664), (9, 2304), (33, 2304), (70, 4608), (263, 4608), (1100, 2304),
+                                 (300, 1152), (0, 2304), (8230, 1664), (8192, 2304)])
+def test_rotate_quant_dense_rpr_ws_matches_oracle(oracle, M, K):
+    say(f"rotate_quant_dense_rpr_ws M={M} K={K}")
+    Xb, _, d, _ = wl.small_case(74, max(M, 1), K, 16, n_outliers=max(1, K // 144), outlier=40.0)
+    Xb = Xb[:M]
+    R1, R2 = _blocks(K + 5, K), _blocks(K + 6, K)
+    perm = np.random.default_rng(K + 1).permutation(K).astype(np.int32)
+    rot1, rot2 = _rot(R1, d), _rot(R2)
+    nbytes = trdq.rotate_quant_dense_rpr_ws_nbytes(M, K)
+    assert (nbytes > 0) == (K > 1536 and M > 0)
+    ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=dev()) if nbytes else None     # NaN patterns: nothing is read unwritten
+    Xq = torch.full((M, K), 99, dtype=torch.int8, device=dev())
+    sx = torch.full((M,), -1.0, dtype=torch.float32, device=dev())
+    perm_dev = torch.from_numpy(perm).to(dev())
+    for rep in range(2):        # the second call finds the first call's values in the workspace
+        trdq.rotate_quant_dense_rpr_ws(bf16_to_dev(Xb), rot1, perm_dev, rot2, Xq, sx, ws)
+    torch.cuda.synchronize()
+    if M:
+        Xq_o, sx_o = oracle.quant_tokens(oracle.rotate_dense_rpr(Xb, d, R1, perm, R2))
+        assert_codes_close(Xq.cpu().numpy(), Xq_o, "Xq (dense R1 P R2, workspace form)")
+        assert_scales_close(sx.cpu().numpy(), sx_o, "s_x (dense R1 P R2, workspace form)")
+    rot1.close(); rot2.close()
+
+
+def test_dense_rpr_ws_argument_errors():
+    K = 2304
+    R = torch.zeros((K // 128, 128, 128), device=dev())
+    rot1, rot2 = trdq.Rotation(R, torch.ones((K,), device=dev())), trdq.Rotation(R)
+    X = torch.zeros((40, K), dtype=torch.bfloat16, device=dev())
+    Xq = torch.zeros((40, K), dtype=torch.int8, device=dev())
+    sx = torch.zeros((40,), device=dev())
+    perm = torch.arange(K, dtype=torch.int32, device=dev())
+    need = trdq.rotate_quant_dense_rpr_ws_nbytes(40, K)
+    with pytest.raises(trdq.TrdqError) as e:
+        trdq.rotate_quant_dense_rpr_ws(X, rot1, perm, rot2, Xq, sx, None)
+    assert e.value.status == trdq.ERR_NULL
+    with pytest.raises(trdq.TrdqError) as e:
+        trdq.rotate_quant_dense_rpr_ws(X, rot1, perm, rot2, Xq, sx, torch.empty((need - 4,), dtype=torch.uint8, device=dev()))
+    assert e.value.status == trdq.ERR_SHAPE
+    ws = torch.empty((need + 16,), dtype=torch.uint8, device=dev())
+    with pytest.raises(trdq.TrdqError) as e:
+        trdq.rotate_quant_dense_rpr_ws(X, rot1, perm, rot2, Xq, sx, ws[4:])         # not 16-byte aligned
+    assert e.value.status == trdq.ERR_SHAPE
+    rot1.close(); rot2.close()
+
+
 @pytest.mark.parametrize("M,K,N,wbits", [(17, 256, 144, 8), (300, 1152, 272, 8), (64, 384, 160, 4), (50, 4608, 144, 8)])
 def test_dense_rpr_linear_end_to_end(oracle, M, K, N, wbits):
     say(f"dense R1 P R2 linear M={M} K={K} N={N} wbits={wbits}")

@@ -345,7 +345,7 @@ def test_two_million_tokens_64_bit_offsets(oracle):
 
 
 # Both rotations dense (Eq. 10 as printed) at config 1's sizes: K = 1152 takes the 16-token kernel, K = 4608 the
-# 8-token one; sampled rows against the oracle (the rotation acts on a row alone, the weights are exact).
+# 8-token one and, with a workspace, the block-resident kernels; sampled rows against the oracle (the rotation acts on a row alone, the weights are exact).
 @pytest.mark.parametrize("kind", ["proj", "fc2"])
 def test_dense_chain_full_size_sampled_rows(oracle, kind):
     cfg = wl.CONFIGS[1]
@@ -377,4 +377,19 @@ def test_dense_chain_full_size_sampled_rows(oracle, kind):
     codes, scales = w.export()
     gu.assert_codes_close(codes, ref["Wq"], f"{kind} Wq (dense R1 P R2)")
     gu.assert_y_close(gu.bf16_to_host(Y[idx]), ref["Y"], f"{kind} Y (dense R1 P R2)")
+    # the workspace form (block-resident kernels; for K = 1152 it needs none and is the call above)
+    nbytes = trdq.rotate_quant_dense_rpr_ws_nbytes(M, K)
+    assert (nbytes > 0) == (K > 1536)
+    ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda") if nbytes else None
+    Xq2 = torch.full((M, K), 99, dtype=torch.int8, device="cuda")
+    sx2 = torch.full((M,), -1.0, dtype=torch.float32, device="cuda")
+    trdq.rotate_quant_dense_rpr_ws(gu.bf16_to_dev(Xb), rot1, perm_dev, rot2, Xq2, sx2, ws)
+    torch.cuda.synchronize()
+    assert bool((Xq2.abs().amax(dim=1)[sx2 > 0] == 127).all())
+    gu.assert_codes_close(Xq2[idx].cpu().numpy(), ref["Xq"], f"{kind} Xq (dense R1 P R2, workspace)")
+    gu.assert_scales_close(sx2[idx].cpu().numpy(), ref["sx"], f"{kind} s_x (dense R1 P R2, workspace)")
+    # the two forms against each other on every token: the same maxima to rounding, codes one step apart at most
+    assert torch.allclose(sx2, sx, rtol=1e-5, atol=0)
+    dq = (Xq2.int() - Xq.int()).abs()
+    assert int(dq.max()) <= 1 and float((dq > 0).float().mean()) <= 1e-4
     w.close(); rot1.close(); rot2.close()
