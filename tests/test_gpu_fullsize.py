@@ -167,6 +167,15 @@ def test_config4_denoiser_sweep_layers(oracle, block, step, kind):
     check_layer(oracle, wl.CONFIGS[4], kind, step, 8, block=block, fused_too=(block == 13 and kind == "proj"))
 
 
+# every time-step group of the sweep (50 steps -> 10 groups: one step from each), one more block
+@pytest.mark.parametrize("step", [2, 7, 12, 17, 22, 27, 32, 37, 42, 47])
+@pytest.mark.parametrize("kind", ["qkv", "proj", "fc1", "fc2"])
+def test_config4_every_time_step_group(oracle, step, kind):
+    say(f"config 4: M=8192 block 7 {kind} step {step}")
+    assert int(oracle.table_default(50, 10)[step]) == step // 5
+    check_layer(oracle, wl.CONFIGS[4], kind, step, 8, block=7)
+
+
 # ---- the full transform of Eq. 9 (rotation, zigzag permutation, rotation) at workload sizes ----
 
 @pytest.mark.parametrize("cfg_id,kind,step", [(1, "fc1", 0), (1, "fc2", 7), (3, "proj", 19), (3, "fc2", 0)])
