@@ -294,10 +294,10 @@ trdq_status trdq_rotate_quant_dense(const void *X_dev, int64_t M, int64_t ldx, c
  * the activation side takes K <= 4608 (ERR_UNSUPPORTED beyond): 16-token workgroups up to K = 1536,
  * 8-token workgroups that run the second rotation twice (maxima, then codes) for wider rows.
  * trdq_rotate_quant_dense_rpr_ws is the same operation with a device workspace, which rows wider than
- * K = 1536 use for a faster form (a workgroup per block with the rotation resident in LDS; the once-rotated
- * values cross the permutation through the workspace as float32): ws_dev holds at least
- * trdq_rotate_quant_dense_rpr_ws_nbytes(M, K) bytes (4 (K + 1) roundup(M, 32); 0 for K <= 1536 or M <= 0, and
- * then ws_dev may be NULL), 16-byte aligned, and belongs to the call until it has finished on its stream;
+ * K = 1536 (and narrower rows from 16384 tokens on) use for a faster form (a workgroup per block with the
+ * rotation resident in LDS; the once-rotated values cross the permutation through the workspace as float32):
+ * ws_dev holds at least trdq_rotate_quant_dense_rpr_ws_nbytes(M, K) bytes (4 (K + 1) roundup(M, 32); 0 for
+ * M <= 0 and for K <= 1536 below 16384 tokens, and then ws_dev may be NULL), 16-byte aligned, and belongs to the call until it has finished on its stream;
  * nothing in it needs to be kept or cleared between calls.  ERR_NULL without it, ERR_SHAPE if it is too
  * small or misaligned, ERR_UNSUPPORTED from 2^32 workspace elements (16 GiB) on; otherwise arguments, results and errors as trdq_rotate_quant_dense_rpr (the two
  * forms round differently in the last float32 bits, so single codes may differ by one step). */

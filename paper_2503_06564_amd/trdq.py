@@ -384,7 +384,7 @@ def rotate_quant_dense_rpr(X, rot1, perm, rot2, Xq, sx, stream=None):
 
 
 def rotate_quant_dense_rpr_ws_nbytes(M, K):
-    """bytes of device workspace rotate_quant_dense_rpr_ws needs (0 up to K = 1536)"""
+    """bytes of device workspace rotate_quant_dense_rpr_ws needs (0 up to K = 1536 below 16384 tokens)"""
     return int(lib().trdq_rotate_quant_dense_rpr_ws_nbytes(M, K))
 
 

@@ -294,7 +294,8 @@ def test_dense_rpr_workspace_size():
     assert n(4096, 4608) == 4 * 4609 * 4096          # K rows of once-rotated values and one of maxima
     assert n(33, 2304) == 4 * 2305 * 64              # tokens rounded up to 32
     assert n(1, 1664) == 4 * 1665 * 32
-    assert n(100, 1536) == 0 and n(100, 128) == 0    # up to 12 blocks: no workspace
+    assert n(100, 1536) == 0 and n(16383, 128) == 0  # up to 12 blocks: no workspace below 16384 tokens
+    assert n(16384, 1152) == 4 * 1153 * 16384 and n(16385, 128) == 4 * 129 * 16416
     assert n(0, 4608) == 0 and n(-3, 4608) == 0 and n(8, 4600) == 0 and n(8, 0) == 0
 
 

@@ -198,11 +198,11 @@ def test_rotate_quant_dense_rpr_matches_oracle(oracle, M, K):
     rot1.close(); rot2.close()
 
 
-# the workspace form: block-resident kernels around float32 once-rotated values (K > 1536); up to K = 1536 it is the
-# plain call.  13 blocks and 36, token counts around the 16- and 32-token groups and beyond one round of workgroups.
+# the workspace form: block-resident kernels around float32 once-rotated values (K > 1536, and narrower rows from
+# 16384 tokens on); otherwise it is the plain call.  13 blocks and 36, token counts around the 16- and 32-token groups and beyond one round of workgroups.
 # (from 8192 tokens on the second rotation takes two token tiles per fragment read)
 @pytest.mark.parametrize("M,K", [(1, 1664), (40, 1664), (9, 2304), (33, 2304), (70, 4608), (263, 4608), (1100, 2304),
-                                 (300, 1152), (0, 2304), (8230, 1664), (8192, 2304)])
+                                 (300, 1152), (0, 2304), (8230, 1664), (8192, 2304), (16400, 384), (16384, 128)])
 def test_rotate_quant_dense_rpr_ws_matches_oracle(oracle, M, K):
     say(f"rotate_quant_dense_rpr_ws M={M} K={K}")
     Xb, _, d, _ = wl.small_case(74, max(M, 1), K, 16, n_outliers=max(1, K // 144), outlier=40.0)
@@ -211,7 +211,7 @@ def test_rotate_quant_dense_rpr_ws_matches_oracle(oracle, M, K):
     perm = np.random.default_rng(K + 1).permutation(K).astype(np.int32)
     rot1, rot2 = _rot(R1, d), _rot(R2)
     nbytes = trdq.rotate_quant_dense_rpr_ws_nbytes(M, K)
-    assert (nbytes > 0) == (K > 1536 and M > 0)
+    assert (nbytes > 0) == (M > 0 and (K > 1536 or M >= 16384))
     ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=dev()) if nbytes else None     # NaN patterns: nothing is read unwritten
     Xq = torch.full((M, K), 99, dtype=torch.int8, device=dev())
     sx = torch.full((M,), -1.0, dtype=torch.float32, device=dev())
